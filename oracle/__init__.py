@@ -1,0 +1,7 @@
+"""CPU oracle package (test infrastructure only; see pq_oracle.py)."""
+
+from .pq_oracle import (  # noqa: F401
+    QMAX, QMIN, build_c, calibrate_absmax, epilogue, gemm_i64, hadamard, linear,
+    linear_dynamic, pack, quantize, quantize_bits, quantize_dynamic, rotate, threads,
+    unpack, weight_rtn,
+)

@@ -1,0 +1,265 @@
+"""Pins for the CPU oracle: each check ties a part of the oracle to something the paper
+or the mathematics fixes, not to the oracle's own formula.
+
+Cited passages: App. B "Details of Rotation" (H orthogonal, entries +-1 at one scale;
+rotation keeps the layer's output unchanged), Eq. 1 (uniform quantizer), Table 1 row O2
+(per-channel weights, per-tensor static activations).  The paper prints no worked
+numeric example for this path, so there is no paper-printed value to compare with.
+"""
+
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle as O
+from paper_2410_05265_amd import synth
+
+
+# ------------------------------------------------------------------ O1 Hadamard
+def sylvester_recursive(h):
+    H = np.array([[1]], dtype=np.int8)
+    while H.shape[0] < h:
+        H = np.block([[H, H], [H, -H]])
+    return H
+
+
+@pytest.mark.parametrize("h", [1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048, 4096, 8192])
+def test_hadamard_orthogonal_and_sylvester(h):
+    H = O.hadamard(h)
+    assert H.shape == (h, h) and H.dtype == np.int8
+    assert set(np.unique(H)) <= {-1, 1}
+    assert np.array_equal(H, sylvester_recursive(h))
+    if h <= 256:
+        G = H.astype(np.int64) @ H.astype(np.int64).T
+    else:  # float64 BLAS product of +-1 entries is exact (|sum| <= 8192 << 2^53)
+        Hf = H.astype(np.float64)
+        G = Hf @ Hf.T
+    assert np.array_equal(G, h * np.eye(h))
+
+
+# ------------------------------------------------------------------ O2 rotation
+def fwht_textbook(v):
+    """In-place butterfly Walsh-Hadamard transform (natural order), unnormalised."""
+    v = [float(t) for t in v]
+    n, d = len(v), 1
+    while d < n:
+        for start in range(0, n, 2 * d):
+            for i in range(start, start + d):
+                a, b = v[i], v[i + d]
+                v[i], v[i + d] = a + b, a - b
+        d *= 2
+    return v
+
+
+@pytest.mark.parametrize("h", [2, 8, 128, 512])
+def test_rotate_matches_textbook_butterflies(h):
+    rng = np.random.default_rng(h)
+    x = rng.standard_normal((3, 2 * h))
+    y = O.rotate(x, h)
+    for m in range(3):
+        for b in range(2):
+            ref = np.array(fwht_textbook(x[m, b * h:(b + 1) * h])) / np.sqrt(h)
+            np.testing.assert_allclose(y[m, b * h:(b + 1) * h], ref, rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("h,K", [(128, 1024), (512, 512), (4096, 4096), (128, 11008)])
+def test_rotate_involution_parseval(h, K):
+    x = synth.activations(5, K, seed=3).astype(np.float64)
+    y = O.rotate(x, h)
+    np.testing.assert_allclose(O.rotate(y, h), x, rtol=0, atol=1e-11)
+    np.testing.assert_allclose(np.linalg.norm(y, axis=1), np.linalg.norm(x, axis=1), rtol=1e-13)
+
+
+def test_rotate_one_hot_and_constant_rows():
+    h = 256
+    x = np.zeros((2, h))
+    x[0, 37] = 3.0          # one-hot: the row of H, scaled
+    x[1, :] = 0.5           # constant: everything lands in channel 0
+    y = O.rotate(x, h)
+    expect0 = 3.0 * np.array([(-1) ** bin(37 & j).count("1") for j in range(h)]) / 16.0
+    np.testing.assert_allclose(y[0], expect0, rtol=0, atol=1e-15)
+    expect1 = np.zeros(h)
+    expect1[0] = 0.5 * 16.0
+    np.testing.assert_allclose(y[1], expect1, rtol=0, atol=1e-13)
+
+
+def test_rotate_blocks_do_not_mix_and_identity():
+    x = synth.activations(4, 1024, seed=1).astype(np.float64)
+    y = O.rotate(x, 128)
+    x2 = x.copy()
+    x2[:, 256:384] += 1.0   # perturb block 2 only
+    y2 = O.rotate(x2, 128)
+    changed = np.any(y2 != y, axis=0).reshape(8, 128).any(axis=1)
+    assert list(changed) == [False, False, True, False, False, False, False, False]
+    assert np.array_equal(O.rotate(x, 1), x) and np.array_equal(O.rotate(x, 0), x)
+    with pytest.raises(ValueError):
+        O.rotate(x, 96)
+    with pytest.raises(ValueError):
+        O.rotate(x[:, :1000], 128)
+
+
+def test_rotation_keeps_layer_output():
+    # App. B: rotating activations and weights alike leaves X W^T unchanged.
+    x = synth.activations(7, 512, seed=2).astype(np.float64)
+    W = synth.weights(24, 512, seed=2).astype(np.float64)
+    for h in (128, 512):
+        np.testing.assert_allclose(O.rotate(x, h) @ O.rotate(W, h).T, x @ W.T, rtol=0, atol=1e-12)
+
+
+# ------------------------------------------------------------------ O3/O4 quantizer, packing
+def test_quantize_exact_halves_and_saturation():
+    s = 0.25
+    t = np.array([0.5, -0.5, 1.5, -1.5, 2.5, -2.5, 3.5, 6.5, 7.5, -7.5, -8.5, 7.49, -8.49,
+                  100.0, -100.0, 0.0, 6.500001, 6.499999])
+    want = np.array([0, 0, 2, -2, 2, -2, 4, 6, 7, -8, -8, 7, -8, 7, -8, 0, 7, 6])
+    assert np.array_equal(O.quantize(t * s, s), want)
+
+
+@pytest.mark.parametrize("j", [0, 3, 7, 10])
+def test_quantize_on_grid_has_zero_error(j):
+    s = 2.0 ** -j
+    q0 = synth.random_codes(9, 256, seed=j)
+    v = (q0.astype(np.float64) * s).astype(np.float16)     # exact: 4-bit integer times 2^-j
+    q = O.quantize(v, np.float32(s))
+    assert np.array_equal(q, q0)
+    assert np.array_equal(q.astype(np.float64) * s, v.astype(np.float64))
+
+
+def test_quantize_step_is_used_as_divisor():
+    # a wrong sign, a multiplied (not divided) step or a missing clamp all fail here
+    y = np.array([[0.3, -0.3, 0.9, -2.0, 5.0]])
+    assert np.array_equal(O.quantize(y, 0.3), [[1, -1, 3, -7, 7]])
+    assert np.array_equal(O.quantize(y, 3.0), [[0, 0, 0, -1, 2]])
+
+
+def test_pack_layout_and_round_trip_all_bytes():
+    assert np.array_equal(O.pack(np.array([[1, 2]], dtype=np.int8)), [[0x21]])
+    assert np.array_equal(O.pack(np.array([[-1, 7, -8, 0]], dtype=np.int8)), [[0x7F, 0x08]])
+    allb = np.arange(256, dtype=np.uint8).reshape(1, 256)
+    codes = O.unpack(allb)
+    assert codes.min() == -8 and codes.max() == 7
+    for b in range(256):
+        lo, hi = b & 15, b >> 4
+        assert codes[0, 2 * b] == (lo - 16 if lo >= 8 else lo)
+        assert codes[0, 2 * b + 1] == (hi - 16 if hi >= 8 else hi)
+    assert np.array_equal(O.pack(codes), allb)
+
+
+@pytest.mark.parametrize("h", [4, 16, 64, 256, 1024, 4096])
+def test_rotate_then_quantize_recovers_sparse_codes(h):
+    # sqrt(h) is a power of two: x = (H q0) s / sqrt(h) is exact in fp16 for sparse q0,
+    # H is an involution up to h, so rotate(x)/s must give q0 back exactly.
+    rng = np.random.default_rng(h)
+    s = 2.0 ** -4
+    q0 = np.zeros((6, h), dtype=np.int8)
+    for m in range(6):
+        idx = rng.choice(h, size=min(3, h), replace=False)
+        q0[m, idx] = rng.integers(-8, 8, size=idx.size)
+    Hq = q0.astype(np.int64) @ O.hadamard(h).astype(np.int64)
+    x = (Hq * s / np.sqrt(h)).astype(np.float16)
+    assert np.array_equal(x.astype(np.float64), Hq * s / np.sqrt(h))
+    y = O.rotate(x, h)
+    assert np.array_equal(O.quantize(y, np.float32(s)), q0)
+
+
+def test_quantize_bits_eight_and_dynamic():
+    y = np.array([[0.0, 1.0, -2.2, 4.0], [0.5, 0.3, -0.125, 0.0], [0.0, 0.0, 0.0, 0.0]])
+    q, s = O.quantize_dynamic(y)
+    assert s.dtype == np.float32
+    np.testing.assert_array_equal(s, np.array([4.0 / 7, 0.5 / 7, 1.0], dtype=np.float32))
+    assert np.array_equal(q, [[0, 2, -4, 7], [7, 4, -2, 0], [0, 0, 0, 0]])
+    q8 = O.quantize_bits(np.array([127.5, -128.5, 300.0, -300.0, 2.5, 3.5]), 1.0, 8)
+    assert np.array_equal(q8, [127, -128, 127, -128, 2, 4])
+    q, s = O.quantize_dynamic(y, clip=0.5)      # clipping halves the step, large values saturate
+    assert np.array_equal(q[0, [0, 2, 3]], [0, -8, 7]) and s[0] == np.float32(2.0 / 7)
+
+
+# ------------------------------------------------------------------ O5 integer product
+def test_gemm_brute_force_tiny():
+    q = synth.random_codes(3, 32, seed=11)
+    w = synth.random_codes(5, 32, seed=12)
+    acc = O.gemm_i64(q, w)
+    assert acc.shape == (3, 5) and acc.dtype == np.int64
+    for m, n in itertools.product(range(3), range(5)):
+        assert acc[m, n] == sum(int(q[m, k]) * int(w[n, k]) for k in range(32))
+
+
+@pytest.mark.parametrize("M,N,K", [(33, 48, 512), (17, 160, 4096), (4, 64, 14336)])
+def test_gemm_equals_float64_blas_product(M, N, K):
+    q = synth.random_codes(M, K, seed=M)
+    w = synth.random_codes(N, K, seed=N + 100)
+    ref = q.astype(np.float64) @ w.astype(np.float64).T     # exact: |sum| < 2^53
+    assert np.array_equal(O.gemm_i64(q, w).astype(np.float64), ref)
+
+
+def test_gemm_special_cases():
+    q = synth.random_codes(6, 1024, seed=5)
+    ones = np.ones((16, 1024), dtype=np.int8)
+    acc = O.gemm_i64(q, ones)
+    assert np.array_equal(acc, np.repeat(q.astype(np.int64).sum(axis=1)[:, None], 16, axis=1))
+    K = 28672
+    acc = O.gemm_i64(np.full((2, K), -8, np.int8), np.full((16, K), -8, np.int8))
+    assert np.all(acc == 1835008)
+    acc = O.gemm_i64(np.full((2, K), 7, np.int8), np.full((16, K), -8, np.int8))
+    assert np.all(acc == -56 * K)
+    with pytest.raises(OverflowError):      # 127*127*140000 > 2^31
+        O.gemm_i64(np.full((1, 140000), 127, np.int8), np.full((1, 140000), 127, np.int8))
+    with pytest.raises(ValueError):
+        O.gemm_i64(q, ones[:, :512])
+
+
+# ------------------------------------------------------------------ O6 epilogue
+def test_epilogue_unit_scales_and_linearity():
+    acc = np.array([[0, 1, -3, 2047, 2049, -1835008]], dtype=np.int64)
+    out = O.epilogue(acc, np.float32(1.0), np.ones(6, np.float32))
+    assert out.dtype == np.float16
+    # 2049 is a tie between 2048 and 2050 in fp16 -> even significand; 1835008 overflows fp16
+    assert np.array_equal(out, np.array([[0, 1, -3, 2047, 2048, -np.inf]], dtype=np.float16))
+    sw = np.array([0.5, 2.0, 0.25, 1.0, 1.0, 2.0 ** -10], np.float32)
+    out = O.epilogue(acc, np.float32(0.5), sw)
+    assert np.array_equal(out, np.array([[0, 1, -0.375, 1023.5, 1024.5, -896]], dtype=np.float16))
+    # per-token step sizes (dynamic variant): row m uses s[m]
+    acc2 = np.array([[4, 8], [4, 8]], dtype=np.int64)
+    out = O.epilogue(acc2, np.array([1.0, 0.5], np.float32), np.array([1.0, 2.0], np.float32))
+    assert np.array_equal(out, np.array([[4, 16], [2, 8]], dtype=np.float16))
+
+
+# ------------------------------------------------------------------ O7 preparation
+def test_weight_rtn_and_calibration():
+    W = synth.weights(64, 512, seed=9)
+    codes, s = O.weight_rtn(W)
+    assert s.dtype == np.float32 and s.shape == (64,)
+    assert np.all(np.abs(codes).max(axis=1) == 7) and codes.min() >= -7
+    err = np.abs(codes.astype(np.float64) * s.astype(np.float64)[:, None] - W.astype(np.float64))
+    assert np.all(err <= 0.5 * s.astype(np.float64)[:, None] * (1 + 1e-6))
+    np.testing.assert_allclose(s, np.abs(W.astype(np.float64)).max(axis=1) / 7, rtol=2 ** -24)
+    Wz = W.copy()
+    Wz[3] = 0
+    codes, s = O.weight_rtn(Wz)
+    assert s[3] == 1.0 and not codes[3].any()
+    xc = synth.calibration(512, seed=9)
+    for h in (1, 128, 512):
+        sx = O.calibrate_absmax(xc, h)
+        assert sx.dtype == np.float32
+        q = O.quantize(O.rotate(xc, h), sx)
+        assert q.max() == 7 or q.min() == -7
+        assert q.min() >= -7        # absmax/7 never reaches the -8 code on its own data
+
+
+# ------------------------------------------------------------------ whole path
+def test_linear_pieces_compose_and_approximate_fp():
+    K, N, M, h = 512, 512, 16, 512
+    x, xc, W = synth.activations(M, K), synth.calibration(K), synth.weights(N, K)
+    wq, sw = O.weight_rtn(W)
+    sx = O.calibrate_absmax(xc, h)
+    r = O.linear(x, O.pack(wq), sw, sx, h, return_all=True)
+    assert r["xq"].shape == (M, K // 2) and r["out"].shape == (M, N)
+    assert np.array_equal(O.unpack(r["xq"]), r["q"])
+    # the quantized layer approximates the fp64 layer computed on dequantised operands exactly
+    deq = (r["q"].astype(np.float64) * np.float64(sx)) @ (wq.astype(np.float64) * sw.astype(np.float64)[:, None]).T
+    np.testing.assert_allclose(r["out"].astype(np.float64), deq, rtol=2 ** -10, atol=1e-7)
+    # and the rotated 4-bit layer tracks the unquantised, unrotated layer (invariance + small noise)
+    ref = x.astype(np.float64) @ O.rotate(wq.astype(np.float64) * sw.astype(np.float64)[:, None], h).T
+    snr = np.linalg.norm(ref) / np.linalg.norm(ref - r["out"].astype(np.float64))
+    assert snr > 4.0
