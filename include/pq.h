@@ -1,0 +1,107 @@
+/* pq.h — C ABI of the statically quantized W4A4 linear layer for AMD MI355X (gfx950).
+ *
+ * The layer is the inference hot path of PrefixQuant's static setting (Table 1, row O2:
+ * weights per-channel, activations per-tensor static):
+ *
+ *   X fp16 [M,K] --online Hadamard rotation--> Y --static symmetric 4-bit quantization,
+ *   two codes per byte--> Xq [M,K/2];  acc = Xq . Wq^T (int4 x int4, int32 accumulate);
+ *   OUT fp16 [M,N] = acc * s_x * s_w[n].
+ *
+ * Conventions that hold for every entry point unless it says otherwise
+ *   - every data pointer is a DEVICE pointer; the caller owns all buffers; the library
+ *     allocates no device memory, never synchronises and never copies results back;
+ *   - all work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream);
+ *   - tensors are row-major and contiguous; base pointers must be 16-byte aligned;
+ *   - 4-bit codes are two's-complement nibbles in [-8,7], two per byte, the even
+ *     channel in the low nibble ("canonical" layout);
+ *   - K % 32 == 0, N % 16 == 0, M >= 0 (M == 0 is a no-op that returns PQ_OK);
+ *   - the return value is PQ_OK or a PQ_ERR_* code; on an error detected by argument
+ *     checking nothing has been enqueued;
+ *   - inputs must be finite; the library is stateless and thread-safe.
+ */
+#ifndef PQ_H
+#define PQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    PQ_OK = 0,
+    PQ_ERR_NULL = 1,        /* a required pointer is NULL                           */
+    PQ_ERR_SHAPE = 2,       /* a size violates the conventions above                */
+    PQ_ERR_ALIGN = 3,       /* a pointer is not 16-byte aligned                     */
+    PQ_ERR_SCALE = 4,       /* a step size is not finite and positive               */
+    PQ_ERR_WORKSPACE = 5,   /* workspace missing or too small                       */
+    PQ_ERR_HIP = 6,         /* the HIP runtime reported an error at launch          */
+    PQ_ERR_UNSUPPORTED = 7  /* valid request that this build has no kernel for      */
+};
+
+/* Library version as major*10000 + minor*100 + patch.  Host only. */
+int pq_version(void);
+
+/* Name of a status code; the string has static storage.  Host only. */
+const char* pq_status_str(int status);
+
+/* Online rotation + static quantization + packing (App. B "Online Rotation"; Eq. 1 in
+ * its symmetric form; Sec. 3 "Dynamic and Static").
+ * For every row m and every block b of had_block consecutive channels
+ *     y[m, b*h + j] = sum_i x[m, b*h + i] * H_h[i][j] / sqrt(h),
+ *     H_h[i][j] = (-1)^popcount(i & j)            (Sylvester order, butterflies in fp32),
+ *     q = clamp(round_half_even(y / act_scale), -8, 7).
+ * had_block: 0 or 1 = no rotation; otherwise a power of two in [2, 16384] that
+ *            divides K.  With had_block <= 1 the codes are exactly
+ *            round_half_even((double)x / (double)act_scale) clamped (no fp32 slip).
+ * x_f16      in  [M,K] fp16.
+ * xq_packed  out [M,K/2] uint8, canonical layout.
+ */
+int pq_rotate_quant(const void* x_f16, int64_t M, int64_t K, int32_t had_block,
+                    float act_scale, void* xq_packed, void* stream);
+
+/* Integer product + dequantisation (Sec. 3: low-bit matrix multiplication; Table 1 row
+ * O2 for the two step sizes).
+ *     acc[m,n] = sum_k xq[m,k] * wq[n,k]              (exact, int32)
+ *     out[m,n] = fp16(acc[m,n] * (act_scale * w_scale[n]))   (fp32 multiply, RNE)
+ * The kernel is chosen from M: a weight-streaming kernel for M <= 16 (decode), an
+ * INT8-MFMA tiled kernel otherwise (prefill).
+ * xq_packed in  [M,K/2] uint8 canonical.      wq_packed in [N,K/2] uint8 canonical.
+ * w_scale   in  [N] fp32.                     act_scale: static step size of xq.
+ * out_f16   out [M,N] fp16; may be NULL iff acc_i32 is not.
+ * acc_i32   out [M,N] int32 raw accumulators, for verification; NULL in production.
+ */
+int pq_w4a4_gemm(const void* xq_packed, const void* wq_packed, const float* w_scale,
+                 float act_scale, int64_t M, int64_t N, int64_t K,
+                 void* out_f16, int32_t* acc_i32, void* stream);
+
+/* Bytes of workspace pq_linear needs (holds Xq): M*K/2 rounded up to 256.  Host only. */
+size_t pq_linear_workspace_bytes(int64_t M, int64_t K);
+
+/* The whole layer: pq_rotate_quant into `workspace`, then pq_w4a4_gemm (same stream).
+ * workspace: device memory, 256-byte aligned, at least pq_linear_workspace_bytes(M,K);
+ * its contents on return are the packed activation codes (canonical layout).
+ */
+int pq_linear(const void* x_f16, const void* wq_packed, const float* w_scale,
+              float act_scale, int32_t had_block, int64_t M, int64_t N, int64_t K,
+              void* out_f16, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Plain, slow device kernel for the same product as pq_w4a4_gemm (one thread per
+ * output, no tiling).  Kept as an on-device cross-check for the fast kernels.
+ */
+int pq_w4a4_gemm_simple(const void* xq_packed, const void* wq_packed, const float* w_scale,
+                        float act_scale, int64_t M, int64_t N, int64_t K,
+                        void* out_f16, int32_t* acc_i32, void* stream);
+
+/* Force a kernel variant of pq_w4a4_gemm for sweeps and tests (host, process-wide,
+ * not thread-safe): 0 = automatic, 1 = weight-streaming (M <= 16 only), 2 = MFMA tiled,
+ * 3 = simple.  Returns the previous value, or -1 if `variant` is unknown.
+ */
+int pq_set_gemm_variant(int variant);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PQ_H */

@@ -1,0 +1,141 @@
+"""ctypes binding of libpq.so: argument marshalling only.
+
+Every step of the layer runs in the HIP kernels behind the C ABI declared in
+include/pq.h; torch is used here for device memory and the current stream, nothing else.
+There is no CPU fallback: if the library has not been built, loading raises.
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpq.so")
+
+PQ_OK, PQ_ERR_NULL, PQ_ERR_SHAPE, PQ_ERR_ALIGN, PQ_ERR_SCALE, PQ_ERR_WORKSPACE, PQ_ERR_HIP, PQ_ERR_UNSUPPORTED = range(8)
+
+_i64, _i32, _f32, _vp, _sz = ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t
+
+# symbol -> (restype, argtypes); mirrors include/pq.h
+SIGNATURES = {
+    "pq_version": (ctypes.c_int, []),
+    "pq_status_str": (ctypes.c_char_p, [ctypes.c_int]),
+    "pq_rotate_quant": (ctypes.c_int, [_vp, _i64, _i64, _i32, _f32, _vp, _vp]),
+    "pq_w4a4_gemm": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i64, _i64, _i64, _vp, _vp, _vp]),
+    "pq_w4a4_gemm_simple": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i64, _i64, _i64, _vp, _vp, _vp]),
+    "pq_linear_workspace_bytes": (_sz, [_i64, _i64]),
+    "pq_linear": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i32, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
+    "pq_set_gemm_variant": (ctypes.c_int, [ctypes.c_int]),
+}
+
+_lib = None
+
+
+class PQError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s" % (where, status_str(status)))
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if libpq.so is missing (build it with build.build_lib())."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                "%s not found: the HIP library is not built (python -m paper_2410_05265_amd.build)" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def status_str(status: int) -> str:
+    return lib().pq_status_str(int(status)).decode()
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc: int, where: str):
+    if rc != PQ_OK:
+        raise PQError(rc, where)
+
+
+def _dev(t: torch.Tensor, dtype, what: str):
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError("%s must be a contiguous %s tensor on the GPU" % (what, dtype))
+
+
+def pq_rotate_quant(x: torch.Tensor, had_block: int, act_scale: float, out: torch.Tensor | None = None):
+    """x fp16 [M,K] -> packed codes uint8 [M,K/2]."""
+    _dev(x, torch.float16, "x")
+    M, K = x.shape
+    if out is None:
+        out = torch.empty((M, K // 2), dtype=torch.uint8, device=x.device)
+    _check(lib().pq_rotate_quant(_ptr(x), M, K, int(had_block), float(act_scale), _ptr(out), _stream()),
+           "pq_rotate_quant")
+    return out
+
+
+def _gemm(fn, name, xq, wq, w_scale, act_scale, want_out, want_acc, out, acc):
+    _dev(xq, torch.uint8, "xq")
+    _dev(wq, torch.uint8, "wq")
+    _dev(w_scale, torch.float32, "w_scale")
+    M, K = xq.shape[0], xq.shape[1] * 2
+    N = wq.shape[0]
+    if wq.shape[1] * 2 != K or w_scale.numel() != N:
+        raise ValueError("shape mismatch")
+    if want_out and out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=xq.device)
+    if want_acc and acc is None:
+        acc = torch.empty((M, N), dtype=torch.int32, device=xq.device)
+    _check(fn(_ptr(xq), _ptr(wq), _ptr(w_scale), float(act_scale), M, N, K, _ptr(out), _ptr(acc), _stream()), name)
+    return out, acc
+
+
+def pq_w4a4_gemm(xq, wq, w_scale, act_scale, want_out=True, want_acc=False, out=None, acc=None):
+    """packed codes [M,K/2] x packed weights [N,K/2] -> (out fp16 [M,N] | None, acc int32 [M,N] | None)."""
+    return _gemm(lib().pq_w4a4_gemm, "pq_w4a4_gemm", xq, wq, w_scale, act_scale, want_out, want_acc, out, acc)
+
+
+def pq_w4a4_gemm_simple(xq, wq, w_scale, act_scale, want_out=True, want_acc=False, out=None, acc=None):
+    return _gemm(lib().pq_w4a4_gemm_simple, "pq_w4a4_gemm_simple", xq, wq, w_scale, act_scale, want_out, want_acc,
+                 out, acc)
+
+
+def pq_linear_workspace_bytes(M: int, K: int) -> int:
+    return int(lib().pq_linear_workspace_bytes(M, K))
+
+
+def pq_linear(x, wq, w_scale, act_scale, had_block, out=None, workspace=None):
+    """The whole layer.  Returns (out fp16 [M,N], workspace uint8 holding the packed codes)."""
+    _dev(x, torch.float16, "x")
+    _dev(wq, torch.uint8, "wq")
+    _dev(w_scale, torch.float32, "w_scale")
+    M, K = x.shape
+    N = wq.shape[0]
+    if wq.shape[1] * 2 != K or w_scale.numel() != N:
+        raise ValueError("shape mismatch")
+    need = pq_linear_workspace_bytes(M, K)
+    if workspace is None:
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=x.device)
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    _check(lib().pq_linear(_ptr(x), _ptr(wq), _ptr(w_scale), float(act_scale), int(had_block), M, N, K, _ptr(out),
+                           _ptr(workspace), workspace.numel(), _stream()), "pq_linear")
+    return out, workspace
+
+
+def pq_set_gemm_variant(variant: int) -> int:
+    return int(lib().pq_set_gemm_variant(int(variant)))

@@ -1,0 +1,119 @@
+// C entry points of libpq: argument checking and kernel choice.  No device memory is
+// allocated here and nothing synchronises; every kernel goes to the caller's stream.
+#include "pq_internal.h"
+
+#include <math.h>
+
+namespace {
+
+int g_variant = 0;  // 0 auto, 1 streaming (M <= 16), 2 MFMA tiled, 3 simple
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool good_scale(float s) { return isfinite(s) && s > 0.0f; }
+
+int check_gemm(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K,
+               const void* out, const int32_t* acc)
+{
+    if (M < 0 || N <= 0 || K <= 0 || (K % 32) != 0 || (N % 16) != 0) return PQ_ERR_SHAPE;
+    if (!xq || !wq || !sw || (!out && !acc)) return PQ_ERR_NULL;
+    if (!aligned16(xq) || !aligned16(wq) || !aligned16(out) || !aligned16(acc) ||
+        (reinterpret_cast<uintptr_t>(sw) & 3u))
+        return PQ_ERR_ALIGN;
+    if (!good_scale(sx)) return PQ_ERR_SCALE;
+    return PQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pq_version(void) { return 100; }
+
+const char* pq_status_str(int status)
+{
+    switch (status) {
+        case PQ_OK: return "PQ_OK";
+        case PQ_ERR_NULL: return "PQ_ERR_NULL";
+        case PQ_ERR_SHAPE: return "PQ_ERR_SHAPE";
+        case PQ_ERR_ALIGN: return "PQ_ERR_ALIGN";
+        case PQ_ERR_SCALE: return "PQ_ERR_SCALE";
+        case PQ_ERR_WORKSPACE: return "PQ_ERR_WORKSPACE";
+        case PQ_ERR_HIP: return "PQ_ERR_HIP";
+        case PQ_ERR_UNSUPPORTED: return "PQ_ERR_UNSUPPORTED";
+        default: return "PQ_ERR_UNKNOWN";
+    }
+}
+
+int pq_rotate_quant(const void* x_f16, int64_t M, int64_t K, int32_t had_block, float act_scale,
+                    void* xq_packed, void* stream)
+{
+    if (M < 0 || K <= 0 || (K % 32) != 0) return PQ_ERR_SHAPE;
+    if (had_block < 0 || had_block > 16384) return PQ_ERR_SHAPE;
+    if (had_block > 1 && ((had_block & (had_block - 1)) != 0 || (K % had_block) != 0)) return PQ_ERR_SHAPE;
+    if (!x_f16 || !xq_packed) return PQ_ERR_NULL;
+    if (!aligned16(x_f16) || !aligned16(xq_packed)) return PQ_ERR_ALIGN;
+    if (!good_scale(act_scale)) return PQ_ERR_SCALE;
+    if (M == 0) return PQ_OK;
+    return pq::launch_rotate_quant(x_f16, M, K, had_block, act_scale, xq_packed, static_cast<hipStream_t>(stream));
+}
+
+int pq_w4a4_gemm(const void* xq_packed, const void* wq_packed, const float* w_scale, float act_scale, int64_t M,
+                 int64_t N, int64_t K, void* out_f16, int32_t* acc_i32, void* stream)
+{
+    int rc = check_gemm(xq_packed, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32);
+    if (rc != PQ_OK) return rc;
+    if (M == 0) return PQ_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int v = g_variant;
+    if (v == 0) v = (M <= 16) ? 1 : 2;
+    switch (v) {
+        case 1:
+            if (M > 16) return PQ_ERR_UNSUPPORTED;
+            return pq::launch_gemv(xq_packed, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32, st);
+        case 2: return pq::launch_gemm_mfma(xq_packed, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32, st);
+        default: return pq::launch_gemm_simple(xq_packed, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32, st);
+    }
+}
+
+int pq_w4a4_gemm_simple(const void* xq_packed, const void* wq_packed, const float* w_scale, float act_scale,
+                        int64_t M, int64_t N, int64_t K, void* out_f16, int32_t* acc_i32, void* stream)
+{
+    int rc = check_gemm(xq_packed, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32);
+    if (rc != PQ_OK) return rc;
+    if (M == 0) return PQ_OK;
+    return pq::launch_gemm_simple(xq_packed, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32,
+                                  static_cast<hipStream_t>(stream));
+}
+
+size_t pq_linear_workspace_bytes(int64_t M, int64_t K)
+{
+    if (M <= 0 || K <= 0) return 0;
+    const size_t b = (size_t)M * (size_t)(K / 2);
+    return (b + 255) & ~(size_t)255;
+}
+
+int pq_linear(const void* x_f16, const void* wq_packed, const float* w_scale, float act_scale, int32_t had_block,
+              int64_t M, int64_t N, int64_t K, void* out_f16, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (M < 0 || N <= 0 || K <= 0 || (K % 32) != 0 || (N % 16) != 0) return PQ_ERR_SHAPE;
+    if (!x_f16 || !wq_packed || !w_scale || !out_f16) return PQ_ERR_NULL;
+    if (M == 0) return PQ_OK;
+    if (!workspace || workspace_bytes < pq_linear_workspace_bytes(M, K)) return PQ_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return PQ_ERR_ALIGN;
+    // check the second stage's arguments before anything is enqueued
+    int rc = check_gemm(workspace, wq_packed, w_scale, act_scale, M, N, K, out_f16, nullptr);
+    if (rc != PQ_OK) return rc;
+    rc = pq_rotate_quant(x_f16, M, K, had_block, act_scale, workspace, stream);
+    if (rc != PQ_OK) return rc;
+    return pq_w4a4_gemm(workspace, wq_packed, w_scale, act_scale, M, N, K, out_f16, nullptr, stream);
+}
+
+int pq_set_gemm_variant(int variant)
+{
+    if (variant < 0 || variant > 3) return -1;
+    const int prev = g_variant;
+    g_variant = variant;
+    return prev;
+}
+
+}  // extern "C"

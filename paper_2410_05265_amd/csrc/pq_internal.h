@@ -1,0 +1,37 @@
+// Internal declarations shared by the translation units of libpq (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/pq.h"
+
+namespace pq {
+
+// Launchers: arguments are already validated by the C entry points.
+int launch_rotate_quant(const void* x, int64_t M, int64_t K, int32_t h, float act_scale,
+                        void* xq, hipStream_t st);
+int launch_gemm_simple(const void* xq, const void* wq, const float* sw, float sx, int64_t M,
+                       int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st);
+int launch_gemm_mfma(const void* xq, const void* wq, const float* sw, float sx, int64_t M,
+                     int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st);
+int launch_gemv(const void* xq, const void* wq, const float* sw, float sx, int64_t M,
+                int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st);
+
+inline int hip_status(hipError_t e) { return e == hipSuccess ? PQ_OK : PQ_ERR_HIP; }
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+// Eight packed 4-bit codes (one dword) become two dwords of int8, each byte equal to
+// 16 * code: the odd-channel nibbles already sit in the high half of their byte, the
+// even-channel nibbles are shifted there.  No sign extension is needed, and a product of
+// two such operands is 256 * (code * code), undone exactly by an arithmetic shift.
+__device__ __forceinline__ void unpack16(const v4i p, v4i& even, v4i& odd)
+{
+    const int m = (int)0xF0F0F0F0u;
+    even.x = (p.x << 4) & m; even.y = (p.y << 4) & m; even.z = (p.z << 4) & m; even.w = (p.w << 4) & m;
+    odd.x = p.x & m; odd.y = p.y & m; odd.z = p.z & m; odd.w = p.w & m;
+}
+
+}  // namespace pq

@@ -1,0 +1,90 @@
+"""The C ABI: every symbol include/pq.h declares is exported, host-only calls work without
+a GPU, and argument errors come back as status codes with nothing launched."""
+
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def b():
+    import paper_2410_05265_amd.binding as binding
+    from paper_2410_05265_amd import build
+    if build.is_stale():
+        build.build_lib()
+    binding.lib()
+    return binding
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "pq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_exported_and_bound(b):
+    names = declared_symbols()
+    assert {"pq_rotate_quant", "pq_w4a4_gemm", "pq_linear"} <= set(names)
+    raw = ctypes.CDLL(b.LIB_PATH)
+    for n in names:
+        assert hasattr(raw, n), n
+        assert n in b.SIGNATURES, n
+        assert hasattr(b, n) or n in ("pq_version", "pq_status_str"), n
+
+
+def test_host_only_calls(b):
+    L = b.lib()
+    assert L.pq_version() >= 100
+    assert b.status_str(0) == "PQ_OK" and b.status_str(4) == "PQ_ERR_SCALE" and b.status_str(99) == "PQ_ERR_UNKNOWN"
+    assert L.pq_linear_workspace_bytes(0, 4096) == 0
+    assert L.pq_linear_workspace_bytes(1, 512) == 256
+    assert L.pq_linear_workspace_bytes(3, 4096) == 6144
+    assert L.pq_linear_workspace_bytes(2048, 14336) == 2048 * 7168
+    assert L.pq_set_gemm_variant(9) == -1 and L.pq_set_gemm_variant(0) == 0
+
+
+def test_argument_errors_launch_nothing(b):
+    L = b.lib()
+    p = ctypes.c_void_p(0x1000)          # never dereferenced: each call fails validation first
+    odd = ctypes.c_void_p(0x1008)
+    nul = ctypes.c_void_p(0)
+    rq = L.pq_rotate_quant
+    assert rq(nul, 4, 512, 128, 0.1, p, nul) == b.PQ_ERR_NULL
+    assert rq(p, 4, 512, 128, 0.1, nul, nul) == b.PQ_ERR_NULL
+    assert rq(p, -1, 512, 128, 0.1, p, nul) == b.PQ_ERR_SHAPE
+    assert rq(p, 4, 500, 1, 0.1, p, nul) == b.PQ_ERR_SHAPE          # K % 32
+    assert rq(p, 4, 512, 96, 0.1, p, nul) == b.PQ_ERR_SHAPE         # not a power of two
+    assert rq(p, 4, 1536, 1024, 0.1, p, nul) == b.PQ_ERR_SHAPE      # does not divide K
+    assert rq(p, 4, 65536, 32768, 0.1, p, nul) == b.PQ_ERR_SHAPE    # too large
+    assert rq(odd, 4, 512, 128, 0.1, p, nul) == b.PQ_ERR_ALIGN
+    for bad in (0.0, -1.0, float("inf"), float("nan")):
+        assert rq(p, 4, 512, 128, bad, p, nul) == b.PQ_ERR_SCALE
+    assert rq(p, 0, 512, 128, 0.1, p, nul) == b.PQ_OK               # empty input: no-op
+
+    for g in (L.pq_w4a4_gemm, L.pq_w4a4_gemm_simple):
+        assert g(nul, p, p, 0.1, 4, 64, 512, p, nul, nul) == b.PQ_ERR_NULL
+        assert g(p, p, nul, 0.1, 4, 64, 512, p, nul, nul) == b.PQ_ERR_NULL
+        assert g(p, p, p, 0.1, 4, 64, 512, nul, nul, nul) == b.PQ_ERR_NULL      # no output at all
+        assert g(p, p, p, 0.1, 4, 60, 512, p, nul, nul) == b.PQ_ERR_SHAPE       # N % 16
+        assert g(p, p, p, 0.1, 4, 64, 48, p, nul, nul) == b.PQ_ERR_SHAPE        # K % 32
+        assert g(p, odd, p, 0.1, 4, 64, 512, p, nul, nul) == b.PQ_ERR_ALIGN
+        assert g(p, p, p, -2.0, 4, 64, 512, p, nul, nul) == b.PQ_ERR_SCALE
+        assert g(p, p, p, 0.1, 0, 64, 512, p, nul, nul) == b.PQ_OK
+
+    lin = L.pq_linear
+    assert lin(p, p, p, 0.1, 128, 4, 64, 512, p, nul, 0, nul) == b.PQ_ERR_WORKSPACE
+    assert lin(p, p, p, 0.1, 128, 4, 64, 512, p, p, 1023, nul) == b.PQ_ERR_WORKSPACE
+    assert lin(p, p, p, 0.1, 128, 4, 64, 512, p, odd, 4096, nul) == b.PQ_ERR_ALIGN
+    assert lin(p, p, p, 0.1, 128, 4, 64, 512, nul, p, 4096, nul) == b.PQ_ERR_NULL
+    assert lin(p, p, p, 0.1, 100, 4, 64, 512, p, p, 4096, nul) == b.PQ_ERR_SHAPE
+    assert lin(p, p, p, 0.0, 128, 4, 64, 512, p, p, 4096, nul) == b.PQ_ERR_SCALE
+    assert lin(p, p, p, 0.1, 128, 0, 64, 512, p, nul, 0, nul) == b.PQ_OK
+    prev = L.pq_set_gemm_variant(1)
+    try:
+        assert L.pq_w4a4_gemm(p, p, p, 0.1, 17, 64, 512, p, nul, nul) == b.PQ_ERR_UNSUPPORTED
+    finally:
+        L.pq_set_gemm_variant(prev)
