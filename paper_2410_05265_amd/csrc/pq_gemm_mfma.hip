@@ -30,6 +30,7 @@
 
 #include <hip/hip_fp16.h>
 #include <stdlib.h>
+#include <type_traits>
 
 namespace pq {
 namespace {
@@ -75,28 +76,32 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_i8(const uint8_t* __restr
     // ---- loader: lane -> (row, packed chunk); rows past the end are clamped (their
     // products are computed and never stored)
     const int lc = tid & 3, lrow = tid >> 2;
-    const uint8_t* gp[L];
+    uint32_t goff[L];  // byte offset of this lane's chunk inside xq / wq (both < 2^32 bytes)
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
         int row = m0 + lrow + RPP * i;
         row = row < M ? row : M - 1;
-        gp[i] = xq + (int64_t)row * Kb + lc * 16;
+        goff[i] = (uint32_t)row * (uint32_t)Kb + lc * 16;
     }
 #pragma unroll
     for (int i = 0; i < LB; ++i) {
         int row = n0 + lrow + RPP * i;
         row = row < N ? row : N - 1;
-        gp[LA + i] = wq + (int64_t)row * Kb + lc * 16;
+        goff[LA + i] = (uint32_t)row * (uint32_t)Kb + lc * 16;
     }
     const int wr0 = ((lrow >> 5) * 4 + 2 * (lc >> 1)) * 1024 + (lc & 1) * 512 + (((lrow & 31) ^ (4 * lc)) << 4);
     auto wr_off = [&](int idx) {  // byte offset inside a stage of staged load idx
         return idx < LA ? wr0 + idx * (RPP / 32) * 4096 : A_BYTES + wr0 + (idx - LA) * (RPP / 32) * 4096;
     };
-    v4i gr[L];
-    auto gload = [&](int idx, int kt) { gr[idx] = *reinterpret_cast<const v4i*>(gp[idx] + kt * 64); };
-    auto expand_store = [&](int idx, uint8_t* stage) {
+    // two sets of staging registers: a global load has two K stages of time to arrive
+    v4i gr[2][L];
+    auto gload = [&](int set, int idx, int kt) {
+        const uint8_t* base = (idx < LA ? xq : wq) + kt * 64;   // uniform: lives in scalar registers
+        gr[set][idx] = *reinterpret_cast<const v4i*>(base + goff[idx]);
+    };
+    auto expand_store = [&](int set, int idx, uint8_t* stage) {
         v4i e, o;
-        unpack16(gr[idx], e, o);
+        unpack16(gr[set][idx], e, o);
         *reinterpret_cast<v4i*>(stage + wr_off(idx)) = e;
         *reinterpret_cast<v4i*>(stage + wr_off(idx) + 1024) = o;
     };
@@ -132,41 +137,67 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_i8(const uint8_t* __restr
                 acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
     };
 
-    // ---- prologue: stage 0 into buffer 0, stage 1 into the staging registers
+    // ---- prologue: stage 0 into buffer 0, stages 1 and 2 into the staging registers
 #pragma unroll
-    for (int idx = 0; idx < L; ++idx) gload(idx, 0);
+    for (int idx = 0; idx < L; ++idx) gload(1, idx, 0);
 #pragma unroll
-    for (int idx = 0; idx < L; ++idx) expand_store(idx, smem);
+    for (int idx = 0; idx < L; ++idx) expand_store(1, idx, smem);
     {
-        const int k1 = nk > 1 ? 1 : 0;
+        const int k1 = nk > 1 ? 1 : nk - 1, k2 = nk > 2 ? 2 : nk - 1;
 #pragma unroll
-        for (int idx = 0; idx < L; ++idx) gload(idx, k1);
+        for (int idx = 0; idx < L; ++idx) gload(0, idx, k1);
+#pragma unroll
+        for (int idx = 0; idx < L; ++idx) gload(1, idx, k2);
     }
     lds_barrier();
     read_frags(smem, 0, 0);
 
-    for (int kt = 0; kt < nk; ++kt) {
-        uint8_t* cur = smem + (kt & 1) * STAGE;
-        uint8_t* nxt = smem + ((kt & 1) ^ 1) * STAGE;
-        const int k2 = (kt + 2 < nk) ? kt + 2 : nk - 1;
-        // steps 0..2: operands of the next step are fetched while this step multiplies;
-        // a third of the staged stage kt+1 is expanded into the other buffer per step and
-        // its registers are refilled with stage kt+2
+    // One K stage.  P = kt & 1 is a compile-time constant so that the staging set and the
+    // LDS buffer are static.  A wavefront issues in order, so the matrix instructions are
+    // interleaved one by one with the LDS reads of the next step, the expansion of stage
+    // kt+1 into the other buffer and the refill of its registers with stage kt+3.
+    auto stage_body = [&](int kt, auto Pc) {
+        constexpr int P = decltype(Pc)::value;
+        uint8_t* cur = smem + P * STAGE;
+        uint8_t* nxt = smem + (P ^ 1) * STAGE;
+        const int k3 = (kt + 3 < nk) ? kt + 3 : nk - 1;
 #pragma unroll
         for (int s = 0; s < 3; ++s) {
             read_frags(cur, s + 1, (s + 1) & 1);
-            mfma_step(s & 1);
 #pragma unroll
             for (int idx = 0; idx < L; ++idx)
                 if (idx % 3 == s) {
-                    expand_store(idx, nxt);
-                    gload(idx, k2);
+                    expand_store(P, idx, nxt);
+                    gload(P, idx, k3);
                 }
+            mfma_step(s & 1);
+#pragma unroll
+            for (int q = 0; q < TM * TN; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one matrix instruction
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
+                __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);  // VALU (expansion, addresses)
+                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // LDS write
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // global load
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
         lds_barrier();  // stage kt+1 complete in nxt; nobody reads cur any more
+        __builtin_amdgcn_sched_barrier(0);
         read_frags(nxt, 0, 0);
         mfma_step(1);
+#pragma unroll
+        for (int q = 0; q < TM * TN; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    for (int kt = 0; kt + 1 < nk; kt += 2) {
+        stage_body(kt, std::integral_constant<int, 0>{});
+        stage_body(kt + 1, std::integral_constant<int, 1>{});
     }
+    if (nk & 1) stage_body(nk - 1, std::integral_constant<int, 0>{});
 
     // ---- epilogue: lane owns column n = ... + r and 16 rows per 32 x 32 tile
 #pragma unroll
@@ -187,6 +218,255 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_i8(const uint8_t* __restr
             }
         }
     }
+}
+
+// ---------------------------------------------------------------------------------------
+// Variant with packed nibbles in LDS, filled by direct global->LDS loads.
+//
+// LDS writes are the scarce resource of the int8 layout above (each packed byte becomes two
+// bytes that have to be stored and read again).  Here the packed bytes go from HBM straight
+// into LDS (global_load_lds_dwordx4: no staging registers, no ds_write), a ring of NS stages
+// deep, and every wavefront expands what it reads (three VALU operations per packed dword,
+// interleaved one by one with the matrix instructions).
+//
+// LDS layout of a stage: plain rows of 64 packed bytes; the 16-byte chunk c of row q sits at
+// chunk position c ^ ((q >> 2) & 3), which makes the 16-byte reads of 32 consecutive rows
+// conflict-free.  One direct load of a wavefront fills 1 KiB = 16 rows, lane l fetching row
+// l / 4, position l % 4 (so 4 lanes read 64 contiguous bytes of HBM).
+// Compile-time instruction schedule of one half stage (64 channels) of a wavefront tile
+// of TM x TN matrix tiles.  A wavefront issues in order, so expansion work (VALU) only
+// overlaps the matrix pipe if it sits between matrix instructions in program order.  The
+// half stage has two phases (even channels, odd channels) of TM*TN matrix instructions
+// each.  Tiles are visited in a growing-square order so that a new operand is needed only
+// every other instruction; the expansion micro-operations (2 per dword for an even
+// operand: shift, mask; 1 per dword for an odd one: mask) are listed in the order the
+// operands are needed and spread evenly over the slots, running `lead` micro-operations
+// ahead of the instruction that needs them (into the next half stage at the end).
+template <int TM, int TN>
+struct MmaSched {
+    static constexpr int NM = TM * TN, NOP = TM + TN, NSLOT = 2 * NM, PER = 12 * NOP;
+    int mi[NM], mj[NM], op_is_a[NOP], op_idx[NOP], need[NSLOT], lead;
+    constexpr MmaSched() : mi{}, mj{}, op_is_a{}, op_idx{}, need{}, lead(0)
+    {
+        int nm = 0, no = 0, before[NM] = {};
+        const int D = TM > TN ? TM : TN;
+        for (int d = 0; d < D; ++d) {
+            if (d < TN) {
+                op_is_a[no] = 0; op_idx[no] = d; ++no;
+                for (int i = 0; i < (d < TM ? d : TM); ++i) { mi[nm] = i; mj[nm] = d; before[nm] = no; ++nm; }
+            }
+            if (d < TM) {
+                op_is_a[no] = 1; op_idx[no] = d; ++no;
+                for (int j = 0; j <= (d < TN - 1 ? d : TN - 1); ++j) { mi[nm] = d; mj[nm] = j; before[nm] = no; ++nm; }
+            }
+        }
+        for (int k = 0; k < NM; ++k) { need[k] = 8 * before[k]; need[NM + k] = 8 * NOP + 4 * before[k]; }
+        for (int n = 0; n < NSLOT; ++n) {
+            const int def = need[n] - n * PER / NSLOT;
+            if (def > lead) lead = def;
+        }
+    }
+};
+template <int TM, int TN> inline constexpr MmaSched<TM, TN> kSched{};
+
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+#define PQ_LDS(p) ((__attribute__((address_space(3))) void*)(p))
+#define PQ_GLB(p) ((const __attribute__((address_space(1))) void*)(p))
+
+template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
+template <int BM, int BN, int WR, int WC, int NS>
+__global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __restrict__ xq,
+                                                          const uint8_t* __restrict__ wq,
+                                                          const float* __restrict__ sw, float sx, int M, int N,
+                                                          int K, int GM, __half* __restrict__ out,
+                                                          int32_t* __restrict__ acc_out)
+{
+    constexpr int NW = WR * WC;
+    constexpr int WM = BM / WR, WN = BN / WC, TM = WM / 32, TN = WN / 32;
+    constexpr int A_BYTES = BM * 64, STAGE = (BM + BN) * 64;
+    constexpr int BLK = (BM + BN) / 16;   // 1 KiB blocks per stage
+    constexpr int LW = BLK / NW;          // direct loads per wavefront per stage
+    static_assert(BLK % NW == 0 && (BM / 16) % NW == 0, "loader shape");
+    constexpr int LWA = (BM / 16) / NW;   // of which for the activation rows
+    extern __shared__ __align__(16) uint8_t smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: keeps LDS targets in scalar registers
+    const int wm = wave / WC, wn = wave % WC;
+    const int r = lane & 31, g = lane >> 5;
+
+    const int tile = xcd_remap(blockIdx.x, gridDim.x);
+    const int m0 = (tile % GM) * BM, n0 = (tile / GM) * BN;
+    const int Kb = K >> 1;
+    const int nk = K >> 7;
+
+    // ---- loader
+    const int lrow = lane >> 2, lpos = lane & 3;
+    const int lchunk = lpos ^ ((lrow >> 2) & 3);
+    uint32_t goff[LW];
+#pragma unroll
+    for (int i = 0; i < LW; ++i) {
+        const int blk = wave + NW * i;  // blocks [0, BM/16) hold activation rows, the rest weight rows
+        int row;
+        if (i < LWA) {
+            row = m0 + blk * 16 + lrow;
+            row = row < M ? row : M - 1;
+        } else {
+            row = n0 + (blk - BM / 16) * 16 + lrow;
+            row = row < N ? row : N - 1;
+        }
+        goff[i] = (uint32_t)row * (uint32_t)Kb + lchunk * 16;
+    }
+    auto dma_stage = [&](int kt, int buf) {
+#pragma unroll
+        for (int i = 0; i < LW; ++i) {
+            const uint8_t* src = (i < LWA ? xq : wq) + (size_t)kt * 64 + goff[i];
+            __builtin_amdgcn_global_load_lds(PQ_GLB(src), PQ_LDS(smem + buf * STAGE + (wave + NW * i) * 1024), 16, 0, 0);
+        }
+    };
+
+    // ---- reader
+    const int swr = (r >> 2) & 3;
+    const int rdA0 = (wm * WM + r) * 64 + (((0 + g) ^ swr) << 4), rdA1 = (wm * WM + r) * 64 + (((2 + g) ^ swr) << 4);
+    const int rdB0 = A_BYTES + (wn * WN + r) * 64 + (((0 + g) ^ swr) << 4);
+    const int rdB1 = A_BYTES + (wn * WN + r) * 64 + (((2 + g) ^ swr) << 4);
+
+    v16i acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+
+    using SC = MmaSched<TM, TN>;
+    v4i pa[2][TM], pb[2][TN];         // packed operands of the current / next half stage
+    v4i xa[2][2][TM], xb[2][2][TN];   // expanded: [half-stage parity][even, odd][tile]
+    constexpr int MASK = (int)0xF0F0F0F0u;
+
+    auto read_frag = [&](const uint8_t* stage, int kk, int set, int f) {  // f < TM: activations, else weights
+        if (f < TM)
+            pa[set][f] = *reinterpret_cast<const v4i*>(stage + (kk ? rdA1 : rdA0) + f * 2048);
+        else
+            pb[set][f - TM] = *reinterpret_cast<const v4i*>(stage + (kk ? rdB1 : rdB0) + (f - TM) * 2048);
+    };
+    // expansion micro-operation u (0 <= u < PER) of the half stage with parity `set`
+    auto micro = [&](auto setc, auto uc) {
+        constexpr int set = decltype(setc)::value, u = decltype(uc)::value;
+        if constexpr (u < 8 * SC::NOP) {
+            constexpr int o = u / 8, d = (u % 8) / 2, kind = u % 2;
+            constexpr int idx = kSched<TM, TN>.op_idx[o];
+            if constexpr (kSched<TM, TN>.op_is_a[o]) {
+                if constexpr (kind == 0) xa[set][0][idx][d] = pa[set][idx][d] << 4; else xa[set][0][idx][d] &= MASK;
+            } else {
+                if constexpr (kind == 0) xb[set][0][idx][d] = pb[set][idx][d] << 4; else xb[set][0][idx][d] &= MASK;
+            }
+        } else {
+            constexpr int v = u - 8 * SC::NOP, o = v / 4, d = v % 4;
+            constexpr int idx = kSched<TM, TN>.op_idx[o];
+            if constexpr (kSched<TM, TN>.op_is_a[o]) xa[set][1][idx][d] = pa[set][idx][d] & MASK;
+            else xb[set][1][idx][d] = pb[set][idx][d] & MASK;
+        }
+    };
+    // one half stage: slot n = micro-operations [lead + n*PER/NSLOT, lead + (n+1)*PER/NSLOT), one LDS read
+    // of the next half stage's operands (first TM+TN slots), optionally one direct load, one matrix instruction
+    auto half_stage = [&](auto setc, const uint8_t* next_stage, int next_kk, bool dma, int dma_kt, int dma_buf) {
+        constexpr int set = decltype(setc)::value;
+        static_for<0, SC::NSLOT>([&](auto nc) {
+            constexpr int n = decltype(nc)::value;
+            if constexpr (n < TM + TN) read_frag(next_stage, next_kk, set ^ 1, n);
+            constexpr int u0 = kSched<TM, TN>.lead + n * SC::PER / SC::NSLOT, u1 = kSched<TM, TN>.lead + (n + 1) * SC::PER / SC::NSLOT;
+            static_for<u0, u1>([&](auto uc) {
+                constexpr int u = decltype(uc)::value;
+                if constexpr (u < SC::PER) micro(std::integral_constant<int, set>{}, std::integral_constant<int, u>{});
+                else micro(std::integral_constant<int, set ^ 1>{}, std::integral_constant<int, u - SC::PER>{});
+            });
+            if constexpr (n >= TM + TN && n < TM + TN + LW) {
+                if (dma) {
+                    constexpr int i = n - (TM + TN);
+                    const uint8_t* src = (i < LWA ? xq : wq) + (size_t)dma_kt * 64 + goff[i];
+                    __builtin_amdgcn_global_load_lds(PQ_GLB(src),
+                                                     PQ_LDS(smem + dma_buf * STAGE + (wave + NW * i) * 1024), 16, 0, 0);
+                }
+            }
+            constexpr int ph = n / SC::NM, k = n % SC::NM;
+            constexpr int i = kSched<TM, TN>.mi[k], j = kSched<TM, TN>.mj[k];
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(xa[set][ph][i], xb[set][ph][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+
+    // ---- prologue: fill the ring, fetch the first operands and run the expansion `lead` ahead
+#pragma unroll
+    for (int st = 0; st < NS; ++st) dma_stage(st < nk ? st : nk - 1, st);
+    wait_vm<(NS - 1) * LW>();
+    lds_barrier();
+    static_for<0, TM + TN>([&](auto fc) { read_frag(smem, 0, 0, decltype(fc)::value); });
+    static_for<0, kSched<TM, TN>.lead>([&](auto uc) { micro(std::integral_constant<int, 0>{}, uc); });
+    __builtin_amdgcn_sched_barrier(0);
+
+    int buf = 0;
+    for (int kt = 0; kt < nk; ++kt) {
+        const uint8_t* cur = smem + buf * STAGE;
+        const int nbuf = (buf + 1 == NS) ? 0 : buf + 1;
+        half_stage(std::integral_constant<int, 0>{}, cur, 1, false, 0, 0);
+        // stage kt+1 has landed (its loads were issued NS-1 stages ago); after the barrier all
+        // reads of stage kt are done, so its buffer can be refilled
+        wait_vm<(NS - 2) * LW>();
+        lds_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        half_stage(std::integral_constant<int, 1>{}, smem + nbuf * STAGE, 0, true, kt + NS < nk ? kt + NS : nk - 1, buf);
+        buf = nbuf;
+    }
+    wait_vm<0>();  // no direct load may still be writing LDS when the wavefront ends
+
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = n0 + wn * WN + j * 32 + r;
+        if (n >= N) continue;
+        const float sc = sx * sw[n];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + wm * WM + i * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+                if (m < M) {
+                    const int a = acc[i][j][v] >> 8;
+                    if (acc_out) acc_out[(int64_t)m * N + n] = a;
+                    if (out) out[(int64_t)m * N + n] = __float2half_rn((float)a * sc);
+                }
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int WR, int WC, int NS>
+int launch_dma(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K, void* out,
+               int32_t* acc, hipStream_t st)
+{
+    const int GM = (int)((M + BM - 1) / BM), GN = (int)((N + BN - 1) / BN);
+    constexpr size_t lds = (size_t)NS * (BM + BN) * 64;
+    auto kern = k_gemm_dma<BM, BN, WR, WC, NS>;
+    static bool attr_set = false;  // benign race: the call is idempotent
+    if (lds > 48 * 1024 && !attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return PQ_ERR_HIP;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)(GM * GN)), dim3(WR * WC * 64), lds, st,
+                       static_cast<const uint8_t*>(xq), static_cast<const uint8_t*>(wq), sw, sx, (int)M, (int)N,
+                       (int)K, GM, static_cast<__half*>(out), acc);
+    return hip_status(hipGetLastError());
 }
 
 // ---------------------------------------------------------------------------------------
@@ -339,8 +619,9 @@ int launch_ragged(const void* xq, const void* wq, const float* sw, float sx, int
 
 struct TileCfg { int bm, bn; double eff; };
 // relative efficiency guesses per tile (larger wave tiles need fewer LDS reads per multiply)
-constexpr int kNumCfg = 4;
-constexpr TileCfg kCfgs[kNumCfg] = {{256, 256, 1.00}, {256, 128, 0.92}, {128, 128, 0.80}, {256, 256, 1.0}};
+constexpr int kNumCfg = 9;
+constexpr TileCfg kCfgs[kNumCfg] = {{256, 256, 1.00}, {256, 128, 0.92}, {128, 128, 0.80}, {256, 256, 1.0},
+                                    {256, 256, 1.0}, {256, 128, 1.0}, {256, 256, 1.0}, {128, 128, 1.0}, {256, 256, 1.0}};
 
 int pick_cfg(int64_t M, int64_t N)
 {
@@ -365,12 +646,18 @@ int launch_gemm_mfma(const void* xq, const void* wq, const float* sw, float sx, 
                      void* out, int32_t* acc, hipStream_t st)
 {
     if (M > (1 << 30) || N > (1 << 30) || K > (1 << 30)) return PQ_ERR_UNSUPPORTED;
+    if (M * (K / 2) >= ((int64_t)1 << 32) || N * (K / 2) >= ((int64_t)1 << 32)) return PQ_ERR_UNSUPPORTED;
     if (K % 128 != 0) return launch_ragged(xq, wq, sw, sx, M, N, K, out, acc, st);
     switch (pick_cfg(M, N)) {
         case 0: return launch_i8<256, 256, 2, 2>(xq, wq, sw, sx, M, N, K, out, acc, st);
         case 1: return launch_i8<256, 128, 2, 2>(xq, wq, sw, sx, M, N, K, out, acc, st);
         case 2: return launch_i8<128, 128, 2, 2>(xq, wq, sw, sx, M, N, K, out, acc, st);
-        default: return launch_i8<256, 256, 2, 4>(xq, wq, sw, sx, M, N, K, out, acc, st);
+        case 3: return launch_i8<256, 256, 2, 4>(xq, wq, sw, sx, M, N, K, out, acc, st);
+        case 4: return launch_dma<256, 256, 2, 2, 3>(xq, wq, sw, sx, M, N, K, out, acc, st);
+        case 5: return launch_dma<256, 128, 2, 2, 3>(xq, wq, sw, sx, M, N, K, out, acc, st);
+        case 6: return launch_dma<256, 256, 2, 4, 3>(xq, wq, sw, sx, M, N, K, out, acc, st);
+        case 7: return launch_dma<128, 128, 2, 2, 3>(xq, wq, sw, sx, M, N, K, out, acc, st);
+        default: return launch_dma<256, 256, 2, 2, 4>(xq, wq, sw, sx, M, N, K, out, acc, st);
     }
 }
 
