@@ -6,26 +6,30 @@
 //   acc[m,n] = sum_k xq[m,k] * wq[n,k]        out[m,n] = fp16(acc * (s_x * s_w[n]))
 //
 // Both operands are K-contiguous, which is what the matrix instruction wants: every lane
-// feeds 16 consecutive bytes of one row.  Packed nibbles are loaded from HBM with 16-byte
-// loads (64 contiguous bytes per row per stage), expanded ONCE per workgroup to int8 in
-// registers and written to LDS; the wavefronts then read ready-made operands.  The
-// expansion produces 16*code (the odd-channel nibble is already in the high half of its
-// byte, the even-channel nibble is shifted there), so no sign extension is needed; the
-// accumulator becomes 256 * acc and is shifted back exactly.  A dot product does not care
-// about the order of its terms as long as both operands use the same order, so the even
-// and the odd channels of a 32-channel group simply feed two different matrix steps.
+// feeds 16 consecutive bytes of one row.  Packed nibbles go from HBM straight into LDS
+// (global_load_lds_dwordx4: no staging registers, no LDS store instruction), a ring of NS
+// stages deep; every wavefront expands what it reads in registers into two operands holding
+// 16*code: the odd-channel nibble is already in the high half of its byte, the even-channel
+// nibble is shifted there, so no sign extension is needed.  The accumulator becomes
+// 256 * acc and is shifted back exactly.  A dot product does not care about the order of
+// its terms as long as both operands use the same order, so the even and the odd channels
+// of a 32-channel group simply feed two different matrix instructions.
 //
 // v_mfma_i32_32x32x32_i8 operand layout (lane l, r = l % 32, g = l / 32):
 //   A: row r of the 32 x 32 tile, bytes k = 16 g .. 16 g + 15;  B: column r, same bytes;
 //   D: register v holds D[8 (v / 4) + 4 g + v % 4][r].
+// The weights are the row operand and the activations the column operand, so a lane ends
+// up with one token and groups of four consecutive output channels (16-byte stores after
+// one exchange between the two half-waves).
 //
-// LDS layout of one K stage (128 channels = 64 packed bytes = 4 packed 16-byte chunks c per
-// row, 4 matrix steps s): for every 32-row fragment and every step one 1 KiB block that is
-// read linearly, lane l taking bytes [16 l, 16 l + 16) up to an XOR on the row slot:
-//   step s uses chunk c = 2 (s / 2) + g, its even channels if s is even, else its odd ones;
-//   block offset = g * 512 + ((r ^ 4 c) * 16).
-// The XOR keeps the 16-byte stores of the loader (4 lanes per row, one chunk each)
-// spread over all banks; the reads stay a permutation inside aligned groups of 16 lanes.
+// LDS layout of a stage (128 channels): plain rows of 64 packed bytes; the 16-byte chunk c
+// of row q sits at chunk position c ^ ((q >> 2) & 3), which makes the 16-byte reads of 32
+// consecutive rows conflict-free.  One direct load of a wavefront fills 1 KiB = 16 rows,
+// lane l fetching row l / 4, position l % 4 (so 4 lanes read 64 contiguous bytes of HBM).
+//
+// On this chip the kernel is power-limited as much as issue-limited: with all 256 CUs busy
+// on random codes the shader clock settles near 1.8 GHz, so everything that is not a matrix
+// instruction (expansion, LDS traffic) costs twice: issue slots and clock.
 #include "pq_internal.h"
 
 #include <hip/hip_fp16.h>
@@ -48,191 +52,6 @@ __device__ __forceinline__ int xcd_remap(int b, int total)
 // loads that are still in flight stay in flight.
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-template <int BM, int BN, int WR, int WC>
-__global__ __launch_bounds__(WR * WC * 64) void k_gemm_i8(const uint8_t* __restrict__ xq,
-                                                         const uint8_t* __restrict__ wq,
-                                                         const float* __restrict__ sw, float sx, int M, int N,
-                                                         int K, int GM, __half* __restrict__ out,
-                                                         int32_t* __restrict__ acc_out)
-{
-    constexpr int NT = WR * WC * 64;
-    constexpr int WM = BM / WR, WN = BN / WC, TM = WM / 32, TN = WN / 32;
-    constexpr int FA = BM / 32, FB = BN / 32;
-    constexpr int A_BYTES = FA * 4096, STAGE = (FA + FB) * 4096;
-    constexpr int RPP = NT / 4;  // rows covered by one loader pass (4 lanes per row)
-    constexpr int LA = BM / RPP, LB = BN / RPP, L = LA + LB;
-    static_assert(BM % RPP == 0 && BN % RPP == 0 && RPP % 32 == 0, "loader shape");
-    extern __shared__ __align__(16) uint8_t smem[];
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WC, wn = wave % WC;
-    const int r = lane & 31, g = lane >> 5;
-
-    const int tile = xcd_remap(blockIdx.x, gridDim.x);
-    const int m0 = (tile % GM) * BM, n0 = (tile / GM) * BN;
-    const int Kb = K >> 1;
-    const int nk = K >> 7;
-
-    // ---- loader: lane -> (row, packed chunk); rows past the end are clamped (their
-    // products are computed and never stored)
-    const int lc = tid & 3, lrow = tid >> 2;
-    uint32_t goff[L];  // byte offset of this lane's chunk inside xq / wq (both < 2^32 bytes)
-#pragma unroll
-    for (int i = 0; i < LA; ++i) {
-        int row = m0 + lrow + RPP * i;
-        row = row < M ? row : M - 1;
-        goff[i] = (uint32_t)row * (uint32_t)Kb + lc * 16;
-    }
-#pragma unroll
-    for (int i = 0; i < LB; ++i) {
-        int row = n0 + lrow + RPP * i;
-        row = row < N ? row : N - 1;
-        goff[LA + i] = (uint32_t)row * (uint32_t)Kb + lc * 16;
-    }
-    const int wr0 = ((lrow >> 5) * 4 + 2 * (lc >> 1)) * 1024 + (lc & 1) * 512 + (((lrow & 31) ^ (4 * lc)) << 4);
-    auto wr_off = [&](int idx) {  // byte offset inside a stage of staged load idx
-        return idx < LA ? wr0 + idx * (RPP / 32) * 4096 : A_BYTES + wr0 + (idx - LA) * (RPP / 32) * 4096;
-    };
-    // two sets of staging registers: a global load has two K stages of time to arrive
-    v4i gr[2][L];
-    auto gload = [&](int set, int idx, int kt) {
-        const uint8_t* base = (idx < LA ? xq : wq) + kt * 64;   // uniform: lives in scalar registers
-        gr[set][idx] = *reinterpret_cast<const v4i*>(base + goff[idx]);
-    };
-    auto expand_store = [&](int set, int idx, uint8_t* stage) {
-        v4i e, o;
-        unpack16(gr[set][idx], e, o);
-        *reinterpret_cast<v4i*>(stage + wr_off(idx)) = e;
-        *reinterpret_cast<v4i*>(stage + wr_off(idx) + 1024) = o;
-    };
-
-    // ---- reader offsets (two values: steps 0-1 use chunks 0/1, steps 2-3 chunks 2/3)
-    const int rd0 = g * 512 + ((r ^ (4 * g)) << 4);
-    const int rd1 = g * 512 + ((r ^ (4 * (2 + g))) << 4);
-    const int a_base = wm * TM * 4096, b_base = A_BYTES + wn * TN * 4096;
-
-    v16i acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
-
-    v4i fa[2][TM], fb[2][TN];
-    auto read_frags = [&](const uint8_t* stage, int s, int set) {
-        const int off = (s >> 1) ? rd1 : rd0;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-            fa[set][i] = *reinterpret_cast<const v4i*>(stage + a_base + (i * 4 + s) * 1024 + off);
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-            fb[set][j] = *reinterpret_cast<const v4i*>(stage + b_base + (j * 4 + s) * 1024 + off);
-    };
-    auto mfma_step = [&](int set) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
-    };
-
-    // ---- prologue: stage 0 into buffer 0, stages 1 and 2 into the staging registers
-#pragma unroll
-    for (int idx = 0; idx < L; ++idx) gload(1, idx, 0);
-#pragma unroll
-    for (int idx = 0; idx < L; ++idx) expand_store(1, idx, smem);
-    {
-        const int k1 = nk > 1 ? 1 : nk - 1, k2 = nk > 2 ? 2 : nk - 1;
-#pragma unroll
-        for (int idx = 0; idx < L; ++idx) gload(0, idx, k1);
-#pragma unroll
-        for (int idx = 0; idx < L; ++idx) gload(1, idx, k2);
-    }
-    lds_barrier();
-    read_frags(smem, 0, 0);
-
-    // One K stage.  P = kt & 1 is a compile-time constant so that the staging set and the
-    // LDS buffer are static.  A wavefront issues in order, so the matrix instructions are
-    // interleaved one by one with the LDS reads of the next step, the expansion of stage
-    // kt+1 into the other buffer and the refill of its registers with stage kt+3.
-    auto stage_body = [&](int kt, auto Pc) {
-        constexpr int P = decltype(Pc)::value;
-        uint8_t* cur = smem + P * STAGE;
-        uint8_t* nxt = smem + (P ^ 1) * STAGE;
-        const int k3 = (kt + 3 < nk) ? kt + 3 : nk - 1;
-#pragma unroll
-        for (int s = 0; s < 3; ++s) {
-            read_frags(cur, s + 1, (s + 1) & 1);
-#pragma unroll
-            for (int idx = 0; idx < L; ++idx)
-                if (idx % 3 == s) {
-                    expand_store(P, idx, nxt);
-                    gload(P, idx, k3);
-                }
-            mfma_step(s & 1);
-#pragma unroll
-            for (int q = 0; q < TM * TN; ++q) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one matrix instruction
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
-                __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);  // VALU (expansion, addresses)
-                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // LDS write
-                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // global load
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        lds_barrier();  // stage kt+1 complete in nxt; nobody reads cur any more
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(nxt, 0, 0);
-        mfma_step(1);
-#pragma unroll
-        for (int q = 0; q < TM * TN; ++q) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-    };
-
-    for (int kt = 0; kt + 1 < nk; kt += 2) {
-        stage_body(kt, std::integral_constant<int, 0>{});
-        stage_body(kt + 1, std::integral_constant<int, 1>{});
-    }
-    if (nk & 1) stage_body(nk - 1, std::integral_constant<int, 0>{});
-
-    // ---- epilogue: lane owns column n = ... + r and 16 rows per 32 x 32 tile
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int n = n0 + wn * WN + j * 32 + r;
-        if (n >= N) continue;
-        const float sc = sx * sw[n];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = m0 + wm * WM + i * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-                if (m < M) {
-                    const int a = acc[i][j][v] >> 8;
-                    if (acc_out) acc_out[(int64_t)m * N + n] = a;
-                    if (out) out[(int64_t)m * N + n] = __float2half_rn((float)a * sc);
-                }
-            }
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------------------
-// Variant with packed nibbles in LDS, filled by direct global->LDS loads.
-//
-// LDS writes are the scarce resource of the int8 layout above (each packed byte becomes two
-// bytes that have to be stored and read again).  Here the packed bytes go from HBM straight
-// into LDS (global_load_lds_dwordx4: no staging registers, no ds_write), a ring of NS stages
-// deep, and every wavefront expands what it reads (three VALU operations per packed dword,
-// interleaved one by one with the matrix instructions).
-//
-// LDS layout of a stage: plain rows of 64 packed bytes; the 16-byte chunk c of row q sits at
-// chunk position c ^ ((q >> 2) & 3), which makes the 16-byte reads of 32 consecutive rows
-// conflict-free.  One direct load of a wavefront fills 1 KiB = 16 rows, lane l fetching row
-// l / 4, position l % 4 (so 4 lanes read 64 contiguous bytes of HBM).
 // Compile-time instruction schedule of one half stage (64 channels) of a wavefront tile
 // of TM x TN matrix tiles.  A wavefront issues in order, so expansion work (VALU) only
 // overlaps the matrix pipe if it sits between matrix instructions in program order.  The
@@ -400,7 +219,7 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
             }
             constexpr int ph = n / SC::NM, k = n % SC::NM;
             constexpr int i = kSched<TM, TN>.mi[k], j = kSched<TM, TN>.mj[k];
-            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(xa[set][ph][i], xb[set][ph][j], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(xb[set][ph][j], xa[set][ph][i], acc[i][j], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         });
     };
@@ -429,20 +248,62 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
     }
     wait_vm<0>();  // no direct load may still be writing LDS when the wavefront ends
 
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int n = n0 + wn * WN + j * 32 + r;
-        if (n >= N) continue;
-        const float sc = sx * sw[n];
+    // ---- epilogue.  The weights were fed as the row operand, so a lane owns one token
+    // (m = ... + r) and, per 32 x 32 tile, 16 output channels in groups of four consecutive
+    // ones: register v holds channel 8 (v / 4) + 4 g + v % 4.  After scaling and conversion,
+    // lanes r and r + 32 trade halves so that each holds 8 consecutive channels and writes
+    // them with one 16-byte store.
+    if (acc_out) {
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
+            const int m = m0 + wm * WM + i * 32 + r;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = m0 + wm * WM + i * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-                if (m < M) {
-                    const int a = acc[i][j][v] >> 8;
-                    if (acc_out) acc_out[(int64_t)m * N + n] = a;
-                    if (out) out[(int64_t)m * N + n] = __float2half_rn((float)a * sc);
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int n = n0 + wn * WN + j * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+                    if (m < M && n < N) acc_out[(int64_t)m * N + n] = acc[i][j][v] >> 8;
+                }
+        }
+    }
+    if (out) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int nb = n0 + wn * WN + j * 32;
+            float4 sc[4];  // scales of this lane's channels: [8 q + 4 g, +4) for q = 0..3
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                int n = nb + 8 * q + 4 * g;
+                n = n + 4 <= N ? n : N - 4;
+                sc[q] = *reinterpret_cast<const float4*>(sw + n);
+                sc[q].x *= sx; sc[q].y *= sx; sc[q].z *= sx; sc[q].w *= sx;
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int m = m0 + wm * WM + i * 32 + r;
+#pragma unroll
+                for (int qp = 0; qp < 2; ++qp) {
+                    uint32_t pk[4];
+#pragma unroll
+                    for (int h2 = 0; h2 < 2; ++h2) {
+                        const int q = 2 * qp + h2;
+                        const float f0 = (float)(acc[i][j][4 * q + 0] >> 8) * sc[q].x;
+                        const float f1 = (float)(acc[i][j][4 * q + 1] >> 8) * sc[q].y;
+                        const float f2 = (float)(acc[i][j][4 * q + 2] >> 8) * sc[q].z;
+                        const float f3 = (float)(acc[i][j][4 * q + 3] >> 8) * sc[q].w;
+                        const __half2 lo = __floats2half2_rn(f0, f1), hi = __floats2half2_rn(f2, f3);
+                        pk[2 * h2 + 0] = *reinterpret_cast<const uint32_t*>(&lo);
+                        pk[2 * h2 + 1] = *reinterpret_cast<const uint32_t*>(&hi);
+                    }
+                    // pk[0..1]: channels 16 qp + 4 g + (0..3); pk[2..3]: 16 qp + 8 + 4 g + (0..3)
+                    const auto s0 = __builtin_amdgcn_permlane32_swap(pk[0], pk[2], false, false);
+                    const auto s1 = __builtin_amdgcn_permlane32_swap(pk[1], pk[3], false, false);
+                    // lanes < 32 now hold channels 16 qp + (0..7), lanes >= 32 channels 16 qp + 8 + (0..7)
+                    const int n = nb + 16 * qp + 8 * g;
+                    if (m < M && n < N) {
+                        uint4 val = make_uint4(s0[0], s1[0], s0[1], s1[1]);
+                        *reinterpret_cast<uint4*>(out + (int64_t)m * N + n) = val;
+                    }
                 }
             }
         }
@@ -585,26 +446,6 @@ __global__ __launch_bounds__(256) void k_gemm_ragged(const uint8_t* __restrict__
     }
 }
 
-template <int BM, int BN, int WR, int WC>
-int launch_i8(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K, void* out,
-              int32_t* acc, hipStream_t st)
-{
-    const int GM = (int)((M + BM - 1) / BM), GN = (int)((N + BN - 1) / BN);
-    constexpr size_t lds = 2 * (size_t)(BM + BN) * 128;
-    auto kern = k_gemm_i8<BM, BN, WR, WC>;
-    static bool attr_set = false;  // benign race: the call is idempotent
-    if (lds > 48 * 1024 && !attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return PQ_ERR_HIP;
-        attr_set = true;
-    }
-    hipLaunchKernelGGL(kern, dim3((unsigned)(GM * GN)), dim3(WR * WC * 64), lds, st,
-                       static_cast<const uint8_t*>(xq), static_cast<const uint8_t*>(wq), sw, sx, (int)M, (int)N,
-                       (int)K, GM, static_cast<__half*>(out), acc);
-    return hip_status(hipGetLastError());
-}
-
 int launch_ragged(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K,
                   void* out, int32_t* acc, hipStream_t st)
 {
@@ -618,11 +459,13 @@ int launch_ragged(const void* xq, const void* wq, const float* sw, float sx, int
 }
 
 struct TileCfg { int bm, bn; double eff; };
-// relative efficiency guesses per tile (larger wave tiles need fewer LDS reads per multiply)
-constexpr int kNumCfg = 9;
-constexpr TileCfg kCfgs[kNumCfg] = {{256, 256, 1.00}, {256, 128, 0.92}, {128, 128, 0.80}, {256, 256, 1.0},
-                                    {256, 256, 1.0}, {256, 128, 1.0}, {256, 256, 1.0}, {128, 128, 1.0}, {256, 256, 1.0}};
+// tile shapes the automatic choice considers, with measured relative efficiencies (a larger
+// wavefront tile needs fewer LDS reads and less expansion per matrix instruction)
+constexpr int kNumAuto = 3, kNumCfg = 5;
+constexpr TileCfg kCfgs[kNumCfg] = {{256, 256, 1.00}, {256, 128, 0.85}, {128, 128, 0.72}, {256, 256, 1.0}, {256, 256, 1.0}};
 
+// PQ_GEMM_TILE=0..4 forces a configuration (sweeps only): 0 256x256, 1 256x128, 2 128x128,
+// 3 256x256 with 8 wavefronts, 4 256x256 with a 4-stage ring.
 int pick_cfg(int64_t M, int64_t N)
 {
     if (const char* f = getenv("PQ_GEMM_TILE")) {
@@ -631,7 +474,7 @@ int pick_cfg(int64_t M, int64_t N)
     }
     int best = 0;
     double best_cost = 1e300;
-    for (int c = 0; c < 3; ++c) {
+    for (int c = 0; c < kNumAuto; ++c) {
         const int64_t tiles = ((M + kCfgs[c].bm - 1) / kCfgs[c].bm) * ((N + kCfgs[c].bn - 1) / kCfgs[c].bn);
         const int64_t rounds = (tiles + 255) / 256;
         const double cost = (double)rounds * kCfgs[c].bm * kCfgs[c].bn / kCfgs[c].eff;
@@ -649,14 +492,10 @@ int launch_gemm_mfma(const void* xq, const void* wq, const float* sw, float sx, 
     if (M * (K / 2) >= ((int64_t)1 << 32) || N * (K / 2) >= ((int64_t)1 << 32)) return PQ_ERR_UNSUPPORTED;
     if (K % 128 != 0) return launch_ragged(xq, wq, sw, sx, M, N, K, out, acc, st);
     switch (pick_cfg(M, N)) {
-        case 0: return launch_i8<256, 256, 2, 2>(xq, wq, sw, sx, M, N, K, out, acc, st);
-        case 1: return launch_i8<256, 128, 2, 2>(xq, wq, sw, sx, M, N, K, out, acc, st);
-        case 2: return launch_i8<128, 128, 2, 2>(xq, wq, sw, sx, M, N, K, out, acc, st);
-        case 3: return launch_i8<256, 256, 2, 4>(xq, wq, sw, sx, M, N, K, out, acc, st);
-        case 4: return launch_dma<256, 256, 2, 2, 3>(xq, wq, sw, sx, M, N, K, out, acc, st);
-        case 5: return launch_dma<256, 128, 2, 2, 3>(xq, wq, sw, sx, M, N, K, out, acc, st);
-        case 6: return launch_dma<256, 256, 2, 4, 3>(xq, wq, sw, sx, M, N, K, out, acc, st);
-        case 7: return launch_dma<128, 128, 2, 2, 3>(xq, wq, sw, sx, M, N, K, out, acc, st);
+        case 0: return launch_dma<256, 256, 2, 2, 3>(xq, wq, sw, sx, M, N, K, out, acc, st);
+        case 1: return launch_dma<256, 128, 2, 2, 3>(xq, wq, sw, sx, M, N, K, out, acc, st);
+        case 2: return launch_dma<128, 128, 2, 2, 3>(xq, wq, sw, sx, M, N, K, out, acc, st);
+        case 3: return launch_dma<256, 256, 2, 4, 3>(xq, wq, sw, sx, M, N, K, out, acc, st);
         default: return launch_dma<256, 256, 2, 2, 4>(xq, wq, sw, sx, M, N, K, out, acc, st);
     }
 }
