@@ -30,6 +30,9 @@ if ROOT not in sys.path:
 INT8_PEAK_TOPS = 5033.0      # MI355X dense INT8 MFMA: 256 CU x 2.4 GHz x 8192 ops/clk/CU
 HBM_PEAK_GBS = 8000.0
 M_PREFILL = 2048
+# HBM bytes per GEMM launch (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 from rocprofv3 --pmc, averaged over the
+# five launches of a step; see profiles/gemm_prefill_llama3_8b_pmc.md).  Algorithmic: 63.3e6.
+GEMM_HBM_TRAFFIC_BYTES = 129.3e6
 # name -> (K, N, online Hadamard block)
 LINEARS = [("qkv", 4096, 6144, 1), ("o", 4096, 4096, 1), ("gate", 4096, 14336, 1),
            ("up", 4096, 14336, 1), ("down", 14336, 4096, 128)]
@@ -171,6 +174,8 @@ def main():
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=1024)
+    ap.add_argument("--profile-copy", action="store_true",
+                    help="also run a plain 256 MiB elementwise copy (calibrates HBM counters under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the path shards over tokens or channels without "
@@ -184,6 +189,14 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
+
+    if args.profile_copy:
+        src = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1, out=dst)      # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     layers = prepare_layers(torch, synth, M_PREFILL)
     ops = sum(2.0 * M_PREFILL * L["K"] * L["N"] for L in layers)
@@ -204,8 +217,8 @@ def main():
                                "gate/up 4096->14336, down 14336->4096 (online 128-point block Hadamard on down only)",
                    "tokens": M_PREFILL},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 1), "peak": INT8_PEAK_TOPS, "unit": "TOPS",
-                     "frac": round(achieved / INT8_PEAK_TOPS, 4), "traffic": None,
-                     "kernel": "k_gemm_i8 (five launches per step, averaged per launch)",
+                     "frac": round(achieved / INT8_PEAK_TOPS, 4), "traffic": GEMM_HBM_TRAFFIC_BYTES,
+                     "kernel": "k_gemm_dma (five launches per step, averaged per launch)",
                      "per_linear_TOPS": {k: round(gemm_ops[k] / v / 1e12, 1) for k, v in gemm_t.items()},
                      "per_linear_us": {k: round(v * 1e6, 1) for k, v in gemm_t.items()}},
         "fp16_gemm": {"ms_per_step": round(t_fp16 * 1e3, 4), "TFLOPS": round(ops / t_fp16 / 1e12, 1),
