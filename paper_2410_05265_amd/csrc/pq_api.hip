@@ -6,7 +6,7 @@
 
 namespace {
 
-int g_variant = 0;  // 0 auto, 1 streaming (M <= 16), 2 MFMA tiled, 3 simple
+int g_variant = 0;  // 0 auto, 1 streaming MFMA (M <= 16), 2 MFMA tiled, 3 simple, 4 streaming dot (M <= 4)
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool good_scale(float s) { return isfinite(s) && s > 0.0f; }
@@ -65,8 +65,12 @@ int pq_w4a4_gemm(const void* xq_packed, const void* wq_packed, const float* w_sc
     if (M == 0) return PQ_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
     int v = g_variant;
-    if (v == 0) v = (M <= 16) ? 1 : 2;
+    if (v == 0) v = (M <= 4 && pq::decode_supported(M, N, K, -1)) ? 4 : ((M <= 16) ? 1 : 2);
     switch (v) {
+        case 4:
+            if (!pq::decode_supported(M, N, K, -1)) return PQ_ERR_UNSUPPORTED;
+            return pq::launch_decode(nullptr, xq_packed, wq_packed, w_scale, act_scale, 1, M, N, K, out_f16, acc_i32,
+                                     nullptr, st);
         case 1:
             if (M > 16) return PQ_ERR_UNSUPPORTED;
             return pq::launch_gemv(xq_packed, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32, st);
@@ -103,6 +107,15 @@ int pq_linear(const void* x_f16, const void* wq_packed, const float* w_scale, fl
     // check the second stage's arguments before anything is enqueued
     int rc = check_gemm(workspace, wq_packed, w_scale, act_scale, M, N, K, out_f16, nullptr);
     if (rc != PQ_OK) return rc;
+    if (had_block < 0 || had_block > 16384 ||
+        (had_block > 1 && ((had_block & (had_block - 1)) != 0 || (K % had_block) != 0)))
+        return PQ_ERR_SHAPE;
+    if (!aligned16(x_f16)) return PQ_ERR_ALIGN;
+    // decode: one fused launch (rotate + quantize per workgroup, weights streamed once)
+    // (quantizing a row costs every CU about 0.2 us per 1024 channels, so long rows keep two launches)
+    if (((g_variant == 0 && M * K <= 8192) || g_variant == 4) && pq::decode_supported(M, N, K, had_block))
+        return pq::launch_decode(x_f16, nullptr, wq_packed, w_scale, act_scale, had_block, M, N, K, out_f16, nullptr,
+                                 workspace, static_cast<hipStream_t>(stream));
     rc = pq_rotate_quant(x_f16, M, K, had_block, act_scale, workspace, stream);
     if (rc != PQ_OK) return rc;
     return pq_w4a4_gemm(workspace, wq_packed, w_scale, act_scale, M, N, K, out_f16, nullptr, stream);
@@ -110,7 +123,7 @@ int pq_linear(const void* x_f16, const void* wq_packed, const float* w_scale, fl
 
 int pq_set_gemm_variant(int variant)
 {
-    if (variant < 0 || variant > 3) return -1;
+    if (variant < 0 || variant > 4) return -1;
     const int prev = g_variant;
     g_variant = variant;
     return prev;

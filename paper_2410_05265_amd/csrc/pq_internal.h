@@ -18,6 +18,10 @@ int launch_gemm_mfma(const void* xq, const void* wq, const float* sw, float sx, 
 int launch_gemv(const void* xq, const void* wq, const float* sw, float sx, int64_t M,
                 int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st);
 
+bool decode_supported(int64_t M, int64_t N, int64_t K, int32_t h);
+int launch_decode(const void* x_f16, const void* xq_in, const void* wq, const float* sw, float sx, int32_t h,
+                  int64_t M, int64_t N, int64_t K, void* out, int32_t* acc, void* xq_out, hipStream_t st);
+
 inline int hip_status(hipError_t e) { return e == hipSuccess ? PQ_OK : PQ_ERR_HIP; }
 
 typedef int v4i __attribute__((ext_vector_type(4)));

@@ -1,0 +1,239 @@
+// Device-side building blocks of the online rotation + static 4-bit quantizer, shared by the
+// stand-alone kernel and the fused decode kernel (App. B "Online Rotation" and Eq. 1 of the
+// paper in its symmetric form).  A workgroup of 256 threads transforms one chunk of a row.
+#pragma once
+
+#include "pq_internal.h"
+
+#include <hip/hip_fp16.h>
+#include <type_traits>
+
+namespace pq {
+namespace rq {
+
+constexpr int kThreads = 256;
+constexpr int kChunk = 2048;  // channels per workgroup per group index
+
+// ---- partner exchange between lanes: returns the value held by lane (id ^ (1 << B)).
+template <int B>
+__device__ __forceinline__ int lane_xor_i(int iv)
+{
+    int r;
+    if constexpr (B == 0) {
+        r = __builtin_amdgcn_update_dpp(iv, iv, 0xB1, 0xF, 0xF, false);  // quad_perm [1,0,3,2]
+    } else if constexpr (B == 1) {
+        r = __builtin_amdgcn_update_dpp(iv, iv, 0x4E, 0xF, 0xF, false);  // quad_perm [2,3,0,1]
+    } else if constexpr (B == 2) {
+        // lanes 0-3 and 8-11 of each row of 16 take lane+4, the others lane-4
+        r = __builtin_amdgcn_update_dpp(iv, iv, 0x104, 0xF, 0x5, false);  // row_shl:4
+        r = __builtin_amdgcn_update_dpp(r, iv, 0x114, 0xF, 0xA, false);   // row_shr:4
+    } else if constexpr (B == 3) {
+        r = __builtin_amdgcn_update_dpp(iv, iv, 0x128, 0xF, 0xF, false);  // row_ror:8
+    } else if constexpr (B == 4) {
+        r = __builtin_amdgcn_ds_swizzle(iv, 0x401F);  // bit-mask mode: and 0x1F, xor 0x10
+    } else {
+        r = __shfl_xor(iv, 32, 64);
+    }
+    return r;
+}
+
+template <int B>
+__device__ __forceinline__ float lane_xor(float v)
+{
+    return __int_as_float(lane_xor_i<B>(__float_as_int(v)));
+}
+
+template <int B, int NV>
+__device__ __forceinline__ void lane_stage(float (&v)[NV], int lane)
+{
+    const bool upper = (lane >> B) & 1;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const float p = lane_xor<B>(v[i]);
+        v[i] = upper ? (p - v[i]) : (p + v[i]);
+    }
+}
+
+// d = 1, 2, 4 inside one group of 8
+__device__ __forceinline__ void reg_stages8(float* v, int nstages)
+{
+    if (nstages >= 1) {
+#pragma unroll
+        for (int i = 0; i < 8; i += 2) { float a = v[i], b = v[i + 1]; v[i] = a + b; v[i + 1] = a - b; }
+    }
+    if (nstages >= 2) {
+#pragma unroll
+        for (int i = 0; i < 8; i += 4)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) { float a = v[i + j], b = v[i + j + 2]; v[i + j] = a + b; v[i + j + 2] = a - b; }
+    }
+    if (nstages >= 3) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { float a = v[j], b = v[j + 4]; v[j] = a + b; v[j + 4] = a - b; }
+    }
+}
+
+// Round-to-nearest-even of eight scaled values, clamp to [-8,7], pack low nibble first.
+// `magic` puts round(t) + 8 into the low mantissa bits of an fp32 in [2^23, 2^24).
+constexpr float kMagic = 12582920.0f;            // 1.5 * 2^23 + 8, bit pattern 0x4B400008
+constexpr uint32_t kMagicSum = 0x4B400000u * 0x11111111u;  // sum of (pattern - offset part) << 4i
+
+template <bool EXACT>
+__device__ __forceinline__ uint32_t quant_pack8(const float* v, const float* raw, float mult, float step)
+{
+    float t[8];
+    uint32_t bits[8];
+    bool suspect = false;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        t[i] = v[i] * mult;
+        const float c = __builtin_amdgcn_fmed3f(t[i], -8.0f, 7.0f);
+        const float r = c + kMagic;                 // fp32 add rounds to an integer, ties to even
+        bits[i] = __float_as_uint(r);
+        if constexpr (EXACT) {
+            const float f = c - (r - kMagic);       // exact; |f| <= 0.5
+            suspect |= (fabsf(f) > 0.5f - 0x1.0p-18f);
+        }
+    }
+    if constexpr (EXACT) {
+        // t carries two fp32 roundings (reciprocal and product), so a quotient within
+        // ~1e-6 of k + 1/2 may have been rounded to the wrong side.  Decide those from
+        // the sign of (k + 1/2) * step - x, which one fused multiply-add gives exactly.
+        if (__builtin_expect(suspect, 0)) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float c = __builtin_amdgcn_fmed3f(t[i], -8.0f, 7.0f);
+                const float r = c + kMagic;
+                const float f = c - (r - kMagic);
+                if (fabsf(f) > 0.5f - 0x1.0p-18f) {
+                    const float k = floorf(t[i]);
+                    const float d = fmaf(k + 0.5f, step, -raw[i]);
+                    const int ki = (int)k;
+                    int q = d > 0.0f ? ki : (d < 0.0f ? ki + 1 : ((ki & 1) ? ki + 1 : ki));
+                    q = q < -8 ? -8 : (q > 7 ? 7 : q);
+                    bits[i] = 0x4B400008u + (uint32_t)q;
+                }
+            }
+        }
+    }
+    uint32_t s = bits[7];
+#pragma unroll
+    for (int i = 6; i >= 0; --i) s = (s << 4) + bits[i];
+    return (s - kMagicSum) ^ 0x88888888u;   // offset-binary nibbles -> two's complement
+}
+
+
+// Rotate (block size 2^log2h, 0 = none), quantize and pack the channels [chunk0, chunk0 + 2048 G)
+// of one row.  x_row points at the row's first channel; packed dwords go to dst_row[channel / 8]
+// (global or LDS).  xch: LDS scratch of 2048 G floats, touched only when log2h > 9.  Must be
+// called by all threads of the workgroup (it contains LDS barriers when log2h > 9): `tid` is
+// the thread's index 0..255 inside the group of 256 that owns the chunk, and threads of other
+// groups, or groups without a chunk, pass active = false and only take part in the barriers.
+// LDS-only barrier: global loads that are still in flight stay in flight.
+__device__ __forceinline__ void lds_sync() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+typedef __attribute__((address_space(3))) const v4i* lds_cv4_ptr;
+typedef __attribute__((address_space(3))) uint32_t* lds_u32_ptr;
+typedef __attribute__((address_space(3))) float* lds_f32_ptr;
+
+// SRC: const __half* (global) or an LDS pointer to fp16; DST: uint32_t* (global) or
+// lds_u32_ptr.  Explicit LDS pointers keep the accesses off the vector-memory counter.
+template <int G, bool EXACT, typename SRC, typename DST>
+__device__ __forceinline__ void rotate_quant_chunk(SRC x_row, int64_t K, int64_t chunk0, int log2h, float mult,
+                                                   float step, DST dst_row, lds_f32_ptr xch, int tid, bool active)
+{
+    using src_v4 = std::conditional_t<std::is_same<SRC, const __half*>::value, const v4i*, lds_cv4_ptr>;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+
+    float v[G][8];
+    bool live[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const int64_t e0 = chunk0 + (int64_t)g * kChunk + tid * 8;
+        live[g] = active && e0 < K;
+        v4i raw = {0, 0, 0, 0};
+        if (live[g]) raw = *(src_v4)(x_row + e0);
+        const __half2* h2 = reinterpret_cast<const __half2*>(&raw);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float2 f = __half22float2(h2[i]);
+            v[g][2 * i] = f.x;
+            v[g][2 * i + 1] = f.y;
+        }
+    }
+
+    if constexpr (EXACT) {
+        // no rotation: the unrotated value doubles as the exact tie-break operand
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            if (live[g]) {
+                const int64_t e0 = chunk0 + (int64_t)g * kChunk + tid * 8;
+                dst_row[e0 >> 3] = quant_pack8<true>(v[g], v[g], mult, step);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int g = 0; g < G; ++g) reg_stages8(v[g], log2h < 3 ? log2h : 3);
+        float(&flat)[G * 8] = reinterpret_cast<float(&)[G * 8]>(v);
+        if (log2h > 3) lane_stage<0>(flat, lane);
+        if (log2h > 4) lane_stage<1>(flat, lane);
+        if (log2h > 5) lane_stage<2>(flat, lane);
+        if (log2h > 6) lane_stage<3>(flat, lane);
+        if (log2h > 7) lane_stage<4>(flat, lane);
+        if (log2h > 8) lane_stage<5>(flat, lane);
+        if (log2h > 9) {
+            // radix-4 (or radix-2 when h == 1024) exchange between the 4 wavefronts
+            if (active) {
+#pragma unroll
+                for (int i = 0; i < G * 8; ++i) xch[(wave * G * 8 + i) * 64 + lane] = flat[i];
+            }
+            lds_sync();
+            const bool two = log2h > 10;
+            if (active) {
+#pragma unroll
+            for (int i = 0; i < G * 8; ++i) {
+                const float a = xch[((wave ^ 1) * G * 8 + i) * 64 + lane];
+                float r = (wave & 1) ? (a - flat[i]) : (a + flat[i]);
+                if (two) {
+                    const float b = xch[((wave ^ 2) * G * 8 + i) * 64 + lane];
+                    const float c = xch[((wave ^ 3) * G * 8 + i) * 64 + lane];
+                    const float rp = (wave & 1) ? (c - b) : (c + b);   // same stage-1 result in the partner pair
+                    r = (wave & 2) ? (rp - r) : (rp + r);
+                }
+                flat[i] = r;
+            }
+            }
+            lds_sync();   // the scratch may be reused by the next call
+        }
+        if constexpr (G > 1) {
+            // d = 2048 * 2^j between groups
+#pragma unroll
+            for (int dg = 1; dg < G; dg <<= 1) {
+                if (log2h > 11 + __builtin_ctz(dg)) {
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        if ((g & dg) == 0) {
+#pragma unroll
+                            for (int i = 0; i < 8; ++i) {
+                                const float a = v[g][i], b = v[g + dg][i];
+                                v[g][i] = a + b;
+                                v[g + dg][i] = a - b;
+                            }
+                        }
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            if (live[g]) {
+                const int64_t e0 = chunk0 + (int64_t)g * kChunk + tid * 8;
+                dst_row[e0 >> 3] = quant_pack8<false>(v[g], v[g], mult, step);
+            }
+        }
+    }
+}
+
+}  // namespace rq
+}  // namespace pq

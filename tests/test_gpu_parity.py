@@ -81,7 +81,7 @@ def test_product_and_epilogue(pq, M, N, K):
         assert none is None and np.array_equal(host(out2).view(np.uint16), host(out).view(np.uint16))
 
 
-@pytest.mark.parametrize("variant,M", [(2, 1), (2, 16), (2, 5), (3, 40), (1, 9)])
+@pytest.mark.parametrize("variant,M", [(2, 1), (2, 16), (2, 5), (3, 40), (1, 9), (1, 1), (1, 4), (4, 1), (4, 3), (4, 4)])
 def test_forced_variants_agree(pq, variant, M):
     N, K = 256, 1024
     xq, wq = synth.random_packed(M, K, seed=3), synth.random_packed(N, K, seed=4, stream=7)
@@ -117,6 +117,25 @@ def test_linear_end_to_end(pq, M, K, N, h):
     out, ws = pq.pq_linear(dev(L["x"]), dev(L["wq_packed"]), dev(L["sw"]), float(L["sx"]), h)
     xq_gpu = host(ws)[: M * K // 2].reshape(M, K // 2)
     check_end_to_end(L["x"], L["wq_packed"], L["sw"], L["sx"], h, host(out), xq_gpu)
+
+
+@pytest.mark.parametrize("M,K,N,h", [(1, 4096, 4096, 1), (1, 4096, 6144, 4096), (1, 14336, 4096, 128), (2, 14336, 512, 128),
+                                     (3, 8192, 256, 8192), (4, 4096, 1024, 1), (4, 2048, 128, 1024), (1, 11008, 256, 128),
+                                     (4, 28672, 64, 128), (1, 28672, 8192, 128), (2, 1024, 48, 2048 // 2), (1, 32, 16, 32),
+                                     (3, 96, 32, 1), (1, 8192, 10240, 1)])
+def test_decode_fused_linear(pq, M, K, N, h):
+    # M <= 4: pq_linear is one fused launch; codes in the workspace, output against the oracle
+    L = prepare_layer(M, K, N, h, seed=K + N + h)
+    for variant in (0, 4):      # automatic choice, and the fused launch forced wherever it is supported
+        prev = pq.pq_set_gemm_variant(variant)
+        try:
+            out, ws = pq.pq_linear(dev(L["x"]), dev(L["wq_packed"]), dev(L["sw"]), float(L["sx"]), h)
+        finally:
+            pq.pq_set_gemm_variant(prev)
+        xq_gpu = host(ws)[: M * K // 2].reshape(M, K // 2)
+        check_end_to_end(L["x"], L["wq_packed"], L["sw"], L["sx"], h, host(out), xq_gpu)
+        if h <= 1:      # unrotated: codes are exact
+            assert np.array_equal(xq_gpu, O.pack(O.quantize(L["x"], L["sx"])))
 
 
 def test_rotation_involution_on_device(pq):
