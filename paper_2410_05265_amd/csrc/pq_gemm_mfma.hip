@@ -276,7 +276,8 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
                 int n = nb + 8 * q + 4 * g;
                 n = n + 4 <= N ? n : N - 4;
                 sc[q] = *reinterpret_cast<const float4*>(sw + n);
-                sc[q].x *= sx; sc[q].y *= sx; sc[q].z *= sx; sc[q].w *= sx;
+                const float f = sx * 0.00390625f;   // the accumulators hold 256 * acc: fold the exact 2^-8 here
+                sc[q].x *= f; sc[q].y *= f; sc[q].z *= f; sc[q].w *= f;
             }
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
@@ -287,10 +288,10 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
 #pragma unroll
                     for (int h2 = 0; h2 < 2; ++h2) {
                         const int q = 2 * qp + h2;
-                        const float f0 = (float)(acc[i][j][4 * q + 0] >> 8) * sc[q].x;
-                        const float f1 = (float)(acc[i][j][4 * q + 1] >> 8) * sc[q].y;
-                        const float f2 = (float)(acc[i][j][4 * q + 2] >> 8) * sc[q].z;
-                        const float f3 = (float)(acc[i][j][4 * q + 3] >> 8) * sc[q].w;
+                        const float f0 = (float)acc[i][j][4 * q + 0] * sc[q].x;
+                        const float f1 = (float)acc[i][j][4 * q + 1] * sc[q].y;
+                        const float f2 = (float)acc[i][j][4 * q + 2] * sc[q].z;
+                        const float f3 = (float)acc[i][j][4 * q + 3] * sc[q].w;
                         const __half2 lo = __floats2half2_rn(f0, f1), hi = __floats2half2_rn(f2, f3);
                         pk[2 * h2 + 0] = *reinterpret_cast<const uint32_t*>(&lo);
                         pk[2 * h2 + 1] = *reinterpret_cast<const uint32_t*>(&hi);
@@ -461,11 +462,12 @@ int launch_ragged(const void* xq, const void* wq, const float* sw, float sx, int
 struct TileCfg { int bm, bn; double eff; };
 // tile shapes the automatic choice considers, with measured relative efficiencies (a larger
 // wavefront tile needs fewer LDS reads and less expansion per matrix instruction)
-constexpr int kNumAuto = 3, kNumCfg = 5;
-constexpr TileCfg kCfgs[kNumCfg] = {{256, 256, 1.00}, {256, 128, 0.85}, {128, 128, 0.72}, {256, 256, 1.0}, {256, 256, 1.0}};
+constexpr int kNumAuto = 4, kNumCfg = 6;
+constexpr TileCfg kCfgs[kNumCfg] = {{256, 256, 1.00}, {256, 128, 0.85}, {128, 128, 0.72}, {256, 192, 0.95},
+                                    {256, 256, 1.0},  {256, 256, 1.0}};
 
-// PQ_GEMM_TILE=0..4 forces a configuration (sweeps only): 0 256x256, 1 256x128, 2 128x128,
-// 3 256x256 with 8 wavefronts, 4 256x256 with a 4-stage ring.
+// PQ_GEMM_TILE=0..5 forces a configuration (sweeps only): 0 256x256, 1 256x128, 2 128x128,
+// 3 256x192, 4 256x256 with 8 wavefronts, 5 256x256 with a 4-stage ring.
 int pick_cfg(int64_t M, int64_t N)
 {
     if (const char* f = getenv("PQ_GEMM_TILE")) {
@@ -495,7 +497,8 @@ int launch_gemm_mfma(const void* xq, const void* wq, const float* sw, float sx, 
         case 0: return launch_dma<256, 256, 2, 2, 3>(xq, wq, sw, sx, M, N, K, out, acc, st);
         case 1: return launch_dma<256, 128, 2, 2, 3>(xq, wq, sw, sx, M, N, K, out, acc, st);
         case 2: return launch_dma<128, 128, 2, 2, 3>(xq, wq, sw, sx, M, N, K, out, acc, st);
-        case 3: return launch_dma<256, 256, 2, 4, 3>(xq, wq, sw, sx, M, N, K, out, acc, st);
+        case 3: return launch_dma<256, 192, 2, 2, 3>(xq, wq, sw, sx, M, N, K, out, acc, st);
+        case 4: return launch_dma<256, 256, 2, 4, 3>(xq, wq, sw, sx, M, N, K, out, acc, st);
         default: return launch_dma<256, 256, 2, 2, 4>(xq, wq, sw, sx, M, N, K, out, acc, st);
     }
 }
