@@ -99,7 +99,7 @@ __device__ __forceinline__ uint32_t quant_pack8(const float* v, const float* raw
         // t carries two fp32 roundings (reciprocal and product), so a quotient within
         // ~1e-6 of k + 1/2 may have been rounded to the wrong side.  Decide those from
         // the sign of (k + 1/2) * step - x, which one fused multiply-add gives exactly.
-        if (__builtin_expect(suspect, 0)) {
+        if (__builtin_amdgcn_ballot_w64(suspect) != 0) {   // wave-uniform: a real branch, taken rarely
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const float c = __builtin_amdgcn_fmed3f(t[i], -8.0f, 7.0f);
@@ -138,23 +138,35 @@ typedef __attribute__((address_space(3))) float* lds_f32_ptr;
 
 // SRC: const __half* (global) or an LDS pointer to fp16; DST: uint32_t* (global) or
 // lds_u32_ptr.  Explicit LDS pointers keep the accesses off the vector-memory counter.
-template <int G, bool EXACT, typename SRC, typename DST>
-__device__ __forceinline__ void rotate_quant_chunk(SRC x_row, int64_t K, int64_t chunk0, int log2h, float mult,
-                                                   float step, DST dst_row, lds_f32_ptr xch, int tid, bool active)
+//
+// load_chunk only issues the loads (branch-free: threads without data read the row's first
+// bytes), so a caller can have several chunks in flight before the arithmetic starts.
+template <int G, typename SRC>
+__device__ __forceinline__ void load_chunk(SRC x_row, int64_t K, int64_t chunk0, int tid, bool active, v4i (&raw)[G],
+                                           bool (&live)[G])
 {
     using src_v4 = std::conditional_t<std::is_same<SRC, const __half*>::value, const v4i*, lds_cv4_ptr>;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-
-    float v[G][8];
-    bool live[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         const int64_t e0 = chunk0 + (int64_t)g * kChunk + tid * 8;
         live[g] = active && e0 < K;
-        v4i raw = {0, 0, 0, 0};
-        if (live[g]) raw = *(src_v4)(x_row + e0);
-        const __half2* h2 = reinterpret_cast<const __half2*>(&raw);
+        raw[g] = *(src_v4)(x_row + (live[g] ? e0 : 0));
+    }
+}
+
+template <int G, bool EXACT, typename DST>
+__device__ __forceinline__ void rotate_quant_regs(const v4i (&raw)[G], const bool (&live)[G], int64_t chunk0,
+                                                  int log2h, float mult, float step, DST dst_row, lds_f32_ptr xch,
+                                                  int tid, bool active)
+{
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+
+    float v[G][8];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const v4i rg = live[g] ? raw[g] : (v4i){0, 0, 0, 0};
+        const __half2* h2 = reinterpret_cast<const __half2*>(&rg);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const float2 f = __half22float2(h2[i]);
@@ -233,6 +245,16 @@ __device__ __forceinline__ void rotate_quant_chunk(SRC x_row, int64_t K, int64_t
             }
         }
     }
+}
+
+template <int G, bool EXACT, typename SRC, typename DST>
+__device__ __forceinline__ void rotate_quant_chunk(SRC x_row, int64_t K, int64_t chunk0, int log2h, float mult,
+                                                   float step, DST dst_row, lds_f32_ptr xch, int tid, bool active)
+{
+    v4i raw[G];
+    bool live[G];
+    load_chunk<G>(x_row, K, chunk0, tid, active, raw, live);
+    rotate_quant_regs<G, EXACT>(raw, live, chunk0, log2h, mult, step, dst_row, xch, tid, active);
 }
 
 }  // namespace rq

@@ -21,15 +21,30 @@ namespace {
 using rq::kChunk;
 using rq::kThreads;
 
-template <int G, bool EXACT>
-__global__ __launch_bounds__(kThreads) void k_rotate_quant(const __half* __restrict__ x, int64_t K, int log2h,
-                                                          float mult, float step, uint32_t* __restrict__ xq)
+// R rows of one chunk column per workgroup: all R loads of a thread are issued before the
+// arithmetic starts (the kernel has 2.5 bytes of traffic per element and little else to hide
+// latency with).
+template <int G, bool EXACT, int R>
+__global__ __launch_bounds__(kThreads) void k_rotate_quant(const __half* __restrict__ x, int64_t M, int64_t K,
+                                                          int log2h, float mult, float step,
+                                                          uint32_t* __restrict__ xq)
 {
     __shared__ float xch[EXACT ? 1 : G * kChunk];
-    const int64_t row = blockIdx.y;
-    rq::rotate_quant_chunk<G, EXACT>(static_cast<const __half*>(x + row * K), K,
-                                     (int64_t)blockIdx.x * (G * kChunk), log2h, mult, step,
-                                     static_cast<uint32_t*>(xq + row * (K >> 3)), (rq::lds_f32_ptr)xch, threadIdx.x, true);
+    const int64_t row0 = (int64_t)blockIdx.y * R;
+    const int64_t chunk0 = (int64_t)blockIdx.x * (G * kChunk);
+    v4i raw[R][G];
+    bool live[R][G];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const bool in = row0 + r < M;
+        rq::load_chunk<G>(static_cast<const __half*>(x + (in ? row0 + r : 0) * K), K, chunk0, threadIdx.x, in, raw[r],
+                          live[r]);
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+        rq::rotate_quant_regs<G, EXACT>(raw[r], live[r], chunk0, log2h, mult, step,
+                                        static_cast<uint32_t*>(xq + (row0 + r) * (K >> 3)), (rq::lds_f32_ptr)xch,
+                                        threadIdx.x, row0 + r < M);
 }
 
 }  // namespace
@@ -50,20 +65,21 @@ int launch_rotate_quant(const void* x, int64_t M, int64_t K, int32_t h, float ac
     }
     if (h <= 1) {
         const float inv = (float)(1.0 / (double)act_scale);
-        dim3 grid((unsigned)((K + kChunk - 1) / kChunk), (unsigned)M);
-        hipLaunchKernelGGL((k_rotate_quant<1, true>), grid, dim3(kThreads), 0, st, xp, K, 0, inv, act_scale, op);
+        dim3 grid((unsigned)((K + kChunk - 1) / kChunk), (unsigned)((M + 1) / 2));
+        hipLaunchKernelGGL((k_rotate_quant<1, true, 2>), grid, dim3(kThreads), 0, st, xp, M, K, 0, inv, act_scale, op);
         return hip_status(hipGetLastError());
     }
     int log2h = 0;
     while ((1 << log2h) < h) ++log2h;
     const float mult = (float)(1.0 / ((double)act_scale * sqrt((double)h)));
     const int G = h <= kChunk ? 1 : h / kChunk;
-    dim3 grid((unsigned)((K + (int64_t)G * kChunk - 1) / ((int64_t)G * kChunk)), (unsigned)M);
+    const int R = G <= 2 ? 2 : 1;
+    dim3 grid((unsigned)((K + (int64_t)G * kChunk - 1) / ((int64_t)G * kChunk)), (unsigned)((M + R - 1) / R));
     switch (G) {
-        case 1: hipLaunchKernelGGL((k_rotate_quant<1, false>), grid, dim3(kThreads), 0, st, xp, K, log2h, mult, act_scale, op); break;
-        case 2: hipLaunchKernelGGL((k_rotate_quant<2, false>), grid, dim3(kThreads), 0, st, xp, K, log2h, mult, act_scale, op); break;
-        case 4: hipLaunchKernelGGL((k_rotate_quant<4, false>), grid, dim3(kThreads), 0, st, xp, K, log2h, mult, act_scale, op); break;
-        case 8: hipLaunchKernelGGL((k_rotate_quant<8, false>), grid, dim3(kThreads), 0, st, xp, K, log2h, mult, act_scale, op); break;
+        case 1: hipLaunchKernelGGL((k_rotate_quant<1, false, 2>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, mult, act_scale, op); break;
+        case 2: hipLaunchKernelGGL((k_rotate_quant<2, false, 2>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, mult, act_scale, op); break;
+        case 4: hipLaunchKernelGGL((k_rotate_quant<4, false, 1>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, mult, act_scale, op); break;
+        case 8: hipLaunchKernelGGL((k_rotate_quant<8, false, 1>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, mult, act_scale, op); break;
         default: return PQ_ERR_UNSUPPORTED;
     }
     return hip_status(hipGetLastError());
