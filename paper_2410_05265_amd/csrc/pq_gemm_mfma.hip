@@ -102,7 +102,7 @@ __device__ __forceinline__ void static_for(F&& f)
 
 template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
-template <int BM, int BN, int WR, int WC, int NS>
+template <int BM, int BN, int WR, int WC, int NS, int SUBS>
 __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __restrict__ xq,
                                                           const uint8_t* __restrict__ wq,
                                                           const float* __restrict__ sw, float sx, int M, int N,
@@ -111,7 +111,8 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
 {
     constexpr int NW = WR * WC;
     constexpr int WM = BM / WR, WN = BN / WC, TM = WM / 32, TN = WN / 32;
-    constexpr int A_BYTES = BM * 64, STAGE = (BM + BN) * 64;
+    // a ring stage is SUBS sub-stages of 128 channels each (one barrier per stage)
+    constexpr int A_BYTES = BM * 64, SUB_BYTES = (BM + BN) * 64, STAGE = SUBS * SUB_BYTES;
     constexpr int BLK = (BM + BN) / 16;   // 1 KiB blocks per stage
     constexpr int LW = BLK / NW;          // direct loads per wavefront per stage
     static_assert(BLK % NW == 0 && (BM / 16) % NW == 0, "loader shape");
@@ -126,7 +127,7 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
     const int tile = xcd_remap(blockIdx.x, gridDim.x);
     const int m0 = (tile % GM) * BM, n0 = (tile / GM) * BN;
     const int Kb = K >> 1;
-    const int nk = K >> 7;
+    const int nk = K / (128 * SUBS);
 
     // ---- loader
     const int lrow = lane >> 2, lpos = lane & 3;
@@ -145,12 +146,14 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
         }
         goff[i] = (uint32_t)row * (uint32_t)Kb + lchunk * 16;
     }
+    auto dma_one = [&](int d, int kt, int buf) {   // d-th direct load of a stage, d < SUBS * LW
+        const int sub = d / LW, i = d % LW;
+        const uint8_t* src = (i < LWA ? xq : wq) + (size_t)(kt * SUBS + sub) * 64 + goff[i];
+        __builtin_amdgcn_global_load_lds(PQ_GLB(src),
+                                         PQ_LDS(smem + buf * STAGE + sub * SUB_BYTES + (wave + NW * i) * 1024), 16, 0, 0);
+    };
     auto dma_stage = [&](int kt, int buf) {
-#pragma unroll
-        for (int i = 0; i < LW; ++i) {
-            const uint8_t* src = (i < LWA ? xq : wq) + (size_t)kt * 64 + goff[i];
-            __builtin_amdgcn_global_load_lds(PQ_GLB(src), PQ_LDS(smem + buf * STAGE + (wave + NW * i) * 1024), 16, 0, 0);
-        }
+        static_for<0, SUBS * LW>([&](auto dc) { dma_one(decltype(dc)::value, kt, buf); });
     };
 
     // ---- reader
@@ -200,6 +203,7 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
     // of the next half stage's operands (first TM+TN slots), optionally one direct load, one matrix instruction
     auto half_stage = [&](auto setc, const uint8_t* next_stage, int next_kk, bool dma, int dma_kt, int dma_buf) {
         constexpr int set = decltype(setc)::value;
+        static_assert(SUBS * LW <= SC::NSLOT, "one direct load per slot");
         static_for<0, SC::NSLOT>([&](auto nc) {
             constexpr int n = decltype(nc)::value;
             if constexpr (n < TM + TN) read_frag(next_stage, next_kk, set ^ 1, n);
@@ -209,13 +213,8 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
                 if constexpr (u < SC::PER) micro(std::integral_constant<int, set>{}, std::integral_constant<int, u>{});
                 else micro(std::integral_constant<int, set ^ 1>{}, std::integral_constant<int, u - SC::PER>{});
             });
-            if constexpr (n >= TM + TN && n < TM + TN + LW) {
-                if (dma) {
-                    constexpr int i = n - (TM + TN);
-                    const uint8_t* src = (i < LWA ? xq : wq) + (size_t)dma_kt * 64 + goff[i];
-                    __builtin_amdgcn_global_load_lds(PQ_GLB(src),
-                                                     PQ_LDS(smem + dma_buf * STAGE + (wave + NW * i) * 1024), 16, 0, 0);
-                }
+            if constexpr (n < SUBS * LW) {
+                if (dma) dma_one(n, dma_kt, dma_buf);
             }
             constexpr int ph = n / SC::NM, k = n % SC::NM;
             constexpr int i = kSched<TM, TN>.mi[k], j = kSched<TM, TN>.mj[k];
@@ -227,7 +226,7 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
     // ---- prologue: fill the ring, fetch the first operands and run the expansion `lead` ahead
 #pragma unroll
     for (int st = 0; st < NS; ++st) dma_stage(st < nk ? st : nk - 1, st);
-    wait_vm<(NS - 1) * LW>();
+    wait_vm<(NS - 1) * SUBS * LW>();
     lds_barrier();
     static_for<0, TM + TN>([&](auto fc) { read_frag(smem, 0, 0, decltype(fc)::value); });
     static_for<0, kSched<TM, TN>.lead>([&](auto uc) { micro(std::integral_constant<int, 0>{}, uc); });
@@ -237,10 +236,14 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
     for (int kt = 0; kt < nk; ++kt) {
         const uint8_t* cur = smem + buf * STAGE;
         const int nbuf = (buf + 1 == NS) ? 0 : buf + 1;
-        half_stage(std::integral_constant<int, 0>{}, cur, 1, false, 0, 0);
+        // all half stages but the last: operands of the next half come from this ring stage
+        static_for<0, 2 * SUBS - 1>([&](auto hc) {
+            constexpr int hi = decltype(hc)::value;
+            half_stage(std::integral_constant<int, hi & 1>{}, cur + ((hi + 1) / 2) * SUB_BYTES, (hi + 1) & 1, false, 0, 0);
+        });
         // stage kt+1 has landed (its loads were issued NS-1 stages ago); after the barrier all
         // reads of stage kt are done, so its buffer can be refilled
-        wait_vm<(NS - 2) * LW>();
+        wait_vm<(NS - 2) * SUBS * LW>();
         lds_barrier();
         __builtin_amdgcn_sched_barrier(0);
         half_stage(std::integral_constant<int, 1>{}, smem + nbuf * STAGE, 0, true, kt + NS < nk ? kt + NS : nk - 1, buf);
@@ -311,13 +314,13 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
     }
 }
 
-template <int BM, int BN, int WR, int WC, int NS>
+template <int BM, int BN, int WR, int WC, int NS, int SUBS>
 int launch_dma(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K, void* out,
                int32_t* acc, hipStream_t st)
 {
     const int GM = (int)((M + BM - 1) / BM), GN = (int)((N + BN - 1) / BN);
-    constexpr size_t lds = (size_t)NS * (BM + BN) * 64;
-    auto kern = k_gemm_dma<BM, BN, WR, WC, NS>;
+    constexpr size_t lds = (size_t)NS * SUBS * (BM + BN) * 64;
+    auto kern = k_gemm_dma<BM, BN, WR, WC, NS, SUBS>;
     static bool attr_set = false;  // benign race: the call is idempotent
     if (lds > 48 * 1024 && !attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -493,13 +496,15 @@ int launch_gemm_mfma(const void* xq, const void* wq, const float* sw, float sx, 
     if (M > (1 << 30) || N > (1 << 30) || K > (1 << 30)) return PQ_ERR_UNSUPPORTED;
     if (M * (K / 2) >= ((int64_t)1 << 32) || N * (K / 2) >= ((int64_t)1 << 32)) return PQ_ERR_UNSUPPORTED;
     if (K % 128 != 0) return launch_ragged(xq, wq, sw, sx, M, N, K, out, acc, st);
+    // (two 128-channel sub-stages per ring stage, i.e. one barrier per 256 channels with a 2-deep
+    // ring, measured 3-10 % slower than a 3-deep ring of single sub-stages: depth wins)
     switch (pick_cfg(M, N)) {
-        case 0: return launch_dma<256, 256, 2, 2, 3>(xq, wq, sw, sx, M, N, K, out, acc, st);
-        case 1: return launch_dma<256, 128, 2, 2, 3>(xq, wq, sw, sx, M, N, K, out, acc, st);
-        case 2: return launch_dma<128, 128, 2, 2, 3>(xq, wq, sw, sx, M, N, K, out, acc, st);
-        case 3: return launch_dma<256, 192, 2, 2, 3>(xq, wq, sw, sx, M, N, K, out, acc, st);
-        case 4: return launch_dma<256, 256, 2, 4, 3>(xq, wq, sw, sx, M, N, K, out, acc, st);
-        default: return launch_dma<256, 256, 2, 2, 4>(xq, wq, sw, sx, M, N, K, out, acc, st);
+        case 0: return launch_dma<256, 256, 2, 2, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
+        case 1: return launch_dma<256, 128, 2, 2, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
+        case 2: return launch_dma<128, 128, 2, 2, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
+        case 3: return launch_dma<256, 192, 2, 2, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
+        case 4: return launch_dma<256, 256, 2, 4, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
+        default: return launch_dma<256, 256, 2, 2, 4, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
     }
 }
 
