@@ -67,8 +67,8 @@ int pq_rotate_quant(const void* x_f16, int64_t M, int64_t K, int32_t had_block,
  *     acc[m,n] = sum_k xq[m,k] * wq[n,k]              (exact, int32)
  *     out[m,n] = fp16(acc[m,n] * (act_scale * w_scale[n]))   (fp32 multiply, RNE)
  * The kernel is chosen from M: weight-streaming kernels for M <= 16 (decode: 4-bit dot
- * products for M <= 4, small matrix tiles up to 16), an INT8-MFMA tiled kernel otherwise
- * (prefill).
+ * products on packed nibbles for M <= 8, small matrix tiles up to 16), an INT8-MFMA tiled
+ * kernel otherwise (prefill).
  * xq_packed in  [M,K/2] uint8 canonical.      wq_packed in [N,K/2] uint8 canonical.
  * w_scale   in  [N] fp32.                     act_scale: static step size of xq.
  * out_f16   out [M,N] fp16; may be NULL iff acc_i32 is not.
@@ -100,7 +100,7 @@ int pq_w4a4_gemm_simple(const void* xq_packed, const void* wq_packed, const floa
 
 /* Force a kernel variant of pq_w4a4_gemm for sweeps and tests (host, process-wide,
  * not thread-safe): 0 = automatic, 1 = weight-streaming matrix tiles (M <= 16 only),
- * 2 = MFMA tiled, 3 = simple, 4 = weight-streaming 4-bit dot products (M <= 4 only).  With 4
+ * 2 = MFMA tiled, 3 = simple, 4 = weight-streaming 4-bit dot products (M <= 8 only).  With 4
  * pq_linear uses its fused single launch whenever the shape allows it; with 1, 2 or 3 it
  * always uses two launches.  Returns the previous value, or -1 if `variant` is unknown.
  */

@@ -65,7 +65,7 @@ int pq_w4a4_gemm(const void* xq_packed, const void* wq_packed, const float* w_sc
     if (M == 0) return PQ_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
     int v = g_variant;
-    if (v == 0) v = (M <= 4 && pq::decode_supported(M, N, K, -1)) ? 4 : ((M <= 16) ? 1 : 2);
+    if (v == 0) v = (M <= 8 && pq::decode_supported(M, N, K, -1)) ? 4 : ((M <= 16) ? 1 : 2);
     switch (v) {
         case 4:
             if (!pq::decode_supported(M, N, K, -1)) return PQ_ERR_UNSUPPORTED;

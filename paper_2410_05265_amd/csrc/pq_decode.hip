@@ -1,5 +1,5 @@
-// Decode (M <= 4 tokens) in ONE launch of one workgroup per CU: rotate + quantize the few activation rows into LDS
-// and stream the packed weight matrix once (Sec. 3 of the paper: weight quantization speeds
+// Decode in ONE launch of one workgroup per CU: rotate + quantize the few activation rows
+// (M <= 4) into LDS, or take given codes (M <= 8), and stream the packed weight matrix once (Sec. 3 of the paper: weight quantization speeds
 // up memory-bound computation; Sec. 5.4, decoding column).
 //
 // At these sizes a linear is 8-30 MB of weights, i.e. 32-112 KB per CU: the kernel is a single
@@ -235,16 +235,21 @@ template <int RPW, int CB, int MP>
 int launch_mode(const __half* x, const uint8_t* xq_in, const uint8_t* wq, const float* sw, float sx, int h, int M,
                 int N, int K, __half* out, int32_t* acc, uint8_t* xq_out, hipStream_t st)
 {
-    if (x == nullptr) return launch_one<RPW, CB, MP, 0>(x, xq_in, wq, sw, sx, 0.f, 0, M, N, K, out, acc, xq_out, st);
-    if (h <= 1) {
+    if constexpr (MP > 4 && RPW > 2) return PQ_ERR_UNSUPPORTED;   // never chosen: too many accumulators
+    else if (x == nullptr) return launch_one<RPW, CB, MP, 0>(x, xq_in, wq, sw, sx, 0.f, 0, M, N, K, out, acc, xq_out, st);
+    if constexpr (MP > 4) return PQ_ERR_UNSUPPORTED;   // more than 4 tokens: codes only, no fused quantizer
+    else if (h <= 1) {
         const float inv = (float)(1.0 / (double)sx);
         return launch_one<RPW, CB, MP, 1>(x, xq_in, wq, sw, sx, inv, 0, M, N, K, out, acc, xq_out, st);
     }
-    int log2h = 0;
-    while ((1 << log2h) < h) ++log2h;
-    const float mult = (float)(1.0 / ((double)sx * sqrt((double)h)));
-    if (h <= kChunk) return launch_one<RPW, CB, MP, 1>(x, xq_in, wq, sw, sx, mult, log2h, M, N, K, out, acc, xq_out, st);
-    return launch_one<RPW, CB, MP, 2>(x, xq_in, wq, sw, sx, mult, log2h, M, N, K, out, acc, xq_out, st);
+    else {
+        int log2h = 0;
+        while ((1 << log2h) < h) ++log2h;
+        const float mult = (float)(1.0 / ((double)sx * sqrt((double)h)));
+        if (h <= kChunk)
+            return launch_one<RPW, CB, MP, 1>(x, xq_in, wq, sw, sx, mult, log2h, M, N, K, out, acc, xq_out, st);
+        return launch_one<RPW, CB, MP, 2>(x, xq_in, wq, sw, sx, mult, log2h, M, N, K, out, acc, xq_out, st);
+    }
 }
 
 template <int MP>
@@ -268,8 +273,9 @@ int launch_shape(int rpw, int cb, const __half* x, const uint8_t* xi, const uint
 // h < 0: the packed codes are given; h >= 0: fused rotate + quantize from fp16 rows
 bool decode_supported(int64_t M, int64_t N, int64_t K, int32_t h)
 {
-    if (!(M >= 1 && M <= 4 && (N % 16) == 0 && K <= 131072 && h <= 2 * kChunk && N <= (1 << 30))) return false;
-    const int64_t mp = M == 1 ? 1 : 4, g = h <= kChunk ? 1 : 2;
+    if (!(M >= 1 && M <= (h < 0 ? 8 : 4) && (N % 16) == 0 && K <= 131072 && h <= 2 * kChunk && N <= (1 << 30)))
+        return false;
+    const int64_t mp = M == 1 ? 1 : (M <= 4 ? 4 : 8), g = h <= kChunk ? 1 : 2;
     const int64_t fused = h >= 0 ? M * K * 2 + g * kChunk * 4 : 16;
     return mp * (K / 2) + 16 + fused <= 160 * 1024;
 }
@@ -294,7 +300,10 @@ int launch_decode(const void* x_f16, const void* xq_in, const void* wq, const fl
     if (rpw == 4 && cb == 8) rpw = 2;
     const int m = (int)M, n = (int)N, k = (int)K;
     if (M == 1) return launch_shape<1>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st);
-    return launch_shape<4>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st);
+    if (M <= 4) return launch_shape<4>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st);
+    // 5..8 tokens: fewer rows per wavefront so that the accumulators stay in registers
+    if (rpw > 2) rpw = 2;
+    return launch_shape<8>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st);
 }
 
 }  // namespace pq

@@ -81,7 +81,7 @@ def test_product_and_epilogue(pq, M, N, K):
         assert none is None and np.array_equal(host(out2).view(np.uint16), host(out).view(np.uint16))
 
 
-@pytest.mark.parametrize("variant,M", [(2, 1), (2, 16), (2, 5), (3, 40), (1, 9), (1, 1), (1, 4), (4, 1), (4, 3), (4, 4)])
+@pytest.mark.parametrize("variant,M", [(2, 1), (2, 16), (2, 5), (3, 40), (1, 9), (1, 1), (1, 4), (4, 1), (4, 3), (4, 4), (4, 5), (4, 8), (1, 11), (1, 16)])
 def test_forced_variants_agree(pq, variant, M):
     N, K = 256, 1024
     xq, wq = synth.random_packed(M, K, seed=3), synth.random_packed(N, K, seed=4, stream=7)
