@@ -106,6 +106,35 @@ int pq_w4a4_gemm_simple(const void* xq_packed, const void* wq_packed, const floa
  */
 int pq_set_gemm_variant(int variant);
 
+/* ---- 4-bit weights, 8-bit static activations (the W4A8 rows of Table 3) -------------------
+ * Same layer with the activation quantizer at 8 bits: q = clamp(round_half_even(y/act_scale),
+ * -128, 127), one int8 per code.  The three calls below mirror pq_rotate_quant, pq_w4a4_gemm and
+ * pq_linear; they need K % 128 == 0, K <= 65536 and M*K < 2^32 (else PQ_ERR_UNSUPPORTED or
+ * PQ_ERR_SHAPE as for the 4-bit calls), and always use the MFMA tiled kernel.
+ *
+ * "Grouped" int8 layout of xq8 [M,K]: inside every group of 32 consecutive channels the 16 even
+ * channels are stored first, then the 16 odd ones: byte 32*g + 16*p + j holds channel
+ * 32*g + 2*j + p (p = parity, j = 0..15).  It is the order in which the matrix kernel pairs them
+ * with the even/odd nibbles of the packed weights, so no shuffle is needed at run time.
+ */
+int pq_rotate_quant8(const void* x_f16, int64_t M, int64_t K, int32_t had_block,
+                     float act_scale, void* xq8_grouped, void* stream);
+
+/* acc[m,n] = sum_k xq8[m,k] * wq[n,k] (exact, int32; |acc| <= 128*8*K fits for K <= 65536);
+ * out = fp16(acc * (act_scale * w_scale[n])).  Arguments as pq_w4a4_gemm except xq8_grouped.
+ */
+int pq_w4a8_gemm(const void* xq8_grouped, const void* wq_packed, const float* w_scale,
+                 float act_scale, int64_t M, int64_t N, int64_t K,
+                 void* out_f16, int32_t* acc_i32, void* stream);
+
+/* Workspace of pq_linear_w4a8: M*K bytes rounded up to 256.  Host only. */
+size_t pq_linear_w4a8_workspace_bytes(int64_t M, int64_t K);
+
+/* pq_rotate_quant8 into `workspace`, then pq_w4a8_gemm, on the same stream. */
+int pq_linear_w4a8(const void* x_f16, const void* wq_packed, const float* w_scale,
+                   float act_scale, int32_t had_block, int64_t M, int64_t N, int64_t K,
+                   void* out_f16, void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

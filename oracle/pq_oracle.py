@@ -33,6 +33,9 @@ What is defined here, and the passage of the paper each part follows:
   quantize_dynamic     per-token dynamic variant (Table 1 row O1): one step size per
                        row, s[m] = clip * max_k|y[m,k]| / qmax.
   quantize_bits        Eq. 1 symmetric at a general bit-width (8 for the W4A8 setting).
+  group_even_odd       storage order of the 8-bit codes (a permutation, no arithmetic): per
+                       32 channels the 16 even ones, then the 16 odd ones.
+  linear_bits          the whole path with the activation quantizer at `bits` bits.
 
 Pins (tests/test_oracle_pins.py): H.H^T = h.I in integers, involution, Parseval,
 one-hot and constant rows, block independence, a textbook in-place butterfly written in
@@ -136,6 +139,22 @@ def unpack(b) -> np.ndarray:
 
 
 # ----------------------------------------------------------------------------- O5
+def group_even_odd(q) -> np.ndarray:
+    """out[m, 32g + 16p + j] = q[m, 32g + 2j + p] for p in {0,1}, j in 0..15 (K % 32 == 0)."""
+    q = np.asarray(q)
+    M, K = q.shape
+    assert K % 32 == 0
+    return np.ascontiguousarray(q.reshape(M, K // 32, 16, 2).transpose(0, 1, 3, 2).reshape(M, K))
+
+
+def ungroup_even_odd(b) -> np.ndarray:
+    """Inverse of group_even_odd."""
+    b = np.asarray(b)
+    M, K = b.shape
+    assert K % 32 == 0
+    return np.ascontiguousarray(b.reshape(M, K // 32, 2, 16).transpose(0, 1, 3, 2).reshape(M, K))
+
+
 def build_c(force: bool = False) -> str:
     """Compile the C part of the oracle (the int64 product) with gcc; returns the path."""
     stale = (not os.path.exists(_C_LIB)) or os.path.getmtime(_C_LIB) < os.path.getmtime(_C_SRC)
@@ -222,6 +241,14 @@ def linear(x, wq_packed, s_w, s_x, h: int, return_all: bool = False):
     if return_all:
         return {"y": y, "q": q, "xq": xq, "acc": acc, "out": out}
     return out
+
+
+def linear_bits(x, wq_packed, s_w, s_x, h: int, bits: int):
+    """The path with `bits`-bit static activation codes (8 for the W4A8 setting of Table 3)."""
+    y = rotate(x, h)
+    q = quantize_bits(y, s_x, bits)
+    acc = gemm_i64(q, unpack(wq_packed))
+    return {"y": y, "q": q, "acc": acc, "out": epilogue(acc, np.float32(s_x), s_w)}
 
 
 def linear_dynamic(x, wq_packed, s_w, h: int, clip: float = 1.0, bits: int = 4):

@@ -29,6 +29,10 @@ SIGNATURES = {
     "pq_linear_workspace_bytes": (_sz, [_i64, _i64]),
     "pq_linear": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i32, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
     "pq_set_gemm_variant": (ctypes.c_int, [ctypes.c_int]),
+    "pq_rotate_quant8": (ctypes.c_int, [_vp, _i64, _i64, _i32, _f32, _vp, _vp]),
+    "pq_w4a8_gemm": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i64, _i64, _i64, _vp, _vp, _vp]),
+    "pq_linear_w4a8_workspace_bytes": (_sz, [_i64, _i64]),
+    "pq_linear_w4a8": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i32, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
 }
 
 _lib = None
@@ -134,6 +138,58 @@ def pq_linear(x, wq, w_scale, act_scale, had_block, out=None, workspace=None):
         out = torch.empty((M, N), dtype=torch.float16, device=x.device)
     _check(lib().pq_linear(_ptr(x), _ptr(wq), _ptr(w_scale), float(act_scale), int(had_block), M, N, K, _ptr(out),
                            _ptr(workspace), workspace.numel(), _stream()), "pq_linear")
+    return out, workspace
+
+
+def pq_rotate_quant8(x: torch.Tensor, had_block: int, act_scale: float, out: torch.Tensor | None = None):
+    """x fp16 [M,K] -> 8-bit codes int8 [M,K] in the grouped (even-then-odd per 32 channels) layout."""
+    _dev(x, torch.float16, "x")
+    M, K = x.shape
+    if out is None:
+        out = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    _check(lib().pq_rotate_quant8(_ptr(x), M, K, int(had_block), float(act_scale), _ptr(out), _stream()),
+           "pq_rotate_quant8")
+    return out
+
+
+def pq_w4a8_gemm(xq8, wq, w_scale, act_scale, want_out=True, want_acc=False, out=None, acc=None):
+    """grouped int8 codes [M,K] x packed weights [N,K/2] -> (out fp16 | None, acc int32 | None)."""
+    _dev(xq8, torch.int8, "xq8")
+    _dev(wq, torch.uint8, "wq")
+    _dev(w_scale, torch.float32, "w_scale")
+    M, K = xq8.shape
+    N = wq.shape[0]
+    if wq.shape[1] * 2 != K or w_scale.numel() != N:
+        raise ValueError("shape mismatch")
+    if want_out and out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=xq8.device)
+    if want_acc and acc is None:
+        acc = torch.empty((M, N), dtype=torch.int32, device=xq8.device)
+    _check(lib().pq_w4a8_gemm(_ptr(xq8), _ptr(wq), _ptr(w_scale), float(act_scale), M, N, K, _ptr(out), _ptr(acc),
+                              _stream()), "pq_w4a8_gemm")
+    return out, acc
+
+
+def pq_linear_w4a8_workspace_bytes(M: int, K: int) -> int:
+    return int(lib().pq_linear_w4a8_workspace_bytes(M, K))
+
+
+def pq_linear_w4a8(x, wq, w_scale, act_scale, had_block, out=None, workspace=None):
+    """The whole W4A8 layer.  Returns (out fp16 [M,N], workspace uint8 holding the grouped int8 codes)."""
+    _dev(x, torch.float16, "x")
+    _dev(wq, torch.uint8, "wq")
+    _dev(w_scale, torch.float32, "w_scale")
+    M, K = x.shape
+    N = wq.shape[0]
+    if wq.shape[1] * 2 != K or w_scale.numel() != N:
+        raise ValueError("shape mismatch")
+    need = pq_linear_w4a8_workspace_bytes(M, K)
+    if workspace is None:
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=x.device)
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    _check(lib().pq_linear_w4a8(_ptr(x), _ptr(wq), _ptr(w_scale), float(act_scale), int(had_block), M, N, K,
+                                _ptr(out), _ptr(workspace), workspace.numel(), _stream()), "pq_linear_w4a8")
     return out, workspace
 
 

@@ -121,6 +121,58 @@ int pq_linear(const void* x_f16, const void* wq_packed, const float* w_scale, fl
     return pq_w4a4_gemm(workspace, wq_packed, w_scale, act_scale, M, N, K, out_f16, nullptr, stream);
 }
 
+int pq_rotate_quant8(const void* x_f16, int64_t M, int64_t K, int32_t had_block, float act_scale,
+                     void* xq8_grouped, void* stream)
+{
+    if (M < 0 || K <= 0 || (K % 128) != 0) return PQ_ERR_SHAPE;
+    if (had_block < 0 || had_block > 16384) return PQ_ERR_SHAPE;
+    if (had_block > 1 && ((had_block & (had_block - 1)) != 0 || (K % had_block) != 0)) return PQ_ERR_SHAPE;
+    if (!x_f16 || !xq8_grouped) return PQ_ERR_NULL;
+    if (!aligned16(x_f16) || !aligned16(xq8_grouped)) return PQ_ERR_ALIGN;
+    if (!good_scale(act_scale)) return PQ_ERR_SCALE;
+    if (M == 0) return PQ_OK;
+    return pq::launch_rotate_quant8(x_f16, M, K, had_block, act_scale, xq8_grouped, static_cast<hipStream_t>(stream));
+}
+
+int pq_w4a8_gemm(const void* xq8_grouped, const void* wq_packed, const float* w_scale, float act_scale, int64_t M,
+                 int64_t N, int64_t K, void* out_f16, int32_t* acc_i32, void* stream)
+{
+    int rc = check_gemm(xq8_grouped, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32);
+    if (rc != PQ_OK) return rc;
+    if ((K % 128) != 0) return PQ_ERR_SHAPE;
+    if (M == 0) return PQ_OK;
+    return pq::launch_gemm_w4a8(xq8_grouped, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32,
+                                static_cast<hipStream_t>(stream));
+}
+
+size_t pq_linear_w4a8_workspace_bytes(int64_t M, int64_t K)
+{
+    if (M <= 0 || K <= 0) return 0;
+    const size_t b = (size_t)M * (size_t)K;
+    return (b + 255) & ~(size_t)255;
+}
+
+int pq_linear_w4a8(const void* x_f16, const void* wq_packed, const float* w_scale, float act_scale,
+                   int32_t had_block, int64_t M, int64_t N, int64_t K, void* out_f16, void* workspace,
+                   size_t workspace_bytes, void* stream)
+{
+    if (M < 0 || N <= 0 || K <= 0 || (K % 128) != 0 || (N % 16) != 0) return PQ_ERR_SHAPE;
+    if (!x_f16 || !wq_packed || !w_scale || !out_f16) return PQ_ERR_NULL;
+    if (M == 0) return PQ_OK;
+    if (!workspace || workspace_bytes < pq_linear_w4a8_workspace_bytes(M, K)) return PQ_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return PQ_ERR_ALIGN;
+    int rc = check_gemm(workspace, wq_packed, w_scale, act_scale, M, N, K, out_f16, nullptr);
+    if (rc != PQ_OK) return rc;
+    if (had_block < 0 || had_block > 16384 ||
+        (had_block > 1 && ((had_block & (had_block - 1)) != 0 || (K % had_block) != 0)))
+        return PQ_ERR_SHAPE;
+    if (!aligned16(x_f16)) return PQ_ERR_ALIGN;
+    if (K > 65536 || M * K >= ((int64_t)1 << 32)) return PQ_ERR_UNSUPPORTED;
+    rc = pq_rotate_quant8(x_f16, M, K, had_block, act_scale, workspace, stream);
+    if (rc != PQ_OK) return rc;
+    return pq_w4a8_gemm(workspace, wq_packed, w_scale, act_scale, M, N, K, out_f16, nullptr, stream);
+}
+
 int pq_set_gemm_variant(int variant)
 {
     if (variant < 0 || variant > 4) return -1;

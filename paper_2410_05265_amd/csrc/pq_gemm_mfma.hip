@@ -61,9 +61,10 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 // operand: shift, mask; 1 per dword for an odd one: mask) are listed in the order the
 // operands are needed and spread evenly over the slots, running `lead` micro-operations
 // ahead of the instruction that needs them (into the next half stage at the end).
-template <int TM, int TN>
+// With 8-bit activations (A8) only the weight operands are expanded.
+template <int TM, int TN, bool A8>
 struct MmaSched {
-    static constexpr int NM = TM * TN, NOP = TM + TN, NSLOT = 2 * NM, PER = 12 * NOP;
+    static constexpr int NM = TM * TN, NOP = A8 ? TN : TM + TN, NSLOT = 2 * NM, PER = 12 * NOP;
     int mi[NM], mj[NM], op_is_a[NOP], op_idx[NOP], need[NSLOT], lead;
     constexpr MmaSched() : mi{}, mj{}, op_is_a{}, op_idx{}, need{}, lead(0)
     {
@@ -75,7 +76,7 @@ struct MmaSched {
                 for (int i = 0; i < (d < TM ? d : TM); ++i) { mi[nm] = i; mj[nm] = d; before[nm] = no; ++nm; }
             }
             if (d < TM) {
-                op_is_a[no] = 1; op_idx[no] = d; ++no;
+                if (!A8) { op_is_a[no] = 1; op_idx[no] = d; ++no; }
                 for (int j = 0; j <= (d < TN - 1 ? d : TN - 1); ++j) { mi[nm] = d; mj[nm] = j; before[nm] = no; ++nm; }
             }
         }
@@ -85,8 +86,19 @@ struct MmaSched {
             if (def > lead) lead = def;
         }
     }
+    // With weight operand j read in slot b_slot0 + j and activation operand i in slot a_slot0 + i of
+    // the preceding half stage: is every operand read before the first micro-operation that uses it?
+    constexpr bool reads_precede_expansion(int b_slot0, int a_slot0) const
+    {
+        for (int o = 0; o < NOP; ++o) {
+            const int rs = (op_is_a[o] ? a_slot0 : b_slot0) + op_idx[o];
+            if (lead + rs * PER / NSLOT > PER + 8 * o) return false;   // slot rs starts after that micro-operation
+            if (lead + rs * PER / NSLOT > PER + 8 * NOP + 4 * o) return false;
+        }
+        return true;
+    }
 };
-template <int TM, int TN> inline constexpr MmaSched<TM, TN> kSched{};
+template <int TM, int TN, bool A8> inline constexpr MmaSched<TM, TN, A8> kSched{};
 
 template <int I, int N, typename F>
 __device__ __forceinline__ void static_for(F&& f)
@@ -102,7 +114,7 @@ __device__ __forceinline__ void static_for(F&& f)
 
 template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
-template <int BM, int BN, int WR, int WC, int NS, int SUBS>
+template <int BM, int BN, int WR, int WC, int NS, int SUBS, int ABITS, int ASHIFT>
 __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __restrict__ xq,
                                                           const uint8_t* __restrict__ wq,
                                                           const float* __restrict__ sw, float sx, int M, int N,
@@ -112,11 +124,17 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
     constexpr int NW = WR * WC;
     constexpr int WM = BM / WR, WN = BN / WC, TM = WM / 32, TN = WN / 32;
     // a ring stage is SUBS sub-stages of 128 channels each (one barrier per stage)
-    constexpr int A_BYTES = BM * 64, SUB_BYTES = (BM + BN) * 64, STAGE = SUBS * SUB_BYTES;
-    constexpr int BLK = (BM + BN) / 16;   // 1 KiB blocks per stage
-    constexpr int LW = BLK / NW;          // direct loads per wavefront per stage
-    static_assert(BLK % NW == 0 && (BM / 16) % NW == 0, "loader shape");
-    constexpr int LWA = (BM / 16) / NW;   // of which for the activation rows
+    // ABITS = 4: activations are packed nibbles like the weights.  ABITS = 8: one int8 per channel
+    // (128 bytes per row per stage), in the order "even channels, then odd channels" inside every
+    // group of 32, so that a 16-byte read is an operand as it stands; the accumulator then carries
+    // a factor 2^ASHIFT (16 from the weights, times whatever the activation bytes carry).
+    constexpr bool A8 = ABITS == 8;
+    constexpr int A_ROW = A8 ? 128 : 64;
+    constexpr int A_BYTES = BM * A_ROW, SUB_BYTES = A_BYTES + BN * 64, STAGE = SUBS * SUB_BYTES;
+    constexpr int ABLK = A_BYTES / 1024, BLK = ABLK + BN / 16;   // 1 KiB blocks per sub-stage
+    constexpr int LW = BLK / NW;          // direct loads per wavefront per sub-stage
+    static_assert(BLK % NW == 0 && ABLK % NW == 0, "loader shape");
+    constexpr int LWA = ABLK / NW;        // of which for the activation rows
     extern __shared__ __align__(16) uint8_t smem[];
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -132,23 +150,28 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
     // ---- loader
     const int lrow = lane >> 2, lpos = lane & 3;
     const int lchunk = lpos ^ ((lrow >> 2) & 3);
+    // int8 activation rows: 8 lanes per 128-byte row, 8 rows per block; the 16-byte unit at position p
+    // of tile row t holds unit p ^ ((t >> 1) & 7).  Block b = wave + NW * i holds rows 8 b .. 8 b + 7 and
+    // NW is even, so bit 3 of t is the wave's parity for every i.
+    static_assert(NW % 2 == 0, "unit swizzle assumes an even number of wavefronts");
+    const int lrow8 = lane >> 3, lchunk8 = (lane & 7) ^ (((wave & 1) << 2) | (lrow8 >> 1));
     uint32_t goff[LW];
 #pragma unroll
     for (int i = 0; i < LW; ++i) {
-        const int blk = wave + NW * i;  // blocks [0, BM/16) hold activation rows, the rest weight rows
-        int row;
+        const int blk = wave + NW * i;  // blocks [0, ABLK) hold activation rows, the rest weight rows
         if (i < LWA) {
-            row = m0 + blk * 16 + lrow;
+            int row = m0 + (A8 ? blk * 8 + lrow8 : blk * 16 + lrow);
             row = row < M ? row : M - 1;
+            goff[i] = A8 ? (uint32_t)row * (uint32_t)K + lchunk8 * 16 : (uint32_t)row * (uint32_t)Kb + lchunk * 16;
         } else {
-            row = n0 + (blk - BM / 16) * 16 + lrow;
+            int row = n0 + (blk - ABLK) * 16 + lrow;
             row = row < N ? row : N - 1;
+            goff[i] = (uint32_t)row * (uint32_t)Kb + lchunk * 16;
         }
-        goff[i] = (uint32_t)row * (uint32_t)Kb + lchunk * 16;
     }
     auto dma_one = [&](int d, int kt, int buf) {   // d-th direct load of a stage, d < SUBS * LW
         const int sub = d / LW, i = d % LW;
-        const uint8_t* src = (i < LWA ? xq : wq) + (size_t)(kt * SUBS + sub) * 64 + goff[i];
+        const uint8_t* src = (i < LWA ? xq + (size_t)(kt * SUBS + sub) * A_ROW : wq + (size_t)(kt * SUBS + sub) * 64) + goff[i];
         __builtin_amdgcn_global_load_lds(PQ_GLB(src),
                                          PQ_LDS(smem + buf * STAGE + sub * SUB_BYTES + (wave + NW * i) * 1024), 16, 0, 0);
     };
@@ -159,6 +182,11 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
     // ---- reader
     const int swr = (r >> 2) & 3;
     const int rdA0 = (wm * WM + r) * 64 + (((0 + g) ^ swr) << 4), rdA1 = (wm * WM + r) * 64 + (((2 + g) ^ swr) << 4);
+    // int8 rows: matrix step s of a stage reads unit 2 (2 (s / 2) + g) + (s & 1) of the row's eight
+    int rdA8[4];
+#pragma unroll
+    for (int st = 0; st < 4; ++st)
+        rdA8[st] = (wm * WM + r) * 128 + (((2 * (2 * (st >> 1) + g) + (st & 1)) ^ ((r >> 1) & 7)) << 4);
     const int rdB0 = A_BYTES + (wn * WN + r) * 64 + (((0 + g) ^ swr) << 4);
     const int rdB1 = A_BYTES + (wn * WN + r) * 64 + (((2 + g) ^ swr) << 4);
 
@@ -170,32 +198,44 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
-    using SC = MmaSched<TM, TN>;
+    using SC = MmaSched<TM, TN, A8>;
     v4i pa[2][TM], pb[2][TN];         // packed operands of the current / next half stage
     v4i xa[2][2][TM], xb[2][2][TN];   // expanded: [half-stage parity][even, odd][tile]
     constexpr int MASK = (int)0xF0F0F0F0u;
 
-    auto read_frag = [&](const uint8_t* stage, int kk, int set, int f) {  // f < TM: activations, else weights
-        if (f < TM)
-            pa[set][f] = *reinterpret_cast<const v4i*>(stage + (kk ? rdA1 : rdA0) + f * 2048);
-        else
-            pb[set][f - TM] = *reinterpret_cast<const v4i*>(stage + (kk ? rdB1 : rdB0) + (f - TM) * 2048);
+    // LDS reads of one half stage: NRD of them, one per slot.  Packed activations: TM + TN reads;
+    // int8 activations: two per activation tile (they are operands as they stand) + TN.
+    constexpr int NRD = A8 ? 2 * TM + TN : TM + TN;
+    auto read_frag = [&](const uint8_t* stage, int kk, int set, int f) {
+        if constexpr (A8) {
+            // weights first: their expansion starts while the previous half stage is still running
+            if (f < TN)
+                pb[set][f] = *reinterpret_cast<const v4i*>(stage + (kk ? rdB1 : rdB0) + f * 2048);
+            else
+                xa[set][(f - TN) & 1][(f - TN) >> 1] =
+                    *reinterpret_cast<const v4i*>(stage + rdA8[2 * kk + ((f - TN) & 1)] + ((f - TN) >> 1) * 4096);
+        } else {
+            if (f < TM)
+                pa[set][f] = *reinterpret_cast<const v4i*>(stage + (kk ? rdA1 : rdA0) + f * 2048);
+            else
+                pb[set][f - TM] = *reinterpret_cast<const v4i*>(stage + (kk ? rdB1 : rdB0) + (f - TM) * 2048);
+        }
     };
     // expansion micro-operation u (0 <= u < PER) of the half stage with parity `set`
     auto micro = [&](auto setc, auto uc) {
         constexpr int set = decltype(setc)::value, u = decltype(uc)::value;
         if constexpr (u < 8 * SC::NOP) {
             constexpr int o = u / 8, d = (u % 8) / 2, kind = u % 2;
-            constexpr int idx = kSched<TM, TN>.op_idx[o];
-            if constexpr (kSched<TM, TN>.op_is_a[o]) {
+            constexpr int idx = kSched<TM, TN, A8>.op_idx[o];
+            if constexpr (kSched<TM, TN, A8>.op_is_a[o]) {
                 if constexpr (kind == 0) xa[set][0][idx][d] = pa[set][idx][d] << 4; else xa[set][0][idx][d] &= MASK;
             } else {
                 if constexpr (kind == 0) xb[set][0][idx][d] = pb[set][idx][d] << 4; else xb[set][0][idx][d] &= MASK;
             }
         } else {
             constexpr int v = u - 8 * SC::NOP, o = v / 4, d = v % 4;
-            constexpr int idx = kSched<TM, TN>.op_idx[o];
-            if constexpr (kSched<TM, TN>.op_is_a[o]) xa[set][1][idx][d] = pa[set][idx][d] & MASK;
+            constexpr int idx = kSched<TM, TN, A8>.op_idx[o];
+            if constexpr (kSched<TM, TN, A8>.op_is_a[o]) xa[set][1][idx][d] = pa[set][idx][d] & MASK;
             else xb[set][1][idx][d] = pb[set][idx][d] & MASK;
         }
     };
@@ -203,11 +243,14 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
     // of the next half stage's operands (first TM+TN slots), optionally one direct load, one matrix instruction
     auto half_stage = [&](auto setc, const uint8_t* next_stage, int next_kk, bool dma, int dma_kt, int dma_buf) {
         constexpr int set = decltype(setc)::value;
-        static_assert(SUBS * LW <= SC::NSLOT, "one direct load per slot");
+        static_assert(SUBS * LW <= SC::NSLOT && NRD <= SC::NSLOT, "one direct load and one LDS read per slot");
+        // a packed operand must be read in a slot no later than the one that runs its first
+        // micro-operation (those of the next half stage's first operands run at the end of this one)
+        static_assert(kSched<TM, TN, A8>.reads_precede_expansion(A8 ? 0 : TM, 0), "operand read too late");
         static_for<0, SC::NSLOT>([&](auto nc) {
             constexpr int n = decltype(nc)::value;
-            if constexpr (n < TM + TN) read_frag(next_stage, next_kk, set ^ 1, n);
-            constexpr int u0 = kSched<TM, TN>.lead + n * SC::PER / SC::NSLOT, u1 = kSched<TM, TN>.lead + (n + 1) * SC::PER / SC::NSLOT;
+            if constexpr (n < NRD) read_frag(next_stage, next_kk, set ^ 1, n);
+            constexpr int u0 = kSched<TM, TN, A8>.lead + n * SC::PER / SC::NSLOT, u1 = kSched<TM, TN, A8>.lead + (n + 1) * SC::PER / SC::NSLOT;
             static_for<u0, u1>([&](auto uc) {
                 constexpr int u = decltype(uc)::value;
                 if constexpr (u < SC::PER) micro(std::integral_constant<int, set>{}, std::integral_constant<int, u>{});
@@ -217,7 +260,7 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
                 if (dma) dma_one(n, dma_kt, dma_buf);
             }
             constexpr int ph = n / SC::NM, k = n % SC::NM;
-            constexpr int i = kSched<TM, TN>.mi[k], j = kSched<TM, TN>.mj[k];
+            constexpr int i = kSched<TM, TN, A8>.mi[k], j = kSched<TM, TN, A8>.mj[k];
             acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(xb[set][ph][j], xa[set][ph][i], acc[i][j], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         });
@@ -228,8 +271,8 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
     for (int st = 0; st < NS; ++st) dma_stage(st < nk ? st : nk - 1, st);
     wait_vm<(NS - 1) * SUBS * LW>();
     lds_barrier();
-    static_for<0, TM + TN>([&](auto fc) { read_frag(smem, 0, 0, decltype(fc)::value); });
-    static_for<0, kSched<TM, TN>.lead>([&](auto uc) { micro(std::integral_constant<int, 0>{}, uc); });
+    static_for<0, NRD>([&](auto fc) { read_frag(smem, 0, 0, decltype(fc)::value); });
+    static_for<0, kSched<TM, TN, A8>.lead>([&](auto uc) { micro(std::integral_constant<int, 0>{}, uc); });
     __builtin_amdgcn_sched_barrier(0);
 
     int buf = 0;
@@ -265,7 +308,7 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int n = n0 + wn * WN + j * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-                    if (m < M && n < N) acc_out[(int64_t)m * N + n] = acc[i][j][v] >> 8;
+                    if (m < M && n < N) acc_out[(int64_t)m * N + n] = acc[i][j][v] >> ASHIFT;
                 }
         }
     }
@@ -279,7 +322,7 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
                 int n = nb + 8 * q + 4 * g;
                 n = n + 4 <= N ? n : N - 4;
                 sc[q] = *reinterpret_cast<const float4*>(sw + n);
-                const float f = sx * 0.00390625f;   // the accumulators hold 256 * acc: fold the exact 2^-8 here
+                const float f = sx * (1.0f / (float)(1 << ASHIFT));   // the accumulators hold 2^ASHIFT * acc: exact
                 sc[q].x *= f; sc[q].y *= f; sc[q].z *= f; sc[q].w *= f;
             }
 #pragma unroll
@@ -314,13 +357,14 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
     }
 }
 
-template <int BM, int BN, int WR, int WC, int NS, int SUBS>
+template <int BM, int BN, int WR, int WC, int NS, int SUBS, int ABITS = 4, int ASHIFT = 8>
 int launch_dma(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K, void* out,
                int32_t* acc, hipStream_t st)
 {
     const int GM = (int)((M + BM - 1) / BM), GN = (int)((N + BN - 1) / BN);
-    constexpr size_t lds = (size_t)NS * SUBS * (BM + BN) * 64;
-    auto kern = k_gemm_dma<BM, BN, WR, WC, NS, SUBS>;
+    constexpr size_t lds = (size_t)NS * SUBS * (BM * (ABITS == 8 ? 128 : 64) + BN * 64);
+    static_assert(lds <= 160 * 1024, "LDS ring too large");
+    auto kern = k_gemm_dma<BM, BN, WR, WC, NS, SUBS, ABITS, ASHIFT>;
     static bool attr_set = false;  // benign race: the call is idempotent
     if (lds > 48 * 1024 && !attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -505,6 +549,21 @@ int launch_gemm_mfma(const void* xq, const void* wq, const float* sw, float sx, 
         case 3: return launch_dma<256, 192, 2, 2, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
         case 4: return launch_dma<256, 256, 2, 4, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
         default: return launch_dma<256, 256, 2, 2, 4, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
+    }
+}
+
+// 4-bit weights x 8-bit activations (codes in the even/odd-grouped byte order written by the
+// 8-bit quantizer): the same kernel with the activation operand taken from LDS as it stands.
+int launch_gemm_w4a8(const void* xq8, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K,
+                     void* out, int32_t* acc, hipStream_t st)
+{
+    if (M > (1 << 30) || N > (1 << 30) || K > 65536 || K % 128 != 0) return PQ_ERR_UNSUPPORTED;
+    if (M * K >= ((int64_t)1 << 32) || N * (K / 2) >= ((int64_t)1 << 32)) return PQ_ERR_UNSUPPORTED;
+    switch (pick_cfg(M, N)) {
+        case 0: return launch_dma<256, 256, 2, 2, 3, 1, 8, 4>(xq8, wq, sw, sx, M, N, K, out, acc, st);
+        case 1: return launch_dma<256, 128, 2, 2, 3, 1, 8, 4>(xq8, wq, sw, sx, M, N, K, out, acc, st);
+        case 3: return launch_dma<256, 192, 2, 2, 3, 1, 8, 4>(xq8, wq, sw, sx, M, N, K, out, acc, st);
+        default: return launch_dma<128, 128, 2, 2, 3, 1, 8, 4>(xq8, wq, sw, sx, M, N, K, out, acc, st);
     }
 }
 

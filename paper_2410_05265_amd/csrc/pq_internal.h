@@ -11,6 +11,10 @@ namespace pq {
 // Launchers: arguments are already validated by the C entry points.
 int launch_rotate_quant(const void* x, int64_t M, int64_t K, int32_t h, float act_scale,
                         void* xq, hipStream_t st);
+int launch_rotate_quant8(const void* x, int64_t M, int64_t K, int32_t h, float act_scale,
+                         void* xq8, hipStream_t st);
+int launch_gemm_w4a8(const void* xq8, const void* wq, const float* sw, float sx, int64_t M,
+                     int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st);
 int launch_gemm_simple(const void* xq, const void* wq, const float* sw, float sx, int64_t M,
                        int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st);
 int launch_gemm_mfma(const void* xq, const void* wq, const float* sw, float sx, int64_t M,

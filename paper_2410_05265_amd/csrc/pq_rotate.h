@@ -122,6 +122,67 @@ __device__ __forceinline__ uint32_t quant_pack8(const float* v, const float* raw
     return (s - kMagicSum) ^ 0x88888888u;   // offset-binary nibbles -> two's complement
 }
 
+// 8-bit variant: codes in [-128, 127], one byte each.  The four even-channel bytes and the four
+// odd-channel bytes of the thread's eight channels are returned as two dwords.
+constexpr float kMagic8 = 12582912.0f;   // 1.5 * 2^23, bit pattern 0x4B400000: low byte = code
+
+template <bool EXACT>
+__device__ __forceinline__ void quant_bytes8(const float* v, const float* raw, float mult, float step, uint32_t& even4,
+                                             uint32_t& odd4)
+{
+    float t[8];
+    uint32_t bits[8];
+    bool suspect = false;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        t[i] = v[i] * mult;
+        const float c = __builtin_amdgcn_fmed3f(t[i], -128.0f, 127.0f);
+        const float r = c + kMagic8;
+        bits[i] = __float_as_uint(r);
+        if constexpr (EXACT) {
+            const float f = c - (r - kMagic8);
+            suspect |= (fabsf(f) > 0.5f - 0x1.0p-14f);   // |t| <= 128: two roundings move t by < 2^-15
+        }
+    }
+    if constexpr (EXACT) {
+        if (__builtin_amdgcn_ballot_w64(suspect) != 0) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float c = __builtin_amdgcn_fmed3f(t[i], -128.0f, 127.0f);
+                const float r = c + kMagic8;
+                const float f = c - (r - kMagic8);
+                if (fabsf(f) > 0.5f - 0x1.0p-14f) {
+                    const float k = floorf(t[i]);
+                    const float d = fmaf(k + 0.5f, step, -raw[i]);
+                    const int ki = (int)k;
+                    int q = d > 0.0f ? ki : (d < 0.0f ? ki + 1 : ((ki & 1) ? ki + 1 : ki));
+                    q = q < -128 ? -128 : (q > 127 ? 127 : q);
+                    bits[i] = 0x4B400000u + (uint32_t)q;
+                }
+            }
+        }
+    }
+    // byte 0 of bits[i] is the code; gather bytes with v_perm_b32 (selector: 0-3 second operand, 4-7 first)
+    even4 = __builtin_amdgcn_perm(bits[2], bits[0], 0x0c0c0400u) | __builtin_amdgcn_perm(bits[6], bits[4], 0x04000c0cu);
+    odd4 = __builtin_amdgcn_perm(bits[3], bits[1], 0x0c0c0400u) | __builtin_amdgcn_perm(bits[7], bits[5], 0x04000c0cu);
+}
+
+// BITS = 4: eight codes packed into dst_row[channel / 8].  BITS = 8: one byte per code; inside every
+// group of 32 channels the 16 even channels come first, then the 16 odd ones (the order in which
+// the matrix kernel consumes them), so a thread stores two dwords.
+template <int BITS, bool EXACT, typename DST>
+__device__ __forceinline__ void store_codes(const float* v, float mult, float step, DST dst_row, int64_t e0)
+{
+    if constexpr (BITS == 4) {
+        dst_row[e0 >> 3] = quant_pack8<EXACT>(v, v, mult, step);
+    } else {
+        uint32_t ev, od;
+        quant_bytes8<EXACT>(v, v, mult, step, ev, od);
+        const int64_t d = (e0 >> 5) * 8 + ((e0 >> 3) & 3);
+        dst_row[d] = ev;
+        dst_row[d + 4] = od;
+    }
+}
 
 // Rotate (block size 2^log2h, 0 = none), quantize and pack the channels [chunk0, chunk0 + 2048 G)
 // of one row.  x_row points at the row's first channel; packed dwords go to dst_row[channel / 8]
@@ -154,7 +215,7 @@ __device__ __forceinline__ void load_chunk(SRC x_row, int64_t K, int64_t chunk0,
     }
 }
 
-template <int G, bool EXACT, typename DST>
+template <int G, bool EXACT, int BITS = 4, typename DST>
 __device__ __forceinline__ void rotate_quant_regs(const v4i (&raw)[G], const bool (&live)[G], int64_t chunk0,
                                                   int log2h, float mult, float step, DST dst_row, lds_f32_ptr xch,
                                                   int tid, bool active)
@@ -181,7 +242,7 @@ __device__ __forceinline__ void rotate_quant_regs(const v4i (&raw)[G], const boo
         for (int g = 0; g < G; ++g) {
             if (live[g]) {
                 const int64_t e0 = chunk0 + (int64_t)g * kChunk + tid * 8;
-                dst_row[e0 >> 3] = quant_pack8<true>(v[g], v[g], mult, step);
+                store_codes<BITS, true>(v[g], mult, step, dst_row, e0);
             }
         }
     } else {
@@ -241,7 +302,7 @@ __device__ __forceinline__ void rotate_quant_regs(const v4i (&raw)[G], const boo
         for (int g = 0; g < G; ++g) {
             if (live[g]) {
                 const int64_t e0 = chunk0 + (int64_t)g * kChunk + tid * 8;
-                dst_row[e0 >> 3] = quant_pack8<false>(v[g], v[g], mult, step);
+                store_codes<BITS, false>(v[g], mult, step, dst_row, e0);
             }
         }
     }

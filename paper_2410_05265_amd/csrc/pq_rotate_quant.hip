@@ -24,7 +24,7 @@ using rq::kThreads;
 // R rows of one chunk column per workgroup: all R loads of a thread are issued before the
 // arithmetic starts (the kernel has 2.5 bytes of traffic per element and little else to hide
 // latency with).
-template <int G, bool EXACT, int R>
+template <int G, bool EXACT, int R, int BITS>
 __global__ __launch_bounds__(kThreads) void k_rotate_quant(const __half* __restrict__ x, int64_t M, int64_t K,
                                                           int log2h, float mult, float step,
                                                           uint32_t* __restrict__ xq)
@@ -42,23 +42,20 @@ __global__ __launch_bounds__(kThreads) void k_rotate_quant(const __half* __restr
     }
 #pragma unroll
     for (int r = 0; r < R; ++r)
-        rq::rotate_quant_regs<G, EXACT>(raw[r], live[r], chunk0, log2h, mult, step,
-                                        static_cast<uint32_t*>(xq + (row0 + r) * (K >> 3)), (rq::lds_f32_ptr)xch,
+        rq::rotate_quant_regs<G, EXACT, BITS>(raw[r], live[r], chunk0, log2h, mult, step,
+                                        static_cast<uint32_t*>(xq + (row0 + r) * (BITS == 8 ? K >> 2 : K >> 3)),
+                                        (rq::lds_f32_ptr)xch,
                                         threadIdx.x, row0 + r < M);
 }
 
-}  // namespace
-
-int launch_rotate_quant(const void* x, int64_t M, int64_t K, int32_t h, float act_scale, void* xq,
-                        hipStream_t st)
+template <int BITS>
+int launch_rq(const __half* xp, int64_t M, int64_t K, int32_t h, float act_scale, uint32_t* op, hipStream_t st)
 {
-    const __half* xp = static_cast<const __half*>(x);
-    uint32_t* op = static_cast<uint32_t*>(xq);
     if (M > 65535) {
-        // grid.y is limited to 65535 rows per launch
-        for (int64_t m0 = 0; m0 < M; m0 += 65535) {
-            const int64_t mm = (M - m0 < 65535) ? (M - m0) : 65535;
-            int rc = launch_rotate_quant(xp + m0 * K, mm, K, h, act_scale, op + m0 * K / 8, st);
+        // grid.y is limited to 65535 per launch
+        for (int64_t m0 = 0; m0 < M; m0 += 65534) {
+            const int64_t mm = (M - m0 < 65534) ? (M - m0) : 65534;
+            int rc = launch_rq<BITS>(xp + m0 * K, mm, K, h, act_scale, op + m0 * (BITS == 8 ? K / 4 : K / 8), st);
             if (rc != PQ_OK) return rc;
         }
         return PQ_OK;
@@ -66,7 +63,7 @@ int launch_rotate_quant(const void* x, int64_t M, int64_t K, int32_t h, float ac
     if (h <= 1) {
         const float inv = (float)(1.0 / (double)act_scale);
         dim3 grid((unsigned)((K + kChunk - 1) / kChunk), (unsigned)((M + 1) / 2));
-        hipLaunchKernelGGL((k_rotate_quant<1, true, 2>), grid, dim3(kThreads), 0, st, xp, M, K, 0, inv, act_scale, op);
+        hipLaunchKernelGGL((k_rotate_quant<1, true, 2, BITS>), grid, dim3(kThreads), 0, st, xp, M, K, 0, inv, act_scale, op);
         return hip_status(hipGetLastError());
     }
     int log2h = 0;
@@ -76,13 +73,25 @@ int launch_rotate_quant(const void* x, int64_t M, int64_t K, int32_t h, float ac
     const int R = G <= 2 ? 2 : 1;
     dim3 grid((unsigned)((K + (int64_t)G * kChunk - 1) / ((int64_t)G * kChunk)), (unsigned)((M + R - 1) / R));
     switch (G) {
-        case 1: hipLaunchKernelGGL((k_rotate_quant<1, false, 2>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, mult, act_scale, op); break;
-        case 2: hipLaunchKernelGGL((k_rotate_quant<2, false, 2>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, mult, act_scale, op); break;
-        case 4: hipLaunchKernelGGL((k_rotate_quant<4, false, 1>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, mult, act_scale, op); break;
-        case 8: hipLaunchKernelGGL((k_rotate_quant<8, false, 1>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, mult, act_scale, op); break;
+        case 1: hipLaunchKernelGGL((k_rotate_quant<1, false, 2, BITS>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, mult, act_scale, op); break;
+        case 2: hipLaunchKernelGGL((k_rotate_quant<2, false, 2, BITS>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, mult, act_scale, op); break;
+        case 4: hipLaunchKernelGGL((k_rotate_quant<4, false, 1, BITS>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, mult, act_scale, op); break;
+        case 8: hipLaunchKernelGGL((k_rotate_quant<8, false, 1, BITS>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, mult, act_scale, op); break;
         default: return PQ_ERR_UNSUPPORTED;
     }
     return hip_status(hipGetLastError());
+}
+
+}  // namespace
+
+int launch_rotate_quant(const void* x, int64_t M, int64_t K, int32_t h, float act_scale, void* xq, hipStream_t st)
+{
+    return launch_rq<4>(static_cast<const __half*>(x), M, K, h, act_scale, static_cast<uint32_t*>(xq), st);
+}
+
+int launch_rotate_quant8(const void* x, int64_t M, int64_t K, int32_t h, float act_scale, void* xq8, hipStream_t st)
+{
+    return launch_rq<8>(static_cast<const __half*>(x), M, K, h, act_scale, static_cast<uint32_t*>(xq8), st);
 }
 
 }  // namespace pq
