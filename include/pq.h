@@ -135,6 +135,41 @@ int pq_linear_w4a8(const void* x_f16, const void* wq_packed, const float* w_scal
                    float act_scale, int32_t had_block, int64_t M, int64_t N, int64_t K,
                    void* out_f16, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- per-token dynamic activation quantization (Table 1, row O1) ---------------------------
+ * The step size is computed on the fly, one per token (row):
+ *     y = rotation of x as in pq_rotate_quant;
+ *     row_scale[m] = fp32(clip * max_k |y[m,k]| / qmax),  qmax = 7 (bits = 4) or 127 (bits = 8);
+ *                    a row of zeros gets 1;
+ *     q[m,k] = clamp(round_half_even(y[m,k] / row_scale[m]), -qmax - 1, qmax).
+ * clip in (0, 1] is the tensor-wise clipping factor (Sec. 3 "Dynamic and Static"; 1 = none).
+ * bits = 4: codes packed canonically [M,K/2]; bits = 8: grouped int8 layout [M,K].
+ * Needs K % 128 == 0 and K <= 32768 (a workgroup holds a whole row), else PQ_ERR_SHAPE /
+ * PQ_ERR_UNSUPPORTED.  row_scale: out [M] fp32, 4-byte aligned.
+ * With had_block <= 1 codes and steps equal the definition evaluated in double precision.
+ */
+int pq_rotate_quant_dynamic(const void* x_f16, int64_t M, int64_t K, int32_t had_block,
+                            float clip, int32_t bits, void* xq, float* row_scale, void* stream);
+
+/* out[m,n] = fp16(acc[m,n] * (row_scale[m] * w_scale[n])), acc as in pq_w4a4_gemm (bits = 4) or
+ * pq_w4a8_gemm (bits = 8).  Always the MFMA tiled kernel; K % 128 == 0, K <= 65536.
+ */
+int pq_gemm_dynamic(const void* xq, int32_t bits, const void* wq_packed, const float* w_scale,
+                    const float* row_scale, int64_t M, int64_t N, int64_t K,
+                    void* out_f16, int32_t* acc_i32, void* stream);
+
+/* Workspace of pq_linear_dynamic: the codes (M*K/2 or M*K bytes, rounded up to 256) followed by
+ * the M row steps (rounded up to 256).  Host only.
+ */
+size_t pq_linear_dynamic_workspace_bytes(int64_t M, int64_t K, int32_t bits);
+
+/* pq_rotate_quant_dynamic into `workspace`, then pq_gemm_dynamic, on the same stream.  On return
+ * the workspace holds the codes at offset 0 and the fp32 row steps at offset
+ * pq_linear_dynamic_workspace_bytes(M,K,bits) - roundup256(4*M).
+ */
+int pq_linear_dynamic(const void* x_f16, const void* wq_packed, const float* w_scale,
+                      float clip, int32_t had_block, int32_t bits, int64_t M, int64_t N, int64_t K,
+                      void* out_f16, void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

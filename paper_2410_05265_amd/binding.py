@@ -33,6 +33,10 @@ SIGNATURES = {
     "pq_w4a8_gemm": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i64, _i64, _i64, _vp, _vp, _vp]),
     "pq_linear_w4a8_workspace_bytes": (_sz, [_i64, _i64]),
     "pq_linear_w4a8": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i32, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
+    "pq_rotate_quant_dynamic": (ctypes.c_int, [_vp, _i64, _i64, _i32, _f32, _i32, _vp, _vp, _vp]),
+    "pq_gemm_dynamic": (ctypes.c_int, [_vp, _i32, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp]),
+    "pq_linear_dynamic_workspace_bytes": (_sz, [_i64, _i64, _i32]),
+    "pq_linear_dynamic": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i32, _i32, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
 }
 
 _lib = None
@@ -190,6 +194,62 @@ def pq_linear_w4a8(x, wq, w_scale, act_scale, had_block, out=None, workspace=Non
         out = torch.empty((M, N), dtype=torch.float16, device=x.device)
     _check(lib().pq_linear_w4a8(_ptr(x), _ptr(wq), _ptr(w_scale), float(act_scale), int(had_block), M, N, K,
                                 _ptr(out), _ptr(workspace), workspace.numel(), _stream()), "pq_linear_w4a8")
+    return out, workspace
+
+
+def pq_rotate_quant_dynamic(x, had_block: int, clip: float = 1.0, bits: int = 4, out=None, row_scale=None):
+    """x fp16 [M,K] -> (codes: uint8 [M,K/2] packed (bits=4) or int8 [M,K] grouped (bits=8), row steps fp32 [M])."""
+    _dev(x, torch.float16, "x")
+    M, K = x.shape
+    if out is None:
+        out = (torch.empty((M, K), dtype=torch.int8, device=x.device) if bits == 8
+               else torch.empty((M, K // 2), dtype=torch.uint8, device=x.device))
+    if row_scale is None:
+        row_scale = torch.empty((max(M, 1),), dtype=torch.float32, device=x.device)[:M]
+    _check(lib().pq_rotate_quant_dynamic(_ptr(x), M, K, int(had_block), float(clip), int(bits), _ptr(out),
+                                         _ptr(row_scale), _stream()), "pq_rotate_quant_dynamic")
+    return out, row_scale
+
+
+def pq_gemm_dynamic(xq, bits, wq, w_scale, row_scale, want_out=True, want_acc=False, out=None, acc=None):
+    """codes x packed weights with per-token steps -> (out fp16 | None, acc int32 | None)."""
+    _dev(xq, torch.int8 if bits == 8 else torch.uint8, "xq")
+    _dev(wq, torch.uint8, "wq")
+    _dev(w_scale, torch.float32, "w_scale")
+    _dev(row_scale, torch.float32, "row_scale")
+    M, K = xq.shape[0], xq.shape[1] * (1 if bits == 8 else 2)
+    N = wq.shape[0]
+    if wq.shape[1] * 2 != K or w_scale.numel() != N or row_scale.numel() != M:
+        raise ValueError("shape mismatch")
+    if want_out and out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=xq.device)
+    if want_acc and acc is None:
+        acc = torch.empty((M, N), dtype=torch.int32, device=xq.device)
+    _check(lib().pq_gemm_dynamic(_ptr(xq), int(bits), _ptr(wq), _ptr(w_scale), _ptr(row_scale), M, N, K, _ptr(out),
+                                 _ptr(acc), _stream()), "pq_gemm_dynamic")
+    return out, acc
+
+
+def pq_linear_dynamic_workspace_bytes(M: int, K: int, bits: int = 4) -> int:
+    return int(lib().pq_linear_dynamic_workspace_bytes(M, K, int(bits)))
+
+
+def pq_linear_dynamic(x, wq, w_scale, had_block, clip: float = 1.0, bits: int = 4, out=None, workspace=None):
+    """The whole per-token dynamic layer.  Returns (out fp16 [M,N], workspace uint8: codes, then row steps)."""
+    _dev(x, torch.float16, "x")
+    _dev(wq, torch.uint8, "wq")
+    _dev(w_scale, torch.float32, "w_scale")
+    M, K = x.shape
+    N = wq.shape[0]
+    if wq.shape[1] * 2 != K or w_scale.numel() != N:
+        raise ValueError("shape mismatch")
+    need = pq_linear_dynamic_workspace_bytes(M, K, bits)
+    if workspace is None:
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=x.device)
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    _check(lib().pq_linear_dynamic(_ptr(x), _ptr(wq), _ptr(w_scale), float(clip), int(had_block), int(bits), M, N, K,
+                                   _ptr(out), _ptr(workspace), workspace.numel(), _stream()), "pq_linear_dynamic")
     return out, workspace
 
 

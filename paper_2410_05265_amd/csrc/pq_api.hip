@@ -173,6 +173,62 @@ int pq_linear_w4a8(const void* x_f16, const void* wq_packed, const float* w_scal
     return pq_w4a8_gemm(workspace, wq_packed, w_scale, act_scale, M, N, K, out_f16, nullptr, stream);
 }
 
+int pq_rotate_quant_dynamic(const void* x_f16, int64_t M, int64_t K, int32_t had_block, float clip, int32_t bits,
+                            void* xq, float* row_scale, void* stream)
+{
+    if (M < 0 || K <= 0 || (K % 128) != 0 || (bits != 4 && bits != 8)) return PQ_ERR_SHAPE;
+    if (had_block < 0 || had_block > 16384) return PQ_ERR_SHAPE;
+    if (had_block > 1 && ((had_block & (had_block - 1)) != 0 || (K % had_block) != 0)) return PQ_ERR_SHAPE;
+    if (!x_f16 || !xq || !row_scale) return PQ_ERR_NULL;
+    if (!aligned16(x_f16) || !aligned16(xq) || (reinterpret_cast<uintptr_t>(row_scale) & 3u)) return PQ_ERR_ALIGN;
+    if (!(isfinite(clip) && clip > 0.0f && clip <= 1.0f)) return PQ_ERR_SCALE;
+    if (K > 32768) return PQ_ERR_UNSUPPORTED;
+    if (M == 0) return PQ_OK;
+    return pq::launch_rotate_quant_dynamic(x_f16, M, K, had_block, clip, bits, xq, row_scale,
+                                           static_cast<hipStream_t>(stream));
+}
+
+int pq_gemm_dynamic(const void* xq, int32_t bits, const void* wq_packed, const float* w_scale, const float* row_scale,
+                    int64_t M, int64_t N, int64_t K, void* out_f16, int32_t* acc_i32, void* stream)
+{
+    if (bits != 4 && bits != 8) return PQ_ERR_SHAPE;
+    int rc = check_gemm(xq, wq_packed, w_scale, 1.0f, M, N, K, out_f16, acc_i32);
+    if (rc != PQ_OK) return rc;
+    if ((K % 128) != 0) return PQ_ERR_SHAPE;
+    if (!row_scale) return PQ_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(row_scale) & 3u) return PQ_ERR_ALIGN;
+    if (M == 0) return PQ_OK;
+    return pq::launch_gemm_dynamic(xq, bits, wq_packed, w_scale, row_scale, M, N, K, out_f16, acc_i32,
+                                   static_cast<hipStream_t>(stream));
+}
+
+size_t pq_linear_dynamic_workspace_bytes(int64_t M, int64_t K, int32_t bits)
+{
+    if (M <= 0 || K <= 0 || (bits != 4 && bits != 8)) return 0;
+    const size_t codes = bits == 8 ? (size_t)M * (size_t)K : (size_t)M * (size_t)(K / 2);
+    return ((codes + 255) & ~(size_t)255) + (((size_t)M * 4 + 255) & ~(size_t)255);
+}
+
+int pq_linear_dynamic(const void* x_f16, const void* wq_packed, const float* w_scale, float clip, int32_t had_block,
+                      int32_t bits, int64_t M, int64_t N, int64_t K, void* out_f16, void* workspace,
+                      size_t workspace_bytes, void* stream)
+{
+    if (M < 0 || N <= 0 || K <= 0 || (K % 128) != 0 || (N % 16) != 0 || (bits != 4 && bits != 8)) return PQ_ERR_SHAPE;
+    if (!x_f16 || !wq_packed || !w_scale || !out_f16) return PQ_ERR_NULL;
+    if (M == 0) return PQ_OK;
+    const size_t need = pq_linear_dynamic_workspace_bytes(M, K, bits);
+    if (!workspace || workspace_bytes < need) return PQ_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return PQ_ERR_ALIGN;
+    float* row_scale = reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + need -
+                                                (((size_t)M * 4 + 255) & ~(size_t)255));
+    int rc = check_gemm(workspace, wq_packed, w_scale, 1.0f, M, N, K, out_f16, nullptr);
+    if (rc != PQ_OK) return rc;
+    if (K > 32768 || M * K >= ((int64_t)1 << 32)) return PQ_ERR_UNSUPPORTED;
+    rc = pq_rotate_quant_dynamic(x_f16, M, K, had_block, clip, bits, workspace, row_scale, stream);
+    if (rc != PQ_OK) return rc;
+    return pq_gemm_dynamic(workspace, bits, wq_packed, w_scale, row_scale, M, N, K, out_f16, nullptr, stream);
+}
+
 int pq_set_gemm_variant(int variant)
 {
     if (variant < 0 || variant > 4) return -1;

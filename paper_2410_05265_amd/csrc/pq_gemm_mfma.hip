@@ -119,10 +119,12 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
                                                           const uint8_t* __restrict__ wq,
                                                           const float* __restrict__ sw, float sx, int M, int N,
                                                           int K, int GM, __half* __restrict__ out,
-                                                          int32_t* __restrict__ acc_out)
+                                                          int32_t* __restrict__ acc_out,
+                                                          const float* __restrict__ srow)
 {
     constexpr int NW = WR * WC;
     constexpr int WM = BM / WR, WN = BN / WC, TM = WM / 32, TN = WN / 32;
+    // srow: per-token step sizes [M] (per-token dynamic quantization) or NULL (one static step sx)
     // a ring stage is SUBS sub-stages of 128 channels each (one barrier per stage)
     // ABITS = 4: activations are packed nibbles like the weights.  ABITS = 8: one int8 per channel
     // (128 bytes per row per stage), in the order "even channels, then odd channels" inside every
@@ -312,7 +314,17 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
                 }
         }
     }
-    if (out) {
+    // DYN = false: one static step, folded into the channel scales once per tile column;
+    // DYN = true: the token's own step (the lane owns one token per tile row) times the channel scale
+    auto store_out = [&](auto dync) {
+        constexpr bool DYN = decltype(dync)::value;
+        constexpr float kUnshift = 1.0f / (float)(1 << ASHIFT);   // the accumulators hold 2^ASHIFT * acc: exact
+        float fm[TM];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int m = m0 + wm * WM + i * 32 + r;
+            fm[i] = DYN ? srow[m < M ? m : M - 1] * kUnshift : 0.0f;
+        }
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int nb = n0 + wn * WN + j * 32;
@@ -322,8 +334,10 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
                 int n = nb + 8 * q + 4 * g;
                 n = n + 4 <= N ? n : N - 4;
                 sc[q] = *reinterpret_cast<const float4*>(sw + n);
-                const float f = sx * (1.0f / (float)(1 << ASHIFT));   // the accumulators hold 2^ASHIFT * acc: exact
-                sc[q].x *= f; sc[q].y *= f; sc[q].z *= f; sc[q].w *= f;
+                if constexpr (!DYN) {
+                    const float f = sx * kUnshift;
+                    sc[q].x *= f; sc[q].y *= f; sc[q].z *= f; sc[q].w *= f;
+                }
             }
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
@@ -334,10 +348,10 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
 #pragma unroll
                     for (int h2 = 0; h2 < 2; ++h2) {
                         const int q = 2 * qp + h2;
-                        const float f0 = (float)acc[i][j][4 * q + 0] * sc[q].x;
-                        const float f1 = (float)acc[i][j][4 * q + 1] * sc[q].y;
-                        const float f2 = (float)acc[i][j][4 * q + 2] * sc[q].z;
-                        const float f3 = (float)acc[i][j][4 * q + 3] * sc[q].w;
+                        const float f0 = (float)acc[i][j][4 * q + 0] * (DYN ? sc[q].x * fm[i] : sc[q].x);
+                        const float f1 = (float)acc[i][j][4 * q + 1] * (DYN ? sc[q].y * fm[i] : sc[q].y);
+                        const float f2 = (float)acc[i][j][4 * q + 2] * (DYN ? sc[q].z * fm[i] : sc[q].z);
+                        const float f3 = (float)acc[i][j][4 * q + 3] * (DYN ? sc[q].w * fm[i] : sc[q].w);
                         const __half2 lo = __floats2half2_rn(f0, f1), hi = __floats2half2_rn(f2, f3);
                         pk[2 * h2 + 0] = *reinterpret_cast<const uint32_t*>(&lo);
                         pk[2 * h2 + 1] = *reinterpret_cast<const uint32_t*>(&hi);
@@ -354,12 +368,16 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
                 }
             }
         }
+    };
+    if (out) {
+        if (srow) store_out(std::true_type{});
+        else store_out(std::false_type{});
     }
 }
 
 template <int BM, int BN, int WR, int WC, int NS, int SUBS, int ABITS = 4, int ASHIFT = 8>
 int launch_dma(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K, void* out,
-               int32_t* acc, hipStream_t st)
+               int32_t* acc, hipStream_t st, const float* srow = nullptr)
 {
     const int GM = (int)((M + BM - 1) / BM), GN = (int)((N + BN - 1) / BN);
     constexpr size_t lds = (size_t)NS * SUBS * (BM * (ABITS == 8 ? 128 : 64) + BN * 64);
@@ -374,7 +392,7 @@ int launch_dma(const void* xq, const void* wq, const float* sw, float sx, int64_
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)(GM * GN)), dim3(WR * WC * 64), lds, st,
                        static_cast<const uint8_t*>(xq), static_cast<const uint8_t*>(wq), sw, sx, (int)M, (int)N,
-                       (int)K, GM, static_cast<__half*>(out), acc);
+                       (int)K, GM, static_cast<__half*>(out), acc, srow);
     return hip_status(hipGetLastError());
 }
 
@@ -564,6 +582,30 @@ int launch_gemm_w4a8(const void* xq8, const void* wq, const float* sw, float sx,
         case 1: return launch_dma<256, 128, 2, 2, 3, 1, 8, 4>(xq8, wq, sw, sx, M, N, K, out, acc, st);
         case 3: return launch_dma<256, 192, 2, 2, 3, 1, 8, 4>(xq8, wq, sw, sx, M, N, K, out, acc, st);
         default: return launch_dma<128, 128, 2, 2, 3, 1, 8, 4>(xq8, wq, sw, sx, M, N, K, out, acc, st);
+    }
+}
+
+// Per-token dynamic quantization (Table 1 row O1): out = acc * row_scale[m] * w_scale[n].  bits = 4
+// (packed codes) or 8 (grouped bytes).
+int launch_gemm_dynamic(const void* xq, int32_t bits, const void* wq, const float* sw, const float* srow, int64_t M,
+                        int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st)
+{
+    if (M > (1 << 30) || N > (1 << 30) || K > 65536 || K % 128 != 0) return PQ_ERR_UNSUPPORTED;
+    if (M * K >= ((int64_t)1 << 32) || N * (K / 2) >= ((int64_t)1 << 32)) return PQ_ERR_UNSUPPORTED;
+    const int cfg = pick_cfg(M, N);
+    if (bits == 8) {
+        switch (cfg) {
+            case 0: return launch_dma<256, 256, 2, 2, 3, 1, 8, 4>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
+            case 1: return launch_dma<256, 128, 2, 2, 3, 1, 8, 4>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
+            case 3: return launch_dma<256, 192, 2, 2, 3, 1, 8, 4>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
+            default: return launch_dma<128, 128, 2, 2, 3, 1, 8, 4>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
+        }
+    }
+    switch (cfg) {
+        case 0: return launch_dma<256, 256, 2, 2, 3, 1>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
+        case 1: return launch_dma<256, 128, 2, 2, 3, 1>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
+        case 3: return launch_dma<256, 192, 2, 2, 3, 1>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
+        default: return launch_dma<128, 128, 2, 2, 3, 1>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
     }
 }
 

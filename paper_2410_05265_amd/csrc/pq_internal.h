@@ -15,6 +15,10 @@ int launch_rotate_quant8(const void* x, int64_t M, int64_t K, int32_t h, float a
                          void* xq8, hipStream_t st);
 int launch_gemm_w4a8(const void* xq8, const void* wq, const float* sw, float sx, int64_t M,
                      int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st);
+int launch_rotate_quant_dynamic(const void* x, int64_t M, int64_t K, int32_t h, float clip, int32_t bits,
+                                void* xq, float* row_scale, hipStream_t st);
+int launch_gemm_dynamic(const void* xq, int32_t bits, const void* wq, const float* sw, const float* srow,
+                        int64_t M, int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st);
 int launch_gemm_simple(const void* xq, const void* wq, const float* sw, float sx, int64_t M,
                        int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st);
 int launch_gemm_mfma(const void* xq, const void* wq, const float* sw, float sx, int64_t M,

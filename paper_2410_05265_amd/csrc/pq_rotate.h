@@ -215,11 +215,23 @@ __device__ __forceinline__ void load_chunk(SRC x_row, int64_t K, int64_t chunk0,
     }
 }
 
-template <int G, bool EXACT, int BITS = 4, typename DST>
-__device__ __forceinline__ void rotate_quant_regs(const v4i (&raw)[G], const bool (&live)[G], int64_t chunk0,
-                                                  int log2h, float mult, float step, DST dst_row, lds_f32_ptr xch,
-                                                  int tid, bool active)
+// The step of a static quantizer: known before the rotation.
+struct StaticStep {
+    float mult, step;
+    template <int NV>
+    __device__ __forceinline__ void operator()(const float (&)[NV], float& m, float& s) const { m = mult; s = step; }
+};
+
+// `steps(values, mult, step)` is called once, after the rotation, with the thread's G * 8 rotated
+// (unnormalised) values, and sets the quantizer's reciprocal step and step: a static quantizer
+// returns constants, a dynamic one derives them from the values (and may synchronise the
+// workgroup; every thread calls it).
+template <int G, bool EXACT, int BITS = 4, typename DST, typename STEPS>
+__device__ __forceinline__ void rotate_quant_regs_with(const v4i (&raw)[G], const bool (&live)[G], int64_t chunk0,
+                                                       int log2h, STEPS steps, DST dst_row, lds_f32_ptr xch,
+                                                       int tid, bool active)
 {
+    float mult, step;
     const int lane = tid & 63;
     const int wave = tid >> 6;
 
@@ -238,6 +250,7 @@ __device__ __forceinline__ void rotate_quant_regs(const v4i (&raw)[G], const boo
 
     if constexpr (EXACT) {
         // no rotation: the unrotated value doubles as the exact tie-break operand
+        steps(reinterpret_cast<float(&)[G * 8]>(v), mult, step);
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             if (live[g]) {
@@ -298,6 +311,7 @@ __device__ __forceinline__ void rotate_quant_regs(const v4i (&raw)[G], const boo
                 }
             }
         }
+        steps(flat, mult, step);
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             if (live[g]) {
@@ -306,6 +320,14 @@ __device__ __forceinline__ void rotate_quant_regs(const v4i (&raw)[G], const boo
             }
         }
     }
+}
+
+template <int G, bool EXACT, int BITS = 4, typename DST>
+__device__ __forceinline__ void rotate_quant_regs(const v4i (&raw)[G], const bool (&live)[G], int64_t chunk0,
+                                                  int log2h, float mult, float step, DST dst_row, lds_f32_ptr xch,
+                                                  int tid, bool active)
+{
+    rotate_quant_regs_with<G, EXACT, BITS>(raw, live, chunk0, log2h, StaticStep{mult, step}, dst_row, xch, tid, active);
 }
 
 template <int G, bool EXACT, typename SRC, typename DST>

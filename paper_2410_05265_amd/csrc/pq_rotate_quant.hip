@@ -82,6 +82,96 @@ int launch_rq(const __half* xp, int64_t M, int64_t K, int32_t h, float act_scale
     return hip_status(hipGetLastError());
 }
 
+// The step of a token: fp32(clip * max|y| / qmax) over the whole row held by the workgroup, with
+// max|y| = max|v| / sqrt(h) for the unnormalised butterfly outputs v; a row of zeros gets 1.
+template <int BITS>
+struct DynamicStep {
+    double inv_sqrt_h;
+    float clip;
+    float* red;        // 4 floats of LDS
+    float* step_out;   // this row's slot of row_scale
+    int tid;
+    template <int NV>
+    __device__ __forceinline__ void operator()(const float (&v)[NV], float& mult, float& step) const
+    {
+        float amax = 0.0f;   // dead groups hold zeros
+#pragma unroll
+        for (int i = 0; i < NV; ++i) amax = fmaxf(amax, fabsf(v[i]));
+        amax = fmaxf(amax, rq::lane_xor<0>(amax));
+        amax = fmaxf(amax, rq::lane_xor<1>(amax));
+        amax = fmaxf(amax, rq::lane_xor<2>(amax));
+        amax = fmaxf(amax, rq::lane_xor<3>(amax));
+        amax = fmaxf(amax, rq::lane_xor<4>(amax));
+        amax = fmaxf(amax, rq::lane_xor<5>(amax));
+        if ((tid & 63) == 0) red[tid >> 6] = amax;
+        __syncthreads();
+        amax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        constexpr double qmax = BITS == 8 ? 127.0 : 7.0;
+        step = (float)(((double)clip * ((double)amax * inv_sqrt_h)) / qmax);
+        if (!(step > 0.0f)) step = 1.0f;
+        mult = (float)(inv_sqrt_h / (double)step);
+        if (tid == 0) *step_out = step;
+    }
+};
+
+// Per-token dynamic variant (Table 1 row O1): the step size of a row depends on that row's rotated
+// values, so a workgroup owns a whole row: NC chunks of 2048 channels stay in registers
+// (K <= 2048 NC) between the rotation, the row maximum and the quantizer.  The row's step goes to
+// row_scale[m]; codes as in the static kernels (BITS = 4 packed, 8 grouped bytes).
+template <int NC, int BITS>
+__global__ __launch_bounds__(kThreads) void k_rotate_quant_dyn(const __half* __restrict__ x, int64_t K, int log2h,
+                                                              double inv_sqrt_h, float clip,
+                                                              uint32_t* __restrict__ xq, float* __restrict__ row_scale)
+{
+    extern __shared__ float xch_dyn[];   // 2048 NC floats when log2h > 9, else unused
+    __shared__ float red[4];
+    const int tid = threadIdx.x;
+    const int64_t row = blockIdx.x;
+    v4i raw[NC];
+    bool live[NC];
+    rq::load_chunk<NC>(static_cast<const __half*>(x + row * K), K, 0, tid, true, raw, live);
+    const DynamicStep<BITS> steps{inv_sqrt_h, clip, red, row_scale + row, tid};
+    uint32_t* dst_row = xq + row * (BITS == 8 ? K >> 2 : K >> 3);
+    if (log2h == 0)
+        rq::rotate_quant_regs_with<NC, true, BITS>(raw, live, 0, 0, steps, dst_row, (rq::lds_f32_ptr)xch_dyn, tid, true);
+    else
+        rq::rotate_quant_regs_with<NC, false, BITS>(raw, live, 0, log2h, steps, dst_row, (rq::lds_f32_ptr)xch_dyn, tid,
+                                                    true);
+}
+
+template <int NC, int BITS>
+int launch_dyn_nc(const __half* xp, int64_t M, int64_t K, int log2h, double inv_sqrt_h, float clip, uint32_t* op,
+                  float* row_scale, hipStream_t st)
+{
+    const size_t lds = log2h > 9 ? (size_t)NC * kChunk * sizeof(float) : 0;
+    auto kern = k_rotate_quant_dyn<NC, BITS>;
+    static bool attr_set = false;  // benign race: the call is idempotent
+    if (lds > 48 * 1024 && !attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)((size_t)NC * kChunk * sizeof(float))) != hipSuccess)
+            return PQ_ERR_HIP;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)M), dim3(kThreads), lds, st, xp, K, log2h, inv_sqrt_h, clip, op, row_scale);
+    return hip_status(hipGetLastError());
+}
+
+template <int BITS>
+int launch_dyn(const __half* xp, int64_t M, int64_t K, int32_t h, float clip, uint32_t* op, float* row_scale,
+               hipStream_t st)
+{
+    if (K > 16 * kChunk || M > 0x7fffffff) return PQ_ERR_UNSUPPORTED;
+    int log2h = 0;
+    while ((1 << log2h) < h) ++log2h;
+    const double inv_sqrt_h = h > 1 ? 1.0 / sqrt((double)h) : 1.0;
+    const int nc = (int)((K + kChunk - 1) / kChunk);
+    if (nc <= 1) return launch_dyn_nc<1, BITS>(xp, M, K, log2h, inv_sqrt_h, clip, op, row_scale, st);
+    if (nc <= 2) return launch_dyn_nc<2, BITS>(xp, M, K, log2h, inv_sqrt_h, clip, op, row_scale, st);
+    if (nc <= 4) return launch_dyn_nc<4, BITS>(xp, M, K, log2h, inv_sqrt_h, clip, op, row_scale, st);
+    if (nc <= 8) return launch_dyn_nc<8, BITS>(xp, M, K, log2h, inv_sqrt_h, clip, op, row_scale, st);
+    return launch_dyn_nc<16, BITS>(xp, M, K, log2h, inv_sqrt_h, clip, op, row_scale, st);
+}
+
 }  // namespace
 
 int launch_rotate_quant(const void* x, int64_t M, int64_t K, int32_t h, float act_scale, void* xq, hipStream_t st)
@@ -92,6 +182,14 @@ int launch_rotate_quant(const void* x, int64_t M, int64_t K, int32_t h, float ac
 int launch_rotate_quant8(const void* x, int64_t M, int64_t K, int32_t h, float act_scale, void* xq8, hipStream_t st)
 {
     return launch_rq<8>(static_cast<const __half*>(x), M, K, h, act_scale, static_cast<uint32_t*>(xq8), st);
+}
+
+int launch_rotate_quant_dynamic(const void* x, int64_t M, int64_t K, int32_t h, float clip, int32_t bits, void* xq,
+                                float* row_scale, hipStream_t st)
+{
+    if (bits == 8)
+        return launch_dyn<8>(static_cast<const __half*>(x), M, K, h, clip, static_cast<uint32_t*>(xq), row_scale, st);
+    return launch_dyn<4>(static_cast<const __half*>(x), M, K, h, clip, static_cast<uint32_t*>(xq), row_scale, st);
 }
 
 }  // namespace pq
