@@ -30,6 +30,7 @@ if ROOT not in sys.path:
 INT8_PEAK_TOPS = 5033.0      # MI355X dense INT8 MFMA: 256 CU x 2.4 GHz x 8192 ops/clk/CU
 HBM_PEAK_GBS = 8000.0
 M_PREFILL = 2048
+EVENT_EVERY = 5             # steps between two event-instrumented steps of the timed region
 # HBM bytes per GEMM launch (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 from rocprofv3 --pmc, averaged over the
 # five launches of a step; see profiles/gemm_prefill_llama3_8b_pmc.md).  Algorithmic: 63.3e6.
 GEMM_HBM_TRAFFIC_BYTES = 129.3e6
@@ -80,14 +81,53 @@ def run_prefill(torch, pq, layers, steps, warmup):
     torch.cuda.synchronize()
     events = []
     t0 = time.perf_counter()
-    for _ in range(steps):
-        step(events)
+    for i in range(steps):
+        # an event pair fences the stream (the next launch cannot start under the tail of the
+        # previous one), so only every EVENT_EVERY-th step of the timed region carries them
+        step(events if i % EVENT_EVERY == 0 else None)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     per = {}
     for name, e0, e1 in events:
         per.setdefault(name, []).append(e0.elapsed_time(e1) * 1e-3)
     return dt / steps, {k: sum(v) / len(v) for k, v in per.items()}
+
+
+def run_variants(torch, pq, layers, steps, warmup, ops):
+    """The same step with the widened quantizers: 8-bit static activations (the paper's W4A8
+    setting) and per-token dynamic steps (Table 1 row O1) at 4 and 8 bits.  Wall time per step."""
+    M = layers[0]["x"].shape[0]
+    for L in layers:
+        L["xq8"] = torch.empty((M, L["K"]), dtype=torch.int8, device="cuda")
+        L["srow"] = torch.empty((M,), dtype=torch.float32, device="cuda")
+
+    def w4a8_static():
+        for L in layers:
+            pq.pq_rotate_quant8(L["x"], L["h"], L["sx"] * 7.0 / 127.0, out=L["xq8"])
+            pq.pq_w4a8_gemm(L["xq8"], L["wq"], L["sw"], L["sx"] * 7.0 / 127.0, out=L["out"])
+
+    def dynamic(bits):
+        def step():
+            for L in layers:
+                q = L["xq8"] if bits == 8 else L["xq"]
+                pq.pq_rotate_quant_dynamic(L["x"], L["h"], 1.0, bits, out=q, row_scale=L["srow"])
+                pq.pq_gemm_dynamic(q, bits, L["wq"], L["sw"], L["srow"], out=L["out"])
+        return step
+
+    res = {}
+    for name, step in (("w4a8_static", w4a8_static), ("w4a4_dynamic", dynamic(4)), ("w4a8_dynamic", dynamic(8))):
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / steps
+        res[name] = {"ms_per_step": round(dt * 1e3, 4), "TOPS": round(ops / dt / 1e12, 1)}
+    for L in layers:
+        del L["xq8"], L["srow"]
+    return res
 
 
 def run_fp16(torch, layers, steps, warmup):
@@ -173,6 +213,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-variants", action="store_true", help="skip the W4A8 / per-token dynamic variants of the step")
     ap.add_argument("--cpu-rows", type=int, default=1024)
     ap.add_argument("--profile-copy", action="store_true",
                     help="also run a plain 256 MiB elementwise copy (calibrates HBM counters under rocprofv3 --pmc)")
@@ -218,12 +259,17 @@ def main():
                    "tokens": M_PREFILL},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 1), "peak": INT8_PEAK_TOPS, "unit": "TOPS",
                      "frac": round(achieved / INT8_PEAK_TOPS, 4), "traffic": GEMM_HBM_TRAFFIC_BYTES,
-                     "kernel": "k_gemm_dma (five launches per step, averaged per launch)",
+                     "kernel": "k_gemm_dma (five launches per step, averaged per launch; HIP events around the "
+                               "launches of every %dth timed step)" % EVENT_EVERY,
                      "per_linear_TOPS": {k: round(gemm_ops[k] / v / 1e12, 1) for k, v in gemm_t.items()},
                      "per_linear_us": {k: round(v * 1e6, 1) for k, v in gemm_t.items()}},
         "fp16_gemm": {"ms_per_step": round(t_fp16 * 1e3, 4), "TFLOPS": round(ops / t_fp16 / 1e12, 1),
                       "speedup_pq_linear": round(t_fp16 / t_step, 3), "impl": "torch.matmul fp16"},
     }
+    if not args.no_variants:
+        result["variants"] = run_variants(torch, pq, layers, max(5, args.steps // 2), max(2, args.warmup // 2), ops)
+        result["variants"]["dynamic_over_static_w4a4"] = round(
+            result["variants"]["w4a4_dynamic"]["ms_per_step"] / result["ms_per_step"], 3)
     if not args.no_decode:
         result["decode"] = run_decode(torch, pq, layers, M=1)
     if not args.no_cpu:
