@@ -170,6 +170,28 @@ int pq_linear_dynamic(const void* x_f16, const void* wq_packed, const float* w_s
                       float clip, int32_t had_block, int32_t bits, int64_t M, int64_t N, int64_t K,
                       void* out_f16, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- attention side: online R3 and per-head static KV-cache quantization ------------------
+ * (App. B "Online Rotation": queries and keys are rotated after RoPE, head by head; Table 1 row
+ * O2: the KV cache is quantized per head with static steps.)
+ *
+ * x_f16 is [T, n_heads*head_dim] (a token's heads side by side); head_dim is a power of two in
+ * [32, 2048].  rotate != 0 applies the head_dim-point Hadamard rotation of pq_rotate_quant to
+ * every head (keys); rotate == 0 quantizes as is (values).  Codes are
+ *     q[t, h*head_dim + j] = clamp(round_half_even(y[t, h*head_dim + j] / head_scale[h]), -8, 7),
+ * packed canonically into xq_packed [T, n_heads*head_dim/2].  head_scale: device, [n_heads] fp32,
+ * 4-byte aligned, every entry finite and positive (not checked: it lives on the device).
+ * With rotate == 0 the codes equal the definition evaluated in double precision.
+ */
+int pq_rotate_quant_heads(const void* x_f16, int64_t T, int32_t n_heads, int32_t head_dim,
+                          int32_t rotate, const float* head_scale, void* xq_packed, void* stream);
+
+/* Rotation only (queries after RoPE): y = fp16(rotation of x) with blocks of had_block channels,
+ * had_block a power of two in [2, 16384] dividing K; K % 32 == 0.  y_f16: out [M,K] fp16; may not
+ * alias x_f16.  fp32 butterflies, one rounding to fp16.
+ */
+int pq_rotate_f16(const void* x_f16, int64_t M, int64_t K, int32_t had_block, void* y_f16,
+                  void* stream);
+
 #ifdef __cplusplus
 }
 #endif

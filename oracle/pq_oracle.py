@@ -36,6 +36,9 @@ What is defined here, and the passage of the paper each part follows:
   group_even_odd       storage order of the 8-bit codes (a permutation, no arithmetic): per
                        32 channels the 16 even ones, then the 16 odd ones.
   linear_bits          the whole path with the activation quantizer at `bits` bits.
+  quantize_heads       per-head static steps (Table 1 row O2, KV cache): the step of channel c is
+                       s[c // head_dim]; with rotate() at block = head_dim this is the online R3
+                       rotation of the keys followed by their cache quantizer (App. B).
 
 Pins (tests/test_oracle_pins.py): H.H^T = h.I in integers, involution, Parseval,
 one-hot and constant rows, block independence, a textbook in-place butterfly written in
@@ -101,6 +104,16 @@ def quantize_bits(y, s, bits: int) -> np.ndarray:
     t = np.asarray(y, dtype=np.float64) / np.float64(s)
     lo, hi = -(1 << (bits - 1)), (1 << (bits - 1)) - 1
     return np.clip(np.rint(t), lo, hi).astype(np.int8)
+
+
+def quantize_heads(y, s_heads, head_dim: int, bits: int = 4) -> np.ndarray:
+    """q[t, h*D + j] = clamp(round_half_even(y[t, h*D + j] / s_heads[h]), lo, hi), D = head_dim."""
+    y64 = np.asarray(y, dtype=np.float64)
+    T, C = y64.shape
+    s = np.repeat(np.asarray(s_heads, dtype=np.float64), head_dim)
+    assert s.shape == (C,)
+    lo, hi = -(1 << (bits - 1)), (1 << (bits - 1)) - 1
+    return np.clip(np.rint(y64 / s[None, :]), lo, hi).astype(np.int8)
 
 
 def quantize_dynamic(y, clip: float = 1.0, bits: int = 4):

@@ -37,6 +37,8 @@ SIGNATURES = {
     "pq_gemm_dynamic": (ctypes.c_int, [_vp, _i32, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp]),
     "pq_linear_dynamic_workspace_bytes": (_sz, [_i64, _i64, _i32]),
     "pq_linear_dynamic": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i32, _i32, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
+    "pq_rotate_quant_heads": (ctypes.c_int, [_vp, _i64, _i32, _i32, _i32, _vp, _vp, _vp]),
+    "pq_rotate_f16": (ctypes.c_int, [_vp, _i64, _i64, _i32, _vp, _vp]),
 }
 
 _lib = None
@@ -251,6 +253,29 @@ def pq_linear_dynamic(x, wq, w_scale, had_block, clip: float = 1.0, bits: int = 
     _check(lib().pq_linear_dynamic(_ptr(x), _ptr(wq), _ptr(w_scale), float(clip), int(had_block), int(bits), M, N, K,
                                    _ptr(out), _ptr(workspace), workspace.numel(), _stream()), "pq_linear_dynamic")
     return out, workspace
+
+
+def pq_rotate_quant_heads(x, n_heads: int, rotate: bool, head_scale, out=None):
+    """x fp16 [T, n_heads*head_dim], head_scale fp32 [n_heads] -> packed codes uint8 [T, n_heads*head_dim/2]."""
+    _dev(x, torch.float16, "x")
+    _dev(head_scale, torch.float32, "head_scale")
+    T, C = x.shape
+    if C % n_heads or head_scale.numel() != n_heads:
+        raise ValueError("shape mismatch")
+    if out is None:
+        out = torch.empty((T, C // 2), dtype=torch.uint8, device=x.device)
+    _check(lib().pq_rotate_quant_heads(_ptr(x), T, int(n_heads), C // n_heads, int(bool(rotate)), _ptr(head_scale),
+                                       _ptr(out), _stream()), "pq_rotate_quant_heads")
+    return out
+
+
+def pq_rotate_f16(x, had_block: int, out=None):
+    """x fp16 [M,K] -> its block-Hadamard rotation, fp16 [M,K]."""
+    _dev(x, torch.float16, "x")
+    if out is None:
+        out = torch.empty_like(x)
+    _check(lib().pq_rotate_f16(_ptr(x), x.shape[0], x.shape[1], int(had_block), _ptr(out), _stream()), "pq_rotate_f16")
+    return out
 
 
 def pq_set_gemm_variant(variant: int) -> int:

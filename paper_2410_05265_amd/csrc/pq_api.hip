@@ -229,6 +229,30 @@ int pq_linear_dynamic(const void* x_f16, const void* wq_packed, const float* w_s
     return pq_gemm_dynamic(workspace, bits, wq_packed, w_scale, row_scale, M, N, K, out_f16, nullptr, stream);
 }
 
+int pq_rotate_quant_heads(const void* x_f16, int64_t T, int32_t n_heads, int32_t head_dim, int32_t rotate,
+                          const float* head_scale, void* xq_packed, void* stream)
+{
+    if (T < 0 || n_heads <= 0 || head_dim < 32 || head_dim > 2048 || (head_dim & (head_dim - 1)) != 0)
+        return PQ_ERR_SHAPE;
+    if (!x_f16 || !head_scale || !xq_packed) return PQ_ERR_NULL;
+    if (!aligned16(x_f16) || !aligned16(xq_packed) || (reinterpret_cast<uintptr_t>(head_scale) & 3u))
+        return PQ_ERR_ALIGN;
+    if (T == 0) return PQ_OK;
+    return pq::launch_rotate_quant_heads(x_f16, T, (int64_t)n_heads * head_dim, head_dim, rotate ? head_dim : 1,
+                                         head_scale, xq_packed, static_cast<hipStream_t>(stream));
+}
+
+int pq_rotate_f16(const void* x_f16, int64_t M, int64_t K, int32_t had_block, void* y_f16, void* stream)
+{
+    if (M < 0 || K <= 0 || (K % 32) != 0) return PQ_ERR_SHAPE;
+    if (had_block < 2 || had_block > 16384 || (had_block & (had_block - 1)) != 0 || (K % had_block) != 0)
+        return PQ_ERR_SHAPE;
+    if (!x_f16 || !y_f16) return PQ_ERR_NULL;
+    if (!aligned16(x_f16) || !aligned16(y_f16)) return PQ_ERR_ALIGN;
+    if (M == 0) return PQ_OK;
+    return pq::launch_rotate_f16(x_f16, M, K, had_block, y_f16, static_cast<hipStream_t>(stream));
+}
+
 int pq_set_gemm_variant(int variant)
 {
     if (variant < 0 || variant > 4) return -1;

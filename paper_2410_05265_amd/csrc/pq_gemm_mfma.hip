@@ -362,8 +362,13 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
                     // lanes < 32 now hold channels 16 qp + (0..7), lanes >= 32 channels 16 qp + 8 + (0..7)
                     const int n = nb + 16 * qp + 8 * g;
                     if (m < M && n < N) {
+#ifdef PQ_EXP_NT
+                        const v4i val = {(int)s0[0], (int)s1[0], (int)s0[1], (int)s1[1]};
+                        __builtin_nontemporal_store(val, reinterpret_cast<v4i*>(out + (int64_t)m * N + n));
+#else
                         uint4 val = make_uint4(s0[0], s1[0], s0[1], s1[1]);
                         *reinterpret_cast<uint4*>(out + (int64_t)m * N + n) = val;
+#endif
                     }
                 }
             }
@@ -527,9 +532,9 @@ int launch_ragged(const void* xq, const void* wq, const float* sw, float sx, int
 struct TileCfg { int bm, bn; double eff; };
 // tile shapes the automatic choice considers, with measured relative efficiencies (a larger
 // wavefront tile needs fewer LDS reads and less expansion per matrix instruction)
-constexpr int kNumAuto = 4, kNumCfg = 6;
+constexpr int kNumAuto = 4, kNumCfg = 8;
 constexpr TileCfg kCfgs[kNumCfg] = {{256, 256, 1.00}, {256, 128, 0.85}, {128, 128, 0.72}, {256, 192, 0.95},
-                                    {256, 256, 1.0},  {256, 256, 1.0}};
+                                    {256, 256, 1.0},  {256, 256, 1.0}, {256, 128, 1.0}, {256, 128, 1.0}};
 
 // PQ_GEMM_TILE=0..5 forces a configuration (sweeps only): 0 256x256, 1 256x128, 2 128x128,
 // 3 256x192, 4 256x256 with 8 wavefronts, 5 256x256 with a 4-stage ring.
@@ -566,6 +571,8 @@ int launch_gemm_mfma(const void* xq, const void* wq, const float* sw, float sx, 
         case 2: return launch_dma<128, 128, 2, 2, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
         case 3: return launch_dma<256, 192, 2, 2, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
         case 4: return launch_dma<256, 256, 2, 4, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
+        case 6: return launch_dma<256, 128, 4, 2, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
+        case 7: return launch_dma<256, 128, 2, 4, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
         default: return launch_dma<256, 256, 2, 2, 4, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
     }
 }

@@ -167,13 +167,23 @@ __device__ __forceinline__ void quant_bytes8(const float* v, const float* raw, f
     odd4 = __builtin_amdgcn_perm(bits[3], bits[1], 0x0c0c0400u) | __builtin_amdgcn_perm(bits[7], bits[5], 0x04000c0cu);
 }
 
+// BITS = 16: no quantizer, fp16 out (global memory only).
 // BITS = 4: eight codes packed into dst_row[channel / 8].  BITS = 8: one byte per code; inside every
 // group of 32 channels the 16 even channels come first, then the 16 odd ones (the order in which
 // the matrix kernel consumes them), so a thread stores two dwords.
 template <int BITS, bool EXACT, typename DST>
 __device__ __forceinline__ void store_codes(const float* v, float mult, float step, DST dst_row, int64_t e0)
 {
-    if constexpr (BITS == 4) {
+    if constexpr (BITS == 16) {
+        // rotation only: the normalised values go out as fp16 (round to nearest even), 16 bytes
+        v4i o;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const __half2 h = __floats2half2_rn(v[2 * i] * mult, v[2 * i + 1] * mult);
+            o[i] = *reinterpret_cast<const int*>(&h);
+        }
+        *reinterpret_cast<v4i*>(&dst_row[e0 >> 1]) = o;
+    } else if constexpr (BITS == 4) {
         dst_row[e0 >> 3] = quant_pack8<EXACT>(v, v, mult, step);
     } else {
         uint32_t ev, od;
@@ -215,17 +225,33 @@ __device__ __forceinline__ void load_chunk(SRC x_row, int64_t K, int64_t chunk0,
     }
 }
 
-// The step of a static quantizer: known before the rotation.
+// The step of a per-tensor static quantizer: known before the rotation, the same everywhere.
 struct StaticStep {
     float mult, step;
     template <int NV>
-    __device__ __forceinline__ void operator()(const float (&)[NV], float& m, float& s) const { m = mult; s = step; }
+    __device__ __forceinline__ void prepare(const float (&)[NV]) {}
+    __device__ __forceinline__ void get(int64_t, float& m, float& s) const { m = mult; s = step; }
 };
 
-// `steps(values, mult, step)` is called once, after the rotation, with the thread's G * 8 rotated
-// (unnormalised) values, and sets the quantizer's reciprocal step and step: a static quantizer
-// returns constants, a dynamic one derives them from the values (and may synchronise the
-// workgroup; every thread calls it).
+// Per-head static steps (one per block of 2^log2d consecutive channels), read from device memory;
+// the reciprocal carries the 1/sqrt(h) of the rotation.
+struct HeadStep {
+    const float* scales;
+    int log2d;
+    double inv_sqrt_h;
+    template <int NV>
+    __device__ __forceinline__ void prepare(const float (&)[NV]) {}
+    __device__ __forceinline__ void get(int64_t e0, float& m, float& s) const
+    {
+        s = scales[e0 >> log2d];
+        m = (float)(inv_sqrt_h / (double)s);
+    }
+};
+
+// A step provider has `prepare(values)`, called once after the rotation by every thread of the
+// workgroup with its G * 8 rotated (unnormalised) values (a dynamic quantizer derives its step
+// there and may synchronise the workgroup), and `get(channel, mult, step)`, called per group of 8
+// channels, which sets the quantizer's reciprocal step and step for that group.
 template <int G, bool EXACT, int BITS = 4, typename DST, typename STEPS>
 __device__ __forceinline__ void rotate_quant_regs_with(const v4i (&raw)[G], const bool (&live)[G], int64_t chunk0,
                                                        int log2h, STEPS steps, DST dst_row, lds_f32_ptr xch,
@@ -250,11 +276,12 @@ __device__ __forceinline__ void rotate_quant_regs_with(const v4i (&raw)[G], cons
 
     if constexpr (EXACT) {
         // no rotation: the unrotated value doubles as the exact tie-break operand
-        steps(reinterpret_cast<float(&)[G * 8]>(v), mult, step);
+        steps.prepare(reinterpret_cast<float(&)[G * 8]>(v));
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             if (live[g]) {
                 const int64_t e0 = chunk0 + (int64_t)g * kChunk + tid * 8;
+                steps.get(e0, mult, step);
                 store_codes<BITS, true>(v[g], mult, step, dst_row, e0);
             }
         }
@@ -311,11 +338,12 @@ __device__ __forceinline__ void rotate_quant_regs_with(const v4i (&raw)[G], cons
                 }
             }
         }
-        steps(flat, mult, step);
+        steps.prepare(flat);
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             if (live[g]) {
                 const int64_t e0 = chunk0 + (int64_t)g * kChunk + tid * 8;
+                steps.get(e0, mult, step);
                 store_codes<BITS, false>(v[g], mult, step, dst_row, e0);
             }
         }

@@ -24,10 +24,9 @@ using rq::kThreads;
 // R rows of one chunk column per workgroup: all R loads of a thread are issued before the
 // arithmetic starts (the kernel has 2.5 bytes of traffic per element and little else to hide
 // latency with).
-template <int G, bool EXACT, int R, int BITS>
+template <int G, bool EXACT, int R, int BITS, typename STEPS>
 __global__ __launch_bounds__(kThreads) void k_rotate_quant(const __half* __restrict__ x, int64_t M, int64_t K,
-                                                          int log2h, float mult, float step,
-                                                          uint32_t* __restrict__ xq)
+                                                          int log2h, STEPS steps, uint32_t* __restrict__ xq)
 {
     __shared__ float xch[EXACT ? 1 : G * kChunk];
     const int64_t row0 = (int64_t)blockIdx.y * R;
@@ -42,44 +41,50 @@ __global__ __launch_bounds__(kThreads) void k_rotate_quant(const __half* __restr
     }
 #pragma unroll
     for (int r = 0; r < R; ++r)
-        rq::rotate_quant_regs<G, EXACT, BITS>(raw[r], live[r], chunk0, log2h, mult, step,
-                                        static_cast<uint32_t*>(xq + (row0 + r) * (BITS == 8 ? K >> 2 : K >> 3)),
-                                        (rq::lds_f32_ptr)xch,
-                                        threadIdx.x, row0 + r < M);
+        rq::rotate_quant_regs_with<G, EXACT, BITS>(
+            raw[r], live[r], chunk0, log2h, steps,
+            static_cast<uint32_t*>(xq + (row0 + r) * (BITS == 16 ? K >> 1 : (BITS == 8 ? K >> 2 : K >> 3))),
+            (rq::lds_f32_ptr)xch, threadIdx.x, row0 + r < M);
 }
 
-template <int BITS>
-int launch_rq(const __half* xp, int64_t M, int64_t K, int32_t h, float act_scale, uint32_t* op, hipStream_t st)
+// `steps` already carries the 1/sqrt(h) factor of the reciprocal step.
+template <int BITS, typename STEPS>
+int launch_rq(const __half* xp, int64_t M, int64_t K, int32_t h, STEPS steps, uint32_t* op, hipStream_t st)
 {
+    constexpr int kWordsShift = BITS == 16 ? 1 : (BITS == 8 ? 2 : 3);   // output dwords per row = K >> shift
     if (M > 65535) {
         // grid.y is limited to 65535 per launch
         for (int64_t m0 = 0; m0 < M; m0 += 65534) {
             const int64_t mm = (M - m0 < 65534) ? (M - m0) : 65534;
-            int rc = launch_rq<BITS>(xp + m0 * K, mm, K, h, act_scale, op + m0 * (BITS == 8 ? K / 4 : K / 8), st);
+            int rc = launch_rq<BITS, STEPS>(xp + m0 * K, mm, K, h, steps, op + m0 * (K >> kWordsShift), st);
             if (rc != PQ_OK) return rc;
         }
         return PQ_OK;
     }
     if (h <= 1) {
-        const float inv = (float)(1.0 / (double)act_scale);
         dim3 grid((unsigned)((K + kChunk - 1) / kChunk), (unsigned)((M + 1) / 2));
-        hipLaunchKernelGGL((k_rotate_quant<1, true, 2, BITS>), grid, dim3(kThreads), 0, st, xp, M, K, 0, inv, act_scale, op);
+        hipLaunchKernelGGL((k_rotate_quant<1, true, 2, BITS, STEPS>), grid, dim3(kThreads), 0, st, xp, M, K, 0, steps, op);
         return hip_status(hipGetLastError());
     }
     int log2h = 0;
     while ((1 << log2h) < h) ++log2h;
-    const float mult = (float)(1.0 / ((double)act_scale * sqrt((double)h)));
     const int G = h <= kChunk ? 1 : h / kChunk;
     const int R = G <= 2 ? 2 : 1;
     dim3 grid((unsigned)((K + (int64_t)G * kChunk - 1) / ((int64_t)G * kChunk)), (unsigned)((M + R - 1) / R));
     switch (G) {
-        case 1: hipLaunchKernelGGL((k_rotate_quant<1, false, 2, BITS>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, mult, act_scale, op); break;
-        case 2: hipLaunchKernelGGL((k_rotate_quant<2, false, 2, BITS>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, mult, act_scale, op); break;
-        case 4: hipLaunchKernelGGL((k_rotate_quant<4, false, 1, BITS>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, mult, act_scale, op); break;
-        case 8: hipLaunchKernelGGL((k_rotate_quant<8, false, 1, BITS>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, mult, act_scale, op); break;
+        case 1: hipLaunchKernelGGL((k_rotate_quant<1, false, 2, BITS, STEPS>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, steps, op); break;
+        case 2: hipLaunchKernelGGL((k_rotate_quant<2, false, 2, BITS, STEPS>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, steps, op); break;
+        case 4: hipLaunchKernelGGL((k_rotate_quant<4, false, 1, BITS, STEPS>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, steps, op); break;
+        case 8: hipLaunchKernelGGL((k_rotate_quant<8, false, 1, BITS, STEPS>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, steps, op); break;
         default: return PQ_ERR_UNSUPPORTED;
     }
     return hip_status(hipGetLastError());
+}
+
+inline rq::StaticStep static_step(float act_scale, int32_t h)
+{
+    const double r = h > 1 ? sqrt((double)h) : 1.0;
+    return rq::StaticStep{(float)(1.0 / ((double)act_scale * r)), act_scale};
 }
 
 // The step of a token: fp32(clip * max|y| / qmax) over the whole row held by the workgroup, with
@@ -91,9 +96,11 @@ struct DynamicStep {
     float* red;        // 4 floats of LDS
     float* step_out;   // this row's slot of row_scale
     int tid;
+    float mult_, step_;   // set by prepare()
     template <int NV>
-    __device__ __forceinline__ void operator()(const float (&v)[NV], float& mult, float& step) const
+    __device__ __forceinline__ void prepare(const float (&v)[NV])
     {
+        float step;
         float amax = 0.0f;   // dead groups hold zeros
 #pragma unroll
         for (int i = 0; i < NV; ++i) amax = fmaxf(amax, fabsf(v[i]));
@@ -109,9 +116,11 @@ struct DynamicStep {
         constexpr double qmax = BITS == 8 ? 127.0 : 7.0;
         step = (float)(((double)clip * ((double)amax * inv_sqrt_h)) / qmax);
         if (!(step > 0.0f)) step = 1.0f;
-        mult = (float)(inv_sqrt_h / (double)step);
+        step_ = step;
+        mult_ = (float)(inv_sqrt_h / (double)step);
         if (tid == 0) *step_out = step;
     }
+    __device__ __forceinline__ void get(int64_t, float& m, float& s) const { m = mult_; s = step_; }
 };
 
 // Per-token dynamic variant (Table 1 row O1): the step size of a row depends on that row's rotated
@@ -130,7 +139,7 @@ __global__ __launch_bounds__(kThreads) void k_rotate_quant_dyn(const __half* __r
     v4i raw[NC];
     bool live[NC];
     rq::load_chunk<NC>(static_cast<const __half*>(x + row * K), K, 0, tid, true, raw, live);
-    const DynamicStep<BITS> steps{inv_sqrt_h, clip, red, row_scale + row, tid};
+    const DynamicStep<BITS> steps{inv_sqrt_h, clip, red, row_scale + row, tid, 0.0f, 0.0f};
     uint32_t* dst_row = xq + row * (BITS == 8 ? K >> 2 : K >> 3);
     if (log2h == 0)
         rq::rotate_quant_regs_with<NC, true, BITS>(raw, live, 0, 0, steps, dst_row, (rq::lds_f32_ptr)xch_dyn, tid, true);
@@ -176,12 +185,28 @@ int launch_dyn(const __half* xp, int64_t M, int64_t K, int32_t h, float clip, ui
 
 int launch_rotate_quant(const void* x, int64_t M, int64_t K, int32_t h, float act_scale, void* xq, hipStream_t st)
 {
-    return launch_rq<4>(static_cast<const __half*>(x), M, K, h, act_scale, static_cast<uint32_t*>(xq), st);
+    return launch_rq<4>(static_cast<const __half*>(x), M, K, h, static_step(act_scale, h), static_cast<uint32_t*>(xq), st);
 }
 
 int launch_rotate_quant8(const void* x, int64_t M, int64_t K, int32_t h, float act_scale, void* xq8, hipStream_t st)
 {
-    return launch_rq<8>(static_cast<const __half*>(x), M, K, h, act_scale, static_cast<uint32_t*>(xq8), st);
+    return launch_rq<8>(static_cast<const __half*>(x), M, K, h, static_step(act_scale, h), static_cast<uint32_t*>(xq8), st);
+}
+
+// Per-head static steps (Table 1 row O2, KV cache): head = channel / head_dim.
+int launch_rotate_quant_heads(const void* x, int64_t M, int64_t K, int32_t head_dim, int32_t h, const float* head_scale,
+                              void* xq, hipStream_t st)
+{
+    int log2d = 0;
+    while ((1 << log2d) < head_dim) ++log2d;
+    const rq::HeadStep steps{head_scale, log2d, h > 1 ? 1.0 / sqrt((double)h) : 1.0};
+    return launch_rq<4>(static_cast<const __half*>(x), M, K, h, steps, static_cast<uint32_t*>(xq), st);
+}
+
+// Rotation only, fp16 out (queries after RoPE, which are rotated like the keys but not quantized).
+int launch_rotate_f16(const void* x, int64_t M, int64_t K, int32_t h, void* y, hipStream_t st)
+{
+    return launch_rq<16>(static_cast<const __half*>(x), M, K, h, static_step(1.0f, h), static_cast<uint32_t*>(y), st);
 }
 
 int launch_rotate_quant_dynamic(const void* x, int64_t M, int64_t K, int32_t h, float clip, int32_t bits, void* xq,

@@ -297,3 +297,23 @@ def test_linear_bits_eight_is_finer_than_four():
     assert err[8] < err[4] / 8          # 16x finer grid: the activation noise drops by about 16
     r4 = O.linear_bits(x, O.pack(wq), sw, O.calibrate_absmax(xc, h), h, 4)
     assert np.array_equal(r4["out"], O.linear(x, O.pack(wq), sw, O.calibrate_absmax(xc, h), h))
+
+
+# ------------------------------------------------------------------ per-head static steps
+def test_quantize_heads_reduces_to_scalar_quantizer_and_is_head_local():
+    rng = np.random.default_rng(21)
+    T, H, D = 5, 4, 32
+    y = rng.standard_normal((T, H * D)) * 3.0
+    s = np.array([0.5, 0.25, 1.0, 0.125], dtype=np.float32)
+    q = O.quantize_heads(y, s, D)
+    for h in range(H):                                   # each head is the scalar quantizer at its own step
+        assert np.array_equal(q[:, h * D:(h + 1) * D], O.quantize(y[:, h * D:(h + 1) * D], s[h]))
+    assert np.array_equal(O.quantize_heads(y, np.full(H, 0.5, dtype=np.float32), D), O.quantize(y, np.float32(0.5)))
+    s2 = s.copy()
+    s2[2] = 3.0                                          # changing one head's step moves only that head
+    q2 = O.quantize_heads(y, s2, D)
+    assert np.array_equal(q2[:, :2 * D], q[:, :2 * D]) and np.array_equal(q2[:, 3 * D:], q[:, 3 * D:])
+    assert not np.array_equal(q2[:, 2 * D:3 * D], q[:, 2 * D:3 * D])
+    # hand-computed values incl. a tie and saturation, two heads of two channels
+    got = O.quantize_heads(np.array([[1.0, -1.25, 1.0, 100.0]]), np.array([0.5, 2.0]), 2)
+    assert np.array_equal(got, [[2, -2, 0, 7]])          # -1.25/0.5 = -2.5 -> -2 (even); 1/2 = 0.5 -> 0 (even)
