@@ -192,6 +192,26 @@ int pq_rotate_quant_heads(const void* x_f16, int64_t T, int32_t n_heads, int32_t
 int pq_rotate_f16(const void* x_f16, int64_t M, int64_t K, int32_t had_block, void* y_f16,
                   void* stream);
 
+/* ---- calibration of the static per-tensor step on the device --------------------------------
+ * (Sec. 3 "Initialization of Quantization Parameters": max-min initialisation, and an MSE-based
+ * grid search over the quantization parameter for per-tensor static quantization.  The paper
+ * scores candidates by block outputs of the model; this library scores the tensor itself.)
+ * With y = rotation of x_cal as in pq_rotate_quant, qmax = 2^(bits-1) - 1 and, for i = 0..n_grid-1,
+ *     gamma_i = 1 - i (1 - gamma_min) / (n_grid - 1),   s_i = fp32(gamma_i * max|y| / qmax),
+ *     err_i   = sum over the tensor of (y - s_i * clamp(round_half_even(y / s_i), -qmax-1, qmax))^2,
+ * result (device, fp32, 4-byte aligned, 3 + n_grid entries) receives
+ *     [0] s of the arg-min of err (lowest index on a tie), [1] s_0 = max|y| / qmax (max-min
+ *     initialisation), [2] gamma of the arg-min, [3 + i] err_i.
+ * x_cal_f16: [T,K] fp16, K % 32 == 0, K <= 32768; bits 4 or 8; 2 <= n_grid <= 128;
+ * 0 < gamma_min < 1.  workspace: device, 256-byte aligned, pq_calibrate_workspace_bytes(T, n_grid).
+ * Sums are taken in a fixed order (fp32 within a row, fp64 over rows): results are reproducible.
+ * An all-zero tensor gives step 1.
+ */
+size_t pq_calibrate_workspace_bytes(int64_t T, int32_t n_grid);
+int pq_calibrate_static(const void* x_cal_f16, int64_t T, int64_t K, int32_t had_block, int32_t bits,
+                        int32_t n_grid, float gamma_min, float* result, void* workspace,
+                        size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -36,6 +36,9 @@ What is defined here, and the passage of the paper each part follows:
   group_even_odd       storage order of the 8-bit codes (a permutation, no arithmetic): per
                        32 channels the 16 even ones, then the 16 odd ones.
   linear_bits          the whole path with the activation quantizer at `bits` bits.
+  calibrate_mse        MSE-based grid search for the static per-tensor step (Sec. 3
+                       "Initialization of Quantization Parameters"); the paper scores candidates by
+                       model block outputs, this build by the tensor's own reconstruction error.
   quantize_heads       per-head static steps (Table 1 row O2, KV cache): the step of channel c is
                        s[c // head_dim]; with rotate() at block = head_dim this is the online R3
                        rotation of the keys followed by their cache quantizer (App. B).
@@ -241,6 +244,31 @@ def calibrate_absmax(x_cal, h: int, bits: int = 4) -> np.float32:
     """s_x = fp32(max |rotate(x_cal, h)| / qmax) over a calibration batch."""
     qmax = (1 << (bits - 1)) - 1
     return np.float32(np.max(np.abs(rotate(x_cal, h))) / qmax)
+
+
+def calibrate_mse(x_cal, h: int, bits: int = 4, n_grid: int = 50, gamma_min: float = 0.5):
+    """Grid search over the clipping factor: gamma_i = 1 - i (1 - gamma_min) / (n_grid - 1),
+    s_i = fp32(gamma_i * max|y| / qmax), err_i = sum (y - s_i * Q(y; s_i))^2 with y = rotate(x_cal, h).
+
+    Returns {"best": arg-min index (lowest on a tie), "s": s_best, "s_max": s_0, "gamma": gamma_best,
+    "errs": fp64 [n_grid], "steps": fp32 [n_grid]}.  An all-zero tensor gives steps of 1.
+    """
+    y = rotate(x_cal, h)
+    qmax = (1 << (bits - 1)) - 1
+    amax = np.max(np.abs(y))
+    steps = np.empty(n_grid, dtype=np.float32)
+    errs = np.empty(n_grid, dtype=np.float64)
+    gammas = np.empty(n_grid, dtype=np.float64)
+    for i in range(n_grid):
+        gammas[i] = 1.0 - i * (1.0 - np.float64(gamma_min)) / (n_grid - 1)
+        s = np.float32(gammas[i] * amax / qmax)
+        if not s > 0:
+            s = np.float32(1.0)
+        steps[i] = s
+        q = quantize_bits(y, s, bits).astype(np.float64)
+        errs[i] = np.sum((y - np.float64(s) * q) ** 2)
+    best = int(np.argmin(errs))
+    return {"best": best, "s": steps[best], "s_max": steps[0], "gamma": gammas[best], "errs": errs, "steps": steps}
 
 
 # ----------------------------------------------------------------------------- path

@@ -39,6 +39,8 @@ SIGNATURES = {
     "pq_linear_dynamic": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i32, _i32, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
     "pq_rotate_quant_heads": (ctypes.c_int, [_vp, _i64, _i32, _i32, _i32, _vp, _vp, _vp]),
     "pq_rotate_f16": (ctypes.c_int, [_vp, _i64, _i64, _i32, _vp, _vp]),
+    "pq_calibrate_workspace_bytes": (_sz, [_i64, _i32]),
+    "pq_calibrate_static": (ctypes.c_int, [_vp, _i64, _i64, _i32, _i32, _i32, _f32, _vp, _vp, _sz, _vp]),
 }
 
 _lib = None
@@ -276,6 +278,23 @@ def pq_rotate_f16(x, had_block: int, out=None):
         out = torch.empty_like(x)
     _check(lib().pq_rotate_f16(_ptr(x), x.shape[0], x.shape[1], int(had_block), _ptr(out), _stream()), "pq_rotate_f16")
     return out
+
+
+def pq_calibrate_workspace_bytes(T: int, n_grid: int) -> int:
+    return int(lib().pq_calibrate_workspace_bytes(T, int(n_grid)))
+
+
+def pq_calibrate_static(x_cal, had_block: int, bits: int = 4, n_grid: int = 50, gamma_min: float = 0.5):
+    """MSE grid search for the static step on the device.  Returns a device tensor fp32 [3 + n_grid]:
+    best step, max-min step, best gamma, then the squared error of every candidate."""
+    _dev(x_cal, torch.float16, "x_cal")
+    T, K = x_cal.shape
+    need = pq_calibrate_workspace_bytes(T, n_grid)
+    ws = torch.empty((max(need, 256),), dtype=torch.uint8, device=x_cal.device)
+    res = torch.empty((3 + n_grid,), dtype=torch.float32, device=x_cal.device)
+    _check(lib().pq_calibrate_static(_ptr(x_cal), T, K, int(had_block), int(bits), int(n_grid), float(gamma_min),
+                                     _ptr(res), _ptr(ws), ws.numel(), _stream()), "pq_calibrate_static")
+    return res
 
 
 def pq_set_gemm_variant(variant: int) -> int:

@@ -167,14 +167,16 @@ __device__ __forceinline__ void quant_bytes8(const float* v, const float* raw, f
     odd4 = __builtin_amdgcn_perm(bits[3], bits[1], 0x0c0c0400u) | __builtin_amdgcn_perm(bits[7], bits[5], 0x04000c0cu);
 }
 
-// BITS = 16: no quantizer, fp16 out (global memory only).
+// BITS = 0: no output.  BITS = 16: no quantizer, fp16 out (global memory only).
 // BITS = 4: eight codes packed into dst_row[channel / 8].  BITS = 8: one byte per code; inside every
 // group of 32 channels the 16 even channels come first, then the 16 odd ones (the order in which
 // the matrix kernel consumes them), so a thread stores two dwords.
 template <int BITS, bool EXACT, typename DST>
 __device__ __forceinline__ void store_codes(const float* v, float mult, float step, DST dst_row, int64_t e0)
 {
-    if constexpr (BITS == 16) {
+    if constexpr (BITS == 0) {
+        // nothing is stored: the caller took the values through its step provider
+    } else if constexpr (BITS == 16) {
         // rotation only: the normalised values go out as fp16 (round to nearest even), 16 bytes
         v4i o;
 #pragma unroll

@@ -45,6 +45,12 @@ def test_host_only_calls(b):
     assert L.pq_linear_workspace_bytes(3, 4096) == 6144
     assert L.pq_linear_workspace_bytes(2048, 14336) == 2048 * 7168
     assert L.pq_set_gemm_variant(9) == -1 and L.pq_set_gemm_variant(0) == 0
+    assert L.pq_linear_w4a8_workspace_bytes(3, 4096) == 12288
+    assert L.pq_linear_dynamic_workspace_bytes(3, 4096, 4) == 6144 + 256
+    assert L.pq_linear_dynamic_workspace_bytes(100, 128, 8) == 12800 + 512
+    assert L.pq_linear_dynamic_workspace_bytes(3, 4096, 5) == 0
+    assert L.pq_calibrate_workspace_bytes(256, 50) == 256 * 51 * 4
+    assert L.pq_calibrate_workspace_bytes(256, 1) == 0 and L.pq_calibrate_workspace_bytes(256, 129) == 0
 
 
 def test_argument_errors_launch_nothing(b):

@@ -317,3 +317,44 @@ def test_quantize_heads_reduces_to_scalar_quantizer_and_is_head_local():
     # hand-computed values incl. a tie and saturation, two heads of two channels
     got = O.quantize_heads(np.array([[1.0, -1.25, 1.0, 100.0]]), np.array([0.5, 2.0]), 2)
     assert np.array_equal(got, [[2, -2, 0, 7]])          # -1.25/0.5 = -2.5 -> -2 (even); 1/2 = 0.5 -> 0 (even)
+
+
+# ------------------------------------------------------------------ MSE grid search
+def test_calibrate_mse_brute_force_and_known_optima():
+    # brute force in plain Python on a tiny tensor
+    x = np.array([[0.3, -1.0, 0.55, 2.0], [0.0, 0.7, -0.2, 1.4]], dtype=np.float16)
+    r = O.calibrate_mse(x, 1, bits=4, n_grid=5, gamma_min=0.5)
+    amax = max(abs(float(v)) for v in x.ravel())
+    for i in range(5):
+        g = 1.0 - i * 0.5 / 4
+        s = float(np.float32(g * amax / 7))
+        assert r["steps"][i] == np.float32(s)
+        e = 0.0
+        for v in x.ravel():
+            t = float(v) / s
+            k = np.floor(t)
+            q = k if t - k < 0.5 else (k + 1 if t - k > 0.5 else (k if k % 2 == 0 else k + 1))
+            q = min(max(q, -8), 7)
+            e += (float(v) - s * q) ** 2
+        assert abs(r["errs"][i] - e) <= 1e-12 * max(e, 1.0)
+    assert r["best"] == int(np.argmin(r["errs"])) and r["s"] == r["steps"][r["best"]] and r["s_max"] == r["steps"][0]
+    # data on the grid of the unclipped step: zero error at gamma = 1, which therefore wins
+    k = np.arange(-7, 8, dtype=np.float64)
+    xg = np.tile(k * 0.25, (4, 2)).astype(np.float16)[:, :32 - 2]
+    xg = np.concatenate([xg, np.full((4, 2), 1.75)], axis=1).astype(np.float16)
+    rg = O.calibrate_mse(xg, 1, bits=4, n_grid=8, gamma_min=0.5)
+    assert rg["best"] == 0 and rg["errs"][0] == 0.0 and rg["s"] == np.float32(0.25)
+    # one huge outlier among small values: clipping it (gamma < 1) lowers the error
+    rng = np.random.default_rng(4)
+    xo = (rng.standard_normal((8, 64)) * 0.1).astype(np.float16)
+    xo[0, 0] = 4.0
+    ro = O.calibrate_mse(xo, 1, bits=4, n_grid=20, gamma_min=0.05)
+    assert ro["best"] > 0 and ro["errs"][ro["best"]] < ro["errs"][0]
+    # all zeros: every step is 1, every error 0, the first candidate wins
+    rz = O.calibrate_mse(np.zeros((2, 32), dtype=np.float16), 1)
+    assert rz["best"] == 0 and rz["s"] == 1.0 and not rz["errs"].any()
+    # rotation enters before the search: same result as searching the rotated tensor
+    xr = synth.activations(4, 256, seed=2)
+    a = O.calibrate_mse(xr, 64, n_grid=6)
+    yr = O.rotate(xr, 64)
+    assert a["s_max"] == np.float32(np.abs(yr).max() / 7)
