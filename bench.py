@@ -147,6 +147,76 @@ def run_fp16(torch, layers, steps, warmup):
     return (time.perf_counter() - t0) / steps
 
 
+def run_int8_ref(torch, layers, steps, warmup):
+    """The vendor's plain int8 GEMM on the same five shapes (torch._int_mm -> hipBLASLt): int8 x int8 ->
+    int32, nothing to unpack, no dequantising epilogue.  A reference point for what the INT8 matrix pipe
+    delivers at these sizes on this GPU."""
+    M = layers[0]["x"].shape[0]
+    ops_ab = [(torch.randint(-8, 8, (M, L["K"]), dtype=torch.int8, device="cuda"),
+               torch.randint(-8, 8, (L["N"], L["K"]), dtype=torch.int8, device="cuda").t()) for L in layers]
+    try:
+        for _ in range(warmup):
+            for a, b in ops_ab:
+                torch._int_mm(a, b)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            for a, b in ops_ab:
+                torch._int_mm(a, b)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+    except Exception:                                    # comparator only: absent on some builds
+        return None
+
+
+def graph_time(torch, fn, reps=3, inner=20):
+    """Microseconds per call of fn, captured `inner` times in a HIP graph (small kernels: the host is not the limit)."""
+    fn()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for _ in range(inner):
+            fn()
+    graph.replay()
+    torch.cuda.synchronize()
+    best = 1e30
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        best = min(best, e0.elapsed_time(e1) * 1e3 / inner)
+    return best
+
+
+def run_side_rows(torch, pq, synth, T):
+    """The rows next to the linear: head-wise rotation of queries, per-head static 4-bit quantization of
+    keys (rotated) and values, at Llama-3-8B's attention shape (32 query heads, 8 KV heads, head_dim 128);
+    and the on-device MSE grid search for a static step (256 x 14336 calibration batch, 50 candidates)."""
+    q = torch.from_numpy(synth.activations(T, 4096, 21)).cuda()
+    kv = torch.from_numpy(synth.activations(T, 1024, 22)).cuda()
+    hs = torch.full((8,), 0.5, dtype=torch.float32, device="cuda")
+    qo, ko = torch.empty_like(q), torch.empty((T, 512), dtype=torch.uint8, device="cuda")
+    res = {}
+    us = graph_time(torch, lambda: pq.pq_rotate_f16(q, 128, out=qo))
+    res["q_rotate_f16"] = {"us": round(us, 2), "GBps": round(T * 4096 * 4 / us / 1e3, 1)}
+    us = graph_time(torch, lambda: pq.pq_rotate_quant_heads(kv, 8, True, hs, out=ko))
+    res["k_rotate_quant_heads"] = {"us": round(us, 2), "GBps": round(T * 1024 * 2.5 / us / 1e3, 1)}
+    us = graph_time(torch, lambda: pq.pq_rotate_quant_heads(kv, 8, False, hs, out=ko))
+    res["v_quant_heads"] = {"us": round(us, 2), "GBps": round(T * 1024 * 2.5 / us / 1e3, 1)}
+    xc = torch.from_numpy(synth.calibration(14336, 4)).cuda()
+    t0 = time.perf_counter()
+    r = pq.pq_calibrate_static(xc, 128, 4, 50, 0.5)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    r = pq.pq_calibrate_static(xc, 128, 4, 50, 0.5)
+    torch.cuda.synchronize()
+    res["calibrate_static"] = {"us": round((time.perf_counter() - t1) * 1e6, 1), "tokens": 256, "K": 14336, "n_grid": 50,
+                               "gamma_best": round(float(r[2].item()), 3)}
+    return res
+
+
 def run_decode(torch, pq, layers, M=1, reps=3):
     """Batch-M decode through pq_linear with cold weights: enough distinct copies of each
     weight matrix that more than 1 GiB is touched before one is reused (the matrices fit
@@ -266,6 +336,13 @@ def main():
         "fp16_gemm": {"ms_per_step": round(t_fp16 * 1e3, 4), "TFLOPS": round(ops / t_fp16 / 1e12, 1),
                       "speedup_pq_linear": round(t_fp16 / t_step, 3), "impl": "torch.matmul fp16"},
     }
+    t_i8 = run_int8_ref(torch, layers, max(5, args.steps // 2), max(2, args.warmup // 2))
+    if t_i8 is not None:
+        result["int8_gemm"] = {"ms_per_step": round(t_i8 * 1e3, 4), "TOPS": round(ops / t_i8 / 1e12, 1),
+                               "pq_gemm_only_ms": round(sum(gemm_t.values()) * 1e3, 4),
+                               "impl": "torch._int_mm (hipBLASLt): int8 x int8 -> int32, no unpack, no epilogue"}
+    if not args.no_variants:
+        result["side_rows"] = run_side_rows(torch, pq, synth, M_PREFILL)
     if not args.no_variants:
         result["variants"] = run_variants(torch, pq, layers, max(5, args.steps // 2), max(2, args.warmup // 2), ops)
         result["variants"]["dynamic_over_static_w4a4"] = round(
