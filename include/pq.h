@@ -151,7 +151,8 @@ int pq_rotate_quant_dynamic(const void* x_f16, int64_t M, int64_t K, int32_t had
                             float clip, int32_t bits, void* xq, float* row_scale, void* stream);
 
 /* out[m,n] = fp16(acc[m,n] * (row_scale[m] * w_scale[n])), acc as in pq_w4a4_gemm (bits = 4) or
- * pq_w4a8_gemm (bits = 8).  Always the MFMA tiled kernel; K % 128 == 0, K <= 65536.
+ * pq_w4a8_gemm (bits = 8).  K % 128 == 0, K <= 65536.  bits = 4 and M <= 8 take the
+ * weight-streaming decode kernel, everything else the MFMA tiled kernel.
  */
 int pq_gemm_dynamic(const void* xq, int32_t bits, const void* wq_packed, const float* w_scale,
                     const float* row_scale, int64_t M, int64_t N, int64_t K,

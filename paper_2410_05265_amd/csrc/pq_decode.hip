@@ -66,7 +66,7 @@ __global__ __launch_bounds__(1024) void k_decode(const __half* __restrict__ x, c
                                                const uint8_t* __restrict__ wq, const float* __restrict__ sw,
                                                float sx, float mult, int log2h, int M, int N, int K,
                                                __half* __restrict__ out, int32_t* __restrict__ acc_out,
-                                               uint8_t* __restrict__ xq_out)
+                                               uint8_t* __restrict__ xq_out, const float* __restrict__ srow)
 {
     constexpr int G = MODE == 2 ? 2 : 1;
     extern __shared__ __align__(16) uint8_t smem[];
@@ -202,7 +202,7 @@ __global__ __launch_bounds__(1024) void k_decode(const __half* __restrict__ x, c
             if (m < M) {
                 const int n = gid * RPW + j;
                 if (acc_out) acc_out[(int64_t)m * N + n] = p[0];
-                if (out) out[(int64_t)m * N + n] = __float2half_rn((float)p[0] * (sx * sw[n]));
+                if (out) out[(int64_t)m * N + n] = __float2half_rn((float)p[0] * ((srow ? srow[m] : sx) * sw[n]));
             }
         }
     }
@@ -210,7 +210,8 @@ __global__ __launch_bounds__(1024) void k_decode(const __half* __restrict__ x, c
 
 template <int RPW, int CB, int MP, int MODE>
 int launch_one(const __half* x, const uint8_t* xq_in, const uint8_t* wq, const float* sw, float sx, float mult,
-               int log2h, int M, int N, int K, __half* out, int32_t* acc, uint8_t* xq_out, hipStream_t st)
+               int log2h, int M, int N, int K, __half* out, int32_t* acc, uint8_t* xq_out, hipStream_t st,
+               const float* srow)
 {
     constexpr int G = MODE == 2 ? 2 : 1;
     const size_t lds = (((size_t)MP * (K / 2) + 15) & ~(size_t)15) +
@@ -227,44 +228,44 @@ int launch_one(const __half* x, const uint8_t* xq_in, const uint8_t* wq, const f
     int grid = (groups + 15) / 16;
     grid = grid > 256 ? 256 : grid;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(1024), lds, st, x, xq_in, wq, sw, sx, mult, log2h, M, N, K, out,
-                       acc, xq_out);
+                       acc, xq_out, srow);
     return hip_status(hipGetLastError());
 }
 
 template <int RPW, int CB, int MP>
 int launch_mode(const __half* x, const uint8_t* xq_in, const uint8_t* wq, const float* sw, float sx, int h, int M,
-                int N, int K, __half* out, int32_t* acc, uint8_t* xq_out, hipStream_t st)
+                int N, int K, __half* out, int32_t* acc, uint8_t* xq_out, hipStream_t st, const float* srow)
 {
-    if constexpr (MP > 4 && RPW > 2) return PQ_ERR_UNSUPPORTED;   // never chosen: too many accumulators
-    else if (x == nullptr) return launch_one<RPW, CB, MP, 0>(x, xq_in, wq, sw, sx, 0.f, 0, M, N, K, out, acc, xq_out, st);
+    if constexpr (MP > 4 && (RPW > 2 || RPW * CB > 8)) return PQ_ERR_UNSUPPORTED;   // never chosen: too many registers
+    else if (x == nullptr) return launch_one<RPW, CB, MP, 0>(x, xq_in, wq, sw, sx, 0.f, 0, M, N, K, out, acc, xq_out, st, srow);
     if constexpr (MP > 4) return PQ_ERR_UNSUPPORTED;   // more than 4 tokens: codes only, no fused quantizer
     else if (h <= 1) {
         const float inv = (float)(1.0 / (double)sx);
-        return launch_one<RPW, CB, MP, 1>(x, xq_in, wq, sw, sx, inv, 0, M, N, K, out, acc, xq_out, st);
+        return launch_one<RPW, CB, MP, 1>(x, xq_in, wq, sw, sx, inv, 0, M, N, K, out, acc, xq_out, st, srow);
     }
     else {
         int log2h = 0;
         while ((1 << log2h) < h) ++log2h;
         const float mult = (float)(1.0 / ((double)sx * sqrt((double)h)));
         if (h <= kChunk)
-            return launch_one<RPW, CB, MP, 1>(x, xq_in, wq, sw, sx, mult, log2h, M, N, K, out, acc, xq_out, st);
-        return launch_one<RPW, CB, MP, 2>(x, xq_in, wq, sw, sx, mult, log2h, M, N, K, out, acc, xq_out, st);
+            return launch_one<RPW, CB, MP, 1>(x, xq_in, wq, sw, sx, mult, log2h, M, N, K, out, acc, xq_out, st, srow);
+        return launch_one<RPW, CB, MP, 2>(x, xq_in, wq, sw, sx, mult, log2h, M, N, K, out, acc, xq_out, st, srow);
     }
 }
 
 template <int MP>
 int launch_shape(int rpw, int cb, const __half* x, const uint8_t* xi, const uint8_t* w, const float* sw, float sx,
-                 int h, int m, int n, int k, __half* o, int32_t* acc, uint8_t* xo, hipStream_t st)
+                 int h, int m, int n, int k, __half* o, int32_t* acc, uint8_t* xo, hipStream_t st, const float* srow)
 {
     switch (rpw * 100 + cb) {
-        case 102: return launch_mode<1, 2, MP>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st);
-        case 202: return launch_mode<2, 2, MP>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st);
-        case 402: return launch_mode<4, 2, MP>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st);
-        case 104: return launch_mode<1, 4, MP>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st);
-        case 204: return launch_mode<2, 4, MP>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st);
-        case 404: return launch_mode<4, 4, MP>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st);
-        case 108: return launch_mode<1, 8, MP>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st);
-        default: return launch_mode<2, 8, MP>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st);
+        case 102: return launch_mode<1, 2, MP>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
+        case 202: return launch_mode<2, 2, MP>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
+        case 402: return launch_mode<4, 2, MP>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
+        case 104: return launch_mode<1, 4, MP>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
+        case 204: return launch_mode<2, 4, MP>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
+        case 404: return launch_mode<4, 4, MP>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
+        case 108: return launch_mode<1, 8, MP>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
+        default: return launch_mode<2, 8, MP>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
     }
 }
 
@@ -281,9 +282,11 @@ bool decode_supported(int64_t M, int64_t N, int64_t K, int32_t h)
 }
 
 // x_f16 != NULL: fused rotate + quantize (codes also written to xq_out if it is not NULL);
-// x_f16 == NULL: packed codes are read from xq_in.
+// x_f16 == NULL: packed codes are read from xq_in.  srow != NULL: per-token steps replace sx in the
+// epilogue (per-token dynamic quantization; only with given codes).
 int launch_decode(const void* x_f16, const void* xq_in, const void* wq, const float* sw, float sx, int32_t h,
-                  int64_t M, int64_t N, int64_t K, void* out, int32_t* acc, void* xq_out, hipStream_t st)
+                  int64_t M, int64_t N, int64_t K, void* out, int32_t* acc, void* xq_out, hipStream_t st,
+                  const float* srow)
 {
     if (!decode_supported(M, N, K, x_f16 ? h : -1)) return PQ_ERR_UNSUPPORTED;
     const __half* x = static_cast<const __half*>(x_f16);
@@ -299,11 +302,12 @@ int launch_decode(const void* x_f16, const void* xq_in, const void* wq, const fl
     while (rpw < 4 && rpw * 2 * cb <= 16 && N / rpw > 4096) rpw *= 2;
     if (rpw == 4 && cb == 8) rpw = 2;
     const int m = (int)M, n = (int)N, k = (int)K;
-    if (M == 1) return launch_shape<1>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st);
-    if (M <= 4) return launch_shape<4>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st);
+    if (M == 1) return launch_shape<1>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
+    if (M <= 4) return launch_shape<4>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
     // 5..8 tokens: fewer rows per wavefront so that the accumulators stay in registers
     if (rpw > 2) rpw = 2;
-    return launch_shape<8>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st);
+    if (cb == 8) rpw = 1;
+    return launch_shape<8>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
 }
 
 }  // namespace pq

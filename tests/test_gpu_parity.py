@@ -95,6 +95,16 @@ def test_forced_variants_agree(pq, variant, M):
     assert np.array_equal(host(acc).astype(np.int64), acc_ref)
 
 
+@pytest.mark.parametrize("M,N,K", [(6, 4608, 16384), (8, 8192, 28672), (5, 4096, 14336), (7, 256, 32768)])
+def test_decode_five_to_eight_tokens_long_rows(pq, M, N, K):
+    xq, wq = synth.random_packed(M, K, seed=13), synth.random_packed(N, K, seed=14, stream=7)
+    sw = synth.random_scales(N, seed=15)
+    acc_ref = O.gemm_i64(O.unpack(xq), O.unpack(wq))
+    out, acc = pq.pq_w4a4_gemm(dev(xq), dev(wq), dev(sw), 0.25, want_out=True, want_acc=True)
+    assert np.array_equal(host(acc).astype(np.int64), acc_ref)
+    assert ulp_diff(host(out), O.epilogue(acc_ref, np.float32(0.25), sw)).max() <= 1
+
+
 def test_product_extreme_codes(pq):
     K = 28672
     for M in (2, 40):

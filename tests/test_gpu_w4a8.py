@@ -138,6 +138,10 @@ def test_w4a8_argument_errors(pq):
         pq.pq_w4a8_gemm(q, w, sw, 1.0)
     assert e.value.status == 2
     buf = torch.full((2, 128), 5, dtype=torch.int8, device="cuda")
-    pq.pq_rotate_quant8(dev(np.ones((2, 128), dtype=np.float16))[:0], 1, 1.0, out=buf[:0])   # M = 0: no-op
+    x2 = dev(np.ones((2, 128), dtype=np.float16))
+    import ctypes
+    rc = pq.lib().pq_rotate_quant8(ctypes.c_void_p(x2.data_ptr()), 0, 128, 1, 1.0, ctypes.c_void_p(buf.data_ptr()),
+                                   None)                                                  # M = 0: no-op
+    assert rc == 0
     torch.cuda.synchronize()
     assert bool((buf == 5).all())
