@@ -193,7 +193,9 @@ def graph_time(torch, fn, reps=3, inner=20):
 def run_side_rows(torch, pq, synth, T):
     """The rows next to the linear: head-wise rotation of queries, per-head static 4-bit quantization of
     keys (rotated) and values, at Llama-3-8B's attention shape (32 query heads, 8 KV heads, head_dim 128);
-    and the on-device MSE grid search for a static step (256 x 14336 calibration batch, 50 candidates)."""
+    the fused producers (silu(gate) * up -> rotate -> quantize for down_proj, RMS norm -> quantize for a
+    4096-channel input); and the on-device MSE grid search for a static step (256 x 14336 calibration
+    batch, 50 candidates)."""
     q = torch.from_numpy(synth.activations(T, 4096, 21)).cuda()
     kv = torch.from_numpy(synth.activations(T, 1024, 22)).cuda()
     hs = torch.full((8,), 0.5, dtype=torch.float32, device="cuda")
@@ -205,6 +207,15 @@ def run_side_rows(torch, pq, synth, T):
     res["k_rotate_quant_heads"] = {"us": round(us, 2), "GBps": round(T * 1024 * 2.5 / us / 1e3, 1)}
     us = graph_time(torch, lambda: pq.pq_rotate_quant_heads(kv, 8, False, hs, out=ko))
     res["v_quant_heads"] = {"us": round(us, 2), "GBps": round(T * 1024 * 2.5 / us / 1e3, 1)}
+    g = torch.from_numpy(synth.activations(T, 14336, 23)).cuda()
+    u = torch.from_numpy(synth.activations(T, 14336, 24)).cuda()
+    do = torch.empty((T, 7168), dtype=torch.uint8, device="cuda")
+    us = graph_time(torch, lambda: pq.pq_silu_mul_rotate_quant(g, u, 128, 0.4, out=do), inner=8)
+    res["silu_mul_rotate_quant"] = {"us": round(us, 2), "GBps": round(T * 14336 * 4.5 / us / 1e3, 1)}
+    ko2 = torch.empty((T, 2048), dtype=torch.uint8, device="cuda")
+    us = graph_time(torch, lambda: pq.pq_rmsnorm_quant(q, 1e-5, 0.4, out=ko2))
+    res["rmsnorm_quant"] = {"us": round(us, 2), "GBps": round(T * 4096 * 2.5 / us / 1e3, 1)}
+    del g, u, do
     xc = torch.from_numpy(synth.calibration(14336, 4)).cuda()
     t0 = time.perf_counter()
     r = pq.pq_calibrate_static(xc, 128, 4, 50, 0.5)

@@ -193,6 +193,25 @@ int pq_rotate_quant_heads(const void* x_f16, int64_t T, int32_t n_heads, int32_t
 int pq_rotate_f16(const void* x_f16, int64_t M, int64_t K, int32_t had_block, void* y_f16,
                   void* stream);
 
+/* ---- producer fusion (Sec. 3 "Dynamic and Static": static steps make operator fusion feasible) --
+ * The elementwise producer of a linear's input is evaluated in the quantizer kernel, so the fp16
+ * intermediate never exists in memory.
+ *
+ * down_proj: x = silu(gate) * up elementwise (silu(g) = g / (1 + exp(-g)), fp32, no intermediate
+ * rounding to fp16), then rotation + static 4-bit quantization exactly as pq_rotate_quant.
+ * gate_f16, up_f16: [M,K] fp16.
+ */
+int pq_silu_mul_rotate_quant(const void* gate_f16, const void* up_f16, int64_t M, int64_t K,
+                             int32_t had_block, float act_scale, void* xq_packed, void* stream);
+
+/* q/k/v/gate/up_proj: y[m,:] = x[m,:] / sqrt(mean_k x[m,k]^2 + eps) (RMS normalisation; its learned
+ * weight is folded into the next linear, as the absorbed rotation requires), then static 4-bit
+ * quantization of y with step act_scale, no rotation.  K % 32 == 0, K <= 32768 (a workgroup holds
+ * a row); eps >= 0.
+ */
+int pq_rmsnorm_quant(const void* x_f16, int64_t M, int64_t K, float eps, float act_scale,
+                     void* xq_packed, void* stream);
+
 /* ---- calibration of the static per-tensor step on the device --------------------------------
  * (Sec. 3 "Initialization of Quantization Parameters": max-min initialisation, and an MSE-based
  * grid search over the quantization parameter for per-tensor static quantization.  The paper

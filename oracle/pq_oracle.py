@@ -36,6 +36,8 @@ What is defined here, and the passage of the paper each part follows:
   group_even_odd       storage order of the 8-bit codes (a permutation, no arithmetic): per
                        32 channels the 16 even ones, then the 16 odd ones.
   linear_bits          the whole path with the activation quantizer at `bits` bits.
+  silu_mul, rmsnorm    the elementwise producers that static quantization allows to fuse into the
+                       quantizer (Sec. 3 "Dynamic and Static"): silu(g) * u and x / rms(x), fp64.
   calibrate_mse        MSE-based grid search for the static per-tensor step (Sec. 3
                        "Initialization of Quantization Parameters"); the paper scores candidates by
                        model block outputs, this build by the tensor's own reconstruction error.
@@ -244,6 +246,18 @@ def calibrate_absmax(x_cal, h: int, bits: int = 4) -> np.float32:
     """s_x = fp32(max |rotate(x_cal, h)| / qmax) over a calibration batch."""
     qmax = (1 << (bits - 1)) - 1
     return np.float32(np.max(np.abs(rotate(x_cal, h))) / qmax)
+
+
+def silu_mul(gate, up) -> np.ndarray:
+    """silu(gate) * up elementwise, silu(g) = g / (1 + exp(-g)), fp64 (no rounding to fp16)."""
+    g = np.asarray(gate, dtype=np.float64)
+    return g / (1.0 + np.exp(-g)) * np.asarray(up, dtype=np.float64)
+
+
+def rmsnorm(x, eps: float) -> np.ndarray:
+    """y[m, :] = x[m, :] / sqrt(mean_k x[m, k]^2 + eps), fp64, no learned weight."""
+    x64 = np.asarray(x, dtype=np.float64)
+    return x64 / np.sqrt(np.mean(x64 * x64, axis=1, keepdims=True) + np.float64(eps))
 
 
 def calibrate_mse(x_cal, h: int, bits: int = 4, n_grid: int = 50, gamma_min: float = 0.5):

@@ -39,6 +39,8 @@ SIGNATURES = {
     "pq_linear_dynamic": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i32, _i32, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
     "pq_rotate_quant_heads": (ctypes.c_int, [_vp, _i64, _i32, _i32, _i32, _vp, _vp, _vp]),
     "pq_rotate_f16": (ctypes.c_int, [_vp, _i64, _i64, _i32, _vp, _vp]),
+    "pq_silu_mul_rotate_quant": (ctypes.c_int, [_vp, _vp, _i64, _i64, _i32, _f32, _vp, _vp]),
+    "pq_rmsnorm_quant": (ctypes.c_int, [_vp, _i64, _i64, _f32, _f32, _vp, _vp]),
     "pq_calibrate_workspace_bytes": (_sz, [_i64, _i32]),
     "pq_calibrate_static": (ctypes.c_int, [_vp, _i64, _i64, _i32, _i32, _i32, _f32, _vp, _vp, _sz, _vp]),
 }
@@ -277,6 +279,31 @@ def pq_rotate_f16(x, had_block: int, out=None):
     if out is None:
         out = torch.empty_like(x)
     _check(lib().pq_rotate_f16(_ptr(x), x.shape[0], x.shape[1], int(had_block), _ptr(out), _stream()), "pq_rotate_f16")
+    return out
+
+
+def pq_silu_mul_rotate_quant(gate, up, had_block: int, act_scale: float, out=None):
+    """gate, up fp16 [M,K] -> packed codes uint8 [M,K/2] of rotate(silu(gate) * up)."""
+    _dev(gate, torch.float16, "gate")
+    _dev(up, torch.float16, "up")
+    if gate.shape != up.shape:
+        raise ValueError("shape mismatch")
+    M, K = gate.shape
+    if out is None:
+        out = torch.empty((M, K // 2), dtype=torch.uint8, device=gate.device)
+    _check(lib().pq_silu_mul_rotate_quant(_ptr(gate), _ptr(up), M, K, int(had_block), float(act_scale), _ptr(out),
+                                          _stream()), "pq_silu_mul_rotate_quant")
+    return out
+
+
+def pq_rmsnorm_quant(x, eps: float, act_scale: float, out=None):
+    """x fp16 [M,K] -> packed codes uint8 [M,K/2] of x / rms(x)."""
+    _dev(x, torch.float16, "x")
+    M, K = x.shape
+    if out is None:
+        out = torch.empty((M, K // 2), dtype=torch.uint8, device=x.device)
+    _check(lib().pq_rmsnorm_quant(_ptr(x), M, K, float(eps), float(act_scale), _ptr(out), _stream()),
+           "pq_rmsnorm_quant")
     return out
 
 

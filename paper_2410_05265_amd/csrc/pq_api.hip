@@ -257,6 +257,32 @@ int pq_rotate_f16(const void* x_f16, int64_t M, int64_t K, int32_t had_block, vo
     return pq::launch_rotate_f16(x_f16, M, K, had_block, y_f16, static_cast<hipStream_t>(stream));
 }
 
+int pq_silu_mul_rotate_quant(const void* gate_f16, const void* up_f16, int64_t M, int64_t K, int32_t had_block,
+                             float act_scale, void* xq_packed, void* stream)
+{
+    if (M < 0 || K <= 0 || (K % 32) != 0) return PQ_ERR_SHAPE;
+    if (had_block < 0 || had_block > 16384) return PQ_ERR_SHAPE;
+    if (had_block > 1 && ((had_block & (had_block - 1)) != 0 || (K % had_block) != 0)) return PQ_ERR_SHAPE;
+    if (!gate_f16 || !up_f16 || !xq_packed) return PQ_ERR_NULL;
+    if (!aligned16(gate_f16) || !aligned16(up_f16) || !aligned16(xq_packed)) return PQ_ERR_ALIGN;
+    if (!good_scale(act_scale)) return PQ_ERR_SCALE;
+    if (M == 0) return PQ_OK;
+    return pq::launch_silu_mul_rotate_quant(gate_f16, up_f16, M, K, had_block, act_scale, xq_packed,
+                                            static_cast<hipStream_t>(stream));
+}
+
+int pq_rmsnorm_quant(const void* x_f16, int64_t M, int64_t K, float eps, float act_scale, void* xq_packed,
+                     void* stream)
+{
+    if (M < 0 || K <= 0 || (K % 32) != 0) return PQ_ERR_SHAPE;
+    if (!x_f16 || !xq_packed) return PQ_ERR_NULL;
+    if (!aligned16(x_f16) || !aligned16(xq_packed)) return PQ_ERR_ALIGN;
+    if (!good_scale(act_scale) || !(isfinite(eps) && eps >= 0.0f)) return PQ_ERR_SCALE;
+    if (K > 32768) return PQ_ERR_UNSUPPORTED;
+    if (M == 0) return PQ_OK;
+    return pq::launch_rmsnorm_quant(x_f16, M, K, eps, act_scale, xq_packed, static_cast<hipStream_t>(stream));
+}
+
 size_t pq_calibrate_workspace_bytes(int64_t T, int32_t n_grid)
 {
     if (T <= 0 || n_grid < 2 || n_grid > pq::max_calibration_grid()) return 0;

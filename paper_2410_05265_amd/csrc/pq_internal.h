@@ -22,6 +22,10 @@ int launch_gemm_dynamic(const void* xq, int32_t bits, const void* wq, const floa
 int launch_rotate_quant_heads(const void* x, int64_t M, int64_t K, int32_t head_dim, int32_t h,
                               const float* head_scale, void* xq, hipStream_t st);
 int launch_rotate_f16(const void* x, int64_t M, int64_t K, int32_t h, void* y, hipStream_t st);
+int launch_silu_mul_rotate_quant(const void* gate, const void* up, int64_t M, int64_t K, int32_t h,
+                                 float act_scale, void* xq, hipStream_t st);
+int launch_rmsnorm_quant(const void* x, int64_t M, int64_t K, float eps, float act_scale, void* xq,
+                         hipStream_t st);
 int max_calibration_grid();
 int launch_calibrate(const void* x, int64_t T, int64_t K, int32_t h, int32_t bits, int32_t n_grid, float gamma_min,
                      float* result, float* ws, hipStream_t st);

@@ -254,10 +254,36 @@ struct HeadStep {
 // workgroup with its G * 8 rotated (unnormalised) values (a dynamic quantizer derives its step
 // there and may synchronise the workgroup), and `get(channel, mult, step)`, called per group of 8
 // channels, which sets the quantizer's reciprocal step and step for that group.
-template <int G, bool EXACT, int BITS = 4, typename DST, typename STEPS>
+//
+// An input transform `xf.apply(g, values)` may rewrite the 8 fp32 values of group g right after
+// they are converted from fp16 (before the rotation): the identity for a plain input, or the
+// fusion of an elementwise producer (see SiluGate).
+struct NoTransform {
+    __device__ __forceinline__ void apply(int, float (&)[8]) const {}
+};
+
+// Producer fusion for down_proj: the layer input is silu(gate) * up, elementwise.  The values
+// passed in are the gate's; the matching 16 bytes of `up` were loaded by the caller.
+struct SiluGate {
+    const v4i* up_raw;   // G loaded groups of the calling thread
+    __device__ __forceinline__ void apply(int g, float (&v)[8]) const
+    {
+        const v4i u = up_raw[g];
+        const __half2* h2 = reinterpret_cast<const __half2*>(&u);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float2 f = __half22float2(h2[i]);
+            // hardware exp2 and reciprocal (about 1 ulp each): far inside the quantizer's tie tolerance
+            v[2 * i] = v[2 * i] * __builtin_amdgcn_rcpf(1.0f + __expf(-v[2 * i])) * f.x;
+            v[2 * i + 1] = v[2 * i + 1] * __builtin_amdgcn_rcpf(1.0f + __expf(-v[2 * i + 1])) * f.y;
+        }
+    }
+};
+
+template <int G, bool EXACT, int BITS = 4, typename DST, typename STEPS, typename XF = NoTransform>
 __device__ __forceinline__ void rotate_quant_regs_with(const v4i (&raw)[G], const bool (&live)[G], int64_t chunk0,
                                                        int log2h, STEPS steps, DST dst_row, lds_f32_ptr xch,
-                                                       int tid, bool active)
+                                                       int tid, bool active, XF xf = XF{})
 {
     float mult, step;
     const int lane = tid & 63;
@@ -274,6 +300,7 @@ __device__ __forceinline__ void rotate_quant_regs_with(const v4i (&raw)[G], cons
             v[g][2 * i] = f.x;
             v[g][2 * i + 1] = f.y;
         }
+        xf.apply(g, v[g]);
     }
 
     if constexpr (EXACT) {

@@ -47,6 +47,35 @@ __global__ __launch_bounds__(kThreads) void k_rotate_quant(const __half* __restr
             (rq::lds_f32_ptr)xch, threadIdx.x, row0 + r < M);
 }
 
+// Producer fusion for down_proj (Sec. 3: static quantization makes operator fusion feasible): the
+// layer input silu(gate) * up is formed in registers from the two projections' fp16 outputs and
+// goes straight into rotation + quantizer, so the intermediate never exists in memory.
+template <int G, int R>
+__global__ __launch_bounds__(kThreads) void k_silu_mul_rotate_quant(const __half* __restrict__ gate,
+                                                                   const __half* __restrict__ up, int64_t M,
+                                                                   int64_t K, int log2h, rq::StaticStep steps,
+                                                                   uint32_t* __restrict__ xq)
+{
+    __shared__ float xch[G * kChunk];
+    const int64_t row0 = (int64_t)blockIdx.y * R;
+    const int64_t chunk0 = (int64_t)blockIdx.x * (G * kChunk);
+    v4i rawg[R][G], rawu[R][G];
+    bool live[R][G];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const bool in = row0 + r < M;
+        const int64_t row = in ? row0 + r : 0;
+        rq::load_chunk<G>(static_cast<const __half*>(gate + row * K), K, chunk0, threadIdx.x, in, rawg[r], live[r]);
+        rq::load_chunk<G>(static_cast<const __half*>(up + row * K), K, chunk0, threadIdx.x, in, rawu[r], live[r]);
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+        rq::rotate_quant_regs_with<G, false, 4>(rawg[r], live[r], chunk0, log2h, steps,
+                                                static_cast<uint32_t*>(xq + (row0 + r) * (K >> 3)),
+                                                (rq::lds_f32_ptr)xch, threadIdx.x, row0 + r < M,
+                                                rq::SiluGate{rawu[r]});
+}
+
 // `steps` already carries the 1/sqrt(h) factor of the reciprocal step.
 template <int BITS, typename STEPS>
 int launch_rq(const __half* xp, int64_t M, int64_t K, int32_t h, STEPS steps, uint32_t* op, hipStream_t st)
@@ -148,6 +177,51 @@ __global__ __launch_bounds__(kThreads) void k_rotate_quant_dyn(const __half* __r
                                                     true);
 }
 
+// Producer fusion for qkv / gate / up: RMS normalisation (its learned weight folded into the next
+// linear, as rotation absorption requires) followed by the static quantizer.  The step of the
+// normalised row is static; what the row supplies is 1 / rms.
+struct NormStep {
+    double inv_step;   // 1 / s
+    double inv_k;      // 1 / K
+    float eps, step;
+    float* red;        // 4 floats of LDS
+    int tid;
+    float mult_;
+    template <int NV>
+    __device__ __forceinline__ void prepare(const float (&v)[NV])
+    {
+        float ss = 0.0f;   // dead groups hold zeros
+#pragma unroll
+        for (int i = 0; i < NV; ++i) ss = fmaf(v[i], v[i], ss);
+        ss += rq::lane_xor<0>(ss);
+        ss += rq::lane_xor<1>(ss);
+        ss += rq::lane_xor<2>(ss);
+        ss += rq::lane_xor<3>(ss);
+        ss += rq::lane_xor<4>(ss);
+        ss += rq::lane_xor<5>(ss);
+        if ((tid & 63) == 0) red[tid >> 6] = ss;
+        __syncthreads();
+        const double total = ((double)red[0] + (double)red[1]) + ((double)red[2] + (double)red[3]);
+        mult_ = (float)(inv_step / sqrt(total * inv_k + (double)eps));
+    }
+    __device__ __forceinline__ void get(int64_t, float& m, float& s) const { m = mult_; s = step; }
+};
+
+template <int NC>
+__global__ __launch_bounds__(kThreads) void k_rmsnorm_quant(const __half* __restrict__ x, int64_t K, double inv_step,
+                                                           float eps, float step, uint32_t* __restrict__ xq)
+{
+    __shared__ float red[4];
+    const int tid = threadIdx.x;
+    const int64_t row = blockIdx.x;
+    v4i raw[NC];
+    bool live[NC];
+    rq::load_chunk<NC>(static_cast<const __half*>(x + row * K), K, 0, tid, true, raw, live);
+    const NormStep steps{inv_step, 1.0 / (double)K, eps, step, red, tid, 0.0f};
+    rq::rotate_quant_regs_with<NC, false, 4>(raw, live, 0, 0, steps, static_cast<uint32_t*>(xq + row * (K >> 3)),
+                                             (rq::lds_f32_ptr) nullptr, tid, true);
+}
+
 template <int NC, int BITS>
 int launch_dyn_nc(const __half* xp, int64_t M, int64_t K, int log2h, double inv_sqrt_h, float clip, uint32_t* op,
                   float* row_scale, hipStream_t st)
@@ -215,6 +289,51 @@ int launch_rotate_quant_dynamic(const void* x, int64_t M, int64_t K, int32_t h, 
     if (bits == 8)
         return launch_dyn<8>(static_cast<const __half*>(x), M, K, h, clip, static_cast<uint32_t*>(xq), row_scale, st);
     return launch_dyn<4>(static_cast<const __half*>(x), M, K, h, clip, static_cast<uint32_t*>(xq), row_scale, st);
+}
+
+int launch_silu_mul_rotate_quant(const void* gate, const void* up, int64_t M, int64_t K, int32_t h, float act_scale,
+                                 void* xq, hipStream_t st)
+{
+    const __half* g = static_cast<const __half*>(gate);
+    const __half* u = static_cast<const __half*>(up);
+    uint32_t* op = static_cast<uint32_t*>(xq);
+    for (int64_t m0 = 0; m0 < M; m0 += 65534) {   // grid.y is limited to 65535 per launch
+        const int64_t mm = (M - m0 < 65534) ? (M - m0) : 65534;
+        int log2h = 0;
+        while ((1 << log2h) < h) ++log2h;
+        const int G = h <= kChunk ? 1 : h / kChunk;
+        const rq::StaticStep steps = static_step(act_scale, h);
+        dim3 grid((unsigned)((K + (int64_t)G * kChunk - 1) / ((int64_t)G * kChunk)), (unsigned)((mm + (G <= 2 ? 1 : 0)) / (G <= 2 ? 2 : 1)));
+        const __half* gp = g + m0 * K;
+        const __half* upp = u + m0 * K;
+        uint32_t* o = op + m0 * (K >> 3);
+        switch (G) {
+            case 1: hipLaunchKernelGGL((k_silu_mul_rotate_quant<1, 2>), grid, dim3(kThreads), 0, st, gp, upp, mm, K, log2h, steps, o); break;
+            case 2: hipLaunchKernelGGL((k_silu_mul_rotate_quant<2, 2>), grid, dim3(kThreads), 0, st, gp, upp, mm, K, log2h, steps, o); break;
+            case 4: hipLaunchKernelGGL((k_silu_mul_rotate_quant<4, 1>), grid, dim3(kThreads), 0, st, gp, upp, mm, K, log2h, steps, o); break;
+            case 8: hipLaunchKernelGGL((k_silu_mul_rotate_quant<8, 1>), grid, dim3(kThreads), 0, st, gp, upp, mm, K, log2h, steps, o); break;
+            default: return PQ_ERR_UNSUPPORTED;
+        }
+        const int rc = hip_status(hipGetLastError());
+        if (rc != PQ_OK) return rc;
+    }
+    return PQ_OK;
+}
+
+int launch_rmsnorm_quant(const void* x, int64_t M, int64_t K, float eps, float act_scale, void* xq, hipStream_t st)
+{
+    if (K > 16 * kChunk || M > 0x7fffffff) return PQ_ERR_UNSUPPORTED;
+    const __half* xp = static_cast<const __half*>(x);
+    uint32_t* op = static_cast<uint32_t*>(xq);
+    const double inv_step = 1.0 / (double)act_scale;
+    const int nc = (int)((K + kChunk - 1) / kChunk);
+    const dim3 grid((unsigned)M), block(kThreads);
+    if (nc <= 1) hipLaunchKernelGGL(k_rmsnorm_quant<1>, grid, block, 0, st, xp, K, inv_step, eps, act_scale, op);
+    else if (nc <= 2) hipLaunchKernelGGL(k_rmsnorm_quant<2>, grid, block, 0, st, xp, K, inv_step, eps, act_scale, op);
+    else if (nc <= 4) hipLaunchKernelGGL(k_rmsnorm_quant<4>, grid, block, 0, st, xp, K, inv_step, eps, act_scale, op);
+    else if (nc <= 8) hipLaunchKernelGGL(k_rmsnorm_quant<8>, grid, block, 0, st, xp, K, inv_step, eps, act_scale, op);
+    else hipLaunchKernelGGL(k_rmsnorm_quant<16>, grid, block, 0, st, xp, K, inv_step, eps, act_scale, op);
+    return hip_status(hipGetLastError());
 }
 
 }  // namespace pq

@@ -358,3 +358,26 @@ def test_calibrate_mse_brute_force_and_known_optima():
     a = O.calibrate_mse(xr, 64, n_grid=6)
     yr = O.rotate(xr, 64)
     assert a["s_max"] == np.float32(np.abs(yr).max() / 7)
+
+
+# ------------------------------------------------------------------ fused producers
+def test_silu_mul_and_rmsnorm_closed_forms():
+    g = np.array([[0.0, 1.0, -1.0, 20.0, -20.0]])
+    u = np.array([[3.0, 2.0, 2.0, 1.0, 1.0]])
+    e = np.e
+    want = [0.0, 2.0 / (1.0 + 1.0 / e), -2.0 / (1.0 + e), 20.0 / (1.0 + np.exp(-20.0)), -20.0 / (1.0 + np.exp(20.0))]
+    np.testing.assert_allclose(O.silu_mul(g, u)[0], want, rtol=1e-15)
+    # silu(g) = g * sigmoid(g) = g * (1 + tanh(g / 2)) / 2: an independent closed form
+    gg = np.linspace(-9, 9, 37)[None, :]
+    np.testing.assert_allclose(O.silu_mul(gg, np.ones_like(gg)), gg * (1 + np.tanh(gg / 2)) / 2, rtol=1e-13, atol=1e-15)
+    x = np.array([[3.0, 4.0, 0.0, 0.0], [1.0, 1.0, 1.0, 1.0], [0.0, 0.0, 0.0, 0.0]])
+    y = O.rmsnorm(x, 0.0 + 1e-30)
+    np.testing.assert_allclose(y[0], np.array([3.0, 4.0, 0.0, 0.0]) / 2.5, rtol=1e-14)      # mean square = 25/4
+    np.testing.assert_allclose(y[1], np.ones(4), rtol=1e-14)
+    assert not y[2].any()
+    y2 = O.rmsnorm(x[:2], 1.0)                            # eps enters under the root
+    np.testing.assert_allclose(y2[0], x[0] / np.sqrt(6.25 + 1.0), rtol=1e-14)
+    xr = np.random.default_rng(6).standard_normal((5, 64)) * 7
+    yr = O.rmsnorm(xr, 0.0)
+    np.testing.assert_allclose(np.mean(yr * yr, axis=1), np.ones(5), rtol=1e-13)           # unit mean square
+    np.testing.assert_allclose(O.rmsnorm(3.5 * xr, 0.0), yr, rtol=1e-13)                    # scale invariance
