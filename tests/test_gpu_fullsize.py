@@ -82,3 +82,66 @@ def test_decode_full_shapes(pq, M, name, K, N, h):
     check_end_to_end(x, wq_packed, sw, sx, h, host(out), xq)
     _, acc = pq.pq_w4a4_gemm(dev(xq), dev(wq_packed), dev(sw), float(sx), want_out=False, want_acc=True)
     assert np.array_equal(host(acc).astype(np.int64), O.gemm_i64(O.unpack(xq), O.unpack(wq_packed)))
+
+
+# ------------------------------------------------------------------ widened quantizers at the benchmark's sizes
+def _sample_rows(M, seed, nsample):
+    rng = np.random.default_rng(seed + 1000)
+    return np.unique(np.concatenate([[0, M - 1], rng.integers(0, M, size=nsample)]))
+
+
+@pytest.mark.parametrize("name,K,N,h", [("qkv", 4096, 6144, 1), ("gate", 4096, 14336, 1), ("down", 14336, 4096, 128)])
+def test_llama3_8b_prefill_2048_w4a8(pq, name, K, N, h):
+    M, seed = 2048, 15
+    x = synth.activations(M, K, seed)
+    wq, sw = O.weight_rtn(synth.weights(N, K, seed))
+    sx = O.calibrate_absmax(synth.calibration(K, seed), h, 8)
+    rows = _sample_rows(M, seed, 16)
+    out, ws = pq.pq_linear_w4a8(dev(x), dev(O.pack(wq)), dev(sw), float(sx), h)
+    codes = host(ws[: M * K].view(M, K)[rows]).view(np.int8)
+    out_s = host(out[rows])
+    del out, ws
+    q_gpu = O.ungroup_even_odd(codes)
+    ref = O.linear_bits(x[rows], O.pack(wq), sw, sx, h, 8)
+    diff = q_gpu.astype(np.int32) - ref["q"].astype(np.int32)
+    idx = np.nonzero(diff)
+    assert idx[0].size <= 1e-3 * diff.size and (h > 1 or idx[0].size == 0)
+    if idx[0].size:
+        t = ref["y"][idx] / np.float64(sx)
+        assert np.all(np.abs(diff[idx]) == 1)
+        assert np.all(np.abs(t - (np.minimum(q_gpu[idx], ref["q"][idx]) + 0.5)) <= 1e-3)
+    o_ref = ref["out"].astype(np.float64)
+    assert np.abs(out_s.astype(np.float64) - o_ref).max() <= 1e-2 * np.abs(o_ref).max()
+    assert ulp_diff(O.epilogue(O.gemm_i64(q_gpu, wq), sx, sw), out_s).max() <= 1
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("name,K,N,h", [("o", 4096, 4096, 1), ("down", 14336, 4096, 128)])
+def test_llama3_8b_prefill_2048_dynamic(pq, bits, name, K, N, h):
+    M, seed = 2048, 16
+    x = synth.activations(M, K, seed)
+    wq, sw = O.weight_rtn(synth.weights(N, K, seed))
+    rows = _sample_rows(M, seed, 16)
+    out, ws = pq.pq_linear_dynamic(dev(x), dev(O.pack(wq)), dev(sw), h, 1.0, bits)
+    total = pq.pq_linear_dynamic_workspace_bytes(M, K, bits)
+    s_off = total - ((4 * M + 255) // 256) * 256
+    s_gpu = host(ws[s_off: s_off + 4 * M]).view(np.float32)[rows]
+    if bits == 8:
+        q_gpu = O.ungroup_even_odd(host(ws[: M * K].view(M, K)[rows]).view(np.int8))
+    else:
+        q_gpu = O.unpack(host(ws[: M * K // 2].view(M, K // 2)[rows]))
+    out_s = host(out[rows])
+    del out, ws
+    ref = O.linear_dynamic(x[rows], O.pack(wq), sw, h, 1.0, bits)
+    ia, ib = s_gpu.view(np.int32).astype(np.int64), ref["s"].view(np.int32).astype(np.int64)
+    assert np.abs(ia - ib).max() <= (0 if h <= 1 else 4)
+    diff = q_gpu.astype(np.int32) - ref["q"].astype(np.int32)
+    idx = np.nonzero(diff)
+    assert idx[0].size <= 1e-3 * diff.size and (h > 1 or idx[0].size == 0)
+    if idx[0].size:
+        t = ref["y"][idx] / ref["s"].astype(np.float64)[idx[0]]
+        assert np.all(np.abs(diff[idx]) == 1)
+        assert np.all(np.abs(t - (np.minimum(q_gpu[idx], ref["q"][idx]) + 0.5)) <= 1e-3)
+    o_ref = ref["out"].astype(np.float64)
+    assert np.abs(out_s.astype(np.float64) - o_ref).max() <= 1e-2 * np.abs(o_ref).max()
+    assert ulp_diff(O.epilogue(O.gemm_i64(q_gpu, wq), s_gpu, sw), out_s).max() <= 1
