@@ -110,7 +110,8 @@ int pq_set_gemm_variant(int variant);
  * Same layer with the activation quantizer at 8 bits: q = clamp(round_half_even(y/act_scale),
  * -128, 127), one int8 per code.  The three calls below mirror pq_rotate_quant, pq_w4a4_gemm and
  * pq_linear; they need K % 128 == 0, K <= 65536 and M*K < 2^32 (else PQ_ERR_UNSUPPORTED or
- * PQ_ERR_SHAPE as for the 4-bit calls), and always use the MFMA tiled kernel.
+ * PQ_ERR_SHAPE as for the 4-bit calls); M <= 8 streams the weights once (decode kernel with 4-way
+ * byte dot products), larger M uses the MFMA tiled kernel.
  *
  * "Grouped" int8 layout of xq8 [M,K]: inside every group of 32 consecutive channels the 16 even
  * channels are stored first, then the 16 odd ones: byte 32*g + 16*p + j holds channel
@@ -151,8 +152,8 @@ int pq_rotate_quant_dynamic(const void* x_f16, int64_t M, int64_t K, int32_t had
                             float clip, int32_t bits, void* xq, float* row_scale, void* stream);
 
 /* out[m,n] = fp16(acc[m,n] * (row_scale[m] * w_scale[n])), acc as in pq_w4a4_gemm (bits = 4) or
- * pq_w4a8_gemm (bits = 8).  K % 128 == 0, K <= 65536.  bits = 4 and M <= 8 take the
- * weight-streaming decode kernel, everything else the MFMA tiled kernel.
+ * pq_w4a8_gemm (bits = 8).  K % 128 == 0, K <= 65536.  M <= 8 takes the weight-streaming decode
+ * kernel (when the rows fit LDS), everything else the MFMA tiled kernel.
  */
 int pq_gemm_dynamic(const void* xq, int32_t bits, const void* wq_packed, const float* w_scale,
                     const float* row_scale, int64_t M, int64_t N, int64_t K,

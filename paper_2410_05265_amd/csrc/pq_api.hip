@@ -141,6 +141,9 @@ int pq_w4a8_gemm(const void* xq8_grouped, const void* wq_packed, const float* w_
     if (rc != PQ_OK) return rc;
     if ((K % 128) != 0) return PQ_ERR_SHAPE;
     if (M == 0) return PQ_OK;
+    if (M <= 8 && (g_variant == 0 || g_variant == 4) && pq::decode_supported(M, N, K, -1, 8))
+        return pq::launch_decode(nullptr, xq8_grouped, wq_packed, w_scale, act_scale, 1, M, N, K, out_f16, acc_i32,
+                                 nullptr, static_cast<hipStream_t>(stream), nullptr, 8);
     return pq::launch_gemm_w4a8(xq8_grouped, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32,
                                 static_cast<hipStream_t>(stream));
 }
@@ -199,9 +202,9 @@ int pq_gemm_dynamic(const void* xq, int32_t bits, const void* wq_packed, const f
     if (reinterpret_cast<uintptr_t>(row_scale) & 3u) return PQ_ERR_ALIGN;
     if (M == 0) return PQ_OK;
     // decode: the weight-streaming kernel with the token's step in its epilogue
-    if (bits == 4 && M <= 8 && (g_variant == 0 || g_variant == 4) && pq::decode_supported(M, N, K, -1))
+    if (M <= 8 && (g_variant == 0 || g_variant == 4) && pq::decode_supported(M, N, K, -1, bits))
         return pq::launch_decode(nullptr, xq, wq_packed, w_scale, 1.0f, 1, M, N, K, out_f16, acc_i32, nullptr,
-                                 static_cast<hipStream_t>(stream), row_scale);
+                                 static_cast<hipStream_t>(stream), row_scale, bits);
     return pq::launch_gemm_dynamic(xq, bits, wq_packed, w_scale, row_scale, M, N, K, out_f16, acc_i32,
                                    static_cast<hipStream_t>(stream));
 }

@@ -61,7 +61,10 @@ __device__ __forceinline__ int bitrev(int x, int bits)
 // or rotated with blocks of 2^log2h <= 2048 first; 2: rotated with blocks of 4096.
 // One workgroup of 16 wavefronts per CU; a wavefront owns RPW weight rows at a time and has
 // RPW * CB 16-byte loads in flight; MP = padded M.
-template <int RPW, int CB, int MP, int MODE>
+// ABITS = 8 (given codes only): the activation codes are int8 in the grouped order (16 even
+// channels, then 16 odd ones per 32), the weight nibbles are expanded to 16 * code bytes and the
+// products are 4-way byte dot products; the sums carry a factor 16, shifted out at the end.
+template <int RPW, int CB, int MP, int MODE, int ABITS = 4>
 __global__ __launch_bounds__(1024) void k_decode(const __half* __restrict__ x, const uint8_t* __restrict__ xq_in,
                                                const uint8_t* __restrict__ wq, const float* __restrict__ sw,
                                                float sx, float mult, int log2h, int M, int N, int K,
@@ -69,23 +72,25 @@ __global__ __launch_bounds__(1024) void k_decode(const __half* __restrict__ x, c
                                                uint8_t* __restrict__ xq_out, const float* __restrict__ srow)
 {
     constexpr int G = MODE == 2 ? 2 : 1;
+    static_assert(ABITS == 4 || (ABITS == 8 && MODE == 0), "8-bit activations: given codes only");
     extern __shared__ __align__(16) uint8_t smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int Kb = K >> 1;
+    const int Ka = ABITS == 8 ? K : Kb;   // bytes per row of activation codes
     const int cpr = (Kb + 1023) >> 10;   // KiB chunks per row
     const int groups = N / RPW, gstride = gridDim.x * 16;
     int gid = blockIdx.x * 16 + wave;
-    // LDS: [MP][Kb] packed codes | rotation scratch | [M][K] fp16 rows (fused modes only)
+    // LDS: [MP][Ka] codes | rotation scratch | [M][K] fp16 rows (fused modes only)
     uint8_t* xs = smem;
-    const int xch_off = (MP * Kb + 15) & ~15;
+    const int xch_off = (MP * Ka + 15) & ~15;
     const int xraw_off = xch_off + (MODE == 0 ? 16 : G * kChunk * 4);
 
     // ---- 1. first pieces of the activation rows (ordinary loads, issued before the weights:
     // loads complete in order, so waiting for these leaves the weight loads in flight)
     constexpr int XB = 2;   // enough for one token of 16384 channels; more pieces wait behind the weights
     const uint8_t* xsrc = MODE == 0 ? xq_in : reinterpret_cast<const uint8_t*>(x);
-    const int pieces = (MODE == 0 ? M * Kb : M * K * 2) >> 4;   // 16-byte pieces
+    const int pieces = (MODE == 0 ? M * Ka : M * K * 2) >> 4;   // 16-byte pieces
     uint8_t* xdst = MODE == 0 ? xs : smem + xraw_off;
     v4i xr[XB];
 #pragma unroll
@@ -176,6 +181,31 @@ __global__ __launch_bounds__(1024) void k_decode(const __half* __restrict__ x, c
             for (int c = 0; c < CB; ++c) {
                 const int off = (cb + c) * 1024 + lane * 16;
                 if (off < Kb) {
+                    if constexpr (ABITS == 8) {
+                        v4i we[RPW], wo[RPW];
+#pragma unroll
+                        for (int j = 0; j < RPW; ++j) unpack16(w[j][c], we[j], wo[j]);
+#pragma unroll
+                        for (int m = 0; m < MP; ++m) {
+                            if (m < M) {
+                                const v4i xe = *(__attribute__((address_space(3))) const v4i*)(xs + m * Ka + 2 * off);
+                                const v4i xo = *(__attribute__((address_space(3))) const v4i*)(xs + m * Ka + 2 * off + 16);
+#pragma unroll
+                                for (int j = 0; j < RPW; ++j) {
+                                    int a = p[j * MP + m];
+                                    a = __builtin_amdgcn_sdot4(we[j].x, xe.x, a, false);
+                                    a = __builtin_amdgcn_sdot4(we[j].y, xe.y, a, false);
+                                    a = __builtin_amdgcn_sdot4(we[j].z, xe.z, a, false);
+                                    a = __builtin_amdgcn_sdot4(we[j].w, xe.w, a, false);
+                                    a = __builtin_amdgcn_sdot4(wo[j].x, xo.x, a, false);
+                                    a = __builtin_amdgcn_sdot4(wo[j].y, xo.y, a, false);
+                                    a = __builtin_amdgcn_sdot4(wo[j].z, xo.z, a, false);
+                                    a = __builtin_amdgcn_sdot4(wo[j].w, xo.w, a, false);
+                                    p[j * MP + m] = a;
+                                }
+                            }
+                        }
+                    } else {
 #pragma unroll
                     for (int m = 0; m < MP; ++m) {
                         if (m < M) {
@@ -191,6 +221,7 @@ __global__ __launch_bounds__(1024) void k_decode(const __half* __restrict__ x, c
                             }
                         }
                     }
+                    }
                 }
             }
         }
@@ -201,22 +232,23 @@ __global__ __launch_bounds__(1024) void k_decode(const __half* __restrict__ x, c
             const int j = idx / MP, m = idx % MP;
             if (m < M) {
                 const int n = gid * RPW + j;
-                if (acc_out) acc_out[(int64_t)m * N + n] = p[0];
-                if (out) out[(int64_t)m * N + n] = __float2half_rn((float)p[0] * ((srow ? srow[m] : sx) * sw[n]));
+                const int total = ABITS == 8 ? p[0] >> 4 : p[0];
+                if (acc_out) acc_out[(int64_t)m * N + n] = total;
+                if (out) out[(int64_t)m * N + n] = __float2half_rn((float)total * ((srow ? srow[m] : sx) * sw[n]));
             }
         }
     }
 }
 
-template <int RPW, int CB, int MP, int MODE>
+template <int RPW, int CB, int MP, int MODE, int ABITS = 4>
 int launch_one(const __half* x, const uint8_t* xq_in, const uint8_t* wq, const float* sw, float sx, float mult,
                int log2h, int M, int N, int K, __half* out, int32_t* acc, uint8_t* xq_out, hipStream_t st,
                const float* srow)
 {
     constexpr int G = MODE == 2 ? 2 : 1;
-    const size_t lds = (((size_t)MP * (K / 2) + 15) & ~(size_t)15) +
+    const size_t lds = (((size_t)MP * (ABITS == 8 ? K : K / 2) + 15) & ~(size_t)15) +
                        (MODE == 0 ? 16 : (size_t)G * kChunk * 4 + (size_t)M * K * 2);
-    auto kern = k_decode<RPW, CB, MP, MODE>;
+    auto kern = k_decode<RPW, CB, MP, MODE, ABITS>;
     static bool attr_set = false;  // benign race: the call is idempotent
     if (lds > 48 * 1024 && !attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -232,10 +264,15 @@ int launch_one(const __half* x, const uint8_t* xq_in, const uint8_t* wq, const f
     return hip_status(hipGetLastError());
 }
 
-template <int RPW, int CB, int MP>
+template <int RPW, int CB, int MP, int ABITS = 4>
 int launch_mode(const __half* x, const uint8_t* xq_in, const uint8_t* wq, const float* sw, float sx, int h, int M,
                 int N, int K, __half* out, int32_t* acc, uint8_t* xq_out, hipStream_t st, const float* srow)
 {
+    if constexpr (ABITS == 8) {
+        if constexpr (RPW > 2 || (MP > 1 && RPW * CB > 8)) return PQ_ERR_UNSUPPORTED;   // never chosen
+        else if (x != nullptr) return PQ_ERR_UNSUPPORTED;                               // given codes only
+        else return launch_one<RPW, CB, MP, 0, 8>(x, xq_in, wq, sw, sx, 0.f, 0, M, N, K, out, acc, xq_out, st, srow);
+    } else
     if constexpr (MP > 4 && (RPW > 2 || RPW * CB > 8)) return PQ_ERR_UNSUPPORTED;   // never chosen: too many registers
     else if (x == nullptr) return launch_one<RPW, CB, MP, 0>(x, xq_in, wq, sw, sx, 0.f, 0, M, N, K, out, acc, xq_out, st, srow);
     if constexpr (MP > 4) return PQ_ERR_UNSUPPORTED;   // more than 4 tokens: codes only, no fused quantizer
@@ -253,27 +290,32 @@ int launch_mode(const __half* x, const uint8_t* xq_in, const uint8_t* wq, const 
     }
 }
 
-template <int MP>
+template <int MP, int ABITS = 4>
 int launch_shape(int rpw, int cb, const __half* x, const uint8_t* xi, const uint8_t* w, const float* sw, float sx,
                  int h, int m, int n, int k, __half* o, int32_t* acc, uint8_t* xo, hipStream_t st, const float* srow)
 {
     switch (rpw * 100 + cb) {
-        case 102: return launch_mode<1, 2, MP>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
-        case 202: return launch_mode<2, 2, MP>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
-        case 402: return launch_mode<4, 2, MP>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
-        case 104: return launch_mode<1, 4, MP>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
-        case 204: return launch_mode<2, 4, MP>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
-        case 404: return launch_mode<4, 4, MP>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
-        case 108: return launch_mode<1, 8, MP>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
-        default: return launch_mode<2, 8, MP>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
+        case 102: return launch_mode<1, 2, MP, ABITS>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
+        case 202: return launch_mode<2, 2, MP, ABITS>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
+        case 402: return launch_mode<4, 2, MP, ABITS>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
+        case 104: return launch_mode<1, 4, MP, ABITS>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
+        case 204: return launch_mode<2, 4, MP, ABITS>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
+        case 404: return launch_mode<4, 4, MP, ABITS>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
+        case 108: return launch_mode<1, 8, MP, ABITS>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
+        default: return launch_mode<2, 8, MP, ABITS>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
     }
 }
 
 }  // namespace
 
 // h < 0: the packed codes are given; h >= 0: fused rotate + quantize from fp16 rows
-bool decode_supported(int64_t M, int64_t N, int64_t K, int32_t h)
+bool decode_supported(int64_t M, int64_t N, int64_t K, int32_t h, int32_t abits)
 {
+    if (abits == 8) {   // int8 codes given: [MP][K] bytes of LDS
+        if (!(h < 0 && M >= 1 && M <= 8 && (N % 16) == 0 && (K % 32) == 0 && K <= 131072 && N <= (1 << 30))) return false;
+        const int64_t mp8 = M == 1 ? 1 : (M <= 4 ? 4 : 8);
+        return mp8 * K + 32 <= 160 * 1024;
+    }
     if (!(M >= 1 && M <= (h < 0 ? 8 : 4) && (N % 16) == 0 && K <= 131072 && h <= 2 * kChunk && N <= (1 << 30)))
         return false;
     const int64_t mp = M == 1 ? 1 : (M <= 4 ? 4 : 8), g = h <= kChunk ? 1 : 2;
@@ -286,9 +328,9 @@ bool decode_supported(int64_t M, int64_t N, int64_t K, int32_t h)
 // epilogue (per-token dynamic quantization; only with given codes).
 int launch_decode(const void* x_f16, const void* xq_in, const void* wq, const float* sw, float sx, int32_t h,
                   int64_t M, int64_t N, int64_t K, void* out, int32_t* acc, void* xq_out, hipStream_t st,
-                  const float* srow)
+                  const float* srow, int32_t abits)
 {
-    if (!decode_supported(M, N, K, x_f16 ? h : -1)) return PQ_ERR_UNSUPPORTED;
+    if (!decode_supported(M, N, K, x_f16 ? h : -1, abits)) return PQ_ERR_UNSUPPORTED;
     const __half* x = static_cast<const __half*>(x_f16);
     const uint8_t* xi = static_cast<const uint8_t*>(xq_in);
     const uint8_t* w = static_cast<const uint8_t*>(wq);
@@ -302,6 +344,13 @@ int launch_decode(const void* x_f16, const void* xq_in, const void* wq, const fl
     while (rpw < 4 && rpw * 2 * cb <= 16 && N / rpw > 4096) rpw *= 2;
     if (rpw == 4 && cb == 8) rpw = 2;
     const int m = (int)M, n = (int)N, k = (int)K;
+    if (abits == 8) {
+        if (rpw > 2) rpw = 2;
+        if (M == 1) return launch_shape<1, 8>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
+        if (cb == 8) rpw = 1;   // more tokens: fewer rows per wavefront keep the accumulators in registers
+        if (M <= 4) return launch_shape<4, 8>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
+        return launch_shape<8, 8>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
+    }
     if (M == 1) return launch_shape<1>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
     if (M <= 4) return launch_shape<4>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow);
     // 5..8 tokens: fewer rows per wavefront so that the accumulators stay in registers

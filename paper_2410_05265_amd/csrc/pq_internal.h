@@ -36,10 +36,10 @@ int launch_gemm_mfma(const void* xq, const void* wq, const float* sw, float sx, 
 int launch_gemv(const void* xq, const void* wq, const float* sw, float sx, int64_t M,
                 int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st);
 
-bool decode_supported(int64_t M, int64_t N, int64_t K, int32_t h);
+bool decode_supported(int64_t M, int64_t N, int64_t K, int32_t h, int32_t abits = 4);
 int launch_decode(const void* x_f16, const void* xq_in, const void* wq, const float* sw, float sx, int32_t h,
                   int64_t M, int64_t N, int64_t K, void* out, int32_t* acc, void* xq_out, hipStream_t st,
-                  const float* srow = nullptr);
+                  const float* srow = nullptr, int32_t abits = 4);
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? PQ_OK : PQ_ERR_HIP; }
 

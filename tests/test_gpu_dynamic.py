@@ -92,21 +92,24 @@ def test_dynamic_product_and_epilogue(pq, bits, M, N, K):
     assert ulp_diff(host(out), out_ref).max() <= 1
 
 
+@pytest.mark.parametrize("bits", [4, 8])
 @pytest.mark.parametrize("M", [1, 3, 4, 5, 8])
 @pytest.mark.parametrize("N,K", [(512, 512), (1024, 14336), (4608, 16384), (6144, 4096)])
-def test_dynamic_decode_sizes(pq, M, N, K):
-    """M <= 8 at 4 bits takes the weight-streaming kernel, with the token's step in its epilogue."""
-    q = synth.random_codes(M, K, seed=M + K, stream=9)
+def test_dynamic_decode_sizes(pq, bits, M, N, K):
+    """M <= 8 takes the weight-streaming kernel, with the token's step in its epilogue."""
+    lo, hi = (-128, 127) if bits == 8 else (-8, 7)
+    q = synth.random_codes(M, K, seed=M + K, stream=9, lo=lo, hi=hi)
     wq = synth.random_packed(N, K, seed=N + K, stream=7)
     sw = synth.random_scales(N, seed=N)
     srow = synth.random_scales(M, seed=M + 2)
     acc_ref = O.gemm_i64(q, O.unpack(wq))
-    out, acc = pq.pq_gemm_dynamic(dev(O.pack(q)), 4, dev(wq), dev(sw), dev(srow), want_out=True, want_acc=True)
+    xq = O.group_even_odd(q) if bits == 8 else O.pack(q)
+    out, acc = pq.pq_gemm_dynamic(dev(xq), bits, dev(wq), dev(sw), dev(srow), want_out=True, want_acc=True)
     assert np.array_equal(host(acc).astype(np.int64), acc_ref)
     assert ulp_diff(host(out), O.epilogue(acc_ref, srow, sw)).max() <= 1
     prev = pq.pq_set_gemm_variant(2)                       # and the tiled kernel gives the same bits
     try:
-        out2, _ = pq.pq_gemm_dynamic(dev(O.pack(q)), 4, dev(wq), dev(sw), dev(srow))
+        out2, _ = pq.pq_gemm_dynamic(dev(xq), bits, dev(wq), dev(sw), dev(srow))
     finally:
         pq.pq_set_gemm_variant(prev)
     assert ulp_diff(host(out2), host(out)).max() <= 1

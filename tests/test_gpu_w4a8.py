@@ -89,6 +89,26 @@ def test_w4a8_product_and_epilogue(pq, M, N, K):
     assert np.array_equal(host(out2), host(out))
 
 
+@pytest.mark.parametrize("M", [1, 2, 4, 5, 8])
+@pytest.mark.parametrize("N,K", [(512, 512), (1024, 14336), (4608, 16384), (6144, 4096), (256, 28672), (48, 2176)])
+def test_w4a8_decode_sizes(pq, M, N, K):
+    """M <= 8 streams the weights once (4-way byte dot products); long rows that do not fit LDS fall back."""
+    q = synth.random_codes(M, K, seed=M + K, stream=8, lo=-128, hi=127)
+    wq = synth.random_packed(N, K, seed=N + K, stream=7)
+    sw = synth.random_scales(N, seed=N)
+    sx = np.float32(0.0213)
+    acc_ref = O.gemm_i64(q, O.unpack(wq))
+    out, acc = pq.pq_w4a8_gemm(dev(O.group_even_odd(q)), dev(wq), dev(sw), float(sx), want_out=True, want_acc=True)
+    assert np.array_equal(host(acc).astype(np.int64), acc_ref)
+    assert ulp_diff(host(out), O.epilogue(acc_ref, sx, sw)).max() <= 1
+    prev = pq.pq_set_gemm_variant(2)                       # the tiled kernel gives the same accumulators
+    try:
+        _, acc2 = pq.pq_w4a8_gemm(dev(O.group_even_odd(q)), dev(wq), dev(sw), float(sx), want_out=False, want_acc=True)
+    finally:
+        pq.pq_set_gemm_variant(prev)
+    assert np.array_equal(host(acc2), host(acc))
+
+
 @pytest.mark.parametrize("a,w", [(-128, -8), (-128, 7), (127, -8), (127, 7)])
 def test_w4a8_extreme_codes_longest_row(pq, a, w):
     M, N, K = 4, 32, 65536
