@@ -114,14 +114,13 @@ __device__ __forceinline__ void static_for(F&& f)
 
 template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
+// One output tile [m0, m0 + BM) x [n0, n0 + BN) by the whole workgroup (the LDS ring is the
+// workgroup's dynamic shared memory).
 template <int BM, int BN, int WR, int WC, int NS, int SUBS, int ABITS, int ASHIFT>
-__global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __restrict__ xq,
-                                                          const uint8_t* __restrict__ wq,
-                                                          const float* __restrict__ sw, float sx, int M, int N,
-                                                          int K, int GM, __half* __restrict__ out,
-                                                          int32_t* __restrict__ acc_out,
-                                                          const float* __restrict__ srow)
+__device__ __forceinline__ void gemm_tile(const uint8_t* xq, const uint8_t* wq, const float* sw, float sx, int M, int N,
+                                          int K, int m0, int n0, __half* out, int32_t* acc_out, const float* srow)
 {
+    extern __shared__ __align__(16) uint8_t smem[];
     constexpr int NW = WR * WC;
     constexpr int WM = BM / WR, WN = BN / WC, TM = WM / 32, TN = WN / 32;
     // srow: per-token step sizes [M] (per-token dynamic quantization) or NULL (one static step sx)
@@ -137,15 +136,12 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
     constexpr int LW = BLK / NW;          // direct loads per wavefront per sub-stage
     static_assert(BLK % NW == 0 && ABLK % NW == 0, "loader shape");
     constexpr int LWA = ABLK / NW;        // of which for the activation rows
-    extern __shared__ __align__(16) uint8_t smem[];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: keeps LDS targets in scalar registers
     const int wm = wave / WC, wn = wave % WC;
     const int r = lane & 31, g = lane >> 5;
 
-    const int tile = xcd_remap(blockIdx.x, gridDim.x);
-    const int m0 = (tile % GM) * BM, n0 = (tile / GM) * BN;
     const int Kb = K >> 1;
     const int nk = K / (128 * SUBS);
 
@@ -376,6 +372,64 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
     }
 }
 
+template <int BM, int BN, int WR, int WC, int NS, int SUBS, int ABITS, int ASHIFT>
+__global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __restrict__ xq,
+                                                          const uint8_t* __restrict__ wq,
+                                                          const float* __restrict__ sw, float sx, int M, int N,
+                                                          int K, int GM, __half* __restrict__ out,
+                                                          int32_t* __restrict__ acc_out,
+                                                          const float* __restrict__ srow)
+{
+    const int tile = xcd_remap(blockIdx.x, gridDim.x);
+    gemm_tile<BM, BN, WR, WC, NS, SUBS, ABITS, ASHIFT>(xq, wq, sw, sx, M, N, K, (tile % GM) * BM, (tile / GM) * BN, out,
+                                                       acc_out, srow);
+}
+
+// Two tile widths in one launch: the first GM * n1 workgroups take tiles BM x BN1 of the columns
+// [0, n1 * BN1), the others tiles BM x BN2 of the rest.  Workgroups are dispatched in index order,
+// so with GM * n1 = GM * n2 = number of CUs every CU computes one tile of each width and no CU idles
+// through a partial last round (gate/up: 14336 = 32 x 256 + 32 x 192).
+template <int BM, int BN1, int BN2, int WR, int WC, int NS>
+__global__ __launch_bounds__(WR * WC * 64) void k_gemm_dual(const uint8_t* __restrict__ xq,
+                                                           const uint8_t* __restrict__ wq,
+                                                           const float* __restrict__ sw, float sx, int M, int N,
+                                                           int K, int GM, int n1, int n2, __half* __restrict__ out,
+                                                           int32_t* __restrict__ acc_out,
+                                                           const float* __restrict__ srow)
+{
+    const int first = GM * n1;
+    if ((int)blockIdx.x < first) {
+        const int tile = xcd_remap(blockIdx.x, first);
+        gemm_tile<BM, BN1, WR, WC, NS, 1, 4, 8>(xq, wq, sw, sx, M, N, K, (tile % GM) * BM, (tile / GM) * BN1, out, acc_out,
+                                                srow);
+    } else {
+        const int tile = xcd_remap(blockIdx.x - first, GM * n2);
+        gemm_tile<BM, BN2, WR, WC, NS, 1, 4, 8>(xq, wq, sw, sx, M, N, K, (tile % GM) * BM, n1 * BN1 + (tile / GM) * BN2, out,
+                                                acc_out, srow);
+    }
+}
+
+template <int BM, int BN1, int BN2, int WR, int WC, int NS>
+int launch_dual(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K, int n1,
+                int n2, void* out, int32_t* acc, hipStream_t st, const float* srow = nullptr)
+{
+    const int GM = (int)((M + BM - 1) / BM);
+    constexpr size_t lds = (size_t)NS * (BM * 64 + (BN1 > BN2 ? BN1 : BN2) * 64);
+    static_assert(lds <= 160 * 1024, "LDS ring too large");
+    auto kern = k_gemm_dual<BM, BN1, BN2, WR, WC, NS>;
+    static bool attr_set = false;  // benign race: the call is idempotent
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds) != hipSuccess)
+            return PQ_ERR_HIP;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)(GM * (n1 + n2))), dim3(WR * WC * 64), lds, st,
+                       static_cast<const uint8_t*>(xq), static_cast<const uint8_t*>(wq), sw, sx, (int)M, (int)N,
+                       (int)K, GM, n1, n2, static_cast<__half*>(out), acc, srow);
+    return hip_status(hipGetLastError());
+}
+
 template <int BM, int BN, int WR, int WC, int NS, int SUBS, int ABITS = 4, int ASHIFT = 8>
 int launch_dma(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K, void* out,
                int32_t* acc, hipStream_t st, const float* srow = nullptr)
@@ -552,6 +606,51 @@ int pick_cfg(int64_t M, int64_t N)
     return best;
 }
 
+// Is a launch of n1 column panels of 256 and n2 of 192 (256 n1 + 192 n2 = N) cheaper than the best
+// single width?  Tiles go to the earliest free CU in index order; a tile's cost is its area over the
+// width's efficiency (the same model as pick_cfg).  PQ_GEMM_TILE switches the mixed launch off.
+bool pick_dual(int64_t M, int64_t N, int* n1_out, int* n2_out)
+{
+    if (getenv("PQ_GEMM_TILE") || (N % 64) != 0 || M < 256) return false;
+    const int64_t GM = (M + 255) / 256;
+    double single = 1e300;
+    for (int c = 0; c < kNumAuto; ++c) {
+        const int64_t tiles = ((M + kCfgs[c].bm - 1) / kCfgs[c].bm) * ((N + kCfgs[c].bn - 1) / kCfgs[c].bn);
+        const double cost = (double)((tiles + 255) / 256) * kCfgs[c].bm * kCfgs[c].bn / kCfgs[c].eff;
+        if (cost < single) single = cost;
+    }
+    const double t1 = 256.0 * 256.0 / kCfgs[0].eff, t2 = 256.0 * 192.0 / kCfgs[3].eff;
+    double best = single * 0.97;   // the mixed launch has to win by a margin
+    bool found = false;
+    for (int64_t n2 = 1; 192 * n2 < N; ++n2) {
+        if ((N - 192 * n2) % 256 != 0) continue;
+        const int64_t n1 = (N - 192 * n2) / 256;
+        if (n1 < 1 || GM * (n1 + n2) > 1 << 20) continue;
+        // 256 CUs take tiles in order: all wide tiles first
+        const int64_t a = GM * n1, b = GM * n2;
+        const int64_t ra = a / 256, xa = a % 256;        // full rounds of wide tiles, CUs with one more
+        // after the wide tiles, xa CUs are busy until (ra + 1) t1 and 256 - xa until ra t1; narrow tiles fill in order
+        double finish;
+        if (xa == 0) {
+            finish = ra * t1 + (double)((b + 255) / 256) * t2;
+        } else {
+            const int64_t early = 256 - xa;               // CUs free at ra * t1
+            // narrow tiles: the early CUs take floor(t1 / t2) + ... ; model conservatively by time steps of t2
+            int64_t left = b;
+            double t_early = ra * t1, t_late = (ra + 1) * t1;
+            // hand tiles to whichever group frees first until none are left
+            while (left > 0) {
+                if (t_early <= t_late) { left -= early < left ? early : left; t_early += t2; }
+                else { left -= xa < left ? xa : left; t_late += t2; }
+            }
+            finish = t_early > t_late ? t_early : t_late;
+            if (finish < (ra + 1) * t1) finish = (ra + 1) * t1;
+        }
+        if (finish < best) { best = finish; *n1_out = (int)n1; *n2_out = (int)n2; found = true; }
+    }
+    return found;
+}
+
 }  // namespace
 
 int launch_gemm_mfma(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K,
@@ -562,6 +661,8 @@ int launch_gemm_mfma(const void* xq, const void* wq, const float* sw, float sx, 
     if (K % 128 != 0) return launch_ragged(xq, wq, sw, sx, M, N, K, out, acc, st);
     // (two 128-channel sub-stages per ring stage, i.e. one barrier per 256 channels with a 2-deep
     // ring, measured 3-10 % slower than a 3-deep ring of single sub-stages: depth wins)
+    int n1 = 0, n2 = 0;
+    if (pick_dual(M, N, &n1, &n2)) return launch_dual<256, 256, 192, 2, 2, 3>(xq, wq, sw, sx, M, N, K, n1, n2, out, acc, st);
     switch (pick_cfg(M, N)) {
         case 0: return launch_dma<256, 256, 2, 2, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
         case 1: return launch_dma<256, 128, 2, 2, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
@@ -605,6 +706,9 @@ int launch_gemm_dynamic(const void* xq, int32_t bits, const void* wq, const floa
             default: return launch_dma<128, 128, 2, 2, 3, 1, 8, 4>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
         }
     }
+    int n1 = 0, n2 = 0;
+    if (pick_dual(M, N, &n1, &n2))
+        return launch_dual<256, 256, 192, 2, 2, 3>(xq, wq, sw, 1.0f, M, N, K, n1, n2, out, acc, st, srow);
     switch (cfg) {
         case 0: return launch_dma<256, 256, 2, 2, 3, 1>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
         case 1: return launch_dma<256, 128, 2, 2, 3, 1>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);

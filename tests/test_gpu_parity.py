@@ -105,6 +105,23 @@ def test_decode_five_to_eight_tokens_long_rows(pq, M, N, K):
     assert ulp_diff(host(out), O.epilogue(acc_ref, np.float32(0.25), sw)).max() <= 1
 
 
+@pytest.mark.parametrize("M,N,K", [(1900, 14336, 256), (2048, 14336, 128), (1030, 14336, 384)])
+def test_product_mixed_tile_widths(pq, M, N, K):
+    """Shapes for which one launch mixes 256- and 192-wide tiles (14336 = 32 x 256 + 32 x 192), ragged in M."""
+    xq = synth.random_packed(M, K, seed=M + K)
+    wq = synth.random_packed(N, K, seed=N + K, stream=7)
+    sw = synth.random_scales(N, seed=N)
+    sx = np.float32(0.0917)
+    acc_ref = O.gemm_i64(O.unpack(xq), O.unpack(wq))
+    out, acc = pq.pq_w4a4_gemm(dev(xq), dev(wq), dev(sw), float(sx), want_out=True, want_acc=True)
+    assert np.array_equal(host(acc).astype(np.int64), acc_ref)
+    assert ulp_diff(host(out), O.epilogue(acc_ref, sx, sw)).max() <= 1
+    srow = synth.random_scales(M, seed=M + 3)
+    out_d, acc_d = pq.pq_gemm_dynamic(dev(xq), 4, dev(wq), dev(sw), dev(srow), want_out=True, want_acc=True)
+    assert np.array_equal(host(acc_d).astype(np.int64), acc_ref)
+    assert ulp_diff(host(out_d), O.epilogue(acc_ref, srow, sw)).max() <= 1
+
+
 def test_product_extreme_codes(pq):
     K = 28672
     for M in (2, 40):
