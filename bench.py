@@ -33,7 +33,7 @@ M_PREFILL = 2048
 EVENT_EVERY = 5             # steps between two event-instrumented steps of the timed region
 # HBM bytes per GEMM launch (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 from rocprofv3 --pmc, averaged over the
 # five launches of a step; see profiles/gemm_prefill_llama3_8b_pmc.md).  Algorithmic: 63.3e6.
-GEMM_HBM_TRAFFIC_BYTES = 129.3e6
+GEMM_HBM_TRAFFIC_BYTES = 131.4e6
 # name -> (K, N, online Hadamard block)
 LINEARS = [("qkv", 4096, 6144, 1), ("o", 4096, 4096, 1), ("gate", 4096, 14336, 1),
            ("up", 4096, 14336, 1), ("down", 14336, 4096, 128)]
@@ -340,7 +340,7 @@ def main():
                    "tokens": M_PREFILL},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 1), "peak": INT8_PEAK_TOPS, "unit": "TOPS",
                      "frac": round(achieved / INT8_PEAK_TOPS, 4), "traffic": GEMM_HBM_TRAFFIC_BYTES,
-                     "kernel": "k_gemm_dma (five launches per step, averaged per launch; HIP events around the "
+                     "kernel": "k_gemm_dma / k_gemm_dual (five launches per step, averaged per launch; HIP events around the "
                                "launches of every %dth timed step)" % EVENT_EVERY,
                      "per_linear_TOPS": {k: round(gemm_ops[k] / v / 1e12, 1) for k, v in gemm_t.items()},
                      "per_linear_us": {k: round(v * 1e6, 1) for k, v in gemm_t.items()}},
