@@ -295,8 +295,18 @@ __device__ __forceinline__ void gemm_tile(const uint8_t* xq, const uint8_t* wq, 
     // ---- epilogue.  The weights were fed as the row operand, so a lane owns one token
     // (m = ... + r) and, per 32 x 32 tile, 16 output channels in groups of four consecutive
     // ones: register v holds channel 8 (v / 4) + 4 g + v % 4.  After scaling and conversion,
-    // lanes r and r + 32 trade halves so that each holds 8 consecutive channels and writes
-    // them with one 16-byte store.
+    // lanes r and r + 32 trade halves so that each holds 8 consecutive channels (16 bytes).
+    // Stored like that, one instruction would touch 32 token rows with 32 bytes each; the output
+    // burst of all CUs then runs at about 3 TB/s.  Instead each wavefront turns its 32 x WN block
+    // through a private LDS region (rows padded by 16 bytes: conflict-free both ways) and stores
+    // whole rows of WN * 2 contiguous bytes: about 4.2 TB/s.  The ring is free by now: every
+    // wavefront has passed its last operand read once the barrier below is behind it.
+    constexpr int UPR = TN * 4;                 // 16-byte units per row of the wavefront's block
+    constexpr int ROWB = UPR * 16 + 16;         // padded row pitch in LDS
+    constexpr int REGION = 32 * ROWB;
+    static_assert((size_t)NW * REGION <= (size_t)NS * STAGE, "epilogue staging does not fit the ring");
+    lds_barrier();
+    uint8_t* stg = smem + wave * REGION;
     if (acc_out) {
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
@@ -321,33 +331,35 @@ __device__ __forceinline__ void gemm_tile(const uint8_t* xq, const uint8_t* wq, 
             const int m = m0 + wm * WM + i * 32 + r;
             fm[i] = DYN ? srow[m < M ? m : M - 1] * kUnshift : 0.0f;
         }
+        float4 sc[TN][4];  // scales of this lane's channels: [8 q + 4 g, +4) for q = 0..3, per tile column
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int nb = n0 + wn * WN + j * 32;
-            float4 sc[4];  // scales of this lane's channels: [8 q + 4 g, +4) for q = 0..3
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 int n = nb + 8 * q + 4 * g;
                 n = n + 4 <= N ? n : N - 4;
-                sc[q] = *reinterpret_cast<const float4*>(sw + n);
+                sc[j][q] = *reinterpret_cast<const float4*>(sw + n);
                 if constexpr (!DYN) {
                     const float f = sx * kUnshift;
-                    sc[q].x *= f; sc[q].y *= f; sc[q].z *= f; sc[q].w *= f;
+                    sc[j][q].x *= f; sc[j][q].y *= f; sc[j][q].z *= f; sc[j][q].w *= f;
                 }
             }
+        }
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const int m = m0 + wm * WM + i * 32 + r;
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
 #pragma unroll
                 for (int qp = 0; qp < 2; ++qp) {
                     uint32_t pk[4];
 #pragma unroll
                     for (int h2 = 0; h2 < 2; ++h2) {
                         const int q = 2 * qp + h2;
-                        const float f0 = (float)acc[i][j][4 * q + 0] * (DYN ? sc[q].x * fm[i] : sc[q].x);
-                        const float f1 = (float)acc[i][j][4 * q + 1] * (DYN ? sc[q].y * fm[i] : sc[q].y);
-                        const float f2 = (float)acc[i][j][4 * q + 2] * (DYN ? sc[q].z * fm[i] : sc[q].z);
-                        const float f3 = (float)acc[i][j][4 * q + 3] * (DYN ? sc[q].w * fm[i] : sc[q].w);
+                        const float f0 = (float)acc[i][j][4 * q + 0] * (DYN ? sc[j][q].x * fm[i] : sc[j][q].x);
+                        const float f1 = (float)acc[i][j][4 * q + 1] * (DYN ? sc[j][q].y * fm[i] : sc[j][q].y);
+                        const float f2 = (float)acc[i][j][4 * q + 2] * (DYN ? sc[j][q].z * fm[i] : sc[j][q].z);
+                        const float f3 = (float)acc[i][j][4 * q + 3] * (DYN ? sc[j][q].w * fm[i] : sc[j][q].w);
                         const __half2 lo = __floats2half2_rn(f0, f1), hi = __floats2half2_rn(f2, f3);
                         pk[2 * h2 + 0] = *reinterpret_cast<const uint32_t*>(&lo);
                         pk[2 * h2 + 1] = *reinterpret_cast<const uint32_t*>(&hi);
@@ -356,13 +368,19 @@ __device__ __forceinline__ void gemm_tile(const uint8_t* xq, const uint8_t* wq, 
                     const auto s0 = __builtin_amdgcn_permlane32_swap(pk[0], pk[2], false, false);
                     const auto s1 = __builtin_amdgcn_permlane32_swap(pk[1], pk[3], false, false);
                     // lanes < 32 now hold channels 16 qp + (0..7), lanes >= 32 channels 16 qp + 8 + (0..7)
-                    const int n = nb + 16 * qp + 8 * g;
-                    if (m < M && n < N) {
-                        // (plain stores: non-temporal ones measured 20-25 % slower for the whole kernel)
-                        uint4 val = make_uint4(s0[0], s1[0], s0[1], s1[1]);
-                        *reinterpret_cast<uint4*>(out + (int64_t)m * N + n) = val;
-                    }
+                    const v4i val = {(int)s0[0], (int)s1[0], (int)s0[1], (int)s1[1]};
+                    *(__attribute__((address_space(3))) v4i*)(stg + r * ROWB + (j * 4 + 2 * qp + g) * 16) = val;
                 }
+            }
+            // LDS operations of a wavefront execute in order: the reads below see the writes above, and
+            // the next token block's writes come after these reads
+#pragma unroll
+            for (int t = 0; t < 2 * TN; ++t) {
+                const int id = 64 * t + lane, row = id / UPR, u = id % UPR;
+                const v4i val = *(__attribute__((address_space(3))) const v4i*)(stg + row * ROWB + u * 16);
+                const int m = m0 + wm * WM + i * 32 + row, n = n0 + wn * WN + u * 8;
+                // (plain stores: non-temporal ones measured 20-25 % slower for the whole kernel)
+                if (m < M && n < N) *reinterpret_cast<v4i*>(out + (int64_t)m * N + n) = val;
             }
         }
     };
