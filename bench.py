@@ -33,7 +33,7 @@ M_PREFILL = 2048
 EVENT_EVERY = 5             # steps between two event-instrumented steps of the timed region
 # HBM bytes per GEMM launch (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 from rocprofv3 --pmc, averaged over the
 # five launches of a step; see profiles/gemm_prefill_llama3_8b_pmc.md).  Algorithmic: 63.3e6.
-GEMM_HBM_TRAFFIC_BYTES = 131.4e6
+GEMM_HBM_TRAFFIC_BYTES = 124.4e6
 # name -> (K, N, online Hadamard block)
 LINEARS = [("qkv", 4096, 6144, 1), ("o", 4096, 4096, 1), ("gate", 4096, 14336, 1),
            ("up", 4096, 14336, 1), ("down", 14336, 4096, 128)]
