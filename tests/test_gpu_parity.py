@@ -105,7 +105,7 @@ def test_decode_five_to_eight_tokens_long_rows(pq, M, N, K):
     assert ulp_diff(host(out), O.epilogue(acc_ref, np.float32(0.25), sw)).max() <= 1
 
 
-@pytest.mark.parametrize("M,N,K", [(1900, 14336, 256), (2048, 14336, 128), (1030, 14336, 384)])
+@pytest.mark.parametrize("M,N,K", [(1900, 14336, 256), (2048, 14336, 128), (1030, 14336, 384), (2048, 28672, 128), (700, 21504, 128)])
 def test_product_mixed_tile_widths(pq, M, N, K):
     """Shapes for which one launch mixes 256- and 192-wide tiles (14336 = 32 x 256 + 32 x 192), ragged in M."""
     xq = synth.random_packed(M, K, seed=M + K)
