@@ -102,7 +102,8 @@ int pq_w4a4_gemm_simple(const void* xq_packed, const void* wq_packed, const floa
  * not thread-safe): 0 = automatic, 1 = weight-streaming matrix tiles (M <= 16 only),
  * 2 = MFMA tiled, 3 = simple, 4 = weight-streaming 4-bit dot products (M <= 8 only).  With 4
  * pq_linear uses its fused single launch whenever the shape allows it; with 1, 2 or 3 it
- * always uses two launches.  Returns the previous value, or -1 if `variant` is unknown.
+ * always uses two launches.  pq_w4a8_gemm and pq_gemm_dynamic use their weight-streaming kernel
+ * (M <= 8) only with 0 or 4.  Returns the previous value, or -1 if `variant` is unknown.
  */
 int pq_set_gemm_variant(int variant);
 
