@@ -94,3 +94,61 @@ def test_argument_errors_launch_nothing(b):
         assert L.pq_w4a4_gemm(p, p, p, 0.1, 17, 64, 512, p, nul, nul) == b.PQ_ERR_UNSUPPORTED
     finally:
         L.pq_set_gemm_variant(prev)
+
+
+def test_argument_errors_of_the_widened_calls(b):
+    L = b.lib()
+    p = ctypes.c_void_p(0x1000)          # never dereferenced: each call fails validation first
+    p256 = ctypes.c_void_p(0x10000)
+    odd = ctypes.c_void_p(0x1008)
+    nul = ctypes.c_void_p(0)
+    E = b
+    # 8-bit static
+    assert L.pq_rotate_quant8(p, 4, 160, 1, 0.1, p, nul) == E.PQ_ERR_SHAPE              # K % 128
+    assert L.pq_rotate_quant8(p, 4, 256, 1, 0.1, nul, nul) == E.PQ_ERR_NULL
+    assert L.pq_rotate_quant8(p, 4, 256, 1, -0.1, p, nul) == E.PQ_ERR_SCALE
+    assert L.pq_rotate_quant8(p, 0, 256, 1, 0.1, p, nul) == E.PQ_OK
+    assert L.pq_w4a8_gemm(p, p, p, 0.1, 4, 64, 160, p, nul, nul) == E.PQ_ERR_SHAPE
+    assert L.pq_w4a8_gemm(p, p, p, 0.1, 4, 64, 256, nul, nul, nul) == E.PQ_ERR_NULL
+    assert L.pq_w4a8_gemm(p, p, p, 0.1, 40, 64, 131072, p, nul, nul) == E.PQ_ERR_UNSUPPORTED   # K > 65536
+    assert L.pq_linear_w4a8(p, p, p, 0.1, 128, 4, 64, 256, p, p256, 512, nul) == E.PQ_ERR_WORKSPACE
+    assert L.pq_linear_w4a8(p, p, p, 0.1, 128, 4, 64, 256, p, odd, 4096, nul) == E.PQ_ERR_ALIGN
+    assert L.pq_linear_w4a8(p, p, p, 0.1, 128, 0, 64, 256, p, nul, 0, nul) == E.PQ_OK
+    # per-token dynamic
+    rqd = L.pq_rotate_quant_dynamic
+    assert rqd(p, 4, 256, 1, 1.0, 4, p, nul, nul) == E.PQ_ERR_NULL                       # no place for the steps
+    assert rqd(p, 4, 256, 1, 1.0, 6, p, p, nul) == E.PQ_ERR_SHAPE
+    assert rqd(p, 4, 256, 1, 0.0, 4, p, p, nul) == E.PQ_ERR_SCALE
+    assert rqd(p, 4, 256, 1, 1.25, 4, p, p, nul) == E.PQ_ERR_SCALE
+    assert rqd(p, 4, 32768 + 128, 1, 1.0, 4, p, p, nul) == E.PQ_ERR_UNSUPPORTED
+    assert rqd(p, 4, 256, 1, 1.0, 4, p, ctypes.c_void_p(0x1002), nul) == E.PQ_ERR_ALIGN
+    assert L.pq_gemm_dynamic(p, 4, p, p, nul, 4, 64, 256, p, nul, nul) == E.PQ_ERR_NULL
+    assert L.pq_gemm_dynamic(p, 3, p, p, p, 4, 64, 256, p, nul, nul) == E.PQ_ERR_SHAPE
+    assert L.pq_linear_dynamic(p, p, p, 1.0, 1, 4, 4, 64, 256, p, p256, 512, nul) == E.PQ_ERR_WORKSPACE   # needs 512 + 256
+    assert L.pq_linear_dynamic(p, p, p, 1.0, 1, 4, 0, 64, 256, p, nul, 0, nul) == E.PQ_OK
+    # attention side
+    rh = L.pq_rotate_quant_heads
+    assert rh(p, 4, 8, 48, 1, p, p, nul) == E.PQ_ERR_SHAPE                               # head_dim not a power of two
+    assert rh(p, 4, 8, 16, 1, p, p, nul) == E.PQ_ERR_SHAPE                               # head_dim < 32
+    assert rh(p, 4, 0, 128, 1, p, p, nul) == E.PQ_ERR_SHAPE
+    assert rh(p, 4, 8, 128, 1, nul, p, nul) == E.PQ_ERR_NULL
+    assert rh(p, 4, 8, 128, 1, ctypes.c_void_p(0x1001), p, nul) == E.PQ_ERR_ALIGN
+    assert rh(p, 0, 8, 128, 1, p, p, nul) == E.PQ_OK
+    assert L.pq_rotate_f16(p, 4, 256, 1, p, nul) == E.PQ_ERR_SHAPE                       # nothing to rotate
+    assert L.pq_rotate_f16(p, 4, 256, 96, p, nul) == E.PQ_ERR_SHAPE
+    assert L.pq_rotate_f16(p, 4, 256, 128, nul, nul) == E.PQ_ERR_NULL
+    # fused producers
+    assert L.pq_silu_mul_rotate_quant(p, nul, 4, 256, 128, 0.1, p, nul) == E.PQ_ERR_NULL
+    assert L.pq_silu_mul_rotate_quant(p, p, 4, 250, 1, 0.1, p, nul) == E.PQ_ERR_SHAPE
+    assert L.pq_silu_mul_rotate_quant(p, odd, 4, 256, 128, 0.1, p, nul) == E.PQ_ERR_ALIGN
+    assert L.pq_rmsnorm_quant(p, 4, 256, -1e-6, 0.1, p, nul) == E.PQ_ERR_SCALE
+    assert L.pq_rmsnorm_quant(p, 4, 65536, 1e-6, 0.1, p, nul) == E.PQ_ERR_UNSUPPORTED
+    assert L.pq_rmsnorm_quant(p, 0, 256, 1e-6, 0.1, p, nul) == E.PQ_OK
+    # calibration
+    cal = L.pq_calibrate_static
+    assert cal(p, 0, 256, 1, 4, 8, 0.5, p, p256, 1 << 20, nul) == E.PQ_ERR_SHAPE          # no tokens
+    assert cal(p, 4, 256, 1, 4, 1, 0.5, p, p256, 1 << 20, nul) == E.PQ_ERR_SHAPE
+    assert cal(p, 4, 256, 1, 4, 8, 1.0, p, p256, 1 << 20, nul) == E.PQ_ERR_SCALE
+    assert cal(p, 4, 256, 1, 4, 8, 0.5, p, p256, 16, nul) == E.PQ_ERR_WORKSPACE
+    assert cal(p, 4, 256, 1, 4, 8, 0.5, nul, p256, 1 << 20, nul) == E.PQ_ERR_NULL
+    assert cal(p, 4, 65536, 1, 4, 8, 0.5, p, p256, 1 << 20, nul) == E.PQ_ERR_UNSUPPORTED
