@@ -30,7 +30,7 @@ if ROOT not in sys.path:
 INT8_PEAK_TOPS = 5033.0      # MI355X dense INT8 MFMA: 256 CU x 2.4 GHz x 8192 ops/clk/CU
 HBM_PEAK_GBS = 8000.0
 M_PREFILL = 2048
-EVENT_EVERY = 5             # steps between two event-instrumented steps of the timed region
+EVENT_EVERY = 10            # steps between two event-instrumented steps of the timed region
 # HBM bytes per GEMM launch (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 from rocprofv3 --pmc, averaged over the
 # five launches of a step; see profiles/gemm_prefill_llama3_8b_pmc.md).  Algorithmic: 63.3e6.
 GEMM_HBM_TRAFFIC_BYTES = 124.4e6
