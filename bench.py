@@ -67,6 +67,9 @@ def prepare_layers(torch, synth, M):
 def run_prefill(torch, pq, layers, steps, warmup):
     def step(events=None):
         for L in layers:
+            if events is not None:
+                q0 = torch.cuda.Event(enable_timing=True)
+                q0.record()
             pq.pq_rotate_quant(L["x"], L["h"], L["sx"], out=L["xq"])
             if events is not None:
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -75,6 +78,7 @@ def run_prefill(torch, pq, layers, steps, warmup):
             if events is not None:
                 e1.record()
                 events.append((L["name"], e0, e1))
+                events.append(("rq_" + L["name"], q0, e0))
 
     for _ in range(warmup):
         step()
@@ -90,7 +94,9 @@ def run_prefill(torch, pq, layers, steps, warmup):
     per = {}
     for name, e0, e1 in events:
         per.setdefault(name, []).append(e0.elapsed_time(e1) * 1e-3)
-    return dt / steps, {k: sum(v) / len(v) for k, v in per.items()}
+    avg = {k: sum(v) / len(v) for k, v in per.items()}
+    return dt / steps, {k: v for k, v in avg.items() if not k.startswith("rq_")}, \
+        {k[3:]: v for k, v in avg.items() if k.startswith("rq_")}
 
 
 def run_variants(torch, pq, layers, steps, warmup, ops):
@@ -128,6 +134,21 @@ def run_variants(torch, pq, layers, steps, warmup, ops):
     for L in layers:
         del L["xq8"], L["srow"]
     return res
+
+
+def run_prefill_8192(torch, pq, layers, steps=10, warmup=3):
+    """The same five linears at M = 8192 tokens (the benchmark configuration's second prefill size): wall time
+    per step and per-launch GEMM time from events around every launch."""
+    M = 8192
+    big = []
+    for L in layers:
+        x = L["x"].repeat(M // L["x"].shape[0], 1).contiguous()
+        big.append(dict(L, x=x, xq=torch.empty((M, L["K"] // 2), dtype=torch.uint8, device="cuda"),
+                        out=torch.empty((M, L["N"]), dtype=torch.float16, device="cuda")))
+    t, g, _ = run_prefill(torch, pq, big, steps, warmup)
+    ops = sum(2.0 * M * L["K"] * L["N"] for L in layers)
+    return {"ms_per_step": round(t * 1e3, 4), "TOPS": round(ops / t / 1e12, 1),
+            "per_linear_TOPS": {L["name"]: round(2.0 * M * L["K"] * L["N"] / g[L["name"]] / 1e12, 1) for L in layers}}
 
 
 def run_fp16(torch, layers, steps, warmup):
@@ -228,7 +249,7 @@ def run_side_rows(torch, pq, synth, T):
     return res
 
 
-def run_decode(torch, pq, layers, M=1, reps=3):
+def run_decode(torch, pq, layers, M=1, reps=3, warm=False):
     """Batch-M decode through pq_linear with cold weights: enough distinct copies of each
     weight matrix that more than 1 GiB is touched before one is reused (the matrices fit
     the 256 MB last-level cache otherwise).  The launches are captured in a HIP graph so
@@ -260,7 +281,13 @@ def run_decode(torch, pq, layers, M=1, reps=3):
             best = min(best, e0.elapsed_time(e1) * 1e-3 / ncopy)
         res[L["name"]] = {"us": round(best * 1e6, 2), "GBps": round(nbytes / best / 1e9, 1),
                           "frac_hbm": round(nbytes / best / 1e9 / HBM_PEAK_GBS, 3)}
-        del graph, ws
+        del graph
+        if warm:
+            # one weight buffer replayed: it stays in the last-level cache ("warm / LLC", not an HBM figure)
+            w0 = ws[0]
+            us = graph_time(torch, lambda: pq.pq_linear(x, w0, L["sw"], L["sx"], h, out=out, workspace=work), inner=32)
+            res[L["name"]]["warm_llc_us"] = round(us, 2)
+        del ws
     tot_b = sum(L["N"] * L["K"] // 2 for L in layers)
     tot_t = sum(v["us"] for v in res.values()) * 1e-6
     return {"M": M, "weights": "cold (>1 GiB cycled)", "per_linear": res, "GBps": round(tot_b / tot_t / 1e9, 1),
@@ -277,14 +304,26 @@ def cpu_baseline(synth, rows=256):
         rng = np.random.default_rng([seed, 9])
         wq_packed = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
         prepared.append((x, wq_packed, synth.random_scales(N, seed), np.float32(0.3), h))
+    stage = {"rotate": 0.0, "quantize+pack": 0.0, "product": 0.0, "epilogue": 0.0}
     t0 = time.perf_counter()
-    for x, wq_packed, sw, sx, h in prepared:
-        O.linear(x, wq_packed, sw, sx, h)
+    for x, wq_packed, sw, sx, h in prepared:          # O.linear, stage by stage
+        a = time.perf_counter()
+        y = O.rotate(x, h)
+        b = time.perf_counter()
+        q = O.quantize(y, sx)
+        O.pack(q)
+        c = time.perf_counter()
+        acc = O.gemm_i64(q, O.unpack(wq_packed))
+        d = time.perf_counter()
+        O.epilogue(acc, np.float32(sx), sw)
+        e = time.perf_counter()
+        for k, v in zip(stage, (b - a, c - b, d - c, e - d)):
+            stage[k] += v
     dt = time.perf_counter() - t0
     ops = sum(2.0 * rows * K * N for _, K, N, _ in LINEARS)
     return {"value": round(ops / dt / 1e12, 5), "unit": "TOPS", "cores": O.threads(), "kind": "oracle",
             "sample": "first %d of 2048 tokens, all five linears, whole path (fp64 dense Hadamard, RNE, int64 "
-                      "product, fp64 epilogue), %.1f s" % (rows, dt)}
+                      "product, fp64 epilogue), %.1f s: %s" % (rows, dt, ", ".join("%s %.1f s" % kv for kv in stage.items()))}
 
 
 def main():
@@ -322,7 +361,7 @@ def main():
 
     layers = prepare_layers(torch, synth, M_PREFILL)
     ops = sum(2.0 * M_PREFILL * L["K"] * L["N"] for L in layers)
-    t_step, gemm_t = run_prefill(torch, pq, layers, args.steps, args.warmup)
+    t_step, gemm_t, rq_t = run_prefill(torch, pq, layers, args.steps, args.warmup)
     t_fp16 = run_fp16(torch, layers, max(5, args.steps // 2), max(2, args.warmup // 2))
 
     gemm_ops = {L["name"]: 2.0 * M_PREFILL * L["K"] * L["N"] for L in layers}
@@ -344,6 +383,10 @@ def main():
                                "launches of every %dth timed step)" % EVENT_EVERY,
                      "per_linear_TOPS": {k: round(gemm_ops[k] / v / 1e12, 1) for k, v in gemm_t.items()},
                      "per_linear_us": {k: round(v * 1e6, 1) for k, v in gemm_t.items()}},
+        "rotate_quant": {"bound": "hbm", "per_linear_us": {k: round(v * 1e6, 1) for k, v in rq_t.items()},
+                         "per_linear_GBps": {L["name"]: round(M_PREFILL * L["K"] * 2.5 / rq_t[L["name"]] / 1e9, 1)
+                                             for L in layers},
+                         "note": "pq_rotate_quant launches of the instrumented steps; 2.5 algorithmic bytes per element"},
         "fp16_gemm": {"ms_per_step": round(t_fp16 * 1e3, 4), "TFLOPS": round(ops / t_fp16 / 1e12, 1),
                       "speedup_pq_linear": round(t_fp16 / t_step, 3), "impl": "torch.matmul fp16"},
     }
@@ -353,13 +396,18 @@ def main():
                                "pq_gemm_only_ms": round(sum(gemm_t.values()) * 1e3, 4),
                                "impl": "torch._int_mm (hipBLASLt): int8 x int8 -> int32, no unpack, no epilogue"}
     if not args.no_variants:
+        result["prefill_8192"] = run_prefill_8192(torch, pq, layers)
         result["side_rows"] = run_side_rows(torch, pq, synth, M_PREFILL)
     if not args.no_variants:
         result["variants"] = run_variants(torch, pq, layers, max(5, args.steps // 2), max(2, args.warmup // 2), ops)
         result["variants"]["dynamic_over_static_w4a4"] = round(
             result["variants"]["w4a4_dynamic"]["ms_per_step"] / result["ms_per_step"], 3)
     if not args.no_decode:
-        result["decode"] = run_decode(torch, pq, layers, M=1)
+        result["decode"] = run_decode(torch, pq, layers, M=1, warm=True)
+        for m in (4, 16):
+            d = run_decode(torch, pq, layers, M=m)
+            result["decode"]["M%d" % m] = {"GBps": d["GBps"], "frac_hbm": d["frac_hbm"],
+                                           "per_linear_us": {k: v["us"] for k, v in d["per_linear"].items()}}
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(synth, args.cpu_rows)
     print(json.dumps(result))
