@@ -214,6 +214,29 @@ int pq_silu_mul_rotate_quant(const void* gate_f16, const void* up_f16, int64_t M
 int pq_rmsnorm_quant(const void* x_f16, int64_t M, int64_t K, float eps, float act_scale,
                      void* xq_packed, void* stream);
 
+/* ---- static activation quantizer with a zero-point (Eq. 1 in its general form) ---------------
+ *     X_INT = clamp(round_half_even(y / act_scale) + zero_point, 0, 15),   zero_point in [0, 15];
+ * the stored nibble is the two's-complement code X_INT - 8, so zero_point = 8 is pq_rotate_quant.
+ * The dequantised activation is (X_INT - zero_point) * act_scale, hence for output channel n
+ *     sum_k (X_INT[k] - z) w[n,k] = acc[n] + (8 - z) * sum_k w[n,k]:
+ * the matrix kernels are unchanged and a per-channel integer, prepared once per weight matrix,
+ * joins the accumulator in the epilogue.
+ */
+int pq_rotate_quant_zp(const void* x_f16, int64_t M, int64_t K, int32_t had_block, float act_scale,
+                       int32_t zero_point, void* xq_packed, void* stream);
+
+/* zp_corr[n] = (8 - zero_point) * sum_k wq[n,k]   (device, [N] int32, 16-byte aligned). */
+int pq_zero_point_correction(const void* wq_packed, int64_t N, int64_t K, int32_t zero_point,
+                             int32_t* zp_corr, void* stream);
+
+/* out[m,n] = fp16((acc[m,n] + zp_corr[n]) * (act_scale * w_scale[n])); acc_i32, if given, receives
+ * the raw accumulators (without the correction).  K % 128 == 0, K <= 32768; M <= 8 takes the
+ * weight-streaming kernel, larger M the MFMA tiled kernel.
+ */
+int pq_w4a4_gemm_zp(const void* xq_packed, const void* wq_packed, const float* w_scale,
+                    float act_scale, const int32_t* zp_corr, int64_t M, int64_t N, int64_t K,
+                    void* out_f16, int32_t* acc_i32, void* stream);
+
 /* ---- calibration of the static per-tensor step on the device --------------------------------
  * (Sec. 3 "Initialization of Quantization Parameters": max-min initialisation, and an MSE-based
  * grid search over the quantization parameter for per-tensor static quantization.  The paper

@@ -36,6 +36,10 @@ What is defined here, and the passage of the paper each part follows:
   group_even_odd       storage order of the 8-bit codes (a permutation, no arithmetic): per
                        32 channels the 16 even ones, then the 16 odd ones.
   linear_bits          the whole path with the activation quantizer at `bits` bits.
+  quantize_zp, minmax_params, linear_zp
+                       Eq. 1 in its general form: X_INT = clamp(round(X/s) + z, 0, 2^N - 1) with
+                       s = (gamma max - beta min) / (2^N - 1), z = -round(beta min / s); the stored
+                       code is X_INT - 8; the layer adds (8 - z) sum_k w[n,k] to every accumulator.
   silu_mul, rmsnorm    the elementwise producers that static quantization allows to fuse into the
                        quantizer (Sec. 3 "Dynamic and Static"): silu(g) * u and x / rms(x), fp64.
   calibrate_mse        MSE-based grid search for the static per-tensor step (Sec. 3
@@ -246,6 +250,37 @@ def calibrate_absmax(x_cal, h: int, bits: int = 4) -> np.float32:
     """s_x = fp32(max |rotate(x_cal, h)| / qmax) over a calibration batch."""
     qmax = (1 << (bits - 1)) - 1
     return np.float32(np.max(np.abs(rotate(x_cal, h))) / qmax)
+
+
+def quantize_zp(y, s, z: int, bits: int = 4) -> np.ndarray:
+    """Eq. 1: X_INT = clamp(round_half_even(y / s) + z, 0, 2^bits - 1); returns X_INT (uint8)."""
+    t = np.asarray(y, dtype=np.float64) / np.float64(s)
+    return np.clip(np.rint(t) + int(z), 0, (1 << bits) - 1).astype(np.uint8)
+
+
+def minmax_params(x, gamma: float = 1.0, beta: float = 1.0, bits: int = 4):
+    """Eq. 1's parameters from a tensor: s = fp32((gamma max - beta min) / (2^bits - 1)),
+    z = -round(beta min / s) clamped to the code range; min is taken as min(x, 0), max as max(x, 0)
+    so that zero stays representable."""
+    x64 = np.asarray(x, dtype=np.float64)
+    hi, lo = max(float(x64.max()), 0.0) * gamma, min(float(x64.min()), 0.0) * beta
+    s = np.float32((hi - lo) / ((1 << bits) - 1))
+    if not s > 0:
+        return np.float32(1.0), 0
+    z = int(np.clip(-np.rint(lo / np.float64(s)), 0, (1 << bits) - 1))
+    return s, z
+
+
+def linear_zp(x, wq_packed, s_w, s_x, z: int, h: int):
+    """The layer with a zero-point: rotate -> Eq. 1 -> sum_k (X_INT - z) w -> epilogue."""
+    y = rotate(x, h)
+    u = quantize_zp(y, s_x, z)
+    wq = unpack(wq_packed)
+    c = u.astype(np.int16) - 8                                   # stored two's-complement codes
+    acc = gemm_i64(c.astype(np.int8), wq)
+    corr = (8 - int(z)) * wq.astype(np.int64).sum(axis=1)
+    return {"y": y, "u": u, "codes": c.astype(np.int8), "acc": acc, "corr": corr,
+            "out": epilogue(acc + corr[None, :], np.float32(s_x), s_w)}
 
 
 def silu_mul(gate, up) -> np.ndarray:

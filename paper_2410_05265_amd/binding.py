@@ -41,6 +41,9 @@ SIGNATURES = {
     "pq_rotate_f16": (ctypes.c_int, [_vp, _i64, _i64, _i32, _vp, _vp]),
     "pq_silu_mul_rotate_quant": (ctypes.c_int, [_vp, _vp, _i64, _i64, _i32, _f32, _vp, _vp]),
     "pq_rmsnorm_quant": (ctypes.c_int, [_vp, _i64, _i64, _f32, _f32, _vp, _vp]),
+    "pq_rotate_quant_zp": (ctypes.c_int, [_vp, _i64, _i64, _i32, _f32, _i32, _vp, _vp]),
+    "pq_zero_point_correction": (ctypes.c_int, [_vp, _i64, _i64, _i32, _vp, _vp]),
+    "pq_w4a4_gemm_zp": (ctypes.c_int, [_vp, _vp, _vp, _f32, _vp, _i64, _i64, _i64, _vp, _vp, _vp]),
     "pq_calibrate_workspace_bytes": (_sz, [_i64, _i32]),
     "pq_calibrate_static": (ctypes.c_int, [_vp, _i64, _i64, _i32, _i32, _i32, _f32, _vp, _vp, _sz, _vp]),
 }
@@ -305,6 +308,47 @@ def pq_rmsnorm_quant(x, eps: float, act_scale: float, out=None):
     _check(lib().pq_rmsnorm_quant(_ptr(x), M, K, float(eps), float(act_scale), _ptr(out), _stream()),
            "pq_rmsnorm_quant")
     return out
+
+
+def pq_rotate_quant_zp(x, had_block: int, act_scale: float, zero_point: int, out=None):
+    """x fp16 [M,K] -> packed codes uint8 [M,K/2] of the quantizer with a zero-point (stored code = X_INT - 8)."""
+    _dev(x, torch.float16, "x")
+    M, K = x.shape
+    if out is None:
+        out = torch.empty((M, K // 2), dtype=torch.uint8, device=x.device)
+    _check(lib().pq_rotate_quant_zp(_ptr(x), M, K, int(had_block), float(act_scale), int(zero_point), _ptr(out),
+                                    _stream()), "pq_rotate_quant_zp")
+    return out
+
+
+def pq_zero_point_correction(wq, zero_point: int, out=None):
+    """packed weights [N,K/2] -> int32 [N]: (8 - zero_point) * sum_k wq[n,k]."""
+    _dev(wq, torch.uint8, "wq")
+    N, K = wq.shape[0], wq.shape[1] * 2
+    if out is None:
+        out = torch.empty((N,), dtype=torch.int32, device=wq.device)
+    _check(lib().pq_zero_point_correction(_ptr(wq), N, K, int(zero_point), _ptr(out), _stream()),
+           "pq_zero_point_correction")
+    return out
+
+
+def pq_w4a4_gemm_zp(xq, wq, w_scale, act_scale, zp_corr, want_out=True, want_acc=False, out=None, acc=None):
+    """(acc + zp_corr[n]) * act_scale * w_scale[n] -> (out fp16 | None, raw acc int32 | None)."""
+    _dev(xq, torch.uint8, "xq")
+    _dev(wq, torch.uint8, "wq")
+    _dev(w_scale, torch.float32, "w_scale")
+    _dev(zp_corr, torch.int32, "zp_corr")
+    M, K = xq.shape[0], xq.shape[1] * 2
+    N = wq.shape[0]
+    if wq.shape[1] * 2 != K or w_scale.numel() != N or zp_corr.numel() != N:
+        raise ValueError("shape mismatch")
+    if want_out and out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=xq.device)
+    if want_acc and acc is None:
+        acc = torch.empty((M, N), dtype=torch.int32, device=xq.device)
+    _check(lib().pq_w4a4_gemm_zp(_ptr(xq), _ptr(wq), _ptr(w_scale), float(act_scale), _ptr(zp_corr), M, N, K, _ptr(out),
+                                 _ptr(acc), _stream()), "pq_w4a4_gemm_zp")
+    return out, acc
 
 
 def pq_calibrate_workspace_bytes(T: int, n_grid: int) -> int:

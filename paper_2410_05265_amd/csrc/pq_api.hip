@@ -286,6 +286,48 @@ int pq_rmsnorm_quant(const void* x_f16, int64_t M, int64_t K, float eps, float a
     return pq::launch_rmsnorm_quant(x_f16, M, K, eps, act_scale, xq_packed, static_cast<hipStream_t>(stream));
 }
 
+int pq_rotate_quant_zp(const void* x_f16, int64_t M, int64_t K, int32_t had_block, float act_scale, int32_t zero_point,
+                       void* xq_packed, void* stream)
+{
+    if (M < 0 || K <= 0 || (K % 32) != 0 || zero_point < 0 || zero_point > 15) return PQ_ERR_SHAPE;
+    if (had_block < 0 || had_block > 16384) return PQ_ERR_SHAPE;
+    if (had_block > 1 && ((had_block & (had_block - 1)) != 0 || (K % had_block) != 0)) return PQ_ERR_SHAPE;
+    if (!x_f16 || !xq_packed) return PQ_ERR_NULL;
+    if (!aligned16(x_f16) || !aligned16(xq_packed)) return PQ_ERR_ALIGN;
+    if (!good_scale(act_scale)) return PQ_ERR_SCALE;
+    if (M == 0) return PQ_OK;
+    return pq::launch_rotate_quant_zp(x_f16, M, K, had_block, act_scale, zero_point, xq_packed,
+                                      static_cast<hipStream_t>(stream));
+}
+
+int pq_zero_point_correction(const void* wq_packed, int64_t N, int64_t K, int32_t zero_point, int32_t* zp_corr,
+                             void* stream)
+{
+    if (N <= 0 || N > (1 << 30) || K <= 0 || K > (1 << 24) || (K % 32) != 0 || zero_point < 0 || zero_point > 15)
+        return PQ_ERR_SHAPE;
+    if (!wq_packed || !zp_corr) return PQ_ERR_NULL;
+    if (!aligned16(wq_packed) || !aligned16(zp_corr)) return PQ_ERR_ALIGN;
+    return pq::launch_zero_point_correction(wq_packed, N, K, zero_point, zp_corr, static_cast<hipStream_t>(stream));
+}
+
+int pq_w4a4_gemm_zp(const void* xq_packed, const void* wq_packed, const float* w_scale, float act_scale,
+                    const int32_t* zp_corr, int64_t M, int64_t N, int64_t K, void* out_f16, int32_t* acc_i32,
+                    void* stream)
+{
+    int rc = check_gemm(xq_packed, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32);
+    if (rc != PQ_OK) return rc;
+    if ((K % 128) != 0) return PQ_ERR_SHAPE;
+    if (!zp_corr) return PQ_ERR_NULL;
+    if (!aligned16(zp_corr)) return PQ_ERR_ALIGN;
+    if (K > 32768) return PQ_ERR_UNSUPPORTED;
+    if (M == 0) return PQ_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (M <= 8 && (g_variant == 0 || g_variant == 4) && pq::decode_supported(M, N, K, -1))
+        return pq::launch_decode(nullptr, xq_packed, wq_packed, w_scale, act_scale, 1, M, N, K, out_f16, acc_i32,
+                                 nullptr, st, nullptr, 4, zp_corr);
+    return pq::launch_gemm_zp(xq_packed, wq_packed, w_scale, act_scale, zp_corr, M, N, K, out_f16, acc_i32, st);
+}
+
 size_t pq_calibrate_workspace_bytes(int64_t T, int32_t n_grid)
 {
     if (T <= 0 || n_grid < 2 || n_grid > pq::max_calibration_grid()) return 0;

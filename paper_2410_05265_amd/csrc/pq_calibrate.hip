@@ -52,6 +52,7 @@ struct Capture {
         for (int i = 0; i < NV; ++i) dst[i] = v[i];
     }
     __device__ __forceinline__ void get(int64_t, float& m, float& s) const { m = 0.0f; s = 0.0f; }
+    __device__ __forceinline__ int zero_offset() const { return 0; }
 };
 
 // Rotated (unnormalised) values of one row, NC chunks of 2048 channels, into v; dead entries zero.

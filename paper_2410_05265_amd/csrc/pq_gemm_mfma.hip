@@ -118,7 +118,8 @@ template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_wai
 // workgroup's dynamic shared memory).
 template <int BM, int BN, int WR, int WC, int NS, int SUBS, int ABITS, int ASHIFT>
 __device__ __forceinline__ void gemm_tile(const uint8_t* xq, const uint8_t* wq, const float* sw, float sx, int M, int N,
-                                          int K, int m0, int n0, __half* out, int32_t* acc_out, const float* srow)
+                                          int K, int m0, int n0, __half* out, int32_t* acc_out, const float* srow,
+                                          const int32_t* zcorr)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     constexpr int NW = WR * WC;
@@ -322,8 +323,10 @@ __device__ __forceinline__ void gemm_tile(const uint8_t* xq, const uint8_t* wq, 
     }
     // DYN = false: one static step, folded into the channel scales once per tile column;
     // DYN = true: the token's own step (the lane owns one token per tile row) times the channel scale
-    auto store_out = [&](auto dync) {
-        constexpr bool DYN = decltype(dync)::value;
+    // ZP: a per-channel integer zcorr[n] joins the accumulator before scaling (zero-point of Eq. 1:
+    // sum_k (c_k + 8 - z) w_k = acc + (8 - z) sum_k w_k)
+    auto store_out = [&](auto dync, auto zpc) {
+        constexpr bool DYN = decltype(dync)::value, ZP = decltype(zpc)::value;
         constexpr float kUnshift = 1.0f / (float)(1 << ASHIFT);   // the accumulators hold 2^ASHIFT * acc: exact
         float fm[TM];
 #pragma unroll
@@ -356,10 +359,17 @@ __device__ __forceinline__ void gemm_tile(const uint8_t* xq, const uint8_t* wq, 
 #pragma unroll
                     for (int h2 = 0; h2 < 2; ++h2) {
                         const int q = 2 * qp + h2;
-                        const float f0 = (float)acc[i][j][4 * q + 0] * (DYN ? sc[j][q].x * fm[i] : sc[j][q].x);
-                        const float f1 = (float)acc[i][j][4 * q + 1] * (DYN ? sc[j][q].y * fm[i] : sc[j][q].y);
-                        const float f2 = (float)acc[i][j][4 * q + 2] * (DYN ? sc[j][q].z * fm[i] : sc[j][q].z);
-                        const float f3 = (float)acc[i][j][4 * q + 3] * (DYN ? sc[j][q].w * fm[i] : sc[j][q].w);
+                        v4i zc = {0, 0, 0, 0};
+                        if constexpr (ZP) {   // re-read per use (cache hit): keeps the static path's registers
+                            int n = n0 + wn * WN + j * 32 + 8 * q + 4 * g;
+                            n = n + 4 <= N ? n : N - 4;
+                            zc = *reinterpret_cast<const v4i*>(zcorr + n);
+                            zc.x <<= ASHIFT; zc.y <<= ASHIFT; zc.z <<= ASHIFT; zc.w <<= ASHIFT;
+                        }
+                        const float f0 = (float)(acc[i][j][4 * q + 0] + zc.x) * (DYN ? sc[j][q].x * fm[i] : sc[j][q].x);
+                        const float f1 = (float)(acc[i][j][4 * q + 1] + zc.y) * (DYN ? sc[j][q].y * fm[i] : sc[j][q].y);
+                        const float f2 = (float)(acc[i][j][4 * q + 2] + zc.z) * (DYN ? sc[j][q].z * fm[i] : sc[j][q].z);
+                        const float f3 = (float)(acc[i][j][4 * q + 3] + zc.w) * (DYN ? sc[j][q].w * fm[i] : sc[j][q].w);
                         const __half2 lo = __floats2half2_rn(f0, f1), hi = __floats2half2_rn(f2, f3);
                         pk[2 * h2 + 0] = *reinterpret_cast<const uint32_t*>(&lo);
                         pk[2 * h2 + 1] = *reinterpret_cast<const uint32_t*>(&hi);
@@ -385,8 +395,9 @@ __device__ __forceinline__ void gemm_tile(const uint8_t* xq, const uint8_t* wq, 
         }
     };
     if (out) {
-        if (srow) store_out(std::true_type{});
-        else store_out(std::false_type{});
+        if (zcorr) store_out(std::false_type{}, std::true_type{});   // (static steps only)
+        else if (srow) store_out(std::true_type{}, std::false_type{});
+        else store_out(std::false_type{}, std::false_type{});
     }
 }
 
@@ -396,11 +407,12 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
                                                           const float* __restrict__ sw, float sx, int M, int N,
                                                           int K, int GM, __half* __restrict__ out,
                                                           int32_t* __restrict__ acc_out,
-                                                          const float* __restrict__ srow)
+                                                          const float* __restrict__ srow,
+                                                          const int32_t* __restrict__ zcorr)
 {
     const int tile = xcd_remap(blockIdx.x, gridDim.x);
     gemm_tile<BM, BN, WR, WC, NS, SUBS, ABITS, ASHIFT>(xq, wq, sw, sx, M, N, K, (tile % GM) * BM, (tile / GM) * BN, out,
-                                                       acc_out, srow);
+                                                       acc_out, srow, zcorr);
 }
 
 // Two tile widths in one launch: the first GM * n1 workgroups take tiles BM x BN1 of the columns
@@ -413,23 +425,25 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dual(const uint8_t* __res
                                                            const float* __restrict__ sw, float sx, int M, int N,
                                                            int K, int GM, int n1, int n2, __half* __restrict__ out,
                                                            int32_t* __restrict__ acc_out,
-                                                           const float* __restrict__ srow)
+                                                           const float* __restrict__ srow,
+                                                           const int32_t* __restrict__ zcorr)
 {
     const int first = GM * n1;
     if ((int)blockIdx.x < first) {
         const int tile = xcd_remap(blockIdx.x, first);
         gemm_tile<BM, BN1, WR, WC, NS, 1, 4, 8>(xq, wq, sw, sx, M, N, K, (tile % GM) * BM, (tile / GM) * BN1, out, acc_out,
-                                                srow);
+                                                srow, zcorr);
     } else {
         const int tile = xcd_remap(blockIdx.x - first, GM * n2);
         gemm_tile<BM, BN2, WR, WC, NS, 1, 4, 8>(xq, wq, sw, sx, M, N, K, (tile % GM) * BM, n1 * BN1 + (tile / GM) * BN2, out,
-                                                acc_out, srow);
+                                                acc_out, srow, zcorr);
     }
 }
 
 template <int BM, int BN1, int BN2, int WR, int WC, int NS>
 int launch_dual(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K, int n1,
-                int n2, void* out, int32_t* acc, hipStream_t st, const float* srow = nullptr)
+                int n2, void* out, int32_t* acc, hipStream_t st, const float* srow = nullptr,
+                const int32_t* zcorr = nullptr)
 {
     const int GM = (int)((M + BM - 1) / BM);
     constexpr size_t lds = (size_t)NS * (BM * 64 + (BN1 > BN2 ? BN1 : BN2) * 64);
@@ -444,13 +458,13 @@ int launch_dual(const void* xq, const void* wq, const float* sw, float sx, int64
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)(GM * (n1 + n2))), dim3(WR * WC * 64), lds, st,
                        static_cast<const uint8_t*>(xq), static_cast<const uint8_t*>(wq), sw, sx, (int)M, (int)N,
-                       (int)K, GM, n1, n2, static_cast<__half*>(out), acc, srow);
+                       (int)K, GM, n1, n2, static_cast<__half*>(out), acc, srow, zcorr);
     return hip_status(hipGetLastError());
 }
 
 template <int BM, int BN, int WR, int WC, int NS, int SUBS, int ABITS = 4, int ASHIFT = 8>
 int launch_dma(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K, void* out,
-               int32_t* acc, hipStream_t st, const float* srow = nullptr)
+               int32_t* acc, hipStream_t st, const float* srow = nullptr, const int32_t* zcorr = nullptr)
 {
     const int GM = (int)((M + BM - 1) / BM), GN = (int)((N + BN - 1) / BN);
     constexpr size_t lds = (size_t)NS * SUBS * (BM * (ABITS == 8 ? 128 : 64) + BN * 64);
@@ -465,7 +479,7 @@ int launch_dma(const void* xq, const void* wq, const float* sw, float sx, int64_
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)(GM * GN)), dim3(WR * WC * 64), lds, st,
                        static_cast<const uint8_t*>(xq), static_cast<const uint8_t*>(wq), sw, sx, (int)M, (int)N,
-                       (int)K, GM, static_cast<__half*>(out), acc, srow);
+                       (int)K, GM, static_cast<__half*>(out), acc, srow, zcorr);
     return hip_status(hipGetLastError());
 }
 
@@ -732,6 +746,23 @@ int launch_gemm_dynamic(const void* xq, int32_t bits, const void* wq, const floa
         case 1: return launch_dma<256, 128, 2, 2, 3, 1>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
         case 3: return launch_dma<256, 192, 2, 2, 3, 1>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
         default: return launch_dma<128, 128, 2, 2, 3, 1>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
+    }
+}
+
+// Static steps with a zero-point (Eq. 1): out = (acc + zcorr[n]) * s_x * s_w[n].
+int launch_gemm_zp(const void* xq, const void* wq, const float* sw, float sx, const int32_t* zcorr, int64_t M, int64_t N,
+                   int64_t K, void* out, int32_t* acc, hipStream_t st)
+{
+    if (M > (1 << 30) || N > (1 << 30) || K > 32768 || K % 128 != 0) return PQ_ERR_UNSUPPORTED;
+    if (M * (K / 2) >= ((int64_t)1 << 32) || N * (K / 2) >= ((int64_t)1 << 32)) return PQ_ERR_UNSUPPORTED;
+    int n1 = 0, n2 = 0;
+    if (pick_dual(M, N, &n1, &n2))
+        return launch_dual<256, 256, 192, 2, 2, 3>(xq, wq, sw, sx, M, N, K, n1, n2, out, acc, st, nullptr, zcorr);
+    switch (pick_cfg(M, N)) {
+        case 0: return launch_dma<256, 256, 2, 2, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st, nullptr, zcorr);
+        case 1: return launch_dma<256, 128, 2, 2, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st, nullptr, zcorr);
+        case 3: return launch_dma<256, 192, 2, 2, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st, nullptr, zcorr);
+        default: return launch_dma<128, 128, 2, 2, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st, nullptr, zcorr);
     }
 }
 

@@ -48,4 +48,27 @@ int launch_gemm_simple(const void* xq, const void* wq, const float* sw, float sx
     return PQ_OK;
 }
 
+// corr[n] = (8 - zero_point) * sum_k wq[n,k]: what the zero-point of Eq. 1 adds to every
+// accumulator of output channel n (offline work: one wavefront per weight row).
+namespace {
+__global__ __launch_bounds__(64) void k_zero_point_correction(const uint8_t* __restrict__ wq, int N, int K, int zo8,
+                                                             int32_t* __restrict__ corr)
+{
+    const int n = blockIdx.x, lane = threadIdx.x;
+    const uint32_t* row = reinterpret_cast<const uint32_t*>(wq + (int64_t)n * (K >> 1));
+    int sum = 0;
+    for (int d = lane; d < (K >> 3); d += 64)
+        sum = __builtin_amdgcn_sdot8((int)row[d], 0x11111111, sum, false);   // eight signed nibbles times 1
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
+    if (lane == 0) corr[n] = zo8 * sum;
+}
+}  // namespace
+
+int launch_zero_point_correction(const void* wq, int64_t N, int64_t K, int32_t zero_point, int32_t* corr, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_zero_point_correction, dim3((unsigned)N), dim3(64), 0, st, static_cast<const uint8_t*>(wq),
+                       (int)N, (int)K, 8 - zero_point, corr);
+    return hip_status(hipGetLastError());
+}
+
 }  // namespace pq

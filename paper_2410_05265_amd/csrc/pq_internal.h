@@ -11,6 +11,8 @@ namespace pq {
 // Launchers: arguments are already validated by the C entry points.
 int launch_rotate_quant(const void* x, int64_t M, int64_t K, int32_t h, float act_scale,
                         void* xq, hipStream_t st);
+int launch_rotate_quant_zp(const void* x, int64_t M, int64_t K, int32_t h, float act_scale, int32_t zero_point,
+                           void* xq, hipStream_t st);
 int launch_rotate_quant8(const void* x, int64_t M, int64_t K, int32_t h, float act_scale,
                          void* xq8, hipStream_t st);
 int launch_gemm_w4a8(const void* xq8, const void* wq, const float* sw, float sx, int64_t M,
@@ -29,6 +31,10 @@ int launch_rmsnorm_quant(const void* x, int64_t M, int64_t K, float eps, float a
 int max_calibration_grid();
 int launch_calibrate(const void* x, int64_t T, int64_t K, int32_t h, int32_t bits, int32_t n_grid, float gamma_min,
                      float* result, float* ws, hipStream_t st);
+int launch_gemm_zp(const void* xq, const void* wq, const float* sw, float sx, const int32_t* zcorr, int64_t M,
+                   int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st);
+int launch_zero_point_correction(const void* wq, int64_t N, int64_t K, int32_t zero_point, int32_t* corr,
+                                 hipStream_t st);
 int launch_gemm_simple(const void* xq, const void* wq, const float* sw, float sx, int64_t M,
                        int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st);
 int launch_gemm_mfma(const void* xq, const void* wq, const float* sw, float sx, int64_t M,
@@ -39,7 +45,7 @@ int launch_gemv(const void* xq, const void* wq, const float* sw, float sx, int64
 bool decode_supported(int64_t M, int64_t N, int64_t K, int32_t h, int32_t abits = 4);
 int launch_decode(const void* x_f16, const void* xq_in, const void* wq, const float* sw, float sx, int32_t h,
                   int64_t M, int64_t N, int64_t K, void* out, int32_t* acc, void* xq_out, hipStream_t st,
-                  const float* srow = nullptr, int32_t abits = 4);
+                  const float* srow = nullptr, int32_t abits = 4, const int32_t* zcorr = nullptr);
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? PQ_OK : PQ_ERR_HIP; }
 

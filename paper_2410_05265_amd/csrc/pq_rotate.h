@@ -78,18 +78,21 @@ __device__ __forceinline__ void reg_stages8(float* v, int nstages)
 constexpr float kMagic = 12582920.0f;            // 1.5 * 2^23 + 8, bit pattern 0x4B400008
 constexpr uint32_t kMagicSum = 0x4B400000u * 0x11111111u;  // sum of (pattern - offset part) << 4i
 
+// zo = zero-point - 8 (Eq. 1 with a zero-point z: stored code = clamp(round(t) + z, 0, 15) - 8); 0 for
+// the symmetric quantizer, in which case the compiler drops every trace of it.
 template <bool EXACT>
-__device__ __forceinline__ uint32_t quant_pack8(const float* v, const float* raw, float mult, float step)
+__device__ __forceinline__ uint32_t quant_pack8(const float* v, const float* raw, float mult, float step, int zo = 0)
 {
     float t[8];
     uint32_t bits[8];
     bool suspect = false;
+    const float lo = -8.0f - (float)zo, hi = 7.0f - (float)zo;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         t[i] = v[i] * mult;
-        const float c = __builtin_amdgcn_fmed3f(t[i], -8.0f, 7.0f);
+        const float c = __builtin_amdgcn_fmed3f(t[i], lo, hi);
         const float r = c + kMagic;                 // fp32 add rounds to an integer, ties to even
-        bits[i] = __float_as_uint(r);
+        bits[i] = __float_as_uint(r) + (uint32_t)zo;   // the offset enters after the rounding (integer add)
         if constexpr (EXACT) {
             const float f = c - (r - kMagic);       // exact; |f| <= 0.5
             suspect |= (fabsf(f) > 0.5f - 0x1.0p-18f);
@@ -102,14 +105,14 @@ __device__ __forceinline__ uint32_t quant_pack8(const float* v, const float* raw
         if (__builtin_amdgcn_ballot_w64(suspect) != 0) {   // wave-uniform: a real branch, taken rarely
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const float c = __builtin_amdgcn_fmed3f(t[i], -8.0f, 7.0f);
+                const float c = __builtin_amdgcn_fmed3f(t[i], lo, hi);
                 const float r = c + kMagic;
                 const float f = c - (r - kMagic);
                 if (fabsf(f) > 0.5f - 0x1.0p-18f) {
                     const float k = floorf(t[i]);
                     const float d = fmaf(k + 0.5f, step, -raw[i]);
                     const int ki = (int)k;
-                    int q = d > 0.0f ? ki : (d < 0.0f ? ki + 1 : ((ki & 1) ? ki + 1 : ki));
+                    int q = (d > 0.0f ? ki : (d < 0.0f ? ki + 1 : ((ki & 1) ? ki + 1 : ki))) + zo;
                     q = q < -8 ? -8 : (q > 7 ? 7 : q);
                     bits[i] = 0x4B400008u + (uint32_t)q;
                 }
@@ -172,7 +175,7 @@ __device__ __forceinline__ void quant_bytes8(const float* v, const float* raw, f
 // group of 32 channels the 16 even channels come first, then the 16 odd ones (the order in which
 // the matrix kernel consumes them), so a thread stores two dwords.
 template <int BITS, bool EXACT, typename DST>
-__device__ __forceinline__ void store_codes(const float* v, float mult, float step, DST dst_row, int64_t e0)
+__device__ __forceinline__ void store_codes(const float* v, float mult, float step, DST dst_row, int64_t e0, int zo = 0)
 {
     if constexpr (BITS == 0) {
         // nothing is stored: the caller took the values through its step provider
@@ -186,7 +189,7 @@ __device__ __forceinline__ void store_codes(const float* v, float mult, float st
         }
         *reinterpret_cast<v4i*>(&dst_row[e0 >> 1]) = o;
     } else if constexpr (BITS == 4) {
-        dst_row[e0 >> 3] = quant_pack8<EXACT>(v, v, mult, step);
+        dst_row[e0 >> 3] = quant_pack8<EXACT>(v, v, mult, step, zo);
     } else {
         uint32_t ev, od;
         quant_bytes8<EXACT>(v, v, mult, step, ev, od);
@@ -233,6 +236,17 @@ struct StaticStep {
     template <int NV>
     __device__ __forceinline__ void prepare(const float (&)[NV]) {}
     __device__ __forceinline__ void get(int64_t, float& m, float& s) const { m = mult; s = step; }
+    __device__ __forceinline__ int zero_offset() const { return 0; }
+};
+
+// Per-tensor static step with a zero-point (Eq. 1 in its general form): zo = zero-point - 8.
+struct StaticStepZp {
+    float mult, step;
+    int zo;
+    template <int NV>
+    __device__ __forceinline__ void prepare(const float (&)[NV]) {}
+    __device__ __forceinline__ void get(int64_t, float& m, float& s) const { m = mult; s = step; }
+    __device__ __forceinline__ int zero_offset() const { return zo; }
 };
 
 // Per-head static steps (one per block of 2^log2d consecutive channels), read from device memory;
@@ -248,6 +262,7 @@ struct HeadStep {
         s = scales[e0 >> log2d];
         m = (float)(inv_sqrt_h / (double)s);
     }
+    __device__ __forceinline__ int zero_offset() const { return 0; }
 };
 
 // A step provider has `prepare(values)`, called once after the rotation by every thread of the
@@ -311,7 +326,7 @@ __device__ __forceinline__ void rotate_quant_regs_with(const v4i (&raw)[G], cons
             if (live[g]) {
                 const int64_t e0 = chunk0 + (int64_t)g * kChunk + tid * 8;
                 steps.get(e0, mult, step);
-                store_codes<BITS, true>(v[g], mult, step, dst_row, e0);
+                store_codes<BITS, true>(v[g], mult, step, dst_row, e0, steps.zero_offset());
             }
         }
     } else {
@@ -373,7 +388,7 @@ __device__ __forceinline__ void rotate_quant_regs_with(const v4i (&raw)[G], cons
             if (live[g]) {
                 const int64_t e0 = chunk0 + (int64_t)g * kChunk + tid * 8;
                 steps.get(e0, mult, step);
-                store_codes<BITS, false>(v[g], mult, step, dst_row, e0);
+                store_codes<BITS, false>(v[g], mult, step, dst_row, e0, steps.zero_offset());
             }
         }
     }

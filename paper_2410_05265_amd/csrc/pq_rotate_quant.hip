@@ -150,6 +150,7 @@ struct DynamicStep {
         if (tid == 0) *step_out = step;
     }
     __device__ __forceinline__ void get(int64_t, float& m, float& s) const { m = mult_; s = step_; }
+    __device__ __forceinline__ int zero_offset() const { return 0; }
 };
 
 // Per-token dynamic variant (Table 1 row O1): the step size of a row depends on that row's rotated
@@ -205,6 +206,7 @@ struct NormStep {
         mult_ = (float)(inv_step / sqrt(total * inv_k + (double)eps));
     }
     __device__ __forceinline__ void get(int64_t, float& m, float& s) const { m = mult_; s = step; }
+    __device__ __forceinline__ int zero_offset() const { return 0; }
 };
 
 template <int NC>
@@ -260,6 +262,15 @@ int launch_dyn(const __half* xp, int64_t M, int64_t K, int32_t h, float clip, ui
 int launch_rotate_quant(const void* x, int64_t M, int64_t K, int32_t h, float act_scale, void* xq, hipStream_t st)
 {
     return launch_rq<4>(static_cast<const __half*>(x), M, K, h, static_step(act_scale, h), static_cast<uint32_t*>(xq), st);
+}
+
+// Eq. 1 with a zero-point: stored code = clamp(round(y / s) + z, 0, 15) - 8.
+int launch_rotate_quant_zp(const void* x, int64_t M, int64_t K, int32_t h, float act_scale, int32_t zero_point, void* xq,
+                           hipStream_t st)
+{
+    const rq::StaticStep b = static_step(act_scale, h);
+    return launch_rq<4>(static_cast<const __half*>(x), M, K, h, rq::StaticStepZp{b.mult, b.step, zero_point - 8},
+                        static_cast<uint32_t*>(xq), st);
 }
 
 int launch_rotate_quant8(const void* x, int64_t M, int64_t K, int32_t h, float act_scale, void* xq8, hipStream_t st)

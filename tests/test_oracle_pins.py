@@ -381,3 +381,37 @@ def test_silu_mul_and_rmsnorm_closed_forms():
     yr = O.rmsnorm(xr, 0.0)
     np.testing.assert_allclose(np.mean(yr * yr, axis=1), np.ones(5), rtol=1e-13)           # unit mean square
     np.testing.assert_allclose(O.rmsnorm(3.5 * xr, 0.0), yr, rtol=1e-13)                    # scale invariance
+
+
+# ------------------------------------------------------------------ Eq. 1 with a zero-point
+def test_zero_point_quantizer_and_layer_identity():
+    # the printed formula on a hand-made tensor: max 3.0, min -1.5 -> s = 4.5 / 15 = 0.3, z = -round(-1.5 / 0.3) = 5
+    x = np.array([[3.0, -1.5, 0.0, 0.44, 0.45, 1.0, -0.15, 9.0]])
+    s, z = O.minmax_params(x[:, :7])
+    assert s == np.float32(0.3) and z == 5
+    u = O.quantize_zp(x, s, z)
+    # 3/0.3 = 10 (+5 = 15); -1.5 -> -5 + 5 = 0; 0 -> 5; 0.44 -> 1.4667 -> 1 -> 6; 0.45/fp32(0.3) = 1.49999.. -> 1 -> 6;
+    # 1 -> 3.33 -> 3 -> 8; -0.15 -> -0.49999.. -> 0 -> 5; 9 -> 30 + 5 -> clamp 15
+    assert np.array_equal(u, [[15, 0, 5, 6, 6, 8, 5, 15]])
+    # z = 8 is the symmetric quantizer
+    y = np.random.default_rng(2).standard_normal((6, 64)) * 3
+    assert np.array_equal(O.quantize_zp(y, np.float32(0.7), 8).astype(np.int16) - 8, O.quantize(y, np.float32(0.7)))
+    # dequantisation error at most half a step inside the representable range [(0 - z) s, (15 - z) s]
+    s2, z2 = O.minmax_params(y)
+    u2 = O.quantize_zp(y, s2, z2).astype(np.float64)
+    assert np.all(np.abs((u2 - z2) * np.float64(s2) - y) <= 0.5 * np.float64(s2) * (1 + 1e-9) + 1e-12)
+    # one-sided data (what follows a gate such as silu): the zero-point halves the step of the symmetric quantizer
+    pos = np.abs(y)
+    sp, zp = O.minmax_params(pos)
+    assert zp == 0 and abs(float(sp) - pos.max() / 15) < 1e-6 and float(sp) < 0.5 * pos.max() / 7 * 1.08
+    # the layer: sum_k (X_INT - z) w computed directly equals accumulator + correction
+    x16 = synth.activations(5, 128, seed=3)
+    wq, sw = O.weight_rtn(synth.weights(16, 128, seed=3))
+    s3, z3 = O.minmax_params(O.rotate(x16, 128))
+    r = O.linear_zp(x16, O.pack(wq), sw, s3, z3, 128)
+    direct = (r["u"].astype(np.int64) - z3) @ wq.astype(np.int64).T
+    assert np.array_equal(r["acc"] + r["corr"][None, :], direct)
+    deq = ((r["u"].astype(np.float64) - z3) * np.float64(s3)) @ (wq.astype(np.float64) * sw.astype(np.float64)[:, None]).T
+    np.testing.assert_allclose(r["out"].astype(np.float64), deq, rtol=2 ** -10, atol=1e-7)
+    # all-zero tensor: step 1, zero-point 0
+    assert O.minmax_params(np.zeros((2, 8))) == (np.float32(1.0), 0)
