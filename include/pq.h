@@ -257,6 +257,21 @@ int pq_calibrate_static(const void* x_cal_f16, int64_t T, int64_t K, int32_t had
                         int32_t n_grid, float gamma_min, float* result, void* workspace,
                         size_t workspace_bytes, void* stream);
 
+/* The same search for Eq. 1 with a zero-point (4 bits): candidates are pairs of clipping factors,
+ *     gamma_i = 1 - i (1 - gamma_min) / (n_gamma - 1) on hi = max(y, 0),
+ *     beta_j  = 1 - j (1 - beta_min)  / (n_beta - 1)  on lo = min(y, 0)      (a single value: factor 1),
+ *     s = fp32((gamma_i hi - beta_j lo) / 15),  z = clamp(-round(beta_j lo / s), 0, 15),
+ *     err = sum (y - s (clamp(round(y / s) + z, 0, 15) - z))^2,   candidate index c = i * n_beta + j.
+ * result (device, fp32, 6 + n_gamma * n_beta entries): [0] s and [1] z of the arg-min (lowest index on
+ * a tie), [2] s and [3] z of candidate 0 (max-min initialisation), [4] i and [5] j of the arg-min,
+ * [6 + c] err_c.  1 <= n_gamma, n_beta and n_gamma * n_beta in [2, 128]; other arguments as
+ * pq_calibrate_static; workspace pq_calibrate_zp_workspace_bytes(T, n_gamma * n_beta).
+ */
+size_t pq_calibrate_zp_workspace_bytes(int64_t T, int32_t n_candidates);
+int pq_calibrate_static_zp(const void* x_cal_f16, int64_t T, int64_t K, int32_t had_block,
+                           int32_t n_gamma, int32_t n_beta, float gamma_min, float beta_min,
+                           float* result, void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -320,6 +320,34 @@ def calibrate_mse(x_cal, h: int, bits: int = 4, n_grid: int = 50, gamma_min: flo
     return {"best": best, "s": steps[best], "s_max": steps[0], "gamma": gammas[best], "errs": errs, "steps": steps}
 
 
+def calibrate_mse_zp(x_cal, h: int, n_gamma: int = 8, n_beta: int = 8, gamma_min: float = 0.5, beta_min: float = 0.5):
+    """Grid search over Eq. 1's parameters: gamma_i on hi = max(y, 0), beta_j on lo = min(y, 0) (linear grids
+    from 1 down to the minima; a grid of one point is the factor 1), s = fp32((gamma hi - beta lo) / 15),
+    z = clamp(-round(beta lo / s), 0, 15), err = sum (y - s (Q - z))^2; candidate index i * n_beta + j.
+
+    Returns {"best", "s", "z", "errs" fp64 [n], "steps" fp32 [n], "zeros" int [n]}.
+    """
+    y = rotate(x_cal, h)
+    hi, lo = max(float(y.max()), 0.0), min(float(y.min()), 0.0)
+    n = n_gamma * n_beta
+    steps, zeros, errs = np.empty(n, np.float32), np.empty(n, np.int64), np.empty(n, np.float64)
+    for i in range(n_gamma):
+        g = 1.0 - i * (1.0 - np.float64(gamma_min)) / (n_gamma - 1) if n_gamma > 1 else 1.0
+        for j in range(n_beta):
+            b = 1.0 - j * (1.0 - np.float64(beta_min)) / (n_beta - 1) if n_beta > 1 else 1.0
+            s = np.float32((g * hi - b * lo) / 15.0)
+            if not s > 0:
+                s, z = np.float32(1.0), 0
+            else:
+                z = int(np.clip(-np.rint(b * lo / np.float64(s)), 0, 15))
+            c = i * n_beta + j
+            steps[c], zeros[c] = s, z
+            u = quantize_zp(y, s, z).astype(np.float64)
+            errs[c] = np.sum((y - np.float64(s) * (u - z)) ** 2)
+    best = int(np.argmin(errs))
+    return {"best": best, "s": steps[best], "z": int(zeros[best]), "errs": errs, "steps": steps, "zeros": zeros}
+
+
 # ----------------------------------------------------------------------------- path
 def linear(x, wq_packed, s_w, s_x, h: int, return_all: bool = False):
     """Whole path: rotate -> quantize -> pack -> int64 product -> epilogue."""

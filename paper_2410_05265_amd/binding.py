@@ -45,6 +45,8 @@ SIGNATURES = {
     "pq_zero_point_correction": (ctypes.c_int, [_vp, _i64, _i64, _i32, _vp, _vp]),
     "pq_w4a4_gemm_zp": (ctypes.c_int, [_vp, _vp, _vp, _f32, _vp, _i64, _i64, _i64, _vp, _vp, _vp]),
     "pq_calibrate_workspace_bytes": (_sz, [_i64, _i32]),
+    "pq_calibrate_zp_workspace_bytes": (_sz, [_i64, _i32]),
+    "pq_calibrate_static_zp": (ctypes.c_int, [_vp, _i64, _i64, _i32, _i32, _i32, _f32, _f32, _vp, _vp, _sz, _vp]),
     "pq_calibrate_static": (ctypes.c_int, [_vp, _i64, _i64, _i32, _i32, _i32, _f32, _vp, _vp, _sz, _vp]),
 }
 
@@ -365,6 +367,25 @@ def pq_calibrate_static(x_cal, had_block: int, bits: int = 4, n_grid: int = 50, 
     res = torch.empty((3 + n_grid,), dtype=torch.float32, device=x_cal.device)
     _check(lib().pq_calibrate_static(_ptr(x_cal), T, K, int(had_block), int(bits), int(n_grid), float(gamma_min),
                                      _ptr(res), _ptr(ws), ws.numel(), _stream()), "pq_calibrate_static")
+    return res
+
+
+def pq_calibrate_zp_workspace_bytes(T: int, n_candidates: int) -> int:
+    return int(lib().pq_calibrate_zp_workspace_bytes(T, int(n_candidates)))
+
+
+def pq_calibrate_static_zp(x_cal, had_block: int, n_gamma: int = 8, n_beta: int = 8, gamma_min: float = 0.5,
+                           beta_min: float = 0.5):
+    """MSE grid search over Eq. 1's (s, z) on the device.  Returns fp32 [6 + n_gamma * n_beta]: best s, best z,
+    max-min s and z, arg-min (i, j), then the squared error of every candidate (index i * n_beta + j)."""
+    _dev(x_cal, torch.float16, "x_cal")
+    T, K = x_cal.shape
+    n = n_gamma * n_beta
+    ws = torch.empty((max(pq_calibrate_zp_workspace_bytes(T, n), 256),), dtype=torch.uint8, device=x_cal.device)
+    res = torch.empty((6 + n,), dtype=torch.float32, device=x_cal.device)
+    _check(lib().pq_calibrate_static_zp(_ptr(x_cal), T, K, int(had_block), int(n_gamma), int(n_beta), float(gamma_min),
+                                        float(beta_min), _ptr(res), _ptr(ws), ws.numel(), _stream()),
+           "pq_calibrate_static_zp")
     return res
 
 

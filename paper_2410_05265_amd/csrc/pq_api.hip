@@ -353,6 +353,31 @@ int pq_calibrate_static(const void* x_cal_f16, int64_t T, int64_t K, int32_t had
                                 static_cast<float*>(workspace), static_cast<hipStream_t>(stream));
 }
 
+size_t pq_calibrate_zp_workspace_bytes(int64_t T, int32_t n_candidates)
+{
+    if (T <= 0 || n_candidates < 2 || n_candidates > pq::max_calibration_grid()) return 0;
+    return (((size_t)T * (size_t)(n_candidates + 2)) * 4 + 255) & ~(size_t)255;
+}
+
+int pq_calibrate_static_zp(const void* x_cal_f16, int64_t T, int64_t K, int32_t had_block, int32_t n_gamma,
+                           int32_t n_beta, float gamma_min, float beta_min, float* result, void* workspace,
+                           size_t workspace_bytes, void* stream)
+{
+    if (T <= 0 || K <= 0 || (K % 32) != 0 || n_gamma < 1 || n_beta < 1) return PQ_ERR_SHAPE;
+    const int64_t n = (int64_t)n_gamma * n_beta;
+    if (n < 2 || n > pq::max_calibration_grid()) return PQ_ERR_SHAPE;
+    if (had_block < 0 || had_block > 16384) return PQ_ERR_SHAPE;
+    if (had_block > 1 && ((had_block & (had_block - 1)) != 0 || (K % had_block) != 0)) return PQ_ERR_SHAPE;
+    if (!x_cal_f16 || !result) return PQ_ERR_NULL;
+    if (!aligned16(x_cal_f16) || (reinterpret_cast<uintptr_t>(result) & 3u)) return PQ_ERR_ALIGN;
+    if (!(gamma_min > 0.0f && gamma_min < 1.0f) || !(beta_min > 0.0f && beta_min < 1.0f)) return PQ_ERR_SCALE;
+    if (!workspace || workspace_bytes < pq_calibrate_zp_workspace_bytes(T, (int32_t)n)) return PQ_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return PQ_ERR_ALIGN;
+    if (K > 32768) return PQ_ERR_UNSUPPORTED;
+    return pq::launch_calibrate_zp(x_cal_f16, T, K, had_block, n_gamma, n_beta, gamma_min, beta_min, result,
+                                   static_cast<float*>(workspace), static_cast<hipStream_t>(stream));
+}
+
 int pq_set_gemm_variant(int variant)
 {
     if (variant < 0 || variant > 4) return -1;

@@ -35,6 +35,8 @@ int launch_gemm_zp(const void* xq, const void* wq, const float* sw, float sx, co
                    int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st);
 int launch_zero_point_correction(const void* wq, int64_t N, int64_t K, int32_t zero_point, int32_t* corr,
                                  hipStream_t st);
+int launch_calibrate_zp(const void* x, int64_t T, int64_t K, int32_t h, int32_t ng, int32_t nb, float gamma_min,
+                        float beta_min, float* result, float* ws, hipStream_t st);
 int launch_gemm_simple(const void* xq, const void* wq, const float* sw, float sx, int64_t M,
                        int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st);
 int launch_gemm_mfma(const void* xq, const void* wq, const float* sw, float sx, int64_t M,

@@ -51,6 +51,7 @@ def test_host_only_calls(b):
     assert L.pq_linear_dynamic_workspace_bytes(3, 4096, 5) == 0
     assert L.pq_calibrate_workspace_bytes(256, 50) == 256 * 51 * 4
     assert L.pq_calibrate_workspace_bytes(256, 1) == 0 and L.pq_calibrate_workspace_bytes(256, 129) == 0
+    assert L.pq_calibrate_zp_workspace_bytes(256, 64) == 256 * 66 * 4 and L.pq_calibrate_zp_workspace_bytes(256, 1) == 0
 
 
 def test_argument_errors_launch_nothing(b):

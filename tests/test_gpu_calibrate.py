@@ -39,6 +39,7 @@ def test_calibration_matches_oracle(pq, T, K, h, bits, n_grid, gmin):
     if T > 2:
         x = x.copy()
         x[0, 0] = np.float16(np.abs(x).max() * 3)          # an outlier, so that clipping can pay
+    gmin = float(np.float32(gmin))                                       # what the C ABI's float argument carries
     ref = O.calibrate_mse(x, h, bits, n_grid, gmin)
     res = host(pq.pq_calibrate_static(dev(x), h, bits, n_grid, gmin))
     errs = res[3:].astype(np.float64)
@@ -88,4 +89,48 @@ def test_calibration_argument_errors(pq):
         args.update(kw)
         with pytest.raises(pq.PQError) as e:
             pq.pq_calibrate_static(x, args["had_block"], args["bits"], args["n_grid"], args["gamma_min"])
+        assert e.value.status == status, kw
+
+
+@pytest.mark.parametrize("T,K,h,ng,nb,gmin,bmin,onesided", [(16, 512, 1, 6, 1, 0.3, 0.5, True), (64, 4096, 1, 8, 8, 0.5, 0.5, False),
+                                                            (33, 14336, 128, 5, 4, 0.4, 0.6, False), (8, 4096, 4096, 1, 9, 0.5, 0.3, False),
+                                                            (256, 4096, 1, 16, 8, 0.25, 0.25, True), (3, 28672, 128, 2, 2, 0.5, 0.5, False)])
+def test_zero_point_search_matches_oracle(pq, T, K, h, ng, nb, gmin, bmin, onesided):
+    x = synth.calibration(K, seed=5)[:T].copy()
+    if onesided:
+        x = np.abs(x)
+    x[0, 0] = np.float16(np.abs(x).max() * 3)
+    gmin, bmin = float(np.float32(gmin)), float(np.float32(bmin))        # what the C ABI's float arguments carry
+    ref = O.calibrate_mse_zp(x, h, ng, nb, gmin, bmin)
+    res = host(pq.pq_calibrate_static_zp(dev(x), h, ng, nb, gmin, bmin))
+    errs = res[6:].astype(np.float64)
+    np.testing.assert_allclose(errs, ref["errs"], rtol=1e-4, atol=1e-12)
+    best = int(res[4]) * nb + int(res[5])
+    assert best == int(np.argmin(errs))
+    assert ref["errs"][best] <= ref["errs"].min() * (1 + 2e-4)
+    assert f32_ulps(res[0], ref["steps"][best]) <= (0 if h <= 1 else 4) and int(res[1]) == ref["zeros"][best]
+    assert f32_ulps(res[2], ref["steps"][0]) <= (0 if h <= 1 else 4) and int(res[3]) == ref["zeros"][0]
+
+
+def test_zero_point_search_feeds_the_quantizer(pq):
+    # one-sided activations: the searched (s, z) gives a lower layer error than the symmetric absmax step
+    M, K, N = 64, 4096, 512
+    x, xc = np.abs(synth.activations(M, K, seed=12)), np.abs(synth.calibration(K, seed=12))
+    wq, sw = O.weight_rtn(synth.weights(N, K, seed=12))
+    res = host(pq.pq_calibrate_static_zp(dev(xc), 1, 10, 1, 0.3, 0.5))
+    s, z = float(res[0]), int(res[1])
+    d_w = dev(O.pack(wq))
+    out, _ = pq.pq_w4a4_gemm_zp(pq.pq_rotate_quant_zp(dev(x), 1, s, z), d_w, dev(sw), s, pq.pq_zero_point_correction(d_w, z))
+    exact = x.astype(np.float64) @ (wq.astype(np.float64) * sw.astype(np.float64)[:, None]).T
+    o_sym, _ = pq.pq_linear(dev(x), d_w, dev(sw), float(np.abs(xc.astype(np.float64)).max() / 7), 1)
+    assert np.linalg.norm(host(out) - exact) < 0.6 * np.linalg.norm(host(o_sym) - exact)
+
+
+def test_zero_point_search_argument_errors(pq):
+    x = dev(np.ones((2, 256), dtype=np.float16))
+    for kw, status in ((dict(ng=1, nb=1), 2), (dict(ng=16, nb=9), 2), (dict(gmin=1.0), 4), (dict(bmin=0.0), 4)):
+        a = dict(ng=4, nb=4, gmin=0.5, bmin=0.5)
+        a.update(kw)
+        with pytest.raises(pq.PQError) as e:
+            pq.pq_calibrate_static_zp(x, 1, a["ng"], a["nb"], a["gmin"], a["bmin"])
         assert e.value.status == status, kw

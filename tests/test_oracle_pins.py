@@ -415,3 +415,34 @@ def test_zero_point_quantizer_and_layer_identity():
     np.testing.assert_allclose(r["out"].astype(np.float64), deq, rtol=2 ** -10, atol=1e-7)
     # all-zero tensor: step 1, zero-point 0
     assert O.minmax_params(np.zeros((2, 8))) == (np.float32(1.0), 0)
+
+
+def test_calibrate_mse_zp_candidates_and_optimum():
+    rng = np.random.default_rng(8)
+    x = np.abs(rng.standard_normal((8, 64)) * 0.5).astype(np.float16)        # one-sided
+    x[0, 0] = 6.0                                                            # an outlier worth clipping
+    r = O.calibrate_mse_zp(x, 1, n_gamma=6, n_beta=1, gamma_min=0.2)
+    # candidate 0 is the max-min initialisation of Eq. 1
+    s0, z0 = O.minmax_params(x)
+    assert r["steps"][0] == s0 and r["zeros"][0] == z0 == 0
+    # brute force of one candidate in plain Python
+    c = 3
+    g = 1.0 - c * 0.8 / 5
+    s = float(np.float32(g * float(x.max()) / 15.0))
+    e = 0.0
+    for v in x.astype(np.float64).ravel():
+        q = min(max(round(v / s), 0), 15)            # Python's round is half-to-even; z = 0
+        e += (v - s * q) ** 2
+    assert abs(r["errs"][c] - e) <= 1e-9 * e
+    assert r["best"] > 0 and r["errs"][r["best"]] < r["errs"][0]
+    # two-sided data with both grids: index i * n_beta + j, z follows the clipped minimum
+    y = (rng.standard_normal((4, 128)) * 2 + 1.0).astype(np.float16)
+    r2 = O.calibrate_mse_zp(y, 1, n_gamma=3, n_beta=4, gamma_min=0.5, beta_min=0.4)
+    hi, lo = float(y.max()), float(y.min())
+    i, j = 2, 3
+    s_ij = np.float32((0.5 * hi - 0.4 * lo) / 15.0)
+    assert r2["steps"][i * 4 + j] == s_ij and r2["zeros"][i * 4 + j] == int(-np.rint(0.4 * lo / np.float64(s_ij)))
+    assert r2["best"] == int(np.argmin(r2["errs"])) and r2["z"] == r2["zeros"][r2["best"]]
+    # a single-point grid on both sides is refused by the library; the oracle just returns the max-min candidate
+    r3 = O.calibrate_mse_zp(y, 1, n_gamma=1, n_beta=1)
+    assert r3["best"] == 0 and (r3["s"], r3["z"]) == O.minmax_params(y)
