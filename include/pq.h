@@ -188,6 +188,17 @@ int pq_linear_dynamic(const void* x_f16, const void* wq_packed, const float* w_s
 int pq_rotate_quant_heads(const void* x_f16, int64_t T, int32_t n_heads, int32_t head_dim,
                           int32_t rotate, const float* head_scale, void* xq_packed, void* stream);
 
+/* Group-wise dynamic variant (Table 1 row O1, "KV cache: group-wise dynamic"): every group of
+ * `group` consecutive channels of a token (32, 64 or 128; a head or a part of one) gets its own step
+ *     group_scale[t, c / group] = fp32(clip * max |y| over the group / 7)   (1 for a group of zeros),
+ * codes as in pq_rotate_quant_heads with that step.  head_dim: rotation block when rotate != 0 (a power
+ * of two in [32, 2048], a multiple of group); C = n_heads * head_dim channels per token.
+ * group_scale: out, device, [T, C / group] fp32.  clip in (0, 1].
+ */
+int pq_rotate_quant_groups(const void* x_f16, int64_t T, int32_t n_heads, int32_t head_dim,
+                           int32_t rotate, int32_t group, float clip, void* xq_packed,
+                           float* group_scale, void* stream);
+
 /* Rotation only (queries after RoPE): y = fp16(rotation of x) with blocks of had_block channels,
  * had_block a power of two in [2, 16384] dividing K; K % 32 == 0.  y_f16: out [M,K] fp16; may not
  * alias x_f16.  fp32 butterflies, one rounding to fp16.

@@ -45,6 +45,7 @@ What is defined here, and the passage of the paper each part follows:
   calibrate_mse        MSE-based grid search for the static per-tensor step (Sec. 3
                        "Initialization of Quantization Parameters"); the paper scores candidates by
                        model block outputs, this build by the tensor's own reconstruction error.
+  quantize_groups_dynamic  one step per token and group of consecutive channels (Table 1 row O1, KV cache).
   quantize_heads       per-head static steps (Table 1 row O2, KV cache): the step of channel c is
                        s[c // head_dim]; with rotate() at block = head_dim this is the online R3
                        rotation of the keys followed by their cache quantizer (App. B).
@@ -123,6 +124,20 @@ def quantize_heads(y, s_heads, head_dim: int, bits: int = 4) -> np.ndarray:
     assert s.shape == (C,)
     lo, hi = -(1 << (bits - 1)), (1 << (bits - 1)) - 1
     return np.clip(np.rint(y64 / s[None, :]), lo, hi).astype(np.int8)
+
+
+def quantize_groups_dynamic(y, group: int, clip: float = 1.0, bits: int = 4):
+    """Group-wise dynamic quantization (Table 1 row O1, KV cache): one step per token and group of `group`
+    consecutive channels, s[t, g] = fp32(clip * max |y[t, g*group:(g+1)*group]| / qmax), 1 for a group of zeros.
+    Returns (codes int8 [T, C], s fp32 [T, C / group])."""
+    y64 = np.asarray(y, dtype=np.float64)
+    T, C = y64.shape
+    qmax = (1 << (bits - 1)) - 1
+    yg = y64.reshape(T, C // group, group)
+    s = (np.float64(clip) * np.max(np.abs(yg), axis=2) / qmax).astype(np.float32)
+    s = np.where(s > 0, s, np.float32(1.0)).astype(np.float32)
+    q = np.clip(np.rint(yg / s.astype(np.float64)[:, :, None]), -qmax - 1, qmax).astype(np.int8)
+    return q.reshape(T, C), s
 
 
 def quantize_dynamic(y, clip: float = 1.0, bits: int = 4):

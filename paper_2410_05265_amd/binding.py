@@ -38,6 +38,7 @@ SIGNATURES = {
     "pq_linear_dynamic_workspace_bytes": (_sz, [_i64, _i64, _i32]),
     "pq_linear_dynamic": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i32, _i32, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
     "pq_rotate_quant_heads": (ctypes.c_int, [_vp, _i64, _i32, _i32, _i32, _vp, _vp, _vp]),
+    "pq_rotate_quant_groups": (ctypes.c_int, [_vp, _i64, _i32, _i32, _i32, _i32, _f32, _vp, _vp, _vp]),
     "pq_rotate_f16": (ctypes.c_int, [_vp, _i64, _i64, _i32, _vp, _vp]),
     "pq_silu_mul_rotate_quant": (ctypes.c_int, [_vp, _vp, _i64, _i64, _i32, _f32, _vp, _vp]),
     "pq_rmsnorm_quant": (ctypes.c_int, [_vp, _i64, _i64, _f32, _f32, _vp, _vp]),
@@ -276,6 +277,21 @@ def pq_rotate_quant_heads(x, n_heads: int, rotate: bool, head_scale, out=None):
     _check(lib().pq_rotate_quant_heads(_ptr(x), T, int(n_heads), C // n_heads, int(bool(rotate)), _ptr(head_scale),
                                        _ptr(out), _stream()), "pq_rotate_quant_heads")
     return out
+
+
+def pq_rotate_quant_groups(x, n_heads: int, rotate: bool, group: int = 128, clip: float = 1.0, out=None, scales=None):
+    """x fp16 [T, n_heads*head_dim] -> (packed codes uint8 [T, C/2], group steps fp32 [T, C/group])."""
+    _dev(x, torch.float16, "x")
+    T, C = x.shape
+    if C % n_heads:
+        raise ValueError("shape mismatch")
+    if out is None:
+        out = torch.empty((T, C // 2), dtype=torch.uint8, device=x.device)
+    if scales is None:
+        scales = torch.empty((T, C // group), dtype=torch.float32, device=x.device)
+    _check(lib().pq_rotate_quant_groups(_ptr(x), T, int(n_heads), C // n_heads, int(bool(rotate)), int(group),
+                                        float(clip), _ptr(out), _ptr(scales), _stream()), "pq_rotate_quant_groups")
+    return out, scales
 
 
 def pq_rotate_f16(x, had_block: int, out=None):

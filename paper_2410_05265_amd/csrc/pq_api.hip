@@ -251,6 +251,21 @@ int pq_rotate_quant_heads(const void* x_f16, int64_t T, int32_t n_heads, int32_t
                                          head_scale, xq_packed, static_cast<hipStream_t>(stream));
 }
 
+int pq_rotate_quant_groups(const void* x_f16, int64_t T, int32_t n_heads, int32_t head_dim, int32_t rotate,
+                           int32_t group, float clip, void* xq_packed, float* group_scale, void* stream)
+{
+    if (T < 0 || n_heads <= 0 || head_dim < 32 || head_dim > 2048 || (head_dim & (head_dim - 1)) != 0)
+        return PQ_ERR_SHAPE;
+    if ((group != 32 && group != 64 && group != 128) || (head_dim % group) != 0) return PQ_ERR_SHAPE;
+    if (!x_f16 || !xq_packed || !group_scale) return PQ_ERR_NULL;
+    if (!aligned16(x_f16) || !aligned16(xq_packed) || (reinterpret_cast<uintptr_t>(group_scale) & 3u))
+        return PQ_ERR_ALIGN;
+    if (!(isfinite(clip) && clip > 0.0f && clip <= 1.0f)) return PQ_ERR_SCALE;
+    if (T == 0) return PQ_OK;
+    return pq::launch_rotate_quant_groups(x_f16, T, (int64_t)n_heads * head_dim, group, rotate ? head_dim : 1, clip,
+                                          xq_packed, group_scale, static_cast<hipStream_t>(stream));
+}
+
 int pq_rotate_f16(const void* x_f16, int64_t M, int64_t K, int32_t had_block, void* y_f16, void* stream)
 {
     if (M < 0 || K <= 0 || (K % 32) != 0) return PQ_ERR_SHAPE;

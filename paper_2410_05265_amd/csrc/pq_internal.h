@@ -28,6 +28,8 @@ int launch_silu_mul_rotate_quant(const void* gate, const void* up, int64_t M, in
                                  float act_scale, void* xq, hipStream_t st);
 int launch_rmsnorm_quant(const void* x, int64_t M, int64_t K, float eps, float act_scale, void* xq,
                          hipStream_t st);
+int launch_rotate_quant_groups(const void* x, int64_t M, int64_t K, int32_t group, int32_t h, float clip, void* xq,
+                               float* group_scale, hipStream_t st);
 int max_calibration_grid();
 int launch_calibrate(const void* x, int64_t T, int64_t K, int32_t h, int32_t bits, int32_t n_grid, float gamma_min,
                      float* result, float* ws, hipStream_t st);

@@ -76,6 +76,68 @@ __global__ __launch_bounds__(kThreads) void k_silu_mul_rotate_quant(const __half
                                                 rq::SiluGate{rawu[r]});
 }
 
+// Group-wise dynamic steps (Table 1 row O1, KV cache): every group of 2^log2gs consecutive channels
+// of a token (gs = 32, 64 or 128: 4, 8 or 16 neighbouring lanes) gets s = fp32(clip * max|y| / 7) of
+// its own rotated values; the steps go to scale_row[channel / gs] of the token's row.
+template <int G>
+struct GroupDynStep {
+    double inv_sqrt_h;
+    float clip;
+    int log2gs;
+    float* scale_base;       // [rows][K / gs]
+    int64_t groups_per_row;
+    int64_t row;
+    int lane;
+    float mult_[G], step_[G];
+    template <int NV>
+    __device__ __forceinline__ void prepare(const float (&v)[NV])
+    {
+        static_assert(NV == G * 8, "one group of 8 values per chunk");
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            float a = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) a = fmaxf(a, fabsf(v[g * 8 + i]));
+            a = fmaxf(a, rq::lane_xor<0>(a));
+            a = fmaxf(a, rq::lane_xor<1>(a));
+            if (log2gs > 5) a = fmaxf(a, rq::lane_xor<2>(a));
+            if (log2gs > 6) a = fmaxf(a, rq::lane_xor<3>(a));
+            float st = (float)(((double)clip * ((double)a * inv_sqrt_h)) / 7.0);
+            if (!(st > 0.0f)) st = 1.0f;
+            step_[g] = st;
+            mult_[g] = (float)(inv_sqrt_h / (double)st);
+        }
+    }
+    __device__ __forceinline__ void get(int64_t e0, float& m, float& s) const
+    {
+        const int g = (int)(e0 >> 11) & (G - 1);      // chunks start at multiples of 2048 G
+        m = mult_[0];
+        s = step_[0];
+#pragma unroll
+        for (int i = 1; i < G; ++i)
+            if (g == i) { m = mult_[i]; s = step_[i]; }
+        if ((lane & ((1 << (log2gs - 3)) - 1)) == 0) scale_base[row * groups_per_row + (e0 >> log2gs)] = s;
+    }
+    __device__ __forceinline__ int zero_offset() const { return 0; }
+};
+
+template <int G, bool EXACT>
+__global__ __launch_bounds__(kThreads) void k_rotate_quant_groups(const __half* __restrict__ x, int64_t M, int64_t K,
+                                                                 int log2h, double inv_sqrt_h, float clip, int log2gs,
+                                                                 uint32_t* __restrict__ xq,
+                                                                 float* __restrict__ group_scale)
+{
+    __shared__ float xch[EXACT ? 1 : G * kChunk];
+    const int64_t row = blockIdx.y;
+    const int64_t chunk0 = (int64_t)blockIdx.x * (G * kChunk);
+    v4i raw[G];
+    bool live[G];
+    rq::load_chunk<G>(static_cast<const __half*>(x + row * K), K, chunk0, threadIdx.x, true, raw, live);
+    GroupDynStep<G> steps{inv_sqrt_h, clip, log2gs, group_scale, K >> log2gs, row, (int)(threadIdx.x & 63), {}, {}};
+    rq::rotate_quant_regs_with<G, EXACT, 4>(raw, live, chunk0, log2h, steps, static_cast<uint32_t*>(xq + row * (K >> 3)),
+                                            (rq::lds_f32_ptr)xch, threadIdx.x, true);
+}
+
 // `steps` already carries the 1/sqrt(h) factor of the reciprocal step.
 template <int BITS, typename STEPS>
 int launch_rq(const __half* xp, int64_t M, int64_t K, int32_t h, STEPS steps, uint32_t* op, hipStream_t st)
@@ -345,6 +407,31 @@ int launch_rmsnorm_quant(const void* x, int64_t M, int64_t K, float eps, float a
     else if (nc <= 8) hipLaunchKernelGGL(k_rmsnorm_quant<8>, grid, block, 0, st, xp, K, inv_step, eps, act_scale, op);
     else hipLaunchKernelGGL(k_rmsnorm_quant<16>, grid, block, 0, st, xp, K, inv_step, eps, act_scale, op);
     return hip_status(hipGetLastError());
+}
+
+int launch_rotate_quant_groups(const void* x, int64_t M, int64_t K, int32_t group, int32_t h, float clip, void* xq,
+                               float* group_scale, hipStream_t st)
+{
+    const __half* xp = static_cast<const __half*>(x);
+    uint32_t* op = static_cast<uint32_t*>(xq);
+    int log2gs = 0, log2h = 0;
+    while ((1 << log2gs) < group) ++log2gs;
+    while ((1 << log2h) < h) ++log2h;
+    const double inv_sqrt_h = h > 1 ? 1.0 / sqrt((double)h) : 1.0;
+    const int G = h <= kChunk ? 1 : h / kChunk;
+    for (int64_t m0 = 0; m0 < M; m0 += 65535) {   // grid.y is limited to 65535 per launch
+        const int64_t mm = (M - m0 < 65535) ? (M - m0) : 65535;
+        dim3 grid((unsigned)((K + (int64_t)G * kChunk - 1) / ((int64_t)G * kChunk)), (unsigned)mm);
+        const __half* xs = xp + m0 * K;
+        uint32_t* os = op + m0 * (K >> 3);
+        float* gs = group_scale + m0 * (K >> log2gs);
+        if (h <= 1) hipLaunchKernelGGL((k_rotate_quant_groups<1, true>), grid, dim3(kThreads), 0, st, xs, mm, K, 0, inv_sqrt_h, clip, log2gs, os, gs);
+        else if (G == 1) hipLaunchKernelGGL((k_rotate_quant_groups<1, false>), grid, dim3(kThreads), 0, st, xs, mm, K, log2h, inv_sqrt_h, clip, log2gs, os, gs);
+        else return PQ_ERR_UNSUPPORTED;
+        const int rc = hip_status(hipGetLastError());
+        if (rc != PQ_OK) return rc;
+    }
+    return PQ_OK;
 }
 
 }  // namespace pq

@@ -107,3 +107,51 @@ def test_heads_argument_errors(pq):
     assert e.value.status == 2
     out = pq.pq_rotate_quant_heads(x, 3, False, s)
     assert np.array_equal(O.unpack(host(out)), np.ones((2, 96), dtype=np.int8))
+
+
+def f32_ulps(a, b):
+    ia = np.asarray(a, dtype=np.float32).view(np.int32).astype(np.int64)
+    ib = np.asarray(b, dtype=np.float32).view(np.int32).astype(np.int64)
+    return np.abs(ia - ib)
+
+
+@pytest.mark.parametrize("group", [32, 64, 128])
+@pytest.mark.parametrize("T,H,D,clip", [(33, 8, 128, 1.0), (7, 32, 128, 0.875), (300, 2, 256, 1.0), (2049, 8, 128, 1.0)])
+def test_groups_dynamic_values_exact(pq, group, T, H, D, clip):
+    x = synth.activations(T, H * D, seed=61)
+    if T > 2:
+        x[1, :group] = 0
+    want_q, want_s = O.quantize_groups_dynamic(x, group, clip)
+    q, s = pq.pq_rotate_quant_groups(dev(x), H, False, group, clip)
+    assert np.array_equal(host(s), want_s)
+    assert np.array_equal(O.unpack(host(q)), want_q)
+
+
+@pytest.mark.parametrize("group", [32, 128])
+@pytest.mark.parametrize("T,H,D", [(33, 8, 128), (7, 32, 128), (5, 4, 256), (3, 3, 2048)])
+def test_groups_dynamic_keys_rotated(pq, group, T, H, D):
+    x = synth.activations(T, H * D, seed=62)
+    y = O.rotate(x, D)
+    want_q, want_s = O.quantize_groups_dynamic(y, group)
+    q, s = pq.pq_rotate_quant_groups(dev(x), H, True, group, 1.0)
+    assert f32_ulps(host(s), want_s).max() <= 4
+    got = O.unpack(host(q))
+    d = np.nonzero(got != want_q)
+    assert d[0].size <= 1e-3 * got.size
+    if d[0].size:
+        t = y[d] / want_s.astype(np.float64)[d[0], d[1] // group]
+        assert np.all(np.abs(got[d].astype(int) - want_q[d]) == 1)
+        assert np.all(np.abs(t - (np.minimum(got[d], want_q[d]) + 0.5)) <= 1e-3)
+
+
+def test_groups_argument_errors(pq):
+    x = dev(np.ones((2, 256), dtype=np.float16))
+    with pytest.raises(pq.PQError) as e:
+        pq.pq_rotate_quant_groups(x, 2, True, 48)
+    assert e.value.status == 2
+    with pytest.raises(pq.PQError) as e:
+        pq.pq_rotate_quant_groups(dev(np.ones((2, 128), dtype=np.float16)), 2, True, 128)      # head_dim 64 < group
+    assert e.value.status == 2
+    with pytest.raises(pq.PQError) as e:
+        pq.pq_rotate_quant_groups(x, 2, True, 64, 0.0)
+    assert e.value.status == 4

@@ -446,3 +446,19 @@ def test_calibrate_mse_zp_candidates_and_optimum():
     # a single-point grid on both sides is refused by the library; the oracle just returns the max-min candidate
     r3 = O.calibrate_mse_zp(y, 1, n_gamma=1, n_beta=1)
     assert r3["best"] == 0 and (r3["s"], r3["z"]) == O.minmax_params(y)
+
+
+def test_quantize_groups_dynamic_is_the_per_token_quantizer_per_group():
+    rng = np.random.default_rng(12)
+    y = rng.standard_normal((6, 256)) * np.exp(rng.standard_normal((1, 256)))
+    y[2, 64:128] = 0                                              # a group of zeros: step 1, codes 0
+    q, s = O.quantize_groups_dynamic(y, 64, clip=0.75)
+    assert q.shape == (6, 256) and s.shape == (6, 4) and s.dtype == np.float32
+    for g in range(4):                                            # each group alone is quantize_dynamic of that slice
+        qg, sg = O.quantize_dynamic(y[:, 64 * g:64 * (g + 1)], 0.75)
+        assert np.array_equal(q[:, 64 * g:64 * (g + 1)], qg) and np.array_equal(s[:, g], sg)
+    assert s[2, 1] == 1.0 and not q[2, 64:128].any()
+    q1, s1 = O.quantize_groups_dynamic(y, 256)                    # one group = the whole row
+    q2, s2 = O.quantize_dynamic(y)
+    assert np.array_equal(q1, q2) and np.array_equal(s1[:, 0], s2)
+    assert np.all(np.abs(q1).max(axis=1) == 7)                    # with clip = 1 the extreme of a row sits on +-7
