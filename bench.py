@@ -404,6 +404,16 @@ def main():
             result["variants"]["w4a4_dynamic"]["ms_per_step"] / result["ms_per_step"], 3)
     if not args.no_decode:
         result["decode"] = run_decode(torch, pq, layers, M=1, warm=True)
+        # gate and up share their input: stored as one [28672, 4096] matrix they stream in one launch
+        gate, up = layers[2], layers[3]
+        fused = dict(gate, name="gate_up", N=gate["N"] + up["N"], wq=torch.cat([gate["wq"], up["wq"]]).contiguous(),
+                     sw=torch.cat([gate["sw"], up["sw"]]).contiguous())
+        gu = run_decode(torch, pq, [fused], M=1)["per_linear"]["gate_up"]
+        pl = result["decode"]["per_linear"]
+        t_block = (pl["qkv"]["us"] + pl["o"]["us"] + gu["us"] + pl["down"]["us"]) * 1e-6
+        b_block = sum(L["N"] * L["K"] // 2 for L in layers)
+        result["decode"]["gate_up_one_launch"] = dict(gu, block_GBps=round(b_block / t_block / 1e9, 1),
+                                                      block_frac_hbm=round(b_block / t_block / 1e9 / HBM_PEAK_GBS, 3))
         for m in (4, 16):
             d = run_decode(torch, pq, layers, M=m)
             result["decode"]["M%d" % m] = {"GBps": d["GBps"], "frac_hbm": d["frac_hbm"],
