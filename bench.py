@@ -120,8 +120,20 @@ def run_variants(torch, pq, layers, steps, warmup, ops):
                 pq.pq_gemm_dynamic(q, bits, L["wq"], L["sw"], L["srow"], out=L["out"])
         return step
 
+    # gate and up read the same tensor in the model: one quantization and one [28672, 4096] weight matrix
+    gate, up = layers[2], layers[3]
+    gu = dict(gate, wq=torch.cat([gate["wq"], up["wq"]]).contiguous(), sw=torch.cat([gate["sw"], up["sw"]]).contiguous(),
+              out=torch.empty((M, gate["N"] + up["N"]), dtype=torch.float16, device="cuda"))
+    fused_layers = [layers[0], layers[1], gu, layers[4]]
+
+    def gate_up_one_matrix():
+        for L in fused_layers:
+            pq.pq_rotate_quant(L["x"], L["h"], L["sx"], out=L["xq"])
+            pq.pq_w4a4_gemm(L["xq"], L["wq"], L["sw"], L["sx"], out=L["out"])
+
     res = {}
-    for name, step in (("w4a8_static", w4a8_static), ("w4a4_dynamic", dynamic(4)), ("w4a8_dynamic", dynamic(8))):
+    for name, step in (("w4a8_static", w4a8_static), ("w4a4_dynamic", dynamic(4)), ("w4a8_dynamic", dynamic(8)),
+                       ("w4a4_static_gate_up_one_matrix", gate_up_one_matrix)):
         for _ in range(warmup):
             step()
         torch.cuda.synchronize()
