@@ -1,6 +1,8 @@
 // Decode in ONE launch of one workgroup per CU: rotate + quantize the few activation rows
-// (M <= 4) into LDS, or take given codes (M <= 8), and stream the packed weight matrix once (Sec. 3 of the paper: weight quantization speeds
-// up memory-bound computation; Sec. 5.4, decoding column).
+// (M <= 4) into LDS, or take given codes (M <= 8; 4-bit packed or 8-bit), and stream the packed
+// weight matrix once (Sec. 3 of the paper: weight quantization speeds up memory-bound computation;
+// Sec. 5.4, decoding column).  Per-token steps and the zero-point correction of Eq. 1 enter in the
+// epilogue when given.
 //
 // At these sizes a linear is 8-30 MB of weights, i.e. 32-112 KB per CU: the kernel is a single
 // burst of loads and its duration is launch + memory latency + bytes / bandwidth, so
@@ -20,7 +22,6 @@ namespace {
 using rq::kChunk;
 
 
-constexpr int kLoads = 8;   // 16-byte weight loads a lane keeps in flight
 
 // Fold V per-lane values over the 64 lanes.  Stage b halves the number of values a lane keeps
 // (lanes with bit b clear keep the first half, the others the second half), so the whole

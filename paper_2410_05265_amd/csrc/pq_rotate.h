@@ -1,6 +1,8 @@
-// Device-side building blocks of the online rotation + static 4-bit quantizer, shared by the
-// stand-alone kernel and the fused decode kernel (App. B "Online Rotation" and Eq. 1 of the
-// paper in its symmetric form).  A workgroup of 256 threads transforms one chunk of a row.
+// Device-side building blocks of the online rotation + quantizer, shared by the stand-alone
+// kernels, the fused decode kernel and the calibration kernels (App. B "Online Rotation" and Eq. 1
+// of the paper).  A workgroup of 256 threads transforms one chunk of a row; what the quantizer's
+// step is (static, per head, per token, per group, with a zero-point) comes from a step provider,
+// and an input transform can fuse an elementwise producer in front.
 #pragma once
 
 #include "pq_internal.h"
