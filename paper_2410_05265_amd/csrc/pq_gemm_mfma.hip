@@ -419,7 +419,7 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dma(const uint8_t* __rest
 // [0, n1 * BN1), the others tiles BM x BN2 of the rest.  Workgroups are dispatched in index order,
 // so with GM * n1 = GM * n2 = number of CUs every CU computes one tile of each width and no CU idles
 // through a partial last round (gate/up: 14336 = 32 x 256 + 32 x 192).
-template <int BM, int BN1, int BN2, int WR, int WC, int NS>
+template <int BM, int BN1, int BN2, int WR, int WC, int NS, int ABITS, int ASHIFT>
 __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dual(const uint8_t* __restrict__ xq,
                                                            const uint8_t* __restrict__ wq,
                                                            const float* __restrict__ sw, float sx, int M, int N,
@@ -431,24 +431,24 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dual(const uint8_t* __res
     const int first = GM * n1;
     if ((int)blockIdx.x < first) {
         const int tile = xcd_remap(blockIdx.x, first);
-        gemm_tile<BM, BN1, WR, WC, NS, 1, 4, 8>(xq, wq, sw, sx, M, N, K, (tile % GM) * BM, (tile / GM) * BN1, out, acc_out,
+        gemm_tile<BM, BN1, WR, WC, NS, 1, ABITS, ASHIFT>(xq, wq, sw, sx, M, N, K, (tile % GM) * BM, (tile / GM) * BN1, out, acc_out,
                                                 srow, zcorr);
     } else {
         const int tile = xcd_remap(blockIdx.x - first, GM * n2);
-        gemm_tile<BM, BN2, WR, WC, NS, 1, 4, 8>(xq, wq, sw, sx, M, N, K, (tile % GM) * BM, n1 * BN1 + (tile / GM) * BN2, out,
+        gemm_tile<BM, BN2, WR, WC, NS, 1, ABITS, ASHIFT>(xq, wq, sw, sx, M, N, K, (tile % GM) * BM, n1 * BN1 + (tile / GM) * BN2, out,
                                                 acc_out, srow, zcorr);
     }
 }
 
-template <int BM, int BN1, int BN2, int WR, int WC, int NS>
+template <int BM, int BN1, int BN2, int WR, int WC, int NS, int ABITS = 4, int ASHIFT = 8>
 int launch_dual(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K, int n1,
                 int n2, void* out, int32_t* acc, hipStream_t st, const float* srow = nullptr,
                 const int32_t* zcorr = nullptr)
 {
     const int GM = (int)((M + BM - 1) / BM);
-    constexpr size_t lds = (size_t)NS * (BM * 64 + (BN1 > BN2 ? BN1 : BN2) * 64);
+    constexpr size_t lds = (size_t)NS * (BM * (ABITS == 8 ? 128 : 64) + (BN1 > BN2 ? BN1 : BN2) * 64);
     static_assert(lds <= 160 * 1024, "LDS ring too large");
-    auto kern = k_gemm_dual<BM, BN1, BN2, WR, WC, NS>;
+    auto kern = k_gemm_dual<BM, BN1, BN2, WR, WC, NS, ABITS, ASHIFT>;
     static bool attr_set = false;  // benign race: the call is idempotent
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -714,6 +714,9 @@ int launch_gemm_w4a8(const void* xq8, const void* wq, const float* sw, float sx,
 {
     if (M > (1 << 30) || N > (1 << 30) || K > 65536 || K % 128 != 0) return PQ_ERR_UNSUPPORTED;
     if (M * K >= ((int64_t)1 << 32) || N * (K / 2) >= ((int64_t)1 << 32)) return PQ_ERR_UNSUPPORTED;
+    int n1 = 0, n2 = 0;
+    if (pick_dual(M, N, &n1, &n2))
+        return launch_dual<256, 256, 192, 2, 2, 3, 8, 4>(xq8, wq, sw, sx, M, N, K, n1, n2, out, acc, st);
     switch (pick_cfg(M, N)) {
         case 0: return launch_dma<256, 256, 2, 2, 3, 1, 8, 4>(xq8, wq, sw, sx, M, N, K, out, acc, st);
         case 1: return launch_dma<256, 128, 2, 2, 3, 1, 8, 4>(xq8, wq, sw, sx, M, N, K, out, acc, st);
@@ -730,7 +733,10 @@ int launch_gemm_dynamic(const void* xq, int32_t bits, const void* wq, const floa
     if (M > (1 << 30) || N > (1 << 30) || K > 65536 || K % 128 != 0) return PQ_ERR_UNSUPPORTED;
     if (M * K >= ((int64_t)1 << 32) || N * (K / 2) >= ((int64_t)1 << 32)) return PQ_ERR_UNSUPPORTED;
     const int cfg = pick_cfg(M, N);
+    int n1 = 0, n2 = 0;
+    const bool dual = pick_dual(M, N, &n1, &n2);
     if (bits == 8) {
+        if (dual) return launch_dual<256, 256, 192, 2, 2, 3, 8, 4>(xq, wq, sw, 1.0f, M, N, K, n1, n2, out, acc, st, srow);
         switch (cfg) {
             case 0: return launch_dma<256, 256, 2, 2, 3, 1, 8, 4>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
             case 1: return launch_dma<256, 128, 2, 2, 3, 1, 8, 4>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
@@ -738,9 +744,7 @@ int launch_gemm_dynamic(const void* xq, int32_t bits, const void* wq, const floa
             default: return launch_dma<128, 128, 2, 2, 3, 1, 8, 4>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
         }
     }
-    int n1 = 0, n2 = 0;
-    if (pick_dual(M, N, &n1, &n2))
-        return launch_dual<256, 256, 192, 2, 2, 3>(xq, wq, sw, 1.0f, M, N, K, n1, n2, out, acc, st, srow);
+    if (dual) return launch_dual<256, 256, 192, 2, 2, 3>(xq, wq, sw, 1.0f, M, N, K, n1, n2, out, acc, st, srow);
     switch (cfg) {
         case 0: return launch_dma<256, 256, 2, 2, 3, 1>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
         case 1: return launch_dma<256, 128, 2, 2, 3, 1>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);

@@ -77,7 +77,7 @@ def test_dynamic_codes_and_steps_rotated(pq, bits, M, K, h, clip):
 
 @pytest.mark.parametrize("bits", [4, 8])
 @pytest.mark.parametrize("M,N,K", [(16, 512, 512), (1, 128, 128), (5, 272, 384), (255, 400, 1152), (257, 512, 2048),
-                                   (130, 1040, 14336), (300, 6144, 512)])
+                                   (130, 1040, 14336), (300, 6144, 512), (1900, 14336, 128)])
 def test_dynamic_product_and_epilogue(pq, bits, M, N, K):
     lo, hi = (-128, 127) if bits == 8 else (-8, 7)
     q = synth.random_codes(M, K, seed=M + K, stream=9, lo=lo, hi=hi)

@@ -71,7 +71,8 @@ def test_codes8_rotated(pq, M, K, h):
 
 # ------------------------------------------------------------------ product + epilogue
 SHAPES = [(16, 512, 512), (1, 128, 128), (3, 48, 256), (5, 272, 384), (64, 128, 128), (255, 400, 1152),
-          (257, 512, 2048), (130, 1040, 14336), (2047, 256, 512), (300, 6144, 512), (513, 768, 1024)]
+          (257, 512, 2048), (130, 1040, 14336), (2047, 256, 512), (300, 6144, 512), (513, 768, 1024),
+          (1900, 14336, 128), (2048, 14336, 256)]      # the last two: one launch mixes 256- and 192-wide tiles
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
