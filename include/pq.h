@@ -99,11 +99,16 @@ int pq_w4a4_gemm_simple(const void* xq_packed, const void* wq_packed, const floa
                         void* out_f16, int32_t* acc_i32, void* stream);
 
 /* Force a kernel variant of pq_w4a4_gemm for sweeps and tests (host, process-wide,
- * not thread-safe): 0 = automatic, 1 = weight-streaming matrix tiles (M <= 16 only),
- * 2 = MFMA tiled, 3 = simple, 4 = weight-streaming 4-bit dot products (M <= 8 only).  With 4
- * pq_linear uses its fused single launch whenever the shape allows it; with 1, 2 or 3 it
- * always uses two launches.  pq_w4a8_gemm and pq_gemm_dynamic use their weight-streaming kernel
- * (M <= 8) only with 0 or 4.  Returns the previous value, or -1 if `variant` is unknown.
+ * not thread-safe): 0 = automatic, 1 = weight-streaming matrix tiles (M <= 16, K % 256 == 0 and
+ * the tokens' codes fit in LDS; else PQ_ERR_UNSUPPORTED), 2 = MFMA tiled, 3 = simple,
+ * 4 = weight-streaming 4-bit dot products (M <= 8 only).  With 4 pq_linear uses its fused single
+ * launch whenever the shape allows it; with 1, 2 or 3 it always uses two launches.
+ * pq_w4a8_gemm, pq_gemm_dynamic and pq_w4a4_gemm_zp use a weight-streaming kernel only with 0,
+ * or with 1 or 4 where that kernel supports the shape, and the tiled kernel otherwise.  The
+ * automatic choice for given codes: dot products up to 4 tokens (8 when K < 8192; with int8
+ * activations 2, or 4 when K < 8192), matrix tiles up to 16, tiled beyond.  Every kernel gives the
+ * same accumulators and the same fp16 outputs bit for bit.
+ * Returns the previous value, or -1 if `variant` is unknown.
  */
 int pq_set_gemm_variant(int variant);
 

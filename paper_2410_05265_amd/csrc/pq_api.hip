@@ -8,6 +8,25 @@ namespace {
 
 int g_variant = 0;  // 0 auto, 1 streaming MFMA (M <= 16), 2 MFMA tiled, 3 simple, 4 streaming dot (M <= 8)
 
+// Kernel for a product with given codes and few tokens: 4 = weight-streaming dot products
+// (k_decode), 1 = weight-streaming matrix tiles (k_stream_mfma), 2 = the tiled kernel, -1 = the
+// forced variant does not support the shape.  Measured on the Llama-3-8B shapes: the dot-product
+// kernel wins up to 4 tokens (with int8 activations up to 2; to 4 on short rows), the matrix
+// kernel from 5 tokens on long rows and from 9 everywhere.
+int pick_few_tokens(int64_t M, int64_t N, int64_t K, int32_t abits)
+{
+    const bool dot = M <= 8 && pq::decode_supported(M, N, K, -1, abits);
+    const bool mat = M <= 16 && pq::stream_mfma_supported(M, N, K, abits);
+    if (g_variant == 4) return dot ? 4 : -1;
+    if (g_variant == 1) return mat ? 1 : -1;
+    if (g_variant != 0) return 2;
+    const bool long_rows = K >= 8192;
+    const int64_t dot_limit = abits == 8 ? (long_rows ? 2 : 4) : (long_rows ? 4 : 8);
+    if (dot && (M <= dot_limit || !mat)) return 4;
+    if (mat) return 1;
+    return 2;
+}
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool good_scale(float s) { return isfinite(s) && s > 0.0f; }
 
@@ -64,18 +83,15 @@ int pq_w4a4_gemm(const void* xq_packed, const void* wq_packed, const float* w_sc
     if (rc != PQ_OK) return rc;
     if (M == 0) return PQ_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    int v = g_variant;
-    if (v == 0) v = (M <= 8 && pq::decode_supported(M, N, K, -1)) ? 4 : ((M <= 16) ? 1 : 2);
-    switch (v) {
+    if (g_variant == 3)
+        return pq::launch_gemm_simple(xq_packed, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32, st);
+    switch (pick_few_tokens(M, N, K, 4)) {
         case 4:
-            if (!pq::decode_supported(M, N, K, -1)) return PQ_ERR_UNSUPPORTED;
             return pq::launch_decode(nullptr, xq_packed, wq_packed, w_scale, act_scale, 1, M, N, K, out_f16, acc_i32,
                                      nullptr, st);
-        case 1:
-            if (M > 16) return PQ_ERR_UNSUPPORTED;
-            return pq::launch_gemv(xq_packed, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32, st);
+        case 1: return pq::launch_stream_mfma(xq_packed, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32, st);
         case 2: return pq::launch_gemm_mfma(xq_packed, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32, st);
-        default: return pq::launch_gemm_simple(xq_packed, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32, st);
+        default: return PQ_ERR_UNSUPPORTED;
     }
 }
 
@@ -143,9 +159,13 @@ int pq_w4a8_gemm(const void* xq8_grouped, const void* wq_packed, const float* w_
     if (rc != PQ_OK) return rc;
     if ((K % 128) != 0) return PQ_ERR_SHAPE;
     if (M == 0) return PQ_OK;
-    if (M <= 8 && (g_variant == 0 || g_variant == 4) && pq::decode_supported(M, N, K, -1, 8))
+    const int few = pick_few_tokens(M, N, K, 8);
+    if (few == 4)
         return pq::launch_decode(nullptr, xq8_grouped, wq_packed, w_scale, act_scale, 1, M, N, K, out_f16, acc_i32,
                                  nullptr, static_cast<hipStream_t>(stream), nullptr, 8);
+    if (few == 1)
+        return pq::launch_stream_mfma(xq8_grouped, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32,
+                                      static_cast<hipStream_t>(stream), nullptr, 8);
     return pq::launch_gemm_w4a8(xq8_grouped, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32,
                                 static_cast<hipStream_t>(stream));
 }
@@ -203,10 +223,14 @@ int pq_gemm_dynamic(const void* xq, int32_t bits, const void* wq_packed, const f
     if (!row_scale) return PQ_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(row_scale) & 3u) return PQ_ERR_ALIGN;
     if (M == 0) return PQ_OK;
-    // decode: the weight-streaming kernel with the token's step in its epilogue
-    if (M <= 8 && (g_variant == 0 || g_variant == 4) && pq::decode_supported(M, N, K, -1, bits))
+    // decode: a weight-streaming kernel with the token's step in its epilogue
+    const int few = pick_few_tokens(M, N, K, bits);
+    if (few == 4)
         return pq::launch_decode(nullptr, xq, wq_packed, w_scale, 1.0f, 1, M, N, K, out_f16, acc_i32, nullptr,
                                  static_cast<hipStream_t>(stream), row_scale, bits);
+    if (few == 1)
+        return pq::launch_stream_mfma(xq, wq_packed, w_scale, 1.0f, M, N, K, out_f16, acc_i32,
+                                      static_cast<hipStream_t>(stream), row_scale, bits);
     return pq::launch_gemm_dynamic(xq, bits, wq_packed, w_scale, row_scale, M, N, K, out_f16, acc_i32,
                                    static_cast<hipStream_t>(stream));
 }
@@ -339,9 +363,13 @@ int pq_w4a4_gemm_zp(const void* xq_packed, const void* wq_packed, const float* w
     if (K > 32768) return PQ_ERR_UNSUPPORTED;
     if (M == 0) return PQ_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (M <= 8 && (g_variant == 0 || g_variant == 4) && pq::decode_supported(M, N, K, -1))
+    const int few = pick_few_tokens(M, N, K, 4);
+    if (few == 4)
         return pq::launch_decode(nullptr, xq_packed, wq_packed, w_scale, act_scale, 1, M, N, K, out_f16, acc_i32,
                                  nullptr, st, nullptr, 4, zp_corr);
+    if (few == 1)
+        return pq::launch_stream_mfma(xq_packed, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32, st, nullptr,
+                                      4, zp_corr);
     return pq::launch_gemm_zp(xq_packed, wq_packed, w_scale, act_scale, zp_corr, M, N, K, out_f16, acc_i32, st);
 }
 

@@ -237,7 +237,7 @@ __global__ __launch_bounds__(1024) void k_decode(const __half* __restrict__ x, c
                 const int total = ABITS == 8 ? p[0] >> 4 : p[0];
                 if (acc_out) acc_out[(int64_t)m * N + n] = total;
                 const int shifted = total + (zcorr ? zcorr[n] : 0);   // zero-point correction of Eq. 1, if any
-                if (out) out[(int64_t)m * N + n] = __float2half_rn((float)shifted * ((srow ? srow[m] : sx) * sw[n]));
+                if (out) out[(int64_t)m * N + n] = __float2half_rn(mul_rn((float)shifted, (srow ? srow[m] : sx) * sw[n]));
             }
         }
     }

@@ -366,10 +366,10 @@ __device__ __forceinline__ void gemm_tile(const uint8_t* xq, const uint8_t* wq, 
                             zc = *reinterpret_cast<const v4i*>(zcorr + n);
                             zc.x <<= ASHIFT; zc.y <<= ASHIFT; zc.z <<= ASHIFT; zc.w <<= ASHIFT;
                         }
-                        const float f0 = (float)(acc[i][j][4 * q + 0] + zc.x) * (DYN ? sc[j][q].x * fm[i] : sc[j][q].x);
-                        const float f1 = (float)(acc[i][j][4 * q + 1] + zc.y) * (DYN ? sc[j][q].y * fm[i] : sc[j][q].y);
-                        const float f2 = (float)(acc[i][j][4 * q + 2] + zc.z) * (DYN ? sc[j][q].z * fm[i] : sc[j][q].z);
-                        const float f3 = (float)(acc[i][j][4 * q + 3] + zc.w) * (DYN ? sc[j][q].w * fm[i] : sc[j][q].w);
+                        const float f0 = mul_rn((float)(acc[i][j][4 * q + 0] + zc.x), DYN ? sc[j][q].x * fm[i] : sc[j][q].x);
+                        const float f1 = mul_rn((float)(acc[i][j][4 * q + 1] + zc.y), DYN ? sc[j][q].y * fm[i] : sc[j][q].y);
+                        const float f2 = mul_rn((float)(acc[i][j][4 * q + 2] + zc.z), DYN ? sc[j][q].z * fm[i] : sc[j][q].z);
+                        const float f3 = mul_rn((float)(acc[i][j][4 * q + 3] + zc.w), DYN ? sc[j][q].w * fm[i] : sc[j][q].w);
                         const __half2 lo = __floats2half2_rn(f0, f1), hi = __floats2half2_rn(f2, f3);
                         pk[2 * h2 + 0] = *reinterpret_cast<const uint32_t*>(&lo);
                         pk[2 * h2 + 1] = *reinterpret_cast<const uint32_t*>(&hi);
@@ -592,7 +592,7 @@ __global__ __launch_bounds__(256) void k_gemm_ragged(const uint8_t* __restrict__
                 if (m < M) {
                     const int a = acc[i][j][v] >> 8;
                     if (acc_out) acc_out[(int64_t)m * N + n] = a;
-                    if (out) out[(int64_t)m * N + n] = __float2half_rn((float)a * sc);
+                    if (out) out[(int64_t)m * N + n] = __float2half_rn(mul_rn((float)a, sc));
                 }
             }
         }

@@ -27,7 +27,7 @@ __global__ __launch_bounds__(256) void k_gemm_simple(const uint8_t* __restrict__
         s += nib_lo(pa) * nib_lo(pb) + nib_hi(pa) * nib_hi(pb);
     }
     if (acc) acc[m * N + n] = s;
-    if (out) out[m * N + n] = __float2half_rn((float)s * (sx * sw[n]));
+    if (out) out[m * N + n] = __float2half_rn(mul_rn((float)s, sx * sw[n]));
 }
 
 }  // namespace

@@ -43,8 +43,10 @@ int launch_gemm_simple(const void* xq, const void* wq, const float* sw, float sx
                        int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st);
 int launch_gemm_mfma(const void* xq, const void* wq, const float* sw, float sx, int64_t M,
                      int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st);
-int launch_gemv(const void* xq, const void* wq, const float* sw, float sx, int64_t M,
-                int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st);
+bool stream_mfma_supported(int64_t M, int64_t N, int64_t K, int32_t abits = 4);
+int launch_stream_mfma(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K,
+                       void* out, int32_t* acc, hipStream_t st, const float* srow = nullptr, int32_t abits = 4,
+                       const int32_t* zcorr = nullptr);
 
 bool decode_supported(int64_t M, int64_t N, int64_t K, int32_t h, int32_t abits = 4);
 int launch_decode(const void* x_f16, const void* xq_in, const void* wq, const float* sw, float sx, int32_t h,
@@ -52,6 +54,17 @@ int launch_decode(const void* x_f16, const void* xq_in, const void* wq, const fl
                   const float* srow = nullptr, int32_t abits = 4, const int32_t* zcorr = nullptr);
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? PQ_OK : PQ_ERR_HIP; }
+
+// A product rounded to fp32 on its own.  Written as a plain a * b the compiler merges the
+// multiplication with the conversion to fp16 that follows (one rounding instead of two) in some
+// kernels and not in others, and then the kernels of this library would differ from one another in
+// an output's last bit.  The empty asm makes the fp32 value opaque.
+__device__ __forceinline__ float mul_rn(float a, float b)
+{
+    float p = a * b;
+    asm("" : "+v"(p));
+    return p;
+}
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
