@@ -39,16 +39,28 @@ LINEARS = [("qkv", 4096, 6144, 1), ("o", 4096, 4096, 1), ("gate", 4096, 14336, 1
            ("up", 4096, 14336, 1), ("down", 14336, 4096, 128)]
 
 
-def prepare_layers(torch, synth, M):
+# Llama-3-70B single-layer linears (the benchmark configuration's large case, one GPU's view of a layer)
+LINEARS_70B = [("qkv", 8192, 10240, 1), ("o", 8192, 8192, 1), ("gate", 8192, 28672, 1),
+               ("up", 8192, 28672, 1), ("down", 28672, 8192, 128)]
+
+
+def prepare_layers(torch, synth, M, linears=LINEARS, device_weights=False):
     """Harness-side preparation (offline in a deployment, never timed): RTN per-channel
     4-bit weights with s_w = rowmax/7, and the static step s_x = max|rotated x_cal| / 7
-    from a separate 256-token calibration batch."""
+    from a separate 256-token calibration batch.  device_weights: the fp weights are drawn on
+    the device (same N(0, 0.02) law, torch's generator) instead of by the seeded host generator,
+    which takes minutes for the large matrices; they are quantized the same way."""
     import numpy as np
     layers = []
-    for seed, (name, K, N, h) in enumerate(LINEARS):
+    for seed, (name, K, N, h) in enumerate(linears):
         x = torch.from_numpy(synth.activations(M, K, seed)).cuda()
         xcal = torch.from_numpy(synth.calibration(K, seed)).cuda().float()
-        W = torch.from_numpy(synth.weights(N, K, seed)).cuda().float()
+        if device_weights:
+            gen = torch.Generator(device="cuda")
+            gen.manual_seed(1000 + seed)
+            W = torch.randn((N, K), generator=gen, device="cuda", dtype=torch.float32) * 0.02
+        else:
+            W = torch.from_numpy(synth.weights(N, K, seed)).cuda().float()
         if h > 1:
             i = np.arange(h)
             Hm = torch.from_numpy(1.0 - 2.0 * (np.bitwise_count(i[:, None] & i[None, :]) & 1)).float().cuda()
@@ -161,6 +173,31 @@ def run_prefill_8192(torch, pq, layers, steps=10, warmup=3):
     ops = sum(2.0 * M * L["K"] * L["N"] for L in layers)
     return {"ms_per_step": round(t * 1e3, 4), "TOPS": round(ops / t / 1e12, 1),
             "per_linear_TOPS": {L["name"]: round(2.0 * M * L["K"] * L["N"] / g[L["name"]] / 1e12, 1) for L in layers}}
+
+
+def run_llama3_70b(torch, pq, synth, decode=True):
+    """The large configuration: Llama-3-70B single-layer linears at M = 2048 prefill (wall time per
+    step, per-launch GEMM time from events, the fp16 GEMM beside it) and at batch-1 decode (cold
+    weights, HIP graph).  More tiles per launch and more bytes per matrix than the 8B shapes, so
+    the fixed cost of a launch weighs less."""
+    layers = prepare_layers(torch, synth, M_PREFILL, LINEARS_70B, device_weights=True)
+    t, g, _ = run_prefill(torch, pq, layers, 2 * EVENT_EVERY, 3)
+    ops = sum(2.0 * M_PREFILL * L["K"] * L["N"] for L in layers)
+    t16 = run_fp16(torch, layers, 5, 2)
+    gemm_ops = sum(2.0 * M_PREFILL * L["K"] * L["N"] for L in layers) / len(layers)
+    ach = gemm_ops / (sum(g.values()) / len(g)) / 1e12
+    res = {"prefill_2048": {"ms_per_step": round(t * 1e3, 4), "TOPS": round(ops / t / 1e12, 1),
+                            "gemm_TOPS_per_launch": round(ach, 1), "gemm_frac_of_int8_peak": round(ach / INT8_PEAK_TOPS, 4),
+                            "per_linear_TOPS": {L["name"]: round(2.0 * M_PREFILL * L["K"] * L["N"] / g[L["name"]] / 1e12, 1)
+                                                for L in layers},
+                            "fp16_ms_per_step": round(t16 * 1e3, 4), "speedup_vs_fp16": round(t16 / t, 3)}}
+    if decode:
+        for L in layers:
+            del L["w_f16"]
+        d = run_decode(torch, pq, layers, M=1)
+        res["decode_M1"] = {"GBps": d["GBps"], "frac_hbm": d["frac_hbm"],
+                            "per_linear": {k: {"us": v["us"], "frac_hbm": v["frac_hbm"]} for k, v in d["per_linear"].items()}}
+    return res
 
 
 def run_fp16(torch, layers, steps, warmup):
@@ -430,6 +467,10 @@ def main():
             d = run_decode(torch, pq, layers, M=m)
             result["decode"]["M%d" % m] = {"GBps": d["GBps"], "frac_hbm": d["frac_hbm"],
                                            "per_linear_us": {k: v["us"] for k, v in d["per_linear"].items()}}
+    if not args.no_variants:
+        del layers
+        torch.cuda.empty_cache()
+        result["llama3_70b"] = run_llama3_70b(torch, pq, synth, decode=not args.no_decode)
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(synth, args.cpu_rows)
     print(json.dumps(result))
