@@ -82,8 +82,9 @@ int pq_w4a4_gemm(const void* xq_packed, const void* wq_packed, const float* w_sc
 size_t pq_linear_workspace_bytes(int64_t M, int64_t K);
 
 /* The whole layer: pq_rotate_quant into `workspace`, then pq_w4a4_gemm (same stream).
- * For M <= 4 and M*K <= 8192 (16384 without rotation) the two steps run in one fused launch (every workgroup rotates
- * and quantizes the few rows for itself while its weight loads are in flight).
+ * For M <= 4 and M*K <= 8192 (16384 without rotation, or for a single token) the two steps run in
+ * one fused launch (every workgroup rotates and quantizes the few rows for itself while its first
+ * weight loads are in flight).
  * workspace: device memory, 256-byte aligned, at least pq_linear_workspace_bytes(M,K);
  * its contents on return are the packed activation codes (canonical layout).
  */

@@ -129,8 +129,9 @@ int pq_linear(const void* x_f16, const void* wq_packed, const float* w_scale, fl
     if (!aligned16(x_f16)) return PQ_ERR_ALIGN;
     // decode: one fused launch (rotate + quantize per workgroup, weights streamed once)
     // (quantizing a row costs every CU about 0.2 us per 1024 channels, so long rows keep two launches)
-    // (without rotation the per-CU cost is lower: up to 16384 elements measured equal or faster fused)
-    if (((g_variant == 0 && (M * K <= 8192 || (had_block <= 1 && M * K <= 16384))) || g_variant == 4) &&
+    // (without rotation the per-CU cost is lower: up to 16384 elements measured equal or faster fused;
+    // a single token also with rotation: 8.3 against 9.1 us at K = 14336, equal at 16384, slower beyond)
+    if (((g_variant == 0 && (M * K <= 8192 || ((had_block <= 1 || M == 1) && M * K <= 16384))) || g_variant == 4) &&
         pq::decode_supported(M, N, K, had_block))
         return pq::launch_decode(x_f16, nullptr, wq_packed, w_scale, act_scale, had_block, M, N, K, out_f16, nullptr,
                                  workspace, static_cast<hipStream_t>(stream));
