@@ -106,9 +106,9 @@ int pq_w4a4_gemm_simple(const void* xq_packed, const void* wq_packed, const floa
  * launch whenever the shape allows it; with 1, 2 or 3 it always uses two launches.
  * pq_w4a8_gemm, pq_gemm_dynamic and pq_w4a4_gemm_zp use a weight-streaming kernel only with 0,
  * or with 1 or 4 where that kernel supports the shape, and the tiled kernel otherwise.  The
- * automatic choice for given codes: dot products up to 4 tokens (8 when K < 8192; with int8
- * activations 2, or 4 when K < 8192), matrix tiles up to 16, tiled beyond.  Every kernel gives the
- * same accumulators and the same fp16 outputs bit for bit.
+ * automatic choice for given codes: dot products up to 4 tokens (8 on matrices under 12 MB; with
+ * int8 activations 2, 4 and 6 on matrices over 24 MB, over 12 MB and smaller), matrix tiles up to
+ * 16, tiled beyond.  Every kernel gives the same accumulators and the same fp16 outputs bit for bit.
  * Returns the previous value, or -1 if `variant` is unknown.
  */
 int pq_set_gemm_variant(int variant);

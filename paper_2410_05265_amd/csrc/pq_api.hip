@@ -10,9 +10,10 @@ int g_variant = 0;  // 0 auto, 1 streaming MFMA (M <= 16), 2 MFMA tiled, 3 simpl
 
 // Kernel for a product with given codes and few tokens: 4 = weight-streaming dot products
 // (k_decode), 1 = weight-streaming matrix tiles (k_stream_mfma), 2 = the tiled kernel, -1 = the
-// forced variant does not support the shape.  Measured on the Llama-3-8B shapes: the dot-product
-// kernel wins up to 4 tokens (with int8 activations up to 2; to 4 on short rows), the matrix
-// kernel from 5 tokens on long rows and from 9 everywhere.
+// forced variant does not support the shape.  The dot-product kernel costs more with every token,
+// the matrix kernel costs the same for any count up to 16 but has a higher floor; where they cross
+// depends on the size of the matrix (measured on the Llama-3-8B shapes, 8 / 12.6 / 29 MB of
+// weights): 4-bit codes from 5 tokens on (9 on small matrices), int8 codes from 3, 5 and 7.
 int pick_few_tokens(int64_t M, int64_t N, int64_t K, int32_t abits)
 {
     const bool dot = M <= 8 && pq::decode_supported(M, N, K, -1, abits);
@@ -20,8 +21,9 @@ int pick_few_tokens(int64_t M, int64_t N, int64_t K, int32_t abits)
     if (g_variant == 4) return dot ? 4 : -1;
     if (g_variant == 1) return mat ? 1 : -1;
     if (g_variant != 0) return 2;
-    const bool long_rows = K >= 8192;
-    const int64_t dot_limit = abits == 8 ? (long_rows ? 2 : 4) : (long_rows ? 4 : 8);
+    const int64_t weight_bytes = N * (K / 2);
+    const int size = weight_bytes >= 24000000 ? 2 : (weight_bytes >= 12000000 ? 1 : 0);
+    const int64_t dot_limit = abits == 8 ? (size == 2 ? 2 : (size == 1 ? 4 : 6)) : (size >= 1 ? 4 : 8);
     if (dot && (M <= dot_limit || !mat)) return 4;
     if (mat) return 1;
     return 2;

@@ -2,35 +2,37 @@
 // matrix is read from HBM exactly once and nothing else matters at these shapes (Sec. 3 of the
 // paper: weight quantization speeds up memory-bound computation; Sec. 5.4, decoding column).
 //
-// One workgroup of 16 wavefronts per CU.  A "row group" is 16 consecutive output channels; the
-// wavefronts of a workgroup split K of a row group into S slices (16 / S row groups per task when
-// K is short), so that every wavefront of the chip has the same few loads, all in flight at once.
+// One workgroup of 16 wavefronts per CU.  A "row group" is 16 consecutive output channels; a
+// task is 16 / S row groups, and the wavefronts of the workgroup split K of each into S slices (as
+// few as leave enough tasks for the chip), so that every wavefront has the same few loads.
 //   - Memory side: a "unit" is 16 rows x 128 contiguous bytes, fetched by two wavefront-loads of
 //     8 rows each (lane l: row l / 8, bytes 16 (l % 8) ..): every request is a whole 128-byte
 //     line (half lines measured 20 % slower).  A ring of DEPTH units per lane stays in flight
-//     across row groups.  Every load is unconditional (slots without work re-read the wavefront's
+//     across tasks.  Every load is unconditional (slots without work re-read the wavefront's
 //     first unit), so the compiler counts outstanding loads exactly and a unit is consumed as soon
 //     as it has arrived.
 //   - Matrix side: v_mfma_i32_16x16x64_i8 wants lane 16 g + i to hold row i, bytes 16 g .. of a
 //     64-byte block.  Two lane-shifted moves interleave the two loads so that one register set holds
 //     the first 64-byte block of all 16 rows and another the second, and the transpose to the
 //     matrix layout is then the same four ds_bpermute_b32 for either.
-//   - The activation codes (given; 4-bit packed or int8 in the even/odd-grouped order): every
-//     wavefront copies its own K range of every token into a private piece of LDS, token rows
-//     padded by 16 bytes, which makes the operand reads (lane 16 g + j: token j, bytes 16 g ..)
-//     conflict-free.  Only the load instructions that some lane needs are issued, before the
-//     weights: each one delays the weight stream, since loads return in order.  Tokens >= M read
-//     token M - 1 and their columns are never stored.
+//   - The activation codes (given; 4-bit packed or int8 in the even/odd-grouped order) are staged
+//     once per workgroup in LDS, token rows padded by 16 bytes, which makes the operand reads
+//     (lane 16 g + j: token j, bytes 16 g ..) conflict-free.  Their loads (only the instructions
+//     that some lane needs: each one delays the weight stream, loads return in order) go out
+//     first, then the first unit of weights; the staging barrier follows at once.  What makes a
+//     barrier expensive in this kernel is a wavefront that still waits for the memory pipeline to
+//     accept its loads: with the whole ring requested before the barrier that is most of the
+//     kernel's duration (measured), with one unit per wavefront it is nothing, and the rest of
+//     the ring is requested right behind the barrier.  Tokens >= M read token M - 1 and their
+//     columns are never stored.
 //   - Both 4-bit operands are expanded to bytes of 16 * code (sum carries 256, shifted out
 //     exactly); with int8 activations only the weights are (factor 16).
-//   - No barrier between the wavefronts once the sums are zeroed: a wavefront adds its partial
-//     16 x 16 tile to the row group's tile in LDS with atomic adds, then bumps the tile's counter;
-//     the wavefront that finds the counter at S - 1 has the complete sums (every other one
-//     finished its adds before its bump, and the LDS executes a wavefront's operations in order)
-//     and writes the outputs.  With a barrier per row group every wavefront waits for the slowest
-//     load of the workgroup before anything is multiplied, and a barrier after the loads are
-//     issued waits for the slowest wavefront to get its loads accepted, which at these sizes is
-//     most of the kernel.
+//   - No barrier after that: a wavefront adds its partial 16 x 16 tile to the row group's tile
+//     in LDS with atomic adds, then bumps the tile's counter; the wavefront that finds the counter
+//     at S - 1 has the complete sums (every other one finished its adds before its bump, and the
+//     LDS executes a wavefront's operations in order) and writes the outputs.  With a barrier
+//     per row group every wavefront waits for the slowest load of the workgroup before anything
+//     is multiplied.
 //     The weight steps and zero-point corrections of the epilogue come through the scalar cache
 //     (the row group is uniform over the wavefront), so they never queue behind the weight
 //     stream; the first ones are touched early so that the tail of the kernel finds them cached.
@@ -46,7 +48,11 @@ namespace {
 
 constexpr int kTiles = 16;                      // row-group tiles of partial sums open at a time
 constexpr int kSumBytes = kTiles * 1024 + 64;   // the tiles and their counters
-constexpr int kXB = 8;                          // 16-byte pieces of activation codes a lane stages up front
+constexpr int kXB = 8;                          // 16-byte pieces of activation codes a lane requests up front
+#ifndef PQ_STREAM_EARLY
+#define PQ_STREAM_EARLY 1
+#endif
+constexpr int kEarly = PQ_STREAM_EARLY;         // units a wavefront requests before the staging barrier
 
 typedef __attribute__((address_space(3))) v4i* lds_v4;
 typedef __attribute__((address_space(3))) const v4i* lds_cv4;
@@ -84,8 +90,8 @@ __global__ __launch_bounds__(1024) void k_stream_mfma(const uint8_t* __restrict_
     extern __shared__ __align__(16) uint8_t smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    // sums and counters start at zero: the only barrier of the kernel (apart from tile reuse),
-    // taken before any load is issued, when the wavefronts are still together
+    // sums and counters start at zero: the first of two barriers (apart from tile reuse), taken
+    // before any load is issued, when the wavefronts are still together
     lds_i counters = (lds_i)(smem + kTiles * 1024);
     auto clear = [&]() {
         ((lds_v4)smem)[tid] = (v4i){0, 0, 0, 0};
@@ -94,14 +100,12 @@ __global__ __launch_bounds__(1024) void k_stream_mfma(const uint8_t* __restrict_
     clear();
     lds_sync();
 
-    constexpr int UB = ABITS == 8 ? 256 : 128;   // bytes of one token's codes that go with a unit
     const int Kb = K >> 1;
     const int Ka = ABITS == 8 ? K : Kb;     // bytes per row of activation codes
     const int S = 1 << log2S;               // slices of K per row group
     const int RG = 16 >> log2S;             // row groups per task
     const int P = Kb >> 7;                  // units (128 bytes) per weight row
     const int upt = (P + S - 1) >> log2S;   // units per slice = per task (the same for every wavefront)
-    const int ns = (P + upt - 1) / upt;     // slices that are not empty
     const int q = wave >> log2S, s = wave & (S - 1);
     const int p0 = s * upt;
     const int p1 = p0 + upt < P ? p0 + upt : P;      // this wavefront's units: [p0, p1), possibly empty
@@ -113,31 +117,22 @@ __global__ __launch_bounds__(1024) void k_stream_mfma(const uint8_t* __restrict_
     // this lane's token step (the load is unconditional so that outstanding loads can be counted)
     const float tstep = (srow ? srow : sw)[srow ? (r < M ? r : M - 1) : 0];
 
-    // ---- this wavefront's K range of every token's codes: private to the wavefront, so no
-    // barrier; token rows padded by 16 bytes (conflict-free operand reads).  The first kXB
-    // pieces per lane are requested before the weights (loads complete in order).
-    const int xstride = UB * upt + 16;
-    uint8_t* xw = smem + kSumBytes + (q * ns + (s < ns ? s : 0)) * (M * xstride);
-    const int ppt = (UB >> 4) * upt;                    // 16-byte pieces per token
-    const int have = (UB >> 4) * (p1 > p0 ? p1 - p0 : 0);   // of which this many exist
-    const int pieces = M * ppt;
-    const uint8_t* xsrc = xq + p0 * UB;
+    // ---- every token's codes go to LDS, rows padded by 16 bytes (conflict-free operand reads).
+    // The first kXB pieces per lane are requested before any weight (loads complete in order, so
+    // they can be waited for without waiting for weights); a wavefront none of whose lanes has a
+    // piece issues no load, since each one delays the weight stream.
+    const int xstride = Ka + 16;
+    uint8_t* xs = smem + kSumBytes;
+    const int ppr = Ka >> 4, pieces = M * ppr;       // 16-byte pieces per row, in all
     v4i xr[kXB];
-    auto xaddr = [&](int i, int& dst) {
-        const int tok = i / ppt, pc = i - tok * ppt;
-        const bool ok = i < pieces && pc < have;
-        dst = ok ? tok * xstride + pc * 16 : -1;
-        return ok ? xsrc + (int64_t)tok * Ka + pc * 16 : xq;
-    };
-    int xdst[kXB];
 #pragma unroll
     for (int u = 0; u < kXB; ++u) {
-        xdst[u] = -1;
-        // uniform: a load instruction no lane needs is not issued (each one delays the weight stream)
-        if (64 * u < pieces) xr[u] = *reinterpret_cast<const v4i*>(xaddr(lane + 64 * u, xdst[u]));
+        const int i = tid + 1024 * u;
+        xr[u] = (v4i){0, 0, 0, 0};
+        if (wave * 64 + 1024 * u < pieces) xr[u] = *reinterpret_cast<const v4i*>(xq + (int64_t)(i < pieces ? i : 0) * 16);
     }
 
-    // ---- ring of weight loads
+    // ---- ring of weight loads: the first kEarly units now, the others behind the staging barrier
     v4i w[DEPTH][2];
     const uint8_t* wlane = wq + (int64_t)(lane >> 3) * Kb + (lane & 7) * 16;
     // a slot without work re-reads this wavefront's first unit (in bounds, and its own cache lines)
@@ -150,9 +145,29 @@ __global__ __launch_bounds__(1024) void k_stream_mfma(const uint8_t* __restrict_
         w[d][0] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(base));
         w[d][1] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(base + 8 * (int64_t)Kb));
     };
+    constexpr int EARLY = DEPTH < kEarly ? DEPTH : kEarly;
     int it = 0, ib = 0;   // task and unit of the next load
 #pragma unroll
-    for (int d = 0; d < DEPTH; ++d) {
+    for (int d = 0; d < EARLY; ++d) {
+        issue(d, it, ib);
+        if (++ib == upt) { ib = 0; ++it; }
+    }
+
+    auto put = [&](int i, const v4i v) {
+        if (i < pieces) {
+            const int row = i / ppr, col = i - row * ppr;
+            *(lds_v4)(xs + row * xstride + col * 16) = v;
+        }
+    };
+#pragma unroll
+    for (int u = 0; u < kXB; ++u) put(tid + 1024 * u, xr[u]);
+    for (int i = tid + 1024 * kXB; i < pieces; i += 1024)   // very long rows: the rest waits behind the early weights
+        put(i, *reinterpret_cast<const v4i*>(xq + (int64_t)i * 16));
+    // the second and last barrier: one unit per wavefront is in flight, so no wavefront is still
+    // waiting for the memory pipeline to accept its loads
+    lds_sync();
+#pragma unroll
+    for (int d = EARLY; d < DEPTH; ++d) {
         issue(d, it, ib);
         if (++ib == upt) { ib = 0; ++it; }
     }
@@ -164,23 +179,13 @@ __global__ __launch_bounds__(1024) void k_stream_mfma(const uint8_t* __restrict_
         if (task < my_tasks && rgw < R) warm = sw[rgw * 16];
     }
     const float st = srow ? tstep : sx;
-
-    // ---- codes into LDS
-#pragma unroll
-    for (int u = 0; u < kXB; ++u)
-        if (xdst[u] >= 0) *(lds_v4)(xw + xdst[u]) = xr[u];
-    for (int i = lane + 64 * kXB; i < pieces; i += 64) {   // long rows: the rest waits behind the weights
-        int dst;
-        const v4i v = *reinterpret_cast<const v4i*>(xaddr(i, dst));
-        if (dst >= 0) *(lds_v4)(xw + dst) = v;
-    }
     asm volatile("" ::"s"(warm));
 
     // ---- units in order; a task ends with this wavefront's contribution to the row group's tile
     // lane 16 g + i of the matrix operand takes (row i, block piece g) from the lane that holds it
     // after the interleave: rows 0-7 at lanes 8 i + g, rows 8-15 at lanes 8 (i - 8) + 4 + g
     const int src = (8 * (r & 7) + 4 * (r >> 3) + g) * 4;
-    const uint8_t* xlane = xw + (r < M ? r : M - 1) * xstride + g * (ABITS == 8 ? 32 : 16);
+    const uint8_t* xlane = xs + (r < M ? r : M - 1) * xstride + g * (ABITS == 8 ? 32 : 16);
     v4i acc = {0, 0, 0, 0};
     int ct = 0, cb = 0;   // task and unit being consumed
     auto consume = [&](int d) {
@@ -203,11 +208,12 @@ __global__ __launch_bounds__(1024) void k_stream_mfma(const uint8_t* __restrict_
                 t.z = __builtin_amdgcn_ds_bpermute(src, u.z);
                 t.w = __builtin_amdgcn_ds_bpermute(src, u.w);
                 unpack16(t, we, wo);
+                const int p = p0 + cb;
                 if constexpr (ABITS == 8) {
-                    xe = *(lds_cv4)(xlane + cb * 256 + kb * 128);
-                    xo = *(lds_cv4)(xlane + cb * 256 + kb * 128 + 16);
+                    xe = *(lds_cv4)(xlane + p * 256 + kb * 128);
+                    xo = *(lds_cv4)(xlane + p * 256 + kb * 128 + 16);
                 } else {
-                    const v4i xv = *(lds_cv4)(xlane + cb * 128 + kb * 64);
+                    const v4i xv = *(lds_cv4)(xlane + p * 128 + kb * 64);
                     unpack16(xv, xe, xo);
                 }
                 acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(we, xe, acc, 0, 0, 0);
@@ -289,17 +295,20 @@ __global__ __launch_bounds__(1024) void k_stream_mfma(const uint8_t* __restrict_
 // N a multiple of 16, and the codes of all tokens fit in LDS beside the tiles of sums
 namespace {
 // slices of K per row group (log2), units per slice and LDS bytes of a launch
-void stream_plan(int64_t M, int64_t K, int32_t abits, int* log2S, int* upt, size_t* lds)
+void stream_plan(int64_t M, int64_t N, int64_t K, int32_t abits, int* log2S, int* upt, size_t* lds)
 {
     const int P = (int)(K / 256);   // units of 128 bytes per weight row
-    int l2 = 2;                     // at least 4 slices
-    while (l2 < 4 && (2 << l2) <= P) ++l2;
-    const int u = (P + (1 << l2) - 1) >> l2;
-    const int ns = (P + u - 1) / u;
-    const int rg = 16 >> l2;
+    const int64_t R = N / 16;
+    int lmax = 2;                   // at least 4 slices, at most one per unit, at most 16
+    while (lmax < 4 && (2 << lmax) <= P) ++lmax;
+    // as few slices as leave enough tasks for the chip: a task then covers more row groups, a
+    // workgroup runs through fewer of them, and every task ends with a round of atomics and an
+    // epilogue (measured at 14336 x 4096: 4 slices 8.3 us, 8 slices 8.8, 16 slices 9.5)
+    int l2 = 2;
+    while (l2 < lmax && (R + (16 >> l2) - 1) / (16 >> l2) < 176) ++l2;
     *log2S = l2;
-    *upt = u;
-    *lds = (size_t)kSumBytes + (size_t)rg * ns * M * ((abits == 8 ? 256 : 128) * u + 16);
+    *upt = (P + (1 << l2) - 1) >> l2;
+    *lds = (size_t)kSumBytes + (size_t)M * ((abits == 8 ? K : K / 2) + 16);
 }
 }  // namespace
 
@@ -309,7 +318,7 @@ bool stream_mfma_supported(int64_t M, int64_t N, int64_t K, int32_t abits)
         return false;
     int log2S, upt;
     size_t lds;
-    stream_plan(M, K, abits, &log2S, &upt, &lds);
+    stream_plan(M, N, K, abits, &log2S, &upt, &lds);
     return lds <= 160 * 1024;
 }
 
@@ -320,7 +329,7 @@ int launch_stream_mfma(const void* xq, const void* wq, const float* sw, float sx
     if (!stream_mfma_supported(M, N, K, abits)) return PQ_ERR_UNSUPPORTED;
     int log2S, upt;
     size_t lds;
-    stream_plan(M, K, abits, &log2S, &upt, &lds);
+    stream_plan(M, N, K, abits, &log2S, &upt, &lds);
     const int RG = 16 >> log2S;
     const int64_t T = (N / 16 + RG - 1) / RG;
     const unsigned grid = (unsigned)(T < 256 ? T : 256);
