@@ -178,3 +178,28 @@ def test_unsupported_shapes_are_refused_when_forced(pq):
     assert e.value.status == 7
     out, acc = pq.pq_w4a4_gemm(dev(xq), dev(wq), dev(sw), 0.1, want_out=True, want_acc=True)   # automatic: another kernel
     assert np.array_equal(host(acc).astype(np.int64), O.gemm_i64(O.unpack(xq), O.unpack(wq)))
+
+
+def test_random_shapes(pq):
+    """Seeded random shapes within the kernel's limits: every combination of slices per row group,
+    ring depth, ragged row groups and token count that the fixed cases above may have missed."""
+    rng = np.random.default_rng(20241005)
+    for case in range(40):
+        bits = 8 if case % 3 == 2 else 4
+        K = 256 * int(rng.integers(1, 49))
+        N = 16 * int(rng.integers(1, max(2, min(1500, 30_000_000 // K // 16))))
+        M = int(rng.integers(1, 17))
+        while not 16448 + M * ((K if bits == 8 else K // 2) + 16) <= 160 * 1024:
+            M -= 1
+        lo, hi = (-128, 127) if bits == 8 else (-8, 7)
+        q = synth.random_codes(M, K, seed=case, stream=9, lo=lo, hi=hi)
+        wq = synth.random_packed(N, K, seed=case, stream=7)
+        sw = synth.random_scales(N, seed=case)
+        acc_ref = O.gemm_i64(q, O.unpack(wq))
+        if bits == 8:
+            out, acc = forced(pq, 1, pq.pq_w4a8_gemm, dev(O.group_even_odd(q)), dev(wq), dev(sw), 0.07, want_out=True,
+                              want_acc=True)
+        else:
+            out, acc = forced(pq, 1, pq.pq_w4a4_gemm, dev(O.pack(q)), dev(wq), dev(sw), 0.07, want_out=True, want_acc=True)
+        assert np.array_equal(host(acc).astype(np.int64), acc_ref), (case, bits, M, N, K)
+        assert ulp_diff(host(out), O.epilogue(acc_ref, np.float32(0.07), sw)).max() <= 1, (case, bits, M, N, K)
