@@ -90,15 +90,13 @@ __global__ __launch_bounds__(1024) void k_stream_mfma(const uint8_t* __restrict_
     extern __shared__ __align__(16) uint8_t smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    // sums and counters start at zero: the first of two barriers (apart from tile reuse), taken
-    // before any load is issued, when the wavefronts are still together
+    // sums and counters start at zero (the staging barrier below orders this before the first add)
     lds_i counters = (lds_i)(smem + kTiles * 1024);
     auto clear = [&]() {
         ((lds_v4)smem)[tid] = (v4i){0, 0, 0, 0};
         if (tid < 16) counters[tid] = 0;
     };
     clear();
-    lds_sync();
 
     const int Kb = K >> 1;
     const int Ka = ABITS == 8 ? K : Kb;     // bytes per row of activation codes
@@ -163,8 +161,8 @@ __global__ __launch_bounds__(1024) void k_stream_mfma(const uint8_t* __restrict_
     for (int u = 0; u < kXB; ++u) put(tid + 1024 * u, xr[u]);
     for (int i = tid + 1024 * kXB; i < pieces; i += 1024)   // very long rows: the rest waits behind the early weights
         put(i, *reinterpret_cast<const v4i*>(xq + (int64_t)i * 16));
-    // the second and last barrier: one unit per wavefront is in flight, so no wavefront is still
-    // waiting for the memory pipeline to accept its loads
+    // the only barrier (apart from tile reuse): one unit per wavefront is in flight, so no
+    // wavefront is still waiting for the memory pipeline to accept its loads
     lds_sync();
 #pragma unroll
     for (int d = EARLY; d < DEPTH; ++d) {
