@@ -101,7 +101,7 @@ int pq_w4a4_gemm_simple(const void* xq_packed, const void* wq_packed, const floa
 
 /* Force a kernel variant of pq_w4a4_gemm for sweeps and tests (host, process-wide,
  * not thread-safe): 0 = automatic, 1 = weight-streaming matrix tiles (M <= 16, K % 256 == 0 and
- * the tokens' codes fit in LDS; else PQ_ERR_UNSUPPORTED), 2 = MFMA tiled, 3 = simple,
+ * the codes of half the tokens fit in LDS; else PQ_ERR_UNSUPPORTED), 2 = MFMA tiled, 3 = simple,
  * 4 = weight-streaming 4-bit dot products (M <= 8 only).  With 4 pq_linear uses its fused single
  * launch whenever the shape allows it; with 1, 2 or 3 it always uses two launches.
  * pq_w4a8_gemm, pq_gemm_dynamic and pq_w4a4_gemm_zp use a weight-streaming kernel only with 0,

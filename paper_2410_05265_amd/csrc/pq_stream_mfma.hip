@@ -290,7 +290,7 @@ __global__ __launch_bounds__(1024) void k_stream_mfma(const uint8_t* __restrict_
 }  // namespace
 
 // M <= 16 tokens of given codes (abits 4: packed; 8: grouped bytes), K a multiple of 256 up to 65536,
-// N a multiple of 16, and the codes of all tokens fit in LDS beside the tiles of sums
+// N a multiple of 16, and the codes of half the tokens fit in LDS beside the tiles of sums
 namespace {
 // slices of K per row group (log2), units per slice and LDS bytes of a launch
 void stream_plan(int64_t M, int64_t N, int64_t K, int32_t abits, int* log2S, int* upt, size_t* lds)
@@ -310,21 +310,18 @@ void stream_plan(int64_t M, int64_t N, int64_t K, int32_t abits, int* log2S, int
 }
 }  // namespace
 
-bool stream_mfma_supported(int64_t M, int64_t N, int64_t K, int32_t abits)
+namespace {
+bool fits_in_lds(int64_t M, int64_t N, int64_t K, int32_t abits)
 {
-    if (!(M >= 1 && M <= 16 && N >= 16 && (N % 16) == 0 && N <= (1 << 30) && K >= 256 && (K % 256) == 0 && K <= 65536))
-        return false;
     int log2S, upt;
     size_t lds;
     stream_plan(M, N, K, abits, &log2S, &upt, &lds);
     return lds <= 160 * 1024;
 }
 
-int launch_stream_mfma(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K,
-                       void* out, int32_t* acc, hipStream_t st, const float* srow, int32_t abits,
-                       const int32_t* zcorr)
+int launch_tokens(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K, void* out,
+                  int32_t* acc, hipStream_t st, const float* srow, int32_t abits, const int32_t* zcorr)
 {
-    if (!stream_mfma_supported(M, N, K, abits)) return PQ_ERR_UNSUPPORTED;
     int log2S, upt;
     size_t lds;
     stream_plan(M, N, K, abits, &log2S, &upt, &lds);
@@ -354,6 +351,30 @@ int launch_stream_mfma(const void* xq, const void* wq, const float* sw, float sx
     if (units <= 1) return launch(k_stream_mfma<4, 1>);
     if (units <= 2) return launch(k_stream_mfma<4, 2>);
     return launch(k_stream_mfma<4, 4>);
+}
+}  // namespace
+
+// Tokens whose codes do not fit in LDS together go in two launches of half of them each (the weights
+// are then streamed twice, which is still faster than the tiled kernel at these token counts).
+bool stream_mfma_supported(int64_t M, int64_t N, int64_t K, int32_t abits)
+{
+    if (!(M >= 1 && M <= 16 && N >= 16 && (N % 16) == 0 && N <= (1 << 30) && K >= 256 && (K % 256) == 0 && K <= 65536))
+        return false;
+    return fits_in_lds((M + 1) / 2, N, K, abits);
+}
+
+int launch_stream_mfma(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K,
+                       void* out, int32_t* acc, hipStream_t st, const float* srow, int32_t abits,
+                       const int32_t* zcorr)
+{
+    if (!stream_mfma_supported(M, N, K, abits)) return PQ_ERR_UNSUPPORTED;
+    if (fits_in_lds(M, N, K, abits)) return launch_tokens(xq, wq, sw, sx, M, N, K, out, acc, st, srow, abits, zcorr);
+    const int64_t m1 = (M + 1) / 2, ka = abits == 8 ? K : K / 2;
+    int rc = launch_tokens(xq, wq, sw, sx, m1, N, K, out, acc, st, srow, abits, zcorr);
+    if (rc != PQ_OK) return rc;
+    return launch_tokens(static_cast<const uint8_t*>(xq) + m1 * ka, wq, sw, sx, M - m1, N, K,
+                         out ? static_cast<__half*>(out) + m1 * N : nullptr, acc ? acc + m1 * N : nullptr, st,
+                         srow ? srow + m1 : nullptr, abits, zcorr);
 }
 
 }  // namespace pq

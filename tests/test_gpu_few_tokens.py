@@ -203,3 +203,36 @@ def test_random_shapes(pq):
             out, acc = forced(pq, 1, pq.pq_w4a4_gemm, dev(O.pack(q)), dev(wq), dev(sw), 0.07, want_out=True, want_acc=True)
         assert np.array_equal(host(acc).astype(np.int64), acc_ref), (case, bits, M, N, K)
         assert ulp_diff(host(out), O.epilogue(acc_ref, np.float32(0.07), sw)).max() <= 1, (case, bits, M, N, K)
+
+
+@pytest.mark.parametrize("bits,M,N,K", [(4, 16, 272, 32768), (4, 11, 8192, 28672), (8, 16, 528, 14336), (8, 9, 64, 16384)])
+def test_tokens_split_over_two_launches(pq, bits, M, N, K):
+    """The codes of all tokens do not fit in LDS together: the call runs the first half of the
+    tokens, then the rest (pointer offsets into codes, steps, accumulators and outputs)."""
+    lo, hi = (-128, 127) if bits == 8 else (-8, 7)
+    q = synth.random_codes(M, K, seed=M + K, stream=9, lo=lo, hi=hi)
+    wq = synth.random_packed(N, K, seed=N + K, stream=7)
+    sw = synth.random_scales(N, seed=N)
+    srow = synth.random_scales(M, seed=M + 3)
+    acc_ref = O.gemm_i64(q, O.unpack(wq))
+    xq = O.group_even_odd(q) if bits == 8 else O.pack(q)
+    out, acc = forced(pq, 1, pq.pq_gemm_dynamic, dev(xq), bits, dev(wq), dev(sw), dev(srow), want_out=True, want_acc=True)
+    assert np.array_equal(host(acc).astype(np.int64), acc_ref)
+    assert ulp_diff(host(out), O.epilogue(acc_ref, srow, sw)).max() <= 1
+    if bits == 8:
+        out2, acc2 = pq.pq_w4a8_gemm(dev(xq), dev(wq), dev(sw), 0.04, want_out=True, want_acc=True)       # automatic choice
+    else:
+        out2, acc2 = pq.pq_w4a4_gemm(dev(xq), dev(wq), dev(sw), 0.04, want_out=True, want_acc=True)
+    assert np.array_equal(host(acc2).astype(np.int64), acc_ref)
+    assert ulp_diff(host(out2), O.epilogue(acc_ref, np.float32(0.04), sw)).max() <= 1
+
+
+def test_codes_of_half_the_tokens_must_fit(pq):
+    xq = synth.random_packed(16, 65536, seed=1)
+    wq = synth.random_packed(32, 65536, seed=2, stream=7)
+    sw = synth.random_scales(32, seed=3)
+    with pytest.raises(pq.PQError) as e:
+        forced(pq, 1, pq.pq_w4a4_gemm, dev(xq), dev(wq), dev(sw), 0.1)
+    assert e.value.status == 7
+    out, acc = pq.pq_w4a4_gemm(dev(xq), dev(wq), dev(sw), 0.1, want_out=True, want_acc=True)   # automatic: the tiled kernel
+    assert np.array_equal(host(acc).astype(np.int64), O.gemm_i64(O.unpack(xq), O.unpack(wq)))
