@@ -67,7 +67,7 @@ int pq_rotate_quant(const void* x_f16, int64_t M, int64_t K, int32_t had_block,
  *     acc[m,n] = sum_k xq[m,k] * wq[n,k]              (exact, int32)
  *     out[m,n] = fp16(acc[m,n] * (act_scale * w_scale[n]))   (fp32 multiply, RNE)
  * The kernel is chosen from M: weight-streaming kernels for M <= 16 (decode: 4-bit dot
- * products on packed nibbles for M <= 8, small matrix tiles up to 16), an INT8-MFMA tiled
+ * products on packed nibbles for M <= 8, small matrix tiles up to 16 or 32), an INT8-MFMA tiled
  * kernel otherwise (prefill).
  * xq_packed in  [M,K/2] uint8 canonical.      wq_packed in [N,K/2] uint8 canonical.
  * w_scale   in  [N] fp32.                     act_scale: static step size of xq.
@@ -100,15 +100,16 @@ int pq_w4a4_gemm_simple(const void* xq_packed, const void* wq_packed, const floa
                         void* out_f16, int32_t* acc_i32, void* stream);
 
 /* Force a kernel variant of pq_w4a4_gemm for sweeps and tests (host, process-wide,
- * not thread-safe): 0 = automatic, 1 = weight-streaming matrix tiles (M <= 16, K % 256 == 0 and
- * the codes of half the tokens fit in LDS; else PQ_ERR_UNSUPPORTED), 2 = MFMA tiled, 3 = simple,
+ * not thread-safe): 0 = automatic, 1 = weight-streaming matrix tiles (M <= 32, K % 256 == 0 and
+ * the codes of 8 tokens fit in LDS; else PQ_ERR_UNSUPPORTED), 2 = MFMA tiled, 3 = simple,
  * 4 = weight-streaming 4-bit dot products (M <= 8 only).  With 4 pq_linear uses its fused single
  * launch whenever the shape allows it; with 1, 2 or 3 it always uses two launches.
  * pq_w4a8_gemm, pq_gemm_dynamic and pq_w4a4_gemm_zp use a weight-streaming kernel only with 0,
  * or with 1 or 4 where that kernel supports the shape, and the tiled kernel otherwise.  The
  * automatic choice for given codes: dot products up to 4 tokens (8 on matrices under 12 MB; with
  * int8 activations 2, 4 and 6 on matrices over 24 MB, over 12 MB and smaller), matrix tiles up to
- * 16, tiled beyond.  Every kernel gives the same accumulators and the same fp16 outputs bit for bit.
+ * 16 (up to 32 in two launches on long rows and on matrices under 24 MB), tiled beyond.  Every kernel
+ * gives the same accumulators and the same fp16 outputs bit for bit.
  * Returns the previous value, or -1 if `variant` is unknown.
  */
 int pq_set_gemm_variant(int variant);

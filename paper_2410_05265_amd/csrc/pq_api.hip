@@ -14,10 +14,12 @@ int g_variant = 0;  // 0 auto, 1 streaming MFMA (M <= 16), 2 MFMA tiled, 3 simpl
 // the matrix kernel costs the same for any count up to 16 but has a higher floor; where they cross
 // depends on the size of the matrix (measured on the Llama-3-8B shapes, 8 / 12.6 / 29 MB of
 // weights): 4-bit codes from 5 tokens on (9 on small matrices), int8 codes from 3, 5 and 7.
+// 17 to 32 tokens are two launches of the matrix kernel where that beats the tiled kernel, whose
+// time at such counts is set by K alone: on long rows and on matrices under 24 MB.
 int pick_few_tokens(int64_t M, int64_t N, int64_t K, int32_t abits)
 {
     const bool dot = M <= 8 && pq::decode_supported(M, N, K, -1, abits);
-    const bool mat = M <= 16 && pq::stream_mfma_supported(M, N, K, abits);
+    const bool mat = M <= 32 && pq::stream_mfma_supported(M, N, K, abits);
     if (g_variant == 4) return dot ? 4 : -1;
     if (g_variant == 1) return mat ? 1 : -1;
     if (g_variant != 0) return 2;
@@ -25,7 +27,7 @@ int pick_few_tokens(int64_t M, int64_t N, int64_t K, int32_t abits)
     const int size = weight_bytes >= 24000000 ? 2 : (weight_bytes >= 12000000 ? 1 : 0);
     const int64_t dot_limit = abits == 8 ? (size == 2 ? 2 : (size == 1 ? 4 : 6)) : (size >= 1 ? 4 : 8);
     if (dot && (M <= dot_limit || !mat)) return 4;
-    if (mat) return 1;
+    if (mat && (M <= 16 || K >= 8192 || size < 2)) return 1;
     return 2;
 }
 

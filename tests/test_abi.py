@@ -92,7 +92,7 @@ def test_argument_errors_launch_nothing(b):
     assert lin(p, p, p, 0.1, 128, 0, 64, 512, p, nul, 0, nul) == b.PQ_OK
     prev = L.pq_set_gemm_variant(1)
     try:
-        assert L.pq_w4a4_gemm(p, p, p, 0.1, 17, 64, 512, p, nul, nul) == b.PQ_ERR_UNSUPPORTED
+        assert L.pq_w4a4_gemm(p, p, p, 0.1, 33, 64, 512, p, nul, nul) == b.PQ_ERR_UNSUPPORTED
     finally:
         L.pq_set_gemm_variant(prev)
 

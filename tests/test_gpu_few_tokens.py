@@ -236,3 +236,25 @@ def test_codes_of_half_the_tokens_must_fit(pq):
     assert e.value.status == 7
     out, acc = pq.pq_w4a4_gemm(dev(xq), dev(wq), dev(sw), 0.1, want_out=True, want_acc=True)   # automatic: the tiled kernel
     assert np.array_equal(host(acc).astype(np.int64), O.gemm_i64(O.unpack(xq), O.unpack(wq)))
+
+
+@pytest.mark.parametrize("bits,M,N,K", [(4, 17, 512, 512), (4, 32, 4096, 4096), (4, 24, 4096, 14336), (4, 29, 272, 28672),
+                                        (8, 32, 1040, 4096), (8, 20, 528, 14336)])
+def test_seventeen_to_thirty_two_tokens(pq, bits, M, N, K):
+    """Blocks of 16 tokens in consecutive launches (and halves of a block whose codes do not fit)."""
+    lo, hi = (-128, 127) if bits == 8 else (-8, 7)
+    q = synth.random_codes(M, K, seed=M + K, stream=9, lo=lo, hi=hi)
+    wq = synth.random_packed(N, K, seed=N + K, stream=7)
+    sw = synth.random_scales(N, seed=N)
+    srow = synth.random_scales(M, seed=M + 5)
+    acc_ref = O.gemm_i64(q, O.unpack(wq))
+    xq = O.group_even_odd(q) if bits == 8 else O.pack(q)
+    out, acc = forced(pq, 1, pq.pq_gemm_dynamic, dev(xq), bits, dev(wq), dev(sw), dev(srow), want_out=True, want_acc=True)
+    assert np.array_equal(host(acc).astype(np.int64), acc_ref)
+    assert ulp_diff(host(out), O.epilogue(acc_ref, srow, sw)).max() <= 1
+    tiled, _ = forced(pq, 2, pq.pq_gemm_dynamic, dev(xq), bits, dev(wq), dev(sw), dev(srow))
+    assert np.array_equal(host(tiled).view(np.uint16), host(out).view(np.uint16))
+    fn = pq.pq_w4a8_gemm if bits == 8 else pq.pq_w4a4_gemm
+    auto, acc0 = fn(dev(xq), dev(wq), dev(sw), 0.03, want_out=True, want_acc=True)          # automatic choice
+    assert np.array_equal(host(acc0).astype(np.int64), acc_ref)
+    assert ulp_diff(host(auto), O.epilogue(acc_ref, np.float32(0.03), sw)).max() <= 1
