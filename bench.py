@@ -480,7 +480,9 @@ def main():
                                              for L in layers},
                          "note": "pq_rotate_quant launches of the instrumented steps; 2.5 algorithmic bytes per element"},
         "fp16_gemm": {"ms_per_step": round(t_fp16 * 1e3, 4), "TFLOPS": round(ops / t_fp16 / 1e12, 1),
-                      "speedup_pq_linear": round(t_fp16 / t_step, 3), "impl": "torch.matmul fp16"},
+                      "frac_of_fp16_peak": round(ops / t_fp16 / 1e12 / (INT8_PEAK_TOPS / 2), 4),
+                      "speedup_pq_linear": round(t_fp16 / t_step, 3),
+                      "speedup_pq_w4a4_gemm_only": round(t_fp16 / sum(gemm_t.values()), 3), "impl": "torch.matmul fp16"},
     }
     t_i8 = run_int8_ref(torch, layers, max(5, args.steps // 2), max(2, args.warmup // 2))
     if t_i8 is not None:
