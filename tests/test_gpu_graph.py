@@ -1,0 +1,95 @@
+"""The calls under HIP graph capture: captured once, replayed several times with new contents in
+the same buffers and eager work in between; every replay must give the eager result bit for bit.
+(The library enqueues kernels only: no allocation, no memset, no synchronisation, so every call
+can be captured.  The benchmark times its decode legs this way.)"""
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from paper_2410_05265_amd import synth
+from pq_testlib import dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def pq():
+    import paper_2410_05265_amd.binding as b
+    b.lib()
+    return b
+
+
+@pytest.mark.parametrize("M,K,N,h", [(1, 4096, 4096, 1), (1, 14336, 512, 128), (4, 4096, 1024, 1), (16, 4096, 2048, 1),
+                                     (12, 14336, 512, 128), (24, 4096, 1024, 1), (300, 1024, 768, 128)])
+def test_linear_replays_match_eager(pq, M, K, N, h):
+    wq, sw = O.weight_rtn(synth.weights(N, K, seed=3))
+    wp = dev(O.pack(wq))
+    dsw = dev(sw)
+    xs = [synth.activations(M, K, seed=40 + i) for i in range(3)]
+    sx = float(O.calibrate_absmax(synth.calibration(K, 3), h))
+    x = dev(xs[0])
+    out = torch.empty((M, N), dtype=torch.float16, device="cuda")
+    work = torch.empty((max(256, pq.pq_linear_workspace_bytes(M, K)),), dtype=torch.uint8, device="cuda")
+    eager = []
+    for xi in xs:
+        x.copy_(torch.from_numpy(xi))
+        o, _ = pq.pq_linear(x, wp, dsw, sx, h)
+        eager.append(host(o).view(np.uint16).copy())
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        x.copy_(torch.from_numpy(xs[0]))
+        pq.pq_linear(x, wp, dsw, sx, h, out=out, workspace=work)          # warm-up on the capture stream
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            pq.pq_linear(x, wp, dsw, sx, h, out=out, workspace=work)
+    torch.cuda.synchronize()
+    for rep in range(2):
+        for i, xi in enumerate(xs):
+            x.copy_(torch.from_numpy(xi))
+            out.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(host(out).view(np.uint16), eager[i]), (rep, i)
+            # eager work of the same library between replays
+            pq.pq_rotate_quant(x, h, sx)
+            torch.cuda.synchronize()
+
+
+def test_quantizer_family_replays_match_eager(pq):
+    M, K = 64, 4096
+    xs = [synth.activations(M, K, seed=50 + i) for i in range(3)]
+    x = dev(xs[0])
+    q4 = torch.empty((M, K // 2), dtype=torch.uint8, device="cuda")
+    q8 = torch.empty((M, K), dtype=torch.int8, device="cuda")
+    qd = torch.empty((M, K // 2), dtype=torch.uint8, device="cuda")
+    srow = torch.empty((M,), dtype=torch.float32, device="cuda")
+    eager = []
+    for xi in xs:
+        x.copy_(torch.from_numpy(xi))
+        a = pq.pq_rotate_quant(x, 128, 0.4)
+        b = pq.pq_rotate_quant8(x, 128, 0.02)
+        c, s = pq.pq_rotate_quant_dynamic(x, 128, 1.0, 4)
+        eager.append((host(a).copy(), host(b).copy(), host(c).copy(), host(s).copy()))
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        pq.pq_rotate_quant(x, 128, 0.4, out=q4)
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            pq.pq_rotate_quant(x, 128, 0.4, out=q4)
+            pq.pq_rotate_quant8(x, 128, 0.02, out=q8)
+            pq.pq_rotate_quant_dynamic(x, 128, 1.0, 4, out=qd, row_scale=srow)
+    torch.cuda.synchronize()
+    for rep in range(2):
+        for i, xi in enumerate(xs):
+            x.copy_(torch.from_numpy(xi))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            a, b, c, s = eager[i]
+            assert np.array_equal(host(q4), a) and np.array_equal(host(q8), b)
+            assert np.array_equal(host(qd), c) and np.array_equal(host(srow), s)
