@@ -93,3 +93,25 @@ def test_quantizer_family_replays_match_eager(pq):
             a, b, c, s = eager[i]
             assert np.array_equal(host(q4), a) and np.array_equal(host(q8), b)
             assert np.array_equal(host(qd), c) and np.array_equal(host(srow), s)
+
+
+def test_two_streams_at_once(pq):
+    """The library keeps no state between calls: different layers on two streams at the same time."""
+    cases = []
+    for seed, (M, K, N, h) in enumerate([(16, 4096, 4096, 1), (2048, 1024, 1024, 128)]):
+        wq, sw = O.weight_rtn(synth.weights(N, K, seed=seed))
+        x = dev(synth.activations(M, K, seed=60 + seed))
+        sx = float(O.calibrate_absmax(synth.calibration(K, seed), h))
+        wp, dsw = dev(O.pack(wq)), dev(sw)
+        ref, _ = pq.pq_linear(x, wp, dsw, sx, h)
+        cases.append((x, wp, dsw, sx, h, host(ref).view(np.uint16).copy(), torch.cuda.Stream(),
+                      torch.empty((M, N), dtype=torch.float16, device="cuda"),
+                      torch.empty((max(256, pq.pq_linear_workspace_bytes(M, K)),), dtype=torch.uint8, device="cuda")))
+    torch.cuda.synchronize()
+    for rep in range(20):
+        for x, wp, dsw, sx, h, ref, st, out, work in cases:
+            with torch.cuda.stream(st):
+                pq.pq_linear(x, wp, dsw, sx, h, out=out, workspace=work)
+    torch.cuda.synchronize()
+    for x, wp, dsw, sx, h, ref, st, out, work in cases:
+        assert np.array_equal(host(out).view(np.uint16), ref)
