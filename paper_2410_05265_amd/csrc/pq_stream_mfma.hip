@@ -49,10 +49,7 @@ namespace {
 constexpr int kTiles = 16;                      // row-group tiles of partial sums open at a time
 constexpr int kSumBytes = kTiles * 1024 + 64;   // the tiles and their counters
 constexpr int kXB = 8;                          // 16-byte pieces of activation codes a lane requests up front
-#ifndef PQ_STREAM_EARLY
-#define PQ_STREAM_EARLY 1
-#endif
-constexpr int kEarly = PQ_STREAM_EARLY;         // units a wavefront requests before the staging barrier
+constexpr int kEarly = 1;                       // units a wavefront requests before the staging barrier (2 and 4 measured slower)
 
 typedef __attribute__((address_space(3))) v4i* lds_v4;
 typedef __attribute__((address_space(3))) const v4i* lds_cv4;
