@@ -235,6 +235,40 @@ def run_llama3_70b(torch, pq, synth, decode=True):
     return res
 
 
+def run_probes(torch, pq):
+    """What the GPU delivers on the two bounds with nothing else going on: matrix instructions only
+    (INT8 32x32x32, operands of three kinds: the pipe's pace depends on the bits it multiplies), and a
+    kernel that only reads 1 GiB from HBM."""
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(7)
+    n = 1 << 20
+    kinds = {"zeros": torch.zeros(n, dtype=torch.int8, device="cuda"),
+             "codes_times_16": (torch.randint(-8, 8, (n,), generator=gen, device="cuda", dtype=torch.int32) * 16).to(torch.int8),
+             "random_bytes": torch.randint(-128, 128, (n,), generator=gen, device="cuda", dtype=torch.int32).to(torch.int8)}
+    res = {"mfma_only_TOPS": {}}
+    for name, t in kinds.items():
+        pq.pq_probe_mfma_i8(t, 1000, 256, sink)
+        device_warmup(torch)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        ops = sum(pq.pq_probe_mfma_i8(t, 1000, 256, sink) for _ in range(5))
+        e1.record()
+        torch.cuda.synchronize()
+        res["mfma_only_TOPS"][name] = round(ops / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+    big = torch.randint(0, 256, (1 << 30,), generator=gen, device="cuda", dtype=torch.uint8)
+    pq.pq_probe_stream_read(big, sink)
+    device_warmup(torch, 40.0)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    nbytes = sum(pq.pq_probe_stream_read(big, sink) for _ in range(3))
+    e1.record()
+    torch.cuda.synchronize()
+    res["stream_read_GBps"] = round(nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+    del big
+    return res
+
+
 def run_fp16(torch, layers, steps, warmup):
     outs = [torch.empty((L["x"].shape[0], L["N"]), dtype=torch.float16, device="cuda") for L in layers]
     device_warmup(torch)
@@ -490,6 +524,9 @@ def main():
                                "pq_gemm_only_ms": round(sum(gemm_t.values()) * 1e3, 4),
                                "impl": "torch._int_mm (hipBLASLt): int8 x int8 -> int32, no unpack, no epilogue"}
     if not args.no_variants:
+        pr = run_probes(torch, pq)
+        pr["product_kernel_frac_of_mfma_only_codes"] = round(achieved / pr["mfma_only_TOPS"]["codes_times_16"], 4)
+        result["achievable"] = pr
         result["prefill_8192"] = run_prefill_8192(torch, pq, layers)
         result["side_rows"] = run_side_rows(torch, pq, synth, M_PREFILL)
     if not args.no_variants:
@@ -508,6 +545,9 @@ def main():
         b_block = sum(L["N"] * L["K"] // 2 for L in layers)
         result["decode"]["gate_up_one_launch"] = dict(gu, block_GBps=round(b_block / t_block / 1e9, 1),
                                                       block_frac_hbm=round(b_block / t_block / 1e9 / HBM_PEAK_GBS, 3))
+        if "achievable" in result:
+            result["achievable"]["decode_frac_of_stream_read"] = round(
+                result["decode"]["GBps"] / result["achievable"]["stream_read_GBps"], 4)
         for m in (4, 16):
             d = run_decode(torch, pq, layers, M=m)
             result["decode"]["M%d" % m] = {"GBps": d["GBps"], "frac_hbm": d["frac_hbm"],

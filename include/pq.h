@@ -99,6 +99,20 @@ int pq_w4a4_gemm_simple(const void* xq_packed, const void* wq_packed, const floa
                         float act_scale, int64_t M, int64_t N, int64_t K,
                         void* out_f16, int32_t* acc_i32, void* stream);
 
+/* ---- measuring sticks for the rooflines (service calls, not part of the path) --------------
+ * pq_probe_mfma_i8: `workgroups` workgroups of four wavefronts, each wavefront issues iters x 16
+ *   independent 32x32x32 INT8 matrix instructions (2 * 32768 integer operations each) and nothing
+ *   else; the operands are read once from `operands` (device, 16-byte aligned, operand_bytes a
+ *   multiple of 16, at most 16 GiB), so their bit patterns are the caller's.  Operations of a launch:
+ *   workgroups * 4 * iters * 16 * 65536.
+ * pq_probe_stream_read: one launch of 256 workgroups reads `bytes` (multiple of 16) from `src`
+ *   (device, 16-byte aligned) once and discards them.
+ * sink: device int32, written practically never (keeps the work alive).  Errors as elsewhere.
+ */
+int pq_probe_mfma_i8(const void* operands, int64_t operand_bytes, int64_t iters, int32_t workgroups,
+                     int32_t* sink, void* stream);
+int pq_probe_stream_read(const void* src, int64_t bytes, int32_t* sink, void* stream);
+
 /* Force a kernel variant of pq_w4a4_gemm for sweeps and tests (host, process-wide,
  * not thread-safe): 0 = automatic, 1 = weight-streaming matrix tiles (M <= 32, K % 256 == 0 and
  * the codes of 8 tokens fit in LDS; else PQ_ERR_UNSUPPORTED), 2 = MFMA tiled, 3 = simple,

@@ -29,6 +29,8 @@ SIGNATURES = {
     "pq_linear_workspace_bytes": (_sz, [_i64, _i64]),
     "pq_linear": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i32, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
     "pq_set_gemm_variant": (ctypes.c_int, [ctypes.c_int]),
+    "pq_probe_mfma_i8": (ctypes.c_int, [_vp, _i64, _i64, _i32, _vp, _vp]),
+    "pq_probe_stream_read": (ctypes.c_int, [_vp, _i64, _vp, _vp]),
     "pq_rotate_quant8": (ctypes.c_int, [_vp, _i64, _i64, _i32, _f32, _vp, _vp]),
     "pq_w4a8_gemm": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i64, _i64, _i64, _vp, _vp, _vp]),
     "pq_linear_w4a8_workspace_bytes": (_sz, [_i64, _i64]),
@@ -407,3 +409,17 @@ def pq_calibrate_static_zp(x_cal, had_block: int, n_gamma: int = 8, n_beta: int 
 
 def pq_set_gemm_variant(variant: int) -> int:
     return int(lib().pq_set_gemm_variant(int(variant)))
+
+
+def pq_probe_mfma_i8(operands: torch.Tensor, iters: int, workgroups: int, sink: torch.Tensor) -> float:
+    """Launches the matrix-pipe probe; returns the integer operations of the launch."""
+    _check(lib().pq_probe_mfma_i8(_ptr(operands), operands.numel() * operands.element_size(), int(iters), int(workgroups),
+                                  _ptr(sink), _stream()), "pq_probe_mfma_i8")
+    return float(workgroups) * 4 * iters * 16 * 65536
+
+
+def pq_probe_stream_read(src: torch.Tensor, sink: torch.Tensor) -> int:
+    """Launches the read-only probe over the whole tensor; returns the bytes read."""
+    nbytes = src.numel() * src.element_size()
+    _check(lib().pq_probe_stream_read(_ptr(src), nbytes, _ptr(sink), _stream()), "pq_probe_stream_read")
+    return nbytes

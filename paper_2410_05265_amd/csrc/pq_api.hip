@@ -426,6 +426,25 @@ int pq_calibrate_static_zp(const void* x_cal_f16, int64_t T, int64_t K, int32_t 
                                    static_cast<float*>(workspace), static_cast<hipStream_t>(stream));
 }
 
+int pq_probe_mfma_i8(const void* operands, int64_t operand_bytes, int64_t iters, int32_t workgroups, int32_t* sink,
+                     void* stream)
+{
+    if (!operands || !sink) return PQ_ERR_NULL;
+    if (!aligned16(operands) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return PQ_ERR_ALIGN;
+    if (operand_bytes < 16 || (operand_bytes % 16) != 0 || operand_bytes > ((int64_t)1 << 34) || iters < 0 || iters > (1 << 24) ||
+        workgroups < 1 || workgroups > (1 << 20))
+        return PQ_ERR_SHAPE;
+    return pq::launch_probe_mfma(operands, operand_bytes, iters, workgroups, sink, static_cast<hipStream_t>(stream));
+}
+
+int pq_probe_stream_read(const void* src, int64_t bytes, int32_t* sink, void* stream)
+{
+    if (!src || !sink) return PQ_ERR_NULL;
+    if (!aligned16(src) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return PQ_ERR_ALIGN;
+    if (bytes < 16 || (bytes % 16) != 0) return PQ_ERR_SHAPE;
+    return pq::launch_probe_read(src, bytes, sink, static_cast<hipStream_t>(stream));
+}
+
 int pq_set_gemm_variant(int variant)
 {
     if (variant < 0 || variant > 4) return -1;

@@ -43,6 +43,10 @@ int launch_gemm_simple(const void* xq, const void* wq, const float* sw, float sx
                        int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st);
 int launch_gemm_mfma(const void* xq, const void* wq, const float* sw, float sx, int64_t M,
                      int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st);
+int launch_probe_mfma(const void* operands, int64_t operand_bytes, int64_t iters, int32_t workgroups, int32_t* sink,
+                      hipStream_t st);
+int launch_probe_read(const void* src, int64_t bytes, int32_t* sink, hipStream_t st);
+
 bool stream_mfma_supported(int64_t M, int64_t N, int64_t K, int32_t abits = 4);
 int launch_stream_mfma(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K,
                        void* out, int32_t* acc, hipStream_t st, const float* srow = nullptr, int32_t abits = 4,

@@ -153,3 +153,19 @@ def test_argument_errors_of_the_widened_calls(b):
     assert cal(p, 4, 256, 1, 4, 8, 0.5, p, p256, 16, nul) == E.PQ_ERR_WORKSPACE
     assert cal(p, 4, 256, 1, 4, 8, 0.5, nul, p256, 1 << 20, nul) == E.PQ_ERR_NULL
     assert cal(p, 4, 65536, 1, 4, 8, 0.5, p, p256, 1 << 20, nul) == E.PQ_ERR_UNSUPPORTED
+
+
+def test_argument_errors_of_the_probes(b):
+    L = b.lib()
+    p = ctypes.c_void_p(0x1000)          # never dereferenced: each call fails validation first
+    odd = ctypes.c_void_p(0x1008)
+    nul = ctypes.c_void_p(0)
+    assert L.pq_probe_mfma_i8(nul, 1024, 10, 256, p, nul) == b.PQ_ERR_NULL
+    assert L.pq_probe_mfma_i8(p, 1024, 10, 256, nul, nul) == b.PQ_ERR_NULL
+    assert L.pq_probe_mfma_i8(odd, 1024, 10, 256, p, nul) == b.PQ_ERR_ALIGN
+    assert L.pq_probe_mfma_i8(p, 1000, 10, 256, p, nul) == b.PQ_ERR_SHAPE          # bytes % 16
+    assert L.pq_probe_mfma_i8(p, 1024, -1, 256, p, nul) == b.PQ_ERR_SHAPE
+    assert L.pq_probe_mfma_i8(p, 1024, 10, 0, p, nul) == b.PQ_ERR_SHAPE
+    assert L.pq_probe_stream_read(nul, 1024, p, nul) == b.PQ_ERR_NULL
+    assert L.pq_probe_stream_read(odd, 1024, p, nul) == b.PQ_ERR_ALIGN
+    assert L.pq_probe_stream_read(p, 8, p, nul) == b.PQ_ERR_SHAPE

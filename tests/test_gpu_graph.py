@@ -115,3 +115,16 @@ def test_two_streams_at_once(pq):
     torch.cuda.synchronize()
     for x, wp, dsw, sx, h, ref, st, out, work in cases:
         assert np.array_equal(host(out).view(np.uint16), ref)
+
+
+def test_roofline_probes_run(pq):
+    """The two measuring sticks of the benchmark: they must run, read in bounds and leave their sink alone."""
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    ops = pq.pq_probe_mfma_i8(torch.zeros(4096, dtype=torch.int8, device="cuda"), 10, 256, sink)
+    assert ops == 256 * 4 * 10 * 16 * 65536
+    ops = pq.pq_probe_mfma_i8(torch.full((16,), 0x70, dtype=torch.int8, device="cuda"), 3, 7, sink)   # one operand set, reused
+    src = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
+    assert pq.pq_probe_stream_read(src, sink) == 4 << 20
+    assert pq.pq_probe_stream_read(src[:4 * 37], sink) == 16 * 37                                    # shorter than one pass
+    torch.cuda.synchronize()
+    assert int(sink.abs().sum().item()) == 0
