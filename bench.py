@@ -518,46 +518,67 @@ def main():
                       "speedup_pq_linear": round(t_fp16 / t_step, 3),
                       "speedup_pq_w4a4_gemm_only": round(t_fp16 / sum(gemm_t.values()), 3), "impl": "torch.matmul fp16"},
     }
-    t_i8 = run_int8_ref(torch, layers, max(5, args.steps // 2), max(2, args.warmup // 2))
-    if t_i8 is not None:
-        result["int8_gemm"] = {"ms_per_step": round(t_i8 * 1e3, 4), "TOPS": round(ops / t_i8 / 1e12, 1),
-                               "pq_gemm_only_ms": round(sum(gemm_t.values()) * 1e3, 4),
-                               "impl": "torch._int_mm (hipBLASLt): int8 x int8 -> int32, no unpack, no epilogue"}
-    if not args.no_variants:
+    # Everything below is a side leg: a failure there is recorded in its place and never costs the line.
+    def leg(key, fn):
+        try:
+            result[key] = fn()
+        except Exception as e:                           # noqa: BLE001 (reported, not swallowed)
+            result[key] = {"error": "%s: %s" % (type(e).__name__, e)}
+            print("bench.py: leg %s failed: %r" % (key, e), file=sys.stderr)
+        return result[key]
+
+    def int8_leg():
+        t_i8 = run_int8_ref(torch, layers, max(5, args.steps // 2), max(2, args.warmup // 2))
+        if t_i8 is None:
+            return {"error": "torch._int_mm not available"}
+        return {"ms_per_step": round(t_i8 * 1e3, 4), "TOPS": round(ops / t_i8 / 1e12, 1),
+                "pq_gemm_only_ms": round(sum(gemm_t.values()) * 1e3, 4),
+                "impl": "torch._int_mm (hipBLASLt): int8 x int8 -> int32, no unpack, no epilogue"}
+
+    def probes_leg():
         pr = run_probes(torch, pq)
         pr["product_kernel_frac_of_mfma_only_codes"] = round(achieved / pr["mfma_only_TOPS"]["codes_times_16"], 4)
-        result["achievable"] = pr
-        result["prefill_8192"] = run_prefill_8192(torch, pq, layers)
-        result["side_rows"] = run_side_rows(torch, pq, synth, M_PREFILL)
-    if not args.no_variants:
-        result["variants"] = run_variants(torch, pq, layers, max(5, args.steps // 2), max(2, args.warmup // 2), ops)
-        result["variants"]["dynamic_over_static_w4a4"] = round(
-            result["variants"]["w4a4_dynamic"]["ms_per_step"] / result["ms_per_step"], 3)
-    if not args.no_decode:
-        result["decode"] = run_decode(torch, pq, layers, M=1, warm=True)
+        return pr
+
+    def variants_leg():
+        v = run_variants(torch, pq, layers, max(5, args.steps // 2), max(2, args.warmup // 2), ops)
+        v["dynamic_over_static_w4a4"] = round(v["w4a4_dynamic"]["ms_per_step"] / result["ms_per_step"], 3)
+        return v
+
+    def decode_leg():
+        dec = run_decode(torch, pq, layers, M=1, warm=True)
         # gate and up share their input: stored as one [28672, 4096] matrix they stream in one launch
         gate, up = layers[2], layers[3]
         fused = dict(gate, name="gate_up", N=gate["N"] + up["N"], wq=torch.cat([gate["wq"], up["wq"]]).contiguous(),
                      sw=torch.cat([gate["sw"], up["sw"]]).contiguous())
         gu = run_decode(torch, pq, [fused], M=1)["per_linear"]["gate_up"]
-        pl = result["decode"]["per_linear"]
+        pl = dec["per_linear"]
         t_block = (pl["qkv"]["us"] + pl["o"]["us"] + gu["us"] + pl["down"]["us"]) * 1e-6
         b_block = sum(L["N"] * L["K"] // 2 for L in layers)
-        result["decode"]["gate_up_one_launch"] = dict(gu, block_GBps=round(b_block / t_block / 1e9, 1),
-                                                      block_frac_hbm=round(b_block / t_block / 1e9 / HBM_PEAK_GBS, 3))
-        if "achievable" in result:
-            result["achievable"]["decode_frac_of_stream_read"] = round(
-                result["decode"]["GBps"] / result["achievable"]["stream_read_GBps"], 4)
+        dec["gate_up_one_launch"] = dict(gu, block_GBps=round(b_block / t_block / 1e9, 1),
+                                         block_frac_hbm=round(b_block / t_block / 1e9 / HBM_PEAK_GBS, 3))
+        if "stream_read_GBps" in result.get("achievable", {}):
+            result["achievable"]["decode_frac_of_stream_read"] = round(dec["GBps"] / result["achievable"]["stream_read_GBps"], 4)
         for m in (4, 16):
             d = run_decode(torch, pq, layers, M=m)
-            result["decode"]["M%d" % m] = {"GBps": d["GBps"], "frac_hbm": d["frac_hbm"],
-                                           "per_linear_us": {k: v["us"] for k, v in d["per_linear"].items()}}
+            dec["M%d" % m] = {"GBps": d["GBps"], "frac_hbm": d["frac_hbm"],
+                              "per_linear_us": {k: v["us"] for k, v in d["per_linear"].items()}}
+        return dec
+
+    leg("int8_gemm", int8_leg)
+    if not args.no_variants:
+        leg("achievable", probes_leg)
+        leg("prefill_8192", lambda: run_prefill_8192(torch, pq, layers))
+        leg("side_rows", lambda: run_side_rows(torch, pq, synth, M_PREFILL))
+        leg("variants", variants_leg)
+    if not args.no_decode:
+        leg("decode", decode_leg)
     if not args.no_variants:
         del layers
         torch.cuda.empty_cache()
-        result["llama3_70b"] = run_llama3_70b(torch, pq, synth, decode=not args.no_decode)
+        leg("llama3_70b", lambda: run_llama3_70b(torch, pq, synth, decode=not args.no_decode))
     if not args.no_cpu:
-        result["cpu_baseline"] = cpu_baseline(synth, args.cpu_rows)
+        leg("cpu_baseline", lambda: cpu_baseline(synth, args.cpu_rows))
     print(json.dumps(result))
 
 
