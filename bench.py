@@ -370,11 +370,12 @@ def run_side_rows(torch, pq, synth, T):
     return res
 
 
-def run_decode(torch, pq, layers, M=1, reps=3, warm=False):
+def run_decode(torch, pq, layers, M=1, reps=3, warm=False, planes=False):
     """Batch-M decode through pq_linear with cold weights: enough distinct copies of each
     weight matrix that more than 1 GiB is touched before one is reused (the matrices fit
     the 256 MB last-level cache otherwise).  The launches are captured in a HIP graph so
-    the host is not the limit; time is per captured launch pair (rotate + streaming GEMM)."""
+    the host is not the limit; time is per captured launch pair (rotate + streaming GEMM).
+    planes: the workspace also holds the partial-sum planes of the split-K launch."""
     res = {}
     for L in layers:
         K, N, h = L["K"], L["N"], L["h"]
@@ -383,7 +384,8 @@ def run_decode(torch, pq, layers, M=1, reps=3, warm=False):
         ws = [L["wq"].clone() for _ in range(ncopy)]
         x = L["x"][:M].contiguous()
         out = torch.empty((M, N), dtype=torch.float16, device="cuda")
-        work = torch.empty((max(256, pq.pq_linear_workspace_bytes(M, K)),), dtype=torch.uint8, device="cuda")
+        wbytes = pq.pq_linear_workspace_bytes_split(M, N, K) if planes else pq.pq_linear_workspace_bytes(M, K)
+        work = torch.empty((max(256, wbytes),), dtype=torch.uint8, device="cuda")
         pq.pq_linear(x, ws[0], L["sw"], L["sx"], h, out=out, workspace=work)
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
@@ -565,6 +567,17 @@ def main():
                               "per_linear_us": {k: v["us"] for k, v in d["per_linear"].items()}}
         return dec
 
+    def serving_leg():
+        # between decode and prefill: the tiled kernel alone, and with planes for its split-K launch
+        res = {"note": "pq_linear, cold weights, us per linear; 'planes': workspace of pq_linear_workspace_bytes_split"}
+        for m in (32, 64, 128, 256):
+            a = run_decode(torch, pq, layers, M=m)
+            b = run_decode(torch, pq, layers, M=m, planes=True)
+            res["M%d" % m] = {"per_linear_us": {k: v["us"] for k, v in a["per_linear"].items()},
+                              "per_linear_us_planes": {k: v["us"] for k, v in b["per_linear"].items()},
+                              "frac_hbm": a["frac_hbm"], "frac_hbm_planes": b["frac_hbm"]}
+        return res
+
     leg("int8_gemm", int8_leg)
     if not args.no_variants:
         leg("achievable", probes_leg)
@@ -573,6 +586,7 @@ def main():
         leg("variants", variants_leg)
     if not args.no_decode:
         leg("decode", decode_leg)
+        leg("serving_batch", serving_leg)
     if not args.no_variants:
         del layers
         torch.cuda.empty_cache()

@@ -78,15 +78,37 @@ int pq_w4a4_gemm(const void* xq_packed, const void* wq_packed, const float* w_sc
                  float act_scale, int64_t M, int64_t N, int64_t K,
                  void* out_f16, int32_t* acc_i32, void* stream);
 
-/* Bytes of workspace pq_linear needs (holds Xq): M*K/2 rounded up to 256.  Host only. */
+/* The same product with scratch memory for the range between decode and prefill (Sec. 5.4 times
+ * both ends; a serving batch of some dozens to some hundreds of tokens lies between): there the
+ * output has far fewer tiles than the GPU has compute units, so the K dimension is split over
+ * workgroups, each leaves an int32 plane of partial sums in `workspace`, and a second kernel adds
+ * the planes and applies the epilogue.  Integer sums are exact in any order: accumulators and
+ * outputs equal pq_w4a4_gemm's bit for bit.
+ * pq_w4a4_gemm_workspace_bytes: what the cost model's choice needs for the shape, 0 where it would
+ *   not split (few tokens: weight-streaming kernels; many: enough tiles).  Host only.
+ * workspace: device memory, 256-byte aligned, or NULL; workspace_bytes may be smaller than asked
+ *   for (fewer planes, or the unsplit kernel) or larger (the rest is untouched).  Its contents on
+ *   return are unspecified.  Calls that share a workspace must be ordered on one stream.
+ * Everything else as pq_w4a4_gemm, which is this call with workspace = NULL.
+ */
+size_t pq_w4a4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+int pq_w4a4_gemm_ws(const void* xq_packed, const void* wq_packed, const float* w_scale,
+                    float act_scale, int64_t M, int64_t N, int64_t K,
+                    void* out_f16, int32_t* acc_i32, void* workspace, size_t workspace_bytes,
+                    void* stream);
+
+/* Bytes of workspace pq_linear needs (holds Xq): M*K/2 rounded up to 256.  Host only.
+ * pq_linear_workspace_bytes_split adds pq_w4a4_gemm_workspace_bytes(M,N,K): with that much,
+ * pq_linear's product may split K as pq_w4a4_gemm_ws does (the codes come first, the planes after). */
 size_t pq_linear_workspace_bytes(int64_t M, int64_t K);
+size_t pq_linear_workspace_bytes_split(int64_t M, int64_t N, int64_t K);
 
 /* The whole layer: pq_rotate_quant into `workspace`, then pq_w4a4_gemm (same stream).
  * For M <= 4 and M*K <= 8192 (16384 without rotation, or for a single token) the two steps run in
  * one fused launch (every workgroup rotates and quantizes the few rows for itself while its first
  * weight loads are in flight).
  * workspace: device memory, 256-byte aligned, at least pq_linear_workspace_bytes(M,K);
- * its contents on return are the packed activation codes (canonical layout).
+ * its first M*K/2 bytes on return are the packed activation codes (canonical layout).
  */
 int pq_linear(const void* x_f16, const void* wq_packed, const float* w_scale,
               float act_scale, int32_t had_block, int64_t M, int64_t N, int64_t K,
@@ -116,7 +138,9 @@ int pq_probe_stream_read(const void* src, int64_t bytes, int32_t* sink, void* st
 /* Force a kernel variant of pq_w4a4_gemm for sweeps and tests (host, process-wide,
  * not thread-safe): 0 = automatic, 1 = weight-streaming matrix tiles (M <= 32, K % 256 == 0 and
  * the codes of 8 tokens fit in LDS; else PQ_ERR_UNSUPPORTED), 2 = MFMA tiled, 3 = simple,
- * 4 = weight-streaming 4-bit dot products (M <= 8 only).  With 4 pq_linear uses its fused single
+ * 4 = weight-streaming 4-bit dot products (M <= 8 only), 5 = MFMA tiled with K split in up to 5
+ * runs whenever the call has a workspace of two planes and K has 512 channels (else
+ * PQ_ERR_UNSUPPORTED; pq_w4a4_gemm_workspace_bytes then answers for 5 runs).  With 4 pq_linear uses its fused single
  * launch whenever the shape allows it; with 1, 2 or 3 it always uses two launches.
  * pq_w4a8_gemm, pq_gemm_dynamic and pq_w4a4_gemm_zp use a weight-streaming kernel only with 0,
  * or with 1 or 4 where that kernel supports the shape, and the tiled kernel otherwise.  The

@@ -27,6 +27,9 @@ SIGNATURES = {
     "pq_w4a4_gemm": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i64, _i64, _i64, _vp, _vp, _vp]),
     "pq_w4a4_gemm_simple": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i64, _i64, _i64, _vp, _vp, _vp]),
     "pq_linear_workspace_bytes": (_sz, [_i64, _i64]),
+    "pq_linear_workspace_bytes_split": (_sz, [_i64, _i64, _i64]),
+    "pq_w4a4_gemm_workspace_bytes": (_sz, [_i64, _i64, _i64]),
+    "pq_w4a4_gemm_ws": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i64, _i64, _i64, _vp, _vp, _vp, _sz, _vp]),
     "pq_linear": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i32, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
     "pq_set_gemm_variant": (ctypes.c_int, [ctypes.c_int]),
     "pq_probe_mfma_i8": (ctypes.c_int, [_vp, _i64, _i64, _i32, _vp, _vp]),
@@ -134,6 +137,25 @@ def pq_w4a4_gemm(xq, wq, w_scale, act_scale, want_out=True, want_acc=False, out=
 def pq_w4a4_gemm_simple(xq, wq, w_scale, act_scale, want_out=True, want_acc=False, out=None, acc=None):
     return _gemm(lib().pq_w4a4_gemm_simple, "pq_w4a4_gemm_simple", xq, wq, w_scale, act_scale, want_out, want_acc,
                  out, acc)
+
+
+def pq_w4a4_gemm_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(lib().pq_w4a4_gemm_workspace_bytes(M, N, K))
+
+
+def pq_w4a4_gemm_ws(xq, wq, w_scale, act_scale, workspace, want_out=True, want_acc=False, out=None, acc=None):
+    """pq_w4a4_gemm with scratch memory (uint8 device tensor or None) for the split-K launch."""
+    if workspace is not None:
+        _dev(workspace, torch.uint8, "workspace")
+
+    def fn(a, b, c, d, M, N, K, o, ac, st):
+        return lib().pq_w4a4_gemm_ws(a, b, c, d, M, N, K, o, ac, _ptr(workspace),
+                                     0 if workspace is None else workspace.numel(), st)
+    return _gemm(fn, "pq_w4a4_gemm_ws", xq, wq, w_scale, act_scale, want_out, want_acc, out, acc)
+
+
+def pq_linear_workspace_bytes_split(M: int, N: int, K: int) -> int:
+    return int(lib().pq_linear_workspace_bytes_split(M, N, K))
 
 
 def pq_linear_workspace_bytes(M: int, K: int) -> int:

@@ -6,7 +6,7 @@
 
 namespace {
 
-int g_variant = 0;  // 0 auto, 1 streaming MFMA (M <= 16), 2 MFMA tiled, 3 simple, 4 streaming dot (M <= 8)
+int g_variant = 0;  // 0 auto, 1 streaming MFMA (M <= 32), 2 MFMA tiled, 3 simple, 4 streaming dot (M <= 8), 5 tiled, K split
 
 // Kernel for a product with given codes and few tokens: 4 = weight-streaming dot products
 // (k_decode), 1 = weight-streaming matrix tiles (k_stream_mfma), 2 = the tiled kernel, -1 = the
@@ -29,6 +29,19 @@ int pick_few_tokens(int64_t M, int64_t N, int64_t K, int32_t abits)
     if (dot && (M <= dot_limit || !mat)) return 4;
     if (mat && (M <= 16 || K >= 8192 || size < 2)) return 1;
     return 2;
+}
+
+// The same choice for 4-bit codes when the call brings scratch memory for partial-sum planes.
+// 17 to 32 tokens: with its planes in place the split tiled launch beats two launches of the matrix
+// streaming kernel on all but small matrices (10-14 us against 11-16; 9-10 either way under 12 MB).
+int pick_with_planes(int64_t M, int64_t N, int64_t K, size_t plane_bytes)
+{
+    const int kernel = pick_few_tokens(M, N, K, 4);
+    if (g_variant == 0 && kernel == 1 && M > 16 && N * (K / 2) >= 12000000) {
+        const size_t want = pq::gemm_splitk_workspace_bytes(M, N, K);
+        if (want > 0 && plane_bytes >= want) return 2;
+    }
+    return kernel;
 }
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -80,23 +93,40 @@ int pq_rotate_quant(const void* x_f16, int64_t M, int64_t K, int32_t had_block, 
     return pq::launch_rotate_quant(x_f16, M, K, had_block, act_scale, xq_packed, static_cast<hipStream_t>(stream));
 }
 
-int pq_w4a4_gemm(const void* xq_packed, const void* wq_packed, const float* w_scale, float act_scale, int64_t M,
-                 int64_t N, int64_t K, void* out_f16, int32_t* acc_i32, void* stream)
+int pq_w4a4_gemm_ws(const void* xq_packed, const void* wq_packed, const float* w_scale, float act_scale, int64_t M,
+                    int64_t N, int64_t K, void* out_f16, int32_t* acc_i32, void* workspace, size_t workspace_bytes,
+                    void* stream)
 {
     int rc = check_gemm(xq_packed, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32);
     if (rc != PQ_OK) return rc;
+    if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 255u)) return PQ_ERR_ALIGN;
     if (M == 0) return PQ_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (g_variant == 3)
         return pq::launch_gemm_simple(xq_packed, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32, st);
-    switch (pick_few_tokens(M, N, K, 4)) {
+    switch (pick_with_planes(M, N, K, workspace ? workspace_bytes : 0)) {
         case 4:
             return pq::launch_decode(nullptr, xq_packed, wq_packed, w_scale, act_scale, 1, M, N, K, out_f16, acc_i32,
                                      nullptr, st);
         case 1: return pq::launch_stream_mfma(xq_packed, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32, st);
-        case 2: return pq::launch_gemm_mfma(xq_packed, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32, st);
+        case 2:
+            return pq::launch_gemm_mfma_ws(xq_packed, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32,
+                                           workspace, workspace ? workspace_bytes : 0, g_variant == 5, st);
         default: return PQ_ERR_UNSUPPORTED;
     }
+}
+
+int pq_w4a4_gemm(const void* xq_packed, const void* wq_packed, const float* w_scale, float act_scale, int64_t M,
+                 int64_t N, int64_t K, void* out_f16, int32_t* acc_i32, void* stream)
+{
+    return pq_w4a4_gemm_ws(xq_packed, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32, nullptr, 0, stream);
+}
+
+size_t pq_w4a4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    if (M <= 0 || N <= 0 || K <= 0 || (K % 32) != 0 || (N % 16) != 0) return 0;
+    if (g_variant == 3 || pick_with_planes(M, N, K, ~(size_t)0) != 2) return 0;
+    return pq::gemm_splitk_workspace_bytes(M, N, K, g_variant == 5);
 }
 
 int pq_w4a4_gemm_simple(const void* xq_packed, const void* wq_packed, const float* w_scale, float act_scale,
@@ -141,7 +171,15 @@ int pq_linear(const void* x_f16, const void* wq_packed, const float* w_scale, fl
                                  workspace, static_cast<hipStream_t>(stream));
     rc = pq_rotate_quant(x_f16, M, K, had_block, act_scale, workspace, stream);
     if (rc != PQ_OK) return rc;
-    return pq_w4a4_gemm(workspace, wq_packed, w_scale, act_scale, M, N, K, out_f16, nullptr, stream);
+    // whatever the workspace holds beyond the codes serves the product's split launch
+    const size_t codes = pq_linear_workspace_bytes(M, K);
+    return pq_w4a4_gemm_ws(workspace, wq_packed, w_scale, act_scale, M, N, K, out_f16, nullptr,
+                           static_cast<uint8_t*>(workspace) + codes, workspace_bytes - codes, stream);
+}
+
+size_t pq_linear_workspace_bytes_split(int64_t M, int64_t N, int64_t K)
+{
+    return pq_linear_workspace_bytes(M, K) + pq_w4a4_gemm_workspace_bytes(M, N, K);
 }
 
 int pq_rotate_quant8(const void* x_f16, int64_t M, int64_t K, int32_t had_block, float act_scale,
@@ -447,7 +485,7 @@ int pq_probe_stream_read(const void* src, int64_t bytes, int32_t* sink, void* st
 
 int pq_set_gemm_variant(int variant)
 {
-    if (variant < 0 || variant > 4) return -1;
+    if (variant < 0 || variant > 5) return -1;
     const int prev = g_variant;
     g_variant = variant;
     return prev;

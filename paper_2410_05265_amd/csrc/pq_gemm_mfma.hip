@@ -116,10 +116,13 @@ template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_wai
 
 // One output tile [m0, m0 + BM) x [n0, n0 + BN) by the whole workgroup (the LDS ring is the
 // workgroup's dynamic shared memory).
-template <int BM, int BN, int WR, int WC, int NS, int SUBS, int ABITS, int ASHIFT>
+// SPLIT: the tile covers only the ring stages [kt0, kt0 + nk_part) of the K dimension and leaves
+// its accumulators (shift undone) in acc_out, a partial-sum plane of M x N int32; nothing else is
+// written.  Without SPLIT the two arguments are ignored and the whole of K is covered.
+template <int BM, int BN, int WR, int WC, int NS, int SUBS, int ABITS, int ASHIFT, bool SPLIT = false>
 __device__ __forceinline__ void gemm_tile(const uint8_t* xq, const uint8_t* wq, const float* sw, float sx, int M, int N,
                                           int K, int m0, int n0, __half* out, int32_t* acc_out, const float* srow,
-                                          const int32_t* zcorr)
+                                          const int32_t* zcorr, int kt0 = 0, int nk_part = 0)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     constexpr int NW = WR * WC;
@@ -144,7 +147,11 @@ __device__ __forceinline__ void gemm_tile(const uint8_t* xq, const uint8_t* wq, 
     const int r = lane & 31, g = lane >> 5;
 
     const int Kb = K >> 1;
-    const int nk = K / (128 * SUBS);
+    const int nk = SPLIT ? nk_part : K / (128 * SUBS);
+    if constexpr (SPLIT) {
+        xq += (size_t)kt0 * SUBS * (ABITS == 8 ? 128 : 64);
+        wq += (size_t)kt0 * SUBS * 64;
+    }
 
     // ---- loader
     const int lrow = lane >> 2, lpos = lane & 3;
@@ -306,6 +313,23 @@ __device__ __forceinline__ void gemm_tile(const uint8_t* xq, const uint8_t* wq, 
     constexpr int ROWB = UPR * 16 + 16;         // padded row pitch in LDS
     constexpr int REGION = 32 * ROWB;
     static_assert((size_t)NW * REGION <= (size_t)NS * STAGE, "epilogue staging does not fit the ring");
+    if constexpr (SPLIT) {
+        // a lane's registers 4 q .. 4 q + 3 are four consecutive channels: 16-byte stores
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int m = m0 + wm * WM + i * 32 + r;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int n = n0 + wn * WN + j * 32 + 8 * q + 4 * g;
+                    const v4i val = {acc[i][j][4 * q] >> ASHIFT, acc[i][j][4 * q + 1] >> ASHIFT,
+                                     acc[i][j][4 * q + 2] >> ASHIFT, acc[i][j][4 * q + 3] >> ASHIFT};
+                    if (m < M && n + 4 <= N) *reinterpret_cast<v4i*>(acc_out + (int64_t)m * N + n) = val;
+                }
+        }
+        return;
+    }
     lds_barrier();
     uint8_t* stg = smem + wave * REGION;
     if (acc_out) {
@@ -480,6 +504,83 @@ int launch_dma(const void* xq, const void* wq, const float* sw, float sx, int64_
     hipLaunchKernelGGL(kern, dim3((unsigned)(GM * GN)), dim3(WR * WC * 64), lds, st,
                        static_cast<const uint8_t*>(xq), static_cast<const uint8_t*>(wq), sw, sx, (int)M, (int)N,
                        (int)K, GM, static_cast<__half*>(out), acc, srow, zcorr);
+    return hip_status(hipGetLastError());
+}
+
+// ---------------------------------------------------------------------------------------
+// Split K: for a few dozen to a few hundred tokens the output has far fewer tiles than the chip has
+// CUs and a tile's time is set by K alone.  Workgroup (tile, s) covers the s-th of S nearly equal
+// runs of 128-channel stages and leaves an int32 plane of partial sums in the caller's workspace;
+// k_splitk_reduce adds the planes and applies the same epilogue arithmetic as the tiled kernel
+// (integer sums are exact in any order, so accumulators and outputs equal the unsplit ones).
+template <int BM, int BN, int WR, int WC, int NS>
+__global__ __launch_bounds__(WR * WC * 64) void k_gemm_splitk(const uint8_t* __restrict__ xq,
+                                                             const uint8_t* __restrict__ wq, int M, int N, int K,
+                                                             int GM, int tiles, int S, int32_t* __restrict__ part)
+{
+    const int tile = blockIdx.x % tiles, s = blockIdx.x / tiles;
+    const int nk = K / 128;
+    const int kt0 = (int)((int64_t)nk * s / S), kt1 = (int)((int64_t)nk * (s + 1) / S);
+    gemm_tile<BM, BN, WR, WC, NS, 1, 4, 8, true>(xq, wq, nullptr, 0.0f, M, N, K, (tile % GM) * BM, (tile / GM) * BN, nullptr,
+                                                 part + (int64_t)s * M * N, nullptr, nullptr, kt0, kt1 - kt0);
+}
+
+// 8 consecutive channels of one token per thread: sum of the S planes, then acc and / or
+// out = fp16(fp32(256 acc) * (sw[n] * (sx / 256))), the tiled kernel's expression.
+__global__ __launch_bounds__(256) void k_splitk_reduce(const int32_t* __restrict__ part, int S, int64_t plane,
+                                                       const float* __restrict__ sw, float sx, int N,
+                                                       __half* __restrict__ out, int32_t* __restrict__ acc_out)
+{
+    const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
+    if (e >= plane) return;
+    const int n = (int)(e % N);
+    v4i a = *reinterpret_cast<const v4i*>(part + e), b = *reinterpret_cast<const v4i*>(part + e + 4);
+    for (int s = 1; s < S; ++s) {
+        a += *reinterpret_cast<const v4i*>(part + s * plane + e);
+        b += *reinterpret_cast<const v4i*>(part + s * plane + e + 4);
+    }
+    if (acc_out) {
+        *reinterpret_cast<v4i*>(acc_out + e) = a;
+        *reinterpret_cast<v4i*>(acc_out + e + 4) = b;
+    }
+    if (out) {
+        const float f = sx * (1.0f / 256.0f);
+        float4 s0 = *reinterpret_cast<const float4*>(sw + n), s1 = *reinterpret_cast<const float4*>(sw + n + 4);
+        s0.x *= f; s0.y *= f; s0.z *= f; s0.w *= f;
+        s1.x *= f; s1.y *= f; s1.z *= f; s1.w *= f;
+        const __half2 h0 = __floats2half2_rn(mul_rn((float)(a.x << 8), s0.x), mul_rn((float)(a.y << 8), s0.y));
+        const __half2 h1 = __floats2half2_rn(mul_rn((float)(a.z << 8), s0.z), mul_rn((float)(a.w << 8), s0.w));
+        const __half2 h2 = __floats2half2_rn(mul_rn((float)(b.x << 8), s1.x), mul_rn((float)(b.y << 8), s1.y));
+        const __half2 h3 = __floats2half2_rn(mul_rn((float)(b.z << 8), s1.z), mul_rn((float)(b.w << 8), s1.w));
+        v4i val;
+        val.x = *reinterpret_cast<const int*>(&h0); val.y = *reinterpret_cast<const int*>(&h1);
+        val.z = *reinterpret_cast<const int*>(&h2); val.w = *reinterpret_cast<const int*>(&h3);
+        *reinterpret_cast<v4i*>(out + e) = val;
+    }
+}
+
+template <int BM>
+int launch_splitk(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K, int S,
+                  void* out, int32_t* acc, int32_t* part, hipStream_t st)
+{
+    // (a ring of 4 or 6 stages measured the same as 3)
+    constexpr int BN = 128, NS = 3;
+    const int GM = (int)((M + BM - 1) / BM), GN = (int)((N + BN - 1) / BN);
+    constexpr size_t lds = (size_t)NS * (BM * 64 + BN * 64);
+    auto kern = k_gemm_splitk<BM, BN, 2, 2, NS>;
+    static bool attr_set = false;  // benign race: the call is idempotent
+    if (lds > 48 * 1024 && !attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds) != hipSuccess)
+            return PQ_ERR_HIP;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)(GM * GN * S)), dim3(256), lds, st, static_cast<const uint8_t*>(xq),
+                       static_cast<const uint8_t*>(wq), (int)M, (int)N, (int)K, GM, GM * GN, S, part);
+    if (hipGetLastError() != hipSuccess) return PQ_ERR_HIP;
+    const int64_t plane = M * N;
+    hipLaunchKernelGGL(k_splitk_reduce, dim3((unsigned)((plane / 8 + 255) / 256)), dim3(256), 0, st, part, S, plane, sw,
+                       sx, (int)N, static_cast<__half*>(out), acc);
     return hip_status(hipGetLastError());
 }
 
@@ -683,6 +784,44 @@ bool pick_dual(int64_t M, int64_t N, int* n1_out, int* n2_out)
     return found;
 }
 
+// Tile height and number of K runs of the split launch, from a cost model in microseconds
+// (per 128-channel stage: 0.42 for a 128 x 128 tile, 0.77 for 256 x 128, 1.35 for 256 x 256; 4 per
+// launch; partial planes written and read back at ~3 TB/s).  S = 1: the unsplit kernel is cheaper
+// or the workspace holds no two planes.
+void plan_splitk(int64_t M, int64_t N, int64_t K, size_t ws_bytes, bool force, int* bm_out, int* s_out)
+{
+    *bm_out = 128;
+    *s_out = 1;
+    if (K % 128 != 0 || N % 8 != 0 || M * N >= ((int64_t)1 << 31)) return;
+    const int64_t nk = K / 128;
+    if (force) {   // as many runs as fit, up to 5 (an odd count: uneven runs); tall tiles from 129 tokens on
+        int S = 5;
+        while (S > 1 && ((int64_t)S * 2 > nk || (size_t)S * (size_t)M * N * 4 > ws_bytes)) --S;
+        *bm_out = M > 128 ? 256 : 128;
+        *s_out = S;
+        return;
+    }
+    const double out_us = (double)M * N * 2 / 4.2e6;
+    double best = 1e300;
+    for (int c = 0; c < kNumAuto; ++c) {
+        const int64_t tiles = ((M + kCfgs[c].bm - 1) / kCfgs[c].bm) * ((N + kCfgs[c].bn - 1) / kCfgs[c].bn);
+        const double tk = 1.35 * kCfgs[c].bm * kCfgs[c].bn / 65536.0 / kCfgs[c].eff;
+        const double cost = 4.0 + (double)((tiles + 255) / 256) * nk * tk + out_us;
+        if (cost < best) best = cost;
+    }
+    const size_t plane_bytes = (size_t)M * N * 4;
+    for (int bm = 128; bm <= 256; bm *= 2) {
+        const int64_t tiles = ((M + bm - 1) / bm) * ((N + 127) / 128);
+        const double tk = bm == 128 ? 0.42 : 0.77;
+        for (int S = 2; S <= 32 && (int64_t)S * 2 <= nk && (size_t)S * plane_bytes <= ws_bytes; ++S) {
+            const int64_t rounds = (tiles * S + 255) / 256;
+            const double cost = 4.0 + (double)rounds * (double)((nk + S - 1) / S) * tk + 3.0 +
+                                (2.0 * S * plane_bytes + (double)M * N * 2) / 3.0e6;
+            if (cost < best) { best = cost; *bm_out = bm; *s_out = S; }
+        }
+    }
+}
+
 }  // namespace
 
 int launch_gemm_mfma(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K,
@@ -705,6 +844,25 @@ int launch_gemm_mfma(const void* xq, const void* wq, const float* sw, float sx, 
         case 7: return launch_dma<256, 128, 2, 4, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
         default: return launch_dma<256, 256, 2, 2, 4, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
     }
+}
+
+size_t gemm_splitk_workspace_bytes(int64_t M, int64_t N, int64_t K, bool force)
+{
+    int bm, S;
+    plan_splitk(M, N, K, ~(size_t)0, force, &bm, &S);
+    return S > 1 ? (size_t)S * (size_t)M * (size_t)N * 4 : 0;
+}
+
+int launch_gemm_mfma_ws(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K,
+                        void* out, int32_t* acc, void* ws, size_t ws_bytes, bool force, hipStream_t st)
+{
+    int bm = 128, S = 1;
+    if (ws && M <= (1 << 30) && N <= (1 << 30) && K <= (1 << 30) && M * (K / 2) < ((int64_t)1 << 32) &&
+        N * (K / 2) < ((int64_t)1 << 32))
+        plan_splitk(M, N, K, ws_bytes, force, &bm, &S);
+    if (S <= 1) return force ? PQ_ERR_UNSUPPORTED : launch_gemm_mfma(xq, wq, sw, sx, M, N, K, out, acc, st);
+    if (bm == 128) return launch_splitk<128>(xq, wq, sw, sx, M, N, K, S, out, acc, static_cast<int32_t*>(ws), st);
+    return launch_splitk<256>(xq, wq, sw, sx, M, N, K, S, out, acc, static_cast<int32_t*>(ws), st);
 }
 
 // 4-bit weights x 8-bit activations (codes in the even/odd-grouped byte order written by the

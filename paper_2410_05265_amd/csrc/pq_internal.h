@@ -43,6 +43,13 @@ int launch_gemm_simple(const void* xq, const void* wq, const float* sw, float sx
                        int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st);
 int launch_gemm_mfma(const void* xq, const void* wq, const float* sw, float sx, int64_t M,
                      int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st);
+// The tiled kernel with K split over workgroups where a cost model finds that cheaper (few tokens
+// per CU); ws holds the partial planes (gemm_splitk_workspace_bytes; 0 = never splits for the shape),
+// a smaller one gets fewer planes or the unsplit launch.  force: split whenever K has two runs of two
+// stages and ws holds two planes (tests); PQ_ERR_UNSUPPORTED if not.
+size_t gemm_splitk_workspace_bytes(int64_t M, int64_t N, int64_t K, bool force = false);
+int launch_gemm_mfma_ws(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K,
+                        void* out, int32_t* acc, void* ws, size_t ws_bytes, bool force, hipStream_t st);
 int launch_probe_mfma(const void* operands, int64_t operand_bytes, int64_t iters, int32_t workgroups, int32_t* sink,
                       hipStream_t st);
 int launch_probe_read(const void* src, int64_t bytes, int32_t* sink, hipStream_t st);

@@ -45,6 +45,16 @@ def test_host_only_calls(b):
     assert L.pq_linear_workspace_bytes(3, 4096) == 6144
     assert L.pq_linear_workspace_bytes(2048, 14336) == 2048 * 7168
     assert L.pq_set_gemm_variant(9) == -1 and L.pq_set_gemm_variant(0) == 0
+    # planes of partial sums for the split launch: none for decode and prefill, some in between
+    wsb = L.pq_w4a4_gemm_workspace_bytes
+    assert wsb(1, 4096, 4096) == 0 and wsb(16, 4096, 14336) == 0 and wsb(2048, 4096, 14336) == 0
+    assert wsb(64, 4096, 14336) == 8 * 64 * 4096 * 4 and wsb(24, 4096, 14336) == 8 * 24 * 4096 * 4
+    assert wsb(64, 4096, 14336 + 32) == 0 and wsb(64, 4090, 4096) == 0 and wsb(-1, 4096, 4096) == 0
+    assert L.pq_linear_workspace_bytes_split(64, 4096, 14336) == 64 * 7168 + 8 * 64 * 4096 * 4
+    assert L.pq_linear_workspace_bytes_split(2048, 4096, 14336) == 2048 * 7168
+    assert L.pq_set_gemm_variant(5) == 0
+    assert wsb(100, 256, 2048) == 5 * 100 * 256 * 4 and wsb(100, 256, 384) == 0
+    assert L.pq_set_gemm_variant(0) == 5
     assert L.pq_linear_w4a8_workspace_bytes(3, 4096) == 12288
     assert L.pq_linear_dynamic_workspace_bytes(3, 4096, 4) == 6144 + 256
     assert L.pq_linear_dynamic_workspace_bytes(100, 128, 8) == 12800 + 512
@@ -81,6 +91,18 @@ def test_argument_errors_launch_nothing(b):
         assert g(p, odd, p, 0.1, 4, 64, 512, p, nul, nul) == b.PQ_ERR_ALIGN
         assert g(p, p, p, -2.0, 4, 64, 512, p, nul, nul) == b.PQ_ERR_SCALE
         assert g(p, p, p, 0.1, 0, 64, 512, p, nul, nul) == b.PQ_OK
+
+    gw = L.pq_w4a4_gemm_ws
+    assert gw(nul, p, p, 0.1, 64, 64, 512, p, nul, nul, 0, nul) == b.PQ_ERR_NULL
+    assert gw(p, p, p, 0.1, 64, 60, 512, p, nul, nul, 0, nul) == b.PQ_ERR_SHAPE
+    assert gw(p, p, p, 0.1, 64, 64, 512, p, nul, odd, 1 << 20, nul) == b.PQ_ERR_ALIGN      # workspace: 256 bytes
+    assert gw(p, p, p, 0.0, 64, 64, 512, p, nul, nul, 0, nul) == b.PQ_ERR_SCALE
+    assert gw(p, p, p, 0.1, 0, 64, 512, p, nul, nul, 0, nul) == b.PQ_OK
+    prev = L.pq_set_gemm_variant(5)
+    try:
+        assert gw(p, p, p, 0.1, 64, 64, 512, p, nul, nul, 0, nul) == b.PQ_ERR_UNSUPPORTED   # forced split, no planes
+    finally:
+        L.pq_set_gemm_variant(prev)
 
     lin = L.pq_linear
     assert lin(p, p, p, 0.1, 128, 4, 64, 512, p, nul, 0, nul) == b.PQ_ERR_WORKSPACE
