@@ -458,6 +458,8 @@ def main():
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-variants", action="store_true", help="skip the W4A8 / per-token dynamic variants of the step")
+    ap.add_argument("--serving-only", action="store_true",
+                    help="of the side legs run only serving_batch (32..256 tokens); for profiles")
     ap.add_argument("--cpu-rows", type=int, default=1024)
     ap.add_argument("--profile-copy", action="store_true",
                     help="also run a plain 256 MiB elementwise copy (calibrates HBM counters under rocprofv3 --pmc)")
@@ -578,14 +580,18 @@ def main():
                               "frac_hbm": a["frac_hbm"], "frac_hbm_planes": b["frac_hbm"]}
         return res
 
-    leg("int8_gemm", int8_leg)
+    if args.serving_only:
+        args.no_variants = args.no_cpu = True
+    else:
+        leg("int8_gemm", int8_leg)
     if not args.no_variants:
         leg("achievable", probes_leg)
         leg("prefill_8192", lambda: run_prefill_8192(torch, pq, layers))
         leg("side_rows", lambda: run_side_rows(torch, pq, synth, M_PREFILL))
         leg("variants", variants_leg)
-    if not args.no_decode:
+    if not args.no_decode and not args.serving_only:
         leg("decode", decode_leg)
+    if args.serving_only or not (args.no_decode or args.no_variants):
         leg("serving_batch", serving_leg)
     if not args.no_variants:
         del layers

@@ -33,11 +33,11 @@ int pick_few_tokens(int64_t M, int64_t N, int64_t K, int32_t abits)
 
 // The same choice for 4-bit codes when the call brings scratch memory for partial-sum planes.
 // 17 to 32 tokens: with its planes in place the split tiled launch beats two launches of the matrix
-// streaming kernel on all but small matrices (10-14 us against 11-16; 9-10 either way under 12 MB).
+// streaming kernel on matrices of 8 MB and more (8-14 us against 9-16; not measured below).
 int pick_with_planes(int64_t M, int64_t N, int64_t K, size_t plane_bytes)
 {
     const int kernel = pick_few_tokens(M, N, K, 4);
-    if (g_variant == 0 && kernel == 1 && M > 16 && N * (K / 2) >= 12000000) {
+    if (g_variant == 0 && kernel == 1 && M > 16 && N * (K / 2) >= 8000000) {
         const size_t want = pq::gemm_splitk_workspace_bytes(M, N, K);
         if (want > 0 && plane_bytes >= want) return 2;
     }

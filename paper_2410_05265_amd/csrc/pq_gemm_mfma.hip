@@ -525,37 +525,35 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_splitk(const uint8_t* __r
                                                  part + (int64_t)s * M * N, nullptr, nullptr, kt0, kt1 - kt0);
 }
 
-// 8 consecutive channels of one token per thread: sum of the S planes, then acc and / or
-// out = fp16(fp32(256 acc) * (sw[n] * (sx / 256))), the tiled kernel's expression.
+// 4 consecutive channels of one token per thread: sum of the S planes (four loads in flight), then
+// acc and / or out = fp16(fp32(256 acc) * (sw[n] * (sx / 256))), the tiled kernel's expression.
 __global__ __launch_bounds__(256) void k_splitk_reduce(const int32_t* __restrict__ part, int S, int64_t plane,
                                                        const float* __restrict__ sw, float sx, int N,
                                                        __half* __restrict__ out, int32_t* __restrict__ acc_out)
 {
-    const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
+    const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
     if (e >= plane) return;
     const int n = (int)(e % N);
-    v4i a = *reinterpret_cast<const v4i*>(part + e), b = *reinterpret_cast<const v4i*>(part + e + 4);
-    for (int s = 1; s < S; ++s) {
-        a += *reinterpret_cast<const v4i*>(part + s * plane + e);
-        b += *reinterpret_cast<const v4i*>(part + s * plane + e + 4);
+    const int32_t* p = part + e;
+    v4i a = {0, 0, 0, 0};
+    int s = 0;
+    for (; s + 4 <= S; s += 4) {
+        const v4i t0 = *reinterpret_cast<const v4i*>(p + (s + 0) * plane), t1 = *reinterpret_cast<const v4i*>(p + (s + 1) * plane);
+        const v4i t2 = *reinterpret_cast<const v4i*>(p + (s + 2) * plane), t3 = *reinterpret_cast<const v4i*>(p + (s + 3) * plane);
+        a += (t0 + t1) + (t2 + t3);
     }
-    if (acc_out) {
-        *reinterpret_cast<v4i*>(acc_out + e) = a;
-        *reinterpret_cast<v4i*>(acc_out + e + 4) = b;
-    }
+    for (; s < S; ++s) a += *reinterpret_cast<const v4i*>(p + s * plane);
+    if (acc_out) *reinterpret_cast<v4i*>(acc_out + e) = a;
     if (out) {
         const float f = sx * (1.0f / 256.0f);
-        float4 s0 = *reinterpret_cast<const float4*>(sw + n), s1 = *reinterpret_cast<const float4*>(sw + n + 4);
+        float4 s0 = *reinterpret_cast<const float4*>(sw + n);
         s0.x *= f; s0.y *= f; s0.z *= f; s0.w *= f;
-        s1.x *= f; s1.y *= f; s1.z *= f; s1.w *= f;
         const __half2 h0 = __floats2half2_rn(mul_rn((float)(a.x << 8), s0.x), mul_rn((float)(a.y << 8), s0.y));
         const __half2 h1 = __floats2half2_rn(mul_rn((float)(a.z << 8), s0.z), mul_rn((float)(a.w << 8), s0.w));
-        const __half2 h2 = __floats2half2_rn(mul_rn((float)(b.x << 8), s1.x), mul_rn((float)(b.y << 8), s1.y));
-        const __half2 h3 = __floats2half2_rn(mul_rn((float)(b.z << 8), s1.z), mul_rn((float)(b.w << 8), s1.w));
-        v4i val;
-        val.x = *reinterpret_cast<const int*>(&h0); val.y = *reinterpret_cast<const int*>(&h1);
-        val.z = *reinterpret_cast<const int*>(&h2); val.w = *reinterpret_cast<const int*>(&h3);
-        *reinterpret_cast<v4i*>(out + e) = val;
+        uint2 val;
+        val.x = *reinterpret_cast<const uint32_t*>(&h0);
+        val.y = *reinterpret_cast<const uint32_t*>(&h1);
+        *reinterpret_cast<uint2*>(out + e) = val;
     }
 }
 
@@ -579,7 +577,7 @@ int launch_splitk(const void* xq, const void* wq, const float* sw, float sx, int
                        static_cast<const uint8_t*>(wq), (int)M, (int)N, (int)K, GM, GM * GN, S, part);
     if (hipGetLastError() != hipSuccess) return PQ_ERR_HIP;
     const int64_t plane = M * N;
-    hipLaunchKernelGGL(k_splitk_reduce, dim3((unsigned)((plane / 8 + 255) / 256)), dim3(256), 0, st, part, S, plane, sw,
+    hipLaunchKernelGGL(k_splitk_reduce, dim3((unsigned)((plane / 4 + 255) / 256)), dim3(256), 0, st, part, S, plane, sw,
                        sx, (int)N, static_cast<__half*>(out), acc);
     return hip_status(hipGetLastError());
 }
