@@ -783,7 +783,8 @@ bool pick_dual(int64_t M, int64_t N, int* n1_out, int* n2_out)
 }
 
 // Tile height and number of K runs of the split launch, from a cost model in microseconds
-// (per 128-channel stage: 0.42 for a 128 x 128 tile, 0.77 for 256 x 128, 1.35 for 256 x 256; 4 per
+// (per 128-channel stage: 0.27 for a 64 x 128 tile, 0.42 for 128 x 128, 0.77 for 256 x 128, 1.35 for
+// 256 x 256; 4 per
 // launch; partial planes written and read back at ~3 TB/s).  S = 1: the unsplit kernel is cheaper
 // or the workspace holds no two planes.
 void plan_splitk(int64_t M, int64_t N, int64_t K, size_t ws_bytes, bool force, int* bm_out, int* s_out)
@@ -792,10 +793,10 @@ void plan_splitk(int64_t M, int64_t N, int64_t K, size_t ws_bytes, bool force, i
     *s_out = 1;
     if (K % 128 != 0 || N % 8 != 0 || M * N >= ((int64_t)1 << 31)) return;
     const int64_t nk = K / 128;
-    if (force) {   // as many runs as fit, up to 5 (an odd count: uneven runs); tall tiles from 129 tokens on
+    if (force) {   // as many runs as fit, up to 5 (an odd count: uneven runs); the lowest tile that covers M
         int S = 5;
         while (S > 1 && ((int64_t)S * 2 > nk || (size_t)S * (size_t)M * N * 4 > ws_bytes)) --S;
-        *bm_out = M > 128 ? 256 : 128;
+        *bm_out = M > 128 ? 256 : (M > 64 ? 128 : 64);
         *s_out = S;
         return;
     }
@@ -808,9 +809,9 @@ void plan_splitk(int64_t M, int64_t N, int64_t K, size_t ws_bytes, bool force, i
         if (cost < best) best = cost;
     }
     const size_t plane_bytes = (size_t)M * N * 4;
-    for (int bm = 128; bm <= 256; bm *= 2) {
+    for (int bm = M <= 128 ? 64 : 128; bm <= 256; bm *= 2) {   // (four row tiles of 64: down_proj measured 5 us slower)
         const int64_t tiles = ((M + bm - 1) / bm) * ((N + 127) / 128);
-        const double tk = bm == 128 ? 0.42 : 0.77;
+        const double tk = bm == 64 ? 0.27 : (bm == 128 ? 0.42 : 0.77);
         for (int S = 2; S <= 32 && (int64_t)S * 2 <= nk && (size_t)S * plane_bytes <= ws_bytes; ++S) {
             const int64_t rounds = (tiles * S + 255) / 256;
             const double cost = 4.0 + (double)rounds * (double)((nk + S - 1) / S) * tk + 3.0 +
@@ -859,6 +860,7 @@ int launch_gemm_mfma_ws(const void* xq, const void* wq, const float* sw, float s
         N * (K / 2) < ((int64_t)1 << 32))
         plan_splitk(M, N, K, ws_bytes, force, &bm, &S);
     if (S <= 1) return force ? PQ_ERR_UNSUPPORTED : launch_gemm_mfma(xq, wq, sw, sx, M, N, K, out, acc, st);
+    if (bm == 64) return launch_splitk<64>(xq, wq, sw, sx, M, N, K, S, out, acc, static_cast<int32_t*>(ws), st);
     if (bm == 128) return launch_splitk<128>(xq, wq, sw, sx, M, N, K, S, out, acc, static_cast<int32_t*>(ws), st);
     return launch_splitk<256>(xq, wq, sw, sx, M, N, K, S, out, acc, static_cast<int32_t*>(ws), st);
 }

@@ -3,7 +3,7 @@ hundreds of tokens) against the oracle.
 
 Integer work: the accumulators are bit-exact whatever the number of K runs, and the fp16 outputs are
 bit-identical to the unsplit tiled kernel's (the reduce kernel applies the same expression).  Shapes
-cover: both tile heights, token counts that are no multiple of a tile, output widths that are no
+cover: the three tile heights, token counts that are no multiple of a tile, output widths that are no
 multiple of 128, run counts that do not divide the number of 128-channel stages, a K with the
 minimum of two stages per run, a workspace that is too small (fewer planes, or none), a workspace
 larger than asked for, the automatic choice at the sizes of the benchmark's linears, and pq_linear
