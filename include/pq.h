@@ -92,6 +92,8 @@ int pq_w4a4_gemm(const void* xq_packed, const void* wq_packed, const float* w_sc
  * Everything else as pq_w4a4_gemm, which is this call with workspace = NULL.
  */
 size_t pq_w4a4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+/* The same query for any of the products below: act_bits = 4 or 8 (else 0). */
+size_t pq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int32_t act_bits);
 int pq_w4a4_gemm_ws(const void* xq_packed, const void* wq_packed, const float* w_scale,
                     float act_scale, int64_t M, int64_t N, int64_t K,
                     void* out_f16, int32_t* acc_i32, void* workspace, size_t workspace_bytes,
@@ -174,8 +176,17 @@ int pq_w4a8_gemm(const void* xq8_grouped, const void* wq_packed, const float* w_
                  float act_scale, int64_t M, int64_t N, int64_t K,
                  void* out_f16, int32_t* acc_i32, void* stream);
 
-/* Workspace of pq_linear_w4a8: M*K bytes rounded up to 256.  Host only. */
+/* pq_w4a8_gemm with scratch memory for the split-K launch: workspace as for pq_w4a4_gemm_ws, sized by
+ * pq_gemm_workspace_bytes(M,N,K,8); results equal pq_w4a8_gemm's bit for bit. */
+int pq_w4a8_gemm_ws(const void* xq8_grouped, const void* wq_packed, const float* w_scale,
+                    float act_scale, int64_t M, int64_t N, int64_t K,
+                    void* out_f16, int32_t* acc_i32, void* workspace, size_t workspace_bytes,
+                    void* stream);
+
+/* Workspace of pq_linear_w4a8: M*K bytes rounded up to 256; _split adds the planes of
+ * pq_gemm_workspace_bytes(M,N,K,8), which the layer's product then uses.  Host only. */
 size_t pq_linear_w4a8_workspace_bytes(int64_t M, int64_t K);
+size_t pq_linear_w4a8_workspace_bytes_split(int64_t M, int64_t N, int64_t K);
 
 /* pq_rotate_quant8 into `workspace`, then pq_w4a8_gemm, on the same stream. */
 int pq_linear_w4a8(const void* x_f16, const void* wq_packed, const float* w_scale,
@@ -205,10 +216,19 @@ int pq_gemm_dynamic(const void* xq, int32_t bits, const void* wq_packed, const f
                     const float* row_scale, int64_t M, int64_t N, int64_t K,
                     void* out_f16, int32_t* acc_i32, void* stream);
 
+/* pq_gemm_dynamic with scratch memory for the split-K launch: workspace as for pq_w4a4_gemm_ws, sized
+ * by pq_gemm_workspace_bytes(M,N,K,bits); results equal pq_gemm_dynamic's bit for bit. */
+int pq_gemm_dynamic_ws(const void* xq, int32_t bits, const void* wq_packed, const float* w_scale,
+                       const float* row_scale, int64_t M, int64_t N, int64_t K,
+                       void* out_f16, int32_t* acc_i32, void* workspace, size_t workspace_bytes,
+                       void* stream);
+
 /* Workspace of pq_linear_dynamic: the codes (M*K/2 or M*K bytes, rounded up to 256) followed by
- * the M row steps (rounded up to 256).  Host only.
+ * the M row steps (rounded up to 256); _split adds the planes of pq_gemm_workspace_bytes(M,N,K,bits)
+ * behind them, which the layer's product then uses.  Host only.
  */
 size_t pq_linear_dynamic_workspace_bytes(int64_t M, int64_t K, int32_t bits);
+size_t pq_linear_dynamic_workspace_bytes_split(int64_t M, int64_t N, int64_t K, int32_t bits);
 
 /* pq_rotate_quant_dynamic into `workspace`, then pq_gemm_dynamic, on the same stream.  On return
  * the workspace holds the codes at offset 0 and the fp32 row steps at offset
@@ -292,6 +312,12 @@ int pq_zero_point_correction(const void* wq_packed, int64_t N, int64_t K, int32_
 int pq_w4a4_gemm_zp(const void* xq_packed, const void* wq_packed, const float* w_scale,
                     float act_scale, const int32_t* zp_corr, int64_t M, int64_t N, int64_t K,
                     void* out_f16, int32_t* acc_i32, void* stream);
+/* The same with scratch memory for the split-K launch (workspace as for pq_w4a4_gemm_ws, sized by
+ * pq_gemm_workspace_bytes(M,N,K,4)); results equal pq_w4a4_gemm_zp's bit for bit. */
+int pq_w4a4_gemm_zp_ws(const void* xq_packed, const void* wq_packed, const float* w_scale,
+                       float act_scale, const int32_t* zp_corr, int64_t M, int64_t N, int64_t K,
+                       void* out_f16, int32_t* acc_i32, void* workspace, size_t workspace_bytes,
+                       void* stream);
 
 /* ---- calibration of the static per-tensor step on the device --------------------------------
  * (Sec. 3 "Initialization of Quantization Parameters": max-min initialisation, and an MSE-based

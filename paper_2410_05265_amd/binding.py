@@ -36,10 +36,15 @@ SIGNATURES = {
     "pq_probe_stream_read": (ctypes.c_int, [_vp, _i64, _vp, _vp]),
     "pq_rotate_quant8": (ctypes.c_int, [_vp, _i64, _i64, _i32, _f32, _vp, _vp]),
     "pq_w4a8_gemm": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i64, _i64, _i64, _vp, _vp, _vp]),
+    "pq_w4a8_gemm_ws": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i64, _i64, _i64, _vp, _vp, _vp, _sz, _vp]),
+    "pq_gemm_workspace_bytes": (_sz, [_i64, _i64, _i64, _i32]),
+    "pq_linear_w4a8_workspace_bytes_split": (_sz, [_i64, _i64, _i64]),
     "pq_linear_w4a8_workspace_bytes": (_sz, [_i64, _i64]),
     "pq_linear_w4a8": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i32, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
     "pq_rotate_quant_dynamic": (ctypes.c_int, [_vp, _i64, _i64, _i32, _f32, _i32, _vp, _vp, _vp]),
     "pq_gemm_dynamic": (ctypes.c_int, [_vp, _i32, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp]),
+    "pq_gemm_dynamic_ws": (ctypes.c_int, [_vp, _i32, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _sz, _vp]),
+    "pq_linear_dynamic_workspace_bytes_split": (_sz, [_i64, _i64, _i64, _i32]),
     "pq_linear_dynamic_workspace_bytes": (_sz, [_i64, _i64, _i32]),
     "pq_linear_dynamic": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i32, _i32, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
     "pq_rotate_quant_heads": (ctypes.c_int, [_vp, _i64, _i32, _i32, _i32, _vp, _vp, _vp]),
@@ -50,6 +55,7 @@ SIGNATURES = {
     "pq_rotate_quant_zp": (ctypes.c_int, [_vp, _i64, _i64, _i32, _f32, _i32, _vp, _vp]),
     "pq_zero_point_correction": (ctypes.c_int, [_vp, _i64, _i64, _i32, _vp, _vp]),
     "pq_w4a4_gemm_zp": (ctypes.c_int, [_vp, _vp, _vp, _f32, _vp, _i64, _i64, _i64, _vp, _vp, _vp]),
+    "pq_w4a4_gemm_zp_ws": (ctypes.c_int, [_vp, _vp, _vp, _f32, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _sz, _vp]),
     "pq_calibrate_workspace_bytes": (_sz, [_i64, _i32]),
     "pq_calibrate_zp_workspace_bytes": (_sz, [_i64, _i32]),
     "pq_calibrate_static_zp": (ctypes.c_int, [_vp, _i64, _i64, _i32, _i32, _i32, _f32, _f32, _vp, _vp, _sz, _vp]),
@@ -86,6 +92,14 @@ def status_str(status: int) -> str:
 
 def _ptr(t):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _ws_args(workspace):
+    """(pointer, bytes) of an optional uint8 scratch tensor."""
+    if workspace is None:
+        return None, 0
+    _dev(workspace, torch.uint8, "workspace")
+    return _ptr(workspace), workspace.numel()
 
 
 def _stream():
@@ -192,8 +206,9 @@ def pq_rotate_quant8(x: torch.Tensor, had_block: int, act_scale: float, out: tor
     return out
 
 
-def pq_w4a8_gemm(xq8, wq, w_scale, act_scale, want_out=True, want_acc=False, out=None, acc=None):
-    """grouped int8 codes [M,K] x packed weights [N,K/2] -> (out fp16 | None, acc int32 | None)."""
+def pq_w4a8_gemm(xq8, wq, w_scale, act_scale, want_out=True, want_acc=False, out=None, acc=None, workspace=None):
+    """grouped int8 codes [M,K] x packed weights [N,K/2] -> (out fp16 | None, acc int32 | None).
+    With `workspace` (uint8 scratch) the call is pq_w4a8_gemm_ws."""
     _dev(xq8, torch.int8, "xq8")
     _dev(wq, torch.uint8, "wq")
     _dev(w_scale, torch.float32, "w_scale")
@@ -205,9 +220,25 @@ def pq_w4a8_gemm(xq8, wq, w_scale, act_scale, want_out=True, want_acc=False, out
         out = torch.empty((M, N), dtype=torch.float16, device=xq8.device)
     if want_acc and acc is None:
         acc = torch.empty((M, N), dtype=torch.int32, device=xq8.device)
-    _check(lib().pq_w4a8_gemm(_ptr(xq8), _ptr(wq), _ptr(w_scale), float(act_scale), M, N, K, _ptr(out), _ptr(acc),
-                              _stream()), "pq_w4a8_gemm")
+    if workspace is None:
+        _check(lib().pq_w4a8_gemm(_ptr(xq8), _ptr(wq), _ptr(w_scale), float(act_scale), M, N, K, _ptr(out), _ptr(acc),
+                                  _stream()), "pq_w4a8_gemm")
+    else:
+        _check(lib().pq_w4a8_gemm_ws(_ptr(xq8), _ptr(wq), _ptr(w_scale), float(act_scale), M, N, K, _ptr(out),
+                                     _ptr(acc), *_ws_args(workspace), _stream()), "pq_w4a8_gemm_ws")
     return out, acc
+
+
+def pq_w4a8_gemm_ws(xq8, wq, w_scale, act_scale, workspace, **kw):
+    return pq_w4a8_gemm(xq8, wq, w_scale, act_scale, workspace=workspace, **kw)
+
+
+def pq_gemm_workspace_bytes(M: int, N: int, K: int, act_bits: int) -> int:
+    return int(lib().pq_gemm_workspace_bytes(M, N, K, int(act_bits)))
+
+
+def pq_linear_w4a8_workspace_bytes_split(M: int, N: int, K: int) -> int:
+    return int(lib().pq_linear_w4a8_workspace_bytes_split(M, N, K))
 
 
 def pq_linear_w4a8_workspace_bytes(M: int, K: int) -> int:
@@ -247,8 +278,10 @@ def pq_rotate_quant_dynamic(x, had_block: int, clip: float = 1.0, bits: int = 4,
     return out, row_scale
 
 
-def pq_gemm_dynamic(xq, bits, wq, w_scale, row_scale, want_out=True, want_acc=False, out=None, acc=None):
-    """codes x packed weights with per-token steps -> (out fp16 | None, acc int32 | None)."""
+def pq_gemm_dynamic(xq, bits, wq, w_scale, row_scale, want_out=True, want_acc=False, out=None, acc=None,
+                    workspace=None):
+    """codes x packed weights with per-token steps -> (out fp16 | None, acc int32 | None).
+    With `workspace` (uint8 scratch) the call is pq_gemm_dynamic_ws."""
     _dev(xq, torch.int8 if bits == 8 else torch.uint8, "xq")
     _dev(wq, torch.uint8, "wq")
     _dev(w_scale, torch.float32, "w_scale")
@@ -261,9 +294,21 @@ def pq_gemm_dynamic(xq, bits, wq, w_scale, row_scale, want_out=True, want_acc=Fa
         out = torch.empty((M, N), dtype=torch.float16, device=xq.device)
     if want_acc and acc is None:
         acc = torch.empty((M, N), dtype=torch.int32, device=xq.device)
-    _check(lib().pq_gemm_dynamic(_ptr(xq), int(bits), _ptr(wq), _ptr(w_scale), _ptr(row_scale), M, N, K, _ptr(out),
-                                 _ptr(acc), _stream()), "pq_gemm_dynamic")
+    if workspace is None:
+        _check(lib().pq_gemm_dynamic(_ptr(xq), int(bits), _ptr(wq), _ptr(w_scale), _ptr(row_scale), M, N, K, _ptr(out),
+                                     _ptr(acc), _stream()), "pq_gemm_dynamic")
+    else:
+        _check(lib().pq_gemm_dynamic_ws(_ptr(xq), int(bits), _ptr(wq), _ptr(w_scale), _ptr(row_scale), M, N, K,
+                                        _ptr(out), _ptr(acc), *_ws_args(workspace), _stream()), "pq_gemm_dynamic_ws")
     return out, acc
+
+
+def pq_gemm_dynamic_ws(xq, bits, wq, w_scale, row_scale, workspace, **kw):
+    return pq_gemm_dynamic(xq, bits, wq, w_scale, row_scale, workspace=workspace, **kw)
+
+
+def pq_linear_dynamic_workspace_bytes_split(M: int, N: int, K: int, bits: int = 4) -> int:
+    return int(lib().pq_linear_dynamic_workspace_bytes_split(M, N, K, int(bits)))
 
 
 def pq_linear_dynamic_workspace_bytes(M: int, K: int, bits: int = 4) -> int:
@@ -374,8 +419,10 @@ def pq_zero_point_correction(wq, zero_point: int, out=None):
     return out
 
 
-def pq_w4a4_gemm_zp(xq, wq, w_scale, act_scale, zp_corr, want_out=True, want_acc=False, out=None, acc=None):
-    """(acc + zp_corr[n]) * act_scale * w_scale[n] -> (out fp16 | None, raw acc int32 | None)."""
+def pq_w4a4_gemm_zp(xq, wq, w_scale, act_scale, zp_corr, want_out=True, want_acc=False, out=None, acc=None,
+                    workspace=None):
+    """(acc + zp_corr[n]) * act_scale * w_scale[n] -> (out fp16 | None, raw acc int32 | None).
+    With `workspace` (uint8 scratch) the call is pq_w4a4_gemm_zp_ws."""
     _dev(xq, torch.uint8, "xq")
     _dev(wq, torch.uint8, "wq")
     _dev(w_scale, torch.float32, "w_scale")
@@ -388,9 +435,17 @@ def pq_w4a4_gemm_zp(xq, wq, w_scale, act_scale, zp_corr, want_out=True, want_acc
         out = torch.empty((M, N), dtype=torch.float16, device=xq.device)
     if want_acc and acc is None:
         acc = torch.empty((M, N), dtype=torch.int32, device=xq.device)
-    _check(lib().pq_w4a4_gemm_zp(_ptr(xq), _ptr(wq), _ptr(w_scale), float(act_scale), _ptr(zp_corr), M, N, K, _ptr(out),
-                                 _ptr(acc), _stream()), "pq_w4a4_gemm_zp")
+    if workspace is None:
+        _check(lib().pq_w4a4_gemm_zp(_ptr(xq), _ptr(wq), _ptr(w_scale), float(act_scale), _ptr(zp_corr), M, N, K,
+                                     _ptr(out), _ptr(acc), _stream()), "pq_w4a4_gemm_zp")
+    else:
+        _check(lib().pq_w4a4_gemm_zp_ws(_ptr(xq), _ptr(wq), _ptr(w_scale), float(act_scale), _ptr(zp_corr), M, N, K,
+                                        _ptr(out), _ptr(acc), *_ws_args(workspace), _stream()), "pq_w4a4_gemm_zp_ws")
     return out, acc
+
+
+def pq_w4a4_gemm_zp_ws(xq, wq, w_scale, act_scale, zp_corr, workspace, **kw):
+    return pq_w4a4_gemm_zp(xq, wq, w_scale, act_scale, zp_corr, workspace=workspace, **kw)
 
 
 def pq_calibrate_workspace_bytes(T: int, n_grid: int) -> int:

@@ -31,12 +31,12 @@ int pick_few_tokens(int64_t M, int64_t N, int64_t K, int32_t abits)
     return 2;
 }
 
-// The same choice for 4-bit codes when the call brings scratch memory for partial-sum planes.
+// The same choice when the call brings scratch memory for partial-sum planes (timings: 4-bit codes).
 // 17 to 32 tokens: with its planes in place the split tiled launch beats two launches of the matrix
 // streaming kernel on matrices of 8 MB and more (8-14 us against 9-16; not measured below).
-int pick_with_planes(int64_t M, int64_t N, int64_t K, size_t plane_bytes)
+int pick_with_planes(int64_t M, int64_t N, int64_t K, size_t plane_bytes, int32_t abits = 4)
 {
-    const int kernel = pick_few_tokens(M, N, K, 4);
+    const int kernel = pick_few_tokens(M, N, K, abits);
     if (g_variant == 0 && kernel == 1 && M > 16 && N * (K / 2) >= 8000000) {
         const size_t want = pq::gemm_splitk_workspace_bytes(M, N, K);
         if (want > 0 && plane_bytes >= want) return 2;
@@ -122,12 +122,14 @@ int pq_w4a4_gemm(const void* xq_packed, const void* wq_packed, const float* w_sc
     return pq_w4a4_gemm_ws(xq_packed, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32, nullptr, 0, stream);
 }
 
-size_t pq_w4a4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
+size_t pq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int32_t act_bits)
 {
-    if (M <= 0 || N <= 0 || K <= 0 || (K % 32) != 0 || (N % 16) != 0) return 0;
-    if (g_variant == 3 || pick_with_planes(M, N, K, ~(size_t)0) != 2) return 0;
+    if (M <= 0 || N <= 0 || K <= 0 || (K % 32) != 0 || (N % 16) != 0 || (act_bits != 4 && act_bits != 8)) return 0;
+    if (g_variant == 3 || pick_with_planes(M, N, K, ~(size_t)0, act_bits) != 2) return 0;
     return pq::gemm_splitk_workspace_bytes(M, N, K, g_variant == 5);
 }
+
+size_t pq_w4a4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) { return pq_gemm_workspace_bytes(M, N, K, 4); }
 
 int pq_w4a4_gemm_simple(const void* xq_packed, const void* wq_packed, const float* w_scale, float act_scale,
                         int64_t M, int64_t N, int64_t K, void* out_f16, int32_t* acc_i32, void* stream)
@@ -195,14 +197,16 @@ int pq_rotate_quant8(const void* x_f16, int64_t M, int64_t K, int32_t had_block,
     return pq::launch_rotate_quant8(x_f16, M, K, had_block, act_scale, xq8_grouped, static_cast<hipStream_t>(stream));
 }
 
-int pq_w4a8_gemm(const void* xq8_grouped, const void* wq_packed, const float* w_scale, float act_scale, int64_t M,
-                 int64_t N, int64_t K, void* out_f16, int32_t* acc_i32, void* stream)
+int pq_w4a8_gemm_ws(const void* xq8_grouped, const void* wq_packed, const float* w_scale, float act_scale, int64_t M,
+                    int64_t N, int64_t K, void* out_f16, int32_t* acc_i32, void* workspace, size_t workspace_bytes,
+                    void* stream)
 {
     int rc = check_gemm(xq8_grouped, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32);
     if (rc != PQ_OK) return rc;
     if ((K % 128) != 0) return PQ_ERR_SHAPE;
+    if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 255u)) return PQ_ERR_ALIGN;
     if (M == 0) return PQ_OK;
-    const int few = pick_few_tokens(M, N, K, 8);
+    const int few = pick_with_planes(M, N, K, workspace ? workspace_bytes : 0, 8);
     if (few == 4)
         return pq::launch_decode(nullptr, xq8_grouped, wq_packed, w_scale, act_scale, 1, M, N, K, out_f16, acc_i32,
                                  nullptr, static_cast<hipStream_t>(stream), nullptr, 8);
@@ -210,7 +214,14 @@ int pq_w4a8_gemm(const void* xq8_grouped, const void* wq_packed, const float* w_
         return pq::launch_stream_mfma(xq8_grouped, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32,
                                       static_cast<hipStream_t>(stream), nullptr, 8);
     return pq::launch_gemm_w4a8(xq8_grouped, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32,
-                                static_cast<hipStream_t>(stream));
+                                static_cast<hipStream_t>(stream), workspace, workspace ? workspace_bytes : 0,
+                                g_variant == 5);
+}
+
+int pq_w4a8_gemm(const void* xq8_grouped, const void* wq_packed, const float* w_scale, float act_scale, int64_t M,
+                 int64_t N, int64_t K, void* out_f16, int32_t* acc_i32, void* stream)
+{
+    return pq_w4a8_gemm_ws(xq8_grouped, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32, nullptr, 0, stream);
 }
 
 size_t pq_linear_w4a8_workspace_bytes(int64_t M, int64_t K)
@@ -238,7 +249,14 @@ int pq_linear_w4a8(const void* x_f16, const void* wq_packed, const float* w_scal
     if (K > 65536 || M * K >= ((int64_t)1 << 32)) return PQ_ERR_UNSUPPORTED;
     rc = pq_rotate_quant8(x_f16, M, K, had_block, act_scale, workspace, stream);
     if (rc != PQ_OK) return rc;
-    return pq_w4a8_gemm(workspace, wq_packed, w_scale, act_scale, M, N, K, out_f16, nullptr, stream);
+    const size_t codes = pq_linear_w4a8_workspace_bytes(M, K);
+    return pq_w4a8_gemm_ws(workspace, wq_packed, w_scale, act_scale, M, N, K, out_f16, nullptr,
+                           static_cast<uint8_t*>(workspace) + codes, workspace_bytes - codes, stream);
+}
+
+size_t pq_linear_w4a8_workspace_bytes_split(int64_t M, int64_t N, int64_t K)
+{
+    return pq_linear_w4a8_workspace_bytes(M, K) + pq_gemm_workspace_bytes(M, N, K, 8);
 }
 
 int pq_rotate_quant_dynamic(const void* x_f16, int64_t M, int64_t K, int32_t had_block, float clip, int32_t bits,
@@ -256,8 +274,9 @@ int pq_rotate_quant_dynamic(const void* x_f16, int64_t M, int64_t K, int32_t had
                                            static_cast<hipStream_t>(stream));
 }
 
-int pq_gemm_dynamic(const void* xq, int32_t bits, const void* wq_packed, const float* w_scale, const float* row_scale,
-                    int64_t M, int64_t N, int64_t K, void* out_f16, int32_t* acc_i32, void* stream)
+int pq_gemm_dynamic_ws(const void* xq, int32_t bits, const void* wq_packed, const float* w_scale,
+                       const float* row_scale, int64_t M, int64_t N, int64_t K, void* out_f16, int32_t* acc_i32,
+                       void* workspace, size_t workspace_bytes, void* stream)
 {
     if (bits != 4 && bits != 8) return PQ_ERR_SHAPE;
     int rc = check_gemm(xq, wq_packed, w_scale, 1.0f, M, N, K, out_f16, acc_i32);
@@ -265,9 +284,10 @@ int pq_gemm_dynamic(const void* xq, int32_t bits, const void* wq_packed, const f
     if ((K % 128) != 0) return PQ_ERR_SHAPE;
     if (!row_scale) return PQ_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(row_scale) & 3u) return PQ_ERR_ALIGN;
+    if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 255u)) return PQ_ERR_ALIGN;
     if (M == 0) return PQ_OK;
     // decode: a weight-streaming kernel with the token's step in its epilogue
-    const int few = pick_few_tokens(M, N, K, bits);
+    const int few = pick_with_planes(M, N, K, workspace ? workspace_bytes : 0, bits);
     if (few == 4)
         return pq::launch_decode(nullptr, xq, wq_packed, w_scale, 1.0f, 1, M, N, K, out_f16, acc_i32, nullptr,
                                  static_cast<hipStream_t>(stream), row_scale, bits);
@@ -275,7 +295,14 @@ int pq_gemm_dynamic(const void* xq, int32_t bits, const void* wq_packed, const f
         return pq::launch_stream_mfma(xq, wq_packed, w_scale, 1.0f, M, N, K, out_f16, acc_i32,
                                       static_cast<hipStream_t>(stream), row_scale, bits);
     return pq::launch_gemm_dynamic(xq, bits, wq_packed, w_scale, row_scale, M, N, K, out_f16, acc_i32,
-                                   static_cast<hipStream_t>(stream));
+                                   static_cast<hipStream_t>(stream), workspace, workspace ? workspace_bytes : 0,
+                                   g_variant == 5);
+}
+
+int pq_gemm_dynamic(const void* xq, int32_t bits, const void* wq_packed, const float* w_scale, const float* row_scale,
+                    int64_t M, int64_t N, int64_t K, void* out_f16, int32_t* acc_i32, void* stream)
+{
+    return pq_gemm_dynamic_ws(xq, bits, wq_packed, w_scale, row_scale, M, N, K, out_f16, acc_i32, nullptr, 0, stream);
 }
 
 size_t pq_linear_dynamic_workspace_bytes(int64_t M, int64_t K, int32_t bits)
@@ -302,7 +329,14 @@ int pq_linear_dynamic(const void* x_f16, const void* wq_packed, const float* w_s
     if (K > 32768 || M * K >= ((int64_t)1 << 32)) return PQ_ERR_UNSUPPORTED;
     rc = pq_rotate_quant_dynamic(x_f16, M, K, had_block, clip, bits, workspace, row_scale, stream);
     if (rc != PQ_OK) return rc;
-    return pq_gemm_dynamic(workspace, bits, wq_packed, w_scale, row_scale, M, N, K, out_f16, nullptr, stream);
+    return pq_gemm_dynamic_ws(workspace, bits, wq_packed, w_scale, row_scale, M, N, K, out_f16, nullptr,
+                              static_cast<uint8_t*>(workspace) + need, workspace_bytes - need, stream);
+}
+
+size_t pq_linear_dynamic_workspace_bytes_split(int64_t M, int64_t N, int64_t K, int32_t bits)
+{
+    const size_t base = pq_linear_dynamic_workspace_bytes(M, K, bits);
+    return base ? base + pq_gemm_workspace_bytes(M, N, K, bits) : 0;
 }
 
 int pq_rotate_quant_heads(const void* x_f16, int64_t T, int32_t n_heads, int32_t head_dim, int32_t rotate,
@@ -394,26 +428,36 @@ int pq_zero_point_correction(const void* wq_packed, int64_t N, int64_t K, int32_
     return pq::launch_zero_point_correction(wq_packed, N, K, zero_point, zp_corr, static_cast<hipStream_t>(stream));
 }
 
-int pq_w4a4_gemm_zp(const void* xq_packed, const void* wq_packed, const float* w_scale, float act_scale,
-                    const int32_t* zp_corr, int64_t M, int64_t N, int64_t K, void* out_f16, int32_t* acc_i32,
-                    void* stream)
+int pq_w4a4_gemm_zp_ws(const void* xq_packed, const void* wq_packed, const float* w_scale, float act_scale,
+                       const int32_t* zp_corr, int64_t M, int64_t N, int64_t K, void* out_f16, int32_t* acc_i32,
+                       void* workspace, size_t workspace_bytes, void* stream)
 {
     int rc = check_gemm(xq_packed, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32);
     if (rc != PQ_OK) return rc;
     if ((K % 128) != 0) return PQ_ERR_SHAPE;
     if (!zp_corr) return PQ_ERR_NULL;
     if (!aligned16(zp_corr)) return PQ_ERR_ALIGN;
+    if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 255u)) return PQ_ERR_ALIGN;
     if (K > 32768) return PQ_ERR_UNSUPPORTED;
     if (M == 0) return PQ_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const int few = pick_few_tokens(M, N, K, 4);
+    const int few = pick_with_planes(M, N, K, workspace ? workspace_bytes : 0, 4);
     if (few == 4)
         return pq::launch_decode(nullptr, xq_packed, wq_packed, w_scale, act_scale, 1, M, N, K, out_f16, acc_i32,
                                  nullptr, st, nullptr, 4, zp_corr);
     if (few == 1)
         return pq::launch_stream_mfma(xq_packed, wq_packed, w_scale, act_scale, M, N, K, out_f16, acc_i32, st, nullptr,
                                       4, zp_corr);
-    return pq::launch_gemm_zp(xq_packed, wq_packed, w_scale, act_scale, zp_corr, M, N, K, out_f16, acc_i32, st);
+    return pq::launch_gemm_zp(xq_packed, wq_packed, w_scale, act_scale, zp_corr, M, N, K, out_f16, acc_i32, st,
+                              workspace, workspace ? workspace_bytes : 0, g_variant == 5);
+}
+
+int pq_w4a4_gemm_zp(const void* xq_packed, const void* wq_packed, const float* w_scale, float act_scale,
+                    const int32_t* zp_corr, int64_t M, int64_t N, int64_t K, void* out_f16, int32_t* acc_i32,
+                    void* stream)
+{
+    return pq_w4a4_gemm_zp_ws(xq_packed, wq_packed, w_scale, act_scale, zp_corr, M, N, K, out_f16, acc_i32, nullptr, 0,
+                              stream);
 }
 
 size_t pq_calibrate_workspace_bytes(int64_t T, int32_t n_grid)

@@ -513,7 +513,7 @@ int launch_dma(const void* xq, const void* wq, const float* sw, float sx, int64_
 // runs of 128-channel stages and leaves an int32 plane of partial sums in the caller's workspace;
 // k_splitk_reduce adds the planes and applies the same epilogue arithmetic as the tiled kernel
 // (integer sums are exact in any order, so accumulators and outputs equal the unsplit ones).
-template <int BM, int BN, int WR, int WC, int NS>
+template <int BM, int BN, int WR, int WC, int NS, int ABITS, int ASHIFT>
 __global__ __launch_bounds__(WR * WC * 64) void k_gemm_splitk(const uint8_t* __restrict__ xq,
                                                              const uint8_t* __restrict__ wq, int M, int N, int K,
                                                              int GM, int tiles, int S, int32_t* __restrict__ part)
@@ -521,15 +521,19 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_splitk(const uint8_t* __r
     const int tile = blockIdx.x % tiles, s = blockIdx.x / tiles;
     const int nk = K / 128;
     const int kt0 = (int)((int64_t)nk * s / S), kt1 = (int)((int64_t)nk * (s + 1) / S);
-    gemm_tile<BM, BN, WR, WC, NS, 1, 4, 8, true>(xq, wq, nullptr, 0.0f, M, N, K, (tile % GM) * BM, (tile / GM) * BN, nullptr,
-                                                 part + (int64_t)s * M * N, nullptr, nullptr, kt0, kt1 - kt0);
+    gemm_tile<BM, BN, WR, WC, NS, 1, ABITS, ASHIFT, true>(xq, wq, nullptr, 0.0f, M, N, K, (tile % GM) * BM, (tile / GM) * BN,
+                                                          nullptr, part + (int64_t)s * M * N, nullptr, nullptr, kt0,
+                                                          kt1 - kt0);
 }
 
 // 4 consecutive channels of one token per thread: sum of the S planes (four loads in flight), then
-// acc and / or out = fp16(fp32(256 acc) * (sw[n] * (sx / 256))), the tiled kernel's expression.
+// acc and / or the tiled kernel's epilogue expression: with u = 2^shift (the factor its accumulators
+// carry) out = fp16(fp32(u (acc + zcorr[n])) * (sw[n] * (step / u))), step = sx or the token's own.
 __global__ __launch_bounds__(256) void k_splitk_reduce(const int32_t* __restrict__ part, int S, int64_t plane,
-                                                       const float* __restrict__ sw, float sx, int N,
-                                                       __half* __restrict__ out, int32_t* __restrict__ acc_out)
+                                                       const float* __restrict__ sw, float sx, int N, int shift,
+                                                       const float* __restrict__ srow,
+                                                       const int32_t* __restrict__ zcorr, __half* __restrict__ out,
+                                                       int32_t* __restrict__ acc_out)
 {
     const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
     if (e >= plane) return;
@@ -545,11 +549,12 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const int32_t* __restrict
     for (; s < S; ++s) a += *reinterpret_cast<const v4i*>(p + s * plane);
     if (acc_out) *reinterpret_cast<v4i*>(acc_out + e) = a;
     if (out) {
-        const float f = sx * (1.0f / 256.0f);
+        if (zcorr) a += *reinterpret_cast<const v4i*>(zcorr + n);
+        const float f = (srow ? srow[e / N] : sx) * (1.0f / (float)(1 << shift));
         float4 s0 = *reinterpret_cast<const float4*>(sw + n);
         s0.x *= f; s0.y *= f; s0.z *= f; s0.w *= f;
-        const __half2 h0 = __floats2half2_rn(mul_rn((float)(a.x << 8), s0.x), mul_rn((float)(a.y << 8), s0.y));
-        const __half2 h1 = __floats2half2_rn(mul_rn((float)(a.z << 8), s0.z), mul_rn((float)(a.w << 8), s0.w));
+        const __half2 h0 = __floats2half2_rn(mul_rn((float)(a.x << shift), s0.x), mul_rn((float)(a.y << shift), s0.y));
+        const __half2 h1 = __floats2half2_rn(mul_rn((float)(a.z << shift), s0.z), mul_rn((float)(a.w << shift), s0.w));
         uint2 val;
         val.x = *reinterpret_cast<const uint32_t*>(&h0);
         val.y = *reinterpret_cast<const uint32_t*>(&h1);
@@ -557,15 +562,22 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const int32_t* __restrict
     }
 }
 
-template <int BM>
-int launch_splitk(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K, int S,
+struct SplitArgs {   // what the epilogue needs beyond the channel scales
+    float sx;
+    const float* srow;
+    const int32_t* zcorr;
+};
+
+template <int BM, int ABITS>
+int launch_splitk(const void* xq, const void* wq, const float* sw, SplitArgs ep, int64_t M, int64_t N, int64_t K, int S,
                   void* out, int32_t* acc, int32_t* part, hipStream_t st)
 {
     // (a ring of 4 or 6 stages measured the same as 3)
-    constexpr int BN = 128, NS = 3;
+    constexpr int BN = 128, NS = 3, ASHIFT = ABITS == 8 ? 4 : 8;
     const int GM = (int)((M + BM - 1) / BM), GN = (int)((N + BN - 1) / BN);
-    constexpr size_t lds = (size_t)NS * (BM * 64 + BN * 64);
-    auto kern = k_gemm_splitk<BM, BN, 2, 2, NS>;
+    constexpr size_t lds = (size_t)NS * (BM * (ABITS == 8 ? 128 : 64) + BN * 64);
+    static_assert(lds <= 160 * 1024, "LDS ring too large");
+    auto kern = k_gemm_splitk<BM, BN, 2, 2, NS, ABITS, ASHIFT>;
     static bool attr_set = false;  // benign race: the call is idempotent
     if (lds > 48 * 1024 && !attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -578,7 +590,7 @@ int launch_splitk(const void* xq, const void* wq, const float* sw, float sx, int
     if (hipGetLastError() != hipSuccess) return PQ_ERR_HIP;
     const int64_t plane = M * N;
     hipLaunchKernelGGL(k_splitk_reduce, dim3((unsigned)((plane / 4 + 255) / 256)), dim3(256), 0, st, part, S, plane, sw,
-                       sx, (int)N, static_cast<__half*>(out), acc);
+                       ep.sx, (int)N, ASHIFT, ep.srow, ep.zcorr, static_cast<__half*>(out), acc);
     return hip_status(hipGetLastError());
 }
 
@@ -852,26 +864,44 @@ size_t gemm_splitk_workspace_bytes(int64_t M, int64_t N, int64_t K, bool force)
     return S > 1 ? (size_t)S * (size_t)M * (size_t)N * 4 : 0;
 }
 
+namespace {
+// The split launch if the plan has one for this workspace; -1: the caller runs the unsplit kernel.
+template <int ABITS>
+int try_splitk(const void* xq, const void* wq, const float* sw, SplitArgs ep, int64_t M, int64_t N, int64_t K, void* out,
+               int32_t* acc, void* ws, size_t ws_bytes, bool force, hipStream_t st)
+{
+    int bm = 128, S = 1;
+    if (ws) plan_splitk(M, N, K, ws_bytes, force, &bm, &S);
+    if (S <= 1) return force ? PQ_ERR_UNSUPPORTED : -1;
+    int32_t* part = static_cast<int32_t*>(ws);
+    if (bm == 64) return launch_splitk<64, ABITS>(xq, wq, sw, ep, M, N, K, S, out, acc, part, st);
+    if (bm == 128) return launch_splitk<128, ABITS>(xq, wq, sw, ep, M, N, K, S, out, acc, part, st);
+    return launch_splitk<256, ABITS>(xq, wq, sw, ep, M, N, K, S, out, acc, part, st);
+}
+}  // namespace
+
 int launch_gemm_mfma_ws(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K,
                         void* out, int32_t* acc, void* ws, size_t ws_bytes, bool force, hipStream_t st)
 {
-    int bm = 128, S = 1;
-    if (ws && M <= (1 << 30) && N <= (1 << 30) && K <= (1 << 30) && M * (K / 2) < ((int64_t)1 << 32) &&
-        N * (K / 2) < ((int64_t)1 << 32))
-        plan_splitk(M, N, K, ws_bytes, force, &bm, &S);
-    if (S <= 1) return force ? PQ_ERR_UNSUPPORTED : launch_gemm_mfma(xq, wq, sw, sx, M, N, K, out, acc, st);
-    if (bm == 64) return launch_splitk<64>(xq, wq, sw, sx, M, N, K, S, out, acc, static_cast<int32_t*>(ws), st);
-    if (bm == 128) return launch_splitk<128>(xq, wq, sw, sx, M, N, K, S, out, acc, static_cast<int32_t*>(ws), st);
-    return launch_splitk<256>(xq, wq, sw, sx, M, N, K, S, out, acc, static_cast<int32_t*>(ws), st);
+    if (M <= (1 << 30) && N <= (1 << 30) && K <= (1 << 30) && M * (K / 2) < ((int64_t)1 << 32) &&
+        N * (K / 2) < ((int64_t)1 << 32)) {
+        const int rc = try_splitk<4>(xq, wq, sw, SplitArgs{sx, nullptr, nullptr}, M, N, K, out, acc, ws, ws_bytes, force, st);
+        if (rc >= 0) return rc;
+    } else if (force) {
+        return PQ_ERR_UNSUPPORTED;
+    }
+    return launch_gemm_mfma(xq, wq, sw, sx, M, N, K, out, acc, st);
 }
 
 // 4-bit weights x 8-bit activations (codes in the even/odd-grouped byte order written by the
 // 8-bit quantizer): the same kernel with the activation operand taken from LDS as it stands.
 int launch_gemm_w4a8(const void* xq8, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K,
-                     void* out, int32_t* acc, hipStream_t st)
+                     void* out, int32_t* acc, hipStream_t st, void* ws, size_t ws_bytes, bool force)
 {
     if (M > (1 << 30) || N > (1 << 30) || K > 65536 || K % 128 != 0) return PQ_ERR_UNSUPPORTED;
     if (M * K >= ((int64_t)1 << 32) || N * (K / 2) >= ((int64_t)1 << 32)) return PQ_ERR_UNSUPPORTED;
+    const int rc = try_splitk<8>(xq8, wq, sw, SplitArgs{sx, nullptr, nullptr}, M, N, K, out, acc, ws, ws_bytes, force, st);
+    if (rc >= 0) return rc;
     int n1 = 0, n2 = 0;
     if (pick_dual(M, N, &n1, &n2))
         return launch_dual<256, 256, 192, 2, 2, 3, 8, 4>(xq8, wq, sw, sx, M, N, K, n1, n2, out, acc, st);
@@ -886,10 +916,17 @@ int launch_gemm_w4a8(const void* xq8, const void* wq, const float* sw, float sx,
 // Per-token dynamic quantization (Table 1 row O1): out = acc * row_scale[m] * w_scale[n].  bits = 4
 // (packed codes) or 8 (grouped bytes).
 int launch_gemm_dynamic(const void* xq, int32_t bits, const void* wq, const float* sw, const float* srow, int64_t M,
-                        int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st)
+                        int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st, void* ws, size_t ws_bytes,
+                        bool force)
 {
     if (M > (1 << 30) || N > (1 << 30) || K > 65536 || K % 128 != 0) return PQ_ERR_UNSUPPORTED;
     if (M * K >= ((int64_t)1 << 32) || N * (K / 2) >= ((int64_t)1 << 32)) return PQ_ERR_UNSUPPORTED;
+    {
+        const SplitArgs ep{1.0f, srow, nullptr};
+        const int rc = bits == 8 ? try_splitk<8>(xq, wq, sw, ep, M, N, K, out, acc, ws, ws_bytes, force, st)
+                                 : try_splitk<4>(xq, wq, sw, ep, M, N, K, out, acc, ws, ws_bytes, force, st);
+        if (rc >= 0) return rc;
+    }
     const int cfg = pick_cfg(M, N);
     int n1 = 0, n2 = 0;
     const bool dual = pick_dual(M, N, &n1, &n2);
@@ -913,10 +950,12 @@ int launch_gemm_dynamic(const void* xq, int32_t bits, const void* wq, const floa
 
 // Static steps with a zero-point (Eq. 1): out = (acc + zcorr[n]) * s_x * s_w[n].
 int launch_gemm_zp(const void* xq, const void* wq, const float* sw, float sx, const int32_t* zcorr, int64_t M, int64_t N,
-                   int64_t K, void* out, int32_t* acc, hipStream_t st)
+                   int64_t K, void* out, int32_t* acc, hipStream_t st, void* ws, size_t ws_bytes, bool force)
 {
     if (M > (1 << 30) || N > (1 << 30) || K > 32768 || K % 128 != 0) return PQ_ERR_UNSUPPORTED;
     if (M * (K / 2) >= ((int64_t)1 << 32) || N * (K / 2) >= ((int64_t)1 << 32)) return PQ_ERR_UNSUPPORTED;
+    const int rc = try_splitk<4>(xq, wq, sw, SplitArgs{sx, nullptr, zcorr}, M, N, K, out, acc, ws, ws_bytes, force, st);
+    if (rc >= 0) return rc;
     int n1 = 0, n2 = 0;
     if (pick_dual(M, N, &n1, &n2))
         return launch_dual<256, 256, 192, 2, 2, 3>(xq, wq, sw, sx, M, N, K, n1, n2, out, acc, st, nullptr, zcorr);

@@ -15,12 +15,15 @@ int launch_rotate_quant_zp(const void* x, int64_t M, int64_t K, int32_t h, float
                            void* xq, hipStream_t st);
 int launch_rotate_quant8(const void* x, int64_t M, int64_t K, int32_t h, float act_scale,
                          void* xq8, hipStream_t st);
+// (ws, ws_bytes, force of the three widened products: as for launch_gemm_mfma_ws below)
 int launch_gemm_w4a8(const void* xq8, const void* wq, const float* sw, float sx, int64_t M,
-                     int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st);
+                     int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st, void* ws = nullptr,
+                     size_t ws_bytes = 0, bool force = false);
 int launch_rotate_quant_dynamic(const void* x, int64_t M, int64_t K, int32_t h, float clip, int32_t bits,
                                 void* xq, float* row_scale, hipStream_t st);
 int launch_gemm_dynamic(const void* xq, int32_t bits, const void* wq, const float* sw, const float* srow,
-                        int64_t M, int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st);
+                        int64_t M, int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st,
+                        void* ws = nullptr, size_t ws_bytes = 0, bool force = false);
 int launch_rotate_quant_heads(const void* x, int64_t M, int64_t K, int32_t head_dim, int32_t h,
                               const float* head_scale, void* xq, hipStream_t st);
 int launch_rotate_f16(const void* x, int64_t M, int64_t K, int32_t h, void* y, hipStream_t st);
@@ -34,7 +37,8 @@ int max_calibration_grid();
 int launch_calibrate(const void* x, int64_t T, int64_t K, int32_t h, int32_t bits, int32_t n_grid, float gamma_min,
                      float* result, float* ws, hipStream_t st);
 int launch_gemm_zp(const void* xq, const void* wq, const float* sw, float sx, const int32_t* zcorr, int64_t M,
-                   int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st);
+                   int64_t N, int64_t K, void* out, int32_t* acc, hipStream_t st, void* ws = nullptr,
+                   size_t ws_bytes = 0, bool force = false);
 int launch_zero_point_correction(const void* wq, int64_t N, int64_t K, int32_t zero_point, int32_t* corr,
                                  hipStream_t st);
 int launch_calibrate_zp(const void* x, int64_t T, int64_t K, int32_t h, int32_t ng, int32_t nb, float gamma_min,

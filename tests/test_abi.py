@@ -53,6 +53,12 @@ def test_host_only_calls(b):
     assert wsb(64, 4096, 14336 + 32) == 0 and wsb(64, 4090, 4096) == 0 and wsb(-1, 4096, 4096) == 0
     assert L.pq_linear_workspace_bytes_split(64, 4096, 14336) == 64 * 7168 + wsb(64, 4096, 14336)
     assert L.pq_linear_workspace_bytes_split(2048, 4096, 14336) == 2048 * 7168
+    gwb = L.pq_gemm_workspace_bytes
+    assert gwb(64, 4096, 14336, 4) == wsb(64, 4096, 14336) and gwb(64, 4096, 14336, 8) % (64 * 4096 * 4) == 0
+    assert gwb(64, 4096, 14336, 8) > 0 and gwb(64, 4096, 14336, 6) == 0 and gwb(2048, 4096, 14336, 8) == 0
+    assert L.pq_linear_w4a8_workspace_bytes_split(64, 4096, 14336) == 64 * 14336 + gwb(64, 4096, 14336, 8)
+    assert L.pq_linear_dynamic_workspace_bytes_split(64, 4096, 14336, 4) == 64 * 7168 + 256 + gwb(64, 4096, 14336, 4)
+    assert L.pq_linear_dynamic_workspace_bytes_split(64, 4096, 14336, 5) == 0
     assert L.pq_set_gemm_variant(5) == 0
     assert wsb(100, 256, 2048) == 5 * 100 * 256 * 4 and wsb(100, 256, 384) == 0
     assert L.pq_set_gemm_variant(0) == 5
@@ -104,6 +110,17 @@ def test_argument_errors_launch_nothing(b):
         assert gw(p, p, p, 0.1, 64, 64, 512, p, nul, nul, 0, nul) == b.PQ_ERR_UNSUPPORTED   # forced split, no planes
     finally:
         L.pq_set_gemm_variant(prev)
+
+    # the widened products with scratch memory: the same checks as without, plus the workspace's alignment
+    assert L.pq_w4a8_gemm_ws(p, p, p, 0.1, 64, 64, 512, p, nul, odd, 1 << 20, nul) == b.PQ_ERR_ALIGN
+    assert L.pq_w4a8_gemm_ws(p, p, p, 0.1, 64, 64, 160, p, nul, nul, 0, nul) == b.PQ_ERR_SHAPE
+    assert L.pq_w4a8_gemm_ws(nul, p, p, 0.1, 64, 64, 512, p, nul, nul, 0, nul) == b.PQ_ERR_NULL
+    assert L.pq_gemm_dynamic_ws(p, 4, p, p, p, 64, 64, 512, p, nul, odd, 1 << 20, nul) == b.PQ_ERR_ALIGN
+    assert L.pq_gemm_dynamic_ws(p, 5, p, p, p, 64, 64, 512, p, nul, nul, 0, nul) == b.PQ_ERR_SHAPE
+    assert L.pq_gemm_dynamic_ws(p, 4, p, p, nul, 64, 64, 512, p, nul, nul, 0, nul) == b.PQ_ERR_NULL
+    assert L.pq_w4a4_gemm_zp_ws(p, p, p, 0.1, p, 64, 64, 512, p, nul, odd, 1 << 20, nul) == b.PQ_ERR_ALIGN
+    assert L.pq_w4a4_gemm_zp_ws(p, p, p, 0.1, nul, 64, 64, 512, p, nul, nul, 0, nul) == b.PQ_ERR_NULL
+    assert L.pq_w4a4_gemm_zp_ws(p, p, p, 0.1, p, 64, 64, 65536, p, nul, nul, 0, nul) == b.PQ_ERR_UNSUPPORTED
 
     lin = L.pq_linear
     assert lin(p, p, p, 0.1, 128, 4, 64, 512, p, nul, 0, nul) == b.PQ_ERR_WORKSPACE

@@ -172,3 +172,84 @@ def test_linear_with_planes_behind_the_codes(pq, M, N, K, h):
     codes = host(ws)[:M * K // 2].reshape(M, K // 2)
     acc_ref = O.gemm_i64(O.unpack(codes), O.unpack(wq))
     assert ulp_diff(host(out), O.epilogue(acc_ref, np.float32(sx), sw)).max() <= 1
+
+
+# ---------------------------------------------------------------- the widened products, split
+WIDE_SHAPES = [(33, 256, 512), (100, 384, 1024), (129, 272, 1280), (257, 256, 1024), (64, 144, 14336), (48, 16, 640)]
+
+
+@pytest.mark.parametrize("M,N,K", WIDE_SHAPES)
+def test_forced_split_int8_activations(pq, M, N, K):
+    q = synth.random_codes(M, K, seed=M + K, stream=9, lo=-128, hi=127)
+    wq = synth.random_packed(N, K, seed=N + K, stream=7)
+    sw = synth.random_scales(N, seed=N)
+    sx = np.float32(0.0173)
+    acc_ref = O.gemm_i64(q, O.unpack(wq))
+    xq8 = O.group_even_odd(q)
+    nbytes = forced(pq, 5, pq.pq_gemm_workspace_bytes, M, N, K, 8)
+    assert nbytes == min(5, K // 256) * M * N * 4
+    out, acc = forced(pq, 5, pq.pq_w4a8_gemm_ws, dev(xq8), dev(wq), dev(sw), float(sx), scratch(nbytes),
+                      want_out=True, want_acc=True)
+    assert np.array_equal(host(acc).astype(np.int64), acc_ref)
+    assert ulp_diff(host(out), O.epilogue(acc_ref, sx, sw)).max() <= 1
+    tiled, _ = forced(pq, 2, pq.pq_w4a8_gemm, dev(xq8), dev(wq), dev(sw), float(sx))
+    assert np.array_equal(host(tiled).view(np.uint16), host(out).view(np.uint16))
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("M,N,K", WIDE_SHAPES)
+def test_forced_split_per_token_steps(pq, bits, M, N, K):
+    lo, hi = (-128, 127) if bits == 8 else (-8, 7)
+    q = synth.random_codes(M, K, seed=M + K, stream=9, lo=lo, hi=hi)
+    wq = synth.random_packed(N, K, seed=N + K, stream=7)
+    sw = synth.random_scales(N, seed=N)
+    srow = synth.random_scales(M, seed=M + 1)
+    acc_ref = O.gemm_i64(q, O.unpack(wq))
+    xq = O.group_even_odd(q) if bits == 8 else O.pack(q)
+    ws = scratch(forced(pq, 5, pq.pq_gemm_workspace_bytes, M, N, K, bits))
+    out, acc = forced(pq, 5, pq.pq_gemm_dynamic_ws, dev(xq), bits, dev(wq), dev(sw), dev(srow), ws,
+                      want_out=True, want_acc=True)
+    assert np.array_equal(host(acc).astype(np.int64), acc_ref)
+    assert ulp_diff(host(out), O.epilogue(acc_ref, srow, sw)).max() <= 1
+    tiled, _ = forced(pq, 2, pq.pq_gemm_dynamic, dev(xq), bits, dev(wq), dev(sw), dev(srow))
+    assert np.array_equal(host(tiled).view(np.uint16), host(out).view(np.uint16))
+
+
+@pytest.mark.parametrize("M,N,K,z", [(33, 256, 512, 3), (100, 384, 1024, 0), (129, 272, 1280, 15), (64, 144, 14336, 6),
+                                     (40, 64, 32768, 11)])
+def test_forced_split_zero_point(pq, M, N, K, z):
+    xq = synth.random_packed(M, K, seed=M + K)
+    wq = synth.random_packed(N, K, seed=N + K, stream=7)
+    sw = synth.random_scales(N, seed=N)
+    sx = np.float32(0.173)
+    acc_ref = O.gemm_i64(O.unpack(xq), O.unpack(wq))
+    corr = (8 - z) * O.unpack(wq).astype(np.int64).sum(axis=1)
+    d_corr = pq.pq_zero_point_correction(dev(wq), z)
+    ws = scratch(forced(pq, 5, pq.pq_gemm_workspace_bytes, M, N, K, 4))
+    out, acc = forced(pq, 5, pq.pq_w4a4_gemm_zp_ws, dev(xq), dev(wq), dev(sw), float(sx), d_corr, ws,
+                      want_out=True, want_acc=True)
+    assert np.array_equal(host(acc).astype(np.int64), acc_ref)          # raw accumulators, without the correction
+    assert ulp_diff(host(out), O.epilogue(acc_ref + corr[None, :], sx, sw)).max() <= 1
+    tiled, _ = forced(pq, 2, pq.pq_w4a4_gemm_zp, dev(xq), dev(wq), dev(sw), float(sx), d_corr)
+    assert np.array_equal(host(tiled).view(np.uint16), host(out).view(np.uint16))
+
+
+def test_widened_layers_with_planes_behind_their_workspace(pq):
+    M, N, K, h = 64, 4096, 14336, 128
+    x = synth.activations(M, K, seed=M + K)
+    wq = synth.random_packed(N, K, seed=N + K, stream=7)
+    sw = synth.random_scales(N, seed=N)
+    small, full = pq.pq_linear_w4a8_workspace_bytes(M, K), pq.pq_linear_w4a8_workspace_bytes_split(M, N, K)
+    assert full > small
+    ref, _ = pq.pq_linear_w4a8(dev(x), dev(wq), dev(sw), 0.021, h, workspace=scratch(small))
+    out, ws = pq.pq_linear_w4a8(dev(x), dev(wq), dev(sw), 0.021, h, workspace=scratch(full))
+    assert np.array_equal(host(out).view(np.uint16), host(ref).view(np.uint16))
+    acc_ref = O.gemm_i64(O.ungroup_even_odd(host(ws)[:M * K].view(np.int8).reshape(M, K)), O.unpack(wq))
+    assert ulp_diff(host(out), O.epilogue(acc_ref, np.float32(0.021), sw)).max() <= 1
+    for bits in (4, 8):
+        small = pq.pq_linear_dynamic_workspace_bytes(M, K, bits)
+        full = pq.pq_linear_dynamic_workspace_bytes_split(M, N, K, bits)
+        assert full > small
+        ref, _ = pq.pq_linear_dynamic(dev(x), dev(wq), dev(sw), h, bits=bits, workspace=scratch(small))
+        out, _ = pq.pq_linear_dynamic(dev(x), dev(wq), dev(sw), h, bits=bits, workspace=scratch(full))
+        assert np.array_equal(host(out).view(np.uint16), host(ref).view(np.uint16))
