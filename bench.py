@@ -460,7 +460,7 @@ def main():
     ap.add_argument("--no-variants", action="store_true", help="skip the W4A8 / per-token dynamic variants of the step")
     ap.add_argument("--serving-only", action="store_true",
                     help="of the side legs run only serving_batch (32..256 tokens); for profiles")
-    ap.add_argument("--cpu-rows", type=int, default=1024)
+    ap.add_argument("--cpu-rows", type=int, default=2048, help="tokens of the workload the CPU oracle is timed on (all 2048: about 12 s)")
     ap.add_argument("--profile-copy", action="store_true",
                     help="also run a plain 256 MiB elementwise copy (calibrates HBM counters under rocprofv3 --pmc)")
     args = ap.parse_args()

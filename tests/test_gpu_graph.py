@@ -21,9 +21,13 @@ def pq():
     return b
 
 
-@pytest.mark.parametrize("M,K,N,h", [(1, 4096, 4096, 1), (1, 14336, 512, 128), (4, 4096, 1024, 1), (16, 4096, 2048, 1),
-                                     (12, 14336, 512, 128), (24, 4096, 1024, 1), (300, 1024, 768, 128)])
-def test_linear_replays_match_eager(pq, M, K, N, h):
+@pytest.mark.parametrize("M,K,N,h,planes", [(1, 4096, 4096, 1, False), (1, 14336, 512, 128, False),
+                                            (4, 4096, 1024, 1, False), (16, 4096, 2048, 1, False),
+                                            (12, 14336, 512, 128, False), (24, 4096, 1024, 1, False),
+                                            (300, 1024, 768, 128, False), (48, 14336, 1024, 128, True),
+                                            (100, 4096, 2048, 1, True)])
+def test_linear_replays_match_eager(pq, M, K, N, h, planes):
+    """planes: the workspace also holds the partial sums of the split-K launch (two more kernels in the graph)."""
     wq, sw = O.weight_rtn(synth.weights(N, K, seed=3))
     wp = dev(O.pack(wq))
     dsw = dev(sw)
@@ -31,7 +35,9 @@ def test_linear_replays_match_eager(pq, M, K, N, h):
     sx = float(O.calibrate_absmax(synth.calibration(K, 3), h))
     x = dev(xs[0])
     out = torch.empty((M, N), dtype=torch.float16, device="cuda")
-    work = torch.empty((max(256, pq.pq_linear_workspace_bytes(M, K)),), dtype=torch.uint8, device="cuda")
+    nbytes = pq.pq_linear_workspace_bytes_split(M, N, K) if planes else pq.pq_linear_workspace_bytes(M, K)
+    assert not planes or nbytes > pq.pq_linear_workspace_bytes(M, K)
+    work = torch.empty((max(256, nbytes),), dtype=torch.uint8, device="cuda")
     eager = []
     for xi in xs:
         x.copy_(torch.from_numpy(xi))
