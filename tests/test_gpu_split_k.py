@@ -253,3 +253,27 @@ def test_widened_layers_with_planes_behind_their_workspace(pq):
         ref, _ = pq.pq_linear_dynamic(dev(x), dev(wq), dev(sw), h, bits=bits, workspace=scratch(small))
         out, _ = pq.pq_linear_dynamic(dev(x), dev(wq), dev(sw), h, bits=bits, workspace=scratch(full))
         assert np.array_equal(host(out).view(np.uint16), host(ref).view(np.uint16))
+
+
+def test_random_shapes_split_equals_unsplit(pq):
+    """Seeded random shapes through the automatic choice with a generous workspace: whatever the cost
+    model picks (tile height, number of runs, or no split at all), accumulators and outputs equal the
+    unsplit tiled kernel's; small cases also against the oracle."""
+    rng = np.random.default_rng(20241005)
+    ws = scratch(96 << 20)
+    split = 0
+    for case in range(48):
+        M = int(rng.integers(17, 420))
+        N = 16 * int(rng.integers(1, 300))
+        K = 128 * int(rng.integers(1, 90))
+        xq = synth.random_packed(M, K, seed=case)
+        wq = synth.random_packed(N, K, seed=case, stream=7)
+        sw = synth.random_scales(N, seed=case)
+        split += pq.pq_w4a4_gemm_workspace_bytes(M, N, K) > 0
+        out, acc = pq.pq_w4a4_gemm_ws(dev(xq), dev(wq), dev(sw), 0.07, ws, want_out=True, want_acc=True)
+        ref_out, ref_acc = forced(pq, 2, pq.pq_w4a4_gemm, dev(xq), dev(wq), dev(sw), 0.07, want_out=True, want_acc=True)
+        assert np.array_equal(host(acc), host(ref_acc)), (M, N, K)
+        assert np.array_equal(host(out).view(np.uint16), host(ref_out).view(np.uint16)), (M, N, K)
+        if M * N * K <= 3e8:
+            assert np.array_equal(host(acc).astype(np.int64), O.gemm_i64(O.unpack(xq), O.unpack(wq))), (M, N, K)
+    assert split >= 12          # the draw exercises the split launch, not only the fallback
