@@ -85,7 +85,8 @@ int pq_w4a4_gemm(const void* xq_packed, const void* wq_packed, const float* w_sc
  * the planes and applies the epilogue.  Integer sums are exact in any order: accumulators and
  * outputs equal pq_w4a4_gemm's bit for bit.
  * pq_w4a4_gemm_workspace_bytes: what the cost model's choice needs for the shape, 0 where it would
- *   not split (few tokens: weight-streaming kernels; many: enough tiles).  Host only.
+ *   not split (up to 16 tokens: weight-streaming kernels; many: enough tiles).  Host only.  With
+ *   that much the split launch also takes over 17 to 32 tokens on matrices of 8 MB and more.
  * workspace: device memory, 256-byte aligned, or NULL; workspace_bytes may be smaller than asked
  *   for (fewer planes, or the unsplit kernel) or larger (the rest is untouched).  Its contents on
  *   return are unspecified.  Calls that share a workspace must be ordered on one stream.
@@ -142,8 +143,8 @@ int pq_probe_stream_read(const void* src, int64_t bytes, int32_t* sink, void* st
  * the codes of 8 tokens fit in LDS; else PQ_ERR_UNSUPPORTED), 2 = MFMA tiled, 3 = simple,
  * 4 = weight-streaming 4-bit dot products (M <= 8 only), 5 = MFMA tiled with K split in up to 5
  * runs whenever the call has a workspace of two planes and K has 512 channels (else
- * PQ_ERR_UNSUPPORTED; pq_w4a4_gemm_workspace_bytes then answers for 5 runs).  With 4 pq_linear uses its fused single
- * launch whenever the shape allows it; with 1, 2 or 3 it always uses two launches.
+ * PQ_ERR_UNSUPPORTED; the workspace queries then answer for 5 runs).  With 4 pq_linear uses its
+ * fused single launch whenever the shape allows it; with 1, 2, 3 or 5 it always uses two launches.
  * pq_w4a8_gemm, pq_gemm_dynamic and pq_w4a4_gemm_zp use a weight-streaming kernel only with 0,
  * or with 1 or 4 where that kernel supports the shape, and the tiled kernel otherwise.  The
  * automatic choice for given codes: dot products up to 4 tokens (8 on matrices under 12 MB; with
