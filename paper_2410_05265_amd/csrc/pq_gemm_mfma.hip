@@ -722,16 +722,19 @@ int launch_ragged(const void* xq, const void* wq, const float* sw, float sx, int
     return hip_status(hipGetLastError());
 }
 
-struct TileCfg { int bm, bn; double eff; };
+struct TileCfg { int bm, bn; double eff, stage_us; };   // stage_us: one 128-channel stage of one tile, all CUs busy
 // tile shapes the automatic choice considers, with measured relative efficiencies (a larger
-// wavefront tile needs fewer LDS reads and less expansion per matrix instruction)
-constexpr int kNumAuto = 4, kNumCfg = 8;
-constexpr TileCfg kCfgs[kNumCfg] = {{256, 256, 1.00}, {256, 128, 0.85}, {128, 128, 0.72}, {256, 192, 0.95},
-                                    {256, 256, 1.0},  {256, 256, 1.0}, {256, 128, 1.0}, {256, 128, 1.0}};
+// wavefront tile needs fewer LDS reads and less expansion per matrix instruction; 64 x 128 is for
+// outputs of at most 256 such tiles, where a tile's time is the walk over K: 14.8 against 16.9 us
+// for 128 x 128 at K = 4096, 40.7 against 46.5 at K = 14336)
+constexpr int kNumAuto = 5, kNumCfg = 9;
+constexpr TileCfg kCfgs[kNumCfg] = {{256, 256, 1.00, 1.35}, {256, 128, 0.85, 0.77}, {128, 128, 0.72, 0.42},
+                                    {256, 192, 0.95, 1.05}, {64, 128, 0.41, 0.33},  {256, 256, 1.0, 1.35},
+                                    {256, 256, 1.0, 1.35},  {256, 128, 1.0, 0.77},  {256, 128, 1.0, 0.77}};
 
-// PQ_GEMM_TILE=0..7 forces a configuration (sweeps only): 0 256x256, 1 256x128, 2 128x128,
-// 3 256x192, 4 256x256 with 8 wavefronts, 5 256x256 with a 4-stage ring, 6 and 7 256x128 with 8
-// wavefronts (4x2 and 2x4).
+// PQ_GEMM_TILE=0..8 forces a configuration (sweeps only): 0 256x256, 1 256x128, 2 128x128,
+// 3 256x192, 4 64x128, 5 256x256 with 8 wavefronts, 6 256x256 with a 4-stage ring, 7 and 8 256x128
+// with 8 wavefronts (4x2 and 2x4).
 int pick_cfg(int64_t M, int64_t N)
 {
     if (const char* f = getenv("PQ_GEMM_TILE")) {
@@ -795,10 +798,9 @@ bool pick_dual(int64_t M, int64_t N, int* n1_out, int* n2_out)
 }
 
 // Tile height and number of K runs of the split launch, from a cost model in microseconds
-// (per 128-channel stage: 0.27 for a 64 x 128 tile, 0.42 for 128 x 128, 0.77 for 256 x 128, 1.35 for
-// 256 x 256; 4 per
-// launch; partial planes written and read back at ~3 TB/s).  S = 1: the unsplit kernel is cheaper
-// or the workspace holds no two planes.
+// (per 128-channel stage: 0.27-0.33 for a 64 x 128 tile, 0.42 for 128 x 128, 0.77 for 256 x 128, 1.35
+// for 256 x 256; 3.5 fixed for the unsplit launch, 5.8 for the split pair; partial planes written
+// and read back at ~4 TB/s).  S = 1: the unsplit kernel is cheaper or the workspace holds no two planes.
 void plan_splitk(int64_t M, int64_t N, int64_t K, size_t ws_bytes, bool force, int* bm_out, int* s_out)
 {
     *bm_out = 128;
@@ -816,18 +818,18 @@ void plan_splitk(int64_t M, int64_t N, int64_t K, size_t ws_bytes, bool force, i
     double best = 1e300;
     for (int c = 0; c < kNumAuto; ++c) {
         const int64_t tiles = ((M + kCfgs[c].bm - 1) / kCfgs[c].bm) * ((N + kCfgs[c].bn - 1) / kCfgs[c].bn);
-        const double tk = 1.35 * kCfgs[c].bm * kCfgs[c].bn / 65536.0 / kCfgs[c].eff;
-        const double cost = 4.0 + (double)((tiles + 255) / 256) * nk * tk + out_us;
+        const double cost = 3.5 + (double)((tiles + 255) / 256) * nk * kCfgs[c].stage_us + out_us;
         if (cost < best) best = cost;
     }
+    best -= 1.0;   // the split pair has to win by a margin
     const size_t plane_bytes = (size_t)M * N * 4;
     for (int bm = M <= 128 ? 64 : 128; bm <= 256; bm *= 2) {   // (four row tiles of 64: down_proj measured 5 us slower)
         const int64_t tiles = ((M + bm - 1) / bm) * ((N + 127) / 128);
         const double tk = bm == 64 ? 0.27 : (bm == 128 ? 0.42 : 0.77);
         for (int S = 2; S <= 32 && (int64_t)S * 2 <= nk && (size_t)S * plane_bytes <= ws_bytes; ++S) {
             const int64_t rounds = (tiles * S + 255) / 256;
-            const double cost = 4.0 + (double)rounds * (double)((nk + S - 1) / S) * tk + 3.0 +
-                                (2.0 * S * plane_bytes + (double)M * N * 2) / 3.0e6;
+            const double cost = 5.8 + (double)rounds * (double)((nk + S - 1) / S) * tk +
+                                (2.0 * S * plane_bytes + (double)M * N * 2) / 4.0e6;
             if (cost < best) { best = cost; *bm_out = bm; *s_out = S; }
         }
     }
@@ -850,9 +852,10 @@ int launch_gemm_mfma(const void* xq, const void* wq, const float* sw, float sx, 
         case 1: return launch_dma<256, 128, 2, 2, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
         case 2: return launch_dma<128, 128, 2, 2, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
         case 3: return launch_dma<256, 192, 2, 2, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
-        case 4: return launch_dma<256, 256, 2, 4, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
-        case 6: return launch_dma<256, 128, 4, 2, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
-        case 7: return launch_dma<256, 128, 2, 4, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
+        case 4: return launch_dma<64, 128, 2, 2, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
+        case 5: return launch_dma<256, 256, 2, 4, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
+        case 7: return launch_dma<256, 128, 4, 2, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
+        case 8: return launch_dma<256, 128, 2, 4, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
         default: return launch_dma<256, 256, 2, 2, 4, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
     }
 }
@@ -909,6 +912,7 @@ int launch_gemm_w4a8(const void* xq8, const void* wq, const float* sw, float sx,
         case 0: return launch_dma<256, 256, 2, 2, 3, 1, 8, 4>(xq8, wq, sw, sx, M, N, K, out, acc, st);
         case 1: return launch_dma<256, 128, 2, 2, 3, 1, 8, 4>(xq8, wq, sw, sx, M, N, K, out, acc, st);
         case 3: return launch_dma<256, 192, 2, 2, 3, 1, 8, 4>(xq8, wq, sw, sx, M, N, K, out, acc, st);
+        case 4: return launch_dma<64, 128, 2, 2, 3, 1, 8, 4>(xq8, wq, sw, sx, M, N, K, out, acc, st);
         default: return launch_dma<128, 128, 2, 2, 3, 1, 8, 4>(xq8, wq, sw, sx, M, N, K, out, acc, st);
     }
 }
@@ -936,6 +940,7 @@ int launch_gemm_dynamic(const void* xq, int32_t bits, const void* wq, const floa
             case 0: return launch_dma<256, 256, 2, 2, 3, 1, 8, 4>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
             case 1: return launch_dma<256, 128, 2, 2, 3, 1, 8, 4>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
             case 3: return launch_dma<256, 192, 2, 2, 3, 1, 8, 4>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
+            case 4: return launch_dma<64, 128, 2, 2, 3, 1, 8, 4>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
             default: return launch_dma<128, 128, 2, 2, 3, 1, 8, 4>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
         }
     }
@@ -944,6 +949,7 @@ int launch_gemm_dynamic(const void* xq, int32_t bits, const void* wq, const floa
         case 0: return launch_dma<256, 256, 2, 2, 3, 1>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
         case 1: return launch_dma<256, 128, 2, 2, 3, 1>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
         case 3: return launch_dma<256, 192, 2, 2, 3, 1>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
+        case 4: return launch_dma<64, 128, 2, 2, 3, 1>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
         default: return launch_dma<128, 128, 2, 2, 3, 1>(xq, wq, sw, 1.0f, M, N, K, out, acc, st, srow);
     }
 }
@@ -963,6 +969,7 @@ int launch_gemm_zp(const void* xq, const void* wq, const float* sw, float sx, co
         case 0: return launch_dma<256, 256, 2, 2, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st, nullptr, zcorr);
         case 1: return launch_dma<256, 128, 2, 2, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st, nullptr, zcorr);
         case 3: return launch_dma<256, 192, 2, 2, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st, nullptr, zcorr);
+        case 4: return launch_dma<64, 128, 2, 2, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st, nullptr, zcorr);
         default: return launch_dma<128, 128, 2, 2, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st, nullptr, zcorr);
     }
 }
