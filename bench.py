@@ -445,7 +445,14 @@ def cpu_baseline(synth, rows=256):
             stage[k] += v
     dt = time.perf_counter() - t0
     ops = sum(2.0 * rows * K * N for _, K, N, _ in LINEARS)
-    return {"value": round(ops / dt / 1e12, 5), "unit": "TOPS", "cores": O.threads(), "kind": "oracle",
+    model = ""
+    try:
+        with open("/proc/cpuinfo") as f:
+            model = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), "")
+    except OSError:
+        pass
+    return {"value": round(ops / dt / 1e12, 5), "unit": "TOPS", "cores": O.threads(), "cpu_model": model,
+            "kind": "oracle",
             "sample": "first %d of 2048 tokens, all five linears, whole path (fp64 dense Hadamard, RNE, int64 "
                       "product, fp64 epilogue), %.1f s: %s" % (rows, dt, ", ".join("%s %.1f s" % kv for kv in stage.items()))}
 
