@@ -152,6 +152,9 @@ int pq_probe_stream_read(const void* src, int64_t bytes, int32_t* sink, void* st
  * 16 (up to 32 in two launches on long rows and on matrices under 24 MB), tiled beyond.  Every kernel
  * gives the same accumulators and the same fp16 outputs bit for bit.
  * Returns the previous value, or -1 if `variant` is unknown.
+ * The environment variable PQ_GEMM_TILE (0..8, read at every call; sweeps and tests only) forces the
+ * tiled kernel's tile: 0 256x256, 1 256x128, 2 128x128, 3 256x192, 4 64x128, 5-8 variants of these with
+ * more wavefronts or a deeper ring; unset, the tile follows from the shape.
  */
 int pq_set_gemm_variant(int variant);
 
