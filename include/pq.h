@@ -85,8 +85,9 @@ int pq_w4a4_gemm(const void* xq_packed, const void* wq_packed, const float* w_sc
  * the planes and applies the epilogue.  Integer sums are exact in any order: accumulators and
  * outputs equal pq_w4a4_gemm's bit for bit.
  * pq_w4a4_gemm_workspace_bytes: what the cost model's choice needs for the shape, 0 where it would
- *   not split (up to 16 tokens: weight-streaming kernels; many: enough tiles).  Host only.  With
- *   that much the split launch also takes over 17 to 32 tokens on matrices of 8 MB and more.
+ *   not split (one launch of a weight-streaming kernel serves, up to 16 tokens; or the output has
+ *   enough tiles).  Host only.  With that much the split launch also takes over from two or more
+ *   weight-streaming launches (17 to 32 tokens, very long rows) on matrices of 8 MB and more.
  * workspace: device memory, 256-byte aligned, or NULL; workspace_bytes may be smaller than asked
  *   for (fewer planes, or the unsplit kernel) or larger (the rest is untouched).  Its contents on
  *   return are unspecified.  Calls that share a workspace must be ordered on one stream.
@@ -149,8 +150,9 @@ int pq_probe_stream_read(const void* src, int64_t bytes, int32_t* sink, void* st
  * or with 1 or 4 where that kernel supports the shape, and the tiled kernel otherwise.  The
  * automatic choice for given codes: dot products up to 4 tokens (8 on matrices under 12 MB; with
  * int8 activations 2, 4 and 6 on matrices over 24 MB, over 12 MB and smaller), matrix tiles up to
- * 16 (up to 32 in two launches on long rows and on matrices under 24 MB), tiled beyond.  Every kernel
- * gives the same accumulators and the same fp16 outputs bit for bit.
+ * 16 (up to 32 in two launches where a cost estimate puts that ahead of the tiled kernel: outputs
+ * of few tiles), tiled beyond.  Every kernel gives the same accumulators and the same fp16 outputs
+ * bit for bit.
  * Returns the previous value, or -1 if `variant` is unknown.
  * The environment variable PQ_GEMM_TILE (0..8, read at every call; sweeps and tests only) forces the
  * tiled kernel's tile: 0 256x256, 1 256x128, 2 128x128, 3 256x192, 4 64x128, 5-8 variants of these with

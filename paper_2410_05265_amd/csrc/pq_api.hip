@@ -14,8 +14,8 @@ int g_variant = 0;  // 0 auto, 1 streaming MFMA (M <= 32), 2 MFMA tiled, 3 simpl
 // the matrix kernel costs the same for any count up to 16 but has a higher floor; where they cross
 // depends on the size of the matrix (measured on the Llama-3-8B shapes, 8 / 12.6 / 29 MB of
 // weights): 4-bit codes from 5 tokens on (9 on small matrices), int8 codes from 3, 5 and 7.
-// 17 to 32 tokens are two launches of the matrix kernel where that beats the tiled kernel, whose
-// time at such counts is set by K alone: on long rows and on matrices under 24 MB.
+// 17 to 32 tokens are two launches of the matrix kernel where a cost estimate puts that ahead of
+// the tiled kernel (8B shapes: everything but gate/up; 70B: not gate/up either, 224 tiles).
 int pick_few_tokens(int64_t M, int64_t N, int64_t K, int32_t abits)
 {
     const bool dot = M <= 8 && pq::decode_supported(M, N, K, -1, abits);
@@ -27,17 +27,26 @@ int pick_few_tokens(int64_t M, int64_t N, int64_t K, int32_t abits)
     const int size = weight_bytes >= 24000000 ? 2 : (weight_bytes >= 12000000 ? 1 : 0);
     const int64_t dot_limit = abits == 8 ? (size == 2 ? 2 : (size == 1 ? 4 : 6)) : (size >= 1 ? 4 : 8);
     if (dot && (M <= dot_limit || !mat)) return 4;
-    if (mat && (M <= 16 || K >= 8192 || size < 2)) return 1;
+    if (mat) {
+        // one launch of up to 16 tokens always; several launches (17..32 tokens, or rows too long for 16
+        // tokens' codes in LDS) that each stream the matrix (2.5 us + bytes at ~5 TB/s) against the tiled
+        // kernel, whose time there is a walk over K by however many tiles the output has
+        const int launches = pq::stream_mfma_launches(M, N, K, abits);
+        if (launches == 1) return 1;
+        const double stream_us = launches * (2.5 + (double)weight_bytes / 5.0e6);
+        if (stream_us < pq::gemm_unsplit_cost_us(M, N, K)) return 1;
+    }
     return 2;
 }
 
 // The same choice when the call brings scratch memory for partial-sum planes (timings: 4-bit codes).
-// 17 to 32 tokens: with its planes in place the split tiled launch beats two launches of the matrix
-// streaming kernel on matrices of 8 MB and more (8-14 us against 9-16; not measured below).
+// Where the matrix streaming kernel needs two or more launches (17 to 32 tokens, or rows too long
+// for 16 tokens' codes in LDS), the split tiled launch with its planes in place beats them on
+// matrices of 8 MB and more (8B shapes at 24 tokens: 8-13 us against 9-16; not measured below 8 MB).
 int pick_with_planes(int64_t M, int64_t N, int64_t K, size_t plane_bytes, int32_t abits = 4)
 {
     const int kernel = pick_few_tokens(M, N, K, abits);
-    if (g_variant == 0 && kernel == 1 && M > 16 && N * (K / 2) >= 8000000) {
+    if (g_variant == 0 && kernel == 1 && N * (K / 2) >= 8000000 && pq::stream_mfma_launches(M, N, K, abits) > 1) {
         const size_t want = pq::gemm_splitk_workspace_bytes(M, N, K);
         if (want > 0 && plane_bytes >= want) return 2;
     }

@@ -814,14 +814,7 @@ void plan_splitk(int64_t M, int64_t N, int64_t K, size_t ws_bytes, bool force, i
         *s_out = S;
         return;
     }
-    const double out_us = (double)M * N * 2 / 4.2e6;
-    double best = 1e300;
-    for (int c = 0; c < kNumAuto; ++c) {
-        const int64_t tiles = ((M + kCfgs[c].bm - 1) / kCfgs[c].bm) * ((N + kCfgs[c].bn - 1) / kCfgs[c].bn);
-        const double cost = 3.5 + (double)((tiles + 255) / 256) * nk * kCfgs[c].stage_us + out_us;
-        if (cost < best) best = cost;
-    }
-    best -= 1.0;   // the split pair has to win by a margin
+    double best = gemm_unsplit_cost_us(M, N, K) - 1.0;   // the split pair has to win by a margin
     const size_t plane_bytes = (size_t)M * N * 4;
     for (int bm = M <= 128 ? 64 : 128; bm <= 256; bm *= 2) {   // (four row tiles of 64: down_proj measured 5 us slower)
         const int64_t tiles = ((M + bm - 1) / bm) * ((N + 127) / 128);
@@ -858,6 +851,21 @@ int launch_gemm_mfma(const void* xq, const void* wq, const float* sw, float sx, 
         case 8: return launch_dma<256, 128, 2, 4, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
         default: return launch_dma<256, 256, 2, 2, 4, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
     }
+}
+
+// The cost model's figure for the unsplit tiled launch, in microseconds (the best automatic tile;
+// K % 128 != 0 takes the generic kernel, which is not modelled: a large number).
+double gemm_unsplit_cost_us(int64_t M, int64_t N, int64_t K)
+{
+    if (K % 128 != 0) return 1e9;
+    const int64_t nk = K / 128;
+    double best = 1e300;
+    for (int c = 0; c < kNumAuto; ++c) {
+        const int64_t tiles = ((M + kCfgs[c].bm - 1) / kCfgs[c].bm) * ((N + kCfgs[c].bn - 1) / kCfgs[c].bn);
+        const double cost = 3.5 + (double)((tiles + 255) / 256) * nk * kCfgs[c].stage_us + (double)M * N * 2 / 4.2e6;
+        if (cost < best) best = cost;
+    }
+    return best;
 }
 
 size_t gemm_splitk_workspace_bytes(int64_t M, int64_t N, int64_t K, bool force)

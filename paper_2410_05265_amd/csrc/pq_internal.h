@@ -52,6 +52,8 @@ int launch_gemm_mfma(const void* xq, const void* wq, const float* sw, float sx, 
 // a smaller one gets fewer planes or the unsplit launch.  force: split whenever K has two runs of two
 // stages and ws holds two planes (tests); PQ_ERR_UNSUPPORTED if not.
 size_t gemm_splitk_workspace_bytes(int64_t M, int64_t N, int64_t K, bool force = false);
+// the cost model's microseconds for the unsplit tiled launch (used to choose between kernels)
+double gemm_unsplit_cost_us(int64_t M, int64_t N, int64_t K);
 int launch_gemm_mfma_ws(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K,
                         void* out, int32_t* acc, void* ws, size_t ws_bytes, bool force, hipStream_t st);
 int launch_probe_mfma(const void* operands, int64_t operand_bytes, int64_t iters, int32_t workgroups, int32_t* sink,
@@ -59,6 +61,7 @@ int launch_probe_mfma(const void* operands, int64_t operand_bytes, int64_t iters
 int launch_probe_read(const void* src, int64_t bytes, int32_t* sink, hipStream_t st);
 
 bool stream_mfma_supported(int64_t M, int64_t N, int64_t K, int32_t abits = 4);
+int stream_mfma_launches(int64_t M, int64_t N, int64_t K, int32_t abits = 4);   // for a supported shape
 int launch_stream_mfma(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K,
                        void* out, int32_t* acc, hipStream_t st, const float* srow = nullptr, int32_t abits = 4,
                        const int32_t* zcorr = nullptr);

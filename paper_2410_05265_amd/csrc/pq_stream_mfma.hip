@@ -353,14 +353,22 @@ int launch_tokens(const void* xq, const void* wq, const float* sw, float sx, int
 
 // The kernel takes up to 16 tokens whose codes fit in LDS together.  Up to 32 tokens, or tokens whose
 // codes do not fit, go in several launches (blocks of 16 tokens, halved where they do not fit): the
-// weights are then streamed once per launch, which at these token counts is still faster than the
-// tiled kernel, whose few tiles walk K one after the other (16 us at K = 4096, 47 us at 14336).
+// weights are then streamed once per launch; the caller weighs that against the tiled kernel, whose
+// few tiles walk K one after the other (stream_mfma_launches says how many launches it would be).
 bool stream_mfma_supported(int64_t M, int64_t N, int64_t K, int32_t abits)
 {
     if (!(M >= 1 && M <= 32 && N >= 16 && (N % 16) == 0 && N <= (1 << 30) && K >= 256 && (K % 256) == 0 && K <= 65536))
         return false;
     const int64_t block = M < 16 ? M : 16;
     return fits_in_lds((block + 1) / 2, N, K, abits);
+}
+
+// Launches launch_stream_mfma makes for a supported shape (each streams the whole matrix).
+int stream_mfma_launches(int64_t M, int64_t N, int64_t K, int32_t abits)
+{
+    if (M <= 16 && fits_in_lds(M, N, K, abits)) return 1;
+    const int64_t m1 = M > 16 ? 16 : (M + 1) / 2;
+    return stream_mfma_launches(m1, N, K, abits) + stream_mfma_launches(M - m1, N, K, abits);
 }
 
 int launch_stream_mfma(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K,
