@@ -277,3 +277,33 @@ def test_random_shapes_split_equals_unsplit(pq):
         if M * N * K <= 3e8:
             assert np.array_equal(host(acc).astype(np.int64), O.gemm_i64(O.unpack(xq), O.unpack(wq))), (M, N, K)
     assert split >= 12          # the draw exercises the split launch, not only the fallback
+
+
+def test_random_shapes_widened_products_with_planes(pq):
+    """Seeded random shapes through the automatic choice of the int8, per-token and zero-point
+    products with a generous workspace, against the oracle."""
+    rng = np.random.default_rng(5265)
+    ws = scratch(64 << 20)
+    for case in range(30):
+        M = int(rng.integers(9, 300))
+        N = 16 * int(rng.integers(1, 120))
+        K = 128 * int(rng.integers(1, 40))
+        q = synth.random_codes(M, K, seed=case, stream=9, lo=-128, hi=127)
+        xq = synth.random_packed(M, K, seed=case)
+        wq = synth.random_packed(N, K, seed=case, stream=7)
+        sw = synth.random_scales(N, seed=case)
+        srow = synth.random_scales(M, seed=case + 1)
+        a8 = O.gemm_i64(q, O.unpack(wq))
+        a4 = O.gemm_i64(O.unpack(xq), O.unpack(wq))
+        out, acc = pq.pq_w4a8_gemm_ws(dev(O.group_even_odd(q)), dev(wq), dev(sw), 0.013, ws, want_out=True, want_acc=True)
+        assert np.array_equal(host(acc).astype(np.int64), a8), (M, N, K)
+        assert ulp_diff(host(out), O.epilogue(a8, np.float32(0.013), sw)).max() <= 1, (M, N, K)
+        out, acc = pq.pq_gemm_dynamic_ws(dev(xq), 4, dev(wq), dev(sw), dev(srow), ws, want_out=True, want_acc=True)
+        assert np.array_equal(host(acc).astype(np.int64), a4), (M, N, K)
+        assert ulp_diff(host(out), O.epilogue(a4, srow, sw)).max() <= 1, (M, N, K)
+        z = int(rng.integers(0, 16))
+        corr = (8 - z) * O.unpack(wq).astype(np.int64).sum(axis=1)
+        out, acc = pq.pq_w4a4_gemm_zp_ws(dev(xq), dev(wq), dev(sw), 0.07, pq.pq_zero_point_correction(dev(wq), z), ws,
+                                         want_out=True, want_acc=True)
+        assert np.array_equal(host(acc).astype(np.int64), a4), (M, N, K)
+        assert ulp_diff(host(out), O.epilogue(a4 + corr[None, :], np.float32(0.07), sw)).max() <= 1, (M, N, K, z)
