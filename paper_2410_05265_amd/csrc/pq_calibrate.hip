@@ -295,15 +295,12 @@ int launch_cal_zp_nc(const __half* xp, int64_t T, int64_t K, int log2h, double i
                      double bmin, float* result, float* ws, hipStream_t st)
 {
     const size_t lds = log2h > 9 ? (size_t)NC * kChunk * sizeof(float) : 0;
-    static bool attr_set = false;  // benign race: the calls are idempotent
-    if (lds > 32 * 1024 && !attr_set) {
-        const int mx = (int)((size_t)NC * kChunk * sizeof(float));
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_cal_rowminmax<NC>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, mx) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void*>(k_cal_rowerr_zp<NC>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, mx) != hipSuccess)
+    static uint64_t lds_a = 0, lds_b = 0;
+    if (lds > 32 * 1024) {
+        const size_t mx = (size_t)NC * kChunk * sizeof(float);
+        if (allow_dynamic_lds(reinterpret_cast<const void*>(k_cal_rowminmax<NC>), mx, lds_a) != PQ_OK ||
+            allow_dynamic_lds(reinterpret_cast<const void*>(k_cal_rowerr_zp<NC>), mx, lds_b) != PQ_OK)
             return PQ_ERR_HIP;
-        attr_set = true;
     }
     hipLaunchKernelGGL(k_cal_rowminmax<NC>, dim3((unsigned)T), dim3(kThreads), lds, st, xp, T, K, log2h, ws);
     hipLaunchKernelGGL(k_cal_rowerr_zp<NC>, dim3((unsigned)T), dim3(kThreads), lds, st, xp, T, K, log2h, inv_sqrt_h, ng, nb,
@@ -317,15 +314,12 @@ int launch_cal_nc(const __half* xp, int64_t T, int64_t K, int log2h, double inv_
                   double gamma_min, float* result, float* ws, hipStream_t st)
 {
     const size_t lds = log2h > 9 ? (size_t)NC * kChunk * sizeof(float) : 0;
-    static bool attr_set = false;  // benign race: the calls are idempotent
-    if (lds > 32 * 1024 && !attr_set) {
-        const int mx = (int)((size_t)NC * kChunk * sizeof(float));
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_cal_rowmax<NC>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, mx) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void*>(k_cal_rowerr<NC>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, mx) != hipSuccess)
+    static uint64_t lds_a = 0, lds_b = 0;
+    if (lds > 32 * 1024) {
+        const size_t mx = (size_t)NC * kChunk * sizeof(float);
+        if (allow_dynamic_lds(reinterpret_cast<const void*>(k_cal_rowmax<NC>), mx, lds_a) != PQ_OK ||
+            allow_dynamic_lds(reinterpret_cast<const void*>(k_cal_rowerr<NC>), mx, lds_b) != PQ_OK)
             return PQ_ERR_HIP;
-        attr_set = true;
     }
     hipLaunchKernelGGL(k_cal_rowmax<NC>, dim3((unsigned)T), dim3(kThreads), lds, st, xp, K, log2h, ws);
     hipLaunchKernelGGL(k_cal_rowerr<NC>, dim3((unsigned)T), dim3(kThreads), lds, st, xp, T, K, log2h, inv_sqrt_h, bits,

@@ -265,13 +265,9 @@ int launch_one(const __half* x, const uint8_t* xq_in, const uint8_t* wq, const f
     const size_t lds = (((size_t)MP * (ABITS == 8 ? K : K / 2) + 15) & ~(size_t)15) +
                        (MODE == 0 ? 16 : (size_t)G * kChunk * 4 + (size_t)M * K * 2);
     auto kern = k_decode<RPW, CB, MP, MODE, ABITS>;
-    static bool attr_set = false;  // benign race: the call is idempotent
-    if (lds > 48 * 1024 && !attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                160 * 1024) != hipSuccess)
-            return PQ_ERR_HIP;
-        attr_set = true;
-    }
+    static uint64_t lds_ok = 0;
+    if (lds > 48 * 1024 && allow_dynamic_lds(reinterpret_cast<const void*>(kern), 160 * 1024, lds_ok) != PQ_OK)
+        return PQ_ERR_HIP;
     const int groups = N / RPW;
     int grid = (groups + 15) / 16;
     grid = grid > 256 ? 256 : grid;

@@ -473,13 +473,8 @@ int launch_dual(const void* xq, const void* wq, const float* sw, float sx, int64
     constexpr size_t lds = (size_t)NS * (BM * (ABITS == 8 ? 128 : 64) + (BN1 > BN2 ? BN1 : BN2) * 64);
     static_assert(lds <= 160 * 1024, "LDS ring too large");
     auto kern = k_gemm_dual<BM, BN1, BN2, WR, WC, NS, ABITS, ASHIFT>;
-    static bool attr_set = false;  // benign race: the call is idempotent
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)lds) != hipSuccess)
-            return PQ_ERR_HIP;
-        attr_set = true;
-    }
+    static uint64_t lds_ok = 0;
+    if (allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds, lds_ok) != PQ_OK) return PQ_ERR_HIP;
     hipLaunchKernelGGL(kern, dim3((unsigned)(GM * (n1 + n2))), dim3(WR * WC * 64), lds, st,
                        static_cast<const uint8_t*>(xq), static_cast<const uint8_t*>(wq), sw, sx, (int)M, (int)N,
                        (int)K, GM, n1, n2, static_cast<__half*>(out), acc, srow, zcorr);
@@ -494,13 +489,9 @@ int launch_dma(const void* xq, const void* wq, const float* sw, float sx, int64_
     constexpr size_t lds = (size_t)NS * SUBS * (BM * (ABITS == 8 ? 128 : 64) + BN * 64);
     static_assert(lds <= 160 * 1024, "LDS ring too large");
     auto kern = k_gemm_dma<BM, BN, WR, WC, NS, SUBS, ABITS, ASHIFT>;
-    static bool attr_set = false;  // benign race: the call is idempotent
-    if (lds > 48 * 1024 && !attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return PQ_ERR_HIP;
-        attr_set = true;
-    }
+    static uint64_t lds_ok = 0;
+    if (lds > 48 * 1024 && allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds, lds_ok) != PQ_OK)
+        return PQ_ERR_HIP;
     hipLaunchKernelGGL(kern, dim3((unsigned)(GM * GN)), dim3(WR * WC * 64), lds, st,
                        static_cast<const uint8_t*>(xq), static_cast<const uint8_t*>(wq), sw, sx, (int)M, (int)N,
                        (int)K, GM, static_cast<__half*>(out), acc, srow, zcorr);
@@ -578,13 +569,9 @@ int launch_splitk(const void* xq, const void* wq, const float* sw, SplitArgs ep,
     constexpr size_t lds = (size_t)NS * (BM * (ABITS == 8 ? 128 : 64) + BN * 64);
     static_assert(lds <= 160 * 1024, "LDS ring too large");
     auto kern = k_gemm_splitk<BM, BN, 2, 2, NS, ABITS, ASHIFT>;
-    static bool attr_set = false;  // benign race: the call is idempotent
-    if (lds > 48 * 1024 && !attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)lds) != hipSuccess)
-            return PQ_ERR_HIP;
-        attr_set = true;
-    }
+    static uint64_t lds_ok = 0;
+    if (lds > 48 * 1024 && allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds, lds_ok) != PQ_OK)
+        return PQ_ERR_HIP;
     hipLaunchKernelGGL(kern, dim3((unsigned)(GM * GN * S)), dim3(256), lds, st, static_cast<const uint8_t*>(xq),
                        static_cast<const uint8_t*>(wq), (int)M, (int)N, (int)K, GM, GM * GN, S, part);
     if (hipGetLastError() != hipSuccess) return PQ_ERR_HIP;

@@ -73,6 +73,20 @@ int launch_decode(const void* x_f16, const void* xq_in, const void* wq, const fl
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? PQ_OK : PQ_ERR_HIP; }
 
+// A kernel may use more than the default amount of dynamic LDS only after the runtime has been told,
+// once per kernel and device.  `done` is that kernel's mask of devices already served (a static of
+// the caller; two first calls racing is harmless, the setting is idempotent).
+inline int allow_dynamic_lds(const void* kern, size_t bytes, uint64_t& done)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return PQ_ERR_HIP;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (done & bit) return PQ_OK;
+    if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) return PQ_ERR_HIP;
+    done |= bit;
+    return PQ_OK;
+}
+
 // A product rounded to fp32 on its own.  Written as a plain a * b the compiler merges the
 // multiplication with the conversion to fp16 that follows (one rounding instead of two) in some
 // kernels and not in others, and then the kernels of this library would differ from one another in

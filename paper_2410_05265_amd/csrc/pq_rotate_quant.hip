@@ -292,13 +292,10 @@ int launch_dyn_nc(const __half* xp, int64_t M, int64_t K, int log2h, double inv_
 {
     const size_t lds = log2h > 9 ? (size_t)NC * kChunk * sizeof(float) : 0;
     auto kern = k_rotate_quant_dyn<NC, BITS>;
-    static bool attr_set = false;  // benign race: the call is idempotent
-    if (lds > 48 * 1024 && !attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)((size_t)NC * kChunk * sizeof(float))) != hipSuccess)
-            return PQ_ERR_HIP;
-        attr_set = true;
-    }
+    static uint64_t lds_ok = 0;
+    if (lds > 48 * 1024 &&
+        allow_dynamic_lds(reinterpret_cast<const void*>(kern), (size_t)NC * kChunk * sizeof(float), lds_ok) != PQ_OK)
+        return PQ_ERR_HIP;
     hipLaunchKernelGGL(kern, dim3((unsigned)M), dim3(kThreads), lds, st, xp, K, log2h, inv_sqrt_h, clip, op, row_scale);
     return hip_status(hipGetLastError());
 }
