@@ -232,6 +232,12 @@ def run_llama3_70b(torch, pq, synth, decode=True):
         d = run_decode(torch, pq, layers, M=1)
         res["decode_M1"] = {"GBps": d["GBps"], "frac_hbm": d["frac_hbm"],
                             "per_linear": {k: {"us": v["us"], "frac_hbm": v["frac_hbm"]} for k, v in d["per_linear"].items()}}
+        # a serving batch: the tiled kernel alone, and with planes for its split-K launch (us per pq_linear)
+        a = run_decode(torch, pq, layers, M=64)
+        b = run_decode(torch, pq, layers, M=64, planes=True)
+        res["serving_M64"] = {"per_linear_us": {k: v["us"] for k, v in a["per_linear"].items()},
+                              "per_linear_us_planes": {k: v["us"] for k, v in b["per_linear"].items()},
+                              "frac_hbm": a["frac_hbm"], "frac_hbm_planes": b["frac_hbm"]}
     return res
 
 
