@@ -509,7 +509,10 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_splitk(const uint8_t* __r
                                                              const uint8_t* __restrict__ wq, int M, int N, int K,
                                                              int GM, int tiles, int S, int32_t* __restrict__ part)
 {
-    const int tile = blockIdx.x % tiles, s = blockIdx.x / tiles;
+    // each XCD takes a contiguous run of (run, tile) pairs, row tiles fastest: the row tiles of one
+    // column panel meet in one L2 and fetch its weights once
+    const int w = xcd_remap(blockIdx.x, gridDim.x);
+    const int tile = w % tiles, s = w / tiles;
     const int nk = K / 128;
     const int kt0 = (int)((int64_t)nk * s / S), kt1 = (int)((int64_t)nk * (s + 1) / S);
     gemm_tile<BM, BN, WR, WC, NS, 1, ABITS, ASHIFT, true>(xq, wq, nullptr, 0.0f, M, N, K, (tile % GM) * BM, (tile / GM) * BN,
