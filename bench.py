@@ -262,6 +262,28 @@ def run_probes(torch, pq):
         e1.record()
         torch.cuda.synchronize()
         res["mfma_only_TOPS"][name] = round(ops / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+    # the 6-bit floating-point matrix instruction on the same codes written as E3M2 (exact for -8..8);
+    # a register image is 32 bytes: 32 values of 6 bits, little-endian bit stream, in the first 24
+    import numpy as np
+    rng = np.random.default_rng(7)
+    codes = rng.integers(-8, 8, size=(1 << 15, 32))
+    table = np.array([0, 12, 16, 18, 20, 21, 22, 23, 24], dtype=np.uint64)        # E3M2 of 0..8
+    enc = table[np.abs(codes)] | (np.uint64(32) * (codes < 0).astype(np.uint64))
+    words = np.zeros((codes.shape[0], 4), dtype=np.uint64)
+    for i in range(32):
+        bit = 6 * i
+        words[:, bit // 64] |= enc[:, i] << np.uint64(bit % 64)
+        if bit % 64 > 58:
+            words[:, bit // 64 + 1] |= enc[:, i] >> np.uint64(64 - bit % 64)
+    t6 = torch.from_numpy(words.view(np.uint8).reshape(-1)).cuda()
+    pq.pq_probe_mfma_f6(t6, 1000, 256, sink)
+    device_warmup(torch)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    ops = sum(pq.pq_probe_mfma_f6(t6, 1000, 256, sink) for _ in range(5))
+    e1.record()
+    torch.cuda.synchronize()
+    res["mfma_only_TOPS"]["codes_as_e3m2_6bit_fp32_accumulate"] = round(ops / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
     big = torch.randint(0, 256, (1 << 30,), generator=gen, device="cuda", dtype=torch.uint8)
     pq.pq_probe_stream_read(big, sink)
     device_warmup(torch, 40.0)

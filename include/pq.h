@@ -138,6 +138,20 @@ int pq_w4a4_gemm_simple(const void* xq_packed, const void* wq_packed, const floa
 int pq_probe_mfma_i8(const void* operands, int64_t operand_bytes, int64_t iters, int32_t workgroups,
                      int32_t* sink, void* stream);
 int pq_probe_stream_read(const void* src, int64_t bytes, int32_t* sink, void* stream);
+/* The 6-bit floating-point matrix instruction of the same GPU (E3M2 operands, fp32 accumulate, twice
+ * the nominal rate of INT8): every 4-bit code -8..7 (and +8) is exact in E3M2, products and sums
+ * below 2^24 are exact in fp32, so it multiplies the codes of Eq. 1 exactly.
+ * pq_probe_mfma_f6: as pq_probe_mfma_i8; operands are raw register images of 32 bytes (32 values of
+ *   6 bits in the first 24 bytes), 32-byte aligned, operand_bytes a multiple of 32.  Operations of a
+ *   launch: workgroups * 4 * iters * 16 * 131072.
+ * pq_probe_f6_product: out[i][j] = sum_k a[i][k] b[j][k] for i, j < 32 through that instruction;
+ *   a_codes, b_codes device int8 [32,K] with values in [-8, 8] (clamped), K % 64 == 0, K <= 262080,
+ *   out_i32 device [32,32]; 16-byte aligned.  One wavefront; a check of exactness, not of speed.
+ */
+int pq_probe_mfma_f6(const void* operands, int64_t operand_bytes, int64_t iters, int32_t workgroups,
+                     int32_t* sink, void* stream);
+int pq_probe_f6_product(const int8_t* a_codes, const int8_t* b_codes, int64_t K, int32_t* out_i32,
+                        void* stream);
 
 /* Force a kernel variant of pq_w4a4_gemm for sweeps and tests (host, process-wide,
  * not thread-safe): 0 = automatic, 1 = weight-streaming matrix tiles (M <= 32, K % 256 == 0 and

@@ -34,6 +34,8 @@ SIGNATURES = {
     "pq_set_gemm_variant": (ctypes.c_int, [ctypes.c_int]),
     "pq_probe_mfma_i8": (ctypes.c_int, [_vp, _i64, _i64, _i32, _vp, _vp]),
     "pq_probe_stream_read": (ctypes.c_int, [_vp, _i64, _vp, _vp]),
+    "pq_probe_mfma_f6": (ctypes.c_int, [_vp, _i64, _i64, _i32, _vp, _vp]),
+    "pq_probe_f6_product": (ctypes.c_int, [_vp, _vp, _i64, _vp, _vp]),
     "pq_rotate_quant8": (ctypes.c_int, [_vp, _i64, _i64, _i32, _f32, _vp, _vp]),
     "pq_w4a8_gemm": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i64, _i64, _i64, _vp, _vp, _vp]),
     "pq_w4a8_gemm_ws": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i64, _i64, _i64, _vp, _vp, _vp, _sz, _vp]),
@@ -493,6 +495,25 @@ def pq_probe_mfma_i8(operands: torch.Tensor, iters: int, workgroups: int, sink: 
     _check(lib().pq_probe_mfma_i8(_ptr(operands), operands.numel() * operands.element_size(), int(iters), int(workgroups),
                                   _ptr(sink), _stream()), "pq_probe_mfma_i8")
     return float(workgroups) * 4 * iters * 16 * 65536
+
+
+def pq_probe_mfma_f6(operands: torch.Tensor, iters: int, workgroups: int, sink: torch.Tensor) -> float:
+    """Launches the 6-bit matrix-instruction probe; returns the operations of the launch."""
+    _check(lib().pq_probe_mfma_f6(_ptr(operands), operands.numel() * operands.element_size(), int(iters), int(workgroups),
+                                  _ptr(sink), _stream()), "pq_probe_mfma_f6")
+    return float(workgroups) * 4 * iters * 16 * 131072
+
+
+def pq_probe_f6_product(a_codes: torch.Tensor, b_codes: torch.Tensor) -> torch.Tensor:
+    """int8 codes [32,K] x [32,K] -> int32 [32,32] through the 6-bit floating-point matrix instruction."""
+    _dev(a_codes, torch.int8, "a_codes")
+    _dev(b_codes, torch.int8, "b_codes")
+    if a_codes.shape != b_codes.shape or a_codes.shape[0] != 32:
+        raise ValueError("shape mismatch")
+    out = torch.empty((32, 32), dtype=torch.int32, device=a_codes.device)
+    _check(lib().pq_probe_f6_product(_ptr(a_codes), _ptr(b_codes), a_codes.shape[1], _ptr(out), _stream()),
+           "pq_probe_f6_product")
+    return out
 
 
 def pq_probe_stream_read(src: torch.Tensor, sink: torch.Tensor) -> int:

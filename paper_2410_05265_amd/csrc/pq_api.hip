@@ -528,6 +528,25 @@ int pq_probe_mfma_i8(const void* operands, int64_t operand_bytes, int64_t iters,
     return pq::launch_probe_mfma(operands, operand_bytes, iters, workgroups, sink, static_cast<hipStream_t>(stream));
 }
 
+int pq_probe_mfma_f6(const void* operands, int64_t operand_bytes, int64_t iters, int32_t workgroups, int32_t* sink,
+                     void* stream)
+{
+    if (!operands || !sink) return PQ_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(operands) & 31u) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return PQ_ERR_ALIGN;
+    if (operand_bytes < 32 || (operand_bytes % 32) != 0 || operand_bytes > ((int64_t)1 << 34) || iters < 0 || iters > (1 << 24) ||
+        workgroups < 1 || workgroups > (1 << 20))
+        return PQ_ERR_SHAPE;
+    return pq::launch_probe_mfma_f6(operands, operand_bytes, iters, workgroups, sink, static_cast<hipStream_t>(stream));
+}
+
+int pq_probe_f6_product(const int8_t* a_codes, const int8_t* b_codes, int64_t K, int32_t* out_i32, void* stream)
+{
+    if (!a_codes || !b_codes || !out_i32) return PQ_ERR_NULL;
+    if (!aligned16(a_codes) || !aligned16(b_codes) || !aligned16(out_i32)) return PQ_ERR_ALIGN;
+    if (K < 64 || (K % 64) != 0 || K > 262080) return PQ_ERR_SHAPE;    // |sum| <= 64 K < 2^24: exact in fp32
+    return pq::launch_probe_f6_product(a_codes, b_codes, K, out_i32, static_cast<hipStream_t>(stream));
+}
+
 int pq_probe_stream_read(const void* src, int64_t bytes, int32_t* sink, void* stream)
 {
     if (!src || !sink) return PQ_ERR_NULL;

@@ -59,6 +59,9 @@ int launch_gemm_mfma_ws(const void* xq, const void* wq, const float* sw, float s
 int launch_probe_mfma(const void* operands, int64_t operand_bytes, int64_t iters, int32_t workgroups, int32_t* sink,
                       hipStream_t st);
 int launch_probe_read(const void* src, int64_t bytes, int32_t* sink, hipStream_t st);
+int launch_probe_mfma_f6(const void* operands, int64_t operand_bytes, int64_t iters, int32_t workgroups, int32_t* sink,
+                         hipStream_t st);
+int launch_probe_f6_product(const int8_t* a, const int8_t* b, int64_t K, int32_t* out, hipStream_t st);
 
 bool stream_mfma_supported(int64_t M, int64_t N, int64_t K, int32_t abits = 4);
 int stream_mfma_launches(int64_t M, int64_t N, int64_t K, int32_t abits = 4);   // for a supported shape

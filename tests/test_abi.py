@@ -137,6 +137,22 @@ def test_argument_errors_launch_nothing(b):
         L.pq_set_gemm_variant(prev)
 
 
+def test_argument_errors_of_the_f6_probes(b):
+    L = b.lib()
+    p = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1008)
+    nul = ctypes.c_void_p(0)
+    assert L.pq_probe_f6_product(nul, p, 64, p, nul) == b.PQ_ERR_NULL
+    assert L.pq_probe_f6_product(p, p, 64, nul, nul) == b.PQ_ERR_NULL
+    assert L.pq_probe_f6_product(odd, p, 64, p, nul) == b.PQ_ERR_ALIGN
+    assert L.pq_probe_f6_product(p, p, 96, p, nul) == b.PQ_ERR_SHAPE          # K % 64
+    assert L.pq_probe_f6_product(p, p, 262144, p, nul) == b.PQ_ERR_SHAPE      # sums could pass 2^24
+    assert L.pq_probe_mfma_f6(nul, 64, 1, 1, p, nul) == b.PQ_ERR_NULL
+    assert L.pq_probe_mfma_f6(ctypes.c_void_p(0x1010), 64, 1, 1, p, nul) == b.PQ_ERR_ALIGN    # 32 bytes
+    assert L.pq_probe_mfma_f6(p, 48, 1, 1, p, nul) == b.PQ_ERR_SHAPE
+    assert L.pq_probe_mfma_f6(p, 64, 1, 0, p, nul) == b.PQ_ERR_SHAPE
+
+
 def test_argument_errors_of_the_widened_calls(b):
     L = b.lib()
     p = ctypes.c_void_p(0x1000)          # never dereferenced: each call fails validation first
