@@ -177,9 +177,30 @@ def run_variants(torch, pq, layers, steps, warmup, ops):
             pq.pq_rotate_quant(L["x"], L["h"], L["sx"], out=L["xq"])
             pq.pq_w4a4_gemm(L["xq"], L["wq"], L["sw"], L["sx"], out=L["out"])
 
+    # the same static W4A4 step with the product on the 6-bit floating-point matrix instruction: weights
+    # repacked once (offline), activations repacked after the quantizer (one more small launch per linear)
+    for L in layers:
+        L["w6"] = pq.pq_repack_f6(L["wq"])
+        L["x6"] = pq.pq_repack_f6(L["xq"])
+
+    def f6_static():
+        for L in layers:
+            pq.pq_rotate_quant(L["x"], L["h"], L["sx"], out=L["xq"])
+            pq.pq_repack_f6(L["xq"], out=L["x6"])
+            pq.pq_w4a4_gemm_f6(L["x6"], L["w6"], L["sw"], L["sx"], M, L["N"], L["K"], out=L["out"])
+
+    def f6_products_only():
+        for L in layers:
+            pq.pq_w4a4_gemm_f6(L["x6"], L["w6"], L["sw"], L["sx"], M, L["N"], L["K"], out=L["out"])
+
+    def int8_products_only():
+        for L in layers:
+            pq.pq_w4a4_gemm(L["xq"], L["wq"], L["sw"], L["sx"], out=L["out"])
+
     res = {}
     for name, step in (("w4a8_static", w4a8_static), ("w4a4_dynamic", dynamic(4)), ("w4a8_dynamic", dynamic(8)),
-                       ("w4a4_static_gate_up_one_matrix", gate_up_one_matrix)):
+                       ("w4a4_static_gate_up_one_matrix", gate_up_one_matrix), ("w4a4_static_f6", f6_static),
+                       ("w4a4_products_only_f6", f6_products_only), ("w4a4_products_only_int8", int8_products_only)):
         device_warmup(torch)
         for _ in range(warmup):
             step()
@@ -191,7 +212,7 @@ def run_variants(torch, pq, layers, steps, warmup, ops):
         dt = (time.perf_counter() - t0) / steps
         res[name] = {"ms_per_step": round(dt * 1e3, 4), "TOPS": round(ops / dt / 1e12, 1)}
     for L in layers:
-        del L["xq8"], L["srow"]
+        del L["xq8"], L["srow"], L["w6"], L["x6"]
     return res
 
 

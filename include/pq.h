@@ -153,6 +153,27 @@ int pq_probe_mfma_f6(const void* operands, int64_t operand_bytes, int64_t iters,
 int pq_probe_f6_product(const int8_t* a_codes, const int8_t* b_codes, int64_t K, int32_t* out_i32,
                         void* stream);
 
+/* ---- the same product on the 6-bit floating-point matrix instruction (prefill) ----------------
+ * (Sec. 3, low-bit matrix multiplication.)  Every code of Eq. 1 is exact as a 6-bit float with 3
+ * exponent and 2 mantissa bits, products and sums below 2^24 are exact in fp32: for K <= 262080 the
+ * accumulators are the integer sums of pq_w4a4_gemm, bit for bit, and so are the outputs.  The
+ * instruction has twice the nominal rate of the INT8 one.  Both operands are repacked first:
+ * pq_repack_f6: codes_packed [rows,K/2] uint8 canonical -> `tiles`, pq_f6_tiles_bytes(rows,K) bytes:
+ *   for every block of 32 rows and every 128 channels 64 lanes x 48 bytes: per lane the register image
+ *   of the first 64 channels (24 bytes), then that of the second; an image of lane l holds row
+ *   32 rb + l % 32 and channels 64 ks + 32 (l / 32) + 0..31 as a little-endian stream of 6-bit values
+ *   (rows past the end are zero); blocks ordered [rb][128-channel group].  K % 128 == 0, K <= 262080,
+ *   the tiles under 4 GiB (else PQ_ERR_SHAPE / PQ_ERR_UNSUPPORTED).  Weights are repacked once,
+ *   offline; activations after pq_rotate_quant.
+ * pq_w4a4_gemm_f6: x_tiles, w_tiles as written by pq_repack_f6 for [M,K] and [N,K]; everything else
+ *   as pq_w4a4_gemm.
+ */
+size_t pq_f6_tiles_bytes(int64_t rows, int64_t K);
+int pq_repack_f6(const void* codes_packed, int64_t rows, int64_t K, void* tiles, void* stream);
+int pq_w4a4_gemm_f6(const void* x_tiles, const void* w_tiles, const float* w_scale,
+                    float act_scale, int64_t M, int64_t N, int64_t K,
+                    void* out_f16, int32_t* acc_i32, void* stream);
+
 /* Force a kernel variant of pq_w4a4_gemm for sweeps and tests (host, process-wide,
  * not thread-safe): 0 = automatic, 1 = weight-streaming matrix tiles (M <= 32, K % 256 == 0 and
  * the codes of 8 tokens fit in LDS; else PQ_ERR_UNSUPPORTED), 2 = MFMA tiled, 3 = simple,

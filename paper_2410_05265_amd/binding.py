@@ -35,6 +35,9 @@ SIGNATURES = {
     "pq_probe_mfma_i8": (ctypes.c_int, [_vp, _i64, _i64, _i32, _vp, _vp]),
     "pq_probe_stream_read": (ctypes.c_int, [_vp, _i64, _vp, _vp]),
     "pq_probe_mfma_f6": (ctypes.c_int, [_vp, _i64, _i64, _i32, _vp, _vp]),
+    "pq_f6_tiles_bytes": (_sz, [_i64, _i64]),
+    "pq_repack_f6": (ctypes.c_int, [_vp, _i64, _i64, _vp, _vp]),
+    "pq_w4a4_gemm_f6": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i64, _i64, _i64, _vp, _vp, _vp]),
     "pq_probe_f6_product": (ctypes.c_int, [_vp, _vp, _i64, _vp, _vp]),
     "pq_rotate_quant8": (ctypes.c_int, [_vp, _i64, _i64, _i32, _f32, _vp, _vp]),
     "pq_w4a8_gemm": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i64, _i64, _i64, _vp, _vp, _vp]),
@@ -495,6 +498,37 @@ def pq_probe_mfma_i8(operands: torch.Tensor, iters: int, workgroups: int, sink: 
     _check(lib().pq_probe_mfma_i8(_ptr(operands), operands.numel() * operands.element_size(), int(iters), int(workgroups),
                                   _ptr(sink), _stream()), "pq_probe_mfma_i8")
     return float(workgroups) * 4 * iters * 16 * 65536
+
+
+def pq_f6_tiles_bytes(rows: int, K: int) -> int:
+    return int(lib().pq_f6_tiles_bytes(rows, K))
+
+
+def pq_repack_f6(codes: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    """packed codes uint8 [rows,K/2] -> register images of the 6-bit matrix instruction (uint8, flat)."""
+    _dev(codes, torch.uint8, "codes")
+    rows, K = codes.shape[0], codes.shape[1] * 2
+    if out is None:
+        out = torch.empty((max(pq_f6_tiles_bytes(rows, K), 16),), dtype=torch.uint8, device=codes.device)
+    _check(lib().pq_repack_f6(_ptr(codes), rows, K, _ptr(out), _stream()), "pq_repack_f6")
+    return out
+
+
+def pq_w4a4_gemm_f6(x_tiles, w_tiles, w_scale, act_scale, M: int, N: int, K: int, want_out=True, want_acc=False,
+                    out=None, acc=None):
+    """tiles of [M,K] x tiles of [N,K] -> (out fp16 [M,N] | None, acc int32 [M,N] | None)."""
+    _dev(x_tiles, torch.uint8, "x_tiles")
+    _dev(w_tiles, torch.uint8, "w_tiles")
+    _dev(w_scale, torch.float32, "w_scale")
+    if (M > 0 and x_tiles.numel() < pq_f6_tiles_bytes(M, K)) or w_tiles.numel() < pq_f6_tiles_bytes(N, K) or w_scale.numel() != N:
+        raise ValueError("shape mismatch")
+    if want_out and out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=x_tiles.device)
+    if want_acc and acc is None:
+        acc = torch.empty((M, N), dtype=torch.int32, device=x_tiles.device)
+    _check(lib().pq_w4a4_gemm_f6(_ptr(x_tiles), _ptr(w_tiles), _ptr(w_scale), float(act_scale), M, N, K, _ptr(out),
+                                 _ptr(acc), _stream()), "pq_w4a4_gemm_f6")
+    return out, acc
 
 
 def pq_probe_mfma_f6(operands: torch.Tensor, iters: int, workgroups: int, sink: torch.Tensor) -> float:

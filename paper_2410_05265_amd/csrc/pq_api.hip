@@ -547,6 +547,36 @@ int pq_probe_f6_product(const int8_t* a_codes, const int8_t* b_codes, int64_t K,
     return pq::launch_probe_f6_product(a_codes, b_codes, K, out_i32, static_cast<hipStream_t>(stream));
 }
 
+size_t pq_f6_tiles_bytes(int64_t rows, int64_t K)
+{
+    if (rows <= 0 || K <= 0 || (K % 128) != 0) return 0;
+    return pq::f6_tiles_bytes(rows, K);
+}
+
+int pq_repack_f6(const void* codes_packed, int64_t rows, int64_t K, void* tiles, void* stream)
+{
+    if (rows < 0 || K <= 0 || (K % 128) != 0) return PQ_ERR_SHAPE;
+    if (!codes_packed || !tiles) return PQ_ERR_NULL;
+    if (!aligned16(codes_packed) || !aligned16(tiles)) return PQ_ERR_ALIGN;
+    if (rows == 0) return PQ_OK;
+    if (K > 262080 || pq::f6_tiles_bytes(rows, K) >= ((size_t)1 << 32)) return PQ_ERR_UNSUPPORTED;
+    return pq::launch_repack_f6(codes_packed, rows, K, tiles, static_cast<hipStream_t>(stream));
+}
+
+int pq_w4a4_gemm_f6(const void* x_tiles, const void* w_tiles, const float* w_scale, float act_scale, int64_t M,
+                    int64_t N, int64_t K, void* out_f16, int32_t* acc_i32, void* stream)
+{
+    int rc = check_gemm(x_tiles, w_tiles, w_scale, act_scale, M, N, K, out_f16, acc_i32);
+    if (rc != PQ_OK) return rc;
+    if ((K % 128) != 0) return PQ_ERR_SHAPE;
+    if (M == 0) return PQ_OK;
+    if (K > 262080 || M > (1 << 30) || N > (1 << 30) || pq::f6_tiles_bytes(M, K) >= ((size_t)1 << 32) ||
+        pq::f6_tiles_bytes(N, K) >= ((size_t)1 << 32))
+        return PQ_ERR_UNSUPPORTED;
+    return pq::launch_gemm_f6(x_tiles, w_tiles, w_scale, act_scale, M, N, K, out_f16, acc_i32,
+                              static_cast<hipStream_t>(stream));
+}
+
 int pq_probe_stream_read(const void* src, int64_t bytes, int32_t* sink, void* stream)
 {
     if (!src || !sink) return PQ_ERR_NULL;

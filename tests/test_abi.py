@@ -153,6 +153,30 @@ def test_argument_errors_of_the_f6_probes(b):
     assert L.pq_probe_mfma_f6(p, 64, 1, 0, p, nul) == b.PQ_ERR_SHAPE
 
 
+def test_argument_errors_of_the_f6_product(b):
+    L = b.lib()
+    p = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1008)
+    nul = ctypes.c_void_p(0)
+    assert L.pq_f6_tiles_bytes(32, 128) == 3072 and L.pq_f6_tiles_bytes(33, 256) == 2 * 2 * 3072
+    assert L.pq_f6_tiles_bytes(2048, 4096) == 2048 * 4096 * 3 // 4
+    assert L.pq_f6_tiles_bytes(32, 64) == 0 and L.pq_f6_tiles_bytes(0, 128) == 0
+    rp = L.pq_repack_f6
+    assert rp(nul, 32, 128, p, nul) == b.PQ_ERR_NULL and rp(p, 32, 128, nul, nul) == b.PQ_ERR_NULL
+    assert rp(p, 32, 64, p, nul) == b.PQ_ERR_SHAPE and rp(p, -1, 128, p, nul) == b.PQ_ERR_SHAPE
+    assert rp(odd, 32, 128, p, nul) == b.PQ_ERR_ALIGN
+    assert rp(p, 0, 128, p, nul) == b.PQ_OK
+    assert rp(p, 32, 262144, p, nul) == b.PQ_ERR_UNSUPPORTED         # sums could pass 2^24
+    g = L.pq_w4a4_gemm_f6
+    assert g(nul, p, p, 0.1, 32, 16, 128, p, nul, nul) == b.PQ_ERR_NULL
+    assert g(p, p, p, 0.1, 32, 16, 128, nul, nul, nul) == b.PQ_ERR_NULL
+    assert g(p, p, p, 0.1, 32, 16, 160, p, nul, nul) == b.PQ_ERR_SHAPE       # K % 128
+    assert g(p, p, p, 0.1, 32, 20, 128, p, nul, nul) == b.PQ_ERR_SHAPE       # N % 16
+    assert g(p, odd, p, 0.1, 32, 16, 128, p, nul, nul) == b.PQ_ERR_ALIGN
+    assert g(p, p, p, float("nan"), 32, 16, 128, p, nul, nul) == b.PQ_ERR_SCALE
+    assert g(p, p, p, 0.1, 0, 16, 128, p, nul, nul) == b.PQ_OK
+
+
 def test_argument_errors_of_the_widened_calls(b):
     L = b.lib()
     p = ctypes.c_void_p(0x1000)          # never dereferenced: each call fails validation first
