@@ -27,13 +27,14 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 constexpr int kImage = 24, kStep = 64 * kImage, kChunkF6 = 2 * kStep;   // 1536 B per (row block, step); 3072 per stage
 constexpr int kRing = 3;                                                 // stages in LDS
 
-__device__ __forceinline__ uint32_t e3m2_of_nibble(uint32_t nib)   // two's complement nibble -> E3M2 (bias 3)
+// two's complement nibble -> E3M2 (bias 3): two tables of eight 6-bit entries, for 0..7 and for -8..-1
+__device__ __forceinline__ uint32_t e3m2_of_nibble(uint32_t nib)
 {
-    const int c = (int)(nib << 28) >> 28;
-    const uint32_t m = (uint32_t)(c < 0 ? -c : c);
-    if (m == 0) return 0;
-    const uint32_t e = 31u - (uint32_t)__builtin_clz(m);
-    return (c < 0 ? 32u : 0u) | ((e + 3u) << 2) | (((m << 2) >> e) & 3u);
+    constexpr uint64_t pos = 0ull | (12ull << 6) | (16ull << 12) | (18ull << 18) | (20ull << 24) | (21ull << 30) | (22ull << 36) |
+                             (23ull << 42);                                            // 0, 1, ..., 7
+    constexpr uint64_t neg = 56ull | (55ull << 6) | (54ull << 12) | (53ull << 18) | (52ull << 24) | (50ull << 30) |
+                             (48ull << 36) | (44ull << 42);                            // -8, -7, ..., -1
+    return (uint32_t)(((nib & 8u) ? neg : pos) >> (6u * (nib & 7u))) & 63u;
 }
 
 // One thread per register image: 32 codes (16 bytes of nibbles) of one row -> 24 bytes.
