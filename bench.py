@@ -189,6 +189,13 @@ def run_variants(torch, pq, layers, steps, warmup, ops):
             pq.pq_repack_f6(L["xq"], out=L["x6"])
             pq.pq_w4a4_gemm_f6(L["x6"], L["w6"], L["sw"], L["sx"], M, L["N"], L["K"], out=L["out"])
 
+    for L in layers:
+        L["work6"] = torch.empty((pq.pq_linear_f6_workspace_bytes(M, L["K"]),), dtype=torch.uint8, device="cuda")
+
+    def f6_linear():      # the layer's prepacked twin: without rotation the quantizer writes the tiles itself
+        for L in layers:
+            pq.pq_linear_f6(L["x"], L["w6"], L["sw"], L["sx"], L["h"], out=L["out"], workspace=L["work6"])
+
     def f6_products_only():
         for L in layers:
             pq.pq_w4a4_gemm_f6(L["x6"], L["w6"], L["sw"], L["sx"], M, L["N"], L["K"], out=L["out"])
@@ -199,7 +206,7 @@ def run_variants(torch, pq, layers, steps, warmup, ops):
 
     res = {}
     for name, step in (("w4a8_static", w4a8_static), ("w4a4_dynamic", dynamic(4)), ("w4a8_dynamic", dynamic(8)),
-                       ("w4a4_static_gate_up_one_matrix", gate_up_one_matrix), ("w4a4_static_f6", f6_static),
+                       ("w4a4_static_gate_up_one_matrix", gate_up_one_matrix), ("w4a4_static_f6", f6_static), ("w4a4_static_f6_linear", f6_linear),
                        ("w4a4_products_only_f6", f6_products_only), ("w4a4_products_only_int8", int8_products_only)):
         device_warmup(torch)
         for _ in range(warmup):
@@ -212,7 +219,7 @@ def run_variants(torch, pq, layers, steps, warmup, ops):
         dt = (time.perf_counter() - t0) / steps
         res[name] = {"ms_per_step": round(dt * 1e3, 4), "TOPS": round(ops / dt / 1e12, 1)}
     for L in layers:
-        del L["xq8"], L["srow"], L["w6"], L["x6"]
+        del L["xq8"], L["srow"], L["w6"], L["x6"], L["work6"]
     return res
 
 

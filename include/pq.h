@@ -174,6 +174,20 @@ int pq_w4a4_gemm_f6(const void* x_tiles, const void* w_tiles, const float* w_sca
                     float act_scale, int64_t M, int64_t N, int64_t K,
                     void* out_f16, int32_t* acc_i32, void* stream);
 
+/* The whole layer on that instruction, for weights repacked beforehand (the prepacked twin of
+ * pq_linear): rotate + quantize, f6 tiles of the codes, pq_w4a4_gemm_f6, on one stream.  Without
+ * rotation (had_block <= 1) the quantizer writes the tiles itself (two launches in all); with
+ * rotation pq_rotate_quant is followed by pq_repack_f6 (three).  The codes are those of
+ * pq_rotate_quant bit for bit, the outputs those of pq_linear.
+ * workspace: device memory, 256-byte aligned, pq_linear_f6_workspace_bytes(M,K) bytes; on return it
+ * holds the tiles (pq_f6_tiles_bytes(M,K), rounded up to 256) and behind them the canonical packed
+ * codes [M,K/2].  K % 128 == 0; limits as pq_repack_f6 and pq_rotate_quant.
+ */
+size_t pq_linear_f6_workspace_bytes(int64_t M, int64_t K);
+int pq_linear_f6(const void* x_f16, const void* w_tiles, const float* w_scale,
+                 float act_scale, int32_t had_block, int64_t M, int64_t N, int64_t K,
+                 void* out_f16, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Force a kernel variant of pq_w4a4_gemm for sweeps and tests (host, process-wide,
  * not thread-safe): 0 = automatic, 1 = weight-streaming matrix tiles (M <= 32, K % 256 == 0 and
  * the codes of 8 tokens fit in LDS; else PQ_ERR_UNSUPPORTED), 2 = MFMA tiled, 3 = simple,

@@ -38,6 +38,8 @@ SIGNATURES = {
     "pq_f6_tiles_bytes": (_sz, [_i64, _i64]),
     "pq_repack_f6": (ctypes.c_int, [_vp, _i64, _i64, _vp, _vp]),
     "pq_w4a4_gemm_f6": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i64, _i64, _i64, _vp, _vp, _vp]),
+    "pq_linear_f6_workspace_bytes": (_sz, [_i64, _i64]),
+    "pq_linear_f6": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i32, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
     "pq_probe_f6_product": (ctypes.c_int, [_vp, _vp, _i64, _vp, _vp]),
     "pq_rotate_quant8": (ctypes.c_int, [_vp, _i64, _i64, _i32, _f32, _vp, _vp]),
     "pq_w4a8_gemm": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i64, _i64, _i64, _vp, _vp, _vp]),
@@ -529,6 +531,30 @@ def pq_w4a4_gemm_f6(x_tiles, w_tiles, w_scale, act_scale, M: int, N: int, K: int
     _check(lib().pq_w4a4_gemm_f6(_ptr(x_tiles), _ptr(w_tiles), _ptr(w_scale), float(act_scale), M, N, K, _ptr(out),
                                  _ptr(acc), _stream()), "pq_w4a4_gemm_f6")
     return out, acc
+
+
+def pq_linear_f6_workspace_bytes(M: int, K: int) -> int:
+    return int(lib().pq_linear_f6_workspace_bytes(M, K))
+
+
+def pq_linear_f6(x, w_tiles, w_scale, act_scale, had_block, out=None, workspace=None):
+    """The whole layer with prepacked weights (pq_repack_f6).  Returns (out fp16 [M,N], workspace uint8:
+    the activation tiles, then the canonical packed codes)."""
+    _dev(x, torch.float16, "x")
+    _dev(w_tiles, torch.uint8, "w_tiles")
+    _dev(w_scale, torch.float32, "w_scale")
+    M, K = x.shape
+    N = w_scale.numel()
+    if w_tiles.numel() < pq_f6_tiles_bytes(N, K):
+        raise ValueError("shape mismatch")
+    need = pq_linear_f6_workspace_bytes(M, K)
+    if workspace is None:
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=x.device)
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    _check(lib().pq_linear_f6(_ptr(x), _ptr(w_tiles), _ptr(w_scale), float(act_scale), int(had_block), M, N, K, _ptr(out),
+                              _ptr(workspace), workspace.numel(), _stream()), "pq_linear_f6")
+    return out, workspace
 
 
 def pq_probe_mfma_f6(operands: torch.Tensor, iters: int, workgroups: int, sink: torch.Tensor) -> float:

@@ -16,6 +16,7 @@
 #include <stdlib.h>
 
 #include "pq_internal.h"
+#include "pq_rotate.h"
 
 namespace pq {
 namespace {
@@ -57,6 +58,54 @@ __global__ __launch_bounds__(256) void k_repack_f6(const uint8_t* __restrict__ c
             const int bit = 6 * i;
             w[bit / 64] |= e << (bit % 64);
             if (bit % 64 > 58) w[bit / 64 + 1] |= e >> (64 - bit % 64);
+        }
+    }
+    uint64_t* o = reinterpret_cast<uint64_t*>(out + ((int64_t)rb * (KS >> 1) + (ks >> 1)) * kChunkF6 + lane * 48 + (ks & 1) * kImage);
+    o[0] = w[0]; o[1] = w[1]; o[2] = w[2];
+}
+
+// Quantizer for unrotated input that writes f6 tiles directly (one launch instead of quantizer + repack):
+// one thread per register image, i.e. 32 consecutive channels of one token: four times the exact-tie
+// quantizer of the nibble path (the same codes bit for bit), then the same conversion as k_repack_f6.
+// Optionally also stores the canonical nibbles (the layer's workspace contract).
+__global__ __launch_bounds__(256) void k_quant_f6(const __half* __restrict__ x, int R, int K, int64_t images, float mult,
+                                                 float step, uint8_t* __restrict__ out, uint8_t* __restrict__ nibbles)
+{
+    const int64_t t0 = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t t = t0 < images ? t0 : images - 1;     // every lane runs the quantizer (it votes across the wavefront)
+    const int KS = K >> 6, lane = (int)(t & 63);
+    const int64_t blk = t >> 6;
+    const int ks = (int)(blk % KS), rb = (int)(blk / KS);
+    const int row = rb * 32 + (lane & 31), k0 = ks * 64 + (lane >> 5) * 32;
+    const bool live = row < R;
+    const __half* src = x + (int64_t)(live ? row : 0) * K + k0;
+    uint32_t d[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const v4i raw = *reinterpret_cast<const v4i*>(src + 8 * c);
+        const __half2* h2 = reinterpret_cast<const __half2*>(&raw);
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float2 f = __half22float2(h2[i]);
+            v[2 * i] = f.x;
+            v[2 * i + 1] = f.y;
+        }
+        d[c] = rq::quant_pack8<true>(v, v, mult, step, 0);
+    }
+    if (t0 >= images) return;
+    uint64_t w[3] = {0, 0, 0};
+    if (live) {
+#pragma unroll
+        for (int i = 0; i < 32; ++i) {
+            const uint64_t e = e3m2_of_nibble((d[i >> 3] >> (4 * (i & 7))) & 15u);
+            const int bit = 6 * i;
+            w[bit / 64] |= e << (bit % 64);
+            if (bit % 64 > 58) w[bit / 64 + 1] |= e >> (64 - bit % 64);
+        }
+        if (nibbles) {
+            const v4i nb = {(int)d[0], (int)d[1], (int)d[2], (int)d[3]};
+            *reinterpret_cast<v4i*>(nibbles + (int64_t)row * (K >> 1) + (k0 >> 1)) = nb;
         }
     }
     uint64_t* o = reinterpret_cast<uint64_t*>(out + ((int64_t)rb * (KS >> 1) + (ks >> 1)) * kChunkF6 + lane * 48 + (ks & 1) * kImage);
@@ -270,6 +319,15 @@ __global__ __launch_bounds__(256) void k_gemm_f6(const uint8_t* __restrict__ x6,
 }  // namespace
 
 size_t f6_tiles_bytes(int64_t R, int64_t K) { return (size_t)((R + 31) / 32) * (size_t)(K / 64) * kStep; }
+
+int launch_quant_f6(const void* x, int64_t R, int64_t K, float act_scale, void* out, void* nibbles, hipStream_t st)
+{
+    const int64_t images = ((R + 31) / 32) * (K / 64) * 64;
+    hipLaunchKernelGGL(k_quant_f6, dim3((unsigned)((images + 255) / 256)), dim3(256), 0, st, static_cast<const __half*>(x),
+                       (int)R, (int)K, images, (float)(1.0 / (double)act_scale), act_scale, static_cast<uint8_t*>(out),
+                       static_cast<uint8_t*>(nibbles));
+    return hip_status(hipGetLastError());
+}
 
 int launch_repack_f6(const void* codes, int64_t R, int64_t K, void* out, hipStream_t st)
 {

@@ -167,6 +167,18 @@ def test_argument_errors_of_the_f6_product(b):
     assert rp(odd, 32, 128, p, nul) == b.PQ_ERR_ALIGN
     assert rp(p, 0, 128, p, nul) == b.PQ_OK
     assert rp(p, 32, 262144, p, nul) == b.PQ_ERR_UNSUPPORTED         # sums could pass 2^24
+    assert L.pq_linear_f6_workspace_bytes(2048, 4096) == 2048 * 4096 * 3 // 4 + 2048 * 2048
+    assert L.pq_linear_f6_workspace_bytes(3, 128) == 3072 + 256 and L.pq_linear_f6_workspace_bytes(3, 96) == 0
+    lf = L.pq_linear_f6
+    p256 = ctypes.c_void_p(0x10000)
+    assert lf(p, p, p, 0.1, 1, 32, 16, 128, p, nul, 0, nul) == b.PQ_ERR_WORKSPACE
+    assert lf(p, p, p, 0.1, 1, 32, 16, 128, p, p256, 100, nul) == b.PQ_ERR_WORKSPACE
+    assert lf(p, p, p, 0.1, 1, 32, 16, 128, p, odd, 1 << 20, nul) == b.PQ_ERR_ALIGN
+    assert lf(nul, p, p, 0.1, 1, 32, 16, 128, p, p256, 1 << 20, nul) == b.PQ_ERR_NULL
+    assert lf(p, p, p, 0.1, 96, 32, 16, 128, p, p256, 1 << 20, nul) == b.PQ_ERR_SHAPE
+    assert lf(p, p, p, 0.1, 1, 32, 16, 64, p, p256, 1 << 20, nul) == b.PQ_ERR_SHAPE
+    assert lf(p, p, p, -1.0, 1, 32, 16, 128, p, p256, 1 << 20, nul) == b.PQ_ERR_SCALE
+    assert lf(p, p, p, 0.1, 1, 0, 16, 128, p, nul, 0, nul) == b.PQ_OK
     g = L.pq_w4a4_gemm_f6
     assert g(nul, p, p, 0.1, 32, 16, 128, p, nul, nul) == b.PQ_ERR_NULL
     assert g(p, p, p, 0.1, 32, 16, 128, nul, nul, nul) == b.PQ_ERR_NULL

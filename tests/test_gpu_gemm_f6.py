@@ -135,3 +135,49 @@ def test_argument_errors(pq):
         pq.pq_w4a4_gemm_f6(x6, w6, sw, 0.0, 32, 16, 128)
     with pytest.raises(pq.PQError, match="PQ_ERR_NULL"):
         pq.pq_w4a4_gemm_f6(x6, w6, sw, 0.1, 32, 16, 128, want_out=False, want_acc=False)
+
+
+@pytest.mark.parametrize("M,K,N,h", [(300, 1152, 400, 1), (2048, 4096, 512, 1), (33, 128, 16, 0), (70, 14336, 512, 128),
+                                     (256, 4096, 1024, 4096), (1, 256, 64, 1)])
+def test_layer_with_prepacked_weights(pq, M, K, N, h):
+    """pq_linear_f6 against pq_linear: the same codes and the same outputs bit for bit; the tiles it leaves are
+    the repacked codes; and (through pq_linear's own parity) the oracle."""
+    x = synth.activations(M, K, seed=M + K)
+    wq = synth.random_packed(N, K, seed=N + K, stream=7)
+    sw = synth.random_scales(N, seed=N)
+    sx = 0.213
+    ref, ref_ws = pq.pq_linear(dev(x), dev(wq), dev(sw), sx, h)
+    w6 = pq.pq_repack_f6(dev(wq))
+    out, ws = pq.pq_linear_f6(dev(x), w6, dev(sw), sx, h)
+    assert np.array_equal(host(out).view(np.uint16), host(ref).view(np.uint16))
+    tiles_bytes = pq.pq_f6_tiles_bytes(M, K)
+    off = (tiles_bytes + 255) // 256 * 256
+    codes = host(ws)[off:off + M * K // 2].reshape(M, K // 2)
+    assert np.array_equal(codes, host(ref_ws)[:M * K // 2].reshape(M, K // 2))
+    assert np.array_equal(host(ws)[:tiles_bytes], tiles_by_definition(O.unpack(codes)))
+    acc_ref = O.gemm_i64(O.unpack(codes), O.unpack(wq))
+    assert ulp_diff(host(out), O.epilogue(acc_ref, np.float32(sx), sw)).max() <= 1
+
+
+def test_unrotated_quantizer_to_tiles_is_exact_for_every_fp16_value(pq):
+    """The fused quantizer of pq_linear_f6 (no rotation) on all finite fp16 values and on constructed ties:
+    the codes beside the tiles equal the oracle's."""
+    v = np.arange(65536, dtype=np.uint32).astype(np.uint16).view(np.float16)
+    x = v[np.isfinite(v)].reshape(31, 2048)
+    wq = synth.random_packed(16, 2048, seed=1, stream=7)
+    sw = synth.random_scales(16, seed=2)
+    w6 = pq.pq_repack_f6(dev(wq))
+    for s in (0.25, 1.0 / 3.0, 0.0123, 41.0):
+        _, ws = pq.pq_linear_f6(dev(x), w6, dev(sw), s, 1)
+        off = (pq.pq_f6_tiles_bytes(31, 2048) + 255) // 256 * 256
+        codes = O.unpack(host(ws)[off:off + 31 * 1024].reshape(31, 1024))
+        assert np.array_equal(codes, O.quantize(x, np.float32(s))), s
+    rng = np.random.default_rng(17)
+    s = np.float32(0.0371)
+    k = rng.integers(-10, 10, size=(8, 1024)).astype(np.float64)
+    xt = ((k + 0.5) * np.float64(s)).astype(np.float16)
+    w6 = pq.pq_repack_f6(dev(synth.random_packed(16, 1024, seed=3, stream=7)))
+    _, ws = pq.pq_linear_f6(dev(xt), w6, dev(sw), float(s), 0)
+    off = (pq.pq_f6_tiles_bytes(8, 1024) + 255) // 256 * 256
+    codes = O.unpack(host(ws)[off:off + 8 * 512].reshape(8, 512))
+    assert np.array_equal(codes, O.quantize(xt, s))
