@@ -652,6 +652,13 @@ def main():
         leg("prefill_8192", lambda: run_prefill_8192(torch, pq, layers))
         leg("side_rows", lambda: run_side_rows(torch, pq, synth, M_PREFILL))
         leg("variants", variants_leg)
+    v6 = result.get("variants", {}).get("w4a4_static_f6_linear") if isinstance(result.get("variants"), dict) else None
+    if isinstance(v6, dict) and "ms_per_step" in v6:
+        # the same step through the optional prepacked path (product on the 6-bit matrix instruction, exact):
+        # not the headline, whose roofline, counters and profiles are the INT8 kernel's
+        result["prepacked_f6_path"] = {"ms_per_step": v6["ms_per_step"], "TOPS": v6["TOPS"],
+                                       "over_headline": round(result["ms_per_step"] / v6["ms_per_step"], 3),
+                                       "speedup_vs_fp16": round(result["fp16_gemm"]["ms_per_step"] / v6["ms_per_step"], 3)}
     if not args.no_decode and not args.serving_only:
         leg("decode", decode_leg)
     if args.serving_only or not (args.no_decode or args.no_variants):
