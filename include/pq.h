@@ -166,7 +166,8 @@ int pq_probe_f6_product(const int8_t* a_codes, const int8_t* b_codes, int64_t K,
  *   the tiles under 4 GiB (else PQ_ERR_SHAPE / PQ_ERR_UNSUPPORTED).  Weights are repacked once,
  *   offline; activations after pq_rotate_quant.
  * pq_w4a4_gemm_f6: x_tiles, w_tiles as written by pq_repack_f6 for [M,K] and [N,K]; everything else
- *   as pq_w4a4_gemm.
+ *   as pq_w4a4_gemm.  (The environment variable PQ_GEMM_F6_TILE = 2, 3 or 4 forces tiles of 128
+ *   channels, the mix of 256 and 192 where N allows it, or 256; sweeps and tests only.)
  */
 size_t pq_f6_tiles_bytes(int64_t rows, int64_t K);
 int pq_repack_f6(const void* codes_packed, int64_t rows, int64_t K, void* tiles, void* stream);

@@ -125,20 +125,20 @@ __device__ __forceinline__ int xcd_run(int b, int total)   // each XCD takes a c
 // CI x 4 matrix tiles.  The weights are the first operand: a lane ends with one token (l % 32) and, per
 // matrix tile, the channels 8 (v / 4) + 4 (l / 32) + v % 4 in register v.
 template <int CI>
-__global__ __launch_bounds__(256) void k_gemm_f6(const uint8_t* __restrict__ x6, const uint8_t* __restrict__ w6,
-                                                const float* __restrict__ sw, float sx, int M, int N, int K,
-                                                int GM, __half* __restrict__ out, int32_t* __restrict__ acc_out)
+__device__ __forceinline__ void f6_tile(const uint8_t* __restrict__ x6, const uint8_t* __restrict__ w6,
+                                        const float* __restrict__ sw, float sx, int M, int N, int K, int m0, int n0,
+                                        __half* __restrict__ out, int32_t* __restrict__ acc_out)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wr = wave >> 1, wc = wave & 1;
-    const int tile = xcd_run(blockIdx.x, gridDim.x);
     constexpr int kWB = 2 * CI;                          // weight row blocks of the tile; 8 token row blocks follow
-    constexpr int kStageF6 = (kWB + 8) * kChunkF6;       // 48 KiB (CI = 4) or 36 KiB
-    constexpr int kLoads = (kWB + 8) * 3 / 4;            // direct loads per wavefront per stage: 12 or 9
+    constexpr int kStageF6 = (kWB + 8) * kChunkF6;       // 48, 42 or 36 KiB
+    constexpr int kPieces = (kWB + 8) * 3;               // 1 KiB pieces of a stage
+    constexpr int kLoads = (kPieces + 3) / 4;            // direct loads per wavefront per stage: 12, 11 or 9 (CI = 3:
+                                                         // 42 pieces, two wavefronts repeat the last one)
     constexpr int NM = 4 * CI;                           // matrix instructions of a step
-    const int m0 = (tile % GM) * 256, n0 = (tile / GM) * (64 * CI);
     const int KS = K >> 6, nk = K >> 7;
     const int RBX = (M + 31) >> 5, RBW = (N + 31) >> 5;
 
@@ -147,7 +147,7 @@ __global__ __launch_bounds__(256) void k_gemm_f6(const uint8_t* __restrict__ x6,
     bool is_w[kLoads];
 #pragma unroll
     for (int t = 0; t < kLoads; ++t) {
-        const int q = wave + 4 * t, chunk = q / 3, part = q % 3;
+        const int q = wave + 4 * t < kPieces ? wave + 4 * t : kPieces - 1, chunk = q / 3, part = q % 3;
         int rb = chunk < kWB ? (n0 >> 5) + chunk : (m0 >> 5) + chunk - kWB;
         const int last = chunk < kWB ? RBW - 1 : RBX - 1;
         rb = rb < last ? rb : last;
@@ -158,7 +158,7 @@ __global__ __launch_bounds__(256) void k_gemm_f6(const uint8_t* __restrict__ x6,
         const int k = kt < nk ? kt : nk - 1;
 #pragma unroll
         for (int t = 0; t < kLoads; ++t) {
-            const int q = wave + 4 * t;
+            const int q = wave + 4 * t < kPieces ? wave + 4 * t : kPieces - 1;
             const uint8_t* src = (is_w[t] ? w6 : x6) + (size_t)goff[t] + (size_t)k * kChunkF6;
             __builtin_amdgcn_global_load_lds(PQ6_GLB(src), PQ6_LDS(smem + buf * kStageF6 + q * 1024), 16, 0, 0);
         }
@@ -213,7 +213,7 @@ __global__ __launch_bounds__(256) void k_gemm_f6(const uint8_t* __restrict__ x6,
             if (refill && n >= D0) {
 #pragma unroll
                 for (int t = (n - D0) * kLoads / DS; t < (n - D0 + 1) * kLoads / DS; ++t) {
-                    const int q = wave + 4 * t;
+                    const int q = wave + 4 * t < kPieces ? wave + 4 * t : kPieces - 1;
                     const int k = refill_kt < nk ? refill_kt : nk - 1;
                     const uint8_t* src = (is_w[t] ? w6 : x6) + (size_t)goff[t] + (size_t)k * kChunkF6;
                     __builtin_amdgcn_global_load_lds(PQ6_GLB(src), PQ6_LDS(smem + refill_buf * kStageF6 + q * 1024), 16, 0, 0);
@@ -316,6 +316,34 @@ __global__ __launch_bounds__(256) void k_gemm_f6(const uint8_t* __restrict__ x6,
     }
 }
 
+template <int CI>
+__global__ __launch_bounds__(256) void k_gemm_f6(const uint8_t* __restrict__ x6, const uint8_t* __restrict__ w6,
+                                                const float* __restrict__ sw, float sx, int M, int N, int K,
+                                                int GM, __half* __restrict__ out, int32_t* __restrict__ acc_out)
+{
+    const int tile = xcd_run(blockIdx.x, gridDim.x);
+    f6_tile<CI>(x6, w6, sw, sx, M, N, K, (tile % GM) * 256, (tile / GM) * (64 * CI), out, acc_out);
+}
+
+// Two tile widths in one launch: the first GM * n1 workgroups take 256-channel tiles of the columns
+// [0, 256 n1), the others 192-channel tiles of the rest.  Workgroups are dispatched in index order, so
+// with GM * n1 = GM * n2 = number of CUs every CU computes one tile of each width and none idles through
+// a partial last round (gate/up: 14336 = 32 x 256 + 32 x 192).
+__global__ __launch_bounds__(256) void k_gemm_f6_dual(const uint8_t* __restrict__ x6, const uint8_t* __restrict__ w6,
+                                                     const float* __restrict__ sw, float sx, int M, int N, int K,
+                                                     int GM, int n1, int n2, __half* __restrict__ out,
+                                                     int32_t* __restrict__ acc_out)
+{
+    const int first = GM * n1;
+    if ((int)blockIdx.x < first) {
+        const int tile = xcd_run(blockIdx.x, first);
+        f6_tile<4>(x6, w6, sw, sx, M, N, K, (tile % GM) * 256, (tile / GM) * 256, out, acc_out);
+    } else {
+        const int tile = xcd_run(blockIdx.x - first, GM * n2);
+        f6_tile<3>(x6, w6, sw, sx, M, N, K, (tile % GM) * 256, n1 * 256 + (tile / GM) * 192, out, acc_out);
+    }
+}
+
 }  // namespace
 
 size_t f6_tiles_bytes(int64_t R, int64_t K) { return (size_t)((R + 31) / 32) * (size_t)(K / 64) * kStep; }
@@ -355,7 +383,8 @@ int launch_f6(const void* x6, const void* w6, const float* sw, float sx, int64_t
 }  // namespace
 
 // 256 channels per tile unless 128 fill the chip better (rounds of 256 tiles; the narrow tile costs
-// about 0.6 of the wide one).  PQ_GEMM_F6_TILE = 2 or 4 forces one (sweeps and tests).
+// about 0.6 of the wide one), or a mix of 256 and 192 in one launch where that saves a partial round.
+// PQ_GEMM_F6_TILE = 2 or 4 forces one width, 3 the mix where N allows one (sweeps and tests).
 int launch_gemm_f6(const void* x6, const void* w6, const float* sw, float sx, int64_t M, int64_t N, int64_t K, void* out,
                    int32_t* acc, hipStream_t st)
 {
@@ -363,8 +392,28 @@ int launch_gemm_f6(const void* x6, const void* w6, const float* sw, float sx, in
     const double wide = (double)((gm * ((N + 255) / 256) + 255) / 256) * 1.0;
     const double narrow = (double)((gm * ((N + 127) / 128) + 255) / 256) * 0.6;
     int ci = narrow < wide ? 2 : 4;
-    if (const char* f = getenv("PQ_GEMM_F6_TILE")) {
-        if (atoi(f) == 2 || atoi(f) == 4) ci = atoi(f);
+    const char* forced = getenv("PQ_GEMM_F6_TILE");
+    if (forced && (atoi(forced) == 2 || atoi(forced) == 4)) ci = atoi(forced);
+    // mixed widths: 256 n1 + 192 n2 = N; rounds of wide tiles, then rounds of 192-wide ones at 0.75 each
+    if (!forced || atoi(forced) == 3) {
+        double best = (narrow < wide ? narrow : wide) * 0.97;
+        int b1 = 0, b2 = 0;
+        for (int64_t n2 = 1; 192 * n2 < N; ++n2) {
+            if ((N - 192 * n2) % 256 != 0) continue;
+            const int64_t n1 = (N - 192 * n2) / 256;
+            if (n1 < 1 || gm * (n1 + n2) > (1 << 20)) continue;
+            const double cost = (double)((gm * n1 + 255) / 256) + 0.75 * (double)((gm * n2 + 255) / 256);
+            if (cost < best || (forced && b1 == 0)) { best = cost; b1 = (int)n1; b2 = (int)n2; }
+        }
+        if (b1 > 0) {
+            constexpr size_t lds = (size_t)kRing * 16 * kChunkF6;
+            static uint64_t lds_ok = 0;
+            if (allow_dynamic_lds(reinterpret_cast<const void*>(k_gemm_f6_dual), lds, lds_ok) != PQ_OK) return PQ_ERR_HIP;
+            hipLaunchKernelGGL(k_gemm_f6_dual, dim3((unsigned)(gm * (b1 + b2))), dim3(256), lds, st,
+                               static_cast<const uint8_t*>(x6), static_cast<const uint8_t*>(w6), sw, sx, (int)M, (int)N, (int)K,
+                               (int)gm, b1, b2, static_cast<__half*>(out), acc);
+            return hip_status(hipGetLastError());
+        }
     }
     return ci == 2 ? launch_f6<2>(x6, w6, sw, sx, M, N, K, out, acc, st) : launch_f6<4>(x6, w6, sw, sx, M, N, K, out, acc, st);
 }

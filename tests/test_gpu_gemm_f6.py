@@ -181,3 +181,20 @@ def test_unrotated_quantizer_to_tiles_is_exact_for_every_fp16_value(pq):
     off = (pq.pq_f6_tiles_bytes(8, 1024) + 255) // 256 * 256
     codes = O.unpack(host(ws)[off:off + 8 * 512].reshape(8, 512))
     assert np.array_equal(codes, O.quantize(xt, s))
+
+
+@pytest.mark.parametrize("M,N,K", [(300, 448, 256), (40, 4096, 1152), (517, 1216, 384), (2048, 14336, 128)])
+def test_mixed_width_launch(pq, tile_env, M, N, K):
+    """N = 256 a + 192 b: tiles of both widths in one launch (forced; the automatic choice takes it for the
+    benchmark's gate/up shape, the last case)."""
+    os.environ["PQ_GEMM_F6_TILE"] = "3"
+    if (M, N) == (2048, 14336):
+        os.environ.pop("PQ_GEMM_F6_TILE")
+    xq = synth.random_packed(M, K, seed=M + K)
+    wq = synth.random_packed(N, K, seed=N + K, stream=7)
+    sw = synth.random_scales(N, seed=N)
+    acc_ref = O.gemm_i64(O.unpack(xq), O.unpack(wq))
+    out, acc = pq.pq_w4a4_gemm_f6(pq.pq_repack_f6(dev(xq)), pq.pq_repack_f6(dev(wq)), dev(sw), 0.0917, M, N, K,
+                                  want_out=True, want_acc=True)
+    assert np.array_equal(host(acc).astype(np.int64), acc_ref)
+    assert ulp_diff(host(out), O.epilogue(acc_ref, np.float32(0.0917), sw)).max() <= 1
