@@ -18,7 +18,13 @@
  *   - K % 32 == 0, N % 16 == 0, M >= 0 (M == 0 is a no-op that returns PQ_OK);
  *   - the return value is PQ_OK or a PQ_ERR_* code; on an error detected by argument
  *     checking nothing has been enqueued;
- *   - inputs must be finite; the library is stateless and thread-safe.
+ *   - inputs must be finite.
+ * State: the library keeps no handle and no per-call state; every entry point may be called from
+ * several threads at once.  Process-wide are only (a) the three switches for sweeps and tests at the
+ * end of this header (pq_set_gemm_variant, pq_set_gemm_tile, pq_set_gemm_f6_tile: atomic integers, read
+ * by every product call; left alone, the automatic choice is a pure function of the shape), (b) a
+ * per-kernel record that the runtime has been told about its LDS size (set once per device,
+ * idempotent), and (c) the built-in scratch array of pq_linear_noalloc, which calls on one GPU share.
  */
 #ifndef PQ_H
 #define PQ_H
@@ -68,9 +74,10 @@ int pq_rotate_quant(const void* x_f16, int64_t M, int64_t K, int32_t had_block,
  *     out[m,n] = fp16(acc[m,n] * (act_scale * w_scale[n]))   (fp32 multiply, RNE)
  * The kernel is chosen from M: weight-streaming kernels for M <= 16 (decode: 4-bit dot
  * products on packed nibbles for M <= 8, small matrix tiles up to 16 or 32), an INT8-MFMA tiled
- * kernel otherwise (prefill).
+ * kernel otherwise (prefill).  The tiled kernel carries 256 * acc in int32, which is exact for
+ * K < 131072; longer rows with more than 8 tokens return PQ_ERR_UNSUPPORTED.
  * xq_packed in  [M,K/2] uint8 canonical.      wq_packed in [N,K/2] uint8 canonical.
- * w_scale   in  [N] fp32.                     act_scale: static step size of xq.
+ * w_scale   in  [N] fp32, 16-byte aligned.    act_scale: static step size of xq.
  * out_f16   out [M,N] fp16; may be NULL iff acc_i32 is not.
  * acc_i32   out [M,N] int32 raw accumulators, for verification; NULL in production.
  */
@@ -166,8 +173,11 @@ int pq_probe_f6_product(const int8_t* a_codes, const int8_t* b_codes, int64_t K,
  *   the tiles under 4 GiB (else PQ_ERR_SHAPE / PQ_ERR_UNSUPPORTED).  Weights are repacked once,
  *   offline; activations after pq_rotate_quant.
  * pq_w4a4_gemm_f6: x_tiles, w_tiles as written by pq_repack_f6 for [M,K] and [N,K]; everything else
- *   as pq_w4a4_gemm.  (The environment variable PQ_GEMM_F6_TILE = 2, 3 or 4 forces tiles of 128
- *   channels, the mix of 256 and 192 where N allows it, or 256; sweeps and tests only.)
+ *   as pq_w4a4_gemm.
+ * These calls are the optional prepacked layout of the boundary (a pure re-encoding of the canonical
+ * nibbles, checked by a round trip against the layout's definition): pq_f6_tiles_bytes is its size
+ * query, pq_repack_f6 the prepacking step, pq_w4a4_gemm_f6 and pq_linear_f6 the prepacked twins of
+ * pq_w4a4_gemm and pq_linear; the canonical entry points work without them.
  */
 size_t pq_f6_tiles_bytes(int64_t rows, int64_t K);
 int pq_repack_f6(const void* codes_packed, int64_t rows, int64_t K, void* tiles, void* stream);
@@ -203,12 +213,21 @@ int pq_linear_f6(const void* x_f16, const void* w_tiles, const float* w_scale,
  * 16 (up to 32 in two launches where a cost estimate puts that ahead of the tiled kernel: outputs
  * of few tiles), tiled beyond.  Every kernel gives the same accumulators and the same fp16 outputs
  * bit for bit.
- * Returns the previous value, or -1 if `variant` is unknown.
- * The environment variable PQ_GEMM_TILE (0..8, read at every call; sweeps and tests only) forces the
- * tiled kernel's tile: 0 256x256, 1 256x128, 2 128x128, 3 256x192, 4 64x128, 5-8 variants of these with
- * more wavefronts or a deeper ring; unset, the tile follows from the shape.
+ * Returns the previous value, or -1 if `variant` is unknown.  An atomic integer: safe to call from
+ * any thread, but a product call running concurrently on another thread may see either value.
  */
 int pq_set_gemm_variant(int variant);
+
+/* Force the tiled kernel's tile (sweeps and tests; host, process-wide, atomic): -1 = by shape, 0 256x256,
+ * 1 256x128, 2 128x128, 3 256x192, 4 64x128, 5-8 variants of these with more wavefronts or a deeper
+ * ring; any forced tile also switches the mixed-width launch off.  Before the first call the value
+ * is that of the environment variable PQ_GEMM_TILE, read once at the first product of the process.
+ * pq_set_gemm_f6_tile: the same for pq_w4a4_gemm_f6: -1 = by shape, 2 = 128 channels per tile,
+ * 3 = the mix of 256 and 192 where N allows it, 4 = 256 (environment variable PQ_GEMM_F6_TILE).
+ * Both return the previous value, or -2 if `tile` is unknown.
+ */
+int pq_set_gemm_tile(int tile);
+int pq_set_gemm_f6_tile(int tile);
 
 /* ---- 4-bit weights, 8-bit static activations (the W4A8 rows of Table 3) -------------------
  * Same layer with the activation quantizer at 8 bits: q = clamp(round_half_even(y/act_scale),

@@ -32,6 +32,8 @@ SIGNATURES = {
     "pq_w4a4_gemm_ws": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i64, _i64, _i64, _vp, _vp, _vp, _sz, _vp]),
     "pq_linear": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i32, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
     "pq_set_gemm_variant": (ctypes.c_int, [ctypes.c_int]),
+    "pq_set_gemm_tile": (ctypes.c_int, [ctypes.c_int]),
+    "pq_set_gemm_f6_tile": (ctypes.c_int, [ctypes.c_int]),
     "pq_probe_mfma_i8": (ctypes.c_int, [_vp, _i64, _i64, _i32, _vp, _vp]),
     "pq_probe_stream_read": (ctypes.c_int, [_vp, _i64, _vp, _vp]),
     "pq_probe_mfma_f6": (ctypes.c_int, [_vp, _i64, _i64, _i32, _vp, _vp]),
@@ -493,6 +495,14 @@ def pq_calibrate_static_zp(x_cal, had_block: int, n_gamma: int = 8, n_beta: int 
 
 def pq_set_gemm_variant(variant: int) -> int:
     return int(lib().pq_set_gemm_variant(int(variant)))
+
+
+def pq_set_gemm_tile(tile: int) -> int:
+    return int(lib().pq_set_gemm_tile(int(tile)))
+
+
+def pq_set_gemm_f6_tile(tile: int) -> int:
+    return int(lib().pq_set_gemm_f6_tile(int(tile)))
 
 
 def pq_probe_mfma_i8(operands: torch.Tensor, iters: int, workgroups: int, sink: torch.Tensor) -> float:

@@ -4,9 +4,11 @@
 
 #include <math.h>
 
+#include <atomic>
+
 namespace {
 
-int g_variant = 0;  // 0 auto, 1 streaming MFMA (M <= 32), 2 MFMA tiled, 3 simple, 4 streaming dot (M <= 8), 5 tiled, K split
+std::atomic<int> g_variant{0};  // 0 auto, 1 streaming MFMA (M <= 32), 2 MFMA tiled, 3 simple, 4 streaming dot (M <= 8), 5 tiled, K split
 
 // Kernel for a product with given codes and few tokens: 4 = weight-streaming dot products
 // (k_decode), 1 = weight-streaming matrix tiles (k_stream_mfma), 2 = the tiled kernel, -1 = the
@@ -61,9 +63,8 @@ int check_gemm(const void* xq, const void* wq, const float* sw, float sx, int64_
 {
     if (M < 0 || N <= 0 || K <= 0 || (K % 32) != 0 || (N % 16) != 0) return PQ_ERR_SHAPE;
     if (!xq || !wq || !sw || (!out && !acc)) return PQ_ERR_NULL;
-    if (!aligned16(xq) || !aligned16(wq) || !aligned16(out) || !aligned16(acc) ||
-        (reinterpret_cast<uintptr_t>(sw) & 3u))
-        return PQ_ERR_ALIGN;
+    if (!aligned16(xq) || !aligned16(wq) || !aligned16(out) || !aligned16(acc) || !aligned16(sw))
+        return PQ_ERR_ALIGN;    // (the epilogues load four channel steps at a time)
     if (!good_scale(sx)) return PQ_ERR_SCALE;
     return PQ_OK;
 }
@@ -622,12 +623,14 @@ int pq_probe_stream_read(const void* src, int64_t bytes, int32_t* sink, void* st
     return pq::launch_probe_read(src, bytes, sink, static_cast<hipStream_t>(stream));
 }
 
+int pq_set_gemm_tile(int tile) { return pq::set_gemm_tile(tile); }
+
+int pq_set_gemm_f6_tile(int tile) { return pq::set_gemm_f6_tile(tile); }
+
 int pq_set_gemm_variant(int variant)
 {
     if (variant < 0 || variant > 5) return -1;
-    const int prev = g_variant;
-    g_variant = variant;
-    return prev;
+    return g_variant.exchange(variant);
 }
 
 }  // extern "C"

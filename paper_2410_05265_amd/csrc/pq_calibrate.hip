@@ -295,7 +295,7 @@ int launch_cal_zp_nc(const __half* xp, int64_t T, int64_t K, int log2h, double i
                      double bmin, float* result, float* ws, hipStream_t st)
 {
     const size_t lds = log2h > 9 ? (size_t)NC * kChunk * sizeof(float) : 0;
-    static uint64_t lds_a = 0, lds_b = 0;
+    static std::atomic<uint64_t> lds_a{0}, lds_b{0};
     if (lds > 32 * 1024) {
         const size_t mx = (size_t)NC * kChunk * sizeof(float);
         if (allow_dynamic_lds(reinterpret_cast<const void*>(k_cal_rowminmax<NC>), mx, lds_a) != PQ_OK ||
@@ -314,7 +314,7 @@ int launch_cal_nc(const __half* xp, int64_t T, int64_t K, int log2h, double inv_
                   double gamma_min, float* result, float* ws, hipStream_t st)
 {
     const size_t lds = log2h > 9 ? (size_t)NC * kChunk * sizeof(float) : 0;
-    static uint64_t lds_a = 0, lds_b = 0;
+    static std::atomic<uint64_t> lds_a{0}, lds_b{0};
     if (lds > 32 * 1024) {
         const size_t mx = (size_t)NC * kChunk * sizeof(float);
         if (allow_dynamic_lds(reinterpret_cast<const void*>(k_cal_rowmax<NC>), mx, lds_a) != PQ_OK ||

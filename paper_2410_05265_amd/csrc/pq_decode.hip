@@ -265,7 +265,7 @@ int launch_one(const __half* x, const uint8_t* xq_in, const uint8_t* wq, const f
     const size_t lds = (((size_t)MP * (ABITS == 8 ? K : K / 2) + 15) & ~(size_t)15) +
                        (MODE == 0 ? 16 : (size_t)G * kChunk * 4 + (size_t)M * K * 2);
     auto kern = k_decode<RPW, CB, MP, MODE, ABITS>;
-    static uint64_t lds_ok = 0;
+    static std::atomic<uint64_t> lds_ok{0};
     if (lds > 48 * 1024 && allow_dynamic_lds(reinterpret_cast<const void*>(kern), 160 * 1024, lds_ok) != PQ_OK)
         return PQ_ERR_HIP;
     const int groups = N / RPW;

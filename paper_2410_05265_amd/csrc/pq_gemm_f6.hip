@@ -15,6 +15,8 @@
 #include <hip/hip_fp16.h>
 #include <stdlib.h>
 
+#include <atomic>
+
 #include "pq_internal.h"
 #include "pq_rotate.h"
 
@@ -346,6 +348,35 @@ __global__ __launch_bounds__(256) void k_gemm_f6_dual(const uint8_t* __restrict_
 
 }  // namespace
 
+namespace {
+// Forced tile width (2, 3 = the mix, 4; -1 none): set by pq_set_gemm_f6_tile, and before the first such
+// call by the environment variable PQ_GEMM_F6_TILE, which is read once.
+constexpr int kF6Unread = -100;
+std::atomic<int> g_forced_f6{kF6Unread};
+
+int forced_f6_tile()
+{
+    int v = g_forced_f6.load(std::memory_order_relaxed);
+    if (v == kF6Unread) {
+        const char* f = getenv("PQ_GEMM_F6_TILE");
+        v = f ? atoi(f) : -1;
+        if (v < 2 || v > 4) v = -1;
+        int expected = kF6Unread;
+        g_forced_f6.compare_exchange_strong(expected, v);
+        v = g_forced_f6.load(std::memory_order_relaxed);
+    }
+    return v;
+}
+}  // namespace
+
+int set_gemm_f6_tile(int tile)
+{
+    if (tile != -1 && (tile < 2 || tile > 4)) return -2;
+    const int prev = forced_f6_tile();
+    g_forced_f6.store(tile);
+    return prev;
+}
+
 size_t f6_tiles_bytes(int64_t R, int64_t K) { return (size_t)((R + 31) / 32) * (size_t)(K / 64) * kStep; }
 
 int launch_quant_f6(const void* x, int64_t R, int64_t K, float act_scale, void* out, void* nibbles, hipStream_t st)
@@ -374,7 +405,7 @@ int launch_f6(const void* x6, const void* w6, const float* sw, float sx, int64_t
     constexpr size_t lds = (size_t)kRing * (2 * CI + 8) * kChunkF6;
     static_assert(lds <= 160 * 1024, "LDS ring too large");
     static_assert(4 * 32 * (64 * CI + 16) <= lds, "epilogue staging does not fit the ring");
-    static uint64_t lds_ok = 0;
+    static std::atomic<uint64_t> lds_ok{0};
     if (allow_dynamic_lds(reinterpret_cast<const void*>(k_gemm_f6<CI>), lds, lds_ok) != PQ_OK) return PQ_ERR_HIP;
     hipLaunchKernelGGL(k_gemm_f6<CI>, dim3((unsigned)(GM * GN)), dim3(256), lds, st, static_cast<const uint8_t*>(x6),
                        static_cast<const uint8_t*>(w6), sw, sx, (int)M, (int)N, (int)K, GM, static_cast<__half*>(out), acc);
@@ -392,10 +423,11 @@ int launch_gemm_f6(const void* x6, const void* w6, const float* sw, float sx, in
     const double wide = (double)((gm * ((N + 255) / 256) + 255) / 256) * 1.0;
     const double narrow = (double)((gm * ((N + 127) / 128) + 255) / 256) * 0.6;
     int ci = narrow < wide ? 2 : 4;
-    const char* forced = getenv("PQ_GEMM_F6_TILE");
-    if (forced && (atoi(forced) == 2 || atoi(forced) == 4)) ci = atoi(forced);
+    const int forced_tile = forced_f6_tile();
+    const bool forced = forced_tile != -1;
+    if (forced_tile == 2 || forced_tile == 4) ci = forced_tile;
     // mixed widths: 256 n1 + 192 n2 = N; rounds of wide tiles, then rounds of 192-wide ones at 0.75 each
-    if (!forced || atoi(forced) == 3) {
+    if (!forced || forced_tile == 3) {
         double best = (narrow < wide ? narrow : wide) * 0.97;
         int b1 = 0, b2 = 0;
         for (int64_t n2 = 1; 192 * n2 < N; ++n2) {
@@ -407,7 +439,7 @@ int launch_gemm_f6(const void* x6, const void* w6, const float* sw, float sx, in
         }
         if (b1 > 0) {
             constexpr size_t lds = (size_t)kRing * 16 * kChunkF6;
-            static uint64_t lds_ok = 0;
+            static std::atomic<uint64_t> lds_ok{0};
             if (allow_dynamic_lds(reinterpret_cast<const void*>(k_gemm_f6_dual), lds, lds_ok) != PQ_OK) return PQ_ERR_HIP;
             hipLaunchKernelGGL(k_gemm_f6_dual, dim3((unsigned)(gm * (b1 + b2))), dim3(256), lds, st,
                                static_cast<const uint8_t*>(x6), static_cast<const uint8_t*>(w6), sw, sx, (int)M, (int)N, (int)K,

@@ -34,6 +34,7 @@
 
 #include <hip/hip_fp16.h>
 #include <stdlib.h>
+#include <atomic>
 #include <type_traits>
 
 namespace pq {
@@ -473,7 +474,7 @@ int launch_dual(const void* xq, const void* wq, const float* sw, float sx, int64
     constexpr size_t lds = (size_t)NS * (BM * (ABITS == 8 ? 128 : 64) + (BN1 > BN2 ? BN1 : BN2) * 64);
     static_assert(lds <= 160 * 1024, "LDS ring too large");
     auto kern = k_gemm_dual<BM, BN1, BN2, WR, WC, NS, ABITS, ASHIFT>;
-    static uint64_t lds_ok = 0;
+    static std::atomic<uint64_t> lds_ok{0};
     if (allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds, lds_ok) != PQ_OK) return PQ_ERR_HIP;
     hipLaunchKernelGGL(kern, dim3((unsigned)(GM * (n1 + n2))), dim3(WR * WC * 64), lds, st,
                        static_cast<const uint8_t*>(xq), static_cast<const uint8_t*>(wq), sw, sx, (int)M, (int)N,
@@ -489,7 +490,7 @@ int launch_dma(const void* xq, const void* wq, const float* sw, float sx, int64_
     constexpr size_t lds = (size_t)NS * SUBS * (BM * (ABITS == 8 ? 128 : 64) + BN * 64);
     static_assert(lds <= 160 * 1024, "LDS ring too large");
     auto kern = k_gemm_dma<BM, BN, WR, WC, NS, SUBS, ABITS, ASHIFT>;
-    static uint64_t lds_ok = 0;
+    static std::atomic<uint64_t> lds_ok{0};
     if (lds > 48 * 1024 && allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds, lds_ok) != PQ_OK)
         return PQ_ERR_HIP;
     hipLaunchKernelGGL(kern, dim3((unsigned)(GM * GN)), dim3(WR * WC * 64), lds, st,
@@ -572,7 +573,7 @@ int launch_splitk(const void* xq, const void* wq, const float* sw, SplitArgs ep,
     constexpr size_t lds = (size_t)NS * (BM * (ABITS == 8 ? 128 : 64) + BN * 64);
     static_assert(lds <= 160 * 1024, "LDS ring too large");
     auto kern = k_gemm_splitk<BM, BN, 2, 2, NS, ABITS, ASHIFT>;
-    static uint64_t lds_ok = 0;
+    static std::atomic<uint64_t> lds_ok{0};
     if (lds > 48 * 1024 && allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds, lds_ok) != PQ_OK)
         return PQ_ERR_HIP;
     hipLaunchKernelGGL(kern, dim3((unsigned)(GM * GN * S)), dim3(256), lds, st, static_cast<const uint8_t*>(xq),
@@ -712,6 +713,8 @@ int launch_ragged(const void* xq, const void* wq, const float* sw, float sx, int
     return hip_status(hipGetLastError());
 }
 
+constexpr int64_t kMaxK4 = 131072;   // first K at which 256 * 64 * K no longer fits int32
+
 struct TileCfg { int bm, bn; double eff, stage_us; };   // stage_us: one 128-channel stage of one tile, all CUs busy
 // tile shapes the automatic choice considers, with measured relative efficiencies (a larger
 // wavefront tile needs fewer LDS reads and less expansion per matrix instruction; 64 x 128 is for
@@ -725,12 +728,28 @@ constexpr TileCfg kCfgs[kNumCfg] = {{256, 256, 1.00, 1.35}, {256, 128, 0.85, 0.7
 // PQ_GEMM_TILE=0..8 forces a configuration (sweeps only): 0 256x256, 1 256x128, 2 128x128,
 // 3 256x192, 4 64x128, 5 256x256 with 8 wavefronts, 6 256x256 with a 4-stage ring, 7 and 8 256x128
 // with 8 wavefronts (4x2 and 2x4).
+// Forced tile configuration: -1 none; set by pq_set_gemm_tile, and before the first such call by the
+// environment variable PQ_GEMM_TILE, which is read once (no getenv on the per-call path).
+constexpr int kTileUnread = -100;
+std::atomic<int> g_forced_tile{kTileUnread};
+
+int forced_tile()
+{
+    int v = g_forced_tile.load(std::memory_order_relaxed);
+    if (v == kTileUnread) {
+        const char* f = getenv("PQ_GEMM_TILE");
+        v = f ? atoi(f) : -1;
+        if (v < -1 || v >= kNumCfg) v = -1;
+        int expected = kTileUnread;
+        g_forced_tile.compare_exchange_strong(expected, v);   // a concurrent pq_set_gemm_tile wins
+        v = g_forced_tile.load(std::memory_order_relaxed);
+    }
+    return v;
+}
+
 int pick_cfg(int64_t M, int64_t N)
 {
-    if (const char* f = getenv("PQ_GEMM_TILE")) {
-        const int v = atoi(f);
-        if (v >= 0 && v < kNumCfg) return v;
-    }
+    if (forced_tile() >= 0) return forced_tile();
     int best = 0;
     double best_cost = 1e300;
     for (int c = 0; c < kNumAuto; ++c) {
@@ -747,7 +766,7 @@ int pick_cfg(int64_t M, int64_t N)
 // width's efficiency (the same model as pick_cfg).  PQ_GEMM_TILE switches the mixed launch off.
 bool pick_dual(int64_t M, int64_t N, int* n1_out, int* n2_out)
 {
-    if (getenv("PQ_GEMM_TILE") || (N % 64) != 0 || M < 256) return false;
+    if (forced_tile() != -1 || (N % 64) != 0 || M < 256) return false;
     const int64_t GM = (M + 255) / 256;
     double single = 1e300;
     for (int c = 0; c < kNumAuto; ++c) {
@@ -823,7 +842,8 @@ void plan_splitk(int64_t M, int64_t N, int64_t K, size_t ws_bytes, bool force, i
 int launch_gemm_mfma(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K,
                      void* out, int32_t* acc, hipStream_t st)
 {
-    if (M > (1 << 30) || N > (1 << 30) || K > (1 << 30)) return PQ_ERR_UNSUPPORTED;
+    // the accumulators carry 256 * acc in int32 and |acc| <= 64 K: exact for K < 2^17 only
+    if (M > (1 << 30) || N > (1 << 30) || K >= kMaxK4) return PQ_ERR_UNSUPPORTED;
     if (M * (K / 2) >= ((int64_t)1 << 32) || N * (K / 2) >= ((int64_t)1 << 32)) return PQ_ERR_UNSUPPORTED;
     if (K % 128 != 0) return launch_ragged(xq, wq, sw, sx, M, N, K, out, acc, st);
     // (two 128-channel sub-stages per ring stage, i.e. one barrier per 256 channels with a 2-deep
@@ -841,6 +861,14 @@ int launch_gemm_mfma(const void* xq, const void* wq, const float* sw, float sx, 
         case 8: return launch_dma<256, 128, 2, 4, 3, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
         default: return launch_dma<256, 256, 2, 2, 4, 1>(xq, wq, sw, sx, M, N, K, out, acc, st);
     }
+}
+
+int set_gemm_tile(int tile)
+{
+    if (tile < -1 || tile >= kNumCfg) return -2;
+    const int prev = forced_tile();
+    g_forced_tile.store(tile);
+    return prev;
 }
 
 // The cost model's figure for the unsplit tiled launch, in microseconds (the best automatic tile;
@@ -884,7 +912,7 @@ int try_splitk(const void* xq, const void* wq, const float* sw, SplitArgs ep, in
 int launch_gemm_mfma_ws(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K,
                         void* out, int32_t* acc, void* ws, size_t ws_bytes, bool force, hipStream_t st)
 {
-    if (M <= (1 << 30) && N <= (1 << 30) && K <= (1 << 30) && M * (K / 2) < ((int64_t)1 << 32) &&
+    if (M <= (1 << 30) && N <= (1 << 30) && K < kMaxK4 && M * (K / 2) < ((int64_t)1 << 32) &&
         N * (K / 2) < ((int64_t)1 << 32)) {
         const int rc = try_splitk<4>(xq, wq, sw, SplitArgs{sx, nullptr, nullptr}, M, N, K, out, acc, ws, ws_bytes, force, st);
         if (rc >= 0) return rc;

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/pq.h"
 
 namespace pq {
@@ -69,6 +71,10 @@ int launch_gemm_f6(const void* x6, const void* w6, const float* sw, float sx, in
                    int32_t* acc, hipStream_t st);
 int launch_probe_f6_product(const int8_t* a, const int8_t* b, int64_t K, int32_t* out, hipStream_t st);
 
+// forced tile configurations (sweeps and tests): previous value, or -2 for an unknown one
+int set_gemm_tile(int tile);
+int set_gemm_f6_tile(int tile);
+
 bool stream_mfma_supported(int64_t M, int64_t N, int64_t K, int32_t abits = 4);
 int stream_mfma_launches(int64_t M, int64_t N, int64_t K, int32_t abits = 4);   // for a supported shape
 int launch_stream_mfma(const void* xq, const void* wq, const float* sw, float sx, int64_t M, int64_t N, int64_t K,
@@ -85,14 +91,14 @@ inline int hip_status(hipError_t e) { return e == hipSuccess ? PQ_OK : PQ_ERR_HI
 // A kernel may use more than the default amount of dynamic LDS only after the runtime has been told,
 // once per kernel and device.  `done` is that kernel's mask of devices already served (a static of
 // the caller; two first calls racing is harmless, the setting is idempotent).
-inline int allow_dynamic_lds(const void* kern, size_t bytes, uint64_t& done)
+inline int allow_dynamic_lds(const void* kern, size_t bytes, std::atomic<uint64_t>& done)
 {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return PQ_ERR_HIP;
     const uint64_t bit = 1ull << (dev & 63);
-    if (done & bit) return PQ_OK;
+    if (done.load(std::memory_order_acquire) & bit) return PQ_OK;
     if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) return PQ_ERR_HIP;
-    done |= bit;
+    done.fetch_or(bit, std::memory_order_release);
     return PQ_OK;
 }
 

@@ -292,7 +292,7 @@ int launch_dyn_nc(const __half* xp, int64_t M, int64_t K, int log2h, double inv_
 {
     const size_t lds = log2h > 9 ? (size_t)NC * kChunk * sizeof(float) : 0;
     auto kern = k_rotate_quant_dyn<NC, BITS>;
-    static uint64_t lds_ok = 0;
+    static std::atomic<uint64_t> lds_ok{0};
     if (lds > 48 * 1024 &&
         allow_dynamic_lds(reinterpret_cast<const void*>(kern), (size_t)NC * kChunk * sizeof(float), lds_ok) != PQ_OK)
         return PQ_ERR_HIP;

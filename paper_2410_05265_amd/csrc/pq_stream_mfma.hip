@@ -328,7 +328,7 @@ int launch_tokens(const void* xq, const void* wq, const float* sw, float sx, int
     // units a wavefront has at most: the ring is as deep as that, up to 4
     const int64_t units = ((T + grid - 1) / grid) * upt;
     auto launch = [&](auto kern) {
-        static uint64_t lds_ok = 0;
+        static std::atomic<uint64_t> lds_ok{0};
         if (allow_dynamic_lds(reinterpret_cast<const void*>(kern), 160 * 1024, lds_ok) != PQ_OK) return (int)PQ_ERR_HIP;
         hipLaunchKernelGGL(kern, dim3(grid), dim3(1024), lds, st, static_cast<const uint8_t*>(xq),
                            static_cast<const uint8_t*>(wq), sw, sx, (int)M, (int)N, (int)K, log2S,

@@ -114,7 +114,9 @@ def test_hip_path_against_the_stored_tiny_configuration():
         assert " ".join(np.float16(v).tobytes().hex() for v in host(out)[0, :8]) == stored["out_row0_first8_f16_hex"]
         assert sha(host(out)) == stored["out_f16_sha256"]
     else:
-        # a rotated value on a rounding tie may fall to the other side in fp32: at most a handful of codes, by one
-        hist = np.array(stored["codes_histogram_-8..7"].split(), np.int64)
-        got = np.array([(codes == v).sum() for v in range(-8, 8)], np.int64)
-        assert np.abs(got - hist).sum() <= 2 * 8 and np.abs(codes[0, :16] - want_row0).max() <= 1
+        # a rotated value on a rounding tie may fall to the other side in fp32: then the differing codes are few,
+        # off by one, and each within 1e-3 of a half-integer of the oracle's fp64 quotient; the outputs follow from
+        # the GPU's own codes through the oracle's product and epilogue (pq_testlib.check_end_to_end)
+        from pq_testlib import check_end_to_end
+        nflip, _ = check_end_to_end(x, O.pack(wq), sw, sx, H, host(out), O.pack(codes))
+        assert 0 < nflip <= 1e-3 * M * K and np.abs(codes[0, :16] - want_row0).max() <= 1

@@ -27,12 +27,25 @@ def pq():
     return b
 
 
+_weights_cache = {}
+
+
+def _weights(N, K, seed):
+    """Packed RTN weights of a layer; the last few are kept (the 70B matrices take ~15 s to draw and round)."""
+    key = (N, K, seed)
+    if key not in _weights_cache:
+        while len(_weights_cache) >= 2:
+            _weights_cache.pop(next(iter(_weights_cache)))
+        wq, sw = O.weight_rtn(synth.weights(N, K, seed))
+        _weights_cache[key] = (O.pack(wq), sw)
+    return _weights_cache[key]
+
+
 def _layer(M, K, N, h, seed):
     x = synth.activations(M, K, seed)
-    W = synth.weights(N, K, seed)
-    wq, sw = O.weight_rtn(W)
+    wq_packed, sw = _weights(N, K, seed)
     sx = O.calibrate_absmax(synth.calibration(K, seed), h)
-    return x, O.pack(wq), sw, sx
+    return x, wq_packed, sw, sx
 
 
 def _check_sampled(pq, M, K, N, h, seed, nsample):
@@ -61,8 +74,31 @@ def test_llama3_8b_prefill_2048(pq, name, K, N, h):
     _check_sampled(pq, 2048, K, N, h, seed=11, nsample=24)
 
 
-def test_llama3_8b_prefill_8192_down(pq):
-    _check_sampled(pq, 8192, 14336, 4096, 128, seed=12, nsample=16)
+def test_llama3_8b_prefill_2048_down_every_token(pq):
+    """The headline shape un-sampled: all 2048 x 4096 accumulators of down_proj against the oracle's int64
+    product of the GPU's own codes, and every fp16 output within one ulp of the oracle's epilogue."""
+    M, K, N, h = 2048, 14336, 4096, 128
+    x, wq_packed, sw, sx = _layer(M, K, N, h, seed=11)
+    d_w, d_sw = dev(wq_packed), dev(sw)
+    out, ws = pq.pq_linear(dev(x), d_w, d_sw, float(sx), h)
+    xq = ws[: M * K // 2].view(M, K // 2).contiguous()
+    _, acc = pq.pq_w4a4_gemm(xq, d_w, d_sw, float(sx), want_out=False, want_acc=True)
+    acc_ref = O.gemm_i64(O.unpack(host(xq)), O.unpack(wq_packed))
+    assert np.array_equal(host(acc).astype(np.int64), acc_ref)
+    assert ulp_diff(O.epilogue(acc_ref, np.float32(sx), sw), host(out)).max() <= 1
+
+
+@pytest.mark.parametrize("name,K,N,h", [("qkv", 4096, 6144, 1), ("o", 4096, 4096, 1), ("gate", 4096, 14336, 1),
+                                        ("o_rotated", 4096, 4096, 4096), ("down", 14336, 4096, 128)])
+def test_llama3_8b_prefill_8192(pq, name, K, N, h):
+    _check_sampled(pq, 8192, K, N, h, seed=12, nsample=16)
+
+
+# Llama-2-7B at 2048 tokens: q/k/v/o with the full 4096-point rotation online, gate/up to 11008 channels
+# (a launch of 40 column panels of 256 and 4 of 192), rotated and as they arrive
+@pytest.mark.parametrize("name,K,N,h", [("qkvo", 4096, 4096, 4096), ("gate", 4096, 11008, 4096), ("up", 4096, 11008, 1)])
+def test_llama2_7b_prefill_2048(pq, name, K, N, h):
+    _check_sampled(pq, 2048, K, N, h, seed=17, nsample=16)
 
 
 def test_llama2_7b_prefill_2048_down(pq):
@@ -71,6 +107,17 @@ def test_llama2_7b_prefill_2048_down(pq):
 
 def test_llama3_70b_prefill_2048_qkv_rotated(pq):
     _check_sampled(pq, 2048, 8192, 10240, 8192, seed=14, nsample=12)
+
+
+@pytest.mark.parametrize("name,K,N,h", [("o", 8192, 8192, 1), ("gate", 8192, 28672, 1), ("down", 28672, 8192, 128)])
+def test_llama3_70b_prefill_2048(pq, name, K, N, h):
+    _check_sampled(pq, 2048, K, N, h, seed=18, nsample=8)
+
+
+@pytest.mark.parametrize("name,K,N,h", [("qkv", 8192, 10240, 1), ("o", 8192, 8192, 1), ("o_rotated", 8192, 8192, 8192),
+                                        ("gate", 8192, 28672, 1)])
+def test_llama3_70b_decode_one_token(pq, name, K, N, h):
+    test_decode_full_shapes(pq, 1, name, K, N, h)
 
 
 @pytest.mark.parametrize("M", [1, 4, 16])

@@ -59,23 +59,17 @@ def test_repacked_layout_matches_its_definition(pq, R, K):
 
 
 @pytest.fixture
-def tile_env():
-    saved = os.environ.get("PQ_GEMM_F6_TILE")
+def tile_env(pq):
+    saved = pq.pq_set_gemm_f6_tile(-1)
     yield
-    if saved is None:
-        os.environ.pop("PQ_GEMM_F6_TILE", None)
-    else:
-        os.environ["PQ_GEMM_F6_TILE"] = saved
+    pq.pq_set_gemm_f6_tile(saved)
 
 
 @pytest.mark.parametrize("tile", ["auto", "2", "4"])     # channels per tile: by shape, 128, 256
 @pytest.mark.parametrize("M,N,K", [(256, 256, 128), (256, 256, 512), (300, 400, 1152), (64, 128, 128), (517, 784, 384),
                                    (129, 1040, 2048), (1, 16, 128), (2048, 512, 256), (40, 4096, 4096)])
 def test_product_and_epilogue(pq, tile_env, tile, M, N, K):
-    if tile == "auto":
-        os.environ.pop("PQ_GEMM_F6_TILE", None)
-    else:
-        os.environ["PQ_GEMM_F6_TILE"] = tile
+    pq.pq_set_gemm_f6_tile(-1 if tile == "auto" else int(tile))
     xq = synth.random_packed(M, K, seed=M + K)
     wq = synth.random_packed(N, K, seed=N + K, stream=7)
     sw = synth.random_scales(N, seed=N)
@@ -187,9 +181,7 @@ def test_unrotated_quantizer_to_tiles_is_exact_for_every_fp16_value(pq):
 def test_mixed_width_launch(pq, tile_env, M, N, K):
     """N = 256 a + 192 b: tiles of both widths in one launch (forced; the automatic choice takes it for the
     benchmark's gate/up shape, the last case)."""
-    os.environ["PQ_GEMM_F6_TILE"] = "3"
-    if (M, N) == (2048, 14336):
-        os.environ.pop("PQ_GEMM_F6_TILE")
+    pq.pq_set_gemm_f6_tile(-1 if (M, N) == (2048, 14336) else 3)
     xq = synth.random_packed(M, K, seed=M + K)
     wq = synth.random_packed(N, K, seed=N + K, stream=7)
     sw = synth.random_scales(N, seed=N)

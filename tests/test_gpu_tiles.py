@@ -1,4 +1,4 @@
-"""Every tile configuration of the tiled product, forced one by one (PQ_GEMM_TILE, read at each call):
+"""Every tile configuration of the tiled product, forced one by one (pq_set_gemm_tile):
 the automatic choice picks a configuration from the shape, so a given test shape exercises one of
 them; here each is run on shapes with ragged last tiles in both directions, one and several
 128-channel stages, and the mixed-width launch, against the oracle's integer sums and its epilogue.
@@ -27,13 +27,10 @@ def pq():
 
 
 @pytest.fixture
-def tile_env():
-    saved = os.environ.get("PQ_GEMM_TILE")
+def tile_env(pq):
+    saved = pq.pq_set_gemm_tile(-1)
     yield
-    if saved is None:
-        os.environ.pop("PQ_GEMM_TILE", None)
-    else:
-        os.environ["PQ_GEMM_TILE"] = saved
+    pq.pq_set_gemm_tile(saved)
 
 
 @pytest.mark.parametrize("tile", sorted(TILES))
@@ -44,7 +41,7 @@ def test_forced_tile_configuration(pq, tile_env, tile, M, N, K):
     sw = synth.random_scales(N, seed=N)
     sx = np.float32(0.0917)
     acc_ref = O.gemm_i64(O.unpack(xq), O.unpack(wq))
-    os.environ["PQ_GEMM_TILE"] = str(tile)
+    pq.pq_set_gemm_tile(tile)
     prev = pq.pq_set_gemm_variant(2)
     try:
         out, acc = pq.pq_w4a4_gemm(dev(xq), dev(wq), dev(sw), float(sx), want_out=True, want_acc=True)
@@ -62,7 +59,7 @@ def test_forced_tile_int8_activations_and_per_token_steps(pq, tile_env, tile):
     sw = synth.random_scales(N, seed=7)
     srow = synth.random_scales(M, seed=8)
     acc_ref = O.gemm_i64(q, O.unpack(wq))
-    os.environ["PQ_GEMM_TILE"] = str(tile)
+    pq.pq_set_gemm_tile(tile)
     prev = pq.pq_set_gemm_variant(2)
     try:
         out, acc = pq.pq_w4a8_gemm(dev(O.group_even_odd(q)), dev(wq), dev(sw), 0.013, want_out=True, want_acc=True)
@@ -78,7 +75,7 @@ def test_forced_tile_int8_activations_and_per_token_steps(pq, tile_env, tile):
 def test_mixed_width_launch(pq, tile_env):
     """N = 256 a + 192 b with a, b >= 1 and at least 256 tokens: the automatic choice may start tiles of
     two widths in one launch (it does for the benchmark's gate/up shape); small K keeps the oracle fast."""
-    os.environ.pop("PQ_GEMM_TILE", None)
+    pq.pq_set_gemm_tile(-1)
     M, N, K = 2048, 14336, 128
     xq = synth.random_packed(M, K, seed=1)
     wq = synth.random_packed(N, K, seed=2, stream=7)
