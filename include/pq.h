@@ -125,6 +125,23 @@ int pq_linear(const void* x_f16, const void* wq_packed, const float* w_scale,
               float act_scale, int32_t had_block, int64_t M, int64_t N, int64_t K,
               void* out_f16, void* workspace, size_t workspace_bytes, void* stream);
 
+/* pq_linear for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the same layer, the same kernels and the same
+ * outputs bit for bit, with pq_linear's workspace taken from an array built into the library
+ * instead of from the caller.  The call allocates nothing, on the device or through any library.
+ * Limit: the packed codes, M*K/2 bytes rounded up to 256, must fit pq_linear_noalloc_max_bytes()
+ * (32 MiB: 2048 tokens of 28672 channels), else PQ_ERR_WORKSPACE and nothing is enqueued.  Every
+ * GPU the library runs on holds one such array until the process ends, and every call on a GPU
+ * uses that GPU's array: calls that overlap on one GPU (two streams, two threads) race; order
+ * them on one stream.  The array's contents between calls are unspecified (nothing in it has to
+ * start at zero: the quantizer writes every code before the product reads it).
+ * Arguments and errors otherwise as pq_linear.
+ */
+size_t pq_linear_noalloc_max_bytes(void);
+int pq_linear_noalloc(const void* x_f16, const void* wq_packed, const float* w_scale,
+                      float act_scale, int32_t had_block, int64_t M, int64_t N, int64_t K,
+                      void* out_f16, void* stream);
+
 /* Plain, slow device kernel for the same product as pq_w4a4_gemm (one thread per
  * output, no tiling).  Kept as an on-device cross-check for the fast kernels.
  */

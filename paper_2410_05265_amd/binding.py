@@ -31,6 +31,8 @@ SIGNATURES = {
     "pq_w4a4_gemm_workspace_bytes": (_sz, [_i64, _i64, _i64]),
     "pq_w4a4_gemm_ws": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i64, _i64, _i64, _vp, _vp, _vp, _sz, _vp]),
     "pq_linear": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i32, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
+    "pq_linear_noalloc_max_bytes": (_sz, []),
+    "pq_linear_noalloc": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i32, _i64, _i64, _i64, _vp, _vp]),
     "pq_set_gemm_variant": (ctypes.c_int, [ctypes.c_int]),
     "pq_set_gemm_tile": (ctypes.c_int, [ctypes.c_int]),
     "pq_set_gemm_f6_tile": (ctypes.c_int, [ctypes.c_int]),
@@ -202,6 +204,25 @@ def pq_linear(x, wq, w_scale, act_scale, had_block, out=None, workspace=None):
     _check(lib().pq_linear(_ptr(x), _ptr(wq), _ptr(w_scale), float(act_scale), int(had_block), M, N, K, _ptr(out),
                            _ptr(workspace), workspace.numel(), _stream()), "pq_linear")
     return out, workspace
+
+
+def pq_linear_noalloc_max_bytes() -> int:
+    return int(lib().pq_linear_noalloc_max_bytes())
+
+
+def pq_linear_noalloc(x, wq, w_scale, act_scale, had_block, out):
+    """pq_linear with the library's built-in scratch array; `out` fp16 [M,N] is the caller's (nothing is allocated)."""
+    _dev(x, torch.float16, "x")
+    _dev(wq, torch.uint8, "wq")
+    _dev(w_scale, torch.float32, "w_scale")
+    _dev(out, torch.float16, "out")
+    M, K = x.shape
+    N = wq.shape[0]
+    if wq.shape[1] * 2 != K or w_scale.numel() != N or tuple(out.shape) != (M, N):
+        raise ValueError("shape mismatch")
+    _check(lib().pq_linear_noalloc(_ptr(x), _ptr(wq), _ptr(w_scale), float(act_scale), int(had_block), M, N, K,
+                                   _ptr(out), _stream()), "pq_linear_noalloc")
+    return out
 
 
 def pq_rotate_quant8(x: torch.Tensor, had_block: int, act_scale: float, out: torch.Tensor | None = None):

@@ -6,7 +6,34 @@
 
 #include <atomic>
 
+// Scratch memory of pq_linear_noalloc: the packed activation codes between the quantizer and the
+// product (and, behind them, the partial-sum planes of a split launch).  One copy per GPU, at an
+// address of its own, alive until the process ends.  In host code this name is only a stand-in for
+// the symbol: the device address comes from hipGetSymbolAddress (scratch_base below).
+constexpr size_t kScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) uint8_t scratch[kScratchBytes];
+
 namespace {
+
+// Device address of `scratch` on the current device; looked up once per device, with that device
+// current, then kept.  Two first calls racing store the same value twice.
+constexpr int kMaxDevices = 64;
+std::atomic<uint8_t*> g_scratch_ptr[kMaxDevices];
+
+int scratch_base(uint8_t** base)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return PQ_ERR_HIP;
+    uint8_t* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        void* sym = nullptr;
+        if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || !sym) return PQ_ERR_HIP;
+        p = static_cast<uint8_t*>(sym);
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *base = p;
+    return PQ_OK;
+}
 
 std::atomic<int> g_variant{0};  // 0 auto, 1 streaming MFMA (M <= 32), 2 MFMA tiled, 3 simple, 4 streaming dot (M <= 8), 5 tiled, K split
 
@@ -626,6 +653,25 @@ int pq_probe_stream_read(const void* src, int64_t bytes, int32_t* sink, void* st
 int pq_set_gemm_tile(int tile) { return pq::set_gemm_tile(tile); }
 
 int pq_set_gemm_f6_tile(int tile) { return pq::set_gemm_f6_tile(tile); }
+
+size_t pq_linear_noalloc_max_bytes(void) { return kScratchBytes; }
+
+int pq_linear_noalloc(const void* x_f16, const void* wq_packed, const float* w_scale, float act_scale,
+                      int32_t had_block, int64_t M, int64_t N, int64_t K, void* out_f16, void* stream)
+{
+    if (M < 0 || N <= 0 || K <= 0 || (K % 32) != 0 || (N % 16) != 0) return PQ_ERR_SHAPE;
+    if (M == 0) return PQ_OK;
+    // the codes must fit the built-in array (M and K are bounded first so that the product cannot wrap)
+    if (M > (int64_t)kScratchBytes || K > 2 * (int64_t)kScratchBytes ||
+        pq_linear_workspace_bytes(M, K) > kScratchBytes)
+        return PQ_ERR_WORKSPACE;
+    uint8_t* base = nullptr;
+    const int rc = scratch_base(&base);
+    if (rc != PQ_OK) return rc;
+    // everything else is pq_linear's business: the same checks, the same kernels, `base` as their workspace
+    // (codes first; what lies behind them may hold the planes of a split launch)
+    return pq_linear(x_f16, wq_packed, w_scale, act_scale, had_block, M, N, K, out_f16, base, kScratchBytes, stream);
+}
 
 int pq_set_gemm_variant(int variant)
 {

@@ -155,3 +155,143 @@ def test_process_wide_switches(b):
     assert first in (-1, 2, 3, 4)
     assert L.pq_set_gemm_f6_tile(first) == 3
 
+
+def test_noalloc_size_checks_need_no_gpu(b):
+    L = b.lib()
+    p = ctypes.c_void_p(0x1000)
+    nul = ctypes.c_void_p(0)
+    limit = L.pq_linear_noalloc_max_bytes()
+    assert limit == 32 << 20
+    na = L.pq_linear_noalloc
+    assert na(p, p, p, 0.1, 1, 2048, 64, 2 * (limit // 2048) + 64, p, nul) == b.PQ_ERR_WORKSPACE
+    assert na(p, p, p, 0.1, 1, 1 << 40, 64, 64, p, nul) == b.PQ_ERR_WORKSPACE
+    assert na(p, p, p, 0.1, 1, 4, 64, 1 << 40, p, nul) == b.PQ_ERR_WORKSPACE
+    assert na(p, p, p, 0.1, 1, 4, 60, 64, p, nul) == b.PQ_ERR_SHAPE
+    assert na(p, p, p, 0.1, 1, 4, 64, 48, p, nul) == b.PQ_ERR_SHAPE
+    assert na(p, p, p, 0.1, 1, 0, 64, 64, p, nul) == b.PQ_OK
+
+
+def test_argument_errors_of_the_f6_probes(b):
+    L = b.lib()
+    p = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1008)
+    nul = ctypes.c_void_p(0)
+    assert L.pq_probe_f6_product(nul, p, 64, p, nul) == b.PQ_ERR_NULL
+    assert L.pq_probe_f6_product(p, p, 64, nul, nul) == b.PQ_ERR_NULL
+    assert L.pq_probe_f6_product(odd, p, 64, p, nul) == b.PQ_ERR_ALIGN
+    assert L.pq_probe_f6_product(p, p, 96, p, nul) == b.PQ_ERR_SHAPE          # K % 64
+    assert L.pq_probe_f6_product(p, p, 262144, p, nul) == b.PQ_ERR_SHAPE      # sums could pass 2^24
+    assert L.pq_probe_mfma_f6(nul, 64, 1, 1, p, nul) == b.PQ_ERR_NULL
+    assert L.pq_probe_mfma_f6(ctypes.c_void_p(0x1010), 64, 1, 1, p, nul) == b.PQ_ERR_ALIGN    # 32 bytes
+    assert L.pq_probe_mfma_f6(p, 48, 1, 1, p, nul) == b.PQ_ERR_SHAPE
+    assert L.pq_probe_mfma_f6(p, 64, 1, 0, p, nul) == b.PQ_ERR_SHAPE
+
+
+def test_argument_errors_of_the_f6_product(b):
+    L = b.lib()
+    p = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1008)
+    nul = ctypes.c_void_p(0)
+    assert L.pq_f6_tiles_bytes(32, 128) == 3072 and L.pq_f6_tiles_bytes(33, 256) == 2 * 2 * 3072
+    assert L.pq_f6_tiles_bytes(2048, 4096) == 2048 * 4096 * 3 // 4
+    assert L.pq_f6_tiles_bytes(32, 64) == 0 and L.pq_f6_tiles_bytes(0, 128) == 0
+    rp = L.pq_repack_f6
+    assert rp(nul, 32, 128, p, nul) == b.PQ_ERR_NULL and rp(p, 32, 128, nul, nul) == b.PQ_ERR_NULL
+    assert rp(p, 32, 64, p, nul) == b.PQ_ERR_SHAPE and rp(p, -1, 128, p, nul) == b.PQ_ERR_SHAPE
+    assert rp(odd, 32, 128, p, nul) == b.PQ_ERR_ALIGN
+    assert rp(p, 0, 128, p, nul) == b.PQ_OK
+    assert rp(p, 32, 262144, p, nul) == b.PQ_ERR_UNSUPPORTED         # sums could pass 2^24
+    assert L.pq_linear_f6_workspace_bytes(2048, 4096) == 2048 * 4096 * 3 // 4 + 2048 * 2048
+    assert L.pq_linear_f6_workspace_bytes(3, 128) == 3072 + 256 and L.pq_linear_f6_workspace_bytes(3, 96) == 0
+    lf = L.pq_linear_f6
+    p256 = ctypes.c_void_p(0x10000)
+    assert lf(p, p, p, 0.1, 1, 32, 16, 128, p, nul, 0, nul) == b.PQ_ERR_WORKSPACE
+    assert lf(p, p, p, 0.1, 1, 32, 16, 128, p, p256, 100, nul) == b.PQ_ERR_WORKSPACE
+    assert lf(p, p, p, 0.1, 1, 32, 16, 128, p, odd, 1 << 20, nul) == b.PQ_ERR_ALIGN
+    assert lf(nul, p, p, 0.1, 1, 32, 16, 128, p, p256, 1 << 20, nul) == b.PQ_ERR_NULL
+    assert lf(p, p, p, 0.1, 96, 32, 16, 128, p, p256, 1 << 20, nul) == b.PQ_ERR_SHAPE
+    assert lf(p, p, p, 0.1, 1, 32, 16, 64, p, p256, 1 << 20, nul) == b.PQ_ERR_SHAPE
+    assert lf(p, p, p, -1.0, 1, 32, 16, 128, p, p256, 1 << 20, nul) == b.PQ_ERR_SCALE
+    assert lf(p, p, p, 0.1, 1, 0, 16, 128, p, nul, 0, nul) == b.PQ_OK
+    g = L.pq_w4a4_gemm_f6
+    assert g(nul, p, p, 0.1, 32, 16, 128, p, nul, nul) == b.PQ_ERR_NULL
+    assert g(p, p, p, 0.1, 32, 16, 128, nul, nul, nul) == b.PQ_ERR_NULL
+    assert g(p, p, p, 0.1, 32, 16, 160, p, nul, nul) == b.PQ_ERR_SHAPE       # K % 128
+    assert g(p, p, p, 0.1, 32, 20, 128, p, nul, nul) == b.PQ_ERR_SHAPE       # N % 16
+    assert g(p, odd, p, 0.1, 32, 16, 128, p, nul, nul) == b.PQ_ERR_ALIGN
+    assert g(p, p, p, float("nan"), 32, 16, 128, p, nul, nul) == b.PQ_ERR_SCALE
+    assert g(p, p, p, 0.1, 0, 16, 128, p, nul, nul) == b.PQ_OK
+
+
+def test_argument_errors_of_the_widened_calls(b):
+    L = b.lib()
+    p = ctypes.c_void_p(0x1000)          # never dereferenced: each call fails validation first
+    p256 = ctypes.c_void_p(0x10000)
+    odd = ctypes.c_void_p(0x1008)
+    nul = ctypes.c_void_p(0)
+    E = b
+    # 8-bit static
+    assert L.pq_rotate_quant8(p, 4, 160, 1, 0.1, p, nul) == E.PQ_ERR_SHAPE              # K % 128
+    assert L.pq_rotate_quant8(p, 4, 256, 1, 0.1, nul, nul) == E.PQ_ERR_NULL
+    assert L.pq_rotate_quant8(p, 4, 256, 1, -0.1, p, nul) == E.PQ_ERR_SCALE
+    assert L.pq_rotate_quant8(p, 0, 256, 1, 0.1, p, nul) == E.PQ_OK
+    assert L.pq_w4a8_gemm(p, p, p, 0.1, 4, 64, 160, p, nul, nul) == E.PQ_ERR_SHAPE
+    assert L.pq_w4a8_gemm(p, p, p, 0.1, 4, 64, 256, nul, nul, nul) == E.PQ_ERR_NULL
+    assert L.pq_w4a8_gemm(p, p, p, 0.1, 40, 64, 131072, p, nul, nul) == E.PQ_ERR_UNSUPPORTED   # K > 65536
+    assert L.pq_linear_w4a8(p, p, p, 0.1, 128, 4, 64, 256, p, p256, 512, nul) == E.PQ_ERR_WORKSPACE
+    assert L.pq_linear_w4a8(p, p, p, 0.1, 128, 4, 64, 256, p, odd, 4096, nul) == E.PQ_ERR_ALIGN
+    assert L.pq_linear_w4a8(p, p, p, 0.1, 128, 0, 64, 256, p, nul, 0, nul) == E.PQ_OK
+    # per-token dynamic
+    rqd = L.pq_rotate_quant_dynamic
+    assert rqd(p, 4, 256, 1, 1.0, 4, p, nul, nul) == E.PQ_ERR_NULL                       # no place for the steps
+    assert rqd(p, 4, 256, 1, 1.0, 6, p, p, nul) == E.PQ_ERR_SHAPE
+    assert rqd(p, 4, 256, 1, 0.0, 4, p, p, nul) == E.PQ_ERR_SCALE
+    assert rqd(p, 4, 256, 1, 1.25, 4, p, p, nul) == E.PQ_ERR_SCALE
+    assert rqd(p, 4, 32768 + 128, 1, 1.0, 4, p, p, nul) == E.PQ_ERR_UNSUPPORTED
+    assert rqd(p, 4, 256, 1, 1.0, 4, p, ctypes.c_void_p(0x1002), nul) == E.PQ_ERR_ALIGN
+    assert L.pq_gemm_dynamic(p, 4, p, p, nul, 4, 64, 256, p, nul, nul) == E.PQ_ERR_NULL
+    assert L.pq_gemm_dynamic(p, 3, p, p, p, 4, 64, 256, p, nul, nul) == E.PQ_ERR_SHAPE
+    assert L.pq_linear_dynamic(p, p, p, 1.0, 1, 4, 4, 64, 256, p, p256, 512, nul) == E.PQ_ERR_WORKSPACE   # needs 512 + 256
+    assert L.pq_linear_dynamic(p, p, p, 1.0, 1, 4, 0, 64, 256, p, nul, 0, nul) == E.PQ_OK
+    # attention side
+    rh = L.pq_rotate_quant_heads
+    assert rh(p, 4, 8, 48, 1, p, p, nul) == E.PQ_ERR_SHAPE                               # head_dim not a power of two
+    assert rh(p, 4, 8, 16, 1, p, p, nul) == E.PQ_ERR_SHAPE                               # head_dim < 32
+    assert rh(p, 4, 0, 128, 1, p, p, nul) == E.PQ_ERR_SHAPE
+    assert rh(p, 4, 8, 128, 1, nul, p, nul) == E.PQ_ERR_NULL
+    assert rh(p, 4, 8, 128, 1, ctypes.c_void_p(0x1001), p, nul) == E.PQ_ERR_ALIGN
+    assert rh(p, 0, 8, 128, 1, p, p, nul) == E.PQ_OK
+    assert L.pq_rotate_f16(p, 4, 256, 1, p, nul) == E.PQ_ERR_SHAPE                       # nothing to rotate
+    assert L.pq_rotate_f16(p, 4, 256, 96, p, nul) == E.PQ_ERR_SHAPE
+    assert L.pq_rotate_f16(p, 4, 256, 128, nul, nul) == E.PQ_ERR_NULL
+    # fused producers
+    assert L.pq_silu_mul_rotate_quant(p, nul, 4, 256, 128, 0.1, p, nul) == E.PQ_ERR_NULL
+    assert L.pq_silu_mul_rotate_quant(p, p, 4, 250, 1, 0.1, p, nul) == E.PQ_ERR_SHAPE
+    assert L.pq_silu_mul_rotate_quant(p, odd, 4, 256, 128, 0.1, p, nul) == E.PQ_ERR_ALIGN
+    assert L.pq_rmsnorm_quant(p, 4, 256, -1e-6, 0.1, p, nul) == E.PQ_ERR_SCALE
+    assert L.pq_rmsnorm_quant(p, 4, 65536, 1e-6, 0.1, p, nul) == E.PQ_ERR_UNSUPPORTED
+    assert L.pq_rmsnorm_quant(p, 0, 256, 1e-6, 0.1, p, nul) == E.PQ_OK
+    # calibration
+    cal = L.pq_calibrate_static
+    assert cal(p, 0, 256, 1, 4, 8, 0.5, p, p256, 1 << 20, nul) == E.PQ_ERR_SHAPE          # no tokens
+    assert cal(p, 4, 256, 1, 4, 1, 0.5, p, p256, 1 << 20, nul) == E.PQ_ERR_SHAPE
+    assert cal(p, 4, 256, 1, 4, 8, 1.0, p, p256, 1 << 20, nul) == E.PQ_ERR_SCALE
+    assert cal(p, 4, 256, 1, 4, 8, 0.5, p, p256, 16, nul) == E.PQ_ERR_WORKSPACE
+    assert cal(p, 4, 256, 1, 4, 8, 0.5, nul, p256, 1 << 20, nul) == E.PQ_ERR_NULL
+    assert cal(p, 4, 65536, 1, 4, 8, 0.5, p, p256, 1 << 20, nul) == E.PQ_ERR_UNSUPPORTED
+
+
+def test_argument_errors_of_the_probes(b):
+    L = b.lib()
+    p = ctypes.c_void_p(0x1000)          # never dereferenced: each call fails validation first
+    odd = ctypes.c_void_p(0x1008)
+    nul = ctypes.c_void_p(0)
+    assert L.pq_probe_mfma_i8(nul, 1024, 10, 256, p, nul) == b.PQ_ERR_NULL
+    assert L.pq_probe_mfma_i8(p, 1024, 10, 256, nul, nul) == b.PQ_ERR_NULL
+    assert L.pq_probe_mfma_i8(odd, 1024, 10, 256, p, nul) == b.PQ_ERR_ALIGN
+    assert L.pq_probe_mfma_i8(p, 1000, 10, 256, p, nul) == b.PQ_ERR_SHAPE          # bytes % 16
+    assert L.pq_probe_mfma_i8(p, 1024, -1, 256, p, nul) == b.PQ_ERR_SHAPE
+    assert L.pq_probe_mfma_i8(p, 1024, 10, 0, p, nul) == b.PQ_ERR_SHAPE
+    assert L.pq_probe_stream_read(nul, 1024, p, nul) == b.PQ_ERR_NULL
+    assert L.pq_probe_stream_read(odd, 1024, p, nul) == b.PQ_ERR_ALIGN
+    assert L.pq_probe_stream_read(p, 8, p, nul) == b.PQ_ERR_SHAPE
