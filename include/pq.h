@@ -183,12 +183,15 @@ int pq_probe_f6_product(const int8_t* a_codes, const int8_t* b_codes, int64_t K,
  * accumulators are the integer sums of pq_w4a4_gemm, bit for bit, and so are the outputs.  The
  * instruction has twice the nominal rate of the INT8 one.  Both operands are repacked first:
  * pq_repack_f6: codes_packed [rows,K/2] uint8 canonical -> `tiles`, pq_f6_tiles_bytes(rows,K) bytes:
- *   for every block of 32 rows and every 128 channels 64 lanes x 48 bytes: per lane the register image
- *   of the first 64 channels (24 bytes), then that of the second; an image of lane l holds row
- *   32 rb + l % 32 and channels 64 ks + 32 (l / 32) + 0..31 as a little-endian stream of 6-bit values
- *   (rows past the end are zero); blocks ordered [rb][128-channel group].  K % 128 == 0, K <= 262080,
- *   the tiles under 4 GiB (else PQ_ERR_SHAPE / PQ_ERR_UNSUPPORTED).  Weights are repacked once,
- *   offline; activations after pq_rotate_quant.
+ *   one block of 3072 bytes for every 32 rows and every 128 channels, blocks ordered [rb][128-channel
+ *   group kt].  A block holds, for each of 64 lanes l and each of the instruction's two 64-channel steps
+ *   s, a register image of 24 bytes: row 32 rb + l % 32, channels 128 kt + 64 s + 32 (l / 32) + 0..31 as a
+ *   little-endian stream of 6-bit values (rows past the end are zero).  The images are stored as four
+ *   planes, each lane after lane: bytes 0-15 of the first step's images (64 x 16 bytes), their bytes
+ *   16-23 (64 x 8), bytes 0-7 of the second step's images (64 x 8), their bytes 8-23 (64 x 16): each plane
+ *   is one load instruction of a wavefront.  K % 128 == 0, K <= 262080, the tiles under 4 GiB (else
+ *   PQ_ERR_SHAPE / PQ_ERR_UNSUPPORTED).  Weights are repacked once, offline; activations after
+ *   pq_rotate_quant (pq_linear_f6 does it).
  * pq_w4a4_gemm_f6: x_tiles, w_tiles as written by pq_repack_f6 for [M,K] and [N,K]; everything else
  *   as pq_w4a4_gemm.
  * These calls are the optional prepacked layout of the boundary (a pure re-encoding of the canonical

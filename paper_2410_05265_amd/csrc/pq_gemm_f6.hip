@@ -6,16 +6,28 @@
 // chip's power limit.
 //
 // Both operands arrive repacked ("f6 tiles", k_repack_f6): for every block of 32 rows and every 128
-// channels (two steps of the instruction) the register images of a wavefront, lane after lane, 48
-// bytes per lane: the image of the first step (24 bytes), then that of the second.  An image of lane
-// l holds row 32 rb + l % 32 and the 32 channels 64 ks + 32 (l / 32) + i as a little-endian stream of
-// 6-bit values.  Such a block is 3072 contiguous bytes and is one row block's share of a ring stage:
-// the loads are straight copies into LDS, the main loop has no expansion work at all, and a lane
-// reads an image as one 16-byte and one 8-byte piece at a stride of 48 bytes (conflict-free).
+// channels (two steps of the instruction) the register images of a wavefront, 3072 bytes.  The image
+// of lane l for step s holds row 32 rb + l % 32 and the 32 channels 64 (2 kt + s) + 32 (l / 32) + i as
+// a little-endian stream of 6-bit values, 24 bytes = six dwords.  A block stores them as four planes,
+// each lane after lane: bytes 0-15 of the first step's images (64 x 16 bytes), their bytes 16-23
+// (64 x 8), bytes 0-7 of the second step's (64 x 8), their bytes 8-23 (64 x 16).  Every plane is what
+// one load instruction of a wavefront fetches (16 or 8 bytes per lane, consecutive lanes adjacent:
+// whole cache lines from memory, conflict-free from LDS), and its destination is a run of registers
+// inside the six of an image, so no instruction is spent on rearranging.
+//
+// At twice the INT8 rate the matrix pipe outruns the LDS if both operands pass through it (a 256 x 256
+// tile reads 96 KiB and writes 48 KiB of LDS per 128 channels, in the 1024 clocks its matrix
+// instructions take).  So only the tokens go through LDS: a workgroup's tile is 128 tokens x 4 wavefronts x
+// 32 CI channels, the 128 tokens' images (12 KiB per 128 channels) are shared by the four
+// wavefronts, and every wavefront streams the weights of its own 32 CI channels from memory straight
+// into the registers the matrix instruction reads (a ring of three stages, refilled image by image
+// right behind the last instruction that uses it): 48 KiB of LDS reads and 12 KiB of writes per 128
+// channels for the same 1024 clocks of matrix work.
 #include <hip/hip_fp16.h>
 #include <stdlib.h>
 
 #include <atomic>
+#include <type_traits>
 
 #include "pq_internal.h"
 #include "pq_rotate.h"
@@ -28,7 +40,8 @@ typedef int v2i __attribute__((ext_vector_type(2)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int kImage = 24, kStep = 64 * kImage, kChunkF6 = 2 * kStep;   // 1536 B per (row block, step); 3072 per stage
-constexpr int kRing = 3;                                                 // stages in LDS
+constexpr int kRing = 3;                                                 // stages in flight (LDS slots of the tokens, register sets of the weights)
+constexpr int kPersistentWorkgroups = 256;                               // one per CU
 
 // two's complement nibble -> E3M2 (bias 3): two tables of eight 6-bit entries, for 0..7 and for -8..-1
 __device__ __forceinline__ uint32_t e3m2_of_nibble(uint32_t nib)
@@ -38,6 +51,22 @@ __device__ __forceinline__ uint32_t e3m2_of_nibble(uint32_t nib)
     constexpr uint64_t neg = 56ull | (55ull << 6) | (54ull << 12) | (53ull << 18) | (52ull << 24) | (50ull << 30) |
                              (48ull << 36) | (44ull << 42);                            // -8, -7, ..., -1
     return (uint32_t)(((nib & 8u) ? neg : pos) >> (6u * (nib & 7u))) & 63u;
+}
+
+// Offsets of the four planes of a block, and an image's 24 bytes (three qwords) into its two planes.
+constexpr int kP0 = 0, kP1 = 1024, kP2 = 1536, kP3 = 2048;
+
+__device__ __forceinline__ void store_image(uint8_t* block, int lane, int step, const uint64_t (&w)[3])
+{
+    if (step == 0) {
+        uint64_t* a = reinterpret_cast<uint64_t*>(block + kP0 + lane * 16);
+        a[0] = w[0]; a[1] = w[1];
+        *reinterpret_cast<uint64_t*>(block + kP1 + lane * 8) = w[2];
+    } else {
+        *reinterpret_cast<uint64_t*>(block + kP2 + lane * 8) = w[0];
+        uint64_t* a = reinterpret_cast<uint64_t*>(block + kP3 + lane * 16);
+        a[0] = w[1]; a[1] = w[2];
+    }
 }
 
 // One thread per register image: 32 codes (16 bytes of nibbles) of one row -> 24 bytes.
@@ -62,8 +91,7 @@ __global__ __launch_bounds__(256) void k_repack_f6(const uint8_t* __restrict__ c
             if (bit % 64 > 58) w[bit / 64 + 1] |= e >> (64 - bit % 64);
         }
     }
-    uint64_t* o = reinterpret_cast<uint64_t*>(out + ((int64_t)rb * (KS >> 1) + (ks >> 1)) * kChunkF6 + lane * 48 + (ks & 1) * kImage);
-    o[0] = w[0]; o[1] = w[1]; o[2] = w[2];
+    store_image(out + ((int64_t)rb * (KS >> 1) + (ks >> 1)) * kChunkF6, lane, ks & 1, w);
 }
 
 // Quantizer for unrotated input that writes f6 tiles directly (one launch instead of quantizer + repack):
@@ -110,8 +138,7 @@ __global__ __launch_bounds__(256) void k_quant_f6(const __half* __restrict__ x, 
             *reinterpret_cast<v4i*>(nibbles + (int64_t)row * (K >> 1) + (k0 >> 1)) = nb;
         }
     }
-    uint64_t* o = reinterpret_cast<uint64_t*>(out + ((int64_t)rb * (KS >> 1) + (ks >> 1)) * kChunkF6 + lane * 48 + (ks & 1) * kImage);
-    o[0] = w[0]; o[1] = w[1]; o[2] = w[2];
+    store_image(out + ((int64_t)rb * (KS >> 1) + (ks >> 1)) * kChunkF6, lane, ks & 1, w);
 }
 
 __device__ __forceinline__ int xcd_run(int b, int total)   // each XCD takes a contiguous run of tiles
@@ -123,9 +150,49 @@ __device__ __forceinline__ int xcd_run(int b, int total)   // each XCD takes a c
 #define PQ6_LDS(p) ((__attribute__((address_space(3))) void*)(p))
 #define PQ6_GLB(p) ((const __attribute__((address_space(1))) void*)(p))
 
-// Tile of 64 CI channels x 256 tokens (CI = 4 or 2); wavefront (wr, wc): 32 CI channels x 128 tokens =
-// CI x 4 matrix tiles.  The weights are the first operand: a lane ends with one token (l % 32) and, per
-// matrix tile, the channels 8 (v / 4) + 4 (l / 32) + v % 4 in register v.
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for6(F&& f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for6<I + 1, N>(f);
+    }
+}
+
+// 16 bytes per lane from global memory straight into LDS (lane l lands at lds_addr + 16 l); base and
+// lds_addr are wavefront-uniform.  Issued as inline assembly on purpose: the compiler's bookkeeping of
+// outstanding loads treats a direct load to LDS as a memory operation of unknown kind and from then on
+// waits for *all* outstanding loads at the next register it needs, which would empty the ring of weight
+// loads every time.  Unknown to the compiler, these loads only make its waits for the weight registers
+// stricter than needed (more loads are in flight than it counts, and vmcnt waits for the oldest first);
+// the waits for the LDS data itself are placed by hand and count every load.
+__device__ __forceinline__ void lds_dma16(const uint8_t* base, uint32_t lane_offset, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(lane_offset), "s"(base), "s"(lds_addr)
+                 : "memory");     // (m0 is written here and used by nothing else in these kernels: the compiler keeps
+                                  // no value in it and sets it itself right in front of the instructions that read it)
+}
+
+constexpr int kTokBlocks = 4;                       // 128 tokens per workgroup tile
+constexpr int kStageA = kTokBlocks * kChunkF6;      // their images for 128 channels: 12 KiB of LDS
+constexpr int kLoadsA = kStageA / 1024 / 4;         // direct loads to LDS per wavefront and stage: 3
+
+// Waits as instructions the compiler knows (not inline asm): its own bookkeeping of outstanding loads,
+// which places the waits for the weight registers, then counts from these.  gfx9 encoding of s_waitcnt:
+// vmcnt in bits 3:0 and 15:14, expcnt in 6:4, lgkmcnt in 11:8; all ones = no wait on that counter.
+template <int N> __device__ __forceinline__ void wait_vm6()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt has six bits");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+__device__ __forceinline__ void wait_lds6() { __builtin_amdgcn_s_waitcnt(15 | (3 << 14) | (7 << 4) | (0 << 8)); }
+
+// Tile of 128 tokens x 128 CI channels (CI = 2, 3 or 4); wavefront w: all 128 tokens x the 32 CI channels
+// n0 + 32 CI w ..., i.e. CI x 4 matrix tiles.  The weights are the first operand: a lane ends with one token
+// (l % 32) and, per matrix tile, the channels 8 (v / 4) + 4 (l / 32) + v % 4 in register v.
+// LDS: kRing stages of token images, then a staging region per wavefront for the epilogue.
 template <int CI>
 __device__ __forceinline__ void f6_tile(const uint8_t* __restrict__ x6, const uint8_t* __restrict__ w6,
                                         const float* __restrict__ sw, float sx, int M, int N, int K, int m0, int n0,
@@ -134,158 +201,197 @@ __device__ __forceinline__ void f6_tile(const uint8_t* __restrict__ x6, const ui
     extern __shared__ __align__(16) uint8_t smem[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int wr = wave >> 1, wc = wave & 1;
-    constexpr int kWB = 2 * CI;                          // weight row blocks of the tile; 8 token row blocks follow
-    constexpr int kStageF6 = (kWB + 8) * kChunkF6;       // 48, 42 or 36 KiB
-    constexpr int kPieces = (kWB + 8) * 3;               // 1 KiB pieces of a stage
-    constexpr int kLoads = (kPieces + 3) / 4;            // direct loads per wavefront per stage: 12, 11 or 9 (CI = 3:
-                                                         // 42 pieces, two wavefronts repeat the last one)
-    constexpr int NM = 4 * CI;                           // matrix instructions of a step
-    const int KS = K >> 6, nk = K >> 7;
+    const uint32_t l16 = (uint32_t)lane * 16u, l8 = (uint32_t)lane * 8u;   // unsigned: scalar base + 32-bit lane offset
+    constexpr int R = kRing;
+    constexpr int VB = 4 * CI;                           // register loads of a wavefront per stage (weights)
+    constexpr int V = VB + kLoadsA;                      // vector memory operations of a wavefront per stage
+    const int nk = K >> 7;
     const int RBX = (M + 31) >> 5, RBW = (N + 31) >> 5;
 
-    // loader: load q = wave + 4 t of a stage is part q % 3 (1 KiB) of chunk q / 3
-    uint32_t goff[kLoads];
-    bool is_w[kLoads];
+    // ---- tokens: piece q = wave + 4 t of a stage is KiB q % 3 of token block q / 3
+    uint32_t aoff[kLoadsA];
 #pragma unroll
-    for (int t = 0; t < kLoads; ++t) {
-        const int q = wave + 4 * t < kPieces ? wave + 4 * t : kPieces - 1, chunk = q / 3, part = q % 3;
-        int rb = chunk < kWB ? (n0 >> 5) + chunk : (m0 >> 5) + chunk - kWB;
-        const int last = chunk < kWB ? RBW - 1 : RBX - 1;
-        rb = rb < last ? rb : last;
-        is_w[t] = chunk < kWB;
-        goff[t] = (uint32_t)rb * (uint32_t)KS * (uint32_t)kStep + part * 1024 + lane * 16;
+    for (int t = 0; t < kLoadsA; ++t) {
+        const int q = wave + 4 * t, j = q / 3, part = q % 3;
+        int rb = (m0 >> 5) + j;
+        rb = rb < RBX - 1 ? rb : RBX - 1;
+        aoff[t] = (uint32_t)rb * (uint32_t)nk * (uint32_t)kChunkF6 + part * 1024 + l16;
     }
-    auto load_stage = [&](int kt, int buf) {
-        const int k = kt < nk ? kt : nk - 1;
+    const uint32_t lds_ring = (uint32_t)(uintptr_t)PQ6_LDS(smem);
+    auto load_a = [&](int t, int kt, int slot) {
+        const int k = kt < nk ? kt : nk - 1;            // (past the last stage: harmless re-reads)
+        lds_dma16(x6 + (size_t)k * kChunkF6, aoff[t], lds_ring + slot * kStageA + (wave + 4 * t) * 1024);
+    };
+    // ---- weights: the wavefront's own CI row blocks, a block of a stage as four loads (its four planes)
+    const uint8_t* wrow[CI];
 #pragma unroll
-        for (int t = 0; t < kLoads; ++t) {
-            const int q = wave + 4 * t < kPieces ? wave + 4 * t : kPieces - 1;
-            const uint8_t* src = (is_w[t] ? w6 : x6) + (size_t)goff[t] + (size_t)k * kChunkF6;
-            __builtin_amdgcn_global_load_lds(PQ6_GLB(src), PQ6_LDS(smem + buf * kStageF6 + q * 1024), 16, 0, 0);
+    for (int i = 0; i < CI; ++i) {
+        int rb = (n0 >> 5) + wave * CI + i;
+        rb = rb < RBW - 1 ? rb : RBW - 1;
+        wrow[i] = w6 + (size_t)rb * (size_t)nk * kChunkF6;
+    }
+    v8i bw[R][2][CI];                                    // [ring slot][step][row block]; six dwords of each count
+    auto load_b = [&](auto slotc, auto stepc, auto ic, int kt) {
+        constexpr int slot = decltype(slotc)::value, st = decltype(stepc)::value, i = decltype(ic)::value;
+        const int k = kt < nk ? kt : nk - 1;
+        const uint8_t* blk = wrow[i] + (size_t)k * kChunkF6;
+        v8i& d = bw[slot][st][i];
+        if constexpr (st == 0) {
+            const v4i t = *reinterpret_cast<const v4i*>(blk + kP0 + l16);
+            const v2i u = *reinterpret_cast<const v2i*>(blk + kP1 + l8);
+            d[0] = t.x; d[1] = t.y; d[2] = t.z; d[3] = t.w; d[4] = u.x; d[5] = u.y;
+        } else {
+            const v2i u = *reinterpret_cast<const v2i*>(blk + kP2 + l8);
+            const v4i t = *reinterpret_cast<const v4i*>(blk + kP3 + l16);
+            d[0] = u.x; d[1] = u.y; d[2] = t.x; d[3] = t.y; d[4] = t.z; d[5] = t.w;
         }
     };
-    v16f acc[CI][4];
+    // ---- token images of one step from LDS: two reads per image
+    auto read_a = [&](int slot, int st, int j, int kind, v8i (&a)[kTokBlocks]) {
+        const uint8_t* blk = smem + slot * kStageA + j * kChunkF6;
+        v8i& d = a[j];
+        if (st == 0) {
+            if (kind == 0) {
+                const v4i t = *(__attribute__((address_space(3))) const v4i*)(blk + kP0 + lane * 16);
+                d[0] = t.x; d[1] = t.y; d[2] = t.z; d[3] = t.w;
+            } else {
+                const v2i u = *(__attribute__((address_space(3))) const v2i*)(blk + kP1 + lane * 8);
+                d[4] = u.x; d[5] = u.y;
+            }
+        } else {
+            if (kind == 0) {
+                const v4i t = *(__attribute__((address_space(3))) const v4i*)(blk + kP3 + lane * 16);
+                d[2] = t.x; d[3] = t.y; d[4] = t.z; d[5] = t.w;
+            } else {
+                const v2i u = *(__attribute__((address_space(3))) const v2i*)(blk + kP2 + lane * 8);
+                d[0] = u.x; d[1] = u.y;
+            }
+        }
+    };
+
+    v16f acc[CI][kTokBlocks];
 #pragma unroll
     for (int i = 0; i < CI; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < kTokBlocks; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+    v8i a0[kTokBlocks], a1[kTokBlocks];                  // token images of the first / second step
+#pragma unroll
+    for (int j = 0; j < kTokBlocks; ++j) { a0[j] = (v8i){0, 0, 0, 0, 0, 0, 0, 0}; a1[j] = a0[j]; }
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int st = 0; st < 2; ++st)
+#pragma unroll
+            for (int i = 0; i < CI; ++i) bw[r][st][i] = (v8i){0, 0, 0, 0, 0, 0, 0, 0};
 
-    // One of the 2 (CI + 4) LDS reads that fetch the images of a 64-channel step: piece p = 2 * operand +
-    // kind, operands 0..CI-1 = weights (the row blocks of this wavefront), CI..CI+3 = tokens; kind 0 = the
-    // 16-byte part of the image, 1 = the 8-byte part.  First step: bytes 0..23 of a lane's 48 (16 + 8),
-    // second step: bytes 24..47 (8 + 16).
-    constexpr int NP = 2 * (CI + 4);
-    auto read_piece = [&](int buf, int s, int p, v8i (&a)[CI], v8i (&b)[4]) {
-        const int o = p >> 1, kind = p & 1;
-        const int chunk = o < CI ? wr * CI + o : kWB + wc * 4 + (o - CI);
-        const uint8_t* src = smem + buf * kStageF6 + lane * 48 + chunk * kChunkF6;
-        v8i& d = o < CI ? a[o < CI ? o : 0] : b[o < CI ? 0 : o - CI];
-        if (kind == 0) {
-            const v4i t = *(__attribute__((address_space(3))) const v4i*)(src + (s ? 32 : 0));
-            if (s == 0) { d[0] = t.x; d[1] = t.y; d[2] = t.z; d[3] = t.w; }
-            else { d[2] = t.x; d[3] = t.y; d[4] = t.z; d[5] = t.w; }
-        } else {
-            const v2i t = *(__attribute__((address_space(3))) const v2i*)(src + (s ? 24 : 16));
-            if (s == 0) { d[4] = t.x; d[5] = t.y; }
-            else { d[0] = t.x; d[1] = t.y; }
-        }
-    };
-    auto read_images = [&](int buf, int s, v8i (&a)[CI], v8i (&b)[4]) {
-#pragma unroll
-        for (int p = 0; p < NP; ++p) read_piece(buf, s, p, a, b);
-    };
-    // One step: NM matrix instructions on the images (ca, cb); between them the reads of the next step's
-    // images into (na, nb), spread over the first half of the instructions, and the direct loads of the
-    // refill, spread over the last three quarters (a wavefront issues in order: what overlaps the matrix
-    // pipe has to sit between its instructions).
-    auto step = [&](const v8i (&ca)[CI], const v8i (&cb)[4], int rbuf, int rs, v8i (&na)[CI], v8i (&nb)[4], bool refill,
-                    int refill_kt, int refill_buf) {
-        constexpr int RS = NM / 2, D0 = NM / 4, DS = NM - D0;
-#pragma unroll
-        for (int n = 0; n < NM; ++n) {
-            const int i = n >> 2, j = n & 3;   // formats 3, 3: E3M2 both; scale bytes 127 = 2^0
-            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ca[i], cb[j], acc[i][j], 3, 3, 0, 127, 0, 127);
-            if (n < RS) {
-#pragma unroll
-                for (int p = n * NP / RS; p < (n + 1) * NP / RS; ++p) read_piece(rbuf, rs, p, na, nb);
+    // One step of a stage: CI x 4 matrix instructions, row block by row block.  Between them: the LDS
+    // reads of the other step's token images (one per instruction, first eight), the refill of this
+    // step's weight images for stage kt + R (right behind the last instruction that reads an image), and
+    // in the second step the refill of the stage's LDS slot.  A wavefront issues in order: what is to
+    // overlap the matrix pipe has to sit between its instructions.
+    auto step = [&](auto slotc, auto stepc, int kt) {
+        constexpr int slot = decltype(slotc)::value, st = decltype(stepc)::value;
+        constexpr int rslot = st == 0 ? slot : (slot + 1) % R;      // where the other step's token images lie
+        static_for6<0, CI * kTokBlocks>([&](auto nc) {
+            constexpr int n = decltype(nc)::value, i = n / kTokBlocks, j = n % kTokBlocks;
+            // formats 3, 3: E3M2 both; scale bytes 127 = 2^0
+            if constexpr (st == 0)
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(bw[slot][0][i], a0[j], acc[i][j], 3, 3, 0, 127, 0, 127);
+            else
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(bw[slot][1][i], a1[j], acc[i][j], 3, 3, 0, 127, 0, 127);
+            if constexpr (n < 2 * kTokBlocks) {
+                if constexpr (st == 0) read_a(rslot, 1, n >> 1, n & 1, a1);
+                else read_a(rslot, 0, n >> 1, n & 1, a0);
             }
-            if (refill && n >= D0) {
-#pragma unroll
-                for (int t = (n - D0) * kLoads / DS; t < (n - D0 + 1) * kLoads / DS; ++t) {
-                    const int q = wave + 4 * t < kPieces ? wave + 4 * t : kPieces - 1;
-                    const int k = refill_kt < nk ? refill_kt : nk - 1;
-                    const uint8_t* src = (is_w[t] ? w6 : x6) + (size_t)goff[t] + (size_t)k * kChunkF6;
-                    __builtin_amdgcn_global_load_lds(PQ6_GLB(src), PQ6_LDS(smem + refill_buf * kStageF6 + q * 1024), 16, 0, 0);
-                }
-            }
+            if constexpr (st == 1 && n < kLoadsA) load_a(n, kt + R, slot);
+            if constexpr (j == kTokBlocks - 1)
+                load_b(std::integral_constant<int, slot>{}, std::integral_constant<int, st>{}, std::integral_constant<int, i>{}, kt + R);
             __builtin_amdgcn_sched_barrier(0);
-        }
+        });
     };
-
-    // ---- prologue: fill the ring, read the first step's images
-#pragma unroll
-    for (int st = 0; st < kRing; ++st) load_stage(st, st);
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((kRing - 1) * kLoads) : "memory");
-    asm volatile("s_barrier" ::: "memory");
-    v8i pa[CI], pb[4], qa[CI], qb[4];     // (only the first six dwords of an image count; the rest stays zero)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) { pb[i] = (v8i){0, 0, 0, 0, 0, 0, 0, 0}; qb[i] = pb[i]; }
-#pragma unroll
-    for (int i = 0; i < CI; ++i) { pa[i] = (v8i){0, 0, 0, 0, 0, 0, 0, 0}; qa[i] = pa[i]; }
-    read_images(0, 0, pa, pb);
-
-    // ---- main loop: while one step multiplies, the next step's images are read; a stage's buffer is
-    // free once every wavefront has read its second step, which is where the barrier sits
-    int buf = 0;
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    for (int kt = 0; kt < nk; ++kt) {
-        // first step of stage kt; its second step's images are read meanwhile
-        step(pa, pb, buf, 1, qa, qb, false, 0, 0);
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((kRing - 2) * kLoads) : "memory");   // own loads of stage kt + 1 landed
+    auto stage = [&](auto slotc, int kt) {
+        constexpr int slot = decltype(slotc)::value;
+        step(std::integral_constant<int, slot>{}, std::integral_constant<int, 0>{}, kt);
+        // The token images of stage kt + 1 were requested in the second step of stage kt + 1 - R; behind
+        // them this wavefront has issued the second-step weights of that stage (2 CI), R - 2 whole stages
+        // and the first-step weights of this one (2 CI).  (In the first R - 1 stages more lies behind
+        // them, so the count is only stricter than needed there.)
+        wait_lds6();
+        wait_vm6<4 * CI + (R - 2) * V>();
         asm volatile("s_barrier" ::: "memory");          // all have read stage kt; all of stage kt + 1 is in LDS
         __builtin_amdgcn_sched_barrier(0);
-        // second step; the next stage's first images are read and the freed buffer is refilled meanwhile
-        const int nbuf = buf + 1 == kRing ? 0 : buf + 1;
-        step(qa, qb, nbuf, 0, pa, pb, true, kt + kRing, buf);   // (past the last stage: harmless re-reads)
-        buf = nbuf;
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // no direct load may still be writing LDS at the end
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    asm volatile("s_barrier" ::: "memory");              // the ring is free: every wavefront is past its last read
+        step(std::integral_constant<int, slot>{}, std::integral_constant<int, 1>{}, kt);
+        wait_lds6();
+        __builtin_amdgcn_sched_barrier(0);
+    };
 
-    // ---- epilogue: out = fp16(fp32(256 acc) * (sw[n] * (sx / 256))), the tiled kernel's expression.
+    // ---- prologue: fill both rings, read the first step's token images
+    // (the waits below count loads in program order: every stage's group is pinned in place)
+    static_for6<0, R>([&](auto rc) {
+        constexpr int r = decltype(rc)::value;
+#pragma unroll
+        for (int t = 0; t < kLoadsA; ++t) load_a(t, r, r);
+        static_for6<0, CI>([&](auto ic) {
+            load_b(std::integral_constant<int, r>{}, std::integral_constant<int, 0>{}, ic, r);
+            load_b(std::integral_constant<int, r>{}, std::integral_constant<int, 1>{}, ic, r);
+        });
+        __builtin_amdgcn_sched_barrier(0);
+    });
+    wait_vm6<(R - 1) * V>();                             // stage 0 has landed (tokens: this wavefront's pieces)
+    asm volatile("s_barrier" ::: "memory");
+#pragma unroll
+    for (int p = 0; p < 2 * kTokBlocks; ++p) read_a(0, 0, p >> 1, p & 1, a0);
+    wait_lds6();
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- main loop; the ring slot of a stage is a compile-time constant (its weights live in registers)
+    int kt = 0;
+    for (; kt + 3 <= nk; kt += 3) {
+        stage(std::integral_constant<int, 0>{}, kt);
+        stage(std::integral_constant<int, 1 % R>{}, kt + 1);
+        stage(std::integral_constant<int, 2 % R>{}, kt + 2);
+    }
+    if (kt < nk) {
+        stage(std::integral_constant<int, 0>{}, kt);
+        if (kt + 1 < nk) stage(std::integral_constant<int, 1 % R>{}, kt + 1);
+    }
+    static_assert(R == 3, "the main loop is unrolled for a ring of three stages");
+    wait_vm6<0>();                                       // no direct load may still be writing LDS at the end
+
+    // ---- epilogue: out = fp16(fp32(256 acc) * (sw[n] * (sx / 256))), the INT8 tiled kernel's expression.
     // A lane owns one token and groups of four channels; stored like that one instruction would touch 32
-    // token rows with 8 bytes each.  Each wavefront turns its 32 tokens x 128 channels through a private,
-    // padded LDS region and stores whole rows of 64 CI contiguous bytes.
+    // token rows with 8 bytes each.  Each wavefront turns its 32 tokens x 32 CI channels through a private,
+    // padded LDS region (behind the ring, so a wavefront that is ahead may already refill the ring for the
+    // workgroup's next tile) and stores whole rows of 64 CI contiguous bytes.
     const int g = lane >> 5, r = lane & 31;
     const float f = sx * (1.0f / 256.0f);
     constexpr int kRowPitch = 64 * CI + 16;
-    uint8_t* stg = smem + wave * (32 * kRowPitch);
+    uint8_t* stg = smem + R * kStageA + wave * (32 * kRowPitch);
+    const int nw = n0 + wave * (32 * CI);
     float4 sc[CI][4];
+    if (out) {
 #pragma unroll
-    for (int i = 0; i < CI; ++i)
+        for (int i = 0; i < CI; ++i)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            int n = n0 + (wr * CI + i) * 32 + 8 * q + 4 * g;
-            n = n + 4 <= N ? n : N - 4;
-            sc[i][q] = *reinterpret_cast<const float4*>(sw + n);
-            sc[i][q].x *= f; sc[i][q].y *= f; sc[i][q].z *= f; sc[i][q].w *= f;
-        }
+            for (int q = 0; q < 4; ++q) {
+                int n = nw + i * 32 + 8 * q + 4 * g;
+                n = n + 4 <= N ? n : N - 4;
+                sc[i][q] = *reinterpret_cast<const float4*>(sw + n);
+                sc[i][q].x *= f; sc[i][q].y *= f; sc[i][q].z *= f; sc[i][q].w *= f;
+            }
+    }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int mb = m0 + (wc * 4 + j) * 32;
+    for (int j = 0; j < kTokBlocks; ++j) {
+        const int mb = m0 + j * 32;
         if (acc_out) {
             const int m = mb + r;
 #pragma unroll
             for (int i = 0; i < CI; ++i)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const int n = n0 + (wr * CI + i) * 32 + 8 * q + 4 * g;
+                    const int n = nw + i * 32 + 8 * q + 4 * g;
                     const v4i iv = {(int)acc[i][j][4 * q], (int)acc[i][j][4 * q + 1], (int)acc[i][j][4 * q + 2],
                                     (int)acc[i][j][4 * q + 3]};
                     if (m < M && n + 4 <= N) *reinterpret_cast<v4i*>(acc_out + (int64_t)m * N + n) = iv;
@@ -311,38 +417,36 @@ __device__ __forceinline__ void f6_tile(const uint8_t* __restrict__ x6, const ui
             for (int t = 0; t < 2 * CI; ++t) {
                 const int id = 64 * t + lane, row = id / (4 * CI), u = id % (4 * CI);
                 const v4i val = *(__attribute__((address_space(3))) const v4i*)(stg + row * kRowPitch + u * 16);
-                const int m = mb + row, n = n0 + wr * (32 * CI) + u * 8;
+                const int m = mb + row, n = nw + u * 8;
                 if (m < M && n + 8 <= N) *reinterpret_cast<v4i*>(out + (int64_t)m * N + n) = val;
             }
         }
     }
 }
 
-template <int CI>
+// Persistent workgroups: workgroup b takes the tiles b, b + G, b + 2 G ... of the list "GM x nA tiles of
+// 128 CA channels, then GM x nB tiles of 128 CB channels" (row tiles fastest; inside a round of G tiles
+// each XCD takes a contiguous run, so the tiles that share a weight panel meet in one L2).  The stores
+// of a tile drain while the workgroup's next tile is already loading.  With GM x nA = GM x nB = the
+// number of CUs every CU computes one tile of each width and none idles through a partial last round
+// (gate/up: 14336 = 16 x 512 + 16 x 384).
+template <int CA, int CB>
 __global__ __launch_bounds__(256) void k_gemm_f6(const uint8_t* __restrict__ x6, const uint8_t* __restrict__ w6,
                                                 const float* __restrict__ sw, float sx, int M, int N, int K,
-                                                int GM, __half* __restrict__ out, int32_t* __restrict__ acc_out)
+                                                int GM, int nA, int nB, __half* __restrict__ out,
+                                                int32_t* __restrict__ acc_out)
 {
-    const int tile = xcd_run(blockIdx.x, gridDim.x);
-    f6_tile<CI>(x6, w6, sw, sx, M, N, K, (tile % GM) * 256, (tile / GM) * (64 * CI), out, acc_out);
-}
-
-// Two tile widths in one launch: the first GM * n1 workgroups take 256-channel tiles of the columns
-// [0, 256 n1), the others 192-channel tiles of the rest.  Workgroups are dispatched in index order, so
-// with GM * n1 = GM * n2 = number of CUs every CU computes one tile of each width and none idles through
-// a partial last round (gate/up: 14336 = 32 x 256 + 32 x 192).
-__global__ __launch_bounds__(256) void k_gemm_f6_dual(const uint8_t* __restrict__ x6, const uint8_t* __restrict__ w6,
-                                                     const float* __restrict__ sw, float sx, int M, int N, int K,
-                                                     int GM, int n1, int n2, __half* __restrict__ out,
-                                                     int32_t* __restrict__ acc_out)
-{
-    const int first = GM * n1;
-    if ((int)blockIdx.x < first) {
-        const int tile = xcd_run(blockIdx.x, first);
-        f6_tile<4>(x6, w6, sw, sx, M, N, K, (tile % GM) * 256, (tile / GM) * 256, out, acc_out);
-    } else {
-        const int tile = xcd_run(blockIdx.x - first, GM * n2);
-        f6_tile<3>(x6, w6, sw, sx, M, N, K, (tile % GM) * 256, n1 * 256 + (tile / GM) * 192, out, acc_out);
+    const int tiles_a = GM * nA, total = tiles_a + GM * nB, G = (int)gridDim.x;
+    for (int base = 0; base < total; base += G) {
+        const int cnt = total - base < G ? total - base : G;
+        if ((int)blockIdx.x >= cnt) break;
+        const int t = base + xcd_run(blockIdx.x, cnt);
+        if (t < tiles_a) {
+            f6_tile<CA>(x6, w6, sw, sx, M, N, K, (t % GM) * 128, (t / GM) * (128 * CA), out, acc_out);
+        } else if constexpr (CB > 0) {
+            const int u = t - tiles_a;
+            f6_tile<CB>(x6, w6, sw, sx, M, N, K, (u % GM) * 128, nA * (128 * CA) + (u / GM) * (128 * CB), out, acc_out);
+        }
     }
 }
 
@@ -397,57 +501,67 @@ int launch_repack_f6(const void* codes, int64_t R, int64_t K, void* out, hipStre
 }
 
 namespace {
-template <int CI>
-int launch_f6(const void* x6, const void* w6, const float* sw, float sx, int64_t M, int64_t N, int64_t K, void* out,
-              int32_t* acc, hipStream_t st)
+constexpr size_t lds_bytes_f6(int ci) { return (size_t)kRing * kStageA + 4 * 32 * (64 * ci + 16); }
+
+template <int CA, int CB>
+int launch_f6(const void* x6, const void* w6, const float* sw, float sx, int64_t M, int64_t N, int64_t K, int nA, int nB,
+              void* out, int32_t* acc, hipStream_t st)
 {
-    const int GM = (int)((M + 255) / 256), GN = (int)((N + 64 * CI - 1) / (64 * CI));
-    constexpr size_t lds = (size_t)kRing * (2 * CI + 8) * kChunkF6;
-    static_assert(lds <= 160 * 1024, "LDS ring too large");
-    static_assert(4 * 32 * (64 * CI + 16) <= lds, "epilogue staging does not fit the ring");
+    const int GM = (int)((M + 127) / 128);
+    const int64_t total = (int64_t)GM * (nA + nB);
+    constexpr size_t lds = lds_bytes_f6(CA > CB ? CA : CB);
+    static_assert(lds <= 160 * 1024, "LDS ring and staging too large");
     static std::atomic<uint64_t> lds_ok{0};
-    if (allow_dynamic_lds(reinterpret_cast<const void*>(k_gemm_f6<CI>), lds, lds_ok) != PQ_OK) return PQ_ERR_HIP;
-    hipLaunchKernelGGL(k_gemm_f6<CI>, dim3((unsigned)(GM * GN)), dim3(256), lds, st, static_cast<const uint8_t*>(x6),
-                       static_cast<const uint8_t*>(w6), sw, sx, (int)M, (int)N, (int)K, GM, static_cast<__half*>(out), acc);
+    if (allow_dynamic_lds(reinterpret_cast<const void*>(k_gemm_f6<CA, CB>), lds, lds_ok) != PQ_OK) return PQ_ERR_HIP;
+    const unsigned grid = (unsigned)(total < kPersistentWorkgroups ? total : kPersistentWorkgroups);
+    hipLaunchKernelGGL((k_gemm_f6<CA, CB>), dim3(grid), dim3(256), lds, st, static_cast<const uint8_t*>(x6),
+                       static_cast<const uint8_t*>(w6), sw, sx, (int)M, (int)N, (int)K, GM, nA, nB,
+                       static_cast<__half*>(out), acc);
     return hip_status(hipGetLastError());
 }
 }  // namespace
 
-// 256 channels per tile unless 128 fill the chip better (rounds of 256 tiles; the narrow tile costs
-// about 0.6 of the wide one), or a mix of 256 and 192 in one launch where that saves a partial round.
-// PQ_GEMM_F6_TILE = 2 or 4 forces one width, 3 the mix where N allows one (sweeps and tests).
+// Channels per tile: 512, 384 or 256 (CI = 4, 3, 2), or a mix of 512 and 384 in one launch where N = 512 a +
+// 384 b; the choice minimises the estimated time of the busiest CU (tiles are dealt round-robin to 256
+// persistent workgroups; a tile costs a fixed part plus a part proportional to its width).
+// pq_set_gemm_f6_tile: 2, 4 force one width, 3 the mix where N allows one (else 384 wide).
 int launch_gemm_f6(const void* x6, const void* w6, const float* sw, float sx, int64_t M, int64_t N, int64_t K, void* out,
                    int32_t* acc, hipStream_t st)
 {
-    const int64_t gm = (M + 255) / 256;
-    const double wide = (double)((gm * ((N + 255) / 256) + 255) / 256) * 1.0;
-    const double narrow = (double)((gm * ((N + 127) / 128) + 255) / 256) * 0.6;
-    int ci = narrow < wide ? 2 : 4;
+    const int64_t gm = (M + 127) / 128;
     const int forced_tile = forced_f6_tile();
-    const bool forced = forced_tile != -1;
-    if (forced_tile == 2 || forced_tile == 4) ci = forced_tile;
-    // mixed widths: 256 n1 + 192 n2 = N; rounds of wide tiles, then rounds of 192-wide ones at 0.75 each
-    if (!forced || forced_tile == 3) {
-        double best = (narrow < wide ? narrow : wide) * 0.97;
-        int b1 = 0, b2 = 0;
-        for (int64_t n2 = 1; 192 * n2 < N; ++n2) {
-            if ((N - 192 * n2) % 256 != 0) continue;
-            const int64_t n1 = (N - 192 * n2) / 256;
-            if (n1 < 1 || gm * (n1 + n2) > (1 << 20)) continue;
-            const double cost = (double)((gm * n1 + 255) / 256) + 0.75 * (double)((gm * n2 + 255) / 256);
-            if (cost < best || (forced && b1 == 0)) { best = cost; b1 = (int)n1; b2 = (int)n2; }
-        }
-        if (b1 > 0) {
-            constexpr size_t lds = (size_t)kRing * 16 * kChunkF6;
-            static std::atomic<uint64_t> lds_ok{0};
-            if (allow_dynamic_lds(reinterpret_cast<const void*>(k_gemm_f6_dual), lds, lds_ok) != PQ_OK) return PQ_ERR_HIP;
-            hipLaunchKernelGGL(k_gemm_f6_dual, dim3((unsigned)(gm * (b1 + b2))), dim3(256), lds, st,
-                               static_cast<const uint8_t*>(x6), static_cast<const uint8_t*>(w6), sw, sx, (int)M, (int)N, (int)K,
-                               (int)gm, b1, b2, static_cast<__half*>(out), acc);
-            return hip_status(hipGetLastError());
+    auto cost_of = [](int ci) { return 0.35 + 0.1625 * ci; };      // relative to a 512-wide tile = 1
+    auto makespan = [&](int64_t tiles_a, double ca, int64_t tiles_b, double cb) {
+        // round-robin over G workgroups: workgroup 0 gets the most tiles; A tiles come first
+        const int64_t G = kPersistentWorkgroups, total = tiles_a + tiles_b;
+        const int64_t mine = (total + G - 1) / G;                  // tiles of workgroup 0: indices 0, G, 2G, ...
+        const int64_t mine_a = (tiles_a + G - 1) / G < mine ? (tiles_a + G - 1) / G : mine;
+        return mine_a * ca + (mine - mine_a) * cb;
+    };
+    int best_ci = 4, best_a = 0, best_b = 0;
+    double best = 1e300;
+    for (int ci = 2; ci <= 4; ++ci) {
+        if (forced_tile != -1 && forced_tile != 3 && forced_tile != ci) continue;
+        const int64_t gn = (N + 128 * ci - 1) / (128 * ci);
+        if (gm * gn > (1 << 24)) continue;
+        const double c = makespan(gm * gn, cost_of(ci), 0, 0.0);
+        if (c < best) { best = c; best_ci = ci; }
+    }
+    if (forced_tile == -1 || forced_tile == 3) {
+        double bar = forced_tile == 3 ? 1e300 : best * 0.97;       // the mixed launch has to win by a margin
+        for (int64_t b = 1; 384 * b < N; ++b) {
+            if ((N - 384 * b) % 512 != 0) continue;
+            const int64_t a = (N - 384 * b) / 512;
+            if (a < 1 || gm * (a + b) > (1 << 24)) continue;
+            const double c = makespan(gm * a, cost_of(4), gm * b, cost_of(3));
+            if (c < bar) { bar = c; best_a = (int)a; best_b = (int)b; }
         }
     }
-    return ci == 2 ? launch_f6<2>(x6, w6, sw, sx, M, N, K, out, acc, st) : launch_f6<4>(x6, w6, sw, sx, M, N, K, out, acc, st);
+    if (best_a > 0) return launch_f6<4, 3>(x6, w6, sw, sx, M, N, K, best_a, best_b, out, acc, st);
+    const int gn = (int)((N + 128 * best_ci - 1) / (128 * best_ci));
+    if (best_ci == 2) return launch_f6<2, 0>(x6, w6, sw, sx, M, N, K, gn, 0, out, acc, st);
+    if (best_ci == 3) return launch_f6<3, 0>(x6, w6, sw, sx, M, N, K, gn, 0, out, acc, st);
+    return launch_f6<4, 0>(x6, w6, sw, sx, M, N, K, gn, 0, out, acc, st);
 }
 
 }  // namespace pq

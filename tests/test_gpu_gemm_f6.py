@@ -3,8 +3,8 @@ pq_w4a4_gemm_f6) against the oracle.
 
 The repacked layout is checked byte for byte against a plain numpy construction written from its
 definition in the header (E3M2 code of every value, 32 values of 6 bits per lane as a little-endian bit
-stream, per lane the images of two steps side by side, 64 lanes per block of 32 rows x 128 channels,
-blocks ordered [row block][group]).  The product's
+stream of 24 bytes, 64 lanes x 2 steps per block of 32 rows x 128 channels stored as four planes, blocks
+ordered [row block][group]).  The product's
 accumulators are the oracle's integer sums bit for bit (fp32 accumulation of such operands is exact),
 the outputs within 1 ulp of the oracle's epilogue and bit-identical to the INT8 tiled kernel's.
 """
@@ -46,7 +46,12 @@ def tiles_by_definition(q):
         words[:, bit // 64] |= v[:, i] << np.uint64(bit % 64)
         if bit % 64 > 58:
             words[:, bit // 64 + 1] |= v[:, i] >> np.uint64(64 - bit % 64)
-    return words.view(np.uint8).reshape(-1)
+    # a block of 32 rows x 128 channels: 64 lanes x 2 steps x 24 bytes, stored as four planes, each lane after
+    # lane: bytes 0-15 of the first step's images, their bytes 16-23, bytes 0-7 of the second step's, their
+    # bytes 8-23
+    img = words.view(np.uint8).reshape(-1, 64, 2, 24)
+    planes = [img[:, :, 0, :16], img[:, :, 0, 16:], img[:, :, 1, :8], img[:, :, 1, 8:]]
+    return np.concatenate([p.reshape(img.shape[0], -1) for p in planes], axis=1).reshape(-1)
 
 
 @pytest.mark.parametrize("R,K", [(32, 128), (33, 256), (100, 1152), (256, 4096), (1, 128)])
