@@ -38,6 +38,7 @@ namespace {
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v2i __attribute__((ext_vector_type(2)));
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
 
 constexpr int kImage = 24, kStep = 64 * kImage, kChunkF6 = 2 * kStep;   // 1536 B per (row block, step); 3072 per stage
 constexpr int kRing = 3;                                                 // stages in flight (LDS slots of the tokens, register sets of the weights)
@@ -189,48 +190,60 @@ template <int N> __device__ __forceinline__ void wait_vm6()
 }
 __device__ __forceinline__ void wait_lds6() { __builtin_amdgcn_s_waitcnt(15 | (3 << 14) | (7 << 4) | (0 << 8)); }
 
-// Tile of 128 tokens x 128 CI channels (CI = 2, 3 or 4); wavefront w: all 128 tokens x the 32 CI channels
-// n0 + 32 CI w ..., i.e. CI x 4 matrix tiles.  The weights are the first operand: a lane ends with one token
-// (l % 32) and, per matrix tile, the channels 8 (v / 4) + 4 (l / 32) + v % 4 in register v.
-// LDS: kRing stages of token images, then a staging region per wavefront for the epilogue.
-template <int CI>
-__device__ __forceinline__ void f6_tile(const uint8_t* __restrict__ x6, const uint8_t* __restrict__ w6,
-                                        const float* __restrict__ sw, float sx, int M, int N, int K, int m0, int n0,
-                                        __half* __restrict__ out, int32_t* __restrict__ acc_out)
+// One workgroup's share of the product: the tiles b, b + G, b + 2 G ... of a list of GM x GN tiles of 128 CI
+// channels that starts at channel n_base (row tiles fastest; inside a round of G tiles each XCD takes a
+// contiguous run, so the tiles that share a weight panel meet in one L2); b = bid, G = workgroups on the list.
+// A tile is 128 tokens x 128 CI channels (CI = 2, 3 or 4); wavefront w holds all 128 tokens x the 32 CI
+// channels n0 + 32 CI w ..., i.e. CI x 4 matrix tiles.  The weights are the first operand: a lane ends with
+// one token (l % 32) and, per matrix tile, the channels 8 (v / 4) + 4 (l / 32) + v % 4 in register v.
+// LDS: kRing stages of token images, a staging region per wavefront for the epilogue, the channel steps.
+// Between two tiles the order is: main loop of tile t, first loads of tile t + G (both rings), epilogue of
+// tile t.  Waits count memory operations in issue order, oldest first: with the next tile's loads issued
+// ahead of this tile's output stores, its first stages never wait for stores, and the stores drain under
+// its main loop.
+template <int CM>
+__device__ __forceinline__ void f6_persistent(const uint8_t* __restrict__ x6, const uint8_t* __restrict__ w6,
+                                              const float* __restrict__ sw, float sx, int M, int N, int K, int GM,
+                                              int GN, int n_base, int bid, int G, __half* __restrict__ out,
+                                              int32_t* __restrict__ acc_out)
 {
     extern __shared__ __align__(16) uint8_t smem[];
+    constexpr int R = kRing;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t l16 = (uint32_t)lane * 16u, l8 = (uint32_t)lane * 8u;   // unsigned: scalar base + 32-bit lane offset
-    constexpr int R = kRing;
-    constexpr int VB = 4 * CI;                           // register loads of a wavefront per stage (weights)
-    constexpr int V = VB + kLoadsA;                      // vector memory operations of a wavefront per stage
     const int nk = K >> 7;
     const int RBX = (M + 31) >> 5, RBW = (N + 31) >> 5;
-
-    // ---- tokens: piece q = wave + 4 t of a stage is KiB q % 3 of token block q / 3
-    uint32_t aoff[kLoadsA];
-#pragma unroll
-    for (int t = 0; t < kLoadsA; ++t) {
-        const int q = wave + 4 * t, j = q / 3, part = q % 3;
-        int rb = (m0 >> 5) + j;
-        rb = rb < RBX - 1 ? rb : RBX - 1;
-        aoff[t] = (uint32_t)rb * (uint32_t)nk * (uint32_t)kChunkF6 + part * 1024 + l16;
-    }
     const uint32_t lds_ring = (uint32_t)(uintptr_t)PQ6_LDS(smem);
+    const int total = GM * GN;
+
+    // tile t of the list: workgroup-uniform
+    auto tile_of = [&](int seq) {             // seq-th tile of this workgroup, -1 past the end
+        const int base = seq * G;
+        if (base >= total) return -1;
+        const int cnt = total - base < G ? total - base : G;
+        return bid < cnt ? base + xcd_run(bid, cnt) : -1;
+    };
+
+    // ---- state of the tile whose loads are in flight / whose main loop runs
+    uint32_t aoff[kLoadsA];                   // tokens: piece q = wave + 4 t of a stage is KiB q % 3 of token block q / 3
+    const uint8_t* wrow[CM];                  // weights: the wavefront's own row blocks
+    v8i bw[R][2][CM];                         // [ring slot][step][row block]; six dwords of each count
+    v8i a0[kTokBlocks], a1[kTokBlocks];       // token images of the first / second step
+    v16f acc[CM][kTokBlocks];
+#pragma unroll
+    for (int j = 0; j < kTokBlocks; ++j) { a0[j] = (v8i){0, 0, 0, 0, 0, 0, 0, 0}; a1[j] = a0[j]; }
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int st = 0; st < 2; ++st)
+#pragma unroll
+            for (int i = 0; i < CM; ++i) bw[r][st][i] = (v8i){0, 0, 0, 0, 0, 0, 0, 0};
+
     auto load_a = [&](int t, int kt, int slot) {
         const int k = kt < nk ? kt : nk - 1;            // (past the last stage: harmless re-reads)
         lds_dma16(x6 + (size_t)k * kChunkF6, aoff[t], lds_ring + slot * kStageA + (wave + 4 * t) * 1024);
     };
-    // ---- weights: the wavefront's own CI row blocks, a block of a stage as four loads (its four planes)
-    const uint8_t* wrow[CI];
-#pragma unroll
-    for (int i = 0; i < CI; ++i) {
-        int rb = (n0 >> 5) + wave * CI + i;
-        rb = rb < RBW - 1 ? rb : RBW - 1;
-        wrow[i] = w6 + (size_t)rb * (size_t)nk * kChunkF6;
-    }
-    v8i bw[R][2][CI];                                    // [ring slot][step][row block]; six dwords of each count
     auto load_b = [&](auto slotc, auto stepc, auto ic, int kt) {
         constexpr int slot = decltype(slotc)::value, st = decltype(stepc)::value, i = decltype(ic)::value;
         const int k = kt < nk ? kt : nk - 1;
@@ -246,207 +259,261 @@ __device__ __forceinline__ void f6_tile(const uint8_t* __restrict__ x6, const ui
             d[0] = u.x; d[1] = u.y; d[2] = t.x; d[3] = t.y; d[4] = t.z; d[5] = t.w;
         }
     };
-    // ---- token images of one step from LDS: two reads per image
+    // token images of one step from LDS: two reads per image
     auto read_a = [&](int slot, int st, int j, int kind, v8i (&a)[kTokBlocks]) {
         const uint8_t* blk = smem + slot * kStageA + j * kChunkF6;
         v8i& d = a[j];
         if (st == 0) {
             if (kind == 0) {
-                const v4i t = *(__attribute__((address_space(3))) const v4i*)(blk + kP0 + lane * 16);
+                const v4i t = *(__attribute__((address_space(3))) const v4i*)(blk + kP0 + l16);
                 d[0] = t.x; d[1] = t.y; d[2] = t.z; d[3] = t.w;
             } else {
-                const v2i u = *(__attribute__((address_space(3))) const v2i*)(blk + kP1 + lane * 8);
+                const v2i u = *(__attribute__((address_space(3))) const v2i*)(blk + kP1 + l8);
                 d[4] = u.x; d[5] = u.y;
             }
         } else {
             if (kind == 0) {
-                const v4i t = *(__attribute__((address_space(3))) const v4i*)(blk + kP3 + lane * 16);
+                const v4i t = *(__attribute__((address_space(3))) const v4i*)(blk + kP3 + l16);
                 d[2] = t.x; d[3] = t.y; d[4] = t.z; d[5] = t.w;
             } else {
-                const v2i u = *(__attribute__((address_space(3))) const v2i*)(blk + kP2 + lane * 8);
+                const v2i u = *(__attribute__((address_space(3))) const v2i*)(blk + kP2 + l8);
                 d[0] = u.x; d[1] = u.y;
             }
         }
     };
 
-    v16f acc[CI][kTokBlocks];
-#pragma unroll
-    for (int i = 0; i < CI; ++i)
-#pragma unroll
-        for (int j = 0; j < kTokBlocks; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-    v8i a0[kTokBlocks], a1[kTokBlocks];                  // token images of the first / second step
-#pragma unroll
-    for (int j = 0; j < kTokBlocks; ++j) { a0[j] = (v8i){0, 0, 0, 0, 0, 0, 0, 0}; a1[j] = a0[j]; }
-#pragma unroll
-    for (int r = 0; r < R; ++r)
-#pragma unroll
-        for (int st = 0; st < 2; ++st)
-#pragma unroll
-            for (int i = 0; i < CI; ++i) bw[r][st][i] = (v8i){0, 0, 0, 0, 0, 0, 0, 0};
+    // The channel steps of a tile travel through LDS: requested as the first of the tile's first loads (one
+    // direct load per wavefront: lane l fetches the steps of channels 4 l ... of the wavefront's 32 CI, lanes
+    // past them a clamped address), read back in the epilogue.  Held in registers they would cost 16 CI of
+    // them while the next tile's weight ring is filling, and loaded in the epilogue they would queue behind
+    // that tile's first loads (loads complete in order).  Two regions, used in turn: the next tile's request
+    // is issued before this tile's epilogue reads.
+    const int scales_at = R * kStageA + 4 * 32 * (64 * CM + 16);
+    auto request_scales = [&](int n0, int parity) {
+        int n = n0 + wave * (32 * CM) + 4 * lane;
+        n = n + 4 <= N ? n : N - 4;
+        lds_dma16(reinterpret_cast<const uint8_t*>(sw), (uint32_t)n * 4u, lds_ring + scales_at + parity * 4096 + wave * 1024);
+    };
 
-    // One step of a stage: CI x 4 matrix instructions, row block by row block.  Between them: the LDS
-    // reads of the other step's token images (one per instruction, first eight), the refill of this
-    // step's weight images for stage kt + R (right behind the last instruction that reads an image), and
-    // in the second step the refill of the stage's LDS slot.  A wavefront issues in order: what is to
-    // overlap the matrix pipe has to sit between its instructions.
-    auto step = [&](auto slotc, auto stepc, int kt) {
-        constexpr int slot = decltype(slotc)::value, st = decltype(stepc)::value;
-        constexpr int rslot = st == 0 ? slot : (slot + 1) % R;      // where the other step's token images lie
-        static_for6<0, CI * kTokBlocks>([&](auto nc) {
-            constexpr int n = decltype(nc)::value, i = n / kTokBlocks, j = n % kTokBlocks;
-            // formats 3, 3: E3M2 both; scale bytes 127 = 2^0
-            if constexpr (st == 0)
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(bw[slot][0][i], a0[j], acc[i][j], 3, 3, 0, 127, 0, 127);
-            else
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(bw[slot][1][i], a1[j], acc[i][j], 3, 3, 0, 127, 0, 127);
-            if constexpr (n < 2 * kTokBlocks) {
-                if constexpr (st == 0) read_a(rslot, 1, n >> 1, n & 1, a1);
-                else read_a(rslot, 0, n >> 1, n & 1, a0);
-            }
-            if constexpr (st == 1 && n < kLoadsA) load_a(n, kt + R, slot);
-            if constexpr (j == kTokBlocks - 1)
-                load_b(std::integral_constant<int, slot>{}, std::integral_constant<int, st>{}, std::integral_constant<int, i>{}, kt + R);
+    // ---- first loads of a tile: addresses, then both rings filled stage by stage.  (The waits count loads
+    // in program order: every stage's group is pinned in place.)  Vector memory operations per wavefront
+    // and stage: kLoadsA direct loads to LDS + 4 CI register loads.
+    auto prefetch = [&](int m0, int n0, int parity) {
+        constexpr int CI = CM;
+#pragma unroll
+        for (int t = 0; t < kLoadsA; ++t) {
+            const int q = wave + 4 * t, j = q / 3, part = q % 3;
+            int rb = (m0 >> 5) + j;
+            rb = rb < RBX - 1 ? rb : RBX - 1;
+            aoff[t] = ((uint32_t)rb * (uint32_t)nk * (uint32_t)kChunkF6 + part * 1024) + l16;   // (wavefront-uniform) + lane
+        }
+#pragma unroll
+        for (int i = 0; i < CI; ++i) {
+            int rb = (n0 >> 5) + wave * CI + i;
+            rb = rb < RBW - 1 ? rb : RBW - 1;
+            wrow[i] = w6 + (size_t)rb * (size_t)nk * kChunkF6;
+        }
+        if (out) request_scales(n0, parity);
+        __builtin_amdgcn_sched_barrier(0);
+        static_for6<0, R>([&](auto rc) {
+            constexpr int r = decltype(rc)::value;
+#pragma unroll
+            for (int t = 0; t < kLoadsA; ++t) load_a(t, r, r);
+            static_for6<0, CI>([&](auto ic) {
+                load_b(std::integral_constant<int, r>{}, std::integral_constant<int, 0>{}, ic, r);
+                load_b(std::integral_constant<int, r>{}, std::integral_constant<int, 1>{}, ic, r);
+            });
             __builtin_amdgcn_sched_barrier(0);
         });
     };
-    auto stage = [&](auto slotc, int kt) {
-        constexpr int slot = decltype(slotc)::value;
-        step(std::integral_constant<int, slot>{}, std::integral_constant<int, 0>{}, kt);
-        // The token images of stage kt + 1 were requested in the second step of stage kt + 1 - R; behind
-        // them this wavefront has issued the second-step weights of that stage (2 CI), R - 2 whole stages
-        // and the first-step weights of this one (2 CI).  (In the first R - 1 stages more lies behind
-        // them, so the count is only stricter than needed there.)
-        wait_lds6();
-        wait_vm6<4 * CI + (R - 2) * V>();
-        asm volatile("s_barrier" ::: "memory");          // all have read stage kt; all of stage kt + 1 is in LDS
-        __builtin_amdgcn_sched_barrier(0);
-        step(std::integral_constant<int, slot>{}, std::integral_constant<int, 1>{}, kt);
-        wait_lds6();
-        __builtin_amdgcn_sched_barrier(0);
-    };
 
-    // ---- prologue: fill both rings, read the first step's token images
-    // (the waits below count loads in program order: every stage's group is pinned in place)
-    static_for6<0, R>([&](auto rc) {
-        constexpr int r = decltype(rc)::value;
-#pragma unroll
-        for (int t = 0; t < kLoadsA; ++t) load_a(t, r, r);
-        static_for6<0, CI>([&](auto ic) {
-            load_b(std::integral_constant<int, r>{}, std::integral_constant<int, 0>{}, ic, r);
-            load_b(std::integral_constant<int, r>{}, std::integral_constant<int, 1>{}, ic, r);
-        });
-        __builtin_amdgcn_sched_barrier(0);
-    });
-    wait_vm6<(R - 1) * V>();                             // stage 0 has landed (tokens: this wavefront's pieces)
-    asm volatile("s_barrier" ::: "memory");
-#pragma unroll
-    for (int p = 0; p < 2 * kTokBlocks; ++p) read_a(0, 0, p >> 1, p & 1, a0);
-    wait_lds6();
-    __builtin_amdgcn_sched_barrier(0);
-
-    // ---- main loop; the ring slot of a stage is a compile-time constant (its weights live in registers)
-    int kt = 0;
-    for (; kt + 3 <= nk; kt += 3) {
-        stage(std::integral_constant<int, 0>{}, kt);
-        stage(std::integral_constant<int, 1 % R>{}, kt + 1);
-        stage(std::integral_constant<int, 2 % R>{}, kt + 2);
-    }
-    if (kt < nk) {
-        stage(std::integral_constant<int, 0>{}, kt);
-        if (kt + 1 < nk) stage(std::integral_constant<int, 1 % R>{}, kt + 1);
-    }
-    static_assert(R == 3, "the main loop is unrolled for a ring of three stages");
-    wait_vm6<0>();                                       // no direct load may still be writing LDS at the end
-
-    // ---- epilogue: out = fp16(fp32(256 acc) * (sw[n] * (sx / 256))), the INT8 tiled kernel's expression.
-    // A lane owns one token and groups of four channels; stored like that one instruction would touch 32
-    // token rows with 8 bytes each.  Each wavefront turns its 32 tokens x 32 CI channels through a private,
-    // padded LDS region (behind the ring, so a wavefront that is ahead may already refill the ring for the
-    // workgroup's next tile) and stores whole rows of 64 CI contiguous bytes.
-    const int g = lane >> 5, r = lane & 31;
-    const float f = sx * (1.0f / 256.0f);
-    constexpr int kRowPitch = 64 * CI + 16;
-    uint8_t* stg = smem + R * kStageA + wave * (32 * kRowPitch);
-    const int nw = n0 + wave * (32 * CI);
-    float4 sc[CI][4];
-    if (out) {
+    // ---- main loop of a tile whose first loads have been issued
+    auto compute = [&](int parity) {
+        constexpr int CI = CM;
+        constexpr int V = 4 * CI + kLoadsA;                  // vector memory operations of a wavefront per stage
 #pragma unroll
         for (int i = 0; i < CI; ++i)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                int n = nw + i * 32 + 8 * q + 4 * g;
-                n = n + 4 <= N ? n : N - 4;
-                sc[i][q] = *reinterpret_cast<const float4*>(sw + n);
-                sc[i][q].x *= f; sc[i][q].y *= f; sc[i][q].z *= f; sc[i][q].w *= f;
-            }
-    }
+            for (int j = 0; j < kTokBlocks; ++j)
 #pragma unroll
-    for (int j = 0; j < kTokBlocks; ++j) {
-        const int mb = m0 + j * 32;
-        if (acc_out) {
-            const int m = mb + r;
-#pragma unroll
-            for (int i = 0; i < CI; ++i)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int n = nw + i * 32 + 8 * q + 4 * g;
-                    const v4i iv = {(int)acc[i][j][4 * q], (int)acc[i][j][4 * q + 1], (int)acc[i][j][4 * q + 2],
-                                    (int)acc[i][j][4 * q + 3]};
-                    if (m < M && n + 4 <= N) *reinterpret_cast<v4i*>(acc_out + (int64_t)m * N + n) = iv;
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+        // One step of a stage: CI x 4 matrix instructions, row block by row block.  Between them: the LDS
+        // reads of the other step's token images (one per instruction, first eight), the refill of this
+        // step's weight images for stage kt + R (right behind the last instruction that reads an image), and
+        // in the second step the refill of the stage's LDS slot.  A wavefront issues in order: what is to
+        // overlap the matrix pipe has to sit between its instructions.
+        auto step = [&](auto slotc, auto stepc, int kt) {
+            constexpr int slot = decltype(slotc)::value, st = decltype(stepc)::value;
+            constexpr int rslot = st == 0 ? slot : (slot + 1) % R;      // where the other step's token images lie
+            static_for6<0, CI * kTokBlocks>([&](auto nc) {
+                constexpr int n = decltype(nc)::value, i = n / kTokBlocks, j = n % kTokBlocks;
+                // formats 3, 3: E3M2 both; scale bytes 127 = 2^0
+                if constexpr (st == 0)
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(bw[slot][0][i], a0[j], acc[i][j], 3, 3, 0, 127, 0, 127);
+                else
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(bw[slot][1][i], a1[j], acc[i][j], 3, 3, 0, 127, 0, 127);
+                if constexpr (n < 2 * kTokBlocks) {
+                    if constexpr (st == 0) read_a(rslot, 1, n >> 1, n & 1, a1);
+                    else read_a(rslot, 0, n >> 1, n & 1, a0);
                 }
+                if constexpr (st == 1 && n < kLoadsA) load_a(n, kt + R, slot);
+                if constexpr (j == kTokBlocks - 1)
+                    load_b(std::integral_constant<int, slot>{}, std::integral_constant<int, st>{}, std::integral_constant<int, i>{}, kt + R);
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        };
+        auto stage = [&](auto slotc, int kt) {
+            constexpr int slot = decltype(slotc)::value;
+            step(std::integral_constant<int, slot>{}, std::integral_constant<int, 0>{}, kt);
+            // The token images of stage kt + 1 were requested in the second step of stage kt + 1 - R; behind
+            // them this wavefront has issued the second-step weights of that stage (2 CI), R - 2 whole stages
+            // and the first-step weights of this one (2 CI).  (In the first R - 1 stages more lies behind
+            // them, the previous tile's output stores included, so there the count is only stricter than needed.)
+            wait_lds6();
+            wait_vm6<4 * CI + (R - 2) * V>();
+            asm volatile("s_barrier" ::: "memory");          // all have read stage kt; all of stage kt + 1 is in LDS
+            __builtin_amdgcn_sched_barrier(0);
+            step(std::integral_constant<int, slot>{}, std::integral_constant<int, 1>{}, kt);
+            wait_lds6();
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        // Stage 0 has landed when all but the (R - 1) V newest operations are complete: behind its own V
+        // operations lie the other R - 1 stages of the first loads and, if a tile preceded, that tile's
+        // output stores (then more than stage 0 is waited for, but never a store: there are at most 8 CI <
+        // (R - 1) V of them).
+        static_assert(8 * CI <= (R - 1) * V, "the first wait of a tile would wait for output stores");
+        wait_vm6<(R - 1) * V>();
+        asm volatile("s_barrier" ::: "memory");
+        if (out && lane < 8 * CI) {
+            // The channel steps have landed (they were requested ahead of stage 0).  Turn them, in place, into
+            // what the epilogue multiplies by: fl(sw * (sx / 256)), the INT8 tiled kernel's factor for its
+            // accumulators of 256 acc, times 256 (exact), so that acc * factor has the same real value, hence
+            // the same rounding, as that kernel's (256 acc) * fl(sw * (sx / 256)).
+            float* mine = reinterpret_cast<float*>(smem + scales_at + parity * 4096 + wave * 1024) + 4 * lane;
+            v4f c = *(__attribute__((address_space(3))) const v4f*)mine;
+            const float f = sx * (1.0f / 256.0f);
+            c.x = mul_rn(c.x, f) * 256.0f; c.y = mul_rn(c.y, f) * 256.0f; c.z = mul_rn(c.z, f) * 256.0f; c.w = mul_rn(c.w, f) * 256.0f;
+            *(__attribute__((address_space(3))) v4f*)mine = c;
         }
-        if (out) {
 #pragma unroll
-            for (int i = 0; i < CI; ++i)
+        for (int p = 0; p < 2 * kTokBlocks; ++p) read_a(0, 0, p >> 1, p & 1, a0);
+        wait_lds6();
+        __builtin_amdgcn_sched_barrier(0);
+        // the ring slot of a stage is a compile-time constant (its weights live in registers)
+        static_assert(R == 3, "the main loop is unrolled for a ring of three stages");
+        int kt = 0;
+        for (; kt + 3 <= nk; kt += 3) {
+            stage(std::integral_constant<int, 0>{}, kt);
+            stage(std::integral_constant<int, 1>{}, kt + 1);
+            stage(std::integral_constant<int, 2>{}, kt + 2);
+        }
+        if (kt < nk) {
+            stage(std::integral_constant<int, 0>{}, kt);
+            if (kt + 1 < nk) stage(std::integral_constant<int, 1>{}, kt + 1);
+        }
+        wait_vm6<0>();      // the loads past the last stage: none may still be writing LDS or registers
+    };
+
+    // ---- epilogue: out = fp16(fp32(acc * factor)) with the factors prepared in LDS: the same real product,
+    // rounded once to fp32 and once to fp16, as the INT8 tiled kernel's fp32(256 acc) * (sw[n] * (sx / 256)).
+    // A lane owns one token and groups of four channels; stored like that one instruction would touch 32
+    // token rows with 8 bytes each.  Each wavefront turns its 32 tokens x 32 CI channels through a private,
+    // padded LDS region (behind the ring, which the next tile's loads are filling meanwhile) and stores
+    // whole rows of 64 CI contiguous bytes.
+    auto epilogue = [&](auto cic, int m0, int n0, int parity) {
+        constexpr int CI = decltype(cic)::value;
+        // (the lane number is taken afresh: kept in a register across the main loop, which uses every one,
+        // the values derived from it would be spilled there and reloaded here, and a reload waits for all
+        // memory operations in flight, the next tile's first loads and this tile's stores included)
+        int lane;
+        asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane));
+        const int g = lane >> 5, r = lane & 31;
+        constexpr int kRowPitch = 64 * CI + 16;
+        uint8_t* stg = smem + R * kStageA + wave * (32 * kRowPitch);
+        const int nw = n0 + wave * (32 * CI);
+        const float* scl = reinterpret_cast<const float*>(smem + scales_at + parity * 4096 + wave * 1024);
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const __half2 lo = __floats2half2_rn(mul_rn(acc[i][j][4 * q] * 256.0f, sc[i][q].x),
-                                                         mul_rn(acc[i][j][4 * q + 1] * 256.0f, sc[i][q].y));
-                    const __half2 hi = __floats2half2_rn(mul_rn(acc[i][j][4 * q + 2] * 256.0f, sc[i][q].z),
-                                                         mul_rn(acc[i][j][4 * q + 3] * 256.0f, sc[i][q].w));
-                    v2i val;
-                    val.x = *reinterpret_cast<const int*>(&lo);
-                    val.y = *reinterpret_cast<const int*>(&hi);
-                    *(__attribute__((address_space(3))) v2i*)(stg + r * kRowPitch + (i * 32 + 8 * q + 4 * g) * 2) = val;
+        for (int j = 0; j < kTokBlocks; ++j) {
+            const int mb = m0 + j * 32;
+            if (acc_out) {
+                const int m = mb + r;
+#pragma unroll
+                for (int i = 0; i < CI; ++i)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int n = nw + i * 32 + 8 * q + 4 * g;
+                        const v4i iv = {(int)acc[i][j][4 * q], (int)acc[i][j][4 * q + 1], (int)acc[i][j][4 * q + 2],
+                                        (int)acc[i][j][4 * q + 3]};
+                        if (m < M && n + 4 <= N) *reinterpret_cast<v4i*>(acc_out + (int64_t)m * N + n) = iv;
+                    }
+            }
+            if (out) {
+#pragma unroll
+                for (int i = 0; i < CI; ++i)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const v4f c = *(__attribute__((address_space(3))) const v4f*)(scl + i * 32 + 8 * q + 4 * g);
+                        const __half2 lo = __floats2half2_rn(mul_rn(acc[i][j][4 * q], c.x), mul_rn(acc[i][j][4 * q + 1], c.y));
+                        const __half2 hi = __floats2half2_rn(mul_rn(acc[i][j][4 * q + 2], c.z), mul_rn(acc[i][j][4 * q + 3], c.w));
+                        v2i val;
+                        val.x = *reinterpret_cast<const int*>(&lo);
+                        val.y = *reinterpret_cast<const int*>(&hi);
+                        *(__attribute__((address_space(3))) v2i*)(stg + r * kRowPitch + (i * 32 + 8 * q + 4 * g) * 2) = val;
+                    }
+                // LDS operations of a wavefront execute in order: the reads below see the writes above, and
+                // the next token block's writes come after these reads.  A pass stores RP whole rows: 4 CI
+                // lanes of 16 bytes per row (CI = 3: 48 of the 64 lanes take part).
+                constexpr int RP = CI == 3 ? 4 : 16 / CI;
+                const int lrow = lane / (4 * CI), lu = lane % (4 * CI);
+                const bool live = lrow < RP && nw + lu * 8 + 8 <= N;
+                __half* dst = out + (int64_t)(mb + lrow) * N + nw + lu * 8;
+                const uint8_t* src = stg + lrow * kRowPitch + lu * 16;
+#pragma unroll
+                for (int t = 0; t < 32 / RP; ++t) {
+                    const v4i val = *(__attribute__((address_space(3))) const v4i*)(src + t * RP * kRowPitch);
+                    if (live && mb + lrow + t * RP < M) *reinterpret_cast<v4i*>(dst + (int64_t)t * RP * N) = val;
                 }
-            // LDS operations of a wavefront execute in order: the reads below see the writes above, and
-            // the next token block's writes come after these reads
-#pragma unroll
-            for (int t = 0; t < 2 * CI; ++t) {
-                const int id = 64 * t + lane, row = id / (4 * CI), u = id % (4 * CI);
-                const v4i val = *(__attribute__((address_space(3))) const v4i*)(stg + row * kRowPitch + u * 16);
-                const int m = mb + row, n = nw + u * 8;
-                if (m < M && n + 8 <= N) *reinterpret_cast<v4i*>(out + (int64_t)m * N + n) = val;
             }
         }
+    };
+
+    auto m0_of = [&](int t) { return (t % GM) * 128; };
+    auto n0_of = [&](int t) { return n_base + (t / GM) * (128 * CM); };
+    int t = tile_of(0);
+    if (t < 0) return;
+    prefetch(m0_of(t), n0_of(t), 0);
+    int next = tile_of(1), parity = 0;
+    for (int seq = 2; next >= 0; ++seq) {
+        compute(parity);
+        prefetch(m0_of(next), n0_of(next), parity ^ 1);
+        epilogue(std::integral_constant<int, CM>{}, m0_of(t), n0_of(t), parity);
+        t = next;
+        next = tile_of(seq);
+        parity ^= 1;
     }
+    compute(parity);
+    epilogue(std::integral_constant<int, CM>{}, m0_of(t), n0_of(t), parity);
 }
 
-// Persistent workgroups: workgroup b takes the tiles b, b + G, b + 2 G ... of the list "GM x nA tiles of
-// 128 CA channels, then GM x nB tiles of 128 CB channels" (row tiles fastest; inside a round of G tiles
-// each XCD takes a contiguous run, so the tiles that share a weight panel meet in one L2).  The stores
-// of a tile drain while the workgroup's next tile is already loading.  With GM x nA = GM x nB = the
-// number of CUs every CU computes one tile of each width and none idles through a partial last round
-// (gate/up: 14336 = 16 x 512 + 16 x 384).
-template <int CA, int CB>
+// Persistent workgroups, one per CU and list.  MIXED: the first GA workgroups walk a list of GM x nA tiles 512
+// channels wide, the others a list of GM x nB tiles 384 wide behind it; workgroups are dispatched in index
+// order, so with GM x nA = GM x nB = the number of CUs every CU computes one tile of each width and none idles
+// through a partial last round (gate/up: 14336 = 16 x 512 + 16 x 384); a workgroup of the second list starts as
+// soon as one of the first has issued its last stores, and loads while those drain.
+template <int CM, bool MIXED>
 __global__ __launch_bounds__(256) void k_gemm_f6(const uint8_t* __restrict__ x6, const uint8_t* __restrict__ w6,
                                                 const float* __restrict__ sw, float sx, int M, int N, int K,
-                                                int GM, int nA, int nB, __half* __restrict__ out,
+                                                int GM, int nA, int nB, int GA, __half* __restrict__ out,
                                                 int32_t* __restrict__ acc_out)
 {
-    const int tiles_a = GM * nA, total = tiles_a + GM * nB, G = (int)gridDim.x;
-    for (int base = 0; base < total; base += G) {
-        const int cnt = total - base < G ? total - base : G;
-        if ((int)blockIdx.x >= cnt) break;
-        const int t = base + xcd_run(blockIdx.x, cnt);
-        if (t < tiles_a) {
-            f6_tile<CA>(x6, w6, sw, sx, M, N, K, (t % GM) * 128, (t / GM) * (128 * CA), out, acc_out);
-        } else if constexpr (CB > 0) {
-            const int u = t - tiles_a;
-            f6_tile<CB>(x6, w6, sw, sx, M, N, K, (u % GM) * 128, nA * (128 * CA) + (u / GM) * (128 * CB), out, acc_out);
-        }
+    if constexpr (MIXED) {
+        if ((int)blockIdx.x < GA)
+            f6_persistent<CM>(x6, w6, sw, sx, M, N, K, GM, nA, 0, (int)blockIdx.x, GA, out, acc_out);
+        else
+            f6_persistent<CM - 1>(x6, w6, sw, sx, M, N, K, GM, nB, nA * (128 * CM), (int)blockIdx.x - GA,
+                                  (int)gridDim.x - GA, out, acc_out);
+    } else {
+        f6_persistent<CM>(x6, w6, sw, sx, M, N, K, GM, nA, 0, (int)blockIdx.x, (int)gridDim.x, out, acc_out);
     }
 }
 
@@ -501,29 +568,30 @@ int launch_repack_f6(const void* codes, int64_t R, int64_t K, void* out, hipStre
 }
 
 namespace {
-constexpr size_t lds_bytes_f6(int ci) { return (size_t)kRing * kStageA + 4 * 32 * (64 * ci + 16); }
+constexpr size_t lds_bytes_f6(int ci) { return (size_t)kRing * kStageA + 4 * 32 * (64 * ci + 16) + 2 * 4096; }   // ring, staging, channel steps (two regions)
 
-template <int CA, int CB>
+template <int CM, bool MIXED>
 int launch_f6(const void* x6, const void* w6, const float* sw, float sx, int64_t M, int64_t N, int64_t K, int nA, int nB,
               void* out, int32_t* acc, hipStream_t st)
 {
     const int GM = (int)((M + 127) / 128);
-    const int64_t total = (int64_t)GM * (nA + nB);
-    constexpr size_t lds = lds_bytes_f6(CA > CB ? CA : CB);
+    const int64_t ta = (int64_t)GM * nA, tb = (int64_t)GM * nB;
+    const int GA = (int)(ta < kPersistentWorkgroups ? ta : kPersistentWorkgroups);
+    const int GB = (int)(tb < kPersistentWorkgroups ? tb : kPersistentWorkgroups);
+    constexpr size_t lds = lds_bytes_f6(CM);
     static_assert(lds <= 160 * 1024, "LDS ring and staging too large");
     static std::atomic<uint64_t> lds_ok{0};
-    if (allow_dynamic_lds(reinterpret_cast<const void*>(k_gemm_f6<CA, CB>), lds, lds_ok) != PQ_OK) return PQ_ERR_HIP;
-    const unsigned grid = (unsigned)(total < kPersistentWorkgroups ? total : kPersistentWorkgroups);
-    hipLaunchKernelGGL((k_gemm_f6<CA, CB>), dim3(grid), dim3(256), lds, st, static_cast<const uint8_t*>(x6),
-                       static_cast<const uint8_t*>(w6), sw, sx, (int)M, (int)N, (int)K, GM, nA, nB,
+    if (allow_dynamic_lds(reinterpret_cast<const void*>(k_gemm_f6<CM, MIXED>), lds, lds_ok) != PQ_OK) return PQ_ERR_HIP;
+    hipLaunchKernelGGL((k_gemm_f6<CM, MIXED>), dim3((unsigned)(GA + GB)), dim3(256), lds, st, static_cast<const uint8_t*>(x6),
+                       static_cast<const uint8_t*>(w6), sw, sx, (int)M, (int)N, (int)K, GM, nA, nB, GA,
                        static_cast<__half*>(out), acc);
     return hip_status(hipGetLastError());
 }
 }  // namespace
 
 // Channels per tile: 512, 384 or 256 (CI = 4, 3, 2), or a mix of 512 and 384 in one launch where N = 512 a +
-// 384 b; the choice minimises the estimated time of the busiest CU (tiles are dealt round-robin to 256
-// persistent workgroups; a tile costs a fixed part plus a part proportional to its width).
+// 384 b; the choice minimises the estimated time of the busiest CU (a tile costs a fixed part plus a part
+// proportional to its width).
 // pq_set_gemm_f6_tile: 2, 4 force one width, 3 the mix where N allows one (else 384 wide).
 int launch_gemm_f6(const void* x6, const void* w6, const float* sw, float sx, int64_t M, int64_t N, int64_t K, void* out,
                    int32_t* acc, hipStream_t st)
@@ -532,11 +600,9 @@ int launch_gemm_f6(const void* x6, const void* w6, const float* sw, float sx, in
     const int forced_tile = forced_f6_tile();
     auto cost_of = [](int ci) { return 0.35 + 0.1625 * ci; };      // relative to a 512-wide tile = 1
     auto makespan = [&](int64_t tiles_a, double ca, int64_t tiles_b, double cb) {
-        // round-robin over G workgroups: workgroup 0 gets the most tiles; A tiles come first
-        const int64_t G = kPersistentWorkgroups, total = tiles_a + tiles_b;
-        const int64_t mine = (total + G - 1) / G;                  // tiles of workgroup 0: indices 0, G, 2G, ...
-        const int64_t mine_a = (tiles_a + G - 1) / G < mine ? (tiles_a + G - 1) / G : mine;
-        return mine_a * ca + (mine - mine_a) * cb;
+        // each list is dealt round-robin to its (up to) 256 workgroups; a CU hosts one workgroup of each list in turn
+        const int64_t G = kPersistentWorkgroups;
+        return (double)((tiles_a + G - 1) / G) * ca + (double)((tiles_b + G - 1) / G) * cb;
     };
     int best_ci = 4, best_a = 0, best_b = 0;
     double best = 1e300;
@@ -557,11 +623,11 @@ int launch_gemm_f6(const void* x6, const void* w6, const float* sw, float sx, in
             if (c < bar) { bar = c; best_a = (int)a; best_b = (int)b; }
         }
     }
-    if (best_a > 0) return launch_f6<4, 3>(x6, w6, sw, sx, M, N, K, best_a, best_b, out, acc, st);
+    if (best_a > 0) return launch_f6<4, true>(x6, w6, sw, sx, M, N, K, best_a, best_b, out, acc, st);
     const int gn = (int)((N + 128 * best_ci - 1) / (128 * best_ci));
-    if (best_ci == 2) return launch_f6<2, 0>(x6, w6, sw, sx, M, N, K, gn, 0, out, acc, st);
-    if (best_ci == 3) return launch_f6<3, 0>(x6, w6, sw, sx, M, N, K, gn, 0, out, acc, st);
-    return launch_f6<4, 0>(x6, w6, sw, sx, M, N, K, gn, 0, out, acc, st);
+    if (best_ci == 2) return launch_f6<2, false>(x6, w6, sw, sx, M, N, K, gn, 0, out, acc, st);
+    if (best_ci == 3) return launch_f6<3, false>(x6, w6, sw, sx, M, N, K, gn, 0, out, acc, st);
+    return launch_f6<4, false>(x6, w6, sw, sx, M, N, K, gn, 0, out, acc, st);
 }
 
 }  // namespace pq
