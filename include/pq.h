@@ -183,8 +183,9 @@ int pq_probe_f6_product(const int8_t* a_codes, const int8_t* b_codes, int64_t K,
  * accumulators are the integer sums of pq_w4a4_gemm, bit for bit, and so are the outputs.  The
  * instruction has twice the nominal rate of the INT8 one.  Both operands are repacked first:
  * pq_repack_f6: codes_packed [rows,K/2] uint8 canonical -> `tiles`, pq_f6_tiles_bytes(rows,K) bytes:
- *   one block of 3072 bytes for every 32 rows and every 128 channels, blocks ordered [rb][128-channel
- *   group kt].  A block holds, for each of 64 lanes l and each of the instruction's two 64-channel steps
+ *   one block of 3072 bytes for every 32 rows and every 128 channels, blocks ordered [128-channel group
+ *   kt][row block rb] (what a launch reads at one time, the same channels of many rows, lies side by
+ *   side).  A block holds, for each of 64 lanes l and each of the instruction's two 64-channel steps
  *   s, a register image of 24 bytes: row 32 rb + l % 32, channels 128 kt + 64 s + 32 (l / 32) + 0..31 as a
  *   little-endian stream of 6-bit values (rows past the end are zero).  The images are stored as four
  *   planes, each lane after lane: bytes 0-15 of the first step's images (64 x 16 bytes), their bytes

@@ -631,9 +631,10 @@ int pq_linear_f6(const void* x_f16, const void* w_tiles, const float* w_scale, f
     hipStream_t st = static_cast<hipStream_t>(stream);
     uint8_t* tiles = static_cast<uint8_t*>(workspace);
     uint8_t* nibbles = tiles + ((pq::f6_tiles_bytes(M, K) + 255) & ~(size_t)255);
-    if (had_block <= 1) {
-        // no rotation: one launch quantizes and writes the tiles (and the canonical codes beside them)
-        rc = pq::launch_quant_f6(x_f16, M, K, act_scale, tiles, nibbles, st);
+    if (pq::quant_f6_supported(M, K, had_block)) {
+        // rotation blocks up to 512 channels (or none): one launch rotates, quantizes and writes the tiles (and
+        // the canonical codes beside them)
+        rc = pq::launch_quant_f6(x_f16, M, K, had_block, act_scale, tiles, nibbles, st);
     } else {
         rc = pq_rotate_quant(x_f16, M, K, had_block, act_scale, nibbles, stream);
         if (rc == PQ_OK) rc = pq::launch_repack_f6(nibbles, M, K, tiles, st);

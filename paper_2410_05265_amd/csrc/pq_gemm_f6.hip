@@ -6,7 +6,8 @@
 // chip's power limit.
 //
 // Both operands arrive repacked ("f6 tiles", k_repack_f6): for every block of 32 rows and every 128
-// channels (two steps of the instruction) the register images of a wavefront, 3072 bytes.  The image
+// channels (two steps of the instruction) the register images of a wavefront, 3072 bytes; the blocks of
+// all row blocks for one group of 128 channels lie side by side, group after group.  The image
 // of lane l for step s holds row 32 rb + l % 32 and the 32 channels 64 (2 kt + s) + 32 (l / 32) + i as
 // a little-endian stream of 6-bit values, 24 bytes = six dwords.  A block stores them as four planes,
 // each lane after lane: bytes 0-15 of the first step's images (64 x 16 bytes), their bytes 16-23
@@ -24,6 +25,7 @@
 // right behind the last instruction that uses it): 48 KiB of LDS reads and 12 KiB of writes per 128
 // channels for the same 1024 clocks of matrix work.
 #include <hip/hip_fp16.h>
+#include <math.h>
 #include <stdlib.h>
 
 #include <atomic>
@@ -41,18 +43,11 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 
 constexpr int kImage = 24, kStep = 64 * kImage, kChunkF6 = 2 * kStep;   // 1536 B per (row block, step); 3072 per stage
-constexpr int kRing = 3;                                                 // stages in flight (LDS slots of the tokens, register sets of the weights)
+// stages in flight (LDS slots of the tokens, register sets of the weights); deeper rings for the narrow tiles
+// (6 stages at CI = 2, 4 at CI = 3: the same 144 registers) measured no faster with cold weights and 1-2 us
+// slower per tile with warm ones
+constexpr int ring_of(int) { return 3; }
 constexpr int kPersistentWorkgroups = 256;                               // one per CU
-
-// two's complement nibble -> E3M2 (bias 3): two tables of eight 6-bit entries, for 0..7 and for -8..-1
-__device__ __forceinline__ uint32_t e3m2_of_nibble(uint32_t nib)
-{
-    constexpr uint64_t pos = 0ull | (12ull << 6) | (16ull << 12) | (18ull << 18) | (20ull << 24) | (21ull << 30) | (22ull << 36) |
-                             (23ull << 42);                                            // 0, 1, ..., 7
-    constexpr uint64_t neg = 56ull | (55ull << 6) | (54ull << 12) | (53ull << 18) | (52ull << 24) | (50ull << 30) |
-                             (48ull << 36) | (44ull << 42);                            // -8, -7, ..., -1
-    return (uint32_t)(((nib & 8u) ? neg : pos) >> (6u * (nib & 7u))) & 63u;
-}
 
 // Offsets of the four planes of a block, and an image's 24 bytes (three qwords) into its two planes.
 constexpr int kP0 = 0, kP1 = 1024, kP2 = 1536, kP3 = 2048;
@@ -70,6 +65,44 @@ __device__ __forceinline__ void store_image(uint8_t* block, int lane, int step, 
     }
 }
 
+// Eight packed two's complement nibbles (channel i in bits 4 i ..) -> their eight E3M2 codes as a 48-bit
+// little-endian stream.  The 16-entry table look-up runs on four codes at a time: v_perm_b32 picks bytes
+// of an 8-entry table by the low three bits of each nibble, once from the table of 0..7 and once from that
+// of -8..-1, and bit 3 selects between the two per byte; then bytes are paired into 12-bit and 24-bit runs.
+__device__ __forceinline__ uint64_t e3m2_stream8(uint32_t w)
+{
+    constexpr uint32_t T0 = 0u | (12u << 8) | (16u << 16) | (18u << 24);    // 0, 1, 2, 3
+    constexpr uint32_t T1 = 20u | (21u << 8) | (22u << 16) | (23u << 24);   // 4, 5, 6, 7
+    constexpr uint32_t T2 = 56u | (55u << 8) | (54u << 16) | (53u << 24);   // -8, -7, -6, -5
+    constexpr uint32_t T3 = 52u | (50u << 8) | (48u << 16) | (44u << 24);   // -4, -3, -2, -1
+    auto lut = [](uint32_t x) {      // four nibbles, one per byte -> four codes
+        const uint32_t sel = x & 0x07070707u;
+        const uint32_t a = __builtin_amdgcn_perm(T1, T0, sel);   // selector 0-3: second operand, 4-7: first
+        const uint32_t b = __builtin_amdgcn_perm(T3, T2, sel);
+        const uint32_t m = (x >> 3) & 0x01010101u;
+        const uint32_t mask = (m << 8) - m;                      // 0xFF in every byte whose nibble has bit 3 set
+        return a ^ ((a ^ b) & mask);
+    };
+    const uint32_t ev = lut(w & 0x0F0F0F0Fu);            // codes of channels 0, 2, 4, 6
+    const uint32_t od = lut((w >> 4) & 0x0F0F0F0Fu);     // codes of channels 1, 3, 5, 7
+    // 16-bit lanes: (c0 | c1 << 6), (c2 | c3 << 6) and (c4 | c5 << 6), (c6 | c7 << 6); selector 0x0c = a zero byte
+    const uint32_t a = __builtin_amdgcn_perm(0u, ev, 0x0c010c00u) | (__builtin_amdgcn_perm(0u, od, 0x0c010c00u) << 6);
+    const uint32_t b = __builtin_amdgcn_perm(0u, ev, 0x0c030c02u) | (__builtin_amdgcn_perm(0u, od, 0x0c030c02u) << 6);
+    const uint32_t h0 = (a & 0xFFFu) | ((a >> 4) & 0xFFF000u);   // c0 .. c3: 24 bits
+    const uint32_t h1 = (b & 0xFFFu) | ((b >> 4) & 0xFFF000u);   // c4 .. c7
+    return (uint64_t)h0 | ((uint64_t)h1 << 24);
+}
+
+// 32 codes of one row (16 bytes of packed nibbles) -> their register image, 24 bytes as three qwords.
+__device__ __forceinline__ void image_of_nibbles(const v4i p, uint64_t (&w)[3])
+{
+    const uint64_t s0 = e3m2_stream8((uint32_t)p.x), s1 = e3m2_stream8((uint32_t)p.y);
+    const uint64_t s2 = e3m2_stream8((uint32_t)p.z), s3 = e3m2_stream8((uint32_t)p.w);
+    w[0] = s0 | (s1 << 48);
+    w[1] = (s1 >> 16) | (s2 << 32);
+    w[2] = (s2 >> 32) | (s3 << 16);
+}
+
 // One thread per register image: 32 codes (16 bytes of nibbles) of one row -> 24 bytes.
 __global__ __launch_bounds__(256) void k_repack_f6(const uint8_t* __restrict__ codes, int R, int K, int64_t images,
                                                   uint8_t* __restrict__ out)
@@ -81,65 +114,67 @@ __global__ __launch_bounds__(256) void k_repack_f6(const uint8_t* __restrict__ c
     const int ks = (int)(blk % KS), rb = (int)(blk / KS);
     const int row = rb * 32 + (lane & 31), k0 = ks * 64 + (lane >> 5) * 32;
     uint64_t w[3] = {0, 0, 0};
-    if (row < R) {
-        const v4i p = *reinterpret_cast<const v4i*>(codes + (int64_t)row * (K >> 1) + (k0 >> 1));
-        const uint32_t d[4] = {(uint32_t)p.x, (uint32_t)p.y, (uint32_t)p.z, (uint32_t)p.w};
-#pragma unroll
-        for (int i = 0; i < 32; ++i) {
-            const uint64_t e = e3m2_of_nibble((d[i >> 3] >> (4 * (i & 7))) & 15u);
-            const int bit = 6 * i;
-            w[bit / 64] |= e << (bit % 64);
-            if (bit % 64 > 58) w[bit / 64 + 1] |= e >> (64 - bit % 64);
-        }
-    }
-    store_image(out + ((int64_t)rb * (KS >> 1) + (ks >> 1)) * kChunkF6, lane, ks & 1, w);
+    if (row < R) image_of_nibbles(*reinterpret_cast<const v4i*>(codes + (int64_t)row * (K >> 1) + (k0 >> 1)), w);
+    store_image(out + ((int64_t)(ks >> 1) * ((R + 31) >> 5) + rb) * kChunkF6, lane, ks & 1, w);
 }
 
-// Quantizer for unrotated input that writes f6 tiles directly (one launch instead of quantizer + repack):
-// one thread per register image, i.e. 32 consecutive channels of one token: four times the exact-tie
-// quantizer of the nibble path (the same codes bit for bit), then the same conversion as k_repack_f6.
-// Optionally also stores the canonical nibbles (the layer's workspace contract).
-__global__ __launch_bounds__(256) void k_quant_f6(const __half* __restrict__ x, int R, int K, int64_t images, float mult,
-                                                 float step, uint8_t* __restrict__ out, uint8_t* __restrict__ nibbles)
+// Rotation (blocks of up to 512 channels) + static quantizer that writes f6 tiles: one launch instead of
+// quantizer + repack, loads and stores both in whole cache lines.  A workgroup owns 32 tokens x 512
+// channels, i.e. four blocks of the tiles, 12 KiB that lie side by side.  First every wavefront takes
+// eight of the tokens, one after the other with all eight loads in flight: a lane holds 8 consecutive
+// channels (16 bytes), rotates and quantizes them exactly as pq_rotate_quant does (the same device code,
+// the same codes bit for bit) and leaves the packed dword in LDS.  Then every thread turns two register
+// images (32 channels of a token each) into their 24 bytes and stores them: a wavefront's store covers a
+// whole plane of a block.  Optionally the canonical nibbles go out as well.
+constexpr int kQCols = 512, kQPitch = kQCols / 2 + 16;     // staged row: 256 bytes of nibbles, padded (bank spread)
+
+template <bool EXACT>
+__global__ __launch_bounds__(256) void k_rotate_quant_f6(const __half* __restrict__ x, int M, int K, int log2h,
+                                                        rq::StaticStep steps, uint8_t* __restrict__ tiles,
+                                                        uint8_t* __restrict__ nibbles)
 {
-    const int64_t t0 = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int64_t t = t0 < images ? t0 : images - 1;     // every lane runs the quantizer (it votes across the wavefront)
-    const int KS = K >> 6, lane = (int)(t & 63);
-    const int64_t blk = t >> 6;
-    const int ks = (int)(blk % KS), rb = (int)(blk / KS);
-    const int row = rb * 32 + (lane & 31), k0 = ks * 64 + (lane >> 5) * 32;
-    const bool live = row < R;
-    const __half* src = x + (int64_t)(live ? row : 0) * K + k0;
-    uint32_t d[4];
+    __shared__ __align__(16) uint8_t stage[32 * kQPitch];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int rb = blockIdx.y, chunk0 = blockIdx.x * kQCols;
+    const int64_t krel = K - chunk0;                      // channels from chunk0 to the end of the row
+    v4i raw[8][1];
+    bool live[8][1];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        const v4i raw = *reinterpret_cast<const v4i*>(src + 8 * c);
-        const __half2* h2 = reinterpret_cast<const __half2*>(&raw);
-        float v[8];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float2 f = __half22float2(h2[i]);
-            v[2 * i] = f.x;
-            v[2 * i + 1] = f.y;
-        }
-        d[c] = rq::quant_pack8<true>(v, v, mult, step, 0);
+    for (int r = 0; r < 8; ++r) {
+        const int64_t row = (int64_t)rb * 32 + wave * 8 + r;
+        const bool in = row < M;
+        rq::load_chunk<1>(static_cast<const __half*>(x + (in ? row : 0) * K + chunk0), krel, 0, lane, in, raw[r], live[r]);
     }
-    if (t0 >= images) return;
-    uint64_t w[3] = {0, 0, 0};
-    if (live) {
 #pragma unroll
-        for (int i = 0; i < 32; ++i) {
-            const uint64_t e = e3m2_of_nibble((d[i >> 3] >> (4 * (i & 7))) & 15u);
-            const int bit = 6 * i;
-            w[bit / 64] |= e << (bit % 64);
-            if (bit % 64 > 58) w[bit / 64 + 1] |= e >> (64 - bit % 64);
-        }
-        if (nibbles) {
-            const v4i nb = {(int)d[0], (int)d[1], (int)d[2], (int)d[3]};
-            *reinterpret_cast<v4i*>(nibbles + (int64_t)row * (K >> 1) + (k0 >> 1)) = nb;
+    for (int r = 0; r < 8; ++r) {
+        rq::lds_u32_ptr dst = (rq::lds_u32_ptr)(stage + (wave * 8 + r) * kQPitch);
+        if (!live[r][0]) dst[lane] = 0u;                  // tokens past the end, channels past K: zero codes
+        rq::rotate_quant_regs_with<1, EXACT, 4>(raw[r], live[r], 0, log2h, steps, dst, (rq::lds_f32_ptr) nullptr, lane,
+                                                live[r][0]);
+    }
+    __syncthreads();
+    const int nk = K >> 7, kt = blockIdx.x * 4 + wave;
+    if (kt < nk) {
+        uint8_t* block = tiles + ((int64_t)kt * gridDim.y + rb) * kChunkF6;
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+            const v4i p = *(__attribute__((address_space(3))) const v4i*)(stage + (lane & 31) * kQPitch + wave * 64 + st * 32 +
+                                                                          (lane >> 5) * 16);
+            uint64_t w[3];
+            image_of_nibbles(p, w);
+            store_image(block, lane, st, w);
         }
     }
-    store_image(out + ((int64_t)rb * (KS >> 1) + (ks >> 1)) * kChunkF6, lane, ks & 1, w);
+    if (nibbles) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int id = i * 256 + threadIdx.x, row = id >> 4, c16 = id & 15;
+            const int64_t grow = (int64_t)rb * 32 + row;
+            if (grow < M && chunk0 + c16 * 32 < K)
+                *reinterpret_cast<v4i*>(nibbles + grow * (K >> 1) + (chunk0 >> 1) + c16 * 16) =
+                    *(__attribute__((address_space(3))) const v4i*)(stage + row * kQPitch + c16 * 16);
+        }
+    }
 }
 
 __device__ __forceinline__ int xcd_run(int b, int total)   // each XCD takes a contiguous run of tiles
@@ -196,7 +231,7 @@ __device__ __forceinline__ void wait_lds6() { __builtin_amdgcn_s_waitcnt(15 | (3
 // A tile is 128 tokens x 128 CI channels (CI = 2, 3 or 4); wavefront w holds all 128 tokens x the 32 CI
 // channels n0 + 32 CI w ..., i.e. CI x 4 matrix tiles.  The weights are the first operand: a lane ends with
 // one token (l % 32) and, per matrix tile, the channels 8 (v / 4) + 4 (l / 32) + v % 4 in register v.
-// LDS: kRing stages of token images, a staging region per wavefront for the epilogue, the channel steps.
+// LDS: ring_of(CI) stages of token images, a staging region per wavefront for the epilogue, the channel steps.
 // Between two tiles the order is: main loop of tile t, first loads of tile t + G (both rings), epilogue of
 // tile t.  Waits count memory operations in issue order, oldest first: with the next tile's loads issued
 // ahead of this tile's output stores, its first stages never wait for stores, and the stores drain under
@@ -208,7 +243,7 @@ __device__ __forceinline__ void f6_persistent(const uint8_t* __restrict__ x6, co
                                               int32_t* __restrict__ acc_out)
 {
     extern __shared__ __align__(16) uint8_t smem[];
-    constexpr int R = kRing;
+    constexpr int R = ring_of(CM);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t l16 = (uint32_t)lane * 16u, l8 = (uint32_t)lane * 8u;   // unsigned: scalar base + 32-bit lane offset
@@ -242,12 +277,12 @@ __device__ __forceinline__ void f6_persistent(const uint8_t* __restrict__ x6, co
 
     auto load_a = [&](int t, int kt, int slot) {
         const int k = kt < nk ? kt : nk - 1;            // (past the last stage: harmless re-reads)
-        lds_dma16(x6 + (size_t)k * kChunkF6, aoff[t], lds_ring + slot * kStageA + (wave + 4 * t) * 1024);
+        lds_dma16(x6 + (size_t)k * ((size_t)RBX * kChunkF6), aoff[t], lds_ring + slot * kStageA + (wave + 4 * t) * 1024);
     };
     auto load_b = [&](auto slotc, auto stepc, auto ic, int kt) {
         constexpr int slot = decltype(slotc)::value, st = decltype(stepc)::value, i = decltype(ic)::value;
         const int k = kt < nk ? kt : nk - 1;
-        const uint8_t* blk = wrow[i] + (size_t)k * kChunkF6;
+        const uint8_t* blk = wrow[i] + (size_t)k * ((size_t)RBW * kChunkF6);
         v8i& d = bw[slot][st][i];
         if constexpr (st == 0) {
             const v4i t = *reinterpret_cast<const v4i*>(blk + kP0 + l16);
@@ -305,13 +340,13 @@ __device__ __forceinline__ void f6_persistent(const uint8_t* __restrict__ x6, co
             const int q = wave + 4 * t, j = q / 3, part = q % 3;
             int rb = (m0 >> 5) + j;
             rb = rb < RBX - 1 ? rb : RBX - 1;
-            aoff[t] = ((uint32_t)rb * (uint32_t)nk * (uint32_t)kChunkF6 + part * 1024) + l16;   // (wavefront-uniform) + lane
+            aoff[t] = ((uint32_t)rb * (uint32_t)kChunkF6 + part * 1024) + l16;   // (wavefront-uniform) + lane
         }
 #pragma unroll
         for (int i = 0; i < CI; ++i) {
             int rb = (n0 >> 5) + wave * CI + i;
             rb = rb < RBW - 1 ? rb : RBW - 1;
-            wrow[i] = w6 + (size_t)rb * (size_t)nk * kChunkF6;
+            wrow[i] = w6 + (size_t)rb * kChunkF6;
         }
         if (out) request_scales(n0, parity);
         __builtin_amdgcn_sched_barrier(0);
@@ -399,18 +434,15 @@ __device__ __forceinline__ void f6_persistent(const uint8_t* __restrict__ x6, co
         for (int p = 0; p < 2 * kTokBlocks; ++p) read_a(0, 0, p >> 1, p & 1, a0);
         wait_lds6();
         __builtin_amdgcn_sched_barrier(0);
-        // the ring slot of a stage is a compile-time constant (its weights live in registers)
-        static_assert(R == 3, "the main loop is unrolled for a ring of three stages");
+        // the ring slot of a stage is a compile-time constant (its weights live in registers): the loop body
+        // is R stages, the remaining nk % R stages follow one by one
         int kt = 0;
-        for (; kt + 3 <= nk; kt += 3) {
-            stage(std::integral_constant<int, 0>{}, kt);
-            stage(std::integral_constant<int, 1>{}, kt + 1);
-            stage(std::integral_constant<int, 2>{}, kt + 2);
-        }
-        if (kt < nk) {
-            stage(std::integral_constant<int, 0>{}, kt);
-            if (kt + 1 < nk) stage(std::integral_constant<int, 1>{}, kt + 1);
-        }
+        for (; kt + R <= nk; kt += R)
+            static_for6<0, R>([&](auto uc) { stage(uc, kt + decltype(uc)::value); });
+        const int rem = nk - kt;
+        static_for6<0, R - 1>([&](auto uc) {
+            if (decltype(uc)::value < rem) stage(uc, kt + decltype(uc)::value);
+        });
         wait_vm6<0>();      // the loads past the last stage: none may still be writing LDS or registers
     };
 
@@ -477,8 +509,23 @@ __device__ __forceinline__ void f6_persistent(const uint8_t* __restrict__ x6, co
         }
     };
 
-    auto m0_of = [&](int t) { return (t % GM) * 128; };
-    auto n0_of = [&](int t) { return n_base + (t / GM) * (128 * CM); };
+    // Position of tile t of the list.  Plain order: row tiles fastest, so the 32 tiles an XCD holds at a time are
+    // 2 panels x 16 row tiles when GM = 16: every XCD fetches all tokens, the panels once.  Where the list
+    // divides into blocks of 8 row tiles x 4 panels, an XCD's 32 tiles are such a block: half of the tokens and
+    // 4 panels, which is the smaller sum when a panel is at least as large as a row tile's tokens.
+    const bool blocked = G == kPersistentWorkgroups && (GM % 8) == 0 && (GN % 4) == 0;
+    auto pos_of = [&](int t, int& mt, int& nt) {
+        if (blocked) {
+            const int blk = t >> 5, in = t & 31, rows_of_blocks = GM >> 3;
+            mt = (blk % rows_of_blocks) * 8 + (in & 7);
+            nt = (blk / rows_of_blocks) * 4 + (in >> 3);
+        } else {
+            mt = t % GM;
+            nt = t / GM;
+        }
+    };
+    auto m0_of = [&](int t) { int mt, nt; pos_of(t, mt, nt); return mt * 128; };
+    auto n0_of = [&](int t) { int mt, nt; pos_of(t, mt, nt); return n_base + nt * (128 * CM); };
     int t = tile_of(0);
     if (t < 0) return;
     prefetch(m0_of(t), n0_of(t), 0);
@@ -550,12 +597,26 @@ int set_gemm_f6_tile(int tile)
 
 size_t f6_tiles_bytes(int64_t R, int64_t K) { return (size_t)((R + 31) / 32) * (size_t)(K / 64) * kStep; }
 
-int launch_quant_f6(const void* x, int64_t R, int64_t K, float act_scale, void* out, void* nibbles, hipStream_t st)
+// had_block: 0 or 1 = no rotation, else a power of two up to 512 that divides K (validated by the caller;
+// larger blocks take pq_rotate_quant + repack).  nibbles: NULL, or where the canonical codes go as well.
+bool quant_f6_supported(int64_t R, int64_t K, int32_t h) { return h <= 512 && (K % 128) == 0 && (R + 31) / 32 <= 65535 && K <= (1 << 30); }
+
+int launch_quant_f6(const void* x, int64_t R, int64_t K, int32_t h, float act_scale, void* out, void* nibbles, hipStream_t st)
 {
-    const int64_t images = ((R + 31) / 32) * (K / 64) * 64;
-    hipLaunchKernelGGL(k_quant_f6, dim3((unsigned)((images + 255) / 256)), dim3(256), 0, st, static_cast<const __half*>(x),
-                       (int)R, (int)K, images, (float)(1.0 / (double)act_scale), act_scale, static_cast<uint8_t*>(out),
-                       static_cast<uint8_t*>(nibbles));
+    if (!quant_f6_supported(R, K, h)) return PQ_ERR_UNSUPPORTED;
+    const dim3 grid((unsigned)((K + kQCols - 1) / kQCols), (unsigned)((R + 31) / 32));
+    if (h <= 1) {
+        const rq::StaticStep steps{(float)(1.0 / (double)act_scale), act_scale};
+        hipLaunchKernelGGL(k_rotate_quant_f6<true>, grid, dim3(256), 0, st, static_cast<const __half*>(x), (int)R, (int)K, 0,
+                           steps, static_cast<uint8_t*>(out), static_cast<uint8_t*>(nibbles));
+    } else {
+        int log2h = 0;
+        while ((1 << log2h) < h) ++log2h;
+        // the 1/sqrt(h) of the rotation is folded into the reciprocal step, as in pq_rotate_quant
+        const rq::StaticStep steps{(float)(1.0 / ((double)act_scale * sqrt((double)h))), act_scale};
+        hipLaunchKernelGGL(k_rotate_quant_f6<false>, grid, dim3(256), 0, st, static_cast<const __half*>(x), (int)R, (int)K,
+                           log2h, steps, static_cast<uint8_t*>(out), static_cast<uint8_t*>(nibbles));
+    }
     return hip_status(hipGetLastError());
 }
 
@@ -568,7 +629,7 @@ int launch_repack_f6(const void* codes, int64_t R, int64_t K, void* out, hipStre
 }
 
 namespace {
-constexpr size_t lds_bytes_f6(int ci) { return (size_t)kRing * kStageA + 4 * 32 * (64 * ci + 16) + 2 * 4096; }   // ring, staging, channel steps (two regions)
+constexpr size_t lds_bytes_f6(int ci) { return (size_t)ring_of(ci) * kStageA + 4 * 32 * (64 * ci + 16) + 2 * 4096; }   // ring, staging, channel steps (two regions)
 
 template <int CM, bool MIXED>
 int launch_f6(const void* x6, const void* w6, const float* sw, float sx, int64_t M, int64_t N, int64_t K, int nA, int nB,

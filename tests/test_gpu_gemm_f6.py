@@ -37,9 +37,9 @@ def tiles_by_definition(q):
     qp = np.zeros((RB * 32, K), np.int64)
     qp[:R] = q
     enc = E3M2[np.abs(qp)] | (np.uint64(32) * (qp < 0).astype(np.uint64))
-    # [rb][row in block][group][step][half][i] -> [rb][group][half][row in block][step][i]
+    # [rb][row in block][group][step][half][i] -> [group][rb][half][row in block][step][i]
     # (lane = 32 half + row in block; a lane's two images, first step then second, lie side by side)
-    v = enc.reshape(RB, 32, KS // 2, 2, 2, 32).transpose(0, 2, 4, 1, 3, 5).reshape(-1, 32)
+    v = enc.reshape(RB, 32, KS // 2, 2, 2, 32).transpose(2, 0, 4, 1, 3, 5).reshape(-1, 32)
     words = np.zeros((v.shape[0], 3), dtype=np.uint64)
     for i in range(32):
         bit = 6 * i
