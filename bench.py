@@ -11,10 +11,17 @@ tensors (paper_2410_05265_amd.synth), resident in HBM before the clock starts.  
 the GPU is kept busy for 80 ms with a plain matmul (device_warmup): after host-side preparation the
 chip needs about 40 ms of load to reach its steady clocks, and the step is 5-15 % slower until then.
 
-Prints ONE JSON line: W4A4 linear TOPS for the step, the roofline of the dominant kernel
-(the INT8-MFMA GEMM) from HIP events around its launches inside the timed region, an fp16
-GEMM of the same shapes on the same GPU, the batch-1 decode bandwidth, and the CPU oracle
-timed on a bounded sample.
+The step runs the layer's prepacked path (pq_linear_f6: weights repacked once, offline, into register
+images of the 6-bit floating-point matrix instruction, on which the 4-bit codes multiply exactly): per
+linear one launch that rotates, quantizes and writes the activations' images, and one product launch.
+The two entry points behind pq_linear_f6 are called one after the other so that events can bracket the
+product.  The canonical path (pq_linear: nibble-packed weights as they are, INT8 matrix instruction) is
+timed beside it.
+
+Prints ONE JSON line: W4A4 linear TOPS for the step (median of REPEATS timed regions of --steps steps),
+the roofline of the dominant kernel (the product) from HIP events around its launches inside the timed
+regions, an fp16 GEMM of the same shapes on the same GPU, the batch-1 decode bandwidth beside what a
+read-only kernel gets on the same bytes, and the CPU oracle timed on a bounded sample.
 """
 
 from __future__ import annotations
@@ -30,12 +37,26 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 INT8_PEAK_TOPS = 5033.0      # MI355X dense INT8 MFMA: 256 CU x 2.4 GHz x 8192 ops/clk/CU
+FP6_PEAK_TFLOPS = 10066.0    # dense 6-bit (and 4-bit) floating-point MFMA: twice the INT8 rate
 HBM_PEAK_GBS = 8000.0
 M_PREFILL = 2048
-EVENT_EVERY = 10            # steps between two event-instrumented steps of the timed region
-# HBM bytes per GEMM launch (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 from rocprofv3 --pmc, averaged over the
-# five launches of a step; see profiles/gemm_prefill_llama3_8b_pmc.md).  Algorithmic: 63.3e6.
-GEMM_HBM_TRAFFIC_BYTES = 124.4e6
+EVENT_EVERY = 10            # steps between two event-instrumented steps of a timed region
+REPEATS = 5                 # timed regions of --steps steps each; the median is reported
+# HBM-side bytes per product launch come from a committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE
+# scaled by what the same counters read for a plain copy), not from this run: the file is named in the line.
+TRAFFIC_FILE = os.path.join("profiles", "gemm_f6_prefill_llama3_8b_pmc.md")
+
+
+def traffic_from_profile():
+    """The line 'TRAFFIC_BYTES_PER_LAUNCH = <number>' of the committed counter summary, or None."""
+    try:
+        with open(os.path.join(ROOT, TRAFFIC_FILE)) as f:
+            for ln in f:
+                if ln.startswith("TRAFFIC_BYTES_PER_LAUNCH"):
+                    return float(ln.split("=")[1].split()[0])
+    except (OSError, ValueError, IndexError):
+        pass
+    return None
 # name -> (K, N, online Hadamard block)
 LINEARS = [("qkv", 4096, 6144, 1), ("o", 4096, 4096, 1), ("gate", 4096, 14336, 1),
            ("up", 4096, 14336, 1), ("down", 14336, 4096, 128)]
@@ -73,9 +94,16 @@ def prepare_layers(torch, synth, M, linears=LINEARS, device_weights=False):
         wq = (q[:, 0::2] | (q[:, 1::2] << 4)).to(torch.uint8).contiguous()
         layers.append({"name": name, "K": K, "N": N, "h": h, "x": x, "wq": wq, "sw": sw, "sx": sx,
                        "w_f16": W.half().contiguous(),
+                       "w6": pq_mod().pq_repack_f6(wq),          # offline: the prepacked weights
+                       "x6": torch.empty((pq_mod().pq_f6_tiles_bytes(M, K),), dtype=torch.uint8, device="cuda"),
                        "xq": torch.empty((M, K // 2), dtype=torch.uint8, device="cuda"),
                        "out": torch.empty((M, N), dtype=torch.float16, device="cuda")})
     return layers
+
+
+def pq_mod():
+    import paper_2410_05265_amd.binding as pq
+    return pq
 
 
 DEVICE_WARMUP_MS = 80.0
@@ -98,17 +126,32 @@ def device_warmup(torch, ms=DEVICE_WARMUP_MS):
         torch.cuda.synchronize()
 
 
-def run_prefill(torch, pq, layers, steps, warmup):
+def run_prefill(torch, pq, layers, steps, warmup, path="f6", repeats=REPEATS):
+    """path "f6": pq_rotate_quant_f6 + pq_w4a4_gemm_f6 (the two launches of pq_linear_f6); "int8": pq_rotate_quant +
+    pq_w4a4_gemm (those of pq_linear).  Returns the median seconds per step over `repeats` timed regions, all of
+    them, and the average event-timed duration per linear of the product and of the quantizer launch."""
+    def quant(L):
+        if path == "f6":
+            pq.pq_rotate_quant_f6(L["x"], L["h"], L["sx"], out=L["x6"])
+        else:
+            pq.pq_rotate_quant(L["x"], L["h"], L["sx"], out=L["xq"])
+
+    def product(L):
+        if path == "f6":
+            pq.pq_w4a4_gemm_f6(L["x6"], L["w6"], L["sw"], L["sx"], L["x"].shape[0], L["N"], L["K"], out=L["out"])
+        else:
+            pq.pq_w4a4_gemm(L["xq"], L["wq"], L["sw"], L["sx"], out=L["out"])
+
     def step(events=None):
         for L in layers:
             if events is not None:
                 q0 = torch.cuda.Event(enable_timing=True)
                 q0.record()
-            pq.pq_rotate_quant(L["x"], L["h"], L["sx"], out=L["xq"])
+            quant(L)
             if events is not None:
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
-            pq.pq_w4a4_gemm(L["xq"], L["wq"], L["sw"], L["sx"], out=L["out"])
+            product(L)
             if events is not None:
                 e1.record()
                 events.append((L["name"], e0, e1))
@@ -118,40 +161,57 @@ def run_prefill(torch, pq, layers, steps, warmup):
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
-    events = []
-    t0 = time.perf_counter()
-    for i in range(steps):
-        # an event pair fences the stream (the next launch cannot start under the tail of the
-        # previous one), so only every EVENT_EVERY-th step of the timed region carries them
-        step(events if i % EVENT_EVERY == 0 else None)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    events, regions, gaps = [], [], []
+    for _ in range(repeats):
+        ev = []
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            # an event pair fences the stream (the next launch cannot start under the tail of the
+            # previous one), so only every EVENT_EVERY-th step of a timed region carries them
+            step(ev if i % EVENT_EVERY == 0 else None)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        regions.append(dt / steps)
+        # what an event pair adds to the kernel it brackets: an instrumented step (first marker to last) against
+        # a plain step, spread over its ten bracketed kernels
+        n_inst = len(ev) // (2 * len(layers))
+        if n_inst and steps > n_inst:
+            first = [e for n, e, _ in ev if n == "rq_" + layers[0]["name"]]
+            last = [e for n, _, e in ev if n == layers[-1]["name"]]
+            t_inst = sum(a.elapsed_time(b) for a, b in zip(first, last)) * 1e-3 / n_inst
+            t_plain = (dt - n_inst * t_inst) / (steps - n_inst)
+            gaps.append(max(0.0, (t_inst - t_plain) / (2 * len(layers))))
+        events += ev
     per = {}
     for name, e0, e1 in events:
         per.setdefault(name, []).append(e0.elapsed_time(e1) * 1e-3)
     avg = {k: sum(v) / len(v) for k, v in per.items()}
-    # what an event pair adds to the kernel it brackets: an instrumented step (first marker to last) against
-    # a plain step, spread over its ten bracketed kernels
-    n_inst = len(events) // (2 * len(layers))
-    if n_inst and steps > n_inst:
-        first = [e for n, e, _ in events if n == "rq_" + layers[0]["name"]]
-        last = [e for n, _, e in events if n == layers[-1]["name"]]
-        t_inst = sum(a.elapsed_time(b) for a, b in zip(first, last)) * 1e-3 / n_inst
-        t_plain = (dt - n_inst * t_inst) / (steps - n_inst)
-        run_prefill.event_gap = max(0.0, (t_inst - t_plain) / (2 * len(layers)))
-    else:
-        run_prefill.event_gap = 0.0
-    return dt / steps, {k: v for k, v in avg.items() if not k.startswith("rq_")}, \
+    run_prefill.event_gap = sorted(gaps)[len(gaps) // 2] if gaps else 0.0
+    run_prefill.regions = regions
+    return sorted(regions)[len(regions) // 2], {k: v for k, v in avg.items() if not k.startswith("rq_")}, \
         {k[3:]: v for k, v in avg.items() if k.startswith("rq_")}
 
 
 def run_variants(torch, pq, layers, steps, warmup, ops):
-    """The same step with the widened quantizers: 8-bit static activations (the paper's W4A8
-    setting) and per-token dynamic steps (Table 1 row O1) at 4 and 8 bits.  Wall time per step."""
+    """The same step through the layer's other entry points: pq_linear_f6 itself (one call per linear), the
+    canonical path pq_linear (INT8 matrix instruction), 8-bit static activations (the paper's W4A8 setting),
+    per-token dynamic steps (Table 1 row O1) at 4 and 8 bits, gate and up as one matrix, the products alone.
+    Wall time per step, median of three timed regions."""
     M = layers[0]["x"].shape[0]
     for L in layers:
         L["xq8"] = torch.empty((M, L["K"]), dtype=torch.int8, device="cuda")
         L["srow"] = torch.empty((M,), dtype=torch.float32, device="cuda")
+        L["work"] = torch.empty((max(pq.pq_linear_workspace_bytes(M, L["K"]), pq.pq_linear_f6_workspace_bytes(M, L["K"], L["h"])),),
+                                dtype=torch.uint8, device="cuda")
+
+    def f6_linear():
+        for L in layers:
+            pq.pq_linear_f6(L["x"], L["w6"], L["sw"], L["sx"], L["h"], out=L["out"], workspace=L["work"])
+
+    def int8_linear():
+        for L in layers:
+            pq.pq_linear(L["x"], L["wq"], L["sw"], L["sx"], L["h"], out=L["out"], workspace=L["work"])
 
     def w4a8_static():
         for L in layers:
@@ -168,33 +228,15 @@ def run_variants(torch, pq, layers, steps, warmup, ops):
 
     # gate and up read the same tensor in the model: one quantization and one [28672, 4096] weight matrix
     gate, up = layers[2], layers[3]
-    gu = dict(gate, wq=torch.cat([gate["wq"], up["wq"]]).contiguous(), sw=torch.cat([gate["sw"], up["sw"]]).contiguous(),
+    wq_gu = torch.cat([gate["wq"], up["wq"]]).contiguous()
+    gu = dict(gate, w6=pq.pq_repack_f6(wq_gu), sw=torch.cat([gate["sw"], up["sw"]]).contiguous(), N=gate["N"] + up["N"],
               out=torch.empty((M, gate["N"] + up["N"]), dtype=torch.float16, device="cuda"))
+    del wq_gu
     fused_layers = [layers[0], layers[1], gu, layers[4]]
 
     def gate_up_one_matrix():
         for L in fused_layers:
-            pq.pq_rotate_quant(L["x"], L["h"], L["sx"], out=L["xq"])
-            pq.pq_w4a4_gemm(L["xq"], L["wq"], L["sw"], L["sx"], out=L["out"])
-
-    # the same static W4A4 step with the product on the 6-bit floating-point matrix instruction: weights
-    # repacked once (offline), activations repacked after the quantizer (one more small launch per linear)
-    for L in layers:
-        L["w6"] = pq.pq_repack_f6(L["wq"])
-        L["x6"] = pq.pq_repack_f6(L["xq"])
-
-    def f6_static():
-        for L in layers:
-            pq.pq_rotate_quant(L["x"], L["h"], L["sx"], out=L["xq"])
-            pq.pq_repack_f6(L["xq"], out=L["x6"])
-            pq.pq_w4a4_gemm_f6(L["x6"], L["w6"], L["sw"], L["sx"], M, L["N"], L["K"], out=L["out"])
-
-    for L in layers:
-        L["work6"] = torch.empty((pq.pq_linear_f6_workspace_bytes(M, L["K"]),), dtype=torch.uint8, device="cuda")
-
-    def f6_linear():      # the layer's prepacked twin: without rotation the quantizer writes the tiles itself
-        for L in layers:
-            pq.pq_linear_f6(L["x"], L["w6"], L["sw"], L["sx"], L["h"], out=L["out"], workspace=L["work6"])
+            pq.pq_linear_f6(L["x"], L["w6"], L["sw"], L["sx"], L["h"], out=L["out"], workspace=L["work"])
 
     def f6_products_only():
         for L in layers:
@@ -205,21 +247,25 @@ def run_variants(torch, pq, layers, steps, warmup, ops):
             pq.pq_w4a4_gemm(L["xq"], L["wq"], L["sw"], L["sx"], out=L["out"])
 
     res = {}
-    for name, step in (("w4a8_static", w4a8_static), ("w4a4_dynamic", dynamic(4)), ("w4a8_dynamic", dynamic(8)),
-                       ("w4a4_static_gate_up_one_matrix", gate_up_one_matrix), ("w4a4_static_f6", f6_static), ("w4a4_static_f6_linear", f6_linear),
+    for name, step in (("w4a4_static_f6_linear", f6_linear), ("w4a4_static_int8_linear", int8_linear),
+                       ("w4a8_static", w4a8_static), ("w4a4_dynamic", dynamic(4)), ("w4a8_dynamic", dynamic(8)),
+                       ("w4a4_static_f6_gate_up_one_matrix", gate_up_one_matrix),
                        ("w4a4_products_only_f6", f6_products_only), ("w4a4_products_only_int8", int8_products_only)):
         device_warmup(torch)
         for _ in range(warmup):
             step()
         torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            step()
-        torch.cuda.synchronize()
-        dt = (time.perf_counter() - t0) / steps
+        ts = []
+        for _ in range(3):
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                step()
+            torch.cuda.synchronize()
+            ts.append((time.perf_counter() - t0) / steps)
+        dt = sorted(ts)[1]
         res[name] = {"ms_per_step": round(dt * 1e3, 4), "TOPS": round(ops / dt / 1e12, 1)}
     for L in layers:
-        del L["xq8"], L["srow"], L["w6"], L["x6"], L["work6"]
+        del L["xq8"], L["srow"], L["work"]
     return res
 
 
@@ -231,8 +277,9 @@ def run_prefill_8192(torch, pq, layers, steps=10, warmup=3):
     for L in layers:
         x = L["x"].repeat(M // L["x"].shape[0], 1).contiguous()
         big.append(dict(L, x=x, xq=torch.empty((M, L["K"] // 2), dtype=torch.uint8, device="cuda"),
+                        x6=torch.empty((pq.pq_f6_tiles_bytes(M, L["K"]),), dtype=torch.uint8, device="cuda"),
                         out=torch.empty((M, L["N"]), dtype=torch.float16, device="cuda")))
-    t, g, _ = run_prefill(torch, pq, big, steps, warmup)
+    t, g, _ = run_prefill(torch, pq, big, steps, warmup, repeats=3)
     ops = sum(2.0 * M * L["K"] * L["N"] for L in layers)
     return {"ms_per_step": round(t * 1e3, 4), "TOPS": round(ops / t / 1e12, 1),
             "per_linear_TOPS": {L["name"]: round(2.0 * M * L["K"] * L["N"] / g[L["name"]] / 1e12, 1) for L in layers}}
@@ -244,22 +291,25 @@ def run_llama3_70b(torch, pq, synth, decode=True):
     weights, HIP graph).  More tiles per launch and more bytes per matrix than the 8B shapes, so
     the fixed cost of a launch weighs less."""
     layers = prepare_layers(torch, synth, M_PREFILL, LINEARS_70B, device_weights=True)
-    t, g, _ = run_prefill(torch, pq, layers, 2 * EVENT_EVERY, 3)
+    t, g, _ = run_prefill(torch, pq, layers, 2 * EVENT_EVERY, 3, repeats=3)
     ops = sum(2.0 * M_PREFILL * L["K"] * L["N"] for L in layers)
     t16 = run_fp16(torch, layers, 5, 2)
     gemm_ops = sum(2.0 * M_PREFILL * L["K"] * L["N"] for L in layers) / len(layers)
     ach = gemm_ops / (sum(g.values()) / len(g)) / 1e12
     res = {"prefill_2048": {"ms_per_step": round(t * 1e3, 4), "TOPS": round(ops / t / 1e12, 1),
                             "gemm_TOPS_per_launch": round(ach, 1), "gemm_frac_of_int8_peak": round(ach / INT8_PEAK_TOPS, 4),
+                            "gemm_frac_of_fp6_peak": round(ach / FP6_PEAK_TFLOPS, 4),
+                            "per_linear_us": {L["name"]: round(g[L["name"]] * 1e6, 1) for L in layers},
                             "per_linear_TOPS": {L["name"]: round(2.0 * M_PREFILL * L["K"] * L["N"] / g[L["name"]] / 1e12, 1)
                                                 for L in layers},
                             "fp16_ms_per_step": round(t16 * 1e3, 4), "speedup_vs_fp16": round(t16 / t, 3)}}
     if decode:
         for L in layers:
             del L["w_f16"]
-        d = run_decode(torch, pq, layers, M=1)
-        res["decode_M1"] = {"GBps": d["GBps"], "frac_hbm": d["frac_hbm"],
-                            "per_linear": {k: {"us": v["us"], "frac_hbm": v["frac_hbm"]} for k, v in d["per_linear"].items()}}
+        d = run_decode(torch, pq, layers, M=1, floor=True)
+        res["decode_M1"] = {"GBps": d["GBps"], "frac_hbm": d["frac_hbm"], "read_only_kernel": d["read_only_kernel"],
+                            "per_linear": {k: {"us": v["us"], "frac_hbm": v["frac_hbm"], "read_only_us": v["read_only_us"]}
+                                           for k, v in d["per_linear"].items()}}
         # a serving batch: the tiled kernel alone, and with planes for its split-K launch (us per pq_linear)
         a = run_decode(torch, pq, layers, M=64)
         b = run_decode(torch, pq, layers, M=64, planes=True)
@@ -366,8 +416,9 @@ def run_int8_ref(torch, layers, steps, warmup):
         return None
 
 
-def graph_time(torch, fn, reps=3, inner=20):
-    """Microseconds per call of fn, captured `inner` times in a HIP graph (small kernels: the host is not the limit)."""
+def graph_time(torch, fn, reps=5, inner=20):
+    """Microseconds per call of fn, captured `inner` times in a HIP graph (small kernels: the host is not the
+    limit); median of `reps` replays."""
     fn()
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
@@ -377,15 +428,15 @@ def graph_time(torch, fn, reps=3, inner=20):
     graph.replay()
     torch.cuda.synchronize()
     device_warmup(torch, 40.0)
-    best = 1e30
+    ts = []
     for _ in range(reps):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         graph.replay()
         e1.record()
         torch.cuda.synchronize()
-        best = min(best, e0.elapsed_time(e1) * 1e3 / inner)
-    return best
+        ts.append(e0.elapsed_time(e1) * 1e3 / inner)
+    return sorted(ts)[len(ts) // 2]
 
 
 def run_side_rows(torch, pq, synth, T):
@@ -426,13 +477,33 @@ def run_side_rows(torch, pq, synth, T):
     return res
 
 
-def run_decode(torch, pq, layers, M=1, reps=3, warm=False, planes=False):
+def replay_median(torch, graph, per, reps=5):
+    """Median over `reps` replays of a captured graph, in seconds per captured item (`per` items per replay)."""
+    graph.replay()
+    torch.cuda.synchronize()
+    device_warmup(torch, 40.0)
+    ts = []
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1) * 1e-3 / per)
+    return sorted(ts)[len(ts) // 2]
+
+
+def run_decode(torch, pq, layers, M=1, reps=5, warm=False, planes=False, floor=False):
     """Batch-M decode through pq_linear with cold weights: enough distinct copies of each
     weight matrix that more than 1 GiB is touched before one is reused (the matrices fit
     the 256 MB last-level cache otherwise).  The launches are captured in a HIP graph so
-    the host is not the limit; time is per captured launch pair (rotate + streaming GEMM).
-    planes: the workspace also holds the partial-sum planes of the split-K launch."""
+    the host is not the limit; time is per captured launch pair (rotate + streaming GEMM), median of
+    `reps` replays.  planes: the workspace also holds the partial-sum planes of the split-K launch.
+    floor: the library's read-only kernel (pq_probe_stream_read: 256 workgroups read the bytes once and
+    discard them) over the same cold copies, captured and timed the same way: what one launch that only
+    streams a matrix of this size costs on this GPU."""
     res = {}
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
     for L in layers:
         K, N, h = L["K"], L["N"], L["h"]
         nbytes = N * K // 2
@@ -448,20 +519,21 @@ def run_decode(torch, pq, layers, M=1, reps=3, warm=False, planes=False):
         with torch.cuda.graph(graph):
             for w in ws:
                 pq.pq_linear(x, w, L["sw"], L["sx"], h, out=out, workspace=work)
-        graph.replay()
-        torch.cuda.synchronize()
-        device_warmup(torch, 40.0)
-        best = 1e30
-        for _ in range(reps):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            graph.replay()
-            e1.record()
-            torch.cuda.synchronize()
-            best = min(best, e0.elapsed_time(e1) * 1e-3 / ncopy)
-        res[L["name"]] = {"us": round(best * 1e6, 2), "GBps": round(nbytes / best / 1e9, 1),
-                          "frac_hbm": round(nbytes / best / 1e9 / HBM_PEAK_GBS, 3)}
+        t = replay_median(torch, graph, ncopy, reps)
+        res[L["name"]] = {"us": round(t * 1e6, 2), "GBps": round(nbytes / t / 1e9, 1),
+                          "frac_hbm": round(nbytes / t / 1e9 / HBM_PEAK_GBS, 3)}
         del graph
+        if floor:
+            pq.pq_probe_stream_read(ws[0].view(-1), sink)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for w in ws:
+                    pq.pq_probe_stream_read(w.view(-1), sink)
+            tf = replay_median(torch, graph, ncopy, reps)
+            res[L["name"]].update({"read_only_us": round(tf * 1e6, 2), "read_only_GBps": round(nbytes / tf / 1e9, 1),
+                                   "over_read_only": round(t / tf, 3)})
+            del graph
         if warm:
             # one weight buffer replayed: it stays in the last-level cache ("warm / LLC", not an HBM figure)
             w0 = ws[0]
@@ -470,8 +542,13 @@ def run_decode(torch, pq, layers, M=1, reps=3, warm=False, planes=False):
         del ws
     tot_b = sum(L["N"] * L["K"] // 2 for L in layers)
     tot_t = sum(v["us"] for v in res.values()) * 1e-6
-    return {"M": M, "weights": "cold (>1 GiB cycled)", "per_linear": res, "GBps": round(tot_b / tot_t / 1e9, 1),
-            "frac_hbm": round(tot_b / tot_t / 1e9 / HBM_PEAK_GBS, 3)}
+    r = {"M": M, "weights": "cold (>1 GiB cycled)", "timing": "median of %d graph replays" % reps, "per_linear": res,
+         "GBps": round(tot_b / tot_t / 1e9, 1), "frac_hbm": round(tot_b / tot_t / 1e9 / HBM_PEAK_GBS, 3)}
+    if floor:
+        tf = sum(v["read_only_us"] for v in res.values()) * 1e-6
+        r["read_only_kernel"] = {"GBps": round(tot_b / tf / 1e9, 1), "frac_hbm": round(tot_b / tf / 1e9 / HBM_PEAK_GBS, 3),
+                                 "note": "256 workgroups read the same cold bytes once and discard them: one launch's floor"}
+    return r
 
 
 def cpu_baseline(synth, rows=256):
@@ -558,33 +635,56 @@ def main():
     avg_ops = sum(gemm_ops.values()) / len(gemm_ops)
     avg_dur = sum(gemm_t.values()) / len(gemm_t)
     achieved = avg_ops / avg_dur / 1e12
+    traffic = traffic_from_profile()
     result = {
         "metric": "W4A4 linear TOPS + speedup vs fp16 GEMM, Llama-3-8B 2048-tok prefill; decode GB/s",
         "value": round(ops / t_step / 1e12, 1), "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(t_step * 1e3, 4), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "int4 codes on the int8 MFMA pipe, int32 accumulate",
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": "int4 codes as E3M2 on the 6-bit floating-point MFMA, fp32 accumulate (exact: integer sums below 2^24)",
         "data": "synthetic",
+        "timing": {"repeats": REPEATS, "ms_per_step_all": [round(t * 1e3, 4) for t in run_prefill.regions],
+                   "note": "%d timed regions of --steps steps each, synchronised on both sides; ms_per_step and value are the median region"
+                           % REPEATS},
         "device_warmup_ms": DEVICE_WARMUP_MS,
         "config": {"workload": "Llama-3-8B block linears, M=2048 prefill: qkv 4096->6144, o 4096->4096, "
                                "gate/up 4096->14336, down 14336->4096 (online 128-point block Hadamard on down only)",
-                   "tokens": M_PREFILL},
-        "roofline": {"bound": "mfma", "achieved": round(achieved, 1), "peak": INT8_PEAK_TOPS, "unit": "TOPS",
-                     "frac": round(achieved / INT8_PEAK_TOPS, 4), "traffic": GEMM_HBM_TRAFFIC_BYTES,
-                     "kernel": "k_gemm_dma / k_gemm_dual (five launches per step, averaged per launch; HIP events around the "
-                               "launches of every %dth timed step)" % EVENT_EVERY,
+                   "tokens": M_PREFILL, "path": "pq_linear_f6 (weights prepacked offline as f6 tiles): per linear "
+                                                "pq_rotate_quant_f6 + pq_w4a4_gemm_f6"},
+        "roofline": {"bound": "mfma", "achieved": round(achieved, 1), "peak": FP6_PEAK_TFLOPS, "unit": "TOPS",
+                     "frac": round(achieved / FP6_PEAK_TFLOPS, 4),
+                     "peak_note": "the contraction runs on the 6-bit floating-point matrix instruction: its own dense peak",
+                     "int8_peak": INT8_PEAK_TOPS, "frac_of_int8_peak": round(achieved / INT8_PEAK_TOPS, 4),
+                     "traffic": traffic, "traffic_source": TRAFFIC_FILE if traffic is not None else None,
+                     "kernel": "k_gemm_f6 (five launches per step, averaged per launch; HIP events around the "
+                               "launches of every %dth step of the timed regions)" % EVENT_EVERY,
                      "event_gap_us": round(event_gap * 1e6, 2),
                      "achieved_without_event_gap": round(avg_ops / max(avg_dur - event_gap, 1e-9) / 1e12, 1),
                      "per_linear_TOPS": {k: round(gemm_ops[k] / v / 1e12, 1) for k, v in gemm_t.items()},
+                     "per_linear_frac_of_int8_peak": {k: round(gemm_ops[k] / v / 1e12 / INT8_PEAK_TOPS, 4) for k, v in gemm_t.items()},
                      "per_linear_us": {k: round(v * 1e6, 1) for k, v in gemm_t.items()}},
-        "rotate_quant": {"bound": "hbm", "per_linear_us": {k: round(v * 1e6, 1) for k, v in rq_t.items()},
-                         "per_linear_GBps": {L["name"]: round(M_PREFILL * L["K"] * 2.5 / rq_t[L["name"]] / 1e9, 1)
+        "rotate_quant": {"bound": "hbm", "kernel": "k_rotate_quant_f6", "per_linear_us": {k: round(v * 1e6, 1) for k, v in rq_t.items()},
+                         "per_linear_GBps": {L["name"]: round(M_PREFILL * L["K"] * 2.75 / rq_t[L["name"]] / 1e9, 1)
                                              for L in layers},
-                         "note": "pq_rotate_quant launches of the instrumented steps; 2.5 algorithmic bytes per element"},
+                         "note": "pq_rotate_quant_f6 launches of the instrumented steps; 2.75 algorithmic bytes per element "
+                                 "(2 read, 0.75 written as 6-bit images)"},
         "fp16_gemm": {"ms_per_step": round(t_fp16 * 1e3, 4), "TFLOPS": round(ops / t_fp16 / 1e12, 1),
                       "frac_of_fp16_peak": round(ops / t_fp16 / 1e12 / (INT8_PEAK_TOPS / 2), 4),
                       "speedup_pq_linear": round(t_fp16 / t_step, 3),
                       "speedup_pq_w4a4_gemm_only": round(t_fp16 / sum(gemm_t.values()), 3), "impl": "torch.matmul fp16"},
     }
+
+    def canonical_leg():
+        # the canonical path: nibble-packed weights as they are, product on the INT8 matrix instruction
+        t8, g8, r8 = run_prefill(torch, pq, layers, args.steps, max(2, args.warmup // 2), path="int8", repeats=3)
+        a8 = avg_ops / (sum(g8.values()) / len(g8)) / 1e12
+        return {"path": "pq_linear: per linear pq_rotate_quant + pq_w4a4_gemm (k_gemm_dma / k_gemm_dual)",
+                "ms_per_step": round(t8 * 1e3, 4), "TOPS": round(ops / t8 / 1e12, 1),
+                "product_TOPS_per_launch": round(a8, 1), "product_frac_of_int8_peak": round(a8 / INT8_PEAK_TOPS, 4),
+                "per_linear_us": {k: round(v * 1e6, 1) for k, v in g8.items()},
+                "rotate_quant_us": {k: round(v * 1e6, 1) for k, v in r8.items()},
+                "headline_over_this": round(t8 / t_step, 3)}
+
     # Everything below is a side leg: a failure there is recorded in its place and never costs the line.
     def leg(key, fn):
         try:
@@ -604,7 +704,7 @@ def main():
 
     def probes_leg():
         pr = run_probes(torch, pq)
-        pr["product_kernel_frac_of_mfma_only_codes"] = round(achieved / pr["mfma_only_TOPS"]["codes_times_16"], 4)
+        pr["product_kernel_frac_of_mfma_only_e3m2"] = round(achieved / pr["mfma_only_TOPS"]["codes_as_e3m2_6bit_fp32_accumulate"], 4)
         return pr
 
     def variants_leg():
@@ -613,12 +713,12 @@ def main():
         return v
 
     def decode_leg():
-        dec = run_decode(torch, pq, layers, M=1, warm=True)
+        dec = run_decode(torch, pq, layers, M=1, warm=True, floor=True)
         # gate and up share their input: stored as one [28672, 4096] matrix they stream in one launch
         gate, up = layers[2], layers[3]
         fused = dict(gate, name="gate_up", N=gate["N"] + up["N"], wq=torch.cat([gate["wq"], up["wq"]]).contiguous(),
                      sw=torch.cat([gate["sw"], up["sw"]]).contiguous())
-        gu = run_decode(torch, pq, [fused], M=1)["per_linear"]["gate_up"]
+        gu = run_decode(torch, pq, [fused], M=1, floor=True)["per_linear"]["gate_up"]
         pl = dec["per_linear"]
         t_block = (pl["qkv"]["us"] + pl["o"]["us"] + gu["us"] + pl["down"]["us"]) * 1e-6
         b_block = sum(L["N"] * L["K"] // 2 for L in layers)
@@ -647,18 +747,13 @@ def main():
         args.no_variants = args.no_cpu = True
     else:
         leg("int8_gemm", int8_leg)
+    if not args.serving_only:
+        leg("canonical_int8_path", canonical_leg)
     if not args.no_variants:
         leg("achievable", probes_leg)
         leg("prefill_8192", lambda: run_prefill_8192(torch, pq, layers))
         leg("side_rows", lambda: run_side_rows(torch, pq, synth, M_PREFILL))
         leg("variants", variants_leg)
-    v6 = result.get("variants", {}).get("w4a4_static_f6_linear") if isinstance(result.get("variants"), dict) else None
-    if isinstance(v6, dict) and "ms_per_step" in v6:
-        # the same step through the optional prepacked path (product on the 6-bit matrix instruction, exact):
-        # not the headline, whose roofline, counters and profiles are the INT8 kernel's
-        result["prepacked_f6_path"] = {"ms_per_step": v6["ms_per_step"], "TOPS": v6["TOPS"],
-                                       "over_headline": round(result["ms_per_step"] / v6["ms_per_step"], 3),
-                                       "speedup_vs_fp16": round(result["fp16_gemm"]["ms_per_step"] / v6["ms_per_step"], 3)}
     if not args.no_decode and not args.serving_only:
         leg("decode", decode_leg)
     if args.serving_only or not (args.no_decode or args.no_variants):

@@ -206,16 +206,25 @@ int pq_w4a4_gemm_f6(const void* x_tiles, const void* w_tiles, const float* w_sca
                     float act_scale, int64_t M, int64_t N, int64_t K,
                     void* out_f16, int32_t* acc_i32, void* stream);
 
-/* The whole layer on that instruction, for weights repacked beforehand (the prepacked twin of
- * pq_linear): rotate + quantize, f6 tiles of the codes, pq_w4a4_gemm_f6, on one stream.  Without
- * rotation (had_block <= 1) the quantizer writes the tiles itself (two launches in all); with
- * rotation pq_rotate_quant is followed by pq_repack_f6 (three).  The codes are those of
- * pq_rotate_quant bit for bit, the outputs those of pq_linear.
- * workspace: device memory, 256-byte aligned, pq_linear_f6_workspace_bytes(M,K) bytes; on return it
- * holds the tiles (pq_f6_tiles_bytes(M,K), rounded up to 256) and behind them the canonical packed
- * codes [M,K/2].  K % 128 == 0; limits as pq_repack_f6 and pq_rotate_quant.
+/* pq_rotate_quant for the prepacked path: rotation + static quantization as pq_rotate_quant (the same
+ * codes bit for bit), written as f6 tiles in one launch: x_tiles, pq_f6_tiles_bytes(M,K) bytes.
+ * xq_packed: NULL, or where the canonical codes [M,K/2] go as well.  had_block: 0 or 1 = no rotation, else
+ * a power of two up to 512 that divides K; larger blocks return PQ_ERR_UNSUPPORTED (pq_rotate_quant +
+ * pq_repack_f6 serve those).  K % 128 == 0; limits as pq_repack_f6.
  */
-size_t pq_linear_f6_workspace_bytes(int64_t M, int64_t K);
+int pq_rotate_quant_f6(const void* x_f16, int64_t M, int64_t K, int32_t had_block, float act_scale,
+                       void* x_tiles, void* xq_packed, void* stream);
+
+/* The whole layer on that instruction, for weights repacked beforehand (the prepacked twin of
+ * pq_linear): pq_rotate_quant_f6, then pq_w4a4_gemm_f6, on one stream: two launches.  Rotation blocks
+ * beyond 512 channels take pq_rotate_quant, pq_repack_f6 and pq_w4a4_gemm_f6: three.  The codes behind
+ * the tiles are those of pq_rotate_quant bit for bit, the outputs those of pq_linear.
+ * workspace: device memory, 256-byte aligned, pq_linear_f6_workspace_bytes(M,K,had_block) bytes; on
+ * return it holds the activations' tiles (pq_f6_tiles_bytes(M,K)), and behind them, rounded up to 256,
+ * the canonical packed codes [M,K/2] if had_block > 512.  K % 128 == 0; limits as pq_repack_f6 and
+ * pq_rotate_quant.
+ */
+size_t pq_linear_f6_workspace_bytes(int64_t M, int64_t K, int32_t had_block);
 int pq_linear_f6(const void* x_f16, const void* w_tiles, const float* w_scale,
                  float act_scale, int32_t had_block, int64_t M, int64_t N, int64_t K,
                  void* out_f16, void* workspace, size_t workspace_bytes, void* stream);

@@ -42,7 +42,8 @@ SIGNATURES = {
     "pq_f6_tiles_bytes": (_sz, [_i64, _i64]),
     "pq_repack_f6": (ctypes.c_int, [_vp, _i64, _i64, _vp, _vp]),
     "pq_w4a4_gemm_f6": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i64, _i64, _i64, _vp, _vp, _vp]),
-    "pq_linear_f6_workspace_bytes": (_sz, [_i64, _i64]),
+    "pq_linear_f6_workspace_bytes": (_sz, [_i64, _i64, _i32]),
+    "pq_rotate_quant_f6": (ctypes.c_int, [_vp, _i64, _i64, _i32, _f32, _vp, _vp, _vp]),
     "pq_linear_f6": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i32, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
     "pq_probe_f6_product": (ctypes.c_int, [_vp, _vp, _i64, _vp, _vp]),
     "pq_rotate_quant8": (ctypes.c_int, [_vp, _i64, _i64, _i32, _f32, _vp, _vp]),
@@ -564,13 +565,27 @@ def pq_w4a4_gemm_f6(x_tiles, w_tiles, w_scale, act_scale, M: int, N: int, K: int
     return out, acc
 
 
-def pq_linear_f6_workspace_bytes(M: int, K: int) -> int:
-    return int(lib().pq_linear_f6_workspace_bytes(M, K))
+def pq_linear_f6_workspace_bytes(M: int, K: int, had_block: int = 1) -> int:
+    return int(lib().pq_linear_f6_workspace_bytes(M, K, int(had_block)))
+
+
+def pq_rotate_quant_f6(x, had_block: int, act_scale: float, out=None, codes=None):
+    """x fp16 [M,K] -> the f6 tiles of its codes (uint8, pq_f6_tiles_bytes(M,K)); codes: optional uint8 [M,K/2]
+    that receives the canonical packed codes as well."""
+    _dev(x, torch.float16, "x")
+    M, K = x.shape
+    if out is None:
+        out = torch.empty((pq_f6_tiles_bytes(M, K),), dtype=torch.uint8, device=x.device)
+    if codes is not None:
+        _dev(codes, torch.uint8, "codes")
+    _check(lib().pq_rotate_quant_f6(_ptr(x), M, K, int(had_block), float(act_scale), _ptr(out), _ptr(codes), _stream()),
+           "pq_rotate_quant_f6")
+    return out
 
 
 def pq_linear_f6(x, w_tiles, w_scale, act_scale, had_block, out=None, workspace=None):
-    """The whole layer with prepacked weights (pq_repack_f6).  Returns (out fp16 [M,N], workspace uint8:
-    the activation tiles, then the canonical packed codes)."""
+    """The whole layer with prepacked weights (pq_repack_f6).  Returns (out fp16 [M,N], workspace uint8: the
+    activation tiles, and behind them the canonical packed codes if had_block > 512)."""
     _dev(x, torch.float16, "x")
     _dev(w_tiles, torch.uint8, "w_tiles")
     _dev(w_scale, torch.float32, "w_scale")
@@ -578,7 +593,7 @@ def pq_linear_f6(x, w_tiles, w_scale, act_scale, had_block, out=None, workspace=
     N = w_scale.numel()
     if w_tiles.numel() < pq_f6_tiles_bytes(N, K):
         raise ValueError("shape mismatch")
-    need = pq_linear_f6_workspace_bytes(M, K)
+    need = pq_linear_f6_workspace_bytes(M, K, had_block)
     if workspace is None:
         workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=x.device)
     if out is None:

@@ -605,10 +605,30 @@ int pq_w4a4_gemm_f6(const void* x_tiles, const void* w_tiles, const float* w_sca
                               static_cast<hipStream_t>(stream));
 }
 
-size_t pq_linear_f6_workspace_bytes(int64_t M, int64_t K)
+int pq_rotate_quant_f6(const void* x_f16, int64_t M, int64_t K, int32_t had_block, float act_scale, void* x_tiles,
+                       void* xq_packed, void* stream)
+{
+    if (M < 0 || K <= 0 || (K % 128) != 0) return PQ_ERR_SHAPE;
+    if (had_block < 0 || had_block > 16384) return PQ_ERR_SHAPE;
+    if (had_block > 1 && ((had_block & (had_block - 1)) != 0 || (K % had_block) != 0)) return PQ_ERR_SHAPE;
+    if (!x_f16 || !x_tiles) return PQ_ERR_NULL;
+    if (!aligned16(x_f16) || !aligned16(x_tiles) || !aligned16(xq_packed)) return PQ_ERR_ALIGN;
+    if (!good_scale(act_scale)) return PQ_ERR_SCALE;
+    if (M == 0) return PQ_OK;
+    if (K > 262080 || pq::f6_tiles_bytes(M, K) >= ((size_t)1 << 32) || M * K >= ((int64_t)1 << 32) ||
+        !pq::quant_f6_supported(M, K, had_block))
+        return PQ_ERR_UNSUPPORTED;
+    return pq::launch_quant_f6(x_f16, M, K, had_block, act_scale, x_tiles, xq_packed, static_cast<hipStream_t>(stream));
+}
+
+// rotation blocks beyond what the tile-writing quantizer handles go through the canonical codes
+static bool f6_needs_codes(int64_t M, int64_t K, int32_t had_block) { return !pq::quant_f6_supported(M, K, had_block); }
+
+size_t pq_linear_f6_workspace_bytes(int64_t M, int64_t K, int32_t had_block)
 {
     if (M <= 0 || K <= 0 || (K % 128) != 0) return 0;
-    return ((pq::f6_tiles_bytes(M, K) + 255) & ~(size_t)255) + pq_linear_workspace_bytes(M, K);
+    const size_t tiles = (pq::f6_tiles_bytes(M, K) + 255) & ~(size_t)255;
+    return tiles + (f6_needs_codes(M, K, had_block) ? pq_linear_workspace_bytes(M, K) : 0);
 }
 
 int pq_linear_f6(const void* x_f16, const void* w_tiles, const float* w_scale, float act_scale, int32_t had_block,
@@ -617,25 +637,24 @@ int pq_linear_f6(const void* x_f16, const void* w_tiles, const float* w_scale, f
     if (M < 0 || N <= 0 || K <= 0 || (K % 128) != 0 || (N % 16) != 0) return PQ_ERR_SHAPE;
     if (!x_f16 || !w_tiles || !w_scale || !out_f16) return PQ_ERR_NULL;
     if (M == 0) return PQ_OK;
-    if (!workspace || workspace_bytes < pq_linear_f6_workspace_bytes(M, K)) return PQ_ERR_WORKSPACE;
-    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return PQ_ERR_ALIGN;
-    int rc = check_gemm(workspace, w_tiles, w_scale, act_scale, M, N, K, out_f16, nullptr);
-    if (rc != PQ_OK) return rc;
     if (had_block < 0 || had_block > 16384 ||
         (had_block > 1 && ((had_block & (had_block - 1)) != 0 || (K % had_block) != 0)))
         return PQ_ERR_SHAPE;
+    if (!workspace || workspace_bytes < pq_linear_f6_workspace_bytes(M, K, had_block)) return PQ_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return PQ_ERR_ALIGN;
+    int rc = check_gemm(workspace, w_tiles, w_scale, act_scale, M, N, K, out_f16, nullptr);
+    if (rc != PQ_OK) return rc;
     if (!aligned16(x_f16)) return PQ_ERR_ALIGN;
     if (K > 262080 || M > (1 << 30) || N > (1 << 30) || pq::f6_tiles_bytes(M, K) >= ((size_t)1 << 32) ||
         pq::f6_tiles_bytes(N, K) >= ((size_t)1 << 32) || M * K >= ((int64_t)1 << 32))
         return PQ_ERR_UNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(stream);
     uint8_t* tiles = static_cast<uint8_t*>(workspace);
-    uint8_t* nibbles = tiles + ((pq::f6_tiles_bytes(M, K) + 255) & ~(size_t)255);
-    if (pq::quant_f6_supported(M, K, had_block)) {
-        // rotation blocks up to 512 channels (or none): one launch rotates, quantizes and writes the tiles (and
-        // the canonical codes beside them)
-        rc = pq::launch_quant_f6(x_f16, M, K, had_block, act_scale, tiles, nibbles, st);
+    if (!f6_needs_codes(M, K, had_block)) {
+        // rotation blocks up to 512 channels (or none): one launch rotates, quantizes and writes the tiles
+        rc = pq::launch_quant_f6(x_f16, M, K, had_block, act_scale, tiles, nullptr, st);
     } else {
+        uint8_t* nibbles = tiles + ((pq::f6_tiles_bytes(M, K) + 255) & ~(size_t)255);
         rc = pq_rotate_quant(x_f16, M, K, had_block, act_scale, nibbles, stream);
         if (rc == PQ_OK) rc = pq::launch_repack_f6(nibbles, M, K, tiles, st);
     }

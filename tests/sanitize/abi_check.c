@@ -42,7 +42,7 @@ int main(void)
                 total += pq_linear_workspace_bytes(M, K) + pq_linear_workspace_bytes_split(M, N, K);
                 total += pq_linear_w4a8_workspace_bytes(M, K) + pq_linear_w4a8_workspace_bytes_split(M, N, K);
                 total += pq_linear_dynamic_workspace_bytes(M, K, 4) + pq_linear_dynamic_workspace_bytes_split(M, N, K, 8);
-                total += pq_f6_tiles_bytes(M, K) + pq_linear_f6_workspace_bytes(M, K);
+                total += pq_f6_tiles_bytes(M, K) + pq_linear_f6_workspace_bytes(M, K, 128) + pq_linear_f6_workspace_bytes(M, K, 4096);
             }
     EXPECT(total > 0, 1);
     EXPECT(pq_calibrate_workspace_bytes(256, 50), 256 * 51 * 4);
@@ -105,6 +105,8 @@ int main(void)
     EXPECT(pq_repack_f6(p, 32, 262144, p, NULL), PQ_ERR_UNSUPPORTED);
     EXPECT(pq_w4a4_gemm_f6(p, p, pf, 0.1f, 32, 16, 160, p, NULL, NULL), PQ_ERR_SHAPE);
     EXPECT(pq_linear_f6(p, p, pf, 0.1f, 1, 32, 16, 128, p, p256, 100, NULL), PQ_ERR_WORKSPACE);
+    EXPECT(pq_rotate_quant_f6(p, 32, 2048, 1024, 0.1f, p, NULL, NULL), PQ_ERR_UNSUPPORTED);
+    EXPECT(pq_rotate_quant_f6(p, 32, 96, 1, 0.1f, p, NULL, NULL), PQ_ERR_SHAPE);
 
     printf(failures ? "abi_check: %d FAILED\n" : "abi_check: ok\n", failures);
     return failures != 0;

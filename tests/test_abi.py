@@ -201,8 +201,16 @@ def test_argument_errors_of_the_f6_product(b):
     assert rp(odd, 32, 128, p, nul) == b.PQ_ERR_ALIGN
     assert rp(p, 0, 128, p, nul) == b.PQ_OK
     assert rp(p, 32, 262144, p, nul) == b.PQ_ERR_UNSUPPORTED         # sums could pass 2^24
-    assert L.pq_linear_f6_workspace_bytes(2048, 4096) == 2048 * 4096 * 3 // 4 + 2048 * 2048
-    assert L.pq_linear_f6_workspace_bytes(3, 128) == 3072 + 256 and L.pq_linear_f6_workspace_bytes(3, 96) == 0
+    assert L.pq_linear_f6_workspace_bytes(2048, 4096, 1) == 2048 * 4096 * 3 // 4
+    assert L.pq_linear_f6_workspace_bytes(2048, 4096, 128) == 2048 * 4096 * 3 // 4
+    assert L.pq_linear_f6_workspace_bytes(2048, 4096, 4096) == 2048 * 4096 * 3 // 4 + 2048 * 2048   # codes as well
+    assert L.pq_linear_f6_workspace_bytes(3, 128, 0) == 3072 and L.pq_linear_f6_workspace_bytes(3, 96, 1) == 0
+    rq6 = L.pq_rotate_quant_f6
+    assert rq6(nul, 32, 128, 1, 0.1, p, nul, nul) == b.PQ_ERR_NULL and rq6(p, 32, 128, 1, 0.1, nul, nul, nul) == b.PQ_ERR_NULL
+    assert rq6(p, 32, 96, 1, 0.1, p, nul, nul) == b.PQ_ERR_SHAPE and rq6(p, 32, 256, 48, 0.1, p, nul, nul) == b.PQ_ERR_SHAPE
+    assert rq6(p, 32, 128, 1, 0.1, p, odd, nul) == b.PQ_ERR_ALIGN and rq6(p, 32, 128, 1, -1.0, p, nul, nul) == b.PQ_ERR_SCALE
+    assert rq6(p, 32, 2048, 1024, 0.1, p, nul, nul) == b.PQ_ERR_UNSUPPORTED          # blocks beyond 512 channels
+    assert rq6(p, 0, 128, 1, 0.1, p, nul, nul) == b.PQ_OK
     lf = L.pq_linear_f6
     p256 = ctypes.c_void_p(0x10000)
     assert lf(p, p, p, 0.1, 1, 32, 16, 128, p, nul, 0, nul) == b.PQ_ERR_WORKSPACE

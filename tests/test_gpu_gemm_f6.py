@@ -13,6 +13,7 @@ import os
 
 import numpy as np
 import pytest
+import torch
 
 import oracle as O
 from paper_2410_05265_amd import synth
@@ -136,50 +137,87 @@ def test_argument_errors(pq):
         pq.pq_w4a4_gemm_f6(x6, w6, sw, 0.1, 32, 16, 128, want_out=False, want_acc=False)
 
 
+def codes_of_tiles(tiles, R, K):
+    """Inverse of tiles_by_definition: the int8 codes [R, K] behind a repacked byte stream."""
+    RB, KS = (R + 31) // 32, K // 64
+    blocks = np.asarray(tiles[:RB * (KS // 2) * 3072]).reshape(-1, 3072)
+    img = np.zeros((blocks.shape[0], 64, 2, 24), np.uint8)
+    img[:, :, 0, :16] = blocks[:, :1024].reshape(-1, 64, 16)
+    img[:, :, 0, 16:] = blocks[:, 1024:1536].reshape(-1, 64, 8)
+    img[:, :, 1, :8] = blocks[:, 1536:2048].reshape(-1, 64, 8)
+    img[:, :, 1, 8:] = blocks[:, 2048:].reshape(-1, 64, 16)
+    bits = np.unpackbits(img.reshape(-1, 24), axis=1, bitorder="little").reshape(-1, 32, 6)
+    e = (bits * (1 << np.arange(6))).sum(axis=2)                      # 6-bit values, little-endian stream
+    mag = np.full(64, -99, np.int64)
+    mag[E3M2.astype(np.int64)] = np.arange(9)
+    val = np.where(e >= 32, -mag[e & 31], mag[e & 31])
+    assert (mag[e & 31] >= 0).all()
+    # [group][rb][half][row in block][step][i] -> [rb][row in block][group][step][half][i]
+    v = val.reshape(KS // 2, RB, 2, 32, 2, 32).transpose(1, 3, 0, 4, 2, 5).reshape(RB * 32, K)
+    assert not v[R:].any()
+    return v[:R].astype(np.int8)
+
+
+def test_codes_of_tiles_inverts_the_definition():
+    q = synth.random_codes(45, 384, seed=3)
+    assert np.array_equal(codes_of_tiles(tiles_by_definition(q), 45, 384), q)
+
+
 @pytest.mark.parametrize("M,K,N,h", [(300, 1152, 400, 1), (2048, 4096, 512, 1), (33, 128, 16, 0), (70, 14336, 512, 128),
-                                     (256, 4096, 1024, 4096), (1, 256, 64, 1)])
+                                     (256, 4096, 1024, 4096), (1, 256, 64, 1), (100, 1536, 64, 512), (65, 2048, 32, 2048)])
 def test_layer_with_prepacked_weights(pq, M, K, N, h):
     """pq_linear_f6 against pq_linear: the same codes and the same outputs bit for bit; the tiles it leaves are
-    the repacked codes; and (through pq_linear's own parity) the oracle."""
+    the repacked codes (rotation blocks beyond 512 channels: the canonical codes lie behind them); and (through
+    pq_linear's own parity) the oracle."""
     x = synth.activations(M, K, seed=M + K)
     wq = synth.random_packed(N, K, seed=N + K, stream=7)
     sw = synth.random_scales(N, seed=N)
     sx = 0.213
     ref, ref_ws = pq.pq_linear(dev(x), dev(wq), dev(sw), sx, h)
+    ref_codes = host(ref_ws)[:M * K // 2].reshape(M, K // 2)
     w6 = pq.pq_repack_f6(dev(wq))
     out, ws = pq.pq_linear_f6(dev(x), w6, dev(sw), sx, h)
     assert np.array_equal(host(out).view(np.uint16), host(ref).view(np.uint16))
     tiles_bytes = pq.pq_f6_tiles_bytes(M, K)
     off = (tiles_bytes + 255) // 256 * 256
-    codes = host(ws)[off:off + M * K // 2].reshape(M, K // 2)
-    assert np.array_equal(codes, host(ref_ws)[:M * K // 2].reshape(M, K // 2))
-    assert np.array_equal(host(ws)[:tiles_bytes], tiles_by_definition(O.unpack(codes)))
-    acc_ref = O.gemm_i64(O.unpack(codes), O.unpack(wq))
+    assert pq.pq_linear_f6_workspace_bytes(M, K, h) == off + (M * K // 2 + 255) // 256 * 256 * (h > 512)
+    assert np.array_equal(host(ws)[:tiles_bytes], tiles_by_definition(O.unpack(ref_codes)))
+    assert np.array_equal(codes_of_tiles(host(ws), M, K), O.unpack(ref_codes))
+    if h > 512:
+        assert np.array_equal(host(ws)[off:off + M * K // 2].reshape(M, K // 2), ref_codes)
+    acc_ref = O.gemm_i64(O.unpack(ref_codes), O.unpack(wq))
     assert ulp_diff(host(out), O.epilogue(acc_ref, np.float32(sx), sw)).max() <= 1
 
 
+@pytest.mark.parametrize("M,K,h", [(70, 1152, 1), (33, 512, 128), (300, 4096, 512), (2048, 14336, 128)])
+def test_tile_writing_quantizer(pq, M, K, h):
+    """pq_rotate_quant_f6: the tiles are those of pq_rotate_quant's codes, with and without the canonical copy."""
+    x = synth.activations(M, K, seed=M + K + h)
+    sx = 0.187
+    codes = host(pq.pq_rotate_quant(dev(x), h, sx))
+    want = tiles_by_definition(O.unpack(codes))
+    nib = torch.full((M, K // 2), 0xAA, dtype=torch.uint8, device="cuda")
+    both = pq.pq_rotate_quant_f6(dev(x), h, sx, codes=nib)
+    assert np.array_equal(host(both)[:want.size], want) and np.array_equal(host(nib), codes)
+    assert np.array_equal(host(pq.pq_rotate_quant_f6(dev(x), h, sx))[:want.size], want)
+    with pytest.raises(pq.PQError, match="PQ_ERR_UNSUPPORTED"):
+        pq.pq_rotate_quant_f6(dev(synth.activations(4, 2048, seed=1)), 1024, sx)
+
+
 def test_unrotated_quantizer_to_tiles_is_exact_for_every_fp16_value(pq):
-    """The fused quantizer of pq_linear_f6 (no rotation) on all finite fp16 values and on constructed ties:
-    the codes beside the tiles equal the oracle's."""
+    """The tile-writing quantizer (no rotation) on all finite fp16 values and on constructed ties: the codes
+    behind the tiles equal the oracle's."""
     v = np.arange(65536, dtype=np.uint32).astype(np.uint16).view(np.float16)
     x = v[np.isfinite(v)].reshape(31, 2048)
-    wq = synth.random_packed(16, 2048, seed=1, stream=7)
-    sw = synth.random_scales(16, seed=2)
-    w6 = pq.pq_repack_f6(dev(wq))
     for s in (0.25, 1.0 / 3.0, 0.0123, 41.0):
-        _, ws = pq.pq_linear_f6(dev(x), w6, dev(sw), s, 1)
-        off = (pq.pq_f6_tiles_bytes(31, 2048) + 255) // 256 * 256
-        codes = O.unpack(host(ws)[off:off + 31 * 1024].reshape(31, 1024))
-        assert np.array_equal(codes, O.quantize(x, np.float32(s))), s
+        tiles = pq.pq_rotate_quant_f6(dev(x), 1, s)
+        assert np.array_equal(codes_of_tiles(host(tiles), 31, 2048), O.quantize(x, np.float32(s))), s
     rng = np.random.default_rng(17)
     s = np.float32(0.0371)
     k = rng.integers(-10, 10, size=(8, 1024)).astype(np.float64)
     xt = ((k + 0.5) * np.float64(s)).astype(np.float16)
-    w6 = pq.pq_repack_f6(dev(synth.random_packed(16, 1024, seed=3, stream=7)))
-    _, ws = pq.pq_linear_f6(dev(xt), w6, dev(sw), float(s), 0)
-    off = (pq.pq_f6_tiles_bytes(8, 1024) + 255) // 256 * 256
-    codes = O.unpack(host(ws)[off:off + 8 * 512].reshape(8, 512))
-    assert np.array_equal(codes, O.quantize(xt, s))
+    tiles = pq.pq_rotate_quant_f6(dev(xt), 0, float(s))
+    assert np.array_equal(codes_of_tiles(host(tiles), 8, 1024), O.quantize(xt, s))
 
 
 @pytest.mark.parametrize("M,N,K", [(300, 448, 256), (40, 4096, 1152), (517, 1216, 384), (2048, 14336, 128)])
