@@ -119,60 +119,66 @@ __global__ __launch_bounds__(256) void k_repack_f6(const uint8_t* __restrict__ c
 }
 
 // Rotation (blocks of up to 512 channels) + static quantizer that writes f6 tiles: one launch instead of
-// quantizer + repack, loads and stores both in whole cache lines.  A workgroup owns 32 tokens x 512
-// channels, i.e. four blocks of the tiles, 12 KiB that lie side by side.  First every wavefront takes
-// eight of the tokens, one after the other with all eight loads in flight: a lane holds 8 consecutive
-// channels (16 bytes), rotates and quantizes them exactly as pq_rotate_quant does (the same device code,
-// the same codes bit for bit) and leaves the packed dword in LDS.  Then every thread turns two register
-// images (32 channels of a token each) into their 24 bytes and stores them: a wavefront's store covers a
-// whole plane of a block.  Optionally the canonical nibbles go out as well.
-constexpr int kQCols = 512, kQPitch = kQCols / 2 + 16;     // staged row: 256 bytes of nibbles, padded (bank spread)
-
-template <bool EXACT>
+// quantizer + repack, loads and stores both in whole cache lines.  A workgroup owns 32 tokens x C channels
+// (C = 128, 256 or 512: the rotation block, at least one block of the tiles), i.e. C / 128 blocks of 3072
+// bytes.  First every wavefront takes eight of the tokens, 512 / C of them at a time, all loads issued before
+// the arithmetic: a lane holds 8 consecutive channels (16 bytes), rotates and quantizes them exactly as
+// pq_rotate_quant does (the same device code, the same codes bit for bit) and leaves the packed dword in LDS.
+// Then one thread per register image (32 channels of a token) turns it into its 24 bytes and stores them: a
+// wavefront's store covers a whole plane of a block.  Optionally the canonical nibbles go out as well.
+// The narrow variants are what keeps the GPU busy on a 2048 x 4096 input (2048 workgroups of C = 128 instead
+// of 512 of C = 512): short workgroups at different phases hide one another's load latency.
+template <bool EXACT, int C>
 __global__ __launch_bounds__(256) void k_rotate_quant_f6(const __half* __restrict__ x, int M, int K, int log2h,
                                                         rq::StaticStep steps, uint8_t* __restrict__ tiles,
                                                         uint8_t* __restrict__ nibbles)
 {
-    __shared__ __align__(16) uint8_t stage[32 * kQPitch];
+    constexpr int LPR = C / 8, RPP = 64 / LPR, PASSES = 8 / RPP;     // lanes per token, tokens per pass, passes
+    constexpr int kPitch = C / 2 + 16;                                // staged row: nibbles, padded (bank spread)
+    __shared__ __align__(16) uint8_t stage[32 * kPitch];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int rb = blockIdx.y, chunk0 = blockIdx.x * kQCols;
-    const int64_t krel = K - chunk0;                      // channels from chunk0 to the end of the row
-    v4i raw[8][1];
-    bool live[8][1];
+    const int lrow = lane / LPR, lcol = lane % LPR;                   // token within a pass, group of 8 channels
+    const int rb = blockIdx.y, chunk0 = blockIdx.x * C;
+    const int64_t krel = K - chunk0;                                  // channels from chunk0 to the end of the row
+    v4i raw[PASSES][1];
+    bool live[PASSES][1];
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-        const int64_t row = (int64_t)rb * 32 + wave * 8 + r;
+    for (int p = 0; p < PASSES; ++p) {
+        const int64_t row = (int64_t)rb * 32 + wave * 8 + p * RPP + lrow;
         const bool in = row < M;
-        rq::load_chunk<1>(static_cast<const __half*>(x + (in ? row : 0) * K + chunk0), krel, 0, lane, in, raw[r], live[r]);
+        rq::load_chunk<1>(static_cast<const __half*>(x + (in ? row : 0) * K + chunk0), krel, 0, lcol, in, raw[p], live[p]);
     }
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-        rq::lds_u32_ptr dst = (rq::lds_u32_ptr)(stage + (wave * 8 + r) * kQPitch);
-        if (!live[r][0]) dst[lane] = 0u;                  // tokens past the end, channels past K: zero codes
-        rq::rotate_quant_regs_with<1, EXACT, 4>(raw[r], live[r], 0, log2h, steps, dst, (rq::lds_f32_ptr) nullptr, lane,
-                                                live[r][0]);
+    for (int p = 0; p < PASSES; ++p) {
+        rq::lds_u32_ptr dst = (rq::lds_u32_ptr)(stage + (wave * 8 + p * RPP + lrow) * kPitch);
+        if (!live[p][0]) dst[lcol] = 0u;                              // tokens past the end, channels past K: zero codes
+        // (lane stages of the rotation pair lanes inside a token's LPR lanes: bit b of lcol is bit b of the lane)
+        rq::rotate_quant_regs_with<1, EXACT, 4>(raw[p], live[p], 0, log2h, steps, dst, (rq::lds_f32_ptr) nullptr, lcol,
+                                                live[p][0]);
     }
     __syncthreads();
-    const int nk = K >> 7, kt = blockIdx.x * 4 + wave;
-    if (kt < nk) {
-        uint8_t* block = tiles + ((int64_t)kt * gridDim.y + rb) * kChunkF6;
+    // images of the workgroup: C / 128 blocks x 2 steps x 64 lanes
+    const int nk = K >> 7;
 #pragma unroll
-        for (int st = 0; st < 2; ++st) {
-            const v4i p = *(__attribute__((address_space(3))) const v4i*)(stage + (lane & 31) * kQPitch + wave * 64 + st * 32 +
-                                                                          (lane >> 5) * 16);
+    for (int i = threadIdx.x; i < (C / 128) * 128; i += 256) {
+        const int blk = i >> 7, st = (i >> 6) & 1, l = i & 63, kt = blockIdx.x * (C / 128) + blk;
+        if (kt < nk) {
+            const v4i p = *(__attribute__((address_space(3))) const v4i*)(stage + (l & 31) * kPitch + blk * 64 + st * 32 +
+                                                                          (l >> 5) * 16);
             uint64_t w[3];
             image_of_nibbles(p, w);
-            store_image(block, lane, st, w);
+            store_image(tiles + ((int64_t)kt * gridDim.y + rb) * kChunkF6, l, st, w);
         }
     }
     if (nibbles) {
+        constexpr int PPR = C / 32;                                   // 16-byte pieces per staged row
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int id = i * 256 + threadIdx.x, row = id >> 4, c16 = id & 15;
+        for (int i = threadIdx.x; i < 32 * PPR; i += 256) {
+            const int row = i / PPR, c16 = i % PPR;
             const int64_t grow = (int64_t)rb * 32 + row;
             if (grow < M && chunk0 + c16 * 32 < K)
                 *reinterpret_cast<v4i*>(nibbles + grow * (K >> 1) + (chunk0 >> 1) + c16 * 16) =
-                    *(__attribute__((address_space(3))) const v4i*)(stage + row * kQPitch + c16 * 16);
+                    *(__attribute__((address_space(3))) const v4i*)(stage + row * kPitch + c16 * 16);
         }
     }
 }
@@ -601,21 +607,30 @@ size_t f6_tiles_bytes(int64_t R, int64_t K) { return (size_t)((R + 31) / 32) * (
 // larger blocks take pq_rotate_quant + repack).  nibbles: NULL, or where the canonical codes go as well.
 bool quant_f6_supported(int64_t R, int64_t K, int32_t h) { return h <= 512 && (K % 128) == 0 && (R + 31) / 32 <= 65535 && K <= (1 << 30); }
 
+template <bool EXACT>
+static void launch_quant_f6_c(int c, const void* x, int64_t R, int64_t K, int log2h, rq::StaticStep steps, void* out,
+                              void* nibbles, hipStream_t st)
+{
+    const dim3 grid((unsigned)((K + c - 1) / c), (unsigned)((R + 31) / 32));
+    const __half* xp = static_cast<const __half*>(x);
+    uint8_t *op = static_cast<uint8_t*>(out), *np = static_cast<uint8_t*>(nibbles);
+    if (c == 128) hipLaunchKernelGGL((k_rotate_quant_f6<EXACT, 128>), grid, dim3(256), 0, st, xp, (int)R, (int)K, log2h, steps, op, np);
+    else if (c == 256) hipLaunchKernelGGL((k_rotate_quant_f6<EXACT, 256>), grid, dim3(256), 0, st, xp, (int)R, (int)K, log2h, steps, op, np);
+    else hipLaunchKernelGGL((k_rotate_quant_f6<EXACT, 512>), grid, dim3(256), 0, st, xp, (int)R, (int)K, log2h, steps, op, np);
+}
+
 int launch_quant_f6(const void* x, int64_t R, int64_t K, int32_t h, float act_scale, void* out, void* nibbles, hipStream_t st)
 {
     if (!quant_f6_supported(R, K, h)) return PQ_ERR_UNSUPPORTED;
-    const dim3 grid((unsigned)((K + kQCols - 1) / kQCols), (unsigned)((R + 31) / 32));
+    const int c = h <= 128 ? 128 : h;                    // channels per workgroup: the rotation block, at least 128
     if (h <= 1) {
-        const rq::StaticStep steps{(float)(1.0 / (double)act_scale), act_scale};
-        hipLaunchKernelGGL(k_rotate_quant_f6<true>, grid, dim3(256), 0, st, static_cast<const __half*>(x), (int)R, (int)K, 0,
-                           steps, static_cast<uint8_t*>(out), static_cast<uint8_t*>(nibbles));
+        launch_quant_f6_c<true>(c, x, R, K, 0, rq::StaticStep{(float)(1.0 / (double)act_scale), act_scale}, out, nibbles, st);
     } else {
         int log2h = 0;
         while ((1 << log2h) < h) ++log2h;
         // the 1/sqrt(h) of the rotation is folded into the reciprocal step, as in pq_rotate_quant
-        const rq::StaticStep steps{(float)(1.0 / ((double)act_scale * sqrt((double)h))), act_scale};
-        hipLaunchKernelGGL(k_rotate_quant_f6<false>, grid, dim3(256), 0, st, static_cast<const __half*>(x), (int)R, (int)K,
-                           log2h, steps, static_cast<uint8_t*>(out), static_cast<uint8_t*>(nibbles));
+        launch_quant_f6_c<false>(c, x, R, K, log2h, rq::StaticStep{(float)(1.0 / ((double)act_scale * sqrt((double)h))), act_scale},
+                                 out, nibbles, st);
     }
     return hip_status(hipGetLastError());
 }
