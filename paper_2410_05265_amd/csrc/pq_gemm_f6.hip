@@ -509,7 +509,10 @@ __device__ __forceinline__ void f6_persistent(const uint8_t* __restrict__ x6, co
 #pragma unroll
                 for (int t = 0; t < 32 / RP; ++t) {
                     const v4i val = *(__attribute__((address_space(3))) const v4i*)(src + t * RP * kRowPitch);
-                    if (live && mb + lrow + t * RP < M) *reinterpret_cast<v4i*>(dst + (int64_t)t * RP * N) = val;
+                    // (the output is written once and not read here again: stored non-temporal, it does not take the place of
+                    // weight panels and token images in the L2, nor of the weights in the memory-side cache)
+                    if (live && mb + lrow + t * RP < M)
+                        __builtin_nontemporal_store(val, reinterpret_cast<v4i*>(dst + (int64_t)t * RP * N));
                 }
             }
         }

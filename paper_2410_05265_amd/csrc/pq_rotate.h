@@ -228,7 +228,11 @@ __device__ __forceinline__ void load_chunk(SRC x_row, int64_t K, int64_t chunk0,
     for (int g = 0; g < G; ++g) {
         const int64_t e0 = chunk0 + (int64_t)g * kChunk + tid * 8;
         live[g] = active && e0 < K;
-        raw[g] = *(src_v4)(x_row + (live[g] ? e0 : 0));
+        // (activations in global memory are read once: non-temporal, they leave the caches to what is read again)
+        if constexpr (std::is_same<SRC, const __half*>::value)
+            raw[g] = __builtin_nontemporal_load((src_v4)(x_row + (live[g] ? e0 : 0)));
+        else
+            raw[g] = *(src_v4)(x_row + (live[g] ? e0 : 0));
     }
 }
 
