@@ -125,6 +125,18 @@ int pq_linear(const void* x_f16, const void* wq_packed, const float* w_scale,
               float act_scale, int32_t had_block, int64_t M, int64_t N, int64_t K,
               void* out_f16, void* workspace, size_t workspace_bytes, void* stream);
 
+/* Two layers that read the same tokens (gate_proj and up_proj of an MLP block, Sec. 3: one quantized input,
+ * two low-bit products): X is rotated and quantized once, OUT_a = Xq . Wq_a^T and OUT_b = Xq . Wq_b^T with
+ * their own channel steps and their own outputs [M, N_a] and [M, N_b].  Outputs equal those of two pq_linear
+ * calls bit for bit.  Where pq_linear would take its fused launch (few tokens), one launch streams both
+ * matrices, which saves the fixed cost of a launch (several microseconds where a matrix takes 4-8);
+ * otherwise one pq_rotate_quant and two products.  N_a, N_b: multiples of 16; K, had_block, workspace
+ * (pq_linear_workspace_bytes(M, K), or more for the split launch of the larger product) as for pq_linear.
+ */
+int pq_linear2(const void* x_f16, const void* wq_a, const float* w_scale_a, int64_t N_a, void* out_a_f16,
+               const void* wq_b, const float* w_scale_b, int64_t N_b, void* out_b_f16, float act_scale,
+               int32_t had_block, int64_t M, int64_t K, void* workspace, size_t workspace_bytes, void* stream);
+
 /* pq_linear for callers that cannot allocate device memory (code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc): the same layer, the same kernels and the same
  * outputs bit for bit, with pq_linear's workspace taken from an array built into the library

@@ -31,6 +31,7 @@ SIGNATURES = {
     "pq_w4a4_gemm_workspace_bytes": (_sz, [_i64, _i64, _i64]),
     "pq_w4a4_gemm_ws": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i64, _i64, _i64, _vp, _vp, _vp, _sz, _vp]),
     "pq_linear": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i32, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
+    "pq_linear2": (ctypes.c_int, [_vp, _vp, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _f32, _i32, _i64, _i64, _vp, _sz, _vp]),
     "pq_linear_noalloc_max_bytes": (_sz, []),
     "pq_linear_noalloc": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i32, _i64, _i64, _i64, _vp, _vp]),
     "pq_set_gemm_variant": (ctypes.c_int, [ctypes.c_int]),
@@ -205,6 +206,28 @@ def pq_linear(x, wq, w_scale, act_scale, had_block, out=None, workspace=None):
     _check(lib().pq_linear(_ptr(x), _ptr(wq), _ptr(w_scale), float(act_scale), int(had_block), M, N, K, _ptr(out),
                            _ptr(workspace), workspace.numel(), _stream()), "pq_linear")
     return out, workspace
+
+
+def pq_linear2(x, wq_a, w_scale_a, wq_b, w_scale_b, act_scale, had_block, out_a=None, out_b=None, workspace=None):
+    """Two layers on the same tokens (gate and up).  Returns (out_a, out_b, workspace)."""
+    _dev(x, torch.float16, "x")
+    M, K = x.shape
+    for w, s in ((wq_a, w_scale_a), (wq_b, w_scale_b)):
+        _dev(w, torch.uint8, "wq")
+        _dev(s, torch.float32, "w_scale")
+        if w.shape[1] * 2 != K or s.numel() != w.shape[0]:
+            raise ValueError("shape mismatch")
+    Na, Nb = wq_a.shape[0], wq_b.shape[0]
+    if workspace is None:
+        workspace = torch.empty((max(pq_linear_workspace_bytes(M, K), 256),), dtype=torch.uint8, device=x.device)
+    if out_a is None:
+        out_a = torch.empty((M, Na), dtype=torch.float16, device=x.device)
+    if out_b is None:
+        out_b = torch.empty((M, Nb), dtype=torch.float16, device=x.device)
+    _check(lib().pq_linear2(_ptr(x), _ptr(wq_a), _ptr(w_scale_a), Na, _ptr(out_a), _ptr(wq_b), _ptr(w_scale_b), Nb,
+                            _ptr(out_b), float(act_scale), int(had_block), M, K, _ptr(workspace), workspace.numel(),
+                            _stream()), "pq_linear2")
+    return out_a, out_b, workspace
 
 
 def pq_linear_noalloc_max_bytes() -> int:

@@ -216,6 +216,38 @@ int pq_linear(const void* x_f16, const void* wq_packed, const float* w_scale, fl
                            static_cast<uint8_t*>(workspace) + codes, workspace_bytes - codes, stream);
 }
 
+int pq_linear2(const void* x_f16, const void* wq_a, const float* w_scale_a, int64_t N_a, void* out_a_f16,
+               const void* wq_b, const float* w_scale_b, int64_t N_b, void* out_b_f16, float act_scale,
+               int32_t had_block, int64_t M, int64_t K, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (M < 0 || N_a <= 0 || N_b <= 0 || K <= 0 || (K % 32) != 0 || (N_a % 16) != 0 || (N_b % 16) != 0) return PQ_ERR_SHAPE;
+    if (!x_f16 || !wq_a || !w_scale_a || !out_a_f16 || !wq_b || !w_scale_b || !out_b_f16) return PQ_ERR_NULL;
+    if (M == 0) return PQ_OK;
+    if (!workspace || workspace_bytes < pq_linear_workspace_bytes(M, K)) return PQ_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return PQ_ERR_ALIGN;
+    int rc = check_gemm(workspace, wq_a, w_scale_a, act_scale, M, N_a, K, out_a_f16, nullptr);
+    if (rc == PQ_OK) rc = check_gemm(workspace, wq_b, w_scale_b, act_scale, M, N_b, K, out_b_f16, nullptr);
+    if (rc != PQ_OK) return rc;
+    if (had_block < 0 || had_block > 16384 ||
+        (had_block > 1 && ((had_block & (had_block - 1)) != 0 || (K % had_block) != 0)))
+        return PQ_ERR_SHAPE;
+    if (!aligned16(x_f16)) return PQ_ERR_ALIGN;
+    // few tokens: one launch streams both matrices (the rule of pq_linear, on the rows of both)
+    if (((g_variant == 0 && (M * K <= 8192 || ((had_block <= 1 || M == 1) && M * K <= 16384))) || g_variant == 4) &&
+        N_a + N_b <= (1 << 30) && pq::decode_supported(M, N_a + N_b, K, had_block)) {
+        const pq::DecodeSecond second{static_cast<const uint8_t*>(wq_b), w_scale_b, static_cast<__half*>(out_b_f16), (int)N_a};
+        return pq::launch_decode(x_f16, nullptr, wq_a, w_scale_a, act_scale, had_block, M, N_a + N_b, K, out_a_f16, nullptr,
+                                 workspace, static_cast<hipStream_t>(stream), nullptr, 4, nullptr, &second);
+    }
+    rc = pq_rotate_quant(x_f16, M, K, had_block, act_scale, workspace, stream);
+    if (rc != PQ_OK) return rc;
+    const size_t codes = pq_linear_workspace_bytes(M, K);
+    uint8_t* planes = static_cast<uint8_t*>(workspace) + codes;
+    rc = pq_w4a4_gemm_ws(workspace, wq_a, w_scale_a, act_scale, M, N_a, K, out_a_f16, nullptr, planes, workspace_bytes - codes, stream);
+    if (rc != PQ_OK) return rc;
+    return pq_w4a4_gemm_ws(workspace, wq_b, w_scale_b, act_scale, M, N_b, K, out_b_f16, nullptr, planes, workspace_bytes - codes, stream);
+}
+
 size_t pq_linear_workspace_bytes_split(int64_t M, int64_t N, int64_t K)
 {
     return pq_linear_workspace_bytes(M, K) + pq_w4a4_gemm_workspace_bytes(M, N, K);

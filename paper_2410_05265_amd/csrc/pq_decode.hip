@@ -72,7 +72,7 @@ __global__ __launch_bounds__(1024) void k_decode(const __half* __restrict__ x, c
                                                float sx, float mult, int log2h, int M, int N, int K,
                                                __half* __restrict__ out, int32_t* __restrict__ acc_out,
                                                uint8_t* __restrict__ xq_out, const float* __restrict__ srow,
-                                               const int32_t* __restrict__ zcorr)
+                                               const int32_t* __restrict__ zcorr, DecodeSecond two)
 {
     constexpr int G = MODE == 2 ? 2 : 1;
     static_assert(ABITS == 4 || (ABITS == 8 && MODE == 0), "8-bit activations: given codes only");
@@ -119,8 +119,10 @@ __global__ __launch_bounds__(1024) void k_decode(const __half* __restrict__ x, c
                 if (c < c0 || c >= c1) continue;
                 int off = (cb + c) * 1024 + lane * 16;
                 off = off < Kb ? off : 0;
-                w[j][c] = __builtin_nontemporal_load(
-                    reinterpret_cast<const v4i*>(wq + (int64_t)(gc * RPW + j) * Kb + off));
+                // (two matrices behind one another: a group of RPW rows never straddles them, n1 % 16 == 0)
+                const int row = gc * RPW + j;
+                const uint8_t* rp = row < two.n1 ? wq + (int64_t)row * Kb : two.wq + (int64_t)(row - two.n1) * Kb;
+                w[j][c] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(rp + off));
             }
     };
     // Only the first loads (at least four per lane) go out before the activation rows are staged:
@@ -248,9 +250,14 @@ __global__ __launch_bounds__(1024) void k_decode(const __half* __restrict__ x, c
             if (m < M) {
                 const int n = gid * RPW + j;
                 const int total = ABITS == 8 ? p[0] >> 4 : p[0];
-                if (acc_out) acc_out[(int64_t)m * N + n] = total;
-                const int shifted = total + (zcorr ? zcorr[n] : 0);   // zero-point correction of Eq. 1, if any
-                if (out) out[(int64_t)m * N + n] = __float2half_rn(mul_rn((float)shifted, (srow ? srow[m] : sx) * sw[n]));
+                if (n >= two.n1) {   // the second matrix: its own channel steps and output
+                    const int n2 = n - two.n1;
+                    two.out[(int64_t)m * (N - two.n1) + n2] = __float2half_rn(mul_rn((float)total, sx * two.sw[n2]));
+                } else {
+                    if (acc_out) acc_out[(int64_t)m * two.n1 + n] = total;
+                    const int shifted = total + (zcorr ? zcorr[n] : 0);   // zero-point correction of Eq. 1, if any
+                    if (out) out[(int64_t)m * two.n1 + n] = __float2half_rn(mul_rn((float)shifted, (srow ? srow[m] : sx) * sw[n]));
+                }
             }
         }
     }
@@ -259,7 +266,7 @@ __global__ __launch_bounds__(1024) void k_decode(const __half* __restrict__ x, c
 template <int RPW, int CB, int MP, int MODE, int ABITS = 4>
 int launch_one(const __half* x, const uint8_t* xq_in, const uint8_t* wq, const float* sw, float sx, float mult,
                int log2h, int M, int N, int K, __half* out, int32_t* acc, uint8_t* xq_out, hipStream_t st,
-               const float* srow, const int32_t* zcorr)
+               const float* srow, const int32_t* zcorr, const DecodeSecond& two)
 {
     constexpr int G = MODE == 2 ? 2 : 1;
     const size_t lds = (((size_t)MP * (ABITS == 8 ? K : K / 2) + 15) & ~(size_t)15) +
@@ -272,51 +279,51 @@ int launch_one(const __half* x, const uint8_t* xq_in, const uint8_t* wq, const f
     int grid = (groups + 15) / 16;
     grid = grid > 256 ? 256 : grid;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(1024), lds, st, x, xq_in, wq, sw, sx, mult, log2h, M, N, K, out,
-                       acc, xq_out, srow, zcorr);
+                       acc, xq_out, srow, zcorr, two);
     return hip_status(hipGetLastError());
 }
 
 template <int RPW, int CB, int MP, int ABITS = 4>
 int launch_mode(const __half* x, const uint8_t* xq_in, const uint8_t* wq, const float* sw, float sx, int h, int M,
                 int N, int K, __half* out, int32_t* acc, uint8_t* xq_out, hipStream_t st, const float* srow,
-                const int32_t* zcorr)
+                const int32_t* zcorr, const DecodeSecond& two)
 {
     if constexpr (ABITS == 8) {
         if constexpr (RPW > 2 || (MP > 1 && RPW * CB > 8)) return PQ_ERR_UNSUPPORTED;   // never chosen
         else if (x != nullptr) return PQ_ERR_UNSUPPORTED;                               // given codes only
-        else return launch_one<RPW, CB, MP, 0, 8>(x, xq_in, wq, sw, sx, 0.f, 0, M, N, K, out, acc, xq_out, st, srow, zcorr);
+        else return launch_one<RPW, CB, MP, 0, 8>(x, xq_in, wq, sw, sx, 0.f, 0, M, N, K, out, acc, xq_out, st, srow, zcorr, two);
     } else
     if constexpr (MP > 4 && (RPW > 2 || RPW * CB > 8)) return PQ_ERR_UNSUPPORTED;   // never chosen: too many registers
-    else if (x == nullptr) return launch_one<RPW, CB, MP, 0>(x, xq_in, wq, sw, sx, 0.f, 0, M, N, K, out, acc, xq_out, st, srow, zcorr);
+    else if (x == nullptr) return launch_one<RPW, CB, MP, 0>(x, xq_in, wq, sw, sx, 0.f, 0, M, N, K, out, acc, xq_out, st, srow, zcorr, two);
     if constexpr (MP > 4) return PQ_ERR_UNSUPPORTED;   // more than 4 tokens: codes only, no fused quantizer
     else if (h <= 1) {
         const float inv = (float)(1.0 / (double)sx);
-        return launch_one<RPW, CB, MP, 1>(x, xq_in, wq, sw, sx, inv, 0, M, N, K, out, acc, xq_out, st, srow, zcorr);
+        return launch_one<RPW, CB, MP, 1>(x, xq_in, wq, sw, sx, inv, 0, M, N, K, out, acc, xq_out, st, srow, zcorr, two);
     }
     else {
         int log2h = 0;
         while ((1 << log2h) < h) ++log2h;
         const float mult = (float)(1.0 / ((double)sx * sqrt((double)h)));
         if (h <= kChunk)
-            return launch_one<RPW, CB, MP, 1>(x, xq_in, wq, sw, sx, mult, log2h, M, N, K, out, acc, xq_out, st, srow, zcorr);
-        return launch_one<RPW, CB, MP, 2>(x, xq_in, wq, sw, sx, mult, log2h, M, N, K, out, acc, xq_out, st, srow, zcorr);
+            return launch_one<RPW, CB, MP, 1>(x, xq_in, wq, sw, sx, mult, log2h, M, N, K, out, acc, xq_out, st, srow, zcorr, two);
+        return launch_one<RPW, CB, MP, 2>(x, xq_in, wq, sw, sx, mult, log2h, M, N, K, out, acc, xq_out, st, srow, zcorr, two);
     }
 }
 
 template <int MP, int ABITS = 4>
 int launch_shape(int rpw, int cb, const __half* x, const uint8_t* xi, const uint8_t* w, const float* sw, float sx,
                  int h, int m, int n, int k, __half* o, int32_t* acc, uint8_t* xo, hipStream_t st, const float* srow,
-                 const int32_t* zcorr)
+                 const int32_t* zcorr, const DecodeSecond& two)
 {
     switch (rpw * 100 + cb) {
-        case 102: return launch_mode<1, 2, MP, ABITS>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr);
-        case 202: return launch_mode<2, 2, MP, ABITS>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr);
-        case 402: return launch_mode<4, 2, MP, ABITS>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr);
-        case 104: return launch_mode<1, 4, MP, ABITS>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr);
-        case 204: return launch_mode<2, 4, MP, ABITS>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr);
-        case 404: return launch_mode<4, 4, MP, ABITS>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr);
-        case 108: return launch_mode<1, 8, MP, ABITS>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr);
-        default: return launch_mode<2, 8, MP, ABITS>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr);
+        case 102: return launch_mode<1, 2, MP, ABITS>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr, two);
+        case 202: return launch_mode<2, 2, MP, ABITS>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr, two);
+        case 402: return launch_mode<4, 2, MP, ABITS>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr, two);
+        case 104: return launch_mode<1, 4, MP, ABITS>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr, two);
+        case 204: return launch_mode<2, 4, MP, ABITS>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr, two);
+        case 404: return launch_mode<4, 4, MP, ABITS>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr, two);
+        case 108: return launch_mode<1, 8, MP, ABITS>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr, two);
+        default: return launch_mode<2, 8, MP, ABITS>(x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr, two);
     }
 }
 
@@ -342,9 +349,15 @@ bool decode_supported(int64_t M, int64_t N, int64_t K, int32_t h, int32_t abits)
 // epilogue (per-token dynamic quantization; only with given codes).
 int launch_decode(const void* x_f16, const void* xq_in, const void* wq, const float* sw, float sx, int32_t h,
                   int64_t M, int64_t N, int64_t K, void* out, int32_t* acc, void* xq_out, hipStream_t st,
-                  const float* srow, int32_t abits, const int32_t* zcorr)
+                  const float* srow, int32_t abits, const int32_t* zcorr, const DecodeSecond* second)
 {
     if (!decode_supported(M, N, K, x_f16 ? h : -1, abits)) return PQ_ERR_UNSUPPORTED;
+    // N counts the rows of both matrices when a second one follows; alone, all N rows are the first's
+    DecodeSecond two{nullptr, nullptr, nullptr, (int)N};
+    if (second) {
+        if (second->n1 <= 0 || second->n1 >= N || (second->n1 % 16) != 0 || acc || zcorr || srow) return PQ_ERR_UNSUPPORTED;
+        two = *second;
+    }
     const __half* x = static_cast<const __half*>(x_f16);
     const uint8_t* xi = static_cast<const uint8_t*>(xq_in);
     const uint8_t* w = static_cast<const uint8_t*>(wq);
@@ -360,17 +373,17 @@ int launch_decode(const void* x_f16, const void* xq_in, const void* wq, const fl
     const int m = (int)M, n = (int)N, k = (int)K;
     if (abits == 8) {
         if (rpw > 2) rpw = 2;
-        if (M == 1) return launch_shape<1, 8>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr);
+        if (M == 1) return launch_shape<1, 8>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr, two);
         if (cb == 8) rpw = 1;   // more tokens: fewer rows per wavefront keep the accumulators in registers
-        if (M <= 4) return launch_shape<4, 8>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr);
-        return launch_shape<8, 8>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr);
+        if (M <= 4) return launch_shape<4, 8>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr, two);
+        return launch_shape<8, 8>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr, two);
     }
-    if (M == 1) return launch_shape<1>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr);
-    if (M <= 4) return launch_shape<4>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr);
+    if (M == 1) return launch_shape<1>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr, two);
+    if (M <= 4) return launch_shape<4>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr, two);
     // 5..8 tokens: fewer rows per wavefront so that the accumulators stay in registers
     if (rpw > 2) rpw = 2;
     if (cb == 8) rpw = 1;
-    return launch_shape<8>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr);
+    return launch_shape<8>(rpw, cb, x, xi, w, sw, sx, h, m, n, k, o, acc, xo, st, srow, zcorr, two);
 }
 
 }  // namespace pq

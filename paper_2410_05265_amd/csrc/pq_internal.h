@@ -1,6 +1,7 @@
 // Internal declarations shared by the translation units of libpq (gfx950 only).
 #pragma once
 
+#include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -82,10 +83,21 @@ int launch_stream_mfma(const void* xq, const void* wq, const float* sw, float sx
                        void* out, int32_t* acc, hipStream_t st, const float* srow = nullptr, int32_t abits = 4,
                        const int32_t* zcorr = nullptr);
 
+// A second weight matrix for the same tokens in the same launch (gate and up of an MLP): its rows follow the
+// n1 rows of the first (n1 % 16 == 0), N of launch_decode counts both, and its product goes to an output of
+// its own, [M, N - n1].  Only with plain fp16 outputs (no accumulators, per-token steps or zero-point).
+struct DecodeSecond {
+    const uint8_t* wq;
+    const float* sw;
+    __half* out;
+    int n1;
+};
+
 bool decode_supported(int64_t M, int64_t N, int64_t K, int32_t h, int32_t abits = 4);
 int launch_decode(const void* x_f16, const void* xq_in, const void* wq, const float* sw, float sx, int32_t h,
                   int64_t M, int64_t N, int64_t K, void* out, int32_t* acc, void* xq_out, hipStream_t st,
-                  const float* srow = nullptr, int32_t abits = 4, const int32_t* zcorr = nullptr);
+                  const float* srow = nullptr, int32_t abits = 4, const int32_t* zcorr = nullptr,
+                  const DecodeSecond* second = nullptr);
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? PQ_OK : PQ_ERR_HIP; }
 
