@@ -10,7 +10,8 @@
 //     else happens, the others as soon as the activation rows are staged;
 //   - the activation rows are rotated, quantized and packed by every workgroup (= every CU)
 //     for itself while those loads are in flight (a second launch would cost more than the
-//     redundant arithmetic);
+//     redundant arithmetic); rows of up to 16384 channels in all go from the registers they were
+//     loaded into straight through the quantizer, 8 or 16 channels per thread;
 //   - a wavefront-load is 1 KiB of ONE weight row (lane l: bytes 16 l .. 16 l + 15), the most
 //     contiguous access the canonical layout allows;
 //   - the products use v_dot8_i32_i4 directly on packed nibbles (no expansion), and the 64
@@ -135,7 +136,33 @@ __global__ __launch_bounds__(1024) void k_decode(const __half* __restrict__ x, c
     load_weights(gid, 0, 0, EARLY);
     __builtin_amdgcn_sched_barrier(0);
 
-    // ---- 3. rows into LDS (later pieces, if any, wait behind the weights), then the codes
+    // ---- 3. the codes of the activation rows into LDS.
+    // Short rows (all pieces in registers already, rotation blocks inside a wavefront: up to 512 channels):
+    // every thread rotates and quantizes the pieces it loaded, straight from its registers (lane l of a
+    // wavefront holds channels 8 l .. 8 l + 7 of 512 consecutive ones, which is what the register form of
+    // the quantizer expects), and writes the packed dword: no staging of the fp16 rows, one barrier.
+    // Otherwise: rows into LDS (later pieces, if any, wait behind the weights), then chunk by chunk.
+    const bool in_registers = MODE == 1 && log2h <= 9 && pieces <= 1024 * XB;
+    if (in_registers) {
+        if constexpr (MODE == 1) {
+#pragma unroll
+            for (int u = 0; u < XB; ++u) {
+                const int i = tid + 1024 * u;
+                if (1024 * u < pieces) {                      // wavefront-uniform up to the last partial wavefront
+                    const v4i raw1[1] = {xr[u]};
+                    const bool live1[1] = {i < pieces};
+                    auto dst = (rq::lds_u32_ptr)xs;           // piece i -> dword i: rows are contiguous, K / 8 dwords each
+                    if (log2h == 0)
+                        rq::rotate_quant_regs_with<1, true, 4>(raw1, live1, 0, 0, rq::StaticStep{mult, sx}, dst,
+                                                               (rq::lds_f32_ptr) nullptr, i, live1[0]);
+                    else
+                        rq::rotate_quant_regs_with<1, false, 4>(raw1, live1, 0, log2h, rq::StaticStep{mult, sx}, dst,
+                                                                (rq::lds_f32_ptr) nullptr, i, live1[0]);
+                }
+            }
+        }
+        rq::lds_sync();
+    } else {
 #pragma unroll
     for (int u = 0; u < XB; ++u) {
         const int i = tid + 1024 * u;   // pieces past the end land in the (still unused) scratch: no branch
@@ -177,6 +204,9 @@ __global__ __launch_bounds__(1024) void k_decode(const __half* __restrict__ x, c
                                                  active);
         }
         rq::lds_sync();
+    }
+    }
+    if constexpr (MODE != 0) {
         if (xq_out != nullptr && blockIdx.x == 0) {
             for (int i = tid * 16; i < M * Kb; i += 1024 * 16)
                 *reinterpret_cast<v4i*>(xq_out + i) = *(__attribute__((address_space(3))) const v4i*)(xs + i);
