@@ -115,7 +115,7 @@ size_t pq_linear_workspace_bytes(int64_t M, int64_t K);
 size_t pq_linear_workspace_bytes_split(int64_t M, int64_t N, int64_t K);
 
 /* The whole layer: pq_rotate_quant into `workspace`, then pq_w4a4_gemm (same stream).
- * For M <= 4 and M*K <= 8192 (16384 without rotation, or for a single token) the two steps run in
+ * For M <= 4 and M*K <= 8192 (16384 for a single token, 32768 without rotation) the two steps run in
  * one fused launch (every workgroup rotates and quantizes the few rows for itself while its first
  * weight loads are in flight).
  * workspace: device memory, 256-byte aligned, at least pq_linear_workspace_bytes(M,K);

@@ -82,6 +82,19 @@ int pick_with_planes(int64_t M, int64_t N, int64_t K, size_t plane_bytes, int32_
     return kernel;
 }
 
+// Whether pq_linear takes the fused launch (every workgroup rotates and quantizes the few rows for itself)
+// when the shape allows it, rather than a quantizer launch and a product launch.  Measured with cold weights
+// on 8 to 117 MB matrices: without rotation the fused launch is level or ahead up to 32768 channels in all
+// (the rows then pass through the quantizer in the registers they were loaded into; 4 tokens of 8192: 10.1
+// against 12.6 us); with rotation a CU spends about 0.2 us per 1024 channels, level for one token up to
+// 16384 channels (7.4 us both ways at 14336), behind from two tokens on (11.3 against 10.2 us).
+inline bool fused_few_tokens(int64_t M, int64_t K, int32_t had_block)
+{
+    const int64_t total = M * K;
+    if (had_block <= 1) return total <= 32768;
+    return total <= 8192 || (M == 1 && total <= 16384);
+}
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool good_scale(float s) { return isfinite(s) && s > 0.0f; }
 
@@ -201,10 +214,7 @@ int pq_linear(const void* x_f16, const void* wq_packed, const float* w_scale, fl
         return PQ_ERR_SHAPE;
     if (!aligned16(x_f16)) return PQ_ERR_ALIGN;
     // decode: one fused launch (rotate + quantize per workgroup, weights streamed once)
-    // (quantizing a row costs every CU about 0.2 us per 1024 channels, so long rows keep two launches)
-    // (without rotation the per-CU cost is lower: up to 16384 elements measured equal or faster fused;
-    // a single token also with rotation: 8.3 against 9.1 us at K = 14336, equal at 16384, slower beyond)
-    if (((g_variant == 0 && (M * K <= 8192 || ((had_block <= 1 || M == 1) && M * K <= 16384))) || g_variant == 4) &&
+    if (((g_variant == 0 && fused_few_tokens(M, K, had_block)) || g_variant == 4) &&
         pq::decode_supported(M, N, K, had_block))
         return pq::launch_decode(x_f16, nullptr, wq_packed, w_scale, act_scale, had_block, M, N, K, out_f16, nullptr,
                                  workspace, static_cast<hipStream_t>(stream));
@@ -233,7 +243,7 @@ int pq_linear2(const void* x_f16, const void* wq_a, const float* w_scale_a, int6
         return PQ_ERR_SHAPE;
     if (!aligned16(x_f16)) return PQ_ERR_ALIGN;
     // few tokens: one launch streams both matrices (the rule of pq_linear, on the rows of both)
-    if (((g_variant == 0 && (M * K <= 8192 || ((had_block <= 1 || M == 1) && M * K <= 16384))) || g_variant == 4) &&
+    if (((g_variant == 0 && fused_few_tokens(M, K, had_block)) || g_variant == 4) &&
         N_a + N_b <= (1 << 30) && pq::decode_supported(M, N_a + N_b, K, had_block)) {
         const pq::DecodeSecond second{static_cast<const uint8_t*>(wq_b), w_scale_b, static_cast<__half*>(out_b_f16), (int)N_a};
         return pq::launch_decode(x_f16, nullptr, wq_a, w_scale_a, act_scale, had_block, M, N_a + N_b, K, out_a_f16, nullptr,

@@ -10,8 +10,8 @@
 //     else happens, the others as soon as the activation rows are staged;
 //   - the activation rows are rotated, quantized and packed by every workgroup (= every CU)
 //     for itself while those loads are in flight (a second launch would cost more than the
-//     redundant arithmetic); rows of up to 16384 channels in all go from the registers they were
-//     loaded into straight through the quantizer, 8 or 16 channels per thread;
+//     redundant arithmetic); rows of up to 32768 channels in all go from the registers they were
+//     loaded into straight through the quantizer, 8 to 32 channels per thread;
 //   - a wavefront-load is 1 KiB of ONE weight row (lane l: bytes 16 l .. 16 l + 15), the most
 //     contiguous access the canonical layout allows;
 //   - the products use v_dot8_i32_i4 directly on packed nibbles (no expansion), and the 64
@@ -92,7 +92,7 @@ __global__ __launch_bounds__(1024) void k_decode(const __half* __restrict__ x, c
 
     // ---- 1. first pieces of the activation rows (ordinary loads, issued before the weights:
     // loads complete in order, so waiting for these leaves the weight loads in flight)
-    constexpr int XB = 2;   // enough for one token of 16384 channels; more pieces wait behind the weights
+    constexpr int XB = 4;   // enough for 32768 channels in all (e.g. one token of 28672); more pieces wait behind the weights
     const uint8_t* xsrc = MODE == 0 ? xq_in : reinterpret_cast<const uint8_t*>(x);
     const int pieces = (MODE == 0 ? M * Ka : M * K * 2) >> 4;   // 16-byte pieces
     uint8_t* xdst = MODE == 0 ? xs : smem + xraw_off;
@@ -100,7 +100,10 @@ __global__ __launch_bounds__(1024) void k_decode(const __half* __restrict__ x, c
 #pragma unroll
     for (int u = 0; u < XB; ++u) {
         const int i = tid + 1024 * u;
-        xr[u] = *reinterpret_cast<const v4i*>(xsrc + (i < pieces ? i : 0) * 16);   // branch-free: clamped
+        if (u < 2 || 1024 * u < pieces)                                            // (workgroup-uniform)
+            xr[u] = *reinterpret_cast<const v4i*>(xsrc + (i < pieces ? i : 0) * 16);   // lanes: clamped, no branch
+        else
+            xr[u] = (v4i){0, 0, 0, 0};
     }
     __builtin_amdgcn_sched_barrier(0);
     // every wavefront has issued its row loads before any weight load enters the memory pipeline:

@@ -149,7 +149,11 @@ def test_linear_end_to_end(pq, M, K, N, h):
 @pytest.mark.parametrize("M,K,N,h", [(1, 4096, 4096, 1), (1, 4096, 6144, 4096), (1, 14336, 4096, 128), (2, 14336, 512, 128),
                                      (3, 8192, 256, 8192), (4, 4096, 1024, 1), (4, 2048, 128, 1024), (1, 11008, 256, 128),
                                      (4, 28672, 64, 128), (1, 28672, 8192, 128), (2, 1024, 48, 2048 // 2), (1, 32, 16, 32),
-                                     (3, 96, 32, 1), (1, 8192, 10240, 1)])
+                                     (3, 96, 32, 1), (1, 8192, 10240, 1),
+                                     # rows quantized from the registers they were loaded into: all four pieces of a
+                                     # thread, a partial last piece, rotation blocks of 64 to 512 channels
+                                     (4, 8192, 256, 1), (3, 10240, 64, 1), (2, 8192, 128, 512), (1, 2048, 64, 256),
+                                     (4, 4096, 64, 64), (2, 12288, 32, 128)])
 def test_decode_fused_linear(pq, M, K, N, h):
     # M <= 4: pq_linear is one fused launch; codes in the workspace, output against the oracle
     L = prepare_layer(M, K, N, h, seed=K + N + h)
