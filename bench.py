@@ -66,6 +66,12 @@ LINEARS = [("qkv", 4096, 6144, 1), ("o", 4096, 4096, 1), ("gate", 4096, 14336, 1
            ("up", 4096, 14336, 1), ("down", 14336, 4096, 128)]
 
 
+# Llama-2-7B block linears (the benchmark configuration's second case): q/k/v (one matrix here) and o behind the
+# full 4096-point rotation, gate/up to 11008 channels, down behind 128-point blocks
+LINEARS_7B = [("qkv", 4096, 12288, 4096), ("o", 4096, 4096, 4096), ("gate", 4096, 11008, 1),
+              ("up", 4096, 11008, 1), ("down", 11008, 4096, 128)]
+
+
 # Llama-3-70B single-layer linears (the benchmark configuration's large case, one GPU's view of a layer)
 LINEARS_70B = [("qkv", 8192, 10240, 1), ("o", 8192, 8192, 1), ("gate", 8192, 28672, 1),
                ("up", 8192, 28672, 1), ("down", 28672, 8192, 128)]
@@ -327,6 +333,50 @@ def run_prefill_8192(torch, pq, layers, steps=10, warmup=3):
     ops = sum(2.0 * M * L["K"] * L["N"] for L in layers)
     return {"ms_per_step": round(t * 1e3, 4), "TOPS": round(ops / t / 1e12, 1),
             "per_linear_TOPS": {L["name"]: round(2.0 * M * L["K"] * L["N"] / g[L["name"]] / 1e12, 1) for L in layers}}
+
+
+def run_llama2_7b(torch, pq, synth, steps=20, warmup=5):
+    """Llama-2-7B block linears at M = 2048 through the whole-layer entry points (the 4096-point rotation of q/k/v/o is
+    beyond the tile-writing quantizer's 512, so pq_linear_f6 takes pq_rotate_quant + repack there): wall time per
+    step, median of three regions, weights' copies in turn, the fp16 GEMM beside it."""
+    layers = prepare_layers(torch, synth, M_PREFILL, LINEARS_7B, device_weights=True)
+    ops = sum(2.0 * M_PREFILL * L["K"] * L["N"] for L in layers)
+    for L in layers:
+        weight_sets(L, "w6", WEIGHT_SETS)
+        weight_sets(L, "wq", WEIGHT_SETS)
+        L["work"] = torch.empty((max(pq.pq_linear_workspace_bytes(M_PREFILL, L["K"]),
+                                     pq.pq_linear_f6_workspace_bytes(M_PREFILL, L["K"], L["h"])),), dtype=torch.uint8, device="cuda")
+    count = [0]
+
+    def f6():
+        count[0] += 1
+        for L in layers:
+            pq.pq_linear_f6(L["x"], L["w6_sets"][count[0] % WEIGHT_SETS], L["sw"], L["sx"], L["h"], out=L["out"], workspace=L["work"])
+
+    def int8():
+        count[0] += 1
+        for L in layers:
+            pq.pq_linear(L["x"], L["wq_sets"][count[0] % WEIGHT_SETS], L["sw"], L["sx"], L["h"], out=L["out"], workspace=L["work"])
+
+    res = {"linears": "qkv 4096->12288 and o 4096->4096 (4096-point rotation), gate/up 4096->11008, down 11008->4096 (128-point blocks)"}
+    for name, step in (("pq_linear_f6", f6), ("pq_linear", int8)):
+        device_warmup(torch)
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(3):
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                step()
+            torch.cuda.synchronize()
+            ts.append((time.perf_counter() - t0) / steps)
+        dt = sorted(ts)[1]
+        res[name] = {"ms_per_step": round(dt * 1e3, 4), "TOPS": round(ops / dt / 1e12, 1)}
+    t16 = run_fp16(torch, layers, 5, 2)
+    res["fp16_ms_per_step"] = round(t16 * 1e3, 4)
+    res["speedup_vs_fp16"] = round(t16 / (res["pq_linear_f6"]["ms_per_step"] * 1e-3), 3)
+    return res
 
 
 def run_llama3_70b(torch, pq, synth, decode=True):
@@ -859,6 +909,8 @@ def main():
         leg("serving_batch", serving_leg)
     if not args.no_variants:
         del layers
+        torch.cuda.empty_cache()
+        leg("llama2_7b", lambda: run_llama2_7b(torch, pq, synth))
         torch.cuda.empty_cache()
         leg("llama3_70b", lambda: run_llama3_70b(torch, pq, synth, decode=not args.no_decode))
     if not args.no_cpu:
