@@ -183,15 +183,6 @@ __global__ __launch_bounds__(256) void k_rotate_quant_f6(const __half* __restric
     }
 }
 
-__device__ __forceinline__ int xcd_run(int b, int total)   // each XCD takes a contiguous run of tiles
-{
-    const int x = b & 7, idx = b >> 3, q = total >> 3, rem = total & 7;
-    return x * q + (x < rem ? x : rem) + idx;
-}
-
-#define PQ6_LDS(p) ((__attribute__((address_space(3))) void*)(p))
-#define PQ6_GLB(p) ((const __attribute__((address_space(1))) void*)(p))
-
 template <int I, int N, typename F>
 __device__ __forceinline__ void static_for6(F&& f)
 {
@@ -200,6 +191,136 @@ __device__ __forceinline__ void static_for6(F&& f)
         static_for6<I + 1, N>(f);
     }
 }
+
+// The 128-point block rotation as a product on the matrix pipe, fused with the quantizer (App. B "Online
+// Rotation" + Eq. 1).  Butterflies cost about 25 vector instructions per element with conversion and
+// quantizer, which bounds the kernel above (2048 x 14336: 23.6 us for 81 MB); here Y^T = H X^T runs on
+// v_mfma_f32_32x32x16_f16 (the fp16 inputs as they are, the +-1 of H exact in fp16, fp32 accumulate: the same
+// sums of 128 terms as the butterflies, in another order, so codes can differ from theirs only where the
+// rotated value sits within fp32 rounding of a tie) and the vector pipe is left with the quantizer and the images.
+//
+// One wavefront = 32 tokens x 128 channels = one rotation block = one block of the tiles, no barriers:
+//  - 8 coalesced 16-byte loads per lane (4 tokens x 256 bytes per instruction) into a padded LDS tile of its own;
+//  - per 16-channel step the token operand (lane = token l % 32, 8 channels 16 s + 8 (l / 32) ...) is one LDS
+//    read; the H operand (lane = output channel j = 32 n + l % 32, same 8 input channels i) is +-1 with sign
+//    parity(popcount(i & j)): the low three bits of i give a per-lane pattern, the bits above flip all eight
+//    together, by lane for bits 3 and 4 and by (n, s) at compile time for bits 5 and 6: four register sets
+//    prepared once serve all 32 matrix instructions;
+//  - the accumulators leave a lane with one token and, per 32 channels, the channels 8 q + 4 (l / 32) + 0..3:
+//    four codes make 16 bits; one exchange between the two half-wavefronts (v_permlane32_swap) pairs them to
+//    dwords of eight channels, a second one hands each half-wavefront the four dwords of its own 32 channels,
+//    which is the 16 bytes of canonical nibbles (stored if asked for) and the input of the register image.
+constexpr int kXPitch = 272;      // LDS row of 128 fp16 + 16 bytes: the 16-byte operand reads of 32 rows spread over all banks
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+
+// (at least four wavefronts per SIMD: with that bound the compiler keeps the accumulators in ordinary registers,
+// which the quantizer reads directly, instead of accumulation registers that cost a move per value)
+template <int WAVES>
+__global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(4, 8))) void k_rotate128_quant_mfma(
+    const __half* __restrict__ x, int M, int K, rq::StaticStep steps, uint8_t* __restrict__ tiles, uint8_t* __restrict__ nibbles)
+{
+    __shared__ __align__(16) uint8_t stage_all[WAVES * 32 * kXPitch];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int nk = K >> 7, kt = blockIdx.x * WAVES + wave, rb = blockIdx.y;
+    if (kt >= nk) return;                                   // (no barriers below: wavefronts are independent)
+    uint8_t* stg = stage_all + wave * (32 * kXPitch);
+    const int t = lane & 31, g = lane >> 5;
+    // ---- tokens into LDS
+    {
+        const int r4 = lane >> 4, c = lane & 15;
+        // (wavefront-uniform 64-bit base, 32-bit lane offsets: 32 rows of at most 2^24 channels)
+        const uint8_t* base = reinterpret_cast<const uint8_t*>(x + ((int64_t)rb * 32 * K + (int64_t)kt * 128));
+        const int rows_left = M - rb * 32;                  // >= 1
+        v4i raw[8];
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+            const int r = 4 * p + r4;
+            const bool in = r < rows_left;
+            const uint32_t off = ((uint32_t)(in ? r : 0) * (uint32_t)K + (uint32_t)c * 8u) * 2u;
+            raw[p] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(base + off));
+            if (!in) raw[p] = (v4i){0, 0, 0, 0};             // tokens past the end: zero codes
+        }
+#pragma unroll
+        for (int p = 0; p < 8; ++p)
+            *(__attribute__((address_space(3))) v4i*)(stg + (4 * p + r4) * kXPitch + c * 16) = raw[p];
+    }
+    // ---- the H operand: hreg[s & 1][flip by (n, s)][4 dwords of two fp16 each]
+    uint32_t hreg[2][2][4];
+    {
+        const int j = t;                                    // low five bits of the output channel
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const uint32_t lo = __builtin_popcount((2 * d) & j & 7) & 1, hi = __builtin_popcount((2 * d + 1) & j & 7) & 1;
+            const uint32_t base = 0x3C003C00u ^ (lo << 15) ^ (hi << 31);
+            const uint32_t f0 = (uint32_t)(g & (j >> 3)) & 1u;              // input bit 3 = half-wavefront
+            const uint32_t f1 = f0 ^ ((uint32_t)(j >> 4) & 1u);            // input bit 4 = s & 1
+            hreg[0][0][d] = base ^ (f0 * 0x80008000u);
+            hreg[0][1][d] = hreg[0][0][d] ^ 0x80008000u;
+            hreg[1][0][d] = base ^ (f1 * 0x80008000u);
+            hreg[1][1][d] = hreg[1][0][d] ^ 0x80008000u;
+        }
+    }
+    v16f acc[4];
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[n][v] = 0.0f;
+    static_for6<0, 8>([&](auto sc) {
+        constexpr int s = decltype(sc)::value;
+        const v4i xi = *(__attribute__((address_space(3))) const v4i*)(stg + t * kXPitch + 32 * s + 16 * g);
+        const v8h xop = __builtin_bit_cast(v8h, xi);
+        static_for6<0, 4>([&](auto nc) {
+            constexpr int n = decltype(nc)::value;
+            constexpr int flip = __builtin_popcount((s >> 1) & n) & 1;     // input bits 5, 6 against output bits 5, 6
+            const v4i hi4 = {(int)hreg[s & 1][flip][0], (int)hreg[s & 1][flip][1], (int)hreg[s & 1][flip][2], (int)hreg[s & 1][flip][3]};
+            acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, hi4), xop, acc[n], 0, 0, 0);
+        });
+    });
+    // ---- quantize, pair, exchange
+    uint32_t lo2[4], hi2[4];                                // per 32 channels: dwords of channels 8 q .. for q = 2 g, 2 g + 1
+    static_for6<0, 4>([&](auto nc) {
+        constexpr int n = decltype(nc)::value;
+        float v01[8], v23[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { v01[i] = acc[n][i]; v23[i] = acc[n][8 + i]; }
+        // low half: four channels of group q = 0 (2), high half: of q = 1 (3), all of this lane's half 4 g ..
+        uint32_t w01 = rq::quant_pack8<false>(v01, v01, steps.mult, steps.step);
+        uint32_t w23 = rq::quant_pack8<false>(v23, v23, steps.mult, steps.step);
+        // after the swap the lower half-wavefront holds (w01 of its own, w01 of the upper), the upper (w23 of the lower, its own w23)
+        const auto sw = __builtin_amdgcn_permlane32_swap(w01, w23, false, false);
+        const uint32_t mine = sw[0], theirs = sw[1];        // channels 4 * 0 .. of two groups, channels 4 * 1 .. of the same two
+        lo2[n] = __builtin_amdgcn_perm(theirs, mine, 0x05040100u);   // group 2 g:     mine.lo16 | theirs.lo16 << 16
+        hi2[n] = __builtin_amdgcn_perm(theirs, mine, 0x07060302u);   // group 2 g + 1: mine.hi16 | theirs.hi16 << 16
+    });
+    const int64_t row = (int64_t)rb * 32 + t;
+    uint8_t* block = tiles ? tiles + ((int64_t)kt * gridDim.y + rb) * kChunkF6 : nullptr;
+    static_for6<0, 2>([&](auto stc) {
+        constexpr int st = decltype(stc)::value;
+        // tiles 2 st (for the lower half-wavefront) and 2 st + 1 (for the upper): the lower half gives its dwords of
+        // the odd tile and takes the upper half's dwords of the even one
+        uint32_t ea = lo2[2 * st], eb = hi2[2 * st], oa = lo2[2 * st + 1], ob = hi2[2 * st + 1];
+        const auto sa = __builtin_amdgcn_permlane32_swap(ea, oa, false, false);
+        const auto sb = __builtin_amdgcn_permlane32_swap(eb, ob, false, false);
+        const v4i p = {(int)sa[0], (int)sb[0], (int)sa[1], (int)sb[1]};   // channels 0-7, 8-15, 16-23, 24-31 of this lane's 32
+        if (nibbles && row < M)
+            *reinterpret_cast<v4i*>(nibbles + row * (K >> 1) + (int64_t)kt * 64 + st * 32 + g * 16) = p;
+        if (block) {
+            uint64_t w[3];
+            image_of_nibbles(p, w);
+            store_image(block, lane, st, w);
+        }
+    });
+}
+
+__device__ __forceinline__ int xcd_run(int b, int total)   // each XCD takes a contiguous run of tiles
+{
+    const int x = b & 7, idx = b >> 3, q = total >> 3, rem = total & 7;
+    return x * q + (x < rem ? x : rem) + idx;
+}
+
+#define PQ6_LDS(p) ((__attribute__((address_space(3))) void*)(p))
+#define PQ6_GLB(p) ((const __attribute__((address_space(1))) void*)(p))
 
 // 16 bytes per lane from global memory straight into LDS (lane l lands at lds_addr + 16 l); base and
 // lds_addr are wavefront-uniform.  Issued as inline assembly on purpose: the compiler's bookkeeping of
@@ -622,9 +743,23 @@ static void launch_quant_f6_c(int c, const void* x, int64_t R, int64_t K, int lo
     else hipLaunchKernelGGL((k_rotate_quant_f6<EXACT, 512>), grid, dim3(256), 0, st, xp, (int)R, (int)K, log2h, steps, op, np);
 }
 
+// 128-point blocks: rotation on the matrix pipe.  out (tiles) or nibbles may be NULL, not both.
+bool rotate128_mfma_supported(int64_t R, int64_t K, int32_t h) { return h == 128 && (K % 128) == 0 && (R + 31) / 32 <= 65535 && K <= (1 << 24) && R >= 1; }
+
+int launch_rotate128_mfma(const void* x, int64_t R, int64_t K, float act_scale, void* tiles, void* nibbles, hipStream_t st)
+{
+    constexpr int W = 4;      // wavefronts per workgroup (1, 2 and 4 measured level)
+    const dim3 grid((unsigned)((K / 128 + W - 1) / W), (unsigned)((R + 31) / 32));
+    const rq::StaticStep steps{(float)(1.0 / ((double)act_scale * sqrt(128.0))), act_scale};
+    hipLaunchKernelGGL(k_rotate128_quant_mfma<W>, grid, dim3(64 * W), 0, st, static_cast<const __half*>(x), (int)R, (int)K, steps,
+                       static_cast<uint8_t*>(tiles), static_cast<uint8_t*>(nibbles));
+    return hip_status(hipGetLastError());
+}
+
 int launch_quant_f6(const void* x, int64_t R, int64_t K, int32_t h, float act_scale, void* out, void* nibbles, hipStream_t st)
 {
     if (!quant_f6_supported(R, K, h)) return PQ_ERR_UNSUPPORTED;
+    if (rotate128_mfma_supported(R, K, h)) return launch_rotate128_mfma(x, R, K, act_scale, out, nibbles, st);
     const int c = h <= 128 ? 128 : h;                    // channels per workgroup: the rotation block, at least 128
     if (h <= 1) {
         launch_quant_f6_c<true>(c, x, R, K, 0, rq::StaticStep{(float)(1.0 / (double)act_scale), act_scale}, out, nibbles, st);

@@ -66,6 +66,8 @@ int launch_probe_mfma_f6(const void* operands, int64_t operand_bytes, int64_t it
                          hipStream_t st);
 // f6 tiles: the register images of the 6-bit matrix instruction, see pq_gemm_f6.hip
 size_t f6_tiles_bytes(int64_t R, int64_t K);
+bool rotate128_mfma_supported(int64_t R, int64_t K, int32_t h);
+int launch_rotate128_mfma(const void* x, int64_t R, int64_t K, float act_scale, void* tiles, void* nibbles, hipStream_t st);
 bool quant_f6_supported(int64_t R, int64_t K, int32_t h);
 int launch_quant_f6(const void* x, int64_t R, int64_t K, int32_t h, float act_scale, void* out, void* nibbles, hipStream_t st);
 int launch_repack_f6(const void* codes, int64_t R, int64_t K, void* out, hipStream_t st);

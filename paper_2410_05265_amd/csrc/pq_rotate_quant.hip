@@ -320,6 +320,9 @@ int launch_dyn(const __half* xp, int64_t M, int64_t K, int32_t h, float clip, ui
 
 int launch_rotate_quant(const void* x, int64_t M, int64_t K, int32_t h, float act_scale, void* xq, hipStream_t st)
 {
+    // 128-point blocks (down_proj of the Llama models): the rotation runs on the matrix pipe, in the kernel that
+    // also writes the prepacked form, so both forms of the layer see the same codes
+    if (rotate128_mfma_supported(M, K, h)) return launch_rotate128_mfma(x, M, K, act_scale, nullptr, xq, st);
     return launch_rq<4>(static_cast<const __half*>(x), M, K, h, static_step(act_scale, h), static_cast<uint32_t*>(xq), st);
 }
 

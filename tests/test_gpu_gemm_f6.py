@@ -204,6 +204,47 @@ def test_tile_writing_quantizer(pq, M, K, h):
         pq.pq_rotate_quant_f6(dev(synth.activations(4, 2048, seed=1)), 1024, sx)
 
 
+@pytest.mark.parametrize("M,K", [(1, 128), (37, 640), (100, 1408), (32, 512), (65, 14336)])
+def test_rotation_of_128_point_blocks_on_the_matrix_pipe(pq, M, K):
+    """128-point blocks take the kernel that rotates with matrix instructions (both outputs of it: canonical
+    nibbles and tiles).  Against the oracle's fp64 rotation: codes differ only where the rotated value is at a
+    rounding tie; token counts that are not multiples of 32, channel counts that are not multiples of 512."""
+    x = synth.activations(M, K, seed=3 * M + K)
+    y = O.rotate(x, 128)
+    sx = np.float32(np.abs(y).max() / 7.0)
+    want = O.quantize(y, sx)
+    codes = host(pq.pq_rotate_quant(dev(x), 128, float(sx)))
+    nib = torch.full((M, K // 2), 0x55, dtype=torch.uint8, device="cuda")
+    tiles = pq.pq_rotate_quant_f6(dev(x), 128, float(sx), codes=nib)
+    assert np.array_equal(host(nib), codes)
+    assert np.array_equal(codes_of_tiles(host(tiles), M, K), O.unpack(codes))
+    assert np.array_equal(host(tiles)[: pq.pq_f6_tiles_bytes(M, K)], tiles_by_definition(O.unpack(codes)))
+    got = O.unpack(codes).astype(np.int32)
+    diff = got - want.astype(np.int32)
+    at = np.nonzero(diff)
+    assert at[0].size <= 1e-3 * diff.size
+    if at[0].size:
+        assert np.all(np.abs(diff[at]) == 1)
+        t = y[at] / np.float64(sx)
+        assert np.all(np.abs(t - (np.minimum(got[at], want[at]) + 0.5)) <= 1e-3)
+
+
+def test_rotation_on_the_matrix_pipe_one_hot_and_constant_rows(pq):
+    """Rows whose rotation is known in closed form: a one-hot row becomes +-v / sqrt(128) in its block (the signs
+    are a row of the Hadamard matrix), a constant block becomes sqrt(128) v in its first channel and zero elsewhere."""
+    K = 384
+    x = np.zeros((130, K), dtype=np.float16)
+    for r in range(128):
+        x[r, 128 + r] = np.float16(3.0 + (r % 5))            # one-hot at every position of the second block
+    x[128, :128] = np.float16(0.25)                           # constant first block
+    x[129, 256:] = np.float16(-1.5)                           # constant third block
+    sx = np.float32(0.1)                                      # 3..7 / sqrt(128) / 0.1 = 2.65 .. 6.19: away from ties
+    want = O.quantize(O.rotate(x, 128), sx)
+    got = O.unpack(host(pq.pq_rotate_quant(dev(x), 128, float(sx))))
+    assert np.array_equal(got, want)
+    assert np.array_equal(codes_of_tiles(host(pq.pq_rotate_quant_f6(dev(x), 128, float(sx))), 130, K), want)
+
+
 def test_unrotated_quantizer_to_tiles_is_exact_for_every_fp16_value(pq):
     """The tile-writing quantizer (no rotation) on all finite fp16 values and on constructed ties: the codes
     behind the tiles equal the oracle's."""
