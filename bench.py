@@ -871,6 +871,10 @@ def main():
                                          block_frac_hbm=round(b_block / t_block / 1e9 / HBM_PEAK_GBS, 3))
         if "stream_read_GBps" in result.get("achievable", {}):
             result["achievable"]["decode_frac_of_stream_read"] = round(dec["GBps"] / result["achievable"]["stream_read_GBps"], 4)
+            # the read-only kernel on one cold matrix of each size: what a single launch that streams that many bytes costs
+            result["achievable"]["stream_read_at_size"] = {
+                "%.1f MB" % (L["N"] * L["K"] / 2 / 1e6): {"us": pl[L["name"]]["read_only_us"], "GBps": pl[L["name"]]["read_only_GBps"]}
+                for L in layers}
         for m in (4, 16):
             d = run_decode(torch, pq, layers, M=m)
             dec["M%d" % m] = {"GBps": d["GBps"], "frac_hbm": d["frac_hbm"],
