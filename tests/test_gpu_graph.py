@@ -65,6 +65,80 @@ def test_linear_replays_match_eager(pq, M, K, N, h, planes):
             torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("M,K,N,h", [(300, 1024, 768, 128), (256, 512, 896, 1), (130, 2048, 512, 512), (64, 4096, 256, 4096)])
+def test_prepacked_linear_replays_match_eager(pq, M, K, N, h):
+    """pq_linear_f6 (tile-writing quantizer or matrix-pipe rotation, persistent product kernel, N = 896 as two tile
+    widths in one launch, the 4096-point rotation through quantizer + repack) captured and replayed."""
+    wq, sw = O.weight_rtn(synth.weights(N, K, seed=5))
+    w6 = pq.pq_repack_f6(dev(O.pack(wq)))
+    dsw = dev(sw)
+    xs = [synth.activations(M, K, seed=60 + i) for i in range(3)]
+    sx = float(O.calibrate_absmax(synth.calibration(K, 5), h))
+    x = dev(xs[0])
+    out = torch.empty((M, N), dtype=torch.float16, device="cuda")
+    work = torch.empty((max(256, pq.pq_linear_f6_workspace_bytes(M, K, h)),), dtype=torch.uint8, device="cuda")
+    eager = []
+    for xi in xs:
+        x.copy_(torch.from_numpy(xi))
+        o, _ = pq.pq_linear_f6(x, w6, dsw, sx, h)
+        eager.append(host(o).view(np.uint16).copy())
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        x.copy_(torch.from_numpy(xs[0]))
+        pq.pq_linear_f6(x, w6, dsw, sx, h, out=out, workspace=work)
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            pq.pq_linear_f6(x, w6, dsw, sx, h, out=out, workspace=work)
+    torch.cuda.synchronize()
+    for rep in range(2):
+        for i, xi in enumerate(xs):
+            x.copy_(torch.from_numpy(xi))
+            out.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(host(out).view(np.uint16), eager[i]), (rep, i)
+            pq.pq_rotate_quant_f6(x, h if h <= 512 else 1, sx)            # eager work of the same library between replays
+            torch.cuda.synchronize()
+
+
+def test_two_matrices_replay_matches_eager(pq):
+    """pq_linear2 at one token (one fused launch for both matrices) and at 40 tokens (quantizer + two products)."""
+    K, Na, Nb, h = 4096, 1024, 528, 1
+    wa, swa = O.weight_rtn(synth.weights(Na, K, seed=7))
+    wb, swb = O.weight_rtn(synth.weights(Nb, K, seed=8))
+    dwa, dswa, dwb, dswb = dev(O.pack(wa)), dev(swa), dev(O.pack(wb)), dev(swb)
+    sx = float(O.calibrate_absmax(synth.calibration(K, 7), h))
+    for M in (1, 40):
+        xs = [synth.activations(M, K, seed=70 + i) for i in range(2)]
+        x = dev(xs[0])
+        oa = torch.empty((M, Na), dtype=torch.float16, device="cuda")
+        ob = torch.empty((M, Nb), dtype=torch.float16, device="cuda")
+        work = torch.empty((max(256, pq.pq_linear_workspace_bytes(M, K)),), dtype=torch.uint8, device="cuda")
+        eager = []
+        for xi in xs:
+            x.copy_(torch.from_numpy(xi))
+            a, b, _ = pq.pq_linear2(x, dwa, dswa, dwb, dswb, sx, h)
+            eager.append((host(a).view(np.uint16).copy(), host(b).view(np.uint16).copy()))
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            pq.pq_linear2(x, dwa, dswa, dwb, dswb, sx, h, out_a=oa, out_b=ob, workspace=work)
+            side.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                pq.pq_linear2(x, dwa, dswa, dwb, dswb, sx, h, out_a=oa, out_b=ob, workspace=work)
+        torch.cuda.synchronize()
+        for rep in range(2):
+            for i, xi in enumerate(xs):
+                x.copy_(torch.from_numpy(xi))
+                oa.zero_(); ob.zero_()
+                torch.cuda.synchronize()
+                graph.replay()
+                torch.cuda.synchronize()
+                assert np.array_equal(host(oa).view(np.uint16), eager[i][0]) and np.array_equal(host(ob).view(np.uint16), eager[i][1]), (M, rep, i)
+
+
 def test_quantizer_family_replays_match_eager(pq):
     M, K = 64, 4096
     xs = [synth.activations(M, K, seed=50 + i) for i in range(3)]
