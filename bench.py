@@ -230,7 +230,8 @@ def run_prefill(torch, pq, layers, steps, warmup, path="f6", repeats=REPEATS, se
 def run_variants(torch, pq, layers, steps, warmup, ops):
     """The same step through the layer's other entry points: pq_linear_f6 itself (one call per linear), the
     canonical path pq_linear (INT8 matrix instruction), 8-bit static activations (the paper's W4A8 setting),
-    per-token dynamic steps (Table 1 row O1) at 4 and 8 bits, gate and up as one matrix, the products alone.
+    per-token dynamic steps (Table 1 row O1) at 4 and 8 bits, gate and up behind one quantizer (pq_linear2_f6), the
+    products alone.
     Wall time per step, median of three timed regions; the weights' copies taken in turn as in run_prefill."""
     M = layers[0]["x"].shape[0]
     for L in layers:
@@ -268,18 +269,16 @@ def run_variants(torch, pq, layers, steps, warmup, ops):
                 pq.pq_gemm_dynamic(q, bits, W(L, "wq"), L["sw"], L["srow"], out=L["out"])
         return step
 
-    # gate and up read the same tensor in the model: one quantization and one [28672, 4096] weight matrix
+    # gate and up read the same tensor in the model: pq_linear2_f6 quantizes it once (two products, two outputs)
     gate, up = layers[2], layers[3]
-    wq_gu = torch.cat([gate["wq"], up["wq"]]).contiguous()
-    gu = dict(gate, w6=pq.pq_repack_f6(wq_gu), sw=torch.cat([gate["sw"], up["sw"]]).contiguous(), N=gate["N"] + up["N"],
-              out=torch.empty((M, gate["N"] + up["N"]), dtype=torch.float16, device="cuda"))
-    del wq_gu, gu["w6_sets"]
-    weight_sets(gu, "w6", WEIGHT_SETS)
-    fused_layers = [layers[0], layers[1], gu, layers[4]]
 
-    def gate_up_one_matrix():
-        for L in fused_layers:
+    def gate_up_one_quantizer():
+        for L in (layers[0], layers[1]):
             pq.pq_linear_f6(L["x"], W(L, "w6"), L["sw"], L["sx"], L["h"], out=L["out"], workspace=L["work"])
+        pq.pq_linear2_f6(gate["x"], W(gate, "w6"), gate["sw"], W(up, "w6"), up["sw"], gate["sx"], gate["h"],
+                         out_a=gate["out"], out_b=up["out"], workspace=gate["work"])
+        L = layers[4]
+        pq.pq_linear_f6(L["x"], W(L, "w6"), L["sw"], L["sx"], L["h"], out=L["out"], workspace=L["work"])
 
     def f6_products_only():
         for L in layers:
@@ -298,7 +297,7 @@ def run_variants(torch, pq, layers, steps, warmup, ops):
     res = {}
     for name, step in (("w4a4_static_f6_linear", f6_linear), ("w4a4_static_int8_linear", int8_linear),
                        ("w4a8_static", w4a8_static), ("w4a4_dynamic", dynamic(4)), ("w4a8_dynamic", dynamic(8)),
-                       ("w4a4_static_f6_gate_up_one_matrix", gate_up_one_matrix),
+                       ("w4a4_static_f6_gate_up_one_quantizer", gate_up_one_quantizer),
                        ("w4a4_products_only_f6", f6_products_only), ("w4a4_products_only_int8", int8_products_only)):
         step = counted(step)
         device_warmup(torch)

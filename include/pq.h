@@ -241,6 +241,14 @@ int pq_linear_f6(const void* x_f16, const void* w_tiles, const float* w_scale,
                  float act_scale, int32_t had_block, int64_t M, int64_t N, int64_t K,
                  void* out_f16, void* workspace, size_t workspace_bytes, void* stream);
 
+/* pq_linear2 on the prepacked path: two weight matrices as f6 tiles on the same tokens (gate_proj and up_proj),
+ * X rotated, quantized and written as tiles once, two products.  Outputs equal those of two pq_linear_f6 calls
+ * (and of pq_linear2 on the canonical weights) bit for bit.  Arguments as for pq_linear_f6; workspace of
+ * pq_linear_f6_workspace_bytes(M, K, had_block). */
+int pq_linear2_f6(const void* x_f16, const void* w_tiles_a, const float* w_scale_a, int64_t N_a, void* out_a_f16,
+                  const void* w_tiles_b, const float* w_scale_b, int64_t N_b, void* out_b_f16, float act_scale,
+                  int32_t had_block, int64_t M, int64_t K, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Force a kernel variant of pq_w4a4_gemm for sweeps and tests (host, process-wide,
  * not thread-safe): 0 = automatic, 1 = weight-streaming matrix tiles (M <= 32, K % 256 == 0 and
  * the codes of 8 tokens fit in LDS; else PQ_ERR_UNSUPPORTED), 2 = MFMA tiled, 3 = simple,

@@ -32,6 +32,7 @@ SIGNATURES = {
     "pq_w4a4_gemm_ws": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i64, _i64, _i64, _vp, _vp, _vp, _sz, _vp]),
     "pq_linear": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i32, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
     "pq_linear2": (ctypes.c_int, [_vp, _vp, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _f32, _i32, _i64, _i64, _vp, _sz, _vp]),
+    "pq_linear2_f6": (ctypes.c_int, [_vp, _vp, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _f32, _i32, _i64, _i64, _vp, _sz, _vp]),
     "pq_linear_noalloc_max_bytes": (_sz, []),
     "pq_linear_noalloc": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i32, _i64, _i64, _i64, _vp, _vp]),
     "pq_set_gemm_variant": (ctypes.c_int, [ctypes.c_int]),
@@ -227,6 +228,25 @@ def pq_linear2(x, wq_a, w_scale_a, wq_b, w_scale_b, act_scale, had_block, out_a=
     _check(lib().pq_linear2(_ptr(x), _ptr(wq_a), _ptr(w_scale_a), Na, _ptr(out_a), _ptr(wq_b), _ptr(w_scale_b), Nb,
                             _ptr(out_b), float(act_scale), int(had_block), M, K, _ptr(workspace), workspace.numel(),
                             _stream()), "pq_linear2")
+    return out_a, out_b, workspace
+
+
+def pq_linear2_f6(x, w_tiles_a, w_scale_a, w_tiles_b, w_scale_b, act_scale, had_block, out_a=None, out_b=None, workspace=None):
+    """pq_linear2 with prepacked weights (pq_repack_f6).  Returns (out_a, out_b, workspace holding the tiles of Xq)."""
+    _dev(x, torch.float16, "x")
+    M, K = x.shape
+    for s in (w_scale_a, w_scale_b):
+        _dev(s, torch.float32, "w_scale")
+    Na, Nb = w_scale_a.numel(), w_scale_b.numel()
+    if workspace is None:
+        workspace = torch.empty((max(pq_linear_f6_workspace_bytes(M, K, had_block), 256),), dtype=torch.uint8, device=x.device)
+    if out_a is None:
+        out_a = torch.empty((M, Na), dtype=torch.float16, device=x.device)
+    if out_b is None:
+        out_b = torch.empty((M, Nb), dtype=torch.float16, device=x.device)
+    _check(lib().pq_linear2_f6(_ptr(x), _ptr(w_tiles_a), _ptr(w_scale_a), Na, _ptr(out_a), _ptr(w_tiles_b), _ptr(w_scale_b), Nb,
+                               _ptr(out_b), float(act_scale), int(had_block), M, K, _ptr(workspace), workspace.numel(),
+                               _stream()), "pq_linear2_f6")
     return out_a, out_b, workspace
 
 

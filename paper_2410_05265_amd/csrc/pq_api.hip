@@ -704,6 +704,41 @@ int pq_linear_f6(const void* x_f16, const void* w_tiles, const float* w_scale, f
     return pq::launch_gemm_f6(tiles, w_tiles, w_scale, act_scale, M, N, K, out_f16, nullptr, st);
 }
 
+int pq_linear2_f6(const void* x_f16, const void* w_tiles_a, const float* w_scale_a, int64_t N_a, void* out_a_f16,
+                  const void* w_tiles_b, const float* w_scale_b, int64_t N_b, void* out_b_f16, float act_scale,
+                  int32_t had_block, int64_t M, int64_t K, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (M < 0 || N_a <= 0 || N_b <= 0 || K <= 0 || (K % 128) != 0 || (N_a % 16) != 0 || (N_b % 16) != 0) return PQ_ERR_SHAPE;
+    if (!x_f16 || !w_tiles_a || !w_scale_a || !out_a_f16 || !w_tiles_b || !w_scale_b || !out_b_f16) return PQ_ERR_NULL;
+    if (M == 0) return PQ_OK;
+    if (had_block < 0 || had_block > 16384 ||
+        (had_block > 1 && ((had_block & (had_block - 1)) != 0 || (K % had_block) != 0)))
+        return PQ_ERR_SHAPE;
+    if (!workspace || workspace_bytes < pq_linear_f6_workspace_bytes(M, K, had_block)) return PQ_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return PQ_ERR_ALIGN;
+    int rc = check_gemm(workspace, w_tiles_a, w_scale_a, act_scale, M, N_a, K, out_a_f16, nullptr);
+    if (rc == PQ_OK) rc = check_gemm(workspace, w_tiles_b, w_scale_b, act_scale, M, N_b, K, out_b_f16, nullptr);
+    if (rc != PQ_OK) return rc;
+    if (!aligned16(x_f16)) return PQ_ERR_ALIGN;
+    const int64_t n_max = N_a > N_b ? N_a : N_b;
+    if (K > 262080 || M > (1 << 30) || n_max > (1 << 30) || pq::f6_tiles_bytes(M, K) >= ((size_t)1 << 32) ||
+        pq::f6_tiles_bytes(n_max, K) >= ((size_t)1 << 32) || M * K >= ((int64_t)1 << 32))
+        return PQ_ERR_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint8_t* tiles = static_cast<uint8_t*>(workspace);
+    if (!f6_needs_codes(M, K, had_block)) {
+        rc = pq::launch_quant_f6(x_f16, M, K, had_block, act_scale, tiles, nullptr, st);
+    } else {
+        uint8_t* nibbles = tiles + ((pq::f6_tiles_bytes(M, K) + 255) & ~(size_t)255);
+        rc = pq_rotate_quant(x_f16, M, K, had_block, act_scale, nibbles, stream);
+        if (rc == PQ_OK) rc = pq::launch_repack_f6(nibbles, M, K, tiles, st);
+    }
+    if (rc != PQ_OK) return rc;
+    rc = pq::launch_gemm_f6(tiles, w_tiles_a, w_scale_a, act_scale, M, N_a, K, out_a_f16, nullptr, st);
+    if (rc != PQ_OK) return rc;
+    return pq::launch_gemm_f6(tiles, w_tiles_b, w_scale_b, act_scale, M, N_b, K, out_b_f16, nullptr, st);
+}
+
 int pq_probe_stream_read(const void* src, int64_t bytes, int32_t* sink, void* stream)
 {
     if (!src || !sink) return PQ_ERR_NULL;

@@ -54,6 +54,21 @@ def test_two_matrices_one_quantization(pq, M, K, Na, Nb, h):
     assert np.array_equal(codes, host(wsb)[: M * K // 2].reshape(M, K // 2))
 
 
+@pytest.mark.parametrize("M,K,Na,Nb,h", [(70, 1152, 272, 528, 128), (300, 512, 896, 256, 1), (33, 4096, 64, 512, 4096)])
+def test_two_matrices_prepacked(pq, M, K, Na, Nb, h):
+    """pq_linear2_f6: the outputs of two pq_linear_f6 calls, and of pq_linear2 on the canonical weights, bit for bit."""
+    x, sx, wa, swa, wb, swb = layer(M, K, Na, Nb, h, seed=M + K)
+    dx, dwa, dswa, dwb, dswb = dev(x), dev(wa), dev(swa), dev(wb), dev(swb)
+    ta, tb = pq.pq_repack_f6(dwa), pq.pq_repack_f6(dwb)
+    oa, ob, _ = pq.pq_linear2_f6(dx, ta, dswa, tb, dswb, float(sx), h)
+    ra, _ = pq.pq_linear_f6(dx, ta, dswa, float(sx), h)
+    rb, _ = pq.pq_linear_f6(dx, tb, dswb, float(sx), h)
+    ca, cb, _ = pq.pq_linear2(dx, dwa, dswa, dwb, dswb, float(sx), h)
+    for got, one, canon in ((oa, ra, ca), (ob, rb, cb)):
+        assert np.array_equal(host(got).view(np.uint16), host(one).view(np.uint16))
+        assert np.array_equal(host(got).view(np.uint16), host(canon).view(np.uint16))
+
+
 def test_argument_errors(pq):
     import torch
     x, sx, wa, swa, wb, swb = layer(1, 512, 32, 32, 1, seed=3)
