@@ -57,7 +57,8 @@ const char* pq_status_str(int status);
  * its symmetric form; Sec. 3 "Dynamic and Static").
  * For every row m and every block b of had_block consecutive channels
  *     y[m, b*h + j] = sum_i x[m, b*h + i] * H_h[i][j] / sqrt(h),
- *     H_h[i][j] = (-1)^popcount(i & j)            (Sylvester order, butterflies in fp32),
+ *     H_h[i][j] = (-1)^popcount(i & j)            (Sylvester order; fp32 sums: butterflies, or for blocks of
+ *                                                  128 a product with H_128 on the matrix pipe),
  *     q = clamp(round_half_even(y / act_scale), -8, 7).
  * had_block: 0 or 1 = no rotation; otherwise a power of two in [2, 16384] that
  *            divides K.  With had_block <= 1 the codes are exactly
