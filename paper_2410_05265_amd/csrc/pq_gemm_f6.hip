@@ -378,6 +378,11 @@ __device__ __forceinline__ void f6_persistent(const uint8_t* __restrict__ x6, co
     const int RBX = (M + 31) >> 5, RBW = (N + 31) >> 5;
     const uint32_t lds_ring = (uint32_t)(uintptr_t)PQ6_LDS(smem);
     const int total = GM * GN;
+    // Workgroup b runs on XCD b % 8.  XCDs that multiply the same tokens or the same weight panels walk K in step;
+    // each starts an eighth of K further on (integer sums do not care in which order the stages are added), so a
+    // line is fetched from HBM by one L2 and found in the memory-side cache by the others, not asked for by
+    // several L2s at once.
+    const int k_first = (int)(((int64_t)(bid & 7) * nk) >> 3);
 
     // tile t of the list: workgroup-uniform
     auto tile_of = [&](int seq) {             // seq-th tile of this workgroup, -1 past the end
@@ -403,12 +408,14 @@ __device__ __forceinline__ void f6_persistent(const uint8_t* __restrict__ x6, co
             for (int i = 0; i < CM; ++i) bw[r][st][i] = (v8i){0, 0, 0, 0, 0, 0, 0, 0};
 
     auto load_a = [&](int t, int kt, int slot) {
-        const int k = kt < nk ? kt : nk - 1;            // (past the last stage: harmless re-reads)
+        int k = (kt < nk ? kt : nk - 1) + k_first;      // (past the last stage: harmless re-reads)
+        k = k >= nk ? k - nk : k;
         lds_dma16(x6 + (size_t)k * ((size_t)RBX * kChunkF6), aoff[t], lds_ring + slot * kStageA + (wave + 4 * t) * 1024);
     };
     auto load_b = [&](auto slotc, auto stepc, auto ic, int kt) {
         constexpr int slot = decltype(slotc)::value, st = decltype(stepc)::value, i = decltype(ic)::value;
-        const int k = kt < nk ? kt : nk - 1;
+        int k = (kt < nk ? kt : nk - 1) + k_first;
+        k = k >= nk ? k - nk : k;
         const uint8_t* blk = wrow[i] + (size_t)k * ((size_t)RBW * kChunkF6);
         v8i& d = bw[slot][st][i];
         if constexpr (st == 0) {
