@@ -237,7 +237,8 @@ def run_variants(torch, pq, layers, steps, warmup, ops):
     for L in layers:
         L["xq8"] = torch.empty((M, L["K"]), dtype=torch.int8, device="cuda")
         L["srow"] = torch.empty((M,), dtype=torch.float32, device="cuda")
-        L["work"] = torch.empty((max(pq.pq_linear_workspace_bytes(M, L["K"]), pq.pq_linear_f6_workspace_bytes(M, L["K"], L["h"])),),
+        L["work"] = torch.empty((max(pq.pq_linear_workspace_bytes(M, L["K"]), pq.pq_linear_f6_workspace_bytes(M, L["K"], L["h"]),
+                                     pq.pq_linear_f6_workspace_bytes(M, L["K"], L["K"] if L["h"] <= 1 else L["h"])),),
                                 dtype=torch.uint8, device="cuda")
 
     for L in layers:
@@ -280,6 +281,13 @@ def run_variants(torch, pq, layers, steps, warmup, ops):
         L = layers[4]
         pq.pq_linear_f6(L["x"], W(L, "w6"), L["sw"], L["sx"], L["h"], out=L["out"], workspace=L["work"])
 
+    # the worst case of the benchmark configuration: q/k/v, o, gate and up rotated online as well (their rotation is
+    # absorbed into the weights in the paper's pipeline), with the full K-point transform (K = 4096)
+    def rotated_everywhere():
+        for L in layers:
+            h = L["h"] if L["h"] > 1 else L["K"]
+            pq.pq_linear_f6(L["x"], W(L, "w6"), L["sw"], L["sx"], h, out=L["out"], workspace=L["work"])
+
     def f6_products_only():
         for L in layers:
             pq.pq_w4a4_gemm_f6(L["x6"], W(L, "w6"), L["sw"], L["sx"], M, L["N"], L["K"], out=L["out"])
@@ -298,6 +306,7 @@ def run_variants(torch, pq, layers, steps, warmup, ops):
     for name, step in (("w4a4_static_f6_linear", f6_linear), ("w4a4_static_int8_linear", int8_linear),
                        ("w4a8_static", w4a8_static), ("w4a4_dynamic", dynamic(4)), ("w4a8_dynamic", dynamic(8)),
                        ("w4a4_static_f6_gate_up_one_quantizer", gate_up_one_quantizer),
+                       ("w4a4_static_f6_every_linear_rotated_online", rotated_everywhere),
                        ("w4a4_products_only_f6", f6_products_only), ("w4a4_products_only_int8", int8_products_only)):
         step = counted(step)
         device_warmup(torch)
