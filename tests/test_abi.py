@@ -144,6 +144,28 @@ def test_argument_errors_launch_nothing(b):
     assert lin(p, p, ctypes.c_void_p(0x1004), 0.1, 128, 4, 64, 512, p, ctypes.c_void_p(0x10000), 4096, nul) == b.PQ_ERR_ALIGN
 
 
+def test_argument_errors_of_the_two_matrix_layers(b):
+    """pq_linear2 and pq_linear2_f6 check both matrices before anything is enqueued (fake pointers: no GPU needed)."""
+    L = b.lib()
+    p, big, nul, odd = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x10000), ctypes.c_void_p(0), ctypes.c_void_p(0x1008)
+    for fn, k in ((L.pq_linear2, 512), (L.pq_linear2_f6, 512)):
+        ok = dict(x=p, wa=p, sa=p, na=64, oa=p, wb=p, sb=p, nb=32, ob=p, s=0.1, h=128, m=4, k=k, ws=big, wsb=1 << 20, st=nul)
+
+        def call(**kw):
+            a = dict(ok, **kw)
+            return fn(a["x"], a["wa"], a["sa"], a["na"], a["oa"], a["wb"], a["sb"], a["nb"], a["ob"], a["s"], a["h"], a["m"], a["k"],
+                      a["ws"], a["wsb"], a["st"])
+
+        assert call(m=0) == b.PQ_OK
+        assert call(wb=nul) == b.PQ_ERR_NULL and call(ob=nul) == b.PQ_ERR_NULL and call(sa=nul) == b.PQ_ERR_NULL
+        assert call(nb=40) == b.PQ_ERR_SHAPE and call(na=0) == b.PQ_ERR_SHAPE and call(h=100) == b.PQ_ERR_SHAPE
+        assert call(ws=nul) == b.PQ_ERR_WORKSPACE and call(wsb=16) == b.PQ_ERR_WORKSPACE
+        assert call(ws=odd) == b.PQ_ERR_ALIGN and call(sb=ctypes.c_void_p(0x1004)) == b.PQ_ERR_ALIGN
+        assert call(s=0.0) == b.PQ_ERR_SCALE and call(s=float("nan")) == b.PQ_ERR_SCALE
+    assert L.pq_linear2_f6(p, p, p, 64, p, p, p, 32, p, 0.1, 1, 4, 480, big, 1 << 20, nul) == b.PQ_ERR_SHAPE       # K % 128
+    assert L.pq_linear2_f6(p, p, p, 64, p, p, p, 32, p, 0.1, 1, 4, 262144, big, 1 << 30, nul) == b.PQ_ERR_UNSUPPORTED  # sums no longer exact
+
+
 def test_process_wide_switches(b):
     L = b.lib()
     assert L.pq_set_gemm_tile(99) == -2 and L.pq_set_gemm_tile(-2) == -2
