@@ -4,6 +4,8 @@ The oracle cannot run whole Llama-sized layers in seconds, so rows are sampled: 
 independent, hence the oracle's result for a sampled token is its result inside the full
 batch.  Codes and int32 accumulators of the sampled tokens must be exact (gate A); the
 fp16 outputs of the whole layer call must pass the end-to-end gate on those tokens (gate B).
+Both forms of the layer run: the canonical one against the oracle, the prepacked one (the
+benchmark's headline) against the canonical one, every output and accumulator bit for bit.
 """
 
 import numpy as np
@@ -58,6 +60,15 @@ def _check_sampled(pq, M, K, N, h, seed, nsample):
     # the same launch configuration with raw accumulators (verification output)
     _, acc = pq.pq_w4a4_gemm(xq_all.contiguous(), d_w, d_sw, float(sx), want_out=False, want_acc=True)
     torch.cuda.synchronize()
+    # the prepacked form of the same layer (what bench.py times as its headline): the whole output and all
+    # accumulators bit-identical to the canonical form's, so the gates below hold for both
+    if K % 128 == 0:
+        w6 = pq.pq_repack_f6(d_w)
+        out6, ws6 = pq.pq_linear_f6(dev(x), w6, d_sw, float(sx), h)
+        assert torch.equal(out6.view(torch.int16), out.view(torch.int16)), "pq_linear_f6 differs from pq_linear"
+        _, acc6 = pq.pq_w4a4_gemm_f6(ws6, w6, d_sw, float(sx), M, N, K, want_out=False, want_acc=True)
+        assert torch.equal(acc6, acc), "accumulators of the 6-bit product differ"
+        del w6, out6, ws6, acc6
     xq_s, out_s, acc_s = host(xq_all[rows]), host(out[rows]), host(acc[rows])
     del out, ws, acc
     # gate A on the sampled tokens: accumulators exact for the GPU's own codes
