@@ -36,6 +36,8 @@ def layer(M, K, Na, Nb, h, seed):
 # N_a not a multiple of the rows a workgroup takes at a time; 5 tokens and 64 tokens leave the fused launch
 CASES = [(1, 512, 256, 256, 1), (1, 4096, 1008, 528, 1), (2, 2048, 4096, 2064, 128), (4, 1024, 16, 8192, 64),
          (1, 8192, 14336, 14336, 1), (3, 4096, 9008, 9008, 4096), (1, 14336, 2048, 1040, 128),
+         (1, 4096, 14336, 14336, 1),      # gate and up of Llama-3-8B at one token: the launch bench.py times
+
          (5, 1024, 528, 272, 128), (64, 1024, 528, 272, 1), (16, 4096, 1024, 512, 128)]
 
 
