@@ -107,6 +107,17 @@ int main(void)
     EXPECT(pq_linear_f6(p, p, pf, 0.1f, 1, 32, 16, 128, p, p256, 100, NULL), PQ_ERR_WORKSPACE);
     EXPECT(pq_rotate_quant_f6(p, 32, 2048, 1024, 0.1f, p, NULL, NULL), PQ_ERR_UNSUPPORTED);
     EXPECT(pq_rotate_quant_f6(p, 32, 96, 1, 0.1f, p, NULL, NULL), PQ_ERR_SHAPE);
+    /* two matrices on one quantized input, canonical and prepacked */
+    EXPECT(pq_linear2(p, p, pf, 64, p, p, pf, 32, p, 0.1f, 128, 0, 512, p256, 4096, NULL), PQ_OK);
+    EXPECT(pq_linear2(p, p, pf, 64, p, NULL, pf, 32, p, 0.1f, 128, 4, 512, p256, 4096, NULL), PQ_ERR_NULL);
+    EXPECT(pq_linear2(p, p, pf, 64, p, p, pf, 40, p, 0.1f, 128, 4, 512, p256, 4096, NULL), PQ_ERR_SHAPE);
+    EXPECT(pq_linear2(p, p, pf, 64, p, p, pf, 32, p, 0.1f, 128, 4, 512, p256, 16, NULL), PQ_ERR_WORKSPACE);
+    EXPECT(pq_linear2(p, p, pf, 64, p, p, pf, 32, p, -1.0f, 128, 4, 512, p256, 4096, NULL), PQ_ERR_SCALE);
+    EXPECT(pq_linear2_f6(p, p, pf, 64, p, p, pf, 32, p, 0.1f, 128, 0, 512, p256, 1 << 20, NULL), PQ_OK);
+    EXPECT(pq_linear2_f6(p, p, pf, 64, p, p, NULL, 32, p, 0.1f, 128, 4, 512, p256, 1 << 20, NULL), PQ_ERR_NULL);
+    EXPECT(pq_linear2_f6(p, p, pf, 64, p, p, pf, 32, p, 0.1f, 128, 4, 480, p256, 1 << 20, NULL), PQ_ERR_SHAPE);
+    EXPECT(pq_linear2_f6(p, p, pf, 64, p, p, pf, 32, p, 0.1f, 128, 4, 512, p256, 64, NULL), PQ_ERR_WORKSPACE);
+    EXPECT(pq_linear2_f6(p, p, pf, 64, p, p, pf, 32, p, 0.1f, 1, 4, 262144, p256, (size_t)1 << 30, NULL), PQ_ERR_UNSUPPORTED);
 
     printf(failures ? "abi_check: %d FAILED\n" : "abi_check: ok\n", failures);
     return failures != 0;
