@@ -215,6 +215,11 @@ int pq_probe_f6_product(const int8_t* a_codes, const int8_t* b_codes, int64_t K,
  */
 size_t pq_f6_tiles_bytes(int64_t rows, int64_t K);
 int pq_repack_f6(const void* codes_packed, int64_t rows, int64_t K, void* tiles, void* stream);
+/* The same two calls under the names a caller who only wants "prepacked weights" looks for, and the layer on them:
+ * pq_prepacked_bytes(N, K) = pq_f6_tiles_bytes(N, K); pq_prepack_weights = pq_repack_f6 on the [N,K] weight codes;
+ * pq_linear_prepacked = pq_linear_f6 (declared below), with pq_linear_f6_workspace_bytes for its workspace. */
+size_t pq_prepacked_bytes(int64_t N, int64_t K);
+int pq_prepack_weights(const void* wq_packed, int64_t N, int64_t K, void* wq_tiled, void* stream);
 int pq_w4a4_gemm_f6(const void* x_tiles, const void* w_tiles, const float* w_scale,
                     float act_scale, int64_t M, int64_t N, int64_t K,
                     void* out_f16, int32_t* acc_i32, void* stream);
@@ -249,6 +254,9 @@ int pq_linear_f6(const void* x_f16, const void* w_tiles, const float* w_scale,
 int pq_linear2_f6(const void* x_f16, const void* w_tiles_a, const float* w_scale_a, int64_t N_a, void* out_a_f16,
                   const void* w_tiles_b, const float* w_scale_b, int64_t N_b, void* out_b_f16, float act_scale,
                   int32_t had_block, int64_t M, int64_t K, void* workspace, size_t workspace_bytes, void* stream);
+int pq_linear_prepacked(const void* x_f16, const void* wq_tiled, const float* w_scale, float act_scale, int32_t had_block,
+                        int64_t M, int64_t N, int64_t K, void* out_f16, void* workspace, size_t workspace_bytes,
+                        void* stream);
 
 /* Force a kernel variant of pq_w4a4_gemm for sweeps and tests (host, process-wide,
  * not thread-safe): 0 = automatic, 1 = weight-streaming matrix tiles (M <= 32, K % 256 == 0 and

@@ -32,6 +32,9 @@ SIGNATURES = {
     "pq_w4a4_gemm_ws": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i64, _i64, _i64, _vp, _vp, _vp, _sz, _vp]),
     "pq_linear": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i32, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
     "pq_linear2": (ctypes.c_int, [_vp, _vp, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _f32, _i32, _i64, _i64, _vp, _sz, _vp]),
+    "pq_prepacked_bytes": (_sz, [_i64, _i64]),
+    "pq_prepack_weights": (ctypes.c_int, [_vp, _i64, _i64, _vp, _vp]),
+    "pq_linear_prepacked": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i32, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
     "pq_linear2_f6": (ctypes.c_int, [_vp, _vp, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _f32, _i32, _i64, _i64, _vp, _sz, _vp]),
     "pq_linear_noalloc_max_bytes": (_sz, []),
     "pq_linear_noalloc": (ctypes.c_int, [_vp, _vp, _vp, _f32, _i32, _i64, _i64, _i64, _vp, _vp]),
@@ -248,6 +251,35 @@ def pq_linear2_f6(x, w_tiles_a, w_scale_a, w_tiles_b, w_scale_b, act_scale, had_
                                _ptr(out_b), float(act_scale), int(had_block), M, K, _ptr(workspace), workspace.numel(),
                                _stream()), "pq_linear2_f6")
     return out_a, out_b, workspace
+
+
+def pq_prepacked_bytes(N: int, K: int) -> int:
+    return int(lib().pq_prepacked_bytes(N, K))
+
+
+def pq_prepack_weights(wq, out=None):
+    """pq_repack_f6 on a weight matrix, under its other name.  wq uint8 [N,K/2] -> tiles."""
+    _dev(wq, torch.uint8, "wq")
+    N, K = wq.shape[0], wq.shape[1] * 2
+    if out is None:
+        out = torch.empty((pq_prepacked_bytes(N, K),), dtype=torch.uint8, device=wq.device)
+    _check(lib().pq_prepack_weights(_ptr(wq), N, K, _ptr(out), _stream()), "pq_prepack_weights")
+    return out
+
+
+def pq_linear_prepacked(x, wq_tiled, w_scale, act_scale, had_block, out=None, workspace=None):
+    """pq_linear_f6 under its other name.  Returns (out, workspace)."""
+    _dev(x, torch.float16, "x")
+    _dev(w_scale, torch.float32, "w_scale")
+    M, K = x.shape
+    N = w_scale.numel()
+    if workspace is None:
+        workspace = torch.empty((max(pq_linear_f6_workspace_bytes(M, K, had_block), 256),), dtype=torch.uint8, device=x.device)
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    _check(lib().pq_linear_prepacked(_ptr(x), _ptr(wq_tiled), _ptr(w_scale), float(act_scale), int(had_block), M, N, K, _ptr(out),
+                                     _ptr(workspace), workspace.numel(), _stream()), "pq_linear_prepacked")
+    return out, workspace
 
 
 def pq_linear_noalloc_max_bytes() -> int:

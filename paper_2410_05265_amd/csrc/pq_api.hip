@@ -739,6 +739,19 @@ int pq_linear2_f6(const void* x_f16, const void* w_tiles_a, const float* w_scale
     return pq::launch_gemm_f6(tiles, w_tiles_b, w_scale_b, act_scale, M, N_b, K, out_b_f16, nullptr, st);
 }
 
+size_t pq_prepacked_bytes(int64_t N, int64_t K) { return pq_f6_tiles_bytes(N, K); }
+
+int pq_prepack_weights(const void* wq_packed, int64_t N, int64_t K, void* wq_tiled, void* stream)
+{
+    return pq_repack_f6(wq_packed, N, K, wq_tiled, stream);
+}
+
+int pq_linear_prepacked(const void* x_f16, const void* wq_tiled, const float* w_scale, float act_scale, int32_t had_block,
+                        int64_t M, int64_t N, int64_t K, void* out_f16, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return pq_linear_f6(x_f16, wq_tiled, w_scale, act_scale, had_block, M, N, K, out_f16, workspace, workspace_bytes, stream);
+}
+
 int pq_probe_stream_read(const void* src, int64_t bytes, int32_t* sink, void* stream)
 {
     if (!src || !sink) return PQ_ERR_NULL;

@@ -245,6 +245,21 @@ def test_rotation_on_the_matrix_pipe_one_hot_and_constant_rows(pq):
     assert np.array_equal(codes_of_tiles(host(pq.pq_rotate_quant_f6(dev(x), 128, float(sx))), 130, K), want)
 
 
+def test_prepack_names(pq):
+    """pq_prepacked_bytes / pq_prepack_weights / pq_linear_prepacked are the tile calls under their other names."""
+    M, K, N, h = 70, 1152, 272, 128
+    x = synth.activations(M, K, seed=9)
+    wq, sw = O.weight_rtn(synth.weights(N, K, seed=9))
+    dw, dsw = dev(O.pack(wq)), dev(sw)
+    assert pq.pq_prepacked_bytes(N, K) == pq.pq_f6_tiles_bytes(N, K)
+    tiled = pq.pq_prepack_weights(dw)
+    assert torch.equal(tiled, pq.pq_repack_f6(dw))
+    a, _ = pq.pq_linear_prepacked(dev(x), tiled, dsw, 0.21, h)
+    b, _ = pq.pq_linear_f6(dev(x), tiled, dsw, 0.21, h)
+    c, _ = pq.pq_linear(dev(x), dw, dsw, 0.21, h)
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16)) and torch.equal(a.view(torch.int16), c.view(torch.int16))
+
+
 def test_unrotated_quantizer_to_tiles_is_exact_for_every_fp16_value(pq):
     """The tile-writing quantizer (no rotation) on all finite fp16 values and on constructed ties: the codes
     behind the tiles equal the oracle's."""
