@@ -281,8 +281,9 @@ int pq_set_gemm_variant(int variant);
  * 1 256x128, 2 128x128, 3 256x192, 4 64x128, 5-8 variants of these with more wavefronts or a deeper
  * ring; any forced tile also switches the mixed-width launch off.  Before the first call the value
  * is that of the environment variable PQ_GEMM_TILE, read once at the first product of the process.
- * pq_set_gemm_f6_tile: the same for pq_w4a4_gemm_f6: -1 = by shape, 2 = 128 channels per tile,
- * 3 = the mix of 256 and 192 where N allows it, 4 = 256 (environment variable PQ_GEMM_F6_TILE).
+ * pq_set_gemm_f6_tile: the same for pq_w4a4_gemm_f6 (tiles of 128 tokens): -1 = by shape, 2 = 256 channels per
+ * tile, 3 = the mix of 512 and 384 in one launch where N allows it, else 384, 4 = 512 (environment variable
+ * PQ_GEMM_F6_TILE).
  * Both return the previous value, or -2 if `tile` is unknown.
  */
 int pq_set_gemm_tile(int tile);
