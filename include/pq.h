@@ -204,8 +204,8 @@ int pq_probe_f6_product(const int8_t* a_codes, const int8_t* b_codes, int64_t K,
  *   planes, each lane after lane: bytes 0-15 of the first step's images (64 x 16 bytes), their bytes
  *   16-23 (64 x 8), bytes 0-7 of the second step's images (64 x 8), their bytes 8-23 (64 x 16): each plane
  *   is one load instruction of a wavefront.  K % 128 == 0, K <= 262080, the tiles under 4 GiB (else
- *   PQ_ERR_SHAPE / PQ_ERR_UNSUPPORTED).  Weights are repacked once, offline; activations after
- *   pq_rotate_quant (pq_linear_f6 does it).
+ *   PQ_ERR_SHAPE / PQ_ERR_UNSUPPORTED).  Weights are repacked once, offline; activations are written in this
+ *   form by pq_rotate_quant_f6 (pq_linear_f6 does it).
  * pq_w4a4_gemm_f6: x_tiles, w_tiles as written by pq_repack_f6 for [M,K] and [N,K]; everything else
  *   as pq_w4a4_gemm.
  * These calls are the optional prepacked layout of the boundary (a pure re-encoding of the canonical
@@ -258,8 +258,8 @@ int pq_linear_prepacked(const void* x_f16, const void* wq_tiled, const float* w_
                         int64_t M, int64_t N, int64_t K, void* out_f16, void* workspace, size_t workspace_bytes,
                         void* stream);
 
-/* Force a kernel variant of pq_w4a4_gemm for sweeps and tests (host, process-wide,
- * not thread-safe): 0 = automatic, 1 = weight-streaming matrix tiles (M <= 32, K % 256 == 0 and
+/* Force a kernel variant of pq_w4a4_gemm for sweeps and tests (host, process-wide, atomic;
+ * see the end of this comment): 0 = automatic, 1 = weight-streaming matrix tiles (M <= 32, K % 256 == 0 and
  * the codes of 8 tokens fit in LDS; else PQ_ERR_UNSUPPORTED), 2 = MFMA tiled, 3 = simple,
  * 4 = weight-streaming 4-bit dot products (M <= 8 only), 5 = MFMA tiled with K split in up to 5
  * runs whenever the call has a workspace of two planes and K has 512 channels (else
