@@ -105,6 +105,17 @@ __global__ __launch_bounds__(1024) void k_decode(const __half* __restrict__ x, c
         else
             xr[u] = (v4i){0, 0, 0, 0};
     }
+    // The channel step this lane will need in the epilogue of the wavefront's first row group, requested with the
+    // activation rows (branch-free, clamped): asked for after the fold it would put a whole memory latency at the
+    // end of a kernel that takes three to seven microseconds.
+    constexpr int VV = RPW * MP;
+    float sw_first;
+    {
+        const int idx = bitrev(lane, ilog2(VV));
+        int n = gid * RPW + idx / MP;
+        n = n < N ? n : N - 1;
+        sw_first = *(n >= two.n1 ? two.sw + (n - two.n1) : sw + n);
+    }
     __builtin_amdgcn_sched_barrier(0);
     // every wavefront has issued its row loads before any weight load enters the memory pipeline:
     // the rows arrive early and are quantized while the weights stream in
@@ -285,11 +296,13 @@ __global__ __launch_bounds__(1024) void k_decode(const __half* __restrict__ x, c
                 const int total = ABITS == 8 ? p[0] >> 4 : p[0];
                 if (n >= two.n1) {   // the second matrix: its own channel steps and output
                     const int n2 = n - two.n1;
-                    two.out[(int64_t)m * (N - two.n1) + n2] = __float2half_rn(mul_rn((float)total, sx * two.sw[n2]));
+                    const float sw_n = first ? sw_first : two.sw[n2];
+                    two.out[(int64_t)m * (N - two.n1) + n2] = __float2half_rn(mul_rn((float)total, sx * sw_n));
                 } else {
                     if (acc_out) acc_out[(int64_t)m * two.n1 + n] = total;
                     const int shifted = total + (zcorr ? zcorr[n] : 0);   // zero-point correction of Eq. 1, if any
-                    if (out) out[(int64_t)m * two.n1 + n] = __float2half_rn(mul_rn((float)shifted, (srow ? srow[m] : sx) * sw[n]));
+                    const float sw_n = first ? sw_first : sw[n];
+                    if (out) out[(int64_t)m * two.n1 + n] = __float2half_rn(mul_rn((float)shifted, (srow ? srow[m] : sx) * sw_n));
                 }
             }
         }
