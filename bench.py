@@ -527,7 +527,8 @@ def graph_time(torch, fn, reps=5, inner=20):
     with torch.cuda.graph(graph):
         for _ in range(inner):
             fn()
-    graph.replay()
+    for _ in range(3):            # (the first replays over freshly allocated copies run up to 20 % slower)
+        graph.replay()
     torch.cuda.synchronize()
     device_warmup(torch, 40.0)
     ts = []
