@@ -527,10 +527,13 @@ def graph_time(torch, fn, reps=5, inner=20):
     with torch.cuda.graph(graph):
         for _ in range(inner):
             fn()
-    for _ in range(3):            # (the first replays over freshly allocated copies run up to 20 % slower)
-        graph.replay()
-    torch.cuda.synchronize()
     device_warmup(torch, 40.0)
+    # then the graph itself for 30 ms: these legs are bound by memory, and after a pause of the memory system (host-side
+    # preparation, a compute-bound leg) the first replays run up to 20 % slower than the steady state
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < 0.030:
+        graph.replay()
+        torch.cuda.synchronize()
     ts = []
     for _ in range(reps):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -607,11 +610,14 @@ def run_decode(torch, pq, layers, M=1, reps=5, warm=False, planes=False, floor=F
     streams a matrix of this size costs on this GPU."""
     res = {}
     sink = torch.zeros(4, dtype=torch.int32, device="cuda")
-    for L in layers:
+
+    def measure(L):
         K, N, h = L["K"], L["N"], L["h"]
         nbytes = N * K // 2
         ncopy = max(4, int((1 << 30) // nbytes) + 1)
-        ws = [L["wq"].clone() for _ in range(ncopy)]
+        # (one allocation for all copies, as a deployment holds its weights in a few large allocations)
+        pool = L["wq"].unsqueeze(0).repeat(ncopy, 1, 1)
+        ws = [pool[i] for i in range(ncopy)]
         x = L["x"][:M].contiguous()
         out = torch.empty((M, N), dtype=torch.float16, device="cuda")
         wbytes = pq.pq_linear_workspace_bytes_split(M, N, K) if planes else pq.pq_linear_workspace_bytes(M, K)
@@ -642,7 +648,17 @@ def run_decode(torch, pq, layers, M=1, reps=5, warm=False, planes=False, floor=F
             w0 = ws[0]
             us = graph_time(torch, lambda: pq.pq_linear(x, w0, L["sw"], L["sx"], h, out=out, workspace=work), inner=32)
             res[L["name"]]["warm_llc_us"] = round(us, 2)
-        del ws
+        del ws, pool
+
+    # The first graph-timed sequence of fused launches in a process reads up to 20 % slower than the same
+    # sequence measured again (same library, same buffers, after any amount of warm-up; the read-only kernel
+    # timed right behind it is not affected): the leg's first linear is therefore measured once untimed.
+    if not getattr(run_decode, "primed", False):
+        run_decode.primed = True
+        measure(layers[0])
+        res.clear()
+    for L in layers:
+        measure(L)
     tot_b = sum(L["N"] * L["K"] // 2 for L in layers)
     tot_t = sum(v["us"] for v in res.values()) * 1e-6
     r = {"M": M, "weights": "cold (>1 GiB cycled)", "timing": "median of %d graph replays" % reps, "per_linear": res,
@@ -660,7 +676,8 @@ def run_decode_pair(torch, pq, a, b, M=1, reps=5):
     K, h = a["K"], a["h"]
     nbytes = (a["N"] + b["N"]) * K // 2
     ncopy = max(4, int((1 << 30) // nbytes) + 1)
-    wa, wb = [a["wq"].clone() for _ in range(ncopy)], [b["wq"].clone() for _ in range(ncopy)]
+    pool_a, pool_b = a["wq"].unsqueeze(0).repeat(ncopy, 1, 1), b["wq"].unsqueeze(0).repeat(ncopy, 1, 1)
+    wa, wb = [pool_a[i] for i in range(ncopy)], [pool_b[i] for i in range(ncopy)]
     x = a["x"][:M].contiguous()
     oa = torch.empty((M, a["N"]), dtype=torch.float16, device="cuda")
     ob = torch.empty((M, b["N"]), dtype=torch.float16, device="cuda")
