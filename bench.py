@@ -40,7 +40,7 @@ INT8_PEAK_TOPS = 5033.0      # MI355X dense INT8 MFMA: 256 CU x 2.4 GHz x 8192 o
 FP6_PEAK_TFLOPS = 10066.0    # dense 6-bit (and 4-bit) floating-point MFMA: twice the INT8 rate
 HBM_PEAK_GBS = 8000.0
 M_PREFILL = 2048
-EVENT_EVERY = 10            # steps between two event-instrumented steps of a timed region
+EVENT_EVERY = 25            # steps between two event-instrumented steps of a timed region (each costs ~50 us extra)
 REPEATS = 5                 # timed regions of --steps steps each; the median is reported
 WEIGHT_SETS = 4             # distinct copies of the block's weights, one per step in turn: with 4 x 163 MB (6-bit
                             # tiles) between two uses of a copy, every step reads its weights from HBM, as the
@@ -195,7 +195,7 @@ def run_prefill(torch, pq, layers, steps, warmup, path="f6", repeats=REPEATS, se
         for i in range(steps):
             # an event pair fences the stream (the next launch cannot start under the tail of the
             # previous one), so only every EVENT_EVERY-th step of a timed region carries them
-            step(ev if i % EVENT_EVERY == 0 else None)
+            step(ev if i % EVENT_EVERY == min(EVENT_EVERY, steps) // 2 else None)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         regions.append(dt / steps)
