@@ -204,11 +204,13 @@ def test_tile_writing_quantizer(pq, M, K, h):
         pq.pq_rotate_quant_f6(dev(synth.activations(4, 2048, seed=1)), 1024, sx)
 
 
-@pytest.mark.parametrize("M,K", [(1, 128), (37, 640), (100, 1408), (32, 512), (65, 14336)])
+@pytest.mark.parametrize("M,K", [(1, 128), (37, 640), (100, 1408), (32, 512), (65, 14336), (21900, 1152)])
 def test_rotation_of_128_point_blocks_on_the_matrix_pipe(pq, M, K):
     """128-point blocks take the kernel that rotates with matrix instructions (both outputs of it: canonical
     nibbles and tiles).  Against the oracle's fp64 rotation: codes differ only where the rotated value is at a
-    rounding tie; token counts that are not multiples of 32, channel counts that are not multiples of 512."""
+    rounding tie; token counts that are not multiples of 32, channel counts that are not multiples of 512.
+    The last case is large enough (6165 blocks) for the launch in which a wavefront takes two blocks, with an
+    odd number of blocks per row (the last wavefront of a row has one)."""
     x = synth.activations(M, K, seed=3 * M + K)
     y = O.rotate(x, 128)
     sx = np.float32(np.abs(y).max() / 7.0)
