@@ -282,8 +282,8 @@ __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(4, 8
         uint8_t* block = tiles ? tiles + ((int64_t)kt * gridDim.y + rb) * kChunkF6 : nullptr;
         // p: this lane's 32 channels of step st as nibbles (channels 0-7, 8-15, 16-23, 24-31)
         auto emit = [&](int st, const v4i p) {
-            if (nibbles && row < M)
-                *reinterpret_cast<v4i*>(nibbles + row * (K >> 1) + (int64_t)kt * 64 + st * 32 + g * 16) = p;
+            if (nibbles && row < M)      // (written through at once, like the images)
+                __builtin_nontemporal_store(p, reinterpret_cast<v4i*>(nibbles + row * (K >> 1) + (int64_t)kt * 64 + st * 32 + g * 16));
             if (block) {
                 uint64_t w[3];
                 image_of_nibbles(p, w);
