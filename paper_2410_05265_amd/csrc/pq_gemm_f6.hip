@@ -52,10 +52,12 @@ constexpr int kPersistentWorkgroups = 256;                               // one 
 // Offsets of the four planes of a block, and an image's 24 bytes (three qwords) into its two planes.
 constexpr int kP0 = 0, kP1 = 1024, kP2 = 1536, kP3 = 2048;
 
-// STREAM: non-temporal stores.  The activation images a quantizer writes are read next by every XCD of the
-// product launch, from the memory side in any case (the L2s are not coherent with one another): written
-// through at once they leave during the kernel instead of at its end, and do not push the weights out of the
-// memory-side cache (2048 x 14336: 21.7 -> 21.3 us; the step with cold weights 344 -> 339 us).
+// STREAM: non-temporal stores (a compile-time choice: a run-time branch around the stores cost the quantizers 5 %).  The activation images a quantizer writes are read next by every XCD of the
+// product launch, from the memory side in any case (the L2s are not coherent with one another).  While all of
+// a launch's images fit the L2s (rq::kStreamBelow), ordinary stores would leave in one burst at the end of the
+// kernel; written through at once they leave during it and do not push the weights out of the memory-side cache
+// (2048 x 14336, 22 MB of images: 21.7 -> 21.3 us, the step with cold weights 344 -> 339 us).  A larger output is
+// evicted as the kernel goes anyway and streaming costs time (8192 x 14336, 88 MB: 58 -> 65 us).
 template <bool STREAM>
 __device__ __forceinline__ void store_image(uint8_t* block, int lane, int step, const uint64_t (&w)[3])
 {
@@ -136,7 +138,7 @@ __global__ __launch_bounds__(256) void k_repack_f6(const uint8_t* __restrict__ c
 // wavefront's store covers a whole plane of a block.  Optionally the canonical nibbles go out as well.
 // The narrow variants are what keeps the GPU busy on a 2048 x 4096 input (2048 workgroups of C = 128 instead
 // of 512 of C = 512): short workgroups at different phases hide one another's load latency.
-template <bool EXACT, int C>
+template <bool EXACT, int C, bool STREAM>
 __global__ __launch_bounds__(256) void k_rotate_quant_f6(const __half* __restrict__ x, int M, int K, int log2h,
                                                         rq::StaticStep steps, uint8_t* __restrict__ tiles,
                                                         uint8_t* __restrict__ nibbles)
@@ -175,7 +177,7 @@ __global__ __launch_bounds__(256) void k_rotate_quant_f6(const __half* __restric
                                                                           (l >> 5) * 16);
             uint64_t w[3];
             image_of_nibbles(p, w);
-            store_image<true>(tiles + ((int64_t)kt * gridDim.y + rb) * kChunkF6, l, st, w);
+            store_image<STREAM>(tiles + ((int64_t)kt * gridDim.y + rb) * kChunkF6, l, st, w);
         }
     }
     if (nibbles) {
@@ -225,7 +227,7 @@ typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 // which the quantizer reads directly, instead of accumulation registers that cost a move per value)
 // TILES: blocks a wavefront takes, one after the other (neighbours along K); the loads of all of them are
 // issued before the first is worked on, so a wavefront's next block is on its way while it rotates one.
-template <int WAVES, int TILES>
+template <int WAVES, int TILES, bool STREAM>
 __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(4, 8))) void k_rotate128_quant_mfma(
     const __half* __restrict__ x, int M, int K, rq::StaticStep steps, uint8_t* __restrict__ tiles, uint8_t* __restrict__ nibbles)
 {
@@ -282,12 +284,15 @@ __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(4, 8
         uint8_t* block = tiles ? tiles + ((int64_t)kt * gridDim.y + rb) * kChunkF6 : nullptr;
         // p: this lane's 32 channels of step st as nibbles (channels 0-7, 8-15, 16-23, 24-31)
         auto emit = [&](int st, const v4i p) {
-            if (nibbles && row < M)      // (written through at once, like the images)
-                __builtin_nontemporal_store(p, reinterpret_cast<v4i*>(nibbles + row * (K >> 1) + (int64_t)kt * 64 + st * 32 + g * 16));
+            if (nibbles && row < M) {
+                v4i* at = reinterpret_cast<v4i*>(nibbles + row * (K >> 1) + (int64_t)kt * 64 + st * 32 + g * 16);
+                if constexpr (STREAM) __builtin_nontemporal_store(p, at);
+                else *at = p;
+            }
             if (block) {
                 uint64_t w[3];
                 image_of_nibbles(p, w);
-                store_image<true>(block, lane, st, w);
+                store_image<STREAM>(block, lane, st, w);
             }
         };
         v16f acc[4];
@@ -766,9 +771,14 @@ static void launch_quant_f6_c(int c, const void* x, int64_t R, int64_t K, int lo
     const dim3 grid((unsigned)((K + c - 1) / c), (unsigned)((R + 31) / 32));
     const __half* xp = static_cast<const __half*>(x);
     uint8_t *op = static_cast<uint8_t*>(out), *np = static_cast<uint8_t*>(nibbles);
-    if (c == 128) hipLaunchKernelGGL((k_rotate_quant_f6<EXACT, 128>), grid, dim3(256), 0, st, xp, (int)R, (int)K, log2h, steps, op, np);
-    else if (c == 256) hipLaunchKernelGGL((k_rotate_quant_f6<EXACT, 256>), grid, dim3(256), 0, st, xp, (int)R, (int)K, log2h, steps, op, np);
-    else hipLaunchKernelGGL((k_rotate_quant_f6<EXACT, 512>), grid, dim3(256), 0, st, xp, (int)R, (int)K, log2h, steps, op, np);
+    auto launch = [&](auto streamc) {
+        constexpr bool S = decltype(streamc)::value;
+        if (c == 128) hipLaunchKernelGGL((k_rotate_quant_f6<EXACT, 128, S>), grid, dim3(256), 0, st, xp, (int)R, (int)K, log2h, steps, op, np);
+        else if (c == 256) hipLaunchKernelGGL((k_rotate_quant_f6<EXACT, 256, S>), grid, dim3(256), 0, st, xp, (int)R, (int)K, log2h, steps, op, np);
+        else hipLaunchKernelGGL((k_rotate_quant_f6<EXACT, 512, S>), grid, dim3(256), 0, st, xp, (int)R, (int)K, log2h, steps, op, np);
+    };
+    if ((int64_t)f6_tiles_bytes(R, K) <= rq::kStreamBelow) launch(std::true_type{});      // (the tiles are the larger output)
+    else launch(std::false_type{});
 }
 
 // 128-point blocks: rotation on the matrix pipe.  out (tiles) or nibbles may be NULL, not both.
@@ -780,17 +790,20 @@ int launch_rotate128_mfma(const void* x, int64_t R, int64_t K, float act_scale, 
     const int64_t nk = K / 128, rbs = (R + 31) / 32;
     // the 1/sqrt(128) of the rotation is folded into the reciprocal step, as in pq_rotate_quant
     const rq::StaticStep steps{(float)(1.0 / ((double)act_scale * sqrt(128.0))), act_scale};
-    // Two blocks per wavefront where that still leaves a CU a dozen wavefronts: the second block's loads are in
-    // flight while the first is rotated (2048 x 14336, 7168 blocks: 21.3 -> 19.0 us); on a small input one block
-    // each, so that there are wavefronts enough.
-    if (nk * rbs >= 6144) {
+    const bool stream = (tiles ? (int64_t)f6_tiles_bytes(R, K) : R * (K / 2)) <= rq::kStreamBelow;   // (the larger output)
+    uint8_t *tp = static_cast<uint8_t*>(tiles), *np = static_cast<uint8_t*>(nibbles);
+    const __half* xp = static_cast<const __half*>(x);
+    // Two blocks per wavefront where that still leaves a CU a dozen wavefronts and the output is streamed: the
+    // second block's loads are in flight while the first is rotated (2048 x 14336, 7168 blocks: 21.3 -> 19.0 us;
+    // with ordinary stores, i.e. on larger inputs, it gains nothing); on a small input one block each, so that
+    // there are wavefronts enough.
+    if (stream && nk * rbs >= 6144) {
         const dim3 grid((unsigned)((nk + 2 * W - 1) / (2 * W)), (unsigned)rbs);
-        hipLaunchKernelGGL((k_rotate128_quant_mfma<W, 2>), grid, dim3(64 * W), 0, st, static_cast<const __half*>(x), (int)R, (int)K,
-                           steps, static_cast<uint8_t*>(tiles), static_cast<uint8_t*>(nibbles));
+        hipLaunchKernelGGL((k_rotate128_quant_mfma<W, 2, true>), grid, dim3(64 * W), 0, st, xp, (int)R, (int)K, steps, tp, np);
     } else {
         const dim3 grid((unsigned)((nk + W - 1) / W), (unsigned)rbs);
-        hipLaunchKernelGGL((k_rotate128_quant_mfma<W, 1>), grid, dim3(64 * W), 0, st, static_cast<const __half*>(x), (int)R, (int)K,
-                           steps, static_cast<uint8_t*>(tiles), static_cast<uint8_t*>(nibbles));
+        if (stream) hipLaunchKernelGGL((k_rotate128_quant_mfma<W, 1, true>), grid, dim3(64 * W), 0, st, xp, (int)R, (int)K, steps, tp, np);
+        else hipLaunchKernelGGL((k_rotate128_quant_mfma<W, 1, false>), grid, dim3(64 * W), 0, st, xp, (int)R, (int)K, steps, tp, np);
     }
     return hip_status(hipGetLastError());
 }

@@ -176,15 +176,29 @@ __device__ __forceinline__ void quant_bytes8(const float* v, const float* raw, f
 // BITS = 4: eight codes packed into dst_row[channel / 8].  BITS = 8: one byte per code; inside every
 // group of 32 channels the 16 even channels come first, then the 16 odd ones (the order in which
 // the matrix kernel consumes them), so a thread stores two dwords.
-// A packed dword to its place: codes that go to global memory are read next by another launch, on every
-// XCD, i.e. from the memory side in any case, so they are written through at once (non-temporal) instead
-// of waiting in this XCD's L2 for the end of the kernel (canonical step of the five 2048-token linears with
-// cold weights 415 -> 406 us; 8-64 tokens unchanged); LDS destinations take a plain store.
+// A row of codes in global memory whose writer chooses how the dwords leave: STREAM = written through at once
+// (non-temporal), else ordinary stores that wait in this XCD's L2.  The codes are read next by another launch,
+// on every XCD, i.e. from the memory side in any case.  While all of a launch's codes fit the L2s, ordinary
+// stores leave in one burst at the end of the kernel, and streaming them out during it is faster (canonical
+// step of the five 2048-token linears with cold weights 415 -> 406 us); a larger output is evicted as the kernel
+// goes anyway, and streaming costs 1 % (8192 tokens: 1419 -> 1434 us).  kStreamBelow is the sum of the eight L2s.
+// (A compile-time choice: a run-time branch around every store cost the kernels 5 %.)
+template <bool STREAM>
+struct GlobalCodes {
+    uint32_t* p;
+};
+constexpr int64_t kStreamBelow = 32ll << 20;
+
 template <typename DST>
 __device__ __forceinline__ void put_codes(DST dst_row, int64_t at, uint32_t w)
 {
-    if constexpr (std::is_same<DST, uint32_t*>::value) __builtin_nontemporal_store(w, dst_row + at);
-    else dst_row[at] = w;
+    if constexpr (std::is_same<DST, GlobalCodes<true>>::value) {
+        __builtin_nontemporal_store(w, dst_row.p + at);
+    } else if constexpr (std::is_same<DST, GlobalCodes<false>>::value) {
+        dst_row.p[at] = w;
+    } else {
+        dst_row[at] = w;
+    }
 }
 
 template <int BITS, bool EXACT, typename DST>

@@ -24,7 +24,7 @@ using rq::kThreads;
 // R rows of one chunk column per workgroup: all R loads of a thread are issued before the
 // arithmetic starts (the kernel has 2.5 bytes of traffic per element and little else to hide
 // latency with).
-template <int G, bool EXACT, int R, int BITS, typename STEPS>
+template <int G, bool EXACT, int R, int BITS, typename STEPS, bool STREAM>
 __global__ __launch_bounds__(kThreads) void k_rotate_quant(const __half* __restrict__ x, int64_t M, int64_t K,
                                                           int log2h, STEPS steps, uint32_t* __restrict__ xq)
 {
@@ -40,17 +40,21 @@ __global__ __launch_bounds__(kThreads) void k_rotate_quant(const __half* __restr
                           live[r]);
     }
 #pragma unroll
-    for (int r = 0; r < R; ++r)
-        rq::rotate_quant_regs_with<G, EXACT, BITS>(
-            raw[r], live[r], chunk0, log2h, steps,
-            static_cast<uint32_t*>(xq + (row0 + r) * (BITS == 16 ? K >> 1 : (BITS == 8 ? K >> 2 : K >> 3))),
-            (rq::lds_f32_ptr)xch, threadIdx.x, row0 + r < M);
+    for (int r = 0; r < R; ++r) {
+        uint32_t* row = xq + (row0 + r) * (BITS == 16 ? K >> 1 : (BITS == 8 ? K >> 2 : K >> 3));
+        if constexpr (BITS == 16)
+            rq::rotate_quant_regs_with<G, EXACT, BITS>(raw[r], live[r], chunk0, log2h, steps, row, (rq::lds_f32_ptr)xch,
+                                                       threadIdx.x, row0 + r < M);
+        else
+            rq::rotate_quant_regs_with<G, EXACT, BITS>(raw[r], live[r], chunk0, log2h, steps, rq::GlobalCodes<STREAM>{row},
+                                                       (rq::lds_f32_ptr)xch, threadIdx.x, row0 + r < M);
+    }
 }
 
 // Producer fusion for down_proj (Sec. 3: static quantization makes operator fusion feasible): the
 // layer input silu(gate) * up is formed in registers from the two projections' fp16 outputs and
 // goes straight into rotation + quantizer, so the intermediate never exists in memory.
-template <int G, int R>
+template <int G, int R, bool STREAM>
 __global__ __launch_bounds__(kThreads) void k_silu_mul_rotate_quant(const __half* __restrict__ gate,
                                                                    const __half* __restrict__ up, int64_t M,
                                                                    int64_t K, int log2h, rq::StaticStep steps,
@@ -71,7 +75,7 @@ __global__ __launch_bounds__(kThreads) void k_silu_mul_rotate_quant(const __half
 #pragma unroll
     for (int r = 0; r < R; ++r)
         rq::rotate_quant_regs_with<G, false, 4>(rawg[r], live[r], chunk0, log2h, steps,
-                                                static_cast<uint32_t*>(xq + (row0 + r) * (K >> 3)),
+                                                rq::GlobalCodes<STREAM>{xq + (row0 + r) * (K >> 3)},
                                                 (rq::lds_f32_ptr)xch, threadIdx.x, row0 + r < M,
                                                 rq::SiluGate{rawu[r]});
 }
@@ -139,6 +143,29 @@ __global__ __launch_bounds__(kThreads) void k_rotate_quant_groups(const __half* 
 }
 
 // `steps` already carries the 1/sqrt(h) factor of the reciprocal step.
+template <int BITS, typename STEPS, bool STREAM>
+int launch_rq_s(const __half* xp, int64_t M, int64_t K, int32_t h, STEPS steps, uint32_t* op, hipStream_t st)
+{
+    if (h <= 1) {
+        dim3 grid((unsigned)((K + kChunk - 1) / kChunk), (unsigned)((M + 1) / 2));
+        hipLaunchKernelGGL((k_rotate_quant<1, true, 2, BITS, STEPS, STREAM>), grid, dim3(kThreads), 0, st, xp, M, K, 0, steps, op);
+        return hip_status(hipGetLastError());
+    }
+    int log2h = 0;
+    while ((1 << log2h) < h) ++log2h;
+    const int G = h <= kChunk ? 1 : h / kChunk;
+    const int R = G <= 2 ? 2 : 1;
+    dim3 grid((unsigned)((K + (int64_t)G * kChunk - 1) / ((int64_t)G * kChunk)), (unsigned)((M + R - 1) / R));
+    switch (G) {
+        case 1: hipLaunchKernelGGL((k_rotate_quant<1, false, 2, BITS, STEPS, STREAM>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, steps, op); break;
+        case 2: hipLaunchKernelGGL((k_rotate_quant<2, false, 2, BITS, STEPS, STREAM>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, steps, op); break;
+        case 4: hipLaunchKernelGGL((k_rotate_quant<4, false, 1, BITS, STEPS, STREAM>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, steps, op); break;
+        case 8: hipLaunchKernelGGL((k_rotate_quant<8, false, 1, BITS, STEPS, STREAM>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, steps, op); break;
+        default: return PQ_ERR_UNSUPPORTED;
+    }
+    return hip_status(hipGetLastError());
+}
+
 template <int BITS, typename STEPS>
 int launch_rq(const __half* xp, int64_t M, int64_t K, int32_t h, STEPS steps, uint32_t* op, hipStream_t st)
 {
@@ -152,24 +179,9 @@ int launch_rq(const __half* xp, int64_t M, int64_t K, int32_t h, STEPS steps, ui
         }
         return PQ_OK;
     }
-    if (h <= 1) {
-        dim3 grid((unsigned)((K + kChunk - 1) / kChunk), (unsigned)((M + 1) / 2));
-        hipLaunchKernelGGL((k_rotate_quant<1, true, 2, BITS, STEPS>), grid, dim3(kThreads), 0, st, xp, M, K, 0, steps, op);
-        return hip_status(hipGetLastError());
-    }
-    int log2h = 0;
-    while ((1 << log2h) < h) ++log2h;
-    const int G = h <= kChunk ? 1 : h / kChunk;
-    const int R = G <= 2 ? 2 : 1;
-    dim3 grid((unsigned)((K + (int64_t)G * kChunk - 1) / ((int64_t)G * kChunk)), (unsigned)((M + R - 1) / R));
-    switch (G) {
-        case 1: hipLaunchKernelGGL((k_rotate_quant<1, false, 2, BITS, STEPS>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, steps, op); break;
-        case 2: hipLaunchKernelGGL((k_rotate_quant<2, false, 2, BITS, STEPS>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, steps, op); break;
-        case 4: hipLaunchKernelGGL((k_rotate_quant<4, false, 1, BITS, STEPS>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, steps, op); break;
-        case 8: hipLaunchKernelGGL((k_rotate_quant<8, false, 1, BITS, STEPS>), grid, dim3(kThreads), 0, st, xp, M, K, log2h, steps, op); break;
-        default: return PQ_ERR_UNSUPPORTED;
-    }
-    return hip_status(hipGetLastError());
+    // (all codes of the launch; the fp16 output of the rotation-only mode is never streamed)
+    if (BITS != 16 && M * (K >> kWordsShift) * 4 <= rq::kStreamBelow) return launch_rq_s<BITS, STEPS, BITS != 16>(xp, M, K, h, steps, op, st);
+    return launch_rq_s<BITS, STEPS, false>(xp, M, K, h, steps, op, st);
 }
 
 inline rq::StaticStep static_step(float act_scale, int32_t h)
@@ -380,13 +392,18 @@ int launch_silu_mul_rotate_quant(const void* gate, const void* up, int64_t M, in
         const __half* gp = g + m0 * K;
         const __half* upp = u + m0 * K;
         uint32_t* o = op + m0 * (K >> 3);
-        switch (G) {
-            case 1: hipLaunchKernelGGL((k_silu_mul_rotate_quant<1, 2>), grid, dim3(kThreads), 0, st, gp, upp, mm, K, log2h, steps, o); break;
-            case 2: hipLaunchKernelGGL((k_silu_mul_rotate_quant<2, 2>), grid, dim3(kThreads), 0, st, gp, upp, mm, K, log2h, steps, o); break;
-            case 4: hipLaunchKernelGGL((k_silu_mul_rotate_quant<4, 1>), grid, dim3(kThreads), 0, st, gp, upp, mm, K, log2h, steps, o); break;
-            case 8: hipLaunchKernelGGL((k_silu_mul_rotate_quant<8, 1>), grid, dim3(kThreads), 0, st, gp, upp, mm, K, log2h, steps, o); break;
-            default: return PQ_ERR_UNSUPPORTED;
-        }
+        auto launch = [&](auto streamc) {
+            constexpr bool S = decltype(streamc)::value;
+            switch (G) {
+                case 1: hipLaunchKernelGGL((k_silu_mul_rotate_quant<1, 2, S>), grid, dim3(kThreads), 0, st, gp, upp, mm, K, log2h, steps, o); return true;
+                case 2: hipLaunchKernelGGL((k_silu_mul_rotate_quant<2, 2, S>), grid, dim3(kThreads), 0, st, gp, upp, mm, K, log2h, steps, o); return true;
+                case 4: hipLaunchKernelGGL((k_silu_mul_rotate_quant<4, 1, S>), grid, dim3(kThreads), 0, st, gp, upp, mm, K, log2h, steps, o); return true;
+                case 8: hipLaunchKernelGGL((k_silu_mul_rotate_quant<8, 1, S>), grid, dim3(kThreads), 0, st, gp, upp, mm, K, log2h, steps, o); return true;
+                default: return false;
+            }
+        };
+        const bool known = mm * (K >> 1) <= rq::kStreamBelow ? launch(std::true_type{}) : launch(std::false_type{});
+        if (!known) return PQ_ERR_UNSUPPORTED;
         const int rc = hip_status(hipGetLastError());
         if (rc != PQ_OK) return rc;
     }

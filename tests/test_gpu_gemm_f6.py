@@ -231,6 +231,23 @@ def test_rotation_of_128_point_blocks_on_the_matrix_pipe(pq, M, K):
         assert np.all(np.abs(t - (np.minimum(got[at], want[at]) + 0.5)) <= 1e-3)
 
 
+def test_outputs_larger_than_the_l2s(pq):
+    """A launch whose codes or images exceed 32 MiB writes them with ordinary stores, a smaller one streams them
+    out: same bytes either way.  17000 x 4096 unrotated: 34.8 MB of nibbles, 52 MB of images; codes against the
+    oracle's (exact without rotation), images against the layout's definition."""
+    M, K = 17000, 4096
+    x = synth.activations(M, K, seed=21)
+    sx = np.float32(0.21)
+    want = O.pack(O.quantize(x, sx))
+    codes = host(pq.pq_rotate_quant(dev(x), 0, float(sx)))
+    assert np.array_equal(codes, want)
+    nib = torch.full((M, K // 2), 0x33, dtype=torch.uint8, device="cuda")
+    tiles = host(pq.pq_rotate_quant_f6(dev(x), 0, float(sx), codes=nib))
+    assert np.array_equal(host(nib), want)
+    del nib
+    assert np.array_equal(tiles[: pq.pq_f6_tiles_bytes(M, K)], tiles_by_definition(O.unpack(want)))
+
+
 def test_rotation_on_the_matrix_pipe_one_hot_and_constant_rows(pq):
     """Rows whose rotation is known in closed form: a one-hot row becomes +-v / sqrt(128) in its block (the signs
     are a row of the Hadamard matrix), a constant block becomes sqrt(128) v in its first channel and zero elsewhere."""
